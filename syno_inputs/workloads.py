@@ -1,0 +1,172 @@
+"""The synthetic workloads: pGraphs of the operators that are evaluated, and
+their seeded input tensors.
+
+The operators are written down with the primitives of Table 1 of the paper;
+the convolution follows Fig. 2 / Listing 1 (three Reduce, three Share, two
+Unfold, C_out matched to the weight), the small examples follow Table 2.
+Shapes are ResNet-18 stage shapes; values are i.i.d. from the distribution
+each workload names.  These stand in for the image-classification layers the
+paper measures on; no dataset is involved.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, Optional
+
+import numpy as np
+
+from .descriptor import BF16, F32, Builder, OpDesc
+from .rng import Stream, bf16_bits_to_f32, to_bf16_bits
+
+
+# ----------------------------------------------------------------------------
+# pGraphs
+# ----------------------------------------------------------------------------
+def conv2d(N, C, Co, H, W, KH=3, KW=None, in_dtype=F32, out_dtype=F32) -> OpDesc:
+    """out[n,co,h,w] = sum_{c,kh,kw} X[n,c,h+kh-KH/2,w+kw-KW/2] * Wt[co,c,kh,kw]."""
+    KW = KH if KW is None else KW
+    b = Builder([("n", N), ("co", Co), ("h", H), ("w", W)], name=f"conv{KH}x{KW}_C{C}_Co{Co}_{H}x{W}_N{N}")
+    n, co, h, w = 0, 1, 2, 3
+    c = b.reduce(C)
+    cx, cw = b.share(c)
+    kh = b.reduce(KH)
+    khx, khw = b.share(kh)
+    kw = b.reduce(KW)
+    kwx, kww = b.share(kw)
+    hh = b.unfold(h, khx)
+    ww = b.unfold(w, kwx)
+    return b.finish([n, cx, hh, ww], [co, cw, khw, kww], in_dtype, out_dtype)
+
+
+def grouped_shift_unfold(N, C=256, Co=256, H=14, W=14, groups=4, K=3,
+                         in_dtype=BF16, out_dtype=F32) -> OpDesc:
+    """out[n,co,h,w] = sum_{c',k} Wt[co,c',k] * X[n, g*Cg+c', (h+g) mod H, w+k-K/2],  g = co div (Co/groups)."""
+    Og, Cg = Co // groups, C // groups
+    b = Builder([("n", N), ("co", Co), ("h", H), ("w", W)], name=f"gshift_unfold_C{C}_g{groups}_{H}x{W}_N{N}")
+    n, co, h, w = 0, 1, 2, 3
+    g, cop = b.merge(co, Og)
+    gx, gw = b.share(g)
+    c = b.reduce(Cg)
+    cx, cw = b.share(c)
+    k = b.reduce(K)
+    kx, kw = b.share(k)
+    cin = b.split(gx, cx)
+    hh = b.shift(h, 0, by=gx, coef=1)
+    ww = b.unfold(w, kx)
+    return b.finish([n, cin, hh, ww], [gw, cop, cw, kw], in_dtype, out_dtype)
+
+
+def strided_depthwise(N, C, H_out, W_out, S=2, K=3, in_dtype=F32, out_dtype=F32) -> OpDesc:
+    """out[n,c,h,w] = sum_{kh,kw} Wt[c,kh,kw] * X[n,c,S*h+kh-K/2,S*w+kw-K/2]."""
+    b = Builder([("n", N), ("c", C), ("h", H_out), ("w", W_out)], name=f"dw{K}x{K}s{S}_C{C}_{H_out}x{W_out}_N{N}")
+    n, c, h, w = 0, 1, 2, 3
+    cx, cw = b.share(c)
+    kh = b.reduce(K)
+    khx, khw = b.share(kh)
+    kw = b.reduce(K)
+    kwx, kww = b.share(kw)
+    hs = b.stride(h, S)
+    ws = b.stride(w, S)
+    hh = b.unfold(hs, khx)
+    ww = b.unfold(ws, kwx)
+    return b.finish([n, cx, hh, ww], [cw, khw, kww], in_dtype, out_dtype)
+
+
+def matmul(M, N, K, in_dtype=F32, out_dtype=F32) -> OpDesc:
+    """Table 2: out[i,j] = sum_k X[i,k] * Wt[k,j]."""
+    b = Builder([("i", M), ("j", N)], name=f"mm_{M}x{N}x{K}")
+    r = b.reduce(K)
+    rx, rw = b.share(r)
+    return b.finish([0, rx], [rw, 1], in_dtype, out_dtype)
+
+
+# ----------------------------------------------------------------------------
+# Workloads = pGraph + seeded tensors
+# ----------------------------------------------------------------------------
+@dataclass
+class Workload:
+    desc: OpDesc
+    x_shape: tuple
+    w_shape: tuple
+    out_shape: tuple
+    X: np.ndarray                 # float32 values (already rounded to bf16 when in_dtype is BF16)
+    W: np.ndarray
+    G: Optional[np.ndarray]       # upstream gradient, same shape as out (None for forward-only workloads)
+    X_bits: Optional[np.ndarray]  # uint16 bf16 patterns when in_dtype is BF16
+    W_bits: Optional[np.ndarray]
+    G_bits: Optional[np.ndarray]
+    flops: int                    # 2 * prod(output iterators) * prod(Reduce sizes)  (section 8 of the paper)
+
+
+def _finish(desc, xs, ws, os, X, W, G, red) -> Workload:
+    Xb = Wb = Gb = None
+    if desc.in_dtype == BF16:
+        Xb, Wb = to_bf16_bits(X), to_bf16_bits(W)
+        X, W = bf16_bits_to_f32(Xb), bf16_bits_to_f32(Wb)
+        if G is not None:
+            Gb = to_bf16_bits(G)
+            G = bf16_bits_to_f32(Gb)
+    flops = 2 * int(np.prod(os)) * int(red)
+    return Workload(desc, tuple(xs), tuple(ws), tuple(os), X, W, G, Xb, Wb, Gb, flops)
+
+
+def make_conv(N, C, H, seed=0, bf16=False, Co=None, Wd=None, K=3, with_grad=False, out_bf16=False) -> Workload:
+    Co = C if Co is None else Co
+    Wd = H if Wd is None else Wd
+    desc = conv2d(N, C, Co, H, Wd, K, K, BF16 if bf16 else F32, BF16 if out_bf16 else F32)
+    s = Stream(seed)
+    xs, ws, os = (N, C, H, Wd), (Co, C, K, K), (N, Co, H, Wd)
+    X = s.normal(xs)
+    W = s.uniform_pm(1.0 / np.sqrt(K * K * C), ws)
+    G = s.normal(os) if with_grad else None
+    return _finish(desc, xs, ws, os, X, W, G, C * K * K)
+
+
+def make_gshift(N, seeds=(0, 0, 0), with_grad=False, C=256, H=14, Wd=14, groups=4, K=3, out_bf16=False) -> Workload:
+    desc = grouped_shift_unfold(N, C, C, H, Wd, groups, K, BF16, BF16 if out_bf16 else F32)
+    Cg = C // groups
+    xs, ws, os = (N, C, H, Wd), (C, Cg, K), (N, C, H, Wd)
+    streams: Dict[int, Stream] = {}
+
+    def st(seed):
+        return streams.setdefault(seed, Stream(seed))
+
+    X = st(seeds[0]).normal(xs)
+    W = st(seeds[1]).uniform_pm(1.0 / np.sqrt(Cg * K), ws)
+    G = st(seeds[2]).normal(os) if with_grad else None
+    return _finish(desc, xs, ws, os, X, W, G, Cg * K)
+
+
+def make_depthwise(N, C, H_in, seed=0, S=2, K=3, with_grad=False) -> Workload:
+    Ho = H_in // S
+    desc = strided_depthwise(N, C, Ho, Ho, S, K, F32, F32)
+    s = Stream(seed)
+    xs, ws, os = (N, C, H_in, H_in), (C, K, K), (N, C, Ho, Ho)
+    X = s.normal(xs)
+    W = s.uniform_pm(1.0 / 3.0, ws)
+    G = s.normal(os) if with_grad else None
+    return _finish(desc, xs, ws, os, X, W, G, K * K)
+
+
+RESNET18_STAGES = ((64, 56), (128, 28), (256, 14), (512, 7))
+
+
+def config0() -> Workload:
+    return make_conv(1, 16, 16, seed=0)
+
+
+def config1(stage: int, bf16: bool, N: int = 32) -> Workload:
+    C, H = RESNET18_STAGES[stage]
+    return make_conv(N, C, H, seed=0, bf16=bf16)
+
+
+def config2(N: int = 32) -> Workload:
+    return make_gshift(N, seeds=(0, 0, 0))
+
+
+def config3(N: int = 64) -> Workload:
+    return make_depthwise(N, 128, 56, seed=0)
+
+
+def config4(N: int = 128) -> Workload:
+    return make_gshift(N, seeds=(1, 2, 3), with_grad=True)

@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark: operator evaluation throughput on one MI355X.
+
+A step is one evaluation of the conv-equivalent synthesized operator (Unfold 3x3, Share, Reduce over
+C,kh,kw) at the four ResNet-18 stage shapes with N=32, each once in fp32 and once with bf16 inputs and
+fp32 accumulation.  Inputs are synthetic, seeded, and resident in HBM before the timed region.  The other
+workloads (grouped shift-unfold forward and training step, strided depthwise) are timed separately and
+reported under "detail".  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
+
+
+def alg_bytes(w, which, in_bytes, out_bytes):
+    """Algorithmic traffic of one call: each operand read once, the result written once."""
+    import numpy as np
+    nx, nw, no = (int(np.prod(s)) for s in (w.x_shape, w.w_shape, w.out_shape))
+    if which == 0:
+        return (nx + nw) * in_bytes + no * out_bytes
+    if which == 1:
+        return (no + nw) * in_bytes + nx * out_bytes
+    return (nx + no) * in_bytes + nw * 4
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-detail", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build uses no second GPU, collective or rank code "
+              "(--gpus must be 1)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2410_23745_amd as syno
+    from syno_inputs import BF16, workloads as wl
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from util import to_dev
+
+    if not os.path.exists(syno.library_path()):
+        from paper_2410_23745_amd import build
+        build.build()
+    syno.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    class Case:
+        """One operator call with its device buffers (several rotating sets so that memory-bound calls do not
+        replay out of the 256 MB last-level cache)."""
+
+        def __init__(self, name, w, which, sets=1):
+            self.name, self.w, self.which = name, w, which
+            self.plan = syno.Plan(w.desc)
+            inb = 2 if w.desc.in_dtype == BF16 else 4
+            outb = 2 if (w.desc.out_dtype == BF16 and which != 2) else 4
+            self.bytes = alg_bytes(w, which, inb, outb)
+            self.flops = w.flops
+            self.dtype = "bf16" if w.desc.in_dtype == BF16 else "f32"
+            X, W = to_dev(w.X, w.X_bits), to_dev(w.W, w.W_bits)
+            G = to_dev(w.G, w.G_bits) if w.G is not None else None
+            self.sets = []
+            for _ in range(sets):
+                a, b = ((X, W), (G, W), (X, G))[which]
+                out_shape = (w.out_shape, w.x_shape, w.w_shape)[which]
+                out_dtype = torch.float32 if which == 2 else self.plan.out_dtype
+                self.sets.append((a.clone(), b.clone(), torch.empty(out_shape, dtype=out_dtype, device=dev)))
+            self.fn = (self.plan.forward, self.plan.backward_data, self.plan.backward_weight)[which]
+            self.kernel = self.plan.kernel(which)
+            self.i = 0
+
+        def launch(self):
+            a, b, o = self.sets[self.i % len(self.sets)]
+            self.i += 1
+            self.fn(a, b, o)
+
+        def time_ms(self, iters, warm=3):
+            for _ in range(warm):
+                self.launch()
+            torch.cuda.synchronize()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+            for s, e in evs:
+                s.record()
+                self.launch()
+                e.record()
+            torch.cuda.synchronize()
+            t = sorted(s.elapsed_time(e) for s, e in evs)
+            return t[len(t) // 2], sum(t) / len(t)
+
+    # ---- the timed step: configs[1] --------------------------------------------------------------------
+    step_cases = []
+    for bf16 in (False, True):
+        for stage, (C, H) in enumerate(wl.RESNET18_STAGES):
+            step_cases.append(Case(f"conv3x3_C{C}_{H}x{H}_N32_{'bf16' if bf16 else 'f32'}", wl.config1(stage, bf16), 0))
+    step_flops = sum(c.flops for c in step_cases)
+
+    def one_step():
+        for c in step_cases:
+            c.launch()
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    ev = {c.name: [] for c in step_cases}
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        for c in step_cases:
+            s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            s.record()        # on the current stream, which is the stream the binding launches on
+            c.launch()
+            e.record()
+            ev[c.name].append((s, e))
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = step_flops / (ms_per_step * 1e-3) / 1e12
+
+    per_case = {}
+    for c in step_cases:
+        ts = [s.elapsed_time(e) for s, e in ev[c.name]]
+        per_case[c.name] = sum(ts) / len(ts)
+    # dominant kernel of the step = the family with the largest summed duration
+    fam_time = {}
+    for c in step_cases:
+        fam_time.setdefault((c.kernel, c.dtype), []).append(c)
+    dom_key = max(fam_time, key=lambda k: sum(per_case[c.name] for c in fam_time[k]))
+    dom = fam_time[dom_key]
+    dom_ms = sum(per_case[c.name] for c in dom) / len(dom)
+    dom_flops = sum(c.flops for c in dom) / len(dom)
+    dom_bytes = sum(c.bytes for c in dom) / len(dom)
+    mfma_peak = MFMA_PEAK_TFLOPS[dom_key[1]]
+    # which roof binds the dominant kernel: min(peak, AI * BW)
+    ai = dom_flops / dom_bytes
+    if ai * HBM_PEAK_GBS / 1e3 < mfma_peak:
+        ach = dom_bytes / (dom_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                    "traffic": None}
+    else:
+        ach = dom_flops / (dom_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": ach, "peak": mfma_peak, "unit": "TFLOP/s", "frac": ach / mfma_peak,
+                    "traffic": None}
+    roofline["kernel"] = f"{dom_key[0]}[{dom_key[1]}]"
+    roofline["avg_launch_us"] = dom_ms * 1e3
+
+    out = {
+        "metric": "operator fwd TFLOP/s & % of roofline at ResNet-style layer shapes",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 and bf16-in/f32-acc", "data": "synthetic",
+        "config": {"workload": "configs[1]: conv-equivalent Syno operator (Unfold 3x3 pad 1, Share, Reduce C,kh,kw), "
+                               "forward, N=32, ResNet-18 stages (64,56) (128,28) (256,14) (512,7), fp32 and bf16 inputs",
+                   "flop_per_step": step_flops},
+        "roofline": roofline,
+        "per_launch_us": {k: v * 1e3 for k, v in per_case.items()},
+    }
+
+    # ---- detail: every workload, per call -----------------------------------------------------------------
+    if not args.no_detail:
+        detail = []
+        w2, w3, w4 = wl.config2(), wl.config3(), wl.config4()
+        cases = [Case("config0_conv16_f32_fwd", wl.config0(), 0)] + step_cases + [
+            Case("config2_gshift_bf16_N32_fwd", w2, 0, sets=8),
+            Case("config3_depthwise_s2_f32_fwd", w3, 0, sets=6),
+            Case("config4_gshift_bf16_N128_fwd", w4, 0, sets=8),
+            Case("config4_gshift_bf16_N128_bwd_data", w4, 1, sets=8),
+            Case("config4_gshift_bf16_N128_bwd_weight", w4, 2, sets=8),
+        ]
+        for c in cases:
+            med, avg = c.time_ms(30)
+            tf = c.flops / (med * 1e-3) / 1e12
+            gbs = c.bytes / (med * 1e-3) / 1e9
+            peak = MFMA_PEAK_TFLOPS[c.dtype]
+            roof_tf = min(peak, c.flops / c.bytes * HBM_PEAK_GBS / 1e3)
+            detail.append({"case": c.name, "kernel": c.kernel, "us": med * 1e3, "TFLOP/s": tf, "GB/s": gbs,
+                           "bound": "hbm" if roof_tf < peak else "mfma", "roofline_frac": tf / roof_tf,
+                           "rotating_sets": len(c.sets)})
+        out["detail"] = detail
+
+    # ---- CPU baseline: the checker as it stands, on a bounded sample of the same workload ---------------------
+    if not args.no_cpu_baseline:
+        import oracle
+        n_s = 131072
+        rng = np.random.default_rng(0)
+        macs, t_cpu = 0, 0.0
+        for stage in range(4):
+            w = wl.config1(stage, False)
+            idx = rng.integers(0, int(np.prod(w.out_shape)), n_s)
+            Xd, Wd = w.X.astype(np.float64), w.W.astype(np.float64)
+            t = time.perf_counter()
+            oracle.forward_at(w.desc, Xd, Wd, idx)
+            t_cpu += time.perf_counter() - t
+            macs += n_s * (w.flops // 2 // int(np.prod(w.out_shape)))
+        out["cpu_baseline"] = {"value": 2 * macs / t_cpu / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(),
+                               "kind": "oracle", "seconds": t_cpu,
+                               "sample": f"{n_s} sampled outputs of each of the four configs[1] shapes (fp64 loop-nest "
+                                         f"interpreter; {macs} multiply-adds in total)"}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

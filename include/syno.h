@@ -1,0 +1,150 @@
+/*
+ * syno.h - C ABI of the MI355X executor for synthesized operators.
+ *
+ * An operator is a primitive graph (pGraph; paper section 5.1, Fig. 2): the output
+ * iterators form the bottom, each primitive of Table 1 rewrites bottom coordinates into top
+ * coordinates, and the top coordinates index one data input X and one weight W (the weight
+ * receives one copy of every Shared coordinate plus the iterators matched to it, section
+ * 5.3).  Each Reduce adds a sum loop, so the operator is the index-mapped contraction
+ *
+ *     out[o] = sum_r  X[f(o,r)] * W[g(o,r)]                      (Listing 1's loop-nest form)
+ *
+ * with terms dropped where an Unfold leaves its domain (zero padding).  The library builds a
+ * plan from such a graph on concrete sizes (section 5.4: symbols are replaced by sizes
+ * before code generation) and evaluates the forward pass and the two gradient contractions
+ * of L = sum_o out[o]*G[o] on the GPU.
+ *
+ * All tensor pointers are DEVICE pointers to dense row-major arrays, 16-byte aligned, owned
+ * by the caller; inputs and outputs must not alias.  Every compute call overwrites its whole
+ * output, enqueues its kernels on `stream`, performs no allocation and no host
+ * synchronisation, and returns a status (no exceptions cross this boundary).  A plan is
+ * immutable after creation; calls on different streams may run concurrently when each has
+ * its own workspace.
+ */
+#ifndef SYNO_H
+#define SYNO_H
+
+#include <stddef.h>
+#include <stdint.h>
+#include <hip/hip_runtime_api.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct syno_plan syno_plan;
+
+typedef enum {
+  SYNO_OK = 0,
+  SYNO_ERR_NULL = 1,          /* a required pointer is NULL */
+  SYNO_ERR_INVALID_DESC = 2,  /* the graph is not a valid pGraph (see syno_plan_create) */
+  SYNO_ERR_SHAPE = 3,         /* an argument (index, count, selector) is out of range */
+  SYNO_ERR_UNSUPPORTED = 4,   /* valid, but outside what the library lowers */
+  SYNO_ERR_WORKSPACE = 5,     /* workspace required but NULL */
+  SYNO_ERR_HIP = 6            /* the HIP runtime reported an error at launch */
+} syno_status;
+
+typedef enum { SYNO_F32 = 0, SYNO_BF16 = 1 } syno_dtype;
+
+/* Table 1 of the paper, bottom <- top.  i, j are the bottom coordinates (`in`), the results
+ * are the top coordinates (`out`).
+ *   SPLIT   [i,j]:[G,B]  <- [B*i+j]:[G*B]
+ *   MERGE B [i]:[N]      <- [i/B, i%B]:[N/B,B]           (B must divide N)
+ *   SHIFT   [i]:[N]      <- [(i+s) mod N]:[N]            (paper: s = 1; see `param`, `shift_by`)
+ *   EXPAND  [i]:[C]      <- nothing                       (the output is repeated along i)
+ *   UNFOLD  [i,j]:[N,K]  <- [i+j-K/2]:[N]                (floored K/2; out of range -> term dropped)
+ *   STRIDE S[i]:[K]      <- [S*i]:[S*K]
+ *   REDUCE N nothing     <- a new sum iterator of domain N
+ *   SHARE   [i]:[N]      <- ([i],[i])                     (out[0] goes on towards X, out[1] to W)
+ */
+typedef enum {
+  SYNO_SPLIT = 0, SYNO_MERGE = 1, SYNO_SHIFT = 2, SYNO_EXPAND = 3,
+  SYNO_UNFOLD = 4, SYNO_STRIDE = 5, SYNO_REDUCE = 6, SYNO_SHARE = 7
+} syno_prim_kind;
+
+typedef struct {
+  const char* name;   /* for messages only; may be NULL */
+  int64_t size;       /* > 0 */
+} syno_dim;
+
+typedef struct {
+  syno_prim_kind kind;
+  int32_t in[2];        /* coordinate ids consumed (bottom side); unused slots are -1 */
+  int32_t out[2];       /* coordinate ids produced (top side), each a fresh id; unused are -1 */
+  int64_t param;        /* MERGE: B.  STRIDE: S.  REDUCE: N.  SHIFT: constant offset s (any sign) */
+  int32_t shift_by;     /* SHIFT only: id of a coordinate whose value is read (not consumed), or -1 */
+  int64_t shift_coef;   /* SHIFT only: the offset is s + shift_coef * value(shift_by) */
+} syno_prim;
+
+/* Coordinate ids 0..n_out-1 are the output iterators in the layout order of `out`; primitives
+ * are applied in array order (bottom-up) and may only consume ids defined before them.  Every
+ * coordinate must be consumed exactly once: by one primitive, or as one axis of X or of W. */
+typedef struct {
+  int32_t n_out;   const syno_dim*  out_dims;
+  int32_t n_prim;  const syno_prim* prims;
+  int32_t n_in;    const int32_t*   input_coords;    /* axes of X, outermost first */
+  int32_t n_w;     const int32_t*   weight_coords;   /* axes of W, outermost first (may be 0: W is one element) */
+  syno_dtype in_dtype;    /* element type of X, W and G */
+  syno_dtype out_dtype;   /* element type of out and dX; accumulation is fp32; dW is always fp32 */
+} syno_desc;
+
+/* Which of the three contractions a selector argument names. */
+enum { SYNO_FWD = 0, SYNO_BWD_DATA = 1, SYNO_BWD_WEIGHT = 2 };
+
+/* Build a plan (host only; copies everything it needs out of `desc`).
+ * SYNO_ERR_INVALID_DESC: unknown / redefined / twice- or never-consumed coordinate, non-positive
+ * size, Merge factor not dividing its domain, a Reduce iterator fed straight into Expand.
+ * SYNO_ERR_UNSUPPORTED: a tensor with more than 2^31-1 elements, more than 8 axes or 24 distinct
+ * coordinates, or a graph whose gradient index maps the planner cannot invert. */
+syno_status syno_plan_create(const syno_desc* desc, syno_plan** plan);
+syno_status syno_plan_destroy(syno_plan* plan);
+
+/* out[o] = sum_r X[f(o,r)] * W[g(o,r)]   (section 5.3; Listing 1 for the convolution). */
+syno_status syno_forward(const syno_plan* plan, const void* X, const void* W, void* out,
+                         void* workspace, hipStream_t stream);
+/* dX[x] = sum over valid (o,r) with f(o,r)=x of G[o]*W[g(o,r)]; elements no term reaches are
+ * written as 0.  The adjoint of the forward map in X (section 5.2: the primitives are differentiable). */
+syno_status syno_backward_data(const syno_plan* plan, const void* G, const void* W, void* dX,
+                               void* workspace, hipStream_t stream);
+/* dW[w] = sum over valid (o,r) with g(o,r)=w of G[o]*X[f(o,r)], fp32.  The adjoint in W. */
+syno_status syno_backward_weight(const syno_plan* plan, const void* X, const void* G, void* dW,
+                                 void* workspace, hipStream_t stream);
+
+/* Bytes of device workspace call `which` needs (0: `workspace` may be NULL). */
+syno_status syno_plan_workspace_bytes(const syno_plan* plan, int which, size_t* bytes);
+
+/* Derived shapes.  Each array must have room for 8 entries; ranks are returned. */
+syno_status syno_plan_shapes(const syno_plan* plan, int32_t* x_rank, int64_t* x_shape,
+                             int32_t* w_rank, int64_t* w_shape, int32_t* out_rank, int64_t* out_shape);
+
+/* Name of the kernel family call `which` dispatches to (static string, never NULL for a valid plan). */
+const char* syno_plan_kernel(const syno_plan* plan, int which);
+
+/* Restrict kernel choice at plan creation: 0 = planner decides (default), 1 = always the generic
+ * index-program kernels.  Process-wide; affects plans created afterwards.  For verification. */
+syno_status syno_set_kernel_policy(int policy);
+
+/* Verification aid (not on the hot path): the index maps of the three contractions, evaluated on
+ * the device from the same lowered tables the generic kernels use.
+ * Each contraction `which` enumerates (target element t, free point q):
+ *   FWD:        t = flat index into out, q = flat Reduce point (Reduce iterators in graph order,
+ *               row-major)                      -> a_off = offset into X, b_off = offset into W
+ *   BWD_DATA:   t = flat index into dX, q < free_size -> a_off = offset into G, b_off = offset into W
+ *   BWD_WEIGHT: t = flat index into dW, q < free_size -> a_off = offset into G, b_off = offset into X
+ * A point whose term does not exist yields -1 in both.  t_flat, q_flat, a_off, b_off are DEVICE
+ * arrays of n entries. */
+syno_status syno_plan_free_size(const syno_plan* plan, int which, int64_t* free_size);
+syno_status syno_debug_gather(const syno_plan* plan, int which, const int64_t* t_flat, const int64_t* q_flat,
+                              int64_t n, int32_t* a_off, int32_t* b_off, hipStream_t stream);
+
+/* The same maps evaluated on the HOST from the same tables (all four arrays are host pointers); lets a
+ * plan be checked on a machine without a GPU.  Index arithmetic only: no tensor data is touched. */
+syno_status syno_debug_gather_host(const syno_plan* plan, int which, const int64_t* t_flat, const int64_t* q_flat,
+                                   int64_t n, int32_t* a_off, int32_t* b_off);
+
+const char* syno_status_string(syno_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SYNO_H */

@@ -1,0 +1,235 @@
+"""ctypes binding of include/syno.h.  Argument marshalling only: every step of the path runs in
+the library's kernels; torch supplies device memory and streams."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch  # loads the HIP runtime the library links against
+
+FWD, BWD_DATA, BWD_WEIGHT = 0, 1, 2
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsyno.so")
+_lib = None
+
+EXPORTS = ("syno_plan_create", "syno_plan_destroy", "syno_forward", "syno_backward_data", "syno_backward_weight",
+           "syno_plan_workspace_bytes", "syno_plan_shapes", "syno_plan_kernel", "syno_set_kernel_policy",
+           "syno_plan_free_size", "syno_debug_gather", "syno_debug_gather_host", "syno_status_string")
+
+
+class _Dim(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char_p), ("size", ctypes.c_int64)]
+
+
+class _Prim(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int), ("in_", ctypes.c_int32 * 2), ("out", ctypes.c_int32 * 2),
+                ("param", ctypes.c_int64), ("shift_by", ctypes.c_int32), ("shift_coef", ctypes.c_int64)]
+
+
+class _Desc(ctypes.Structure):
+    _fields_ = [("n_out", ctypes.c_int32), ("out_dims", ctypes.POINTER(_Dim)),
+                ("n_prim", ctypes.c_int32), ("prims", ctypes.POINTER(_Prim)),
+                ("n_in", ctypes.c_int32), ("input_coords", ctypes.POINTER(ctypes.c_int32)),
+                ("n_w", ctypes.c_int32), ("weight_coords", ctypes.POINTER(ctypes.c_int32)),
+                ("in_dtype", ctypes.c_int), ("out_dtype", ctypes.c_int)]
+
+
+class SynoError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        msg = load_library().syno_status_string(status)
+        super().__init__(f"{what}: {msg.decode() if msg else status}")
+        self.status = status
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libsyno.so.  There is no fallback: without the built HIP library nothing runs."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2410_23745_amd.build`")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i64p, i32p = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int32)
+    lib.syno_plan_create.argtypes = [ctypes.POINTER(_Desc), ctypes.POINTER(vp)]
+    lib.syno_plan_destroy.argtypes = [vp]
+    for fn in (lib.syno_forward, lib.syno_backward_data, lib.syno_backward_weight):
+        fn.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.syno_plan_workspace_bytes.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
+    lib.syno_plan_shapes.argtypes = [vp, i32p, i64p, i32p, i64p, i32p, i64p]
+    lib.syno_plan_kernel.argtypes = [vp, ctypes.c_int]
+    lib.syno_plan_kernel.restype = ctypes.c_char_p
+    lib.syno_set_kernel_policy.argtypes = [ctypes.c_int]
+    lib.syno_plan_free_size.argtypes = [vp, ctypes.c_int, i64p]
+    lib.syno_debug_gather.argtypes = [vp, ctypes.c_int, vp, vp, ctypes.c_int64, vp, vp, vp]
+    lib.syno_debug_gather_host.argtypes = [vp, ctypes.c_int, vp, vp, ctypes.c_int64, vp, vp]
+    lib.syno_status_string.argtypes = [ctypes.c_int]
+    lib.syno_status_string.restype = ctypes.c_char_p
+    for name in EXPORTS:
+        if name not in ("syno_plan_kernel", "syno_status_string"):
+            getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def set_kernel_policy(policy: int) -> None:
+    """0: planner decides; 1: always the generic index-program kernels (plans created afterwards)."""
+    st = load_library().syno_set_kernel_policy(int(policy))
+    if st:
+        raise SynoError(st, "syno_set_kernel_policy")
+
+
+_TORCH_DTYPE = {0: torch.float32, 1: torch.bfloat16}
+
+
+class Plan:
+    """Owns one syno_plan.  `desc` is an OpDesc-like object (out_dims, prims, input_coords, weight_coords,
+    in_dtype, out_dtype)."""
+
+    def __init__(self, desc):
+        lib = load_library()
+        dims = (_Dim * max(1, len(desc.out_dims)))()
+        self._names = [str(n).encode() for n, _ in desc.out_dims]
+        for i, (_, s) in enumerate(desc.out_dims):
+            dims[i].name, dims[i].size = self._names[i], int(s)
+        prims = (_Prim * max(1, len(desc.prims)))()
+        for i, p in enumerate(desc.prims):
+            prims[i].kind = int(p.kind)
+            ins = list(p.ins) + [-1] * (2 - len(p.ins))
+            outs = list(p.outs) + [-1] * (2 - len(p.outs))
+            prims[i].in_[0], prims[i].in_[1] = ins
+            prims[i].out[0], prims[i].out[1] = outs
+            prims[i].param, prims[i].shift_by, prims[i].shift_coef = int(p.param), int(p.shift_by), int(p.shift_coef)
+        ic = (ctypes.c_int32 * max(1, len(desc.input_coords)))(*desc.input_coords)
+        wc = (ctypes.c_int32 * max(1, len(desc.weight_coords)))(*desc.weight_coords)
+        d = _Desc(len(desc.out_dims), dims, len(desc.prims), prims, len(desc.input_coords), ic,
+                  len(desc.weight_coords), wc, int(desc.in_dtype), int(desc.out_dtype))
+        handle = ctypes.c_void_p()
+        st = lib.syno_plan_create(ctypes.byref(d), ctypes.byref(handle))
+        if st:
+            raise SynoError(st, "syno_plan_create")
+        self._h = handle
+        self.in_dtype = _TORCH_DTYPE[int(desc.in_dtype)]
+        self.out_dtype = _TORCH_DTYPE[int(desc.out_dtype)]
+        xr, wr, orr = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+        xs, ws, os_ = (ctypes.c_int64 * 8)(), (ctypes.c_int64 * 8)(), (ctypes.c_int64 * 8)()
+        st = lib.syno_plan_shapes(self._h, ctypes.byref(xr), xs, ctypes.byref(wr), ws, ctypes.byref(orr), os_)
+        if st:
+            raise SynoError(st, "syno_plan_shapes")
+        self.x_shape = tuple(xs[:xr.value])
+        self.w_shape = tuple(ws[:wr.value])
+        self.out_shape = tuple(os_[:orr.value])
+        self._ws = {}
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h and _lib is not None:
+            _lib.syno_plan_destroy(h)
+
+    # -- queries ---------------------------------------------------------------------------
+    def workspace_bytes(self, which: int) -> int:
+        n = ctypes.c_size_t()
+        st = load_library().syno_plan_workspace_bytes(self._h, which, ctypes.byref(n))
+        if st:
+            raise SynoError(st, "syno_plan_workspace_bytes")
+        return n.value
+
+    def kernel(self, which: int) -> str:
+        s = load_library().syno_plan_kernel(self._h, which)
+        return s.decode() if s else ""
+
+    def free_size(self, which: int) -> int:
+        n = ctypes.c_int64()
+        st = load_library().syno_plan_free_size(self._h, which, ctypes.byref(n))
+        if st:
+            raise SynoError(st, "syno_plan_free_size")
+        return n.value
+
+    # -- compute ---------------------------------------------------------------------------
+    @staticmethod
+    def _numel(shape) -> int:
+        n = 1
+        for s in shape:
+            n *= int(s)
+        return n
+
+    def _arg(self, t: torch.Tensor, shape, dtype, what: str) -> int:
+        if not (t.is_cuda and t.is_contiguous() and t.dtype == dtype and t.numel() == self._numel(shape)):
+            raise ValueError(f"{what}: need a contiguous {dtype} device tensor with {self._numel(shape)} elements")
+        if t.data_ptr() % 16:
+            raise ValueError(f"{what}: pointer must be 16-byte aligned")
+        return t.data_ptr()
+
+    def _workspace(self, which: int, device, workspace: Optional[torch.Tensor]) -> int:
+        need = self.workspace_bytes(which)
+        if need == 0:
+            return 0
+        if workspace is None:
+            workspace = self._ws.get((which, device))
+            if workspace is None:
+                workspace = self._ws[(which, device)] = torch.empty(need, dtype=torch.uint8, device=device)
+        if workspace.numel() * workspace.element_size() < need:
+            raise ValueError("workspace too small")
+        return workspace.data_ptr()
+
+    def _call(self, fn, which, a, a_shape, b, b_shape, out, out_shape, out_dtype, workspace, what):
+        pa = self._arg(a, a_shape, self.in_dtype, what + " first input")
+        pb = self._arg(b, b_shape, self.in_dtype, what + " second input")
+        if out is None:
+            out = torch.empty(out_shape if out_shape else (1,), dtype=out_dtype, device=a.device)
+        po = self._arg(out, out_shape, out_dtype, what + " output")
+        ws = self._workspace(which, a.device, workspace)
+        stream = torch.cuda.current_stream(a.device).cuda_stream
+        st = fn(self._h, pa, pb, po, ws, stream)
+        if st:
+            raise SynoError(st, what)
+        return out
+
+    def forward(self, X, W, out=None, workspace=None):
+        return self._call(load_library().syno_forward, FWD, X, self.x_shape, W, self.w_shape, out, self.out_shape,
+                          self.out_dtype, workspace, "syno_forward")
+
+    def backward_data(self, G, W, dX=None, workspace=None):
+        return self._call(load_library().syno_backward_data, BWD_DATA, G, self.out_shape, W, self.w_shape, dX,
+                          self.x_shape, self.out_dtype, workspace, "syno_backward_data")
+
+    def backward_weight(self, X, G, dW=None, workspace=None):
+        return self._call(load_library().syno_backward_weight, BWD_WEIGHT, X, self.x_shape, G, self.out_shape, dW,
+                          self.w_shape, torch.float32, workspace, "syno_backward_weight")
+
+    def debug_gather_host(self, which: int, t_flat, q_flat):
+        """Same maps as `debug_gather`, evaluated on the host (numpy int64 in, numpy int32 out)."""
+        import numpy as np
+        t = np.ascontiguousarray(t_flat, dtype=np.int64)
+        q = np.ascontiguousarray(q_flat, dtype=np.int64)
+        if t.shape != q.shape:
+            raise ValueError("debug_gather_host: length mismatch")
+        a = np.empty(t.shape, dtype=np.int32)
+        b = np.empty(t.shape, dtype=np.int32)
+        st = load_library().syno_debug_gather_host(self._h, which, t.ctypes.data, q.ctypes.data, t.size,
+                                                   a.ctypes.data, b.ctypes.data)
+        if st:
+            raise SynoError(st, "syno_debug_gather_host")
+        return a, b
+
+    def debug_gather(self, which: int, t_flat: torch.Tensor, q_flat: torch.Tensor):
+        """Index maps of contraction `which` at the listed (target, free point) pairs; int64 device tensors in,
+        two int32 device tensors out (-1 where the term does not exist)."""
+        for t in (t_flat, q_flat):
+            if not (t.is_cuda and t.is_contiguous() and t.dtype == torch.int64):
+                raise ValueError("debug_gather: need contiguous int64 device tensors")
+        if t_flat.numel() != q_flat.numel():
+            raise ValueError("debug_gather: length mismatch")
+        n = t_flat.numel()
+        a = torch.empty(n, dtype=torch.int32, device=t_flat.device)
+        b = torch.empty(n, dtype=torch.int32, device=t_flat.device)
+        stream = torch.cuda.current_stream(t_flat.device).cuda_stream
+        st = load_library().syno_debug_gather(self._h, which, t_flat.data_ptr(), q_flat.data_ptr(), n, a.data_ptr(),
+                                              b.data_ptr(), stream)
+        if st:
+            raise SynoError(st, "syno_debug_gather")
+        return a, b

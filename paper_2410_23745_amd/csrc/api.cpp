@@ -1,0 +1,138 @@
+// The C ABI of include/syno.h: argument checks and dispatch to the kernel families.
+#include <atomic>
+#include <new>
+#include <string>
+
+#include "plan.h"
+
+namespace syno {
+syno_status launch_bandwidth(const syno_plan* p, int which, const void* A, const void* B, void* out, void* ws,
+                             hipStream_t stream);
+syno_status launch_mfma(const syno_plan* p, int which, const void* A, const void* B, void* out, void* ws,
+                        hipStream_t stream);
+}
+
+namespace {
+std::atomic<int> g_policy{0};
+
+const char* const kKernelNames[syno::KERNEL_COUNT] = {
+    "generic_index_program", "bandwidth_depthwise", "mfma_contraction_f32", "mfma_contraction_bf16"};
+
+syno_status run(const syno_plan* plan, int which, const void* A, const void* B, void* out, void* ws,
+                hipStream_t stream) {
+  if (!plan || !A || !B || !out) return SYNO_ERR_NULL;
+  const syno::Launch& L = plan->launch[which];
+  if (L.workspace && !ws) return SYNO_ERR_WORKSPACE;
+  switch (L.kernel) {
+    case syno::KERNEL_GENERIC: return syno::launch_generic(plan, which, A, B, out, stream);
+    case syno::KERNEL_BW_DEPTHWISE: return syno::launch_bandwidth(plan, which, A, B, out, ws, stream);
+    case syno::KERNEL_MFMA_F32:
+    case syno::KERNEL_MFMA_BF16: return syno::launch_mfma(plan, which, A, B, out, ws, stream);
+    default: return SYNO_ERR_UNSUPPORTED;
+  }
+}
+}  // namespace
+
+extern "C" {
+
+syno_status syno_plan_create(const syno_desc* desc, syno_plan** plan) {
+  if (!desc || !plan) return SYNO_ERR_NULL;
+  *plan = nullptr;
+  syno_plan* p = new (std::nothrow) syno_plan();
+  if (!p) return SYNO_ERR_UNSUPPORTED;
+  std::string why;
+  const syno_status st = syno::build_plan(desc, g_policy.load(), p, &why);
+  if (st != SYNO_OK) {
+    delete p;
+    return st;
+  }
+  *plan = p;
+  return SYNO_OK;
+}
+
+syno_status syno_plan_destroy(syno_plan* plan) {
+  delete plan;
+  return SYNO_OK;
+}
+
+syno_status syno_forward(const syno_plan* plan, const void* X, const void* W, void* out, void* ws,
+                         hipStream_t stream) {
+  return run(plan, SYNO_FWD, X, W, out, ws, stream);
+}
+
+syno_status syno_backward_data(const syno_plan* plan, const void* G, const void* W, void* dX, void* ws,
+                               hipStream_t stream) {
+  return run(plan, SYNO_BWD_DATA, G, W, dX, ws, stream);
+}
+
+syno_status syno_backward_weight(const syno_plan* plan, const void* X, const void* G, void* dW, void* ws,
+                                 hipStream_t stream) {
+  // the lowered forms take the upstream gradient first
+  return run(plan, SYNO_BWD_WEIGHT, G, X, dW, ws, stream);
+}
+
+syno_status syno_plan_workspace_bytes(const syno_plan* plan, int which, size_t* bytes) {
+  if (!plan || !bytes) return SYNO_ERR_NULL;
+  if (which < 0 || which > 2) return SYNO_ERR_SHAPE;
+  *bytes = plan->launch[which].workspace;
+  return SYNO_OK;
+}
+
+syno_status syno_plan_shapes(const syno_plan* plan, int32_t* x_rank, int64_t* x_shape, int32_t* w_rank,
+                             int64_t* w_shape, int32_t* out_rank, int64_t* out_shape) {
+  if (!plan || !x_rank || !x_shape || !w_rank || !w_shape || !out_rank || !out_shape) return SYNO_ERR_NULL;
+  *x_rank = plan->x_rank;
+  *w_rank = plan->w_rank;
+  *out_rank = plan->out_rank;
+  for (int i = 0; i < plan->x_rank; ++i) x_shape[i] = plan->x_shape[i];
+  for (int i = 0; i < plan->w_rank; ++i) w_shape[i] = plan->w_shape[i];
+  for (int i = 0; i < plan->out_rank; ++i) out_shape[i] = plan->out_shape[i];
+  return SYNO_OK;
+}
+
+const char* syno_plan_kernel(const syno_plan* plan, int which) {
+  if (!plan || which < 0 || which > 2) return nullptr;
+  return kKernelNames[plan->launch[which].kernel];
+}
+
+syno_status syno_set_kernel_policy(int policy) {
+  if (policy < 0 || policy > 1) return SYNO_ERR_SHAPE;
+  g_policy.store(policy);
+  return SYNO_OK;
+}
+
+syno_status syno_plan_free_size(const syno_plan* plan, int which, int64_t* free_size) {
+  if (!plan || !free_size) return SYNO_ERR_NULL;
+  if (which < 0 || which > 2) return SYNO_ERR_SHAPE;
+  *free_size = plan->prog[which].n_free;
+  return SYNO_OK;
+}
+
+syno_status syno_debug_gather(const syno_plan* plan, int which, const int64_t* t_flat, const int64_t* q_flat,
+                              int64_t n, int32_t* a_off, int32_t* b_off, hipStream_t stream) {
+  if (!plan || (n > 0 && (!t_flat || !q_flat || !a_off || !b_off))) return SYNO_ERR_NULL;
+  if (which < 0 || which > 2 || n < 0) return SYNO_ERR_SHAPE;
+  return syno::launch_debug_gather(plan, which, t_flat, q_flat, n, a_off, b_off, stream);
+}
+
+syno_status syno_debug_gather_host(const syno_plan* plan, int which, const int64_t* t_flat, const int64_t* q_flat,
+                                   int64_t n, int32_t* a_off, int32_t* b_off) {
+  if (!plan || (n > 0 && (!t_flat || !q_flat || !a_off || !b_off))) return SYNO_ERR_NULL;
+  if (which < 0 || which > 2 || n < 0) return SYNO_ERR_SHAPE;
+  return syno::host_debug_gather(plan, which, t_flat, q_flat, n, a_off, b_off);
+}
+
+const char* syno_status_string(syno_status s) {
+  switch (s) {
+    case SYNO_OK: return "ok";
+    case SYNO_ERR_NULL: return "null pointer";
+    case SYNO_ERR_INVALID_DESC: return "invalid primitive graph";
+    case SYNO_ERR_SHAPE: return "argument out of range";
+    case SYNO_ERR_UNSUPPORTED: return "unsupported";
+    case SYNO_ERR_WORKSPACE: return "workspace required";
+    case SYNO_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,108 @@
+// Internal: lowered forms a plan holds, shared by the planner (host) and the kernels.
+#pragma once
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+#include "syno.h"
+
+namespace syno {
+
+constexpr int kMaxSlots = 24;   // distinct coordinate values (Share copies alias one slot)
+constexpr int kMaxOps = 32;
+constexpr int kMaxAxes = 8;
+
+// ---------------------------------------------------------------------------------------------
+// Index program: the general lowered form of one contraction.  A target element (decoded from
+// its flat index along `tgt`) and a free point (decoded along `fre`) fill some slots; the ops
+// then derive every other coordinate, forwards (Table 1 as written) or inverted (for the
+// gradients), and the two source offsets are dot products of slots with strides.
+// ---------------------------------------------------------------------------------------------
+enum OpKind : int32_t {
+  OP_MULADD = 0,   // v[d0] = v[a]*p0 + v[b]                       Split forwards, Merge inverted
+  OP_DIVMOD = 1,   // v[d0] = v[a]/p0 ; v[d1] = v[a]%p0            Merge forwards, Split inverted
+  OP_SHIFT  = 2,   // v[d0] = (v[a] + p1 + p2*v[b]) mod p0, >= 0   Shift, either way
+  OP_ADDCHK = 3,   // t = v[a] + p2*v[b] + p1 ; ok &= 0<=t<p0 ; v[d0]=t   Unfold, either way
+  OP_MUL    = 4,   // v[d0] = v[a]*p0                              Stride forwards
+  OP_DIVCHK = 5    // ok &= v[a]%p0==0 ; v[d0] = v[a]/p0           Stride inverted
+};
+
+struct IndexOp {
+  int32_t kind, a, b, d0, d1, p0, p1, p2;
+};
+
+struct AxisRef {
+  int32_t slot, size, stride;
+};
+
+struct IndexProgram {
+  int32_t n_tgt, n_fre, n_ops0, n_ops, n_a, n_b;   // ops[0..n_ops0) depend on the target only
+  AxisRef tgt[kMaxAxes];     // target tensor axes, outermost first (stride unused)
+  AxisRef fre[kMaxAxes];     // free coordinates, outermost first (stride unused)
+  IndexOp ops[kMaxOps];
+  AxisRef a[kMaxAxes];       // first source: slots and element strides
+  AxisRef b[kMaxAxes];       // second source
+  int64_t n_target, n_free;  // products of the sizes above
+};
+
+// ---------------------------------------------------------------------------------------------
+// Convolution-like lowered form: what the forward index map looks like when every X axis is an
+// affine function of the iterators, optionally wrapped (Shift) or range-checked (Unfold), on a
+// 4-axis input [batch, channel, row, column].  The tuned kernels take this record.
+//   out[n, g*Og+o, h, w] = sum_{c,kh,kw} X[n, g*Cg+c, row(h,kh,g), col(w,kw,g)] * W[g,o,c,kh,kw]
+//   row = sh*h + kh - ph (+ shift, mod Hi when h_wrap), dropped when outside [0,Hi) otherwise
+// ---------------------------------------------------------------------------------------------
+struct ConvLike {
+  int32_t N, G, Og, Cg, Ho, Wo, Hi, Wi, KH, KW;
+  int32_t sh, sw, ph, pw;
+  int32_t h_wrap, w_wrap;           // 1: cyclic (mod Hi / Wi), 0: zero outside
+  int32_t h_shift, h_shift_g;       // row offset = h_shift + h_shift_g * g (only when wrapped)
+  int32_t w_shift, w_shift_g;
+  // weight element strides per role (0 when the role has size 1 or is absent)
+  int32_t ws_g, ws_o, ws_c, ws_kh, ws_kw;
+};
+
+enum KernelId : int32_t {
+  KERNEL_GENERIC = 0,
+  KERNEL_BW_DEPTHWISE,
+  KERNEL_MFMA_F32,
+  KERNEL_MFMA_BF16,
+  KERNEL_COUNT
+};
+
+struct Launch {
+  KernelId kernel = KERNEL_GENERIC;
+  int32_t coop = 0;           // generic kernel: one workgroup per target (1) or one lane per target (0)
+  int32_t variant = 0;        // tile configuration index within the family
+  size_t workspace = 0;
+};
+
+}  // namespace syno
+
+struct syno_plan {
+  // shapes
+  int32_t x_rank = 0, w_rank = 0, out_rank = 0;
+  int64_t x_shape[syno::kMaxAxes] = {}, w_shape[syno::kMaxAxes] = {}, out_shape[syno::kMaxAxes] = {};
+  int64_t x_elems = 0, w_elems = 0, out_elems = 0, n_reduce = 0;
+  syno_dtype in_dtype = SYNO_F32, out_dtype = SYNO_F32;
+  // lowered forms
+  syno::IndexProgram prog[3];
+  bool conv_like = false;
+  syno::ConvLike conv{};
+  syno::Launch launch[3];
+};
+
+namespace syno {
+
+// planner.cpp
+syno_status build_plan(const syno_desc* desc, int policy, syno_plan* plan, std::string* why);
+
+// kernels_generic.hip
+syno_status launch_generic(const syno_plan* p, int which, const void* A, const void* B, void* out,
+                           hipStream_t stream);
+syno_status launch_debug_gather(const syno_plan* p, int which, const int64_t* t, const int64_t* q, int64_t n,
+                                int32_t* a_off, int32_t* b_off, hipStream_t stream);
+syno_status host_debug_gather(const syno_plan* p, int which, const int64_t* t, const int64_t* q, int64_t n,
+                              int32_t* a_off, int32_t* b_off);
+
+}  // namespace syno

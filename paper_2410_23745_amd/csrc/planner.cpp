@@ -1,0 +1,668 @@
+// Host planner: pGraph -> validated graph -> lowered index programs for the forward pass and the
+// two gradients -> convolution-like form when the index map is affine -> kernel choice.
+//
+// Semantics follow Table 1 of the paper evaluated bottom-up (section 5.3).  The gradients are
+// lowered as gathers: starting from the axes of the tensor being produced, every primitive is
+// inverted where it is a bijection (Split, Merge, Shift), Unfold v = i + j - K/2 is solved for i
+// once j is enumerated (with a range test), Stride v = S*i is solved when S divides v, and
+// coordinates nothing determines are enumerated.
+#include <algorithm>
+#include <cstring>
+#include <map>
+#include <string>
+#include <vector>
+
+#include "plan.h"
+
+namespace syno {
+namespace {
+
+constexpr int kMaxCoordId = 256;
+constexpr int64_t kMaxElems = 2147483647LL;
+
+struct Graph {
+  int n_out = 0;
+  std::vector<int64_t> dom;        // by coordinate id (0 where undefined)
+  std::vector<int> slot;           // by coordinate id: value slot (Share copies share one)
+  std::vector<syno_prim> prims;
+  std::vector<int> in_coords, w_coords;
+  int n_slots = 0;
+  std::vector<int64_t> slot_dom;
+  std::vector<int> reduce_coords;  // in graph order
+  std::vector<int64_t> out_stride; // by output axis
+  int64_t D(int c) const { return dom[c]; }
+  int S(int c) const { return slot[c]; }
+};
+
+int arity_in(int kind) {
+  switch (kind) {
+    case SYNO_SPLIT: case SYNO_UNFOLD: return 2;
+    case SYNO_REDUCE: return 0;
+    default: return 1;
+  }
+}
+int arity_out(int kind) {
+  switch (kind) {
+    case SYNO_MERGE: case SYNO_SHARE: return 2;
+    case SYNO_EXPAND: return 0;
+    default: return 1;
+  }
+}
+
+syno_status parse_graph(const syno_desc* d, Graph& g, std::string* why) {
+  auto bad = [&](const char* m) { if (why) *why = m; return SYNO_ERR_INVALID_DESC; };
+  if (d->n_out < 0 || d->n_prim < 0 || d->n_in < 0 || d->n_w < 0) return bad("negative count");
+  if ((d->n_out && !d->out_dims) || (d->n_prim && !d->prims) || (d->n_in && !d->input_coords) ||
+      (d->n_w && !d->weight_coords))
+    return SYNO_ERR_NULL;
+  if (d->n_out > kMaxAxes || d->n_in > kMaxAxes || d->n_w > kMaxAxes) {
+    if (why) *why = "more than 8 axes";
+    return SYNO_ERR_UNSUPPORTED;
+  }
+  if (d->in_dtype != SYNO_F32 && d->in_dtype != SYNO_BF16) return bad("in_dtype");
+  if (d->out_dtype != SYNO_F32 && d->out_dtype != SYNO_BF16) return bad("out_dtype");
+  g.n_out = d->n_out;
+  g.dom.assign(kMaxCoordId, 0);
+  std::vector<char> defined(kMaxCoordId, 0), used(kMaxCoordId, 0), from_reduce(kMaxCoordId, 0);
+  std::vector<int> parent(kMaxCoordId);
+  for (int i = 0; i < kMaxCoordId; ++i) parent[i] = i;
+  auto find = [&](int x) { while (parent[x] != x) x = parent[x] = parent[parent[x]]; return x; };
+  for (int i = 0; i < d->n_out; ++i) {
+    if (d->out_dims[i].size <= 0) return bad("output size <= 0");
+    g.dom[i] = d->out_dims[i].size;
+    defined[i] = 1;
+  }
+  for (int k = 0; k < d->n_prim; ++k) {
+    const syno_prim& p = d->prims[k];
+    if ((int)p.kind < 0 || (int)p.kind > SYNO_SHARE) return bad("unknown primitive");
+    const int ni = arity_in(p.kind), no = arity_out(p.kind);
+    for (int t = 0; t < 2; ++t) {
+      if (t < ni) {
+        const int c = p.in[t];
+        if (c < 0 || c >= kMaxCoordId || !defined[c]) return bad("primitive consumes an undefined coordinate");
+        if (used[c]) return bad("coordinate consumed twice");
+        used[c] = 1;
+      } else if (p.in[t] != -1) return bad("unused in slot must be -1");
+      if (t < no) {
+        const int c = p.out[t];
+        if (c < 0 || c >= kMaxCoordId) return bad("coordinate id out of range");
+        if (defined[c]) return bad("coordinate defined twice");
+        defined[c] = 1;
+      } else if (p.out[t] != -1) return bad("unused out slot must be -1");
+    }
+    switch (p.kind) {
+      case SYNO_SPLIT: g.dom[p.out[0]] = g.dom[p.in[0]] * g.dom[p.in[1]]; break;
+      case SYNO_MERGE:
+        if (p.param <= 0 || g.dom[p.in[0]] % p.param) return bad("Merge factor must divide the domain");
+        g.dom[p.out[0]] = g.dom[p.in[0]] / p.param;
+        g.dom[p.out[1]] = p.param;
+        break;
+      case SYNO_SHIFT:
+        if (p.shift_by != -1 && (p.shift_by < 0 || p.shift_by >= kMaxCoordId || !defined[p.shift_by]))
+          return bad("shift_by names an undefined coordinate");
+        g.dom[p.out[0]] = g.dom[p.in[0]];
+        break;
+      case SYNO_EXPAND:
+        if (from_reduce[p.in[0]]) return bad("a Reduce iterator is fed straight into Expand");
+        break;
+      case SYNO_UNFOLD: g.dom[p.out[0]] = g.dom[p.in[0]]; break;
+      case SYNO_STRIDE:
+        if (p.param <= 0) return bad("Stride factor <= 0");
+        g.dom[p.out[0]] = g.dom[p.in[0]] * p.param;
+        break;
+      case SYNO_REDUCE:
+        if (p.param <= 0) return bad("Reduce size <= 0");
+        g.dom[p.out[0]] = p.param;
+        from_reduce[p.out[0]] = 1;
+        g.reduce_coords.push_back(p.out[0]);
+        break;
+      case SYNO_SHARE:
+        g.dom[p.out[0]] = g.dom[p.out[1]] = g.dom[p.in[0]];
+        parent[find(p.out[0])] = find(p.in[0]);
+        parent[find(p.out[1])] = find(p.in[0]);
+        break;
+    }
+    for (int t = 0; t < no; ++t)
+      if (g.dom[p.out[t]] > kMaxElems) { if (why) *why = "domain too large"; return SYNO_ERR_UNSUPPORTED; }
+    g.prims.push_back(p);
+  }
+  for (int i = 0; i < d->n_in; ++i) {
+    const int c = d->input_coords[i];
+    if (c < 0 || c >= kMaxCoordId || !defined[c]) return bad("X axis names an undefined coordinate");
+    if (used[c]) return bad("coordinate consumed twice");
+    used[c] = 1;
+    g.in_coords.push_back(c);
+  }
+  for (int i = 0; i < d->n_w; ++i) {
+    const int c = d->weight_coords[i];
+    if (c < 0 || c >= kMaxCoordId || !defined[c]) return bad("W axis names an undefined coordinate");
+    if (used[c]) return bad("coordinate consumed twice");
+    used[c] = 1;
+    g.w_coords.push_back(c);
+  }
+  for (int c = 0; c < kMaxCoordId; ++c)
+    if (defined[c] && !used[c]) return bad("coordinate never consumed");
+  // slots
+  g.slot.assign(kMaxCoordId, -1);
+  std::map<int, int> root_slot;
+  for (int c = 0; c < kMaxCoordId; ++c) {
+    if (!defined[c]) continue;
+    const int r = find(c);
+    auto it = root_slot.find(r);
+    if (it == root_slot.end()) {
+      it = root_slot.emplace(r, g.n_slots++).first;
+      g.slot_dom.push_back(g.dom[c]);
+    }
+    g.slot[c] = it->second;
+  }
+  if (g.n_slots > kMaxSlots || (int)g.prims.size() > kMaxOps) {
+    if (why) *why = "graph too large";
+    return SYNO_ERR_UNSUPPORTED;
+  }
+  g.out_stride.assign(g.n_out, 1);
+  for (int i = g.n_out - 2; i >= 0; --i) g.out_stride[i] = g.out_stride[i + 1] * g.dom[i + 1];
+  return SYNO_OK;
+}
+
+int32_t pos_mod(int64_t a, int64_t n) {
+  int64_t m = a % n;
+  return (int32_t)(m < 0 ? m + n : m);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Index-program construction
+// ---------------------------------------------------------------------------------------------
+struct Builder {
+  const Graph& g;
+  std::vector<char> known;        // by slot
+  std::vector<IndexOp> ops;
+  std::vector<int> free_slots;    // in the order they were chosen
+  bool failed = false;
+  explicit Builder(const Graph& gg) : g(gg), known(gg.n_slots, 0) {}
+  bool K(int c) const { return known[g.S(c)]; }
+  void set(int c) { known[g.S(c)] = 1; }
+  void emit(int kind, int a, int b, int d0, int d1, int64_t p0, int64_t p1, int64_t p2) {
+    IndexOp o{kind, a, b, d0, d1, (int32_t)p0, (int32_t)p1, (int32_t)p2};
+    ops.push_back(o);
+  }
+};
+
+// Try to process primitive k with what is known.  Returns true when it is finished.
+bool step_prim(Builder& b, const syno_prim& p, bool* progress) {
+  const Graph& g = b.g;
+  auto S = [&](int c) { return g.S(c); };
+  switch (p.kind) {
+    case SYNO_SHARE: return true;                       // copies alias one slot
+    case SYNO_REDUCE: return b.K(p.out[0]);
+    case SYNO_EXPAND: return b.K(p.in[0]);
+    case SYNO_SPLIT: {
+      const int i = p.in[0], j = p.in[1], v = p.out[0];
+      if (b.K(i) && b.K(j) && !b.K(v)) {
+        b.emit(OP_MULADD, S(i), S(j), S(v), -1, g.D(j), 0, 0);
+        b.set(v);
+      } else if (b.K(v) && !b.K(i) && !b.K(j)) {
+        b.emit(OP_DIVMOD, S(v), -1, S(i), S(j), g.D(j), 0, 0);
+        b.set(i); b.set(j);
+      } else {
+        if (b.K(v) && (b.K(i) || b.K(j))) b.failed = true;   // determined twice
+        return false;
+      }
+      *progress = true;
+      return true;
+    }
+    case SYNO_MERGE: {
+      const int i = p.in[0], q = p.out[0], r = p.out[1];
+      if (b.K(i) && !b.K(q) && !b.K(r)) {
+        b.emit(OP_DIVMOD, S(i), -1, S(q), S(r), p.param, 0, 0);
+        b.set(q); b.set(r);
+      } else if (b.K(q) && b.K(r) && !b.K(i)) {
+        b.emit(OP_MULADD, S(q), S(r), S(i), -1, p.param, 0, 0);
+        b.set(i);
+      } else {
+        if (b.K(i) && (b.K(q) || b.K(r))) b.failed = true;
+        return false;
+      }
+      *progress = true;
+      return true;
+    }
+    case SYNO_SHIFT: {
+      const int i = p.in[0], v = p.out[0], by = p.shift_by;
+      if (by >= 0 && !b.K(by)) return false;
+      const int64_t N = g.D(i);
+      const int bs = by >= 0 ? S(by) : -1;
+      const int64_t coef = by >= 0 ? p.shift_coef : 0;
+      if (b.K(i) && !b.K(v)) {
+        b.emit(OP_SHIFT, S(i), bs >= 0 ? bs : S(i), S(v), -1, N, pos_mod(p.param, N), pos_mod(coef, N));
+        b.set(v);
+      } else if (b.K(v) && !b.K(i)) {
+        b.emit(OP_SHIFT, S(v), bs >= 0 ? bs : S(v), S(i), -1, N, pos_mod(-p.param, N), pos_mod(-coef, N));
+        b.set(i);
+      } else {
+        if (b.K(i) && b.K(v)) b.failed = true;
+        return false;
+      }
+      *progress = true;
+      return true;
+    }
+    case SYNO_UNFOLD: {
+      const int i = p.in[0], j = p.in[1], v = p.out[0];
+      const int64_t N = g.D(i), Kd = g.D(j);
+      if (b.K(i) && b.K(j) && !b.K(v)) {
+        b.emit(OP_ADDCHK, S(i), S(j), S(v), -1, N, -(Kd / 2), 1);
+        b.set(v);
+      } else if (b.K(v) && b.K(j) && !b.K(i)) {
+        b.emit(OP_ADDCHK, S(v), S(j), S(i), -1, N, Kd / 2, -1);      // i = v - j + K/2 within [0,N)
+        b.set(i);
+      } else if (b.K(v) && b.K(i) && !b.K(j)) {
+        b.emit(OP_ADDCHK, S(v), S(i), S(j), -1, Kd, Kd / 2, -1);     // j = v - i + K/2 within [0,K)
+        b.set(j);
+      } else {
+        if (b.K(v) && b.K(i) && b.K(j)) b.failed = true;
+        return false;
+      }
+      *progress = true;
+      return true;
+    }
+    case SYNO_STRIDE: {
+      const int i = p.in[0], v = p.out[0];
+      if (b.K(i) && !b.K(v)) {
+        b.emit(OP_MUL, S(i), -1, S(v), -1, p.param, 0, 0);
+        b.set(v);
+      } else if (b.K(v) && !b.K(i)) {
+        b.emit(OP_DIVCHK, S(v), -1, S(i), -1, p.param, 0, 0);
+        b.set(i);
+      } else {
+        if (b.K(i) && b.K(v)) b.failed = true;
+        return false;
+      }
+      *progress = true;
+      return true;
+    }
+  }
+  return false;
+}
+
+// Coordinate to enumerate when nothing more can be derived: prefer one that unblocks a
+// half-determined primitive (smallest domain first), else any undetermined iterator.
+int pick_free(const Builder& b, const std::vector<char>& done) {
+  const Graph& g = b.g;
+  int best = -1;
+  auto consider = [&](int c) {
+    if (c >= 0 && !b.K(c) && (best < 0 || g.D(c) < g.D(best))) best = c;
+  };
+  for (size_t k = 0; k < g.prims.size(); ++k) {
+    if (done[k]) continue;
+    const syno_prim& p = g.prims[k];
+    switch (p.kind) {
+      case SYNO_UNFOLD:
+        if (b.K(p.out[0]) && !b.K(p.in[0]) && !b.K(p.in[1])) consider(p.in[1]);
+        else if (!b.K(p.out[0]) && b.K(p.in[0]) != b.K(p.in[1])) consider(b.K(p.in[0]) ? p.in[1] : p.in[0]);
+        break;
+      case SYNO_MERGE:
+        if (!b.K(p.in[0]) && b.K(p.out[0]) != b.K(p.out[1])) consider(b.K(p.out[0]) ? p.out[1] : p.out[0]);
+        break;
+      case SYNO_SPLIT:
+        if (!b.K(p.out[0]) && b.K(p.in[0]) != b.K(p.in[1])) consider(b.K(p.in[0]) ? p.in[1] : p.in[0]);
+        break;
+      case SYNO_SHIFT:
+        if (p.shift_by >= 0 && !b.K(p.shift_by) && (b.K(p.in[0]) || b.K(p.out[0]))) consider(p.shift_by);
+        break;
+      default: break;
+    }
+  }
+  if (best >= 0) return best;
+  for (int i = 0; i < g.n_out; ++i) consider(i);
+  for (int c : g.reduce_coords) consider(c);
+  return best;
+}
+
+struct TensorAxes {
+  std::vector<int> coords;
+  std::vector<int64_t> stride;
+};
+
+TensorAxes axes_of(const Graph& g, const std::vector<int>& coords) {
+  TensorAxes t;
+  t.coords = coords;
+  t.stride.assign(coords.size(), 1);
+  for (int i = (int)coords.size() - 2; i >= 0; --i) t.stride[i] = t.stride[i + 1] * g.D(coords[i + 1]);
+  return t;
+}
+
+// Build the program that, for each element of `target` and each free point, yields the offsets
+// into tensors `A` and `B`.  `forced_free` (forward pass only) fixes the free coordinates.
+bool build_program(const Graph& g, const TensorAxes& target, const std::vector<int>* forced_free,
+                   const TensorAxes& A, const TensorAxes& B, IndexProgram& out) {
+  Builder b(g);
+  std::memset(&out, 0, sizeof(out));
+  // a coordinate value can be fixed by one target axis only
+  for (size_t i = 0; i < target.coords.size(); ++i) {
+    if (b.K(target.coords[i])) return false;
+    b.set(target.coords[i]);
+  }
+  if (forced_free)
+    for (int c : *forced_free) {
+      if (b.K(c)) return false;
+      b.set(c);
+      b.free_slots.push_back(g.S(c));
+    }
+  std::vector<char> done(g.prims.size(), 0);
+  for (;;) {
+    bool progress = false;
+    for (size_t k = 0; k < g.prims.size(); ++k)
+      if (!done[k]) {
+        const bool was = done[k];
+        done[k] = step_prim(b, g.prims[k], &progress);
+        if (done[k] != was) progress = true;
+        if (b.failed) return false;
+      }
+    if (progress) continue;
+    bool all = true;
+    for (char d : done) all = all && d;
+    for (int s = 0; s < g.n_slots; ++s) all = all && b.known[s];
+    if (all) break;
+    if (forced_free) return false;
+    const int c = pick_free(b, done);
+    if (c < 0) return false;
+    b.set(c);
+    b.free_slots.push_back(g.S(c));
+  }
+  if (!forced_free) std::reverse(b.free_slots.begin(), b.free_slots.end());   // first chosen varies fastest
+  if (b.ops.size() > (size_t)kMaxOps || b.free_slots.size() > (size_t)kMaxAxes) return false;
+  // split the ops into those that depend on the target only and the rest
+  std::vector<char> dep(g.n_slots, 0);
+  for (int s : b.free_slots) dep[s] = 1;
+  std::vector<IndexOp> first, second;
+  for (const IndexOp& o : b.ops) {
+    bool d = dep[o.a] || (o.b >= 0 && dep[o.b]);
+    if (o.d0 >= 0) dep[o.d0] = d;
+    if (o.d1 >= 0) dep[o.d1] = d;
+    (d ? second : first).push_back(o);
+  }
+  out.n_ops0 = (int32_t)first.size();
+  out.n_ops = (int32_t)b.ops.size();
+  int w = 0;
+  for (const IndexOp& o : first) out.ops[w++] = o;
+  for (const IndexOp& o : second) out.ops[w++] = o;
+  out.n_tgt = (int32_t)target.coords.size();
+  out.n_target = 1;
+  for (int i = 0; i < out.n_tgt; ++i) {
+    out.tgt[i] = AxisRef{g.S(target.coords[i]), (int32_t)g.D(target.coords[i]), (int32_t)target.stride[i]};
+    out.n_target *= g.D(target.coords[i]);
+  }
+  out.n_fre = (int32_t)b.free_slots.size();
+  out.n_free = 1;
+  for (int i = 0; i < out.n_fre; ++i) {
+    out.fre[i] = AxisRef{b.free_slots[i], (int32_t)g.slot_dom[b.free_slots[i]], 0};
+    out.n_free *= g.slot_dom[b.free_slots[i]];
+  }
+  out.n_a = (int32_t)A.coords.size();
+  for (int i = 0; i < out.n_a; ++i)
+    out.a[i] = AxisRef{g.S(A.coords[i]), (int32_t)g.D(A.coords[i]), (int32_t)A.stride[i]};
+  out.n_b = (int32_t)B.coords.size();
+  for (int i = 0; i < out.n_b; ++i)
+    out.b[i] = AxisRef{g.S(B.coords[i]), (int32_t)g.D(B.coords[i]), (int32_t)B.stride[i]};
+  return true;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Affine analysis of the forward index map and recognition of the convolution-like form
+// ---------------------------------------------------------------------------------------------
+struct Root {
+  bool is_reduce = false;
+  bool alive = true;
+  int64_t size = 0;
+  int64_t out_stride = 0;   // output iterators (and their digits): element stride in `out`
+};
+
+struct Expr {
+  std::map<int, int64_t> coef;   // root -> coefficient
+  int64_t c = 0;
+  int64_t wrap = 0;              // value is taken mod `wrap` when non-zero
+  bool complex = false;
+  bool pure() const { return !complex && wrap == 0; }
+};
+
+struct Check { Expr e; int64_t bound; };
+
+Expr add(const Expr& x, int64_t kx, const Expr& y, int64_t ky, int64_t c) {
+  Expr r;
+  r.complex = !x.pure() || !y.pure();
+  for (auto& t : x.coef) r.coef[t.first] += kx * t.second;
+  for (auto& t : y.coef) r.coef[t.first] += ky * t.second;
+  for (auto it = r.coef.begin(); it != r.coef.end();) it = it->second == 0 ? r.coef.erase(it) : std::next(it);
+  r.c = kx * x.c + ky * y.c + c;
+  return r;
+}
+
+bool same_affine(const Expr& a, const Expr& b) { return a.coef == b.coef && a.c == b.c; }
+
+bool recognise_conv(const Graph& g, ConvLike& cv) {
+  std::vector<Root> roots;
+  std::vector<Expr> e(g.n_slots);
+  std::vector<Check> checks;
+  for (int i = 0; i < g.n_out; ++i) {
+    Root r; r.size = g.D(i); r.out_stride = g.out_stride[i];
+    roots.push_back(r);
+    e[g.S(i)].coef[(int)roots.size() - 1] = 1;
+  }
+  for (const syno_prim& p : g.prims) {
+    switch (p.kind) {
+      case SYNO_REDUCE: {
+        Root r; r.is_reduce = true; r.size = p.param;
+        roots.push_back(r);
+        e[g.S(p.out[0])].coef[(int)roots.size() - 1] = 1;
+        break;
+      }
+      case SYNO_SHARE: break;
+      case SYNO_EXPAND: return false;
+      case SYNO_MERGE: {
+        const Expr& x = e[g.S(p.in[0])];
+        if (!x.pure() || x.c != 0 || x.coef.size() != 1 || x.coef.begin()->second != 1) return false;
+        const int r0 = x.coef.begin()->first;      // a bare iterator: refine it into two digits
+        Root hi = roots[r0], lo = roots[r0];
+        hi.size = roots[r0].size / p.param; hi.out_stride = roots[r0].out_stride * p.param;
+        lo.size = p.param;
+        roots[r0].alive = false;
+        roots.push_back(hi);
+        e[g.S(p.out[0])].coef[(int)roots.size() - 1] = 1;
+        roots.push_back(lo);
+        e[g.S(p.out[1])].coef[(int)roots.size() - 1] = 1;
+        break;
+      }
+      case SYNO_SPLIT:
+        e[g.S(p.out[0])] = add(e[g.S(p.in[0])], g.D(p.in[1]), e[g.S(p.in[1])], 1, 0);
+        break;
+      case SYNO_STRIDE:
+        e[g.S(p.out[0])] = add(e[g.S(p.in[0])], p.param, Expr(), 0, 0);
+        break;
+      case SYNO_SHIFT: {
+        Expr by;
+        if (p.shift_by >= 0) by = e[g.S(p.shift_by)];
+        Expr r = add(e[g.S(p.in[0])], 1, by, p.shift_by >= 0 ? p.shift_coef : 0, p.param);
+        r.wrap = g.D(p.in[0]);
+        e[g.S(p.out[0])] = r;
+        break;
+      }
+      case SYNO_UNFOLD: {
+        Expr r = add(e[g.S(p.in[0])], 1, e[g.S(p.in[1])], 1, -(g.D(p.in[1]) / 2));
+        checks.push_back(Check{r, g.D(p.in[0])});
+        e[g.S(p.out[0])] = r;
+        break;
+      }
+    }
+  }
+  if (g.in_coords.size() != 4) return false;
+  const Expr* ax[4];
+  for (int i = 0; i < 4; ++i) {
+    ax[i] = &e[g.S(g.in_coords[i])];
+    if (ax[i]->complex) return false;
+  }
+  // roles
+  enum { R_NONE, R_N, R_G, R_O, R_C, R_H, R_W, R_KH, R_KW };
+  std::vector<int> role(roots.size(), R_NONE);
+  std::memset(&cv, 0, sizeof(cv));
+  cv.N = cv.G = cv.Og = cv.Cg = cv.Ho = cv.Wo = cv.KH = cv.KW = 1;
+  cv.sh = cv.sw = 1;
+  // axis 0: the batch iterator alone
+  if (!ax[0]->pure() || ax[0]->c != 0 || ax[0]->coef.size() != 1) return false;
+  {
+    const int r = ax[0]->coef.begin()->first;
+    if (ax[0]->coef.begin()->second != 1 || roots[r].is_reduce) return false;
+    role[r] = R_N; cv.N = (int32_t)roots[r].size;
+  }
+  // axis 1: channel = Cg*g + c  |  c  |  g
+  if (!ax[1]->pure() || ax[1]->c != 0 || ax[1]->coef.empty() || ax[1]->coef.size() > 2) return false;
+  for (auto& t : ax[1]->coef) {
+    if (role[t.first] != R_NONE) return false;
+    if (roots[t.first].is_reduce) {
+      if (t.second != 1 || cv.Cg != 1) return false;
+      role[t.first] = R_C; cv.Cg = (int32_t)roots[t.first].size;
+    } else {
+      if (cv.G != 1) return false;
+      role[t.first] = R_G; cv.G = (int32_t)roots[t.first].size;
+    }
+  }
+  for (auto& t : ax[1]->coef)
+    if (role[t.first] == R_G && t.second != cv.Cg) return false;
+  if ((int64_t)cv.G * cv.Cg != g.D(g.in_coords[1])) return false;
+  // axes 2, 3: s*h + kh - pad, zero outside; or (h + shift + coef*g) mod size
+  for (int a = 2; a < 4; ++a) {
+    const Expr& x = *ax[a];
+    const int64_t size = g.D(g.in_coords[a]);
+    int32_t out_sz = 1, k_sz = 1, stride = 1, shift_g = 0;
+    for (auto& t : x.coef) {
+      const int r = t.first;
+      if (role[r] == R_G) { if (!x.wrap) return false; shift_g = (int32_t)t.second; continue; }
+      if (role[r] != R_NONE) return false;
+      if (roots[r].is_reduce) {
+        if (t.second != 1 || k_sz != 1 || x.wrap) return false;
+        role[r] = a == 2 ? R_KH : R_KW; k_sz = (int32_t)roots[r].size;
+      } else {
+        if (t.second < 1 || out_sz != 1) return false;
+        role[r] = a == 2 ? R_H : R_W; out_sz = (int32_t)roots[r].size; stride = (int32_t)t.second;
+      }
+    }
+    if (x.wrap) {
+      if (x.wrap != size || stride != 1 || out_sz != size) return false;
+      (a == 2 ? cv.h_wrap : cv.w_wrap) = 1;
+      (a == 2 ? cv.h_shift : cv.w_shift) = pos_mod(x.c, size);
+      (a == 2 ? cv.h_shift_g : cv.w_shift_g) = pos_mod(shift_g, size);
+    } else {
+      if (x.c > 0) return false;
+      (a == 2 ? cv.ph : cv.pw) = (int32_t)(-x.c);
+    }
+    (a == 2 ? cv.Ho : cv.Wo) = out_sz;
+    (a == 2 ? cv.KH : cv.KW) = k_sz;
+    (a == 2 ? cv.sh : cv.sw) = stride;
+    (a == 2 ? cv.Hi : cv.Wi) = (int32_t)size;
+    // Without a window the map must stay inside the axis by itself; with one the Unfold's test guards it.
+    const int64_t lo = x.c, hi = x.c + (int64_t)stride * (out_sz - 1) + (k_sz - 1);
+    if (!x.wrap && k_sz == 1 && (lo < 0 || hi >= size)) return false;
+  }
+  // every range test must be exactly "this X axis lies inside its size"
+  for (const Check& c : checks) {
+    bool ok = false;
+    for (int a = 2; a < 4; ++a)
+      if (!ax[a]->wrap && same_affine(c.e, *ax[a]) && c.bound == g.D(g.in_coords[a])) ok = true;
+    if (!ok) return false;
+  }
+  // weight axes: one bare iterator each
+  std::vector<int64_t> wstride(g.w_coords.size(), 1);
+  for (int i = (int)g.w_coords.size() - 2; i >= 0; --i) wstride[i] = wstride[i + 1] * g.D(g.w_coords[i + 1]);
+  std::vector<char> in_w(roots.size(), 0);
+  for (size_t i = 0; i < g.w_coords.size(); ++i) {
+    const Expr& x = e[g.S(g.w_coords[i])];
+    if (!x.pure() || x.c != 0 || x.coef.size() != 1 || x.coef.begin()->second != 1) return false;
+    const int r = x.coef.begin()->first;
+    if (in_w[r]) return false;
+    in_w[r] = 1;
+    if (role[r] == R_NONE) {
+      if (roots[r].is_reduce || cv.Og != 1) return false;
+      role[r] = R_O; cv.Og = (int32_t)roots[r].size;
+    }
+    const int32_t s = (int32_t)wstride[i];
+    switch (role[r]) {
+      case R_G: cv.ws_g = s; break;
+      case R_O: cv.ws_o = s; break;
+      case R_C: cv.ws_c = s; break;
+      case R_KH: cv.ws_kh = s; break;
+      case R_KW: cv.ws_kw = s; break;
+      default: return false;      // batch or spatial iterators do not index the weight here
+    }
+  }
+  // every live iterator has a role; reduce iterators must reach the weight (else it is a plain sum)
+  for (size_t r = 0; r < roots.size(); ++r) {
+    if (!roots[r].alive) continue;
+    if (role[r] == R_NONE) return false;
+    if (roots[r].is_reduce && !in_w[r]) return false;
+    if (role[r] == R_G && !in_w[r] && roots[r].size > 1) return false;
+  }
+  // the output must be laid out [N, G*Og, Ho, Wo]
+  int64_t expect[9] = {};
+  expect[R_W] = 1; expect[R_H] = cv.Wo; expect[R_O] = (int64_t)cv.Ho * cv.Wo;
+  expect[R_G] = expect[R_O] * cv.Og; expect[R_N] = expect[R_G] * cv.G;
+  for (size_t r = 0; r < roots.size(); ++r) {
+    if (!roots[r].alive || roots[r].is_reduce) continue;
+    if (roots[r].size > 1 && roots[r].out_stride != expect[role[r]]) return false;
+  }
+  return true;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+syno_status build_plan(const syno_desc* desc, int policy, syno_plan* plan, std::string* why) {
+  Graph g;
+  syno_status st = parse_graph(desc, g, why);
+  if (st != SYNO_OK) return st;
+  auto unsupported = [&](const char* m) { if (why) *why = m; return SYNO_ERR_UNSUPPORTED; };
+
+  plan->in_dtype = desc->in_dtype;
+  plan->out_dtype = desc->out_dtype;
+  plan->out_rank = g.n_out;
+  plan->out_elems = 1;
+  for (int i = 0; i < g.n_out; ++i) { plan->out_shape[i] = g.D(i); plan->out_elems *= g.D(i); }
+  plan->x_rank = (int32_t)g.in_coords.size();
+  plan->x_elems = 1;
+  for (int i = 0; i < plan->x_rank; ++i) { plan->x_shape[i] = g.D(g.in_coords[i]); plan->x_elems *= plan->x_shape[i]; }
+  plan->w_rank = (int32_t)g.w_coords.size();
+  plan->w_elems = 1;
+  for (int i = 0; i < plan->w_rank; ++i) { plan->w_shape[i] = g.D(g.w_coords[i]); plan->w_elems *= plan->w_shape[i]; }
+  plan->n_reduce = 1;
+  for (int c : g.reduce_coords) plan->n_reduce *= g.D(c);
+  if (plan->out_elems > kMaxElems || plan->x_elems > kMaxElems || plan->w_elems > kMaxElems ||
+      plan->n_reduce > kMaxElems)
+    return unsupported("a tensor has more than 2^31-1 elements");
+  // Shift offsets are reduced mod N on the host; the kernel's sum i + s + coef*v must fit 32 bits.
+  for (const syno_prim& p : g.prims)
+    if (p.kind == SYNO_SHIFT) {
+      const int64_t N = g.D(p.in[0]), by = p.shift_by >= 0 ? g.D(p.shift_by) : 1;
+      if (2 * N + N * by > kMaxElems) return unsupported("Shift offset range too large");
+    }
+
+  std::vector<int> outs(g.n_out);
+  for (int i = 0; i < g.n_out; ++i) outs[i] = i;
+  const TensorAxes O = axes_of(g, outs), X = axes_of(g, g.in_coords), W = axes_of(g, g.w_coords);
+  if (!build_program(g, O, &g.reduce_coords, X, W, plan->prog[SYNO_FWD]))
+    return unsupported("forward index map could not be lowered");
+  if (!build_program(g, X, nullptr, O, W, plan->prog[SYNO_BWD_DATA]))
+    return unsupported("backward-data index map could not be inverted");
+  if (!build_program(g, W, nullptr, O, X, plan->prog[SYNO_BWD_WEIGHT]))
+    return unsupported("backward-weight index map could not be inverted");
+
+  plan->conv_like = recognise_conv(g, plan->conv);
+
+  for (int which = 0; which < 3; ++which) {
+    Launch& L = plan->launch[which];
+    const IndexProgram& P = plan->prog[which];
+    L.kernel = KERNEL_GENERIC;
+    // Few targets with a long sum each: one workgroup per target, lanes share the sum.
+    L.coop = (P.n_free >= 512 && P.n_target < (1 << 18)) ? 1 : 0;
+    L.workspace = 0;
+  }
+  (void)policy;
+  return SYNO_OK;
+}
+
+}  // namespace syno

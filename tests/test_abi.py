@@ -1,0 +1,139 @@
+"""Host-side checks of the GPU library: it loads, exports what the header declares, rejects bad
+graphs, and its lowered index maps (forward and both gradients) agree with the CPU checker bit
+for bit.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from syno_inputs import BF16, F32, Builder, workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def syno():
+    import paper_2410_23745_amd as s
+    if not os.path.exists(s.library_path()):
+        from paper_2410_23745_amd import build
+        build.build()
+    s.load_library()
+    return s
+
+
+def test_library_exports_every_declared_symbol(syno):
+    header = open(os.path.join(ROOT, "include", "syno.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(syno_[a-z_]+)\s*\(", header))
+    assert {"syno_plan_create", "syno_forward", "syno_backward_data", "syno_backward_weight",
+            "syno_plan_destroy"} <= declared
+    lib = ctypes.CDLL(syno.library_path())
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+
+
+def test_status_strings(syno):
+    lib = syno.load_library()
+    assert lib.syno_status_string(0) == b"ok"
+    assert all(lib.syno_status_string(i) for i in range(8))
+
+
+def test_rejects_invalid_graphs(syno):
+    b = Builder([("i", 10)])
+    q, r = b.merge(0, 3)
+    with pytest.raises(syno.SynoError) as e:
+        syno.Plan(b.finish([q, r], []))
+    assert e.value.status == 2
+    b = Builder([("i", 4), ("j", 4)])
+    with pytest.raises(syno.SynoError):
+        syno.Plan(b.finish([0], []))                 # j never consumed
+    b = Builder([("i", 4)])
+    with pytest.raises(syno.SynoError):
+        syno.Plan(b.finish([0, 0], []))              # i consumed twice
+    b = Builder([("i", 4)])
+    r = b.reduce(3)
+    b.expand(r)
+    with pytest.raises(syno.SynoError):
+        syno.Plan(b.finish([0], []))                 # Reduce straight into Expand
+    b = Builder([("i", 1 << 20), ("j", 1 << 12)])
+    v = b.split(0, 1)
+    with pytest.raises(syno.SynoError) as e:
+        syno.Plan(b.finish([v], []))                 # 2^32 elements
+    assert e.value.status == 4
+
+
+def test_shapes_match_the_checker(syno, oracle):
+    for d in (wl.conv2d(2, 3, 4, 5, 6), wl.grouped_shift_unfold(2), wl.strided_depthwise(2, 4, 7, 7), wl.matmul(3, 4, 5)):
+        p = syno.Plan(d)
+        xs, ws, red = oracle.describe(d)
+        assert p.x_shape == xs and p.w_shape == ws and p.out_shape == oracle.out_shape(d)
+        assert p.free_size(syno.FWD) == int(np.prod(red))
+
+
+def pixel_unshuffle_conv():
+    """A graph outside the convolution-like form: Merge above Unfold, Stride, Expand, two Shifts."""
+    b = Builder([("n", 2), ("co", 3), ("h", 6), ("e", 2)])
+    c = b.reduce(4)
+    cx, cw = b.share(c)
+    k = b.reduce(3)
+    kx, kw = b.share(k)
+    u = b.unfold(2, kx)          # h + k - 1 : 6
+    q, r = b.merge(u, 2)         # (u/2, u%2) : 3, 2
+    s = b.shift(q, -1)
+    t = b.stride(r, 3)           # 3*(u%2) : 6
+    t2 = b.shift(t, 2, by=s, coef=1)
+    b.expand(3)
+    return b.finish([0, cx, s, t2], [1, cw, kw])
+
+
+CASES = [
+    lambda: wl.conv2d(2, 3, 4, 5, 6),
+    lambda: wl.conv2d(1, 2, 2, 4, 5, 4, 2),
+    lambda: wl.grouped_shift_unfold(2, 8, 8, 5, 4, 4, 3),
+    lambda: wl.strided_depthwise(2, 3, 3, 4),
+    lambda: wl.matmul(3, 4, 5),
+    pixel_unshuffle_conv,
+]
+
+
+@pytest.mark.parametrize("mk", CASES)
+def test_index_maps_bit_exact_against_checker(syno, oracle, mk):
+    d = mk()
+    p = syno.Plan(d)
+    _, _, red = oracle.describe(d)
+    n_o, n_r = int(np.prod(p.out_shape)), int(np.prod(red)) if red else 1
+    o, r = (a.ravel() for a in np.meshgrid(np.arange(n_o), np.arange(n_r), indexing="ij"))
+    xo, wo = oracle.gather_map(d, o, r)
+    a, b = p.debug_gather_host(syno.FWD, o, r)
+    assert np.array_equal(a, xo) and np.array_equal(b, wo)
+    ok = xo >= 0
+    terms = sorted(zip(o[ok].tolist(), xo[ok].tolist(), wo[ok].tolist()))
+    # The gradients enumerate the same set of terms (o, x, w), grouped by x or by w; the order inside a group is
+    # the planner's own, so compare as sorted sets: every term once, none invented.
+    for which, n_t in ((syno.BWD_DATA, int(np.prod(p.x_shape))), (syno.BWD_WEIGHT, int(np.prod(p.w_shape)))):
+        t, q = (v.ravel() for v in np.meshgrid(np.arange(n_t), np.arange(p.free_size(which)), indexing="ij"))
+        a, b = p.debug_gather_host(which, t, q)
+        v = a >= 0
+        assert np.array_equal(v, b >= 0)
+        got = zip(a[v].tolist(), t[v].tolist(), b[v].tolist()) if which == syno.BWD_DATA else \
+            zip(a[v].tolist(), b[v].tolist(), t[v].tolist())
+        assert sorted(got) == terms
+
+
+def test_out_of_range_points_yield_minus_one(syno):
+    p = syno.Plan(wl.conv2d(1, 2, 2, 3, 3))
+    a, b = p.debug_gather_host(syno.FWD, [0, 18, -1, 0], [0, 0, 0, 18])
+    assert a[1] == -1 and a[2] == -1 and a[3] == -1 and b[2] == -1
+
+
+def test_kernel_choice(syno):
+    names = lambda d: [syno.Plan(d).kernel(i) for i in range(3)]
+    assert all(n == "generic_index_program" for n in names(wl.matmul(3, 4, 5)))
+    assert all(n == "generic_index_program" for n in names(pixel_unshuffle_conv()))
+    syno.set_kernel_policy(1)
+    try:
+        assert all(n == "generic_index_program" for n in names(wl.strided_depthwise(2, 4, 7, 7)))
+    finally:
+        syno.set_kernel_policy(0)

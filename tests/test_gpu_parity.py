@@ -1,0 +1,183 @@
+"""GPU parity: the HIP path against the CPU checker on the same seeded inputs, through the C ABI.
+
+Small cases are compared element by element (sizes the checker finishes in seconds, spanning several
+tiles and ragged tails); the full-size workloads are compared on sampled outputs where the checker
+cannot finish the whole tensor quickly, else in full.  Index maps are compared bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+from syno_inputs import BF16, F32, Builder, workloads as wl
+from util import rel_l2, to_dev, to_host, tol_for
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def syno():
+    import paper_2410_23745_amd as s
+    s.load_library()          # raises if the HIP library has not been built: there is no fallback
+    assert torch.cuda.is_available()
+    return s
+
+
+def run_all(syno, oracle, w, policy, directions=(0, 1, 2), full=True, n_sample=4096, seed=0):
+    """Run the requested directions on the GPU and compare with the checker.  Returns kernel names."""
+    syno.set_kernel_policy(policy)
+    try:
+        plan = syno.Plan(w.desc)
+    finally:
+        syno.set_kernel_policy(0)
+    d, tol = w.desc, tol_for(w.desc)
+    X, W = to_dev(w.X, w.X_bits), to_dev(w.W, w.W_bits)
+    rng = np.random.default_rng(seed)
+    names = [plan.kernel(i) for i in range(3)]
+    if 0 in directions:
+        print(f"[case] {d.name} fwd kernel={names[0]} policy={policy}", flush=True)
+        out = plan.forward(X, W)
+        torch.cuda.synchronize()
+        got = to_host(out).ravel()
+        if full:
+            ref = oracle.forward(d, w.X, w.W).ravel()
+        else:
+            idx = np.unique(rng.integers(0, got.size, n_sample))
+            ref, got = oracle.forward_at(d, w.X, w.W, idx), got[idx]
+        e = rel_l2(got, ref)
+        assert e <= tol, f"forward rel-L2 {e:.3e} > {tol}"
+    if 1 in directions or 2 in directions:
+        G = to_dev(w.G, w.G_bits)
+        xs = ws = None
+        if not full:
+            xs = np.unique(rng.integers(0, int(np.prod(w.x_shape)), n_sample))
+            ws = np.unique(rng.integers(0, int(np.prod(w.w_shape)), n_sample))
+        rdx, rdw = oracle.backward(d, w.X, w.W, w.G, 1 in directions, 2 in directions, x_sample=xs, w_sample=ws)
+        if 1 in directions:
+            print(f"[case] {d.name} bwd-data kernel={names[1]} policy={policy}", flush=True)
+            dX = plan.backward_data(G, W)
+            torch.cuda.synchronize()
+            got = to_host(dX).ravel()
+            e = rel_l2(got if full else got[xs], rdx)
+            assert e <= tol, f"backward-data rel-L2 {e:.3e} > {tol}"
+        if 2 in directions:
+            print(f"[case] {d.name} bwd-weight kernel={names[2]} policy={policy}", flush=True)
+            dW = plan.backward_weight(X, G)
+            torch.cuda.synchronize()
+            assert dW.dtype == torch.float32
+            got = to_host(dW).ravel()
+            e = rel_l2(got if full else got[ws], rdw)
+            assert e <= tol, f"backward-weight rel-L2 {e:.3e} > {tol}"
+    return names
+
+
+# ------------------------------------------------------------------------------------------------
+# small cases, every direction, both the generic kernels (policy 1) and the planner's choice (0)
+# ------------------------------------------------------------------------------------------------
+def small_cases():
+    c = {}
+    c["config0"] = lambda: wl.make_conv(1, 16, 16, seed=0, with_grad=True)
+    c["conv_f32_ragged"] = lambda: wl.make_conv(3, 24, 13, seed=4, Co=40, Wd=19, with_grad=True)
+    c["conv_bf16_ragged"] = lambda: wl.make_conv(3, 40, 13, seed=5, Co=24, Wd=19, bf16=True, with_grad=True)
+    c["conv_bf16_out_bf16"] = lambda: wl.make_conv(2, 32, 14, seed=6, bf16=True, with_grad=True, out_bf16=True)
+    c["conv_f32_5x5"] = lambda: wl.make_conv(2, 8, 9, seed=7, Co=16, K=5, with_grad=True)
+    c["conv_f32_1x1"] = lambda: wl.make_conv(2, 16, 7, seed=8, Co=32, K=1, with_grad=True)
+    c["conv_f32_stage3_small_batch"] = lambda: wl.make_conv(2, 512, 7, seed=9, with_grad=True)
+    c["gshift_bf16"] = lambda: wl.make_gshift(3, seeds=(1, 2, 3), with_grad=True)
+    c["gshift_bf16_small_groups"] = lambda: wl.make_gshift(2, seeds=(4, 5, 6), with_grad=True, C=96, H=9, Wd=11, groups=3)
+    c["depthwise_f32"] = lambda: wl.make_depthwise(3, 20, 30, seed=2, with_grad=True)
+    c["depthwise_f32_odd"] = lambda: wl.make_depthwise(2, 7, 18, seed=3, with_grad=True)
+    return c
+
+
+@pytest.mark.parametrize("policy", [1, 0])
+@pytest.mark.parametrize("name", list(small_cases()))
+def test_small_cases_all_directions(syno, oracle, name, policy):
+    run_all(syno, oracle, small_cases()[name](), policy)
+
+
+def test_table2_examples_and_odd_graphs(syno, oracle):
+    rng = np.random.default_rng(11)
+    from test_abi import pixel_unshuffle_conv
+    for d in (wl.matmul(37, 29, 45), pixel_unshuffle_conv()):
+        xs, ws, _ = oracle.describe(d)
+        X, W = rng.standard_normal(xs).astype(np.float32), rng.standard_normal(ws).astype(np.float32)
+        G = rng.standard_normal(oracle.out_shape(d)).astype(np.float32)
+        w = wl.Workload(d, xs, ws, oracle.out_shape(d), X, W, G, None, None, None, 0)
+        run_all(syno, oracle, w, 0)
+
+
+def test_stride_backward_writes_zeros(syno, oracle):
+    # Stride 2 under a 1-wide window: odd rows and columns of dX receive no term and must be written as 0.
+    b = Builder([("n", 2), ("c", 5), ("h", 6), ("w", 7)])
+    cx, cw = b.share(1)
+    hs, ws_ = b.stride(2, 2), b.stride(3, 2)
+    d = b.finish([0, cx, hs, ws_], [cw])
+    plan = syno.Plan(d)
+    G = torch.randn(plan.out_shape, device="cuda")
+    W = torch.randn(plan.w_shape, device="cuda")
+    dX = torch.full(plan.x_shape, 7.0, device="cuda")
+    plan.backward_data(G, W, dX=dX)
+    torch.cuda.synchronize()
+    ref, _ = oracle.backward(d, np.zeros(plan.x_shape), to_host(W), to_host(G), True, False)
+    assert rel_l2(to_host(dX), ref) <= 1e-6
+    assert float(dX[:, :, 1::2, :].abs().max()) == 0.0 and float(dX[:, :, :, 1::2].abs().max()) == 0.0
+
+
+# ------------------------------------------------------------------------------------------------
+# index maps on the device, bit exact
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("mk", [lambda: wl.config0().desc, lambda: wl.grouped_shift_unfold(32),
+                                lambda: wl.strided_depthwise(64, 128, 28, 28),
+                                lambda: wl.conv2d(32, 512, 512, 7, 7)])
+def test_device_gather_map_bit_exact(syno, oracle, mk):
+    d = mk()
+    plan = syno.Plan(d)
+    n_o, n_r = int(np.prod(plan.out_shape)), plan.free_size(syno.FWD)
+    if n_o * n_r <= (1 << 20):
+        o, r = (a.ravel() for a in np.meshgrid(np.arange(n_o), np.arange(n_r), indexing="ij"))
+    else:
+        rng = np.random.default_rng(1)
+        o, r = rng.integers(0, n_o, 1 << 20), rng.integers(0, n_r, 1 << 20)
+    xo, wo = oracle.gather_map(d, o, r)
+    a, b = plan.debug_gather(syno.FWD, torch.from_numpy(o).cuda(), torch.from_numpy(r).cuda())
+    assert np.array_equal(a.cpu().numpy(), xo) and np.array_equal(b.cpu().numpy(), wo)
+    # the device and the host evaluation of the gradient maps agree as well
+    for which, n_t in ((syno.BWD_DATA, int(np.prod(plan.x_shape))), (syno.BWD_WEIGHT, int(np.prod(plan.w_shape)))):
+        rng = np.random.default_rng(2 + which)
+        t, q = rng.integers(0, n_t, 1 << 16), rng.integers(0, plan.free_size(which), 1 << 16)
+        a, b = plan.debug_gather(which, torch.from_numpy(t).cuda(), torch.from_numpy(q).cuda())
+        ha, hb = plan.debug_gather_host(which, t, q)
+        assert np.array_equal(a.cpu().numpy(), ha) and np.array_equal(b.cpu().numpy(), hb)
+
+
+# ------------------------------------------------------------------------------------------------
+# the full-size workloads, in the configuration the benchmark times
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("stage", [0, 1, 2, 3])
+def test_config1_full_size_sampled(syno, oracle, stage, bf16):
+    run_all(syno, oracle, wl.config1(stage, bf16), 0, directions=(0,), full=False)
+
+
+def test_config2_full_size(syno, oracle):
+    run_all(syno, oracle, wl.config2(), 0, directions=(0,), full=True)
+
+
+def test_config3_full_size(syno, oracle):
+    run_all(syno, oracle, wl.config3(), 0, directions=(0,), full=True)
+
+
+def test_config4_full_size_training_step(syno, oracle):
+    run_all(syno, oracle, wl.config4(), 0, directions=(0, 1, 2), full=False, n_sample=8192)
+
+
+def test_rejects_wrong_arguments(syno):
+    plan = syno.Plan(wl.conv2d(1, 4, 4, 5, 5))
+    X = torch.zeros(plan.x_shape, device="cuda")
+    W = torch.zeros(plan.w_shape, device="cuda")
+    with pytest.raises(ValueError):
+        plan.forward(X[:, :2], W)
+    with pytest.raises(ValueError):
+        plan.forward(X.to(torch.bfloat16), W)
+    lib = syno.load_library()
+    assert lib.syno_forward(plan._h, None, W.data_ptr(), X.data_ptr(), None, None) == 1

@@ -1,10 +1,392 @@
-// MFMA contraction family (placeholder until the tuned kernels land).
+// MFMA contraction family: convolution-like operators whose Reduce is a real dense contraction,
+//   out[n, g*Og+o, h, w] = sum_{c,kh,kw} X[n, g*Cg+c, row(h,kh,g), w+kw-pw] * W[g,o,c,kh,kw]
+// computed as an implicit GEMM per group: M = output pixels (n,h,w), N = output channels o,
+// K = (c,kh,kw).  Nothing is materialised: Unfold's window, Shift's cyclic row offset and the
+// zero padding are folded into how the input tile is gathered into LDS.
+//
+// One workgroup owns TR whole output rows (of one or several images) x BN output channels.  Per
+// chunk of KC input channels it stages
+//   - the input rows those output rows touch, each row into a "slot" of Wp = Wi+KW-1 pixels whose
+//     edge pixels stay zero (the padding), rows outside the image left zero; pixels are stored
+//     channel-innermost, CI channels = 16 bytes per pixel, so that an MFMA operand fragment is one
+//     LDS read per lane and a window tap is a constant address offset (kh*Wp + kw pixels);
+//   - the BN x KC x KH x KW weight block;
+// then issues 16x16 MFMAs whose K-step is CI consecutive channels at one tap.
 #include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
 
 #include "plan.h"
 
 namespace syno {
-syno_status launch_mfma(const syno_plan*, int, const void*, const void*, void*, void*, hipStream_t) {
-  return SYNO_ERR_UNSUPPORTED;
+
+struct MfmaParams {
+  // problem, in forward terms
+  int32_t G, Og, Cg, Ho, Wo, Hi, Wi, KH, KW, ph, pw;
+  int32_t rows_total;                 // N*Ho output rows
+  int32_t h_wrap, h_shift, h_shift_g; // cyclic rows: input row = (h + h_shift + h_shift_g*g) mod Hi  (KH = 1)
+  int32_t xs_n, xs_c;                 // source strides: image, channel (rows are Wi apart, columns adjacent)
+  int32_t os_n, os_o;                 // result strides: image, channel
+  int32_t ws_g, ws_o, ws_c, ws_kh, ws_kw, w_base;
+  // tiling
+  int32_t TR, KC, n_mblocks, n_nblocks, n_chunks;
+  int32_t n_slots, Wp, cgrps;
+  int32_t w_row;                      // LDS weight row pitch (elements)
+  int32_t lds_w_off, lds_tab_off, lds_bytes;
+};
+
+namespace {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
 }
+
+// Source of each row slot: element offset of the input row inside the tensor, or -1 when the slot
+// is padding (above/below the image, or beyond the rows this block owns).
+__device__ __forceinline__ int slot_source(const MfmaParams& p, int R0, int rows, int g, int s) {
+  if (p.h_wrap) {
+    if (s >= rows) return -1;
+    const int rho = R0 + s, n = rho / p.Ho, h = rho - n * p.Ho;
+    const int r = (h + p.h_shift + p.h_shift_g * g) % p.Hi;
+    return n * p.xs_n + r * p.Wi;
+  }
+  int rho = R0, s0 = 0;
+  const int end = R0 + rows;
+  while (rho < end) {
+    const int n = rho / p.Ho, h = rho - n * p.Ho;
+    const int seg_rows = min(p.Ho - h, end - rho);
+    const int seg_slots = seg_rows + p.KH - 1;
+    if (s < s0 + seg_slots) {
+      const int r = h + (s - s0) - p.ph;
+      return (r >= 0 && r < p.Hi) ? n * p.xs_n + r * p.Wi : -1;
+    }
+    s0 += seg_slots;
+    rho += seg_rows;
+  }
+  return -1;
+}
+
+// First slot of output row i of the block (tap kh adds kh slots).
+__device__ __forceinline__ int slot_of_row(const MfmaParams& p, int R0, int i) {
+  if (p.h_wrap) return i;
+  return i + (p.KH - 1) * ((R0 + i) / p.Ho - R0 / p.Ho);
+}
+
+// fp32: CI = 4 channels per pixel slot, v_mfma_f32_16x16x4_f32 (A: lane -> row l%16, k l/16).
+template <int WM, int WN, int TM, int TN, int XI, int WI, bool OUTBF>
+__global__ __launch_bounds__(WM* WN * 64) void conv_mfma_f32(const MfmaParams p, const float* __restrict__ X,
+                                                             const float* __restrict__ Wt, void* __restrict__ out) {
+  constexpr int NT = WM * WN * 64;
+  constexpr int BN = WN * TN * 16;
+  constexpr int CI = 4;
+  extern __shared__ __align__(16) unsigned char smem[];
+  float4* xl = reinterpret_cast<float4*>(smem);
+  const float* xlf = reinterpret_cast<const float*>(smem);
+  float* wl = reinterpret_cast<float*>(smem + p.lds_w_off);
+  int* slot_src = reinterpret_cast<int*>(smem + p.lds_tab_off);
+
+  const int tid = threadIdx.x, lane = tid & 63, widx = tid >> 6;
+  const int wn = widx / WM;
+  const int wm = (widx + wn) % WM;          // spread the fuller wave rows over the SIMDs
+  int bid = blockIdx.x;
+  const int nb = bid % p.n_nblocks; bid /= p.n_nblocks;
+  const int mb = bid % p.n_mblocks;
+  const int g = bid / p.n_mblocks;
+  const int R0 = mb * p.TR;
+  const int rows = min(p.TR, p.rows_total - R0);
+  const int KHW = p.KH * p.KW;
+
+  for (int s = tid; s < p.n_slots; s += NT) slot_src[s] = slot_source(p, R0, rows, g, s);
+  {
+    const int n16 = p.cgrps * p.n_slots * p.Wp;
+    for (int i = tid; i < n16; i += NT) xl[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  __syncthreads();
+
+  // ---- loop-invariant descriptors of what this thread stages per chunk
+  const float* Xg = X + (int64_t)g * p.Cg * p.xs_c;
+  const float* Wg = Wt + p.w_base + (int64_t)g * p.ws_g + (int64_t)nb * BN * p.ws_o;
+  int x_goff[XI], x_loff[XI], x_cg[XI];
+  {
+    const int per_cg = p.n_slots * p.Wi, total = p.cgrps * per_cg;
+#pragma unroll
+    for (int k = 0; k < XI; ++k) {
+      const int idx = tid + k * NT;
+      const int cg = idx / per_cg, rem = idx - cg * per_cg;
+      const int s = rem / p.Wi, x = rem - s * p.Wi;
+      const int src = idx < total ? slot_src[s] : -1;
+      x_goff[k] = src >= 0 ? src + x + cg * CI * p.xs_c : -1;
+      x_loff[k] = (cg * p.n_slots + s) * p.Wp + x + p.pw;
+      x_cg[k] = cg * CI;
+    }
+  }
+  int w_goff[WI], w_meta[WI];   // meta: LDS dword offset | local channel << 20
+  {
+    const int per_o = p.KC * KHW, total = BN * per_o;
+#pragma unroll
+    for (int k = 0; k < WI; ++k) {
+      const int idx = tid + k * NT;
+      const int o = idx / per_o, e = idx - o * per_o;
+      const int cl = e / KHW, tap = e - cl * KHW;
+      const int kh = tap / p.KW, kw = tap - kh * p.KW;
+      const bool ok = idx < total && nb * BN + o < p.Og;
+      w_goff[k] = ok ? o * p.ws_o + cl * p.ws_c + kh * p.ws_kh + kw * p.ws_kw : -1;
+      w_meta[k] = (idx < total ? o * p.w_row + e : 0) | (cl << 20) | (idx < total ? 0 : (1 << 30));
+    }
+  }
+  // ---- per-lane operand bases (dword indices)
+  const int block_px = rows * p.Wo;
+  int a_base[TM];
+#pragma unroll
+  for (int t = 0; t < TM; ++t) {
+    int m = (wm * TM + t) * 16 + (lane & 15);
+    if (m >= block_px) m = 0;
+    const int i = m / p.Wo, w = m - i * p.Wo;
+    a_base[t] = (slot_of_row(p, R0, i) * p.Wp + w) * 4 + (lane >> 4);
+  }
+  int b_base[TN];
+#pragma unroll
+  for (int u = 0; u < TN; ++u) b_base[u] = ((wn * TN + u) * 16 + (lane & 15)) * p.w_row + (lane >> 4) * KHW;
+  const int MT = (block_px + 15) >> 4;
+  const int my_tiles = max(0, min(TM, MT - wm * TM));
+
+  floatx4 acc[TM][TN];
+#pragma unroll
+  for (int t = 0; t < TM; ++t)
+#pragma unroll
+    for (int u = 0; u < TN; ++u) acc[t][u] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  float xr[XI][CI], wr[WI];
+  auto fetch = [&](int c0) {
+#pragma unroll
+    for (int k = 0; k < XI; ++k)
+#pragma unroll
+      for (int j = 0; j < CI; ++j) {
+        const int c = c0 + x_cg[k] + j;
+        xr[k][j] = (x_goff[k] >= 0 && c < p.Cg) ? Xg[x_goff[k] + (int64_t)(c0 + j) * p.xs_c] : 0.f;
+      }
+#pragma unroll
+    for (int k = 0; k < WI; ++k) {
+      const int cl = (w_meta[k] >> 20) & 1023;
+      wr[k] = (w_goff[k] >= 0 && c0 + cl < p.Cg) ? Wg[w_goff[k] + (int64_t)c0 * p.ws_c] : 0.f;
+    }
+  };
+  fetch(0);
+  for (int ch = 0; ch < p.n_chunks; ++ch) {
+    __syncthreads();   // everyone has finished reading the previous chunk
+#pragma unroll
+    for (int k = 0; k < XI; ++k)
+      if (x_goff[k] >= 0) xl[x_loff[k]] = make_float4(xr[k][0], xr[k][1], xr[k][2], xr[k][3]);
+#pragma unroll
+    for (int k = 0; k < WI; ++k)
+      if (!(w_meta[k] >> 30)) wl[w_meta[k] & 0xfffff] = wr[k];
+    __syncthreads();
+    if (ch + 1 < p.n_chunks) fetch((ch + 1) * p.KC);
+    for (int cg = 0; cg < p.cgrps; ++cg) {
+      const int a_cg = cg * p.n_slots * p.Wp * 4;
+      const int b_cg = cg * CI * KHW;
+      for (int kh = 0; kh < p.KH; ++kh)
+        for (int kw = 0; kw < p.KW; ++kw) {
+          const int a_off = a_cg + (kh * p.Wp + kw) * 4;
+          const int b_off = b_cg + kh * p.KW + kw;
+          float b[TN];
+#pragma unroll
+          for (int u = 0; u < TN; ++u) b[u] = wl[b_base[u] + b_off];
+#pragma unroll
+          for (int t = 0; t < TM; ++t)
+            if (t < my_tiles) {
+              const float a = xlf[a_base[t] + a_off];
+#pragma unroll
+              for (int u = 0; u < TN; ++u) acc[t][u] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b[u], acc[t][u], 0, 0, 0);
+            }
+        }
+    }
+  }
+
+  // ---- store: lane holds 4 consecutive pixels (rows of D) of one channel (column of D)
+  const int img_px = p.Ho * p.Wo;
+#pragma unroll
+  for (int t = 0; t < TM; ++t) {
+    if (t >= my_tiles) continue;
+    const int m0 = (wm * TM + t) * 16 + 4 * (lane >> 4);
+#pragma unroll
+    for (int u = 0; u < TN; ++u) {
+      const int o = nb * BN + (wn * TN + u) * 16 + (lane & 15);
+      if (o >= p.Og || m0 >= block_px) continue;
+      const int mg = R0 * p.Wo + m0;
+      const int n = mg / img_px, px = mg - n * img_px;
+      const int64_t off = (int64_t)n * p.os_n + (int64_t)(g * p.Og + o) * p.os_o + px;
+      const bool together = m0 + 3 < block_px && px + 3 < img_px;
+      if constexpr (OUTBF) {
+        uint16_t* op = reinterpret_cast<uint16_t*>(out);
+        if (together && (off & 3) == 0) {
+          uint2 v;
+          v.x = f32_to_bf16_rne(acc[t][u][0]) | ((uint32_t)f32_to_bf16_rne(acc[t][u][1]) << 16);
+          v.y = f32_to_bf16_rne(acc[t][u][2]) | ((uint32_t)f32_to_bf16_rne(acc[t][u][3]) << 16);
+          *reinterpret_cast<uint2*>(op + off) = v;
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (m0 + j < block_px) {
+              const int mgj = mg + j, nj = mgj / img_px;
+              op[(int64_t)nj * p.os_n + (int64_t)(g * p.Og + o) * p.os_o + (mgj - nj * img_px)] =
+                  f32_to_bf16_rne(acc[t][u][j]);
+            }
+        }
+      } else {
+        float* op = reinterpret_cast<float*>(out);
+        if (together && (off & 3) == 0) {
+          *reinterpret_cast<float4*>(op + off) = make_float4(acc[t][u][0], acc[t][u][1], acc[t][u][2], acc[t][u][3]);
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (m0 + j < block_px) {
+              const int mgj = mg + j, nj = mgj / img_px;
+              op[(int64_t)nj * p.os_n + (int64_t)(g * p.Og + o) * p.os_o + (mgj - nj * img_px)] = acc[t][u][j];
+            }
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Host side: tile choice and launch
+// ---------------------------------------------------------------------------------------------
+struct Variant {
+  int WM, WN, TM, TN, XI, WI;
+  constexpr int NT() const { return WM * WN * 64; }
+  constexpr int BN() const { return WN * TN * 16; }
+  constexpr int MT() const { return WM * TM; }
+};
+// fp32 tile variants: BN = 64, 32, 16 output channels per workgroup; 8 waves
+constexpr Variant kF32Variants[] = {{4, 2, 7, 2, 3, 9}, {4, 2, 7, 1, 3, 5}, {8, 1, 4, 1, 3, 3}};
+constexpr int kNumCU = 256;
+
+int images_spanned(int TR, int Ho) { return (TR + Ho - 2) / Ho + 1; }
+
+// LDS weight row pitch (in elements) >= need such that the 64 lanes of a B-fragment read
+// (16 rows x 4 channel steps of `kstep` elements) fall into distinct banks where possible.
+int pick_w_row(int need, int kstep) {
+  int best = need, best_conf = 1 << 30;
+  for (int r = need; r < need + 64; ++r) {
+    int cnt[64] = {};
+    int conf = 0;
+    for (int n = 0; n < 16; ++n)
+      for (int k = 0; k < 4; ++k) conf = std::max(conf, ++cnt[(n * r + k * kstep) & 63]);
+    if (conf < best_conf) { best_conf = conf; best = r; }
+    if (conf == 1) break;
+  }
+  return best;
+}
+
+bool fill_params_f32(const syno_plan* plan, int vi, int TR, MfmaParams& p) {
+  const ConvLike& c = plan->conv;
+  const Variant& v = kF32Variants[vi];
+  p = MfmaParams{};
+  p.G = c.G; p.Og = c.Og; p.Cg = c.Cg; p.Ho = c.Ho; p.Wo = c.Wo; p.Hi = c.Hi; p.Wi = c.Wi;
+  p.KH = c.KH; p.KW = c.KW; p.ph = c.ph; p.pw = c.pw;
+  p.rows_total = c.N * c.Ho;
+  p.h_wrap = c.h_wrap; p.h_shift = c.h_shift; p.h_shift_g = c.h_shift_g;
+  p.xs_c = c.Hi * c.Wi; p.xs_n = c.G * c.Cg * p.xs_c;
+  p.os_o = c.Ho * c.Wo; p.os_n = c.G * c.Og * p.os_o;
+  p.ws_g = c.ws_g; p.ws_o = c.ws_o; p.ws_c = c.ws_c; p.ws_kh = c.ws_kh; p.ws_kw = c.ws_kw; p.w_base = 0;
+  p.TR = TR;
+  const int KHW = c.KH * c.KW;
+  p.KC = 8;
+  while (p.KC > 4 && (v.BN() * p.KC * KHW > v.WI * v.NT())) p.KC -= 4;
+  if (v.BN() * p.KC * KHW > v.WI * v.NT()) return false;
+  p.cgrps = p.KC / 4;
+  p.n_chunks = (c.Cg + p.KC - 1) / p.KC;
+  p.n_mblocks = (p.rows_total + TR - 1) / TR;
+  p.n_nblocks = (c.Og + v.BN() - 1) / v.BN();
+  p.n_slots = c.h_wrap ? TR : TR + (c.KH - 1) * images_spanned(TR, c.Ho);
+  p.Wp = c.Wi + c.KW - 1;
+  if ((TR * c.Wo + 15) / 16 > v.MT()) return false;
+  if (p.cgrps * p.n_slots * c.Wi > v.XI * v.NT()) return false;
+  p.w_row = pick_w_row(p.KC * KHW, KHW);
+  const int x_bytes = p.cgrps * p.n_slots * p.Wp * 16;
+  p.lds_w_off = x_bytes;
+  p.lds_tab_off = p.lds_w_off + v.BN() * p.w_row * 4;
+  p.lds_bytes = p.lds_tab_off + ((p.n_slots * 4 + 15) & ~15);
+  return p.lds_bytes <= 64 * 1024 && p.w_row * v.BN() < (1 << 20);
+}
+
+// Estimated duration in units of "one 16x16 MFMA tile over the whole reduction per SIMD".
+double tile_cost(const MfmaParams& p, const Variant& v, const ConvLike& c) {
+  const int64_t wgs = (int64_t)p.n_mblocks * p.n_nblocks * c.G;
+  const int MT = (p.TR * c.Wo + 15) / 16;
+  const double per_wg = std::ceil(MT * (double)(v.BN() / 16) / 4.0);      // tiles per SIMD
+  const double rounds = std::ceil((double)wgs / kNumCU);
+  // staging and barriers cost a little per chunk; prefer fuller tiles at equal MFMA time
+  return rounds * (per_wg + 0.35) ;
+}
+
+template <int VI, bool OUTBF>
+void launch_f32(const MfmaParams& p, const float* X, const float* W, void* out, hipStream_t s) {
+  constexpr Variant v = kF32Variants[VI];
+  const int grid = p.n_mblocks * p.n_nblocks * p.G;
+  hipLaunchKernelGGL((conv_mfma_f32<v.WM, v.WN, v.TM, v.TN, v.XI, v.WI, OUTBF>), dim3(grid), dim3(v.WM * v.WN * 64),
+                     p.lds_bytes, s, p, X, W, out);
+}
+
+}  // namespace
+
+bool mfma_supports(const syno_plan* p, int which) {
+  if (!p->conv_like || which != SYNO_FWD) return false;
+  if (p->in_dtype != SYNO_F32) return false;
+  const ConvLike& c = p->conv;
+  if (c.sh != 1 || c.sw != 1 || c.w_wrap) return false;
+  if (c.h_wrap && c.KH != 1) return false;
+  if (c.Wi != c.Wo || c.Hi != c.Ho) return false;
+  if (c.Og == 1 && c.Cg == 1) return false;          // no contraction to speak of
+  MfmaParams mp;
+  for (int vi = 0; vi < 3; ++vi)
+    for (int TR = 1; TR <= c.N * c.Ho; ++TR) {
+      if (fill_params_f32(p, vi, TR, mp)) return true;
+      if (TR * c.Wo > 16 * 32) break;
+    }
+  return false;
+}
+
+void mfma_configure(syno_plan* plan, int which) {
+  const ConvLike& c = plan->conv;
+  double best = 1e300;
+  int best_v = -1, best_tr = 0;
+  MfmaParams mp;
+  for (int vi = 0; vi < 3; ++vi)
+    for (int TR = 1; TR <= c.N * c.Ho && TR * c.Wo <= 16 * 32; ++TR) {
+      if (!fill_params_f32(plan, vi, TR, mp)) continue;
+      const double cost = tile_cost(mp, kF32Variants[vi], c);
+      if (cost < best) { best = cost; best_v = vi; best_tr = TR; }
+    }
+  plan->launch[which].variant = best_v * 4096 + best_tr;
+  plan->launch[which].workspace = 0;
+}
+
+syno_status launch_mfma(const syno_plan* plan, int which, const void* A, const void* B, void* out, void*,
+                        hipStream_t stream) {
+  const int vi = plan->launch[which].variant / 4096, TR = plan->launch[which].variant % 4096;
+  MfmaParams p;
+  if (vi < 0 || vi > 2 || !fill_params_f32(plan, vi, TR, p)) return SYNO_ERR_UNSUPPORTED;
+  const float* X = static_cast<const float*>(A);
+  const float* W = static_cast<const float*>(B);
+  const bool obf = plan->out_dtype == SYNO_BF16;
+  switch (vi * 2 + (obf ? 1 : 0)) {
+    case 0: launch_f32<0, false>(p, X, W, out, stream); break;
+    case 1: launch_f32<0, true>(p, X, W, out, stream); break;
+    case 2: launch_f32<1, false>(p, X, W, out, stream); break;
+    case 3: launch_f32<1, true>(p, X, W, out, stream); break;
+    case 4: launch_f32<2, false>(p, X, W, out, stream); break;
+    case 5: launch_f32<2, true>(p, X, W, out, stream); break;
+  }
+  return hipGetLastError() == hipSuccess ? SYNO_OK : SYNO_ERR_HIP;
+}
+
 }  // namespace syno

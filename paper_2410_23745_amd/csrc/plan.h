@@ -105,4 +105,10 @@ syno_status launch_debug_gather(const syno_plan* p, int which, const int64_t* t,
 syno_status host_debug_gather(const syno_plan* p, int which, const int64_t* t, const int64_t* q, int64_t n,
                               int32_t* a_off, int32_t* b_off);
 
+// kernels_bandwidth.hip / kernels_mfma.hip: can the family take contraction `which` of this plan?
+bool bandwidth_supports(const syno_plan* p, int which);
+bool mfma_supports(const syno_plan* p, int which);
+// fills launch[which] (tile variant, workspace bytes) for the MFMA family
+void mfma_configure(syno_plan* p, int which);
+
 }  // namespace syno

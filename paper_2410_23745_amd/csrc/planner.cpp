@@ -660,8 +660,17 @@ syno_status build_plan(const syno_desc* desc, int policy, syno_plan* plan, std::
     // Few targets with a long sum each: one workgroup per target, lanes share the sum.
     L.coop = (P.n_free >= 512 && P.n_target < (1 << 18)) ? 1 : 0;
     L.workspace = 0;
+    if (policy == 1) continue;
+    // Kernel choice.  A per-channel window (one input and one output channel per group) has about one
+    // flop per byte: stream it.  A Reduce shared with a weight that also carries its own output
+    // iterator is a real contraction: MFMA.  Everything else stays on the index-program kernels.
+    if (bandwidth_supports(plan, which)) {
+      L.kernel = KERNEL_BW_DEPTHWISE;
+    } else if (mfma_supports(plan, which)) {
+      L.kernel = plan->in_dtype == SYNO_BF16 ? KERNEL_MFMA_BF16 : KERNEL_MFMA_F32;
+      mfma_configure(plan, which);
+    }
   }
-  (void)policy;
   return SYNO_OK;
 }
 

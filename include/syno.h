@@ -120,6 +120,10 @@ syno_status syno_plan_shapes(const syno_plan* plan, int32_t* x_rank, int64_t* x_
 /* Name of the kernel family call `which` dispatches to (static string, never NULL for a valid plan). */
 const char* syno_plan_kernel(const syno_plan* plan, int which);
 
+/* Human-readable summary of how call `which` will be launched (kernel family, tile shape, grid, LDS),
+ * written NUL-terminated into buf[0..size).  For logs and tests; the format is not an interface. */
+syno_status syno_plan_describe(const syno_plan* plan, int which, char* buf, size_t size);
+
 /* Restrict kernel choice at plan creation: 0 = planner decides (default), 1 = always the generic
  * index-program kernels.  Process-wide; affects plans created afterwards.  For verification. */
 syno_status syno_set_kernel_policy(int policy);

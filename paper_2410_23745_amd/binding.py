@@ -14,7 +14,7 @@ _LIB_PATH = os.path.join(_HERE, "libsyno.so")
 _lib = None
 
 EXPORTS = ("syno_plan_create", "syno_plan_destroy", "syno_forward", "syno_backward_data", "syno_backward_weight",
-           "syno_plan_workspace_bytes", "syno_plan_shapes", "syno_plan_kernel", "syno_set_kernel_policy",
+           "syno_plan_workspace_bytes", "syno_plan_shapes", "syno_plan_kernel", "syno_plan_describe", "syno_set_kernel_policy",
            "syno_plan_free_size", "syno_debug_gather", "syno_debug_gather_host", "syno_status_string")
 
 
@@ -63,6 +63,7 @@ def load_library():
     lib.syno_plan_shapes.argtypes = [vp, i32p, i64p, i32p, i64p, i32p, i64p]
     lib.syno_plan_kernel.argtypes = [vp, ctypes.c_int]
     lib.syno_plan_kernel.restype = ctypes.c_char_p
+    lib.syno_plan_describe.argtypes = [vp, ctypes.c_int, ctypes.c_char_p, ctypes.c_size_t]
     lib.syno_set_kernel_policy.argtypes = [ctypes.c_int]
     lib.syno_plan_free_size.argtypes = [vp, ctypes.c_int, i64p]
     lib.syno_debug_gather.argtypes = [vp, ctypes.c_int, vp, vp, ctypes.c_int64, vp, vp, vp]
@@ -141,6 +142,13 @@ class Plan:
     def kernel(self, which: int) -> str:
         s = load_library().syno_plan_kernel(self._h, which)
         return s.decode() if s else ""
+
+    def describe(self, which: int) -> str:
+        buf = ctypes.create_string_buffer(512)
+        st = load_library().syno_plan_describe(self._h, which, buf, 512)
+        if st:
+            raise SynoError(st, "syno_plan_describe")
+        return buf.value.decode()
 
     def free_size(self, which: int) -> int:
         n = ctypes.c_int64()

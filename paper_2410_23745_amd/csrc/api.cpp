@@ -1,5 +1,6 @@
 // The C ABI of include/syno.h: argument checks and dispatch to the kernel families.
 #include <atomic>
+#include <cstdio>
 #include <new>
 #include <string>
 
@@ -10,6 +11,7 @@ syno_status launch_bandwidth(const syno_plan* p, int which, const void* A, const
                              hipStream_t stream);
 syno_status launch_mfma(const syno_plan* p, int which, const void* A, const void* B, void* out, void* ws,
                         hipStream_t stream);
+std::string mfma_describe(const syno_plan* p, int which);
 }
 
 namespace {
@@ -93,6 +95,20 @@ syno_status syno_plan_shapes(const syno_plan* plan, int32_t* x_rank, int64_t* x_
 const char* syno_plan_kernel(const syno_plan* plan, int which) {
   if (!plan || which < 0 || which > 2) return nullptr;
   return kKernelNames[plan->launch[which].kernel];
+}
+
+syno_status syno_plan_describe(const syno_plan* plan, int which, char* buf, size_t size) {
+  if (!plan || !buf) return SYNO_ERR_NULL;
+  if (which < 0 || which > 2 || size == 0) return SYNO_ERR_SHAPE;
+  std::string d = kKernelNames[plan->launch[which].kernel];
+  switch (plan->launch[which].kernel) {
+    case syno::KERNEL_GENERIC: d += plan->launch[which].coop ? " workgroup-per-target" : " lane-per-target"; break;
+    case syno::KERNEL_MFMA_F32:
+    case syno::KERNEL_MFMA_BF16: d += " " + syno::mfma_describe(plan, which); break;
+    default: break;
+  }
+  snprintf(buf, size, "%s", d.c_str());
+  return SYNO_OK;
 }
 
 syno_status syno_set_kernel_policy(int policy) {

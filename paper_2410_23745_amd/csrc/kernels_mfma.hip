@@ -16,6 +16,10 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <string>
+#include <type_traits>
 
 #include "plan.h"
 
@@ -91,7 +95,8 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_mfma_f32(const MfmaParams p,
   float* wl = reinterpret_cast<float*>(smem + p.lds_w_off);
   int* slot_src = reinterpret_cast<int*>(smem + p.lds_tab_off);
 
-  const int tid = threadIdx.x, lane = tid & 63, widx = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int widx = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in an SGPR
   const int wn = widx / WM;
   const int wm = (widx + wn) % WM;          // spread the fuller wave rows over the SIMDs
   int bid = blockIdx.x;
@@ -140,21 +145,23 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_mfma_f32(const MfmaParams p,
       w_meta[k] = (idx < total ? o * p.w_row + e : 0) | (cl << 20) | (idx < total ? 0 : (1 << 30));
     }
   }
-  // ---- per-lane operand bases (dword indices)
+  // ---- per-lane operand bases (dword indices); the block's MT row tiles are dealt out evenly
   const int block_px = rows * p.Wo;
+  const int MT = (block_px + 15) >> 4;
+  const int tiles_base = MT / WM, tiles_extra = MT - tiles_base * WM;
+  const int my_tiles = tiles_base + (wm < tiles_extra ? 1 : 0);
+  const int my_first = wm * tiles_base + min(wm, tiles_extra);
   int a_base[TM];
 #pragma unroll
   for (int t = 0; t < TM; ++t) {
-    int m = (wm * TM + t) * 16 + (lane & 15);
-    if (m >= block_px) m = 0;
+    int m = (my_first + t) * 16 + (lane & 15);
+    if (t >= my_tiles || m >= block_px) m = 0;
     const int i = m / p.Wo, w = m - i * p.Wo;
     a_base[t] = (slot_of_row(p, R0, i) * p.Wp + w) * 4 + (lane >> 4);
   }
   int b_base[TN];
 #pragma unroll
   for (int u = 0; u < TN; ++u) b_base[u] = ((wn * TN + u) * 16 + (lane & 15)) * p.w_row + (lane >> 4) * KHW;
-  const int MT = (block_px + 15) >> 4;
-  const int my_tiles = max(0, min(TM, MT - wm * TM));
 
   floatx4 acc[TM][TN];
 #pragma unroll
@@ -188,24 +195,53 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_mfma_f32(const MfmaParams p,
       if (!(w_meta[k] >> 30)) wl[w_meta[k] & 0xfffff] = wr[k];
     __syncthreads();
     if (ch + 1 < p.n_chunks) fetch((ch + 1) * p.KC);
-    for (int cg = 0; cg < p.cgrps; ++cg) {
-      const int a_cg = cg * p.n_slots * p.Wp * 4;
-      const int b_cg = cg * CI * KHW;
-      for (int kh = 0; kh < p.KH; ++kh)
-        for (int kw = 0; kw < p.KW; ++kw) {
-          const int a_off = a_cg + (kh * p.Wp + kw) * 4;
-          const int b_off = b_cg + kh * p.KW + kw;
-          float b[TN];
+    // One k-step = CI channels at one tap.  Fragments of step i+1 are read from LDS while the
+    // MFMAs of step i issue.  The tile count is a compile-time constant per case so that the
+    // MFMA block is straight-line code.
+    auto compute = [&](auto ntl_c) {
+      constexpr int NTL = decltype(ntl_c)::value;
+      const int steps = p.cgrps * KHW;
+      int cg = 0, kh = 0, kw = 0;
+      float a0[NTL], b0[TN], a1[NTL], b1[TN];
+      auto read = [&](float (&a)[NTL], float (&b)[TN]) {
+        const int a_off = cg * p.n_slots * p.Wp * 4 + (kh * p.Wp + kw) * 4;
+        const int b_off = cg * CI * KHW + kh * p.KW + kw;
 #pragma unroll
-          for (int u = 0; u < TN; ++u) b[u] = wl[b_base[u] + b_off];
+        for (int u = 0; u < TN; ++u) b[u] = wl[b_base[u] + b_off];
 #pragma unroll
-          for (int t = 0; t < TM; ++t)
-            if (t < my_tiles) {
-              const float a = xlf[a_base[t] + a_off];
+        for (int t = 0; t < NTL; ++t) a[t] = xlf[a_base[t] + a_off];
+      };
+      auto advance = [&]() {
+        if (++kw == p.KW) { kw = 0; if (++kh == p.KH) { kh = 0; ++cg; } }
+      };
+      auto mfmas = [&](const float (&a)[NTL], const float (&b)[TN]) {
 #pragma unroll
-              for (int u = 0; u < TN; ++u) acc[t][u] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b[u], acc[t][u], 0, 0, 0);
-            }
-        }
+        for (int t = 0; t < NTL; ++t)
+#pragma unroll
+          for (int u = 0; u < TN; ++u)
+            acc[t][u] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[t], b[u], acc[t][u], 0, 0, 0);
+      };
+      read(a0, b0);
+      for (int it = 0;;) {
+        if (it + 1 < steps) { advance(); read(a1, b1); }
+        mfmas(a0, b0);
+        if (++it >= steps) break;
+        if (it + 1 < steps) { advance(); read(a0, b0); }
+        mfmas(a1, b1);
+        if (++it >= steps) break;
+      }
+    };
+    static_assert(TM <= 8, "extend the dispatch below");
+    switch (my_tiles) {
+      case 1: compute(std::integral_constant<int, 1>{}); break;
+      case 2: if constexpr (TM >= 2) compute(std::integral_constant<int, 2>{}); break;
+      case 3: if constexpr (TM >= 3) compute(std::integral_constant<int, 3>{}); break;
+      case 4: if constexpr (TM >= 4) compute(std::integral_constant<int, 4>{}); break;
+      case 5: if constexpr (TM >= 5) compute(std::integral_constant<int, 5>{}); break;
+      case 6: if constexpr (TM >= 6) compute(std::integral_constant<int, 6>{}); break;
+      case 7: if constexpr (TM >= 7) compute(std::integral_constant<int, 7>{}); break;
+      case 8: if constexpr (TM >= 8) compute(std::integral_constant<int, 8>{}); break;
+      default: break;
     }
   }
 
@@ -214,7 +250,7 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_mfma_f32(const MfmaParams p,
 #pragma unroll
   for (int t = 0; t < TM; ++t) {
     if (t >= my_tiles) continue;
-    const int m0 = (wm * TM + t) * 16 + 4 * (lane >> 4);
+    const int m0 = (my_first + t) * 16 + 4 * (lane >> 4);
 #pragma unroll
     for (int u = 0; u < TN; ++u) {
       const int o = nb * BN + (wn * TN + u) * 16 + (lane & 15);
@@ -269,7 +305,12 @@ struct Variant {
 constexpr Variant kF32Variants[] = {{4, 2, 7, 2, 3, 9}, {4, 2, 7, 1, 3, 5}, {8, 1, 4, 1, 3, 3}};
 constexpr int kNumCU = 256;
 
-int images_spanned(int TR, int Ho) { return (TR + Ho - 2) / Ho + 1; }
+// most images a run of TR consecutive output rows can touch (blocks start at multiples of TR)
+int images_spanned(int TR, int Ho) {
+  if (Ho % TR == 0) return 1;
+  if (TR % Ho == 0) return TR / Ho;
+  return (TR + Ho - 2) / Ho + 1;
+}
 
 // LDS weight row pitch (in elements) >= need such that the 64 lanes of a B-fragment read
 // (16 rows x 4 channel steps of `kstep` elements) fall into distinct banks where possible.
@@ -318,14 +359,29 @@ bool fill_params_f32(const syno_plan* plan, int vi, int TR, MfmaParams& p) {
   return p.lds_bytes <= 64 * 1024 && p.w_row * v.BN() < (1 << 20);
 }
 
-// Estimated duration in units of "one 16x16 MFMA tile over the whole reduction per SIMD".
+// Estimated duration of the launch in SIMD cycles.  Row tiles are dealt evenly to the WM wave rows, wave
+// widx runs on SIMD widx%4, a 16x16x4 fp32 MFMA occupies its SIMD's matrix pipe for 32 cycles, and one
+// k-step of a wave cannot finish faster than its LDS reads allow.  Staging, barriers and the prologue
+// overlap with another resident workgroup's MFMAs only when more than one fits on a CU.
 double tile_cost(const MfmaParams& p, const Variant& v, const ConvLike& c) {
   const int64_t wgs = (int64_t)p.n_mblocks * p.n_nblocks * c.G;
-  const int MT = (p.TR * c.Wo + 15) / 16;
-  const double per_wg = std::ceil(MT * (double)(v.BN() / 16) / 4.0);      // tiles per SIMD
-  const double rounds = std::ceil((double)wgs / kNumCU);
-  // staging and barriers cost a little per chunk; prefer fuller tiles at equal MFMA time
-  return rounds * (per_wg + 0.35) ;
+  const int MT = (std::min(p.TR, p.rows_total) * c.Wo + 15) / 16;
+  const int base = MT / v.WM, extra = MT % v.WM;
+  double simd_mfma[4] = {0, 0, 0, 0}, simd_lds[4] = {0, 0, 0, 0};
+  for (int widx = 0; widx < v.WM * v.WN; ++widx) {
+    const int wn = widx / v.WM, wm = (widx + wn) % v.WM;
+    const int tiles = base + (wm < extra ? 1 : 0);
+    if (!tiles) continue;
+    simd_mfma[widx & 3] += 32.0 * tiles * v.TN;
+    simd_lds[widx & 3] += 8.0 * (tiles + v.TN) + 40.0;
+  }
+  double step = 0;
+  for (int s = 0; s < 4; ++s) step = std::max(step, std::max(simd_mfma[s], simd_lds[s] + 60.0));
+  const double steps = (double)p.n_chunks * p.cgrps * c.KH * c.KW;
+  const double overhead = p.n_chunks * 1500.0 + 6000.0;
+  const int resident = std::max(1, std::min(2048 / v.NT(), (160 * 1024) / std::max(1, p.lds_bytes)));
+  const double per_cu_wgs = std::ceil((double)wgs / kNumCU);
+  return per_cu_wgs * steps * step + std::ceil(per_cu_wgs / resident) * overhead;
 }
 
 template <int VI, bool OUTBF>
@@ -360,6 +416,15 @@ void mfma_configure(syno_plan* plan, int which) {
   double best = 1e300;
   int best_v = -1, best_tr = 0;
   MfmaParams mp;
+  // SYNO_MFMA_TILE="variant,rows" overrides the tile choice (tuning aid)
+  if (const char* f = getenv("SYNO_MFMA_TILE")) {
+    int vi = -1, tr = 0;
+    if (sscanf(f, "%d,%d", &vi, &tr) == 2 && vi >= 0 && vi < 3 && fill_params_f32(plan, vi, tr, mp)) {
+      plan->launch[which].variant = vi * 4096 + tr;
+      plan->launch[which].workspace = 0;
+      return;
+    }
+  }
   for (int vi = 0; vi < 3; ++vi)
     for (int TR = 1; TR <= c.N * c.Ho && TR * c.Wo <= 16 * 32; ++TR) {
       if (!fill_params_f32(plan, vi, TR, mp)) continue;
@@ -368,6 +433,17 @@ void mfma_configure(syno_plan* plan, int which) {
     }
   plan->launch[which].variant = best_v * 4096 + best_tr;
   plan->launch[which].workspace = 0;
+}
+
+std::string mfma_describe(const syno_plan* plan, int which) {
+  const int vi = plan->launch[which].variant / 4096, TR = plan->launch[which].variant % 4096;
+  MfmaParams p;
+  if (vi < 0 || vi > 2 || !fill_params_f32(plan, vi, TR, p)) return "unconfigured";
+  const Variant& v = kF32Variants[vi];
+  char b[256];
+  snprintf(b, sizeof b, "rows/block=%d BN=%d KC=%d waves=%dx%d grid=%d lds=%dB slots=%d", TR, v.BN(), p.KC, v.WM, v.WN,
+           p.n_mblocks * p.n_nblocks * p.G, p.lds_bytes, p.n_slots);
+  return b;
 }
 
 syno_status launch_mfma(const syno_plan* plan, int which, const void* A, const void* B, void* out, void*,

@@ -8,10 +8,17 @@
 // chunk of KC input channels it stages
 //   - the input rows those output rows touch, each row into a "slot" of Wp = Wi+KW-1 pixels whose
 //     edge pixels stay zero (the padding), rows outside the image left zero; pixels are stored
-//     channel-innermost, CI channels = 16 bytes per pixel, so that an MFMA operand fragment is one
-//     LDS read per lane and a window tap is a constant address offset (kh*Wp + kw pixels);
-//   - the BN x KC x KH x KW weight block;
-// then issues 16x16 MFMAs whose K-step is CI consecutive channels at one tap.
+//     channel-innermost, CI channels = 16 bytes per pixel (4 fp32 or 8 bf16), so that an MFMA
+//     operand fragment is one LDS read per lane and a window tap is a constant address offset
+//     (kh*Wp + kw pixels);
+//   - the BN x KC x KH x KW weight block (fp32: as it lies in memory; bf16: from a copy a small
+//     kernel has re-ordered into [tap][o][c], because the bf16 MFMA wants 8 consecutive channels
+//     per lane);
+// then issues 16x16 MFMAs whose K-step is 4 (fp32) or 32 (bf16) consecutive channels at one tap.
+//
+// The backward-data contraction is the same computation with the roles of the two channel axes
+// exchanged, the taps reversed and the row shift negated, so it runs through the same kernel on
+// an adjoint parameter record.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -34,15 +41,17 @@ struct MfmaParams {
   int32_t os_n, os_o;                 // result strides: image, channel
   int32_t ws_g, ws_o, ws_c, ws_kh, ws_kw, w_base;
   // tiling
-  int32_t TR, KC, n_mblocks, n_nblocks, n_chunks;
+  int32_t TR, BN, KC, n_mblocks, n_nblocks, n_chunks;
   int32_t n_slots, Wp, cgrps;
   int32_t w_row;                      // LDS weight row pitch (elements)
   int32_t lds_w_off, lds_tab_off, lds_bytes;
+  int32_t w_block;                    // bf16: elements of one packed weight block (KH*KW*BN*w_row)
 };
 
 namespace {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   uint32_t u = __float_as_uint(f);
@@ -82,17 +91,43 @@ __device__ __forceinline__ int slot_of_row(const MfmaParams& p, int R0, int i) {
   return i + (p.KH - 1) * ((R0 + i) / p.Ho - R0 / p.Ho);
 }
 
-// fp32: CI = 4 channels per pixel slot, v_mfma_f32_16x16x4_f32 (A: lane -> row l%16, k l/16).
-template <int WM, int WN, int TM, int TN, int XI, int WI, bool OUTBF>
-__global__ __launch_bounds__(WM* WN * 64) void conv_mfma_f32(const MfmaParams p, const float* __restrict__ X,
-                                                             const float* __restrict__ Wt, void* __restrict__ out) {
+// bf16 only: W[g][o][c][kh][kw] (any strides) -> blocks [g][nb][chunk] of [tap][o_local][w_row] with the
+// channel innermost; rows beyond Og / Cg and the row padding are zero.
+__global__ __launch_bounds__(256) void pack_weight_bf16(const MfmaParams p, const uint16_t* __restrict__ Wt,
+                                                        uint16_t* __restrict__ packed, int64_t total) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int KHW = p.KH * p.KW;
+  int64_t r = i;
+  const int cl = (int)(r % p.w_row); r /= p.w_row;
+  const int ol = (int)(r % p.BN); r /= p.BN;
+  const int tap = (int)(r % KHW); r /= KHW;
+  const int ch = (int)(r % p.n_chunks); r /= p.n_chunks;
+  const int nb = (int)(r % p.n_nblocks);
+  const int g = (int)(r / p.n_nblocks);
+  const int o = nb * p.BN + ol, c = ch * p.KC + cl;
+  const int kh = tap / p.KW, kw = tap - kh * p.KW;
+  uint16_t v = 0;
+  if (cl < p.KC && o < p.Og && c < p.Cg)
+    v = Wt[p.w_base + (int64_t)g * p.ws_g + (int64_t)o * p.ws_o + (int64_t)c * p.ws_c + kh * p.ws_kh + kw * p.ws_kw];
+  packed[i] = v;
+}
+
+// BF = false: fp32 inputs, CI = 4, v_mfma_f32_16x16x4_f32  (A: lane -> row l%16, k = l/16).
+// BF = true : bf16 inputs, CI = 8, v_mfma_f32_16x16x32_bf16 (A: lane -> row l%16, k = 8*(l/16)..+7);
+//             `Wv` is the packed copy.
+template <bool BF, int WM, int WN, int TM, int TN, int XI, int WI, bool OUTBF>
+__global__ __launch_bounds__(WM* WN * 64) void conv_mfma(const MfmaParams p, const void* __restrict__ Xv,
+                                                         const void* __restrict__ Wv, void* __restrict__ out) {
   constexpr int NT = WM * WN * 64;
   constexpr int BN = WN * TN * 16;
-  constexpr int CI = 4;
+  constexpr int CI = BF ? 8 : 4;
+  constexpr int CG_STEP = BF ? 4 : 1;        // channel groups one MFMA consumes
+  using XT = std::conditional_t<BF, uint16_t, float>;
+  using Frag = std::conditional_t<BF, bf16x8, float>;
+  using WReg = std::conditional_t<BF, uint4, float>;
   extern __shared__ __align__(16) unsigned char smem[];
   float4* xl = reinterpret_cast<float4*>(smem);
-  const float* xlf = reinterpret_cast<const float*>(smem);
-  float* wl = reinterpret_cast<float*>(smem + p.lds_w_off);
   int* slot_src = reinterpret_cast<int*>(smem + p.lds_tab_off);
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -115,8 +150,7 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_mfma_f32(const MfmaParams p,
   __syncthreads();
 
   // ---- loop-invariant descriptors of what this thread stages per chunk
-  const float* Xg = X + (int64_t)g * p.Cg * p.xs_c;
-  const float* Wg = Wt + p.w_base + (int64_t)g * p.ws_g + (int64_t)nb * BN * p.ws_o;
+  const XT* Xg = reinterpret_cast<const XT*>(Xv) + (int64_t)g * p.Cg * p.xs_c;
   int x_goff[XI], x_loff[XI], x_cg[XI];
   {
     const int per_cg = p.n_slots * p.Wi, total = p.cgrps * per_cg;
@@ -131,8 +165,23 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_mfma_f32(const MfmaParams p,
       x_cg[k] = cg * CI;
     }
   }
-  int w_goff[WI], w_meta[WI];   // meta: LDS dword offset | local channel << 20
-  {
+  // fp32: one weight element per item, gathered with the operator's strides into [o][c*KHW+tap].
+  // bf16: 16-byte pieces of this block's packed image, copied as they are.
+  const float* Wg32 = nullptr;
+  const uint4* Wg16 = nullptr;
+  int w_goff[WI], w_meta[WI];   // fp32 meta: LDS dword offset | local channel << 20 | zero-fill << 29 | unused << 30
+  if constexpr (BF) {
+    Wg16 = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(Wv) +
+                                          ((int64_t)(g * p.n_nblocks + nb) * p.n_chunks) * p.w_block);
+    const int units = p.w_block >> 3;
+#pragma unroll
+    for (int k = 0; k < WI; ++k) {
+      const int idx = tid + k * NT;
+      w_goff[k] = idx < units ? idx : -1;
+      w_meta[k] = 0;
+    }
+  } else {
+    Wg32 = reinterpret_cast<const float*>(Wv) + p.w_base + (int64_t)g * p.ws_g + (int64_t)nb * BN * p.ws_o;
     const int per_o = p.KC * KHW, total = BN * per_o;
 #pragma unroll
     for (int k = 0; k < WI; ++k) {
@@ -141,27 +190,33 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_mfma_f32(const MfmaParams p,
       const int cl = e / KHW, tap = e - cl * KHW;
       const int kh = tap / p.KW, kw = tap - kh * p.KW;
       const bool ok = idx < total && nb * BN + o < p.Og;
-      w_goff[k] = ok ? o * p.ws_o + cl * p.ws_c + kh * p.ws_kh + kw * p.ws_kw : -1;
-      w_meta[k] = (idx < total ? o * p.w_row + e : 0) | (cl << 20) | (idx < total ? 0 : (1 << 30));
+      // tap strides may be negative (reversed taps of the adjoint), so validity lives in the meta word
+      w_goff[k] = ok ? o * p.ws_o + cl * p.ws_c + kh * p.ws_kh + kw * p.ws_kw : 0;
+      w_meta[k] = (idx < total ? o * p.w_row + e : 0) | (cl << 20) | (ok ? 0 : (1 << 29)) | (idx < total ? 0 : (1 << 30));
     }
   }
-  // ---- per-lane operand bases (dword indices); the block's MT row tiles are dealt out evenly
+  // ---- per-lane operand bases; the block's MT row tiles are dealt out evenly to the wave rows
   const int block_px = rows * p.Wo;
   const int MT = (block_px + 15) >> 4;
   const int tiles_base = MT / WM, tiles_extra = MT - tiles_base * WM;
   const int my_tiles = tiles_base + (wm < tiles_extra ? 1 : 0);
   const int my_first = wm * tiles_base + min(wm, tiles_extra);
-  int a_base[TM];
+  const int cg_stride = p.n_slots * p.Wp;          // 16-byte units between channel groups
+  int a_base[TM];                                   // fp32: dword index; bf16: 16-byte unit index
 #pragma unroll
   for (int t = 0; t < TM; ++t) {
     int m = (my_first + t) * 16 + (lane & 15);
     if (t >= my_tiles || m >= block_px) m = 0;
     const int i = m / p.Wo, w = m - i * p.Wo;
-    a_base[t] = (slot_of_row(p, R0, i) * p.Wp + w) * 4 + (lane >> 4);
+    const int px = slot_of_row(p, R0, i) * p.Wp + w;
+    a_base[t] = BF ? px + (lane >> 4) * cg_stride : px * 4 + (lane >> 4);
   }
-  int b_base[TN];
+  int b_base[TN];                                   // fp32: dword index; bf16: element index
 #pragma unroll
-  for (int u = 0; u < TN; ++u) b_base[u] = ((wn * TN + u) * 16 + (lane & 15)) * p.w_row + (lane >> 4) * KHW;
+  for (int u = 0; u < TN; ++u) {
+    const int ol = (wn * TN + u) * 16 + (lane & 15);
+    b_base[u] = BF ? ol * p.w_row + (lane >> 4) * 8 : ol * p.w_row + (lane >> 4) * KHW;
+  }
 
   floatx4 acc[TM][TN];
 #pragma unroll
@@ -169,57 +224,104 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_mfma_f32(const MfmaParams p,
 #pragma unroll
     for (int u = 0; u < TN; ++u) acc[t][u] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-  float xr[XI][CI], wr[WI];
-  auto fetch = [&](int c0) {
+  XT xr[XI][CI];
+  WReg wr[WI];
+  auto fetch = [&](int ch) {
+    const int c0 = ch * p.KC;
 #pragma unroll
     for (int k = 0; k < XI; ++k)
 #pragma unroll
       for (int j = 0; j < CI; ++j) {
         const int c = c0 + x_cg[k] + j;
-        xr[k][j] = (x_goff[k] >= 0 && c < p.Cg) ? Xg[x_goff[k] + (int64_t)(c0 + j) * p.xs_c] : 0.f;
+        xr[k][j] = (x_goff[k] >= 0 && c < p.Cg) ? Xg[x_goff[k] + (int64_t)(c0 + j) * p.xs_c] : XT(0);
       }
+    if constexpr (BF) {
+      const uint4* src = Wg16 + (int64_t)ch * (p.w_block >> 3);
 #pragma unroll
-    for (int k = 0; k < WI; ++k) {
-      const int cl = (w_meta[k] >> 20) & 1023;
-      wr[k] = (w_goff[k] >= 0 && c0 + cl < p.Cg) ? Wg[w_goff[k] + (int64_t)c0 * p.ws_c] : 0.f;
+      for (int k = 0; k < WI; ++k) wr[k] = w_goff[k] >= 0 ? src[w_goff[k]] : make_uint4(0, 0, 0, 0);
+    } else {
+#pragma unroll
+      for (int k = 0; k < WI; ++k) {
+        const int cl = (w_meta[k] >> 20) & 511;
+        wr[k] = (!(w_meta[k] >> 29) && c0 + cl < p.Cg) ? Wg32[w_goff[k] + (int64_t)c0 * p.ws_c] : 0.f;
+      }
     }
   };
+  auto stage = [&]() {
+#pragma unroll
+    for (int k = 0; k < XI; ++k)
+      if (x_goff[k] >= 0) {
+        if constexpr (BF) {
+          uint4 v;
+          v.x = xr[k][0] | ((uint32_t)xr[k][1] << 16);
+          v.y = xr[k][2] | ((uint32_t)xr[k][3] << 16);
+          v.z = xr[k][4] | ((uint32_t)xr[k][5] << 16);
+          v.w = xr[k][6] | ((uint32_t)xr[k][7] << 16);
+          reinterpret_cast<uint4*>(xl)[x_loff[k]] = v;
+        } else {
+          xl[x_loff[k]] = make_float4(xr[k][0], xr[k][1], xr[k][2], xr[k][3]);
+        }
+      }
+    if constexpr (BF) {
+      uint4* wl = reinterpret_cast<uint4*>(smem + p.lds_w_off);
+#pragma unroll
+      for (int k = 0; k < WI; ++k)
+        if (w_goff[k] >= 0) wl[w_goff[k]] = wr[k];
+    } else {
+      float* wl = reinterpret_cast<float*>(smem + p.lds_w_off);
+#pragma unroll
+      for (int k = 0; k < WI; ++k)
+        if (!(w_meta[k] >> 30)) wl[w_meta[k] & 0xfffff] = wr[k];
+    }
+  };
+
   fetch(0);
   for (int ch = 0; ch < p.n_chunks; ++ch) {
     __syncthreads();   // everyone has finished reading the previous chunk
-#pragma unroll
-    for (int k = 0; k < XI; ++k)
-      if (x_goff[k] >= 0) xl[x_loff[k]] = make_float4(xr[k][0], xr[k][1], xr[k][2], xr[k][3]);
-#pragma unroll
-    for (int k = 0; k < WI; ++k)
-      if (!(w_meta[k] >> 30)) wl[w_meta[k] & 0xfffff] = wr[k];
+    stage();
     __syncthreads();
-    if (ch + 1 < p.n_chunks) fetch((ch + 1) * p.KC);
-    // One k-step = CI channels at one tap.  Fragments of step i+1 are read from LDS while the
-    // MFMAs of step i issue.  The tile count is a compile-time constant per case so that the
-    // MFMA block is straight-line code.
+    if (ch + 1 < p.n_chunks) fetch(ch + 1);
+    // One k-step = CI*CG_STEP channels at one tap.  Fragments of step i+1 are read from LDS while the
+    // MFMAs of step i issue.  The tile count is a compile-time constant per case so that the MFMA
+    // block is straight-line code.
     auto compute = [&](auto ntl_c) {
       constexpr int NTL = decltype(ntl_c)::value;
-      const int steps = p.cgrps * KHW;
+      const int steps = (p.cgrps / CG_STEP) * KHW;
       int cg = 0, kh = 0, kw = 0;
-      float a0[NTL], b0[TN], a1[NTL], b1[TN];
-      auto read = [&](float (&a)[NTL], float (&b)[TN]) {
-        const int a_off = cg * p.n_slots * p.Wp * 4 + (kh * p.Wp + kw) * 4;
-        const int b_off = cg * CI * KHW + kh * p.KW + kw;
+      Frag a0[NTL], b0[TN], a1[NTL], b1[TN];
+      auto read = [&](Frag (&a)[NTL], Frag (&b)[TN]) {
+        if constexpr (BF) {
+          const uint4* xq = reinterpret_cast<const uint4*>(smem);
+          const uint16_t* wq = reinterpret_cast<const uint16_t*>(smem + p.lds_w_off);
+          const int a_off = cg * CG_STEP * cg_stride + kh * p.Wp + kw;
+          const int b_off = ((kh * p.KW + kw) * BN) * p.w_row + cg * CG_STEP * CI;
 #pragma unroll
-        for (int u = 0; u < TN; ++u) b[u] = wl[b_base[u] + b_off];
+          for (int u = 0; u < TN; ++u)
+            b[u] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(wq + b_base[u] + b_off));
 #pragma unroll
-        for (int t = 0; t < NTL; ++t) a[t] = xlf[a_base[t] + a_off];
+          for (int t = 0; t < NTL; ++t) a[t] = __builtin_bit_cast(bf16x8, xq[a_base[t] + a_off]);
+        } else {
+          const float* xq = reinterpret_cast<const float*>(smem);
+          const float* wq = reinterpret_cast<const float*>(smem + p.lds_w_off);
+          const int a_off = (cg * cg_stride + kh * p.Wp + kw) * 4;
+          const int b_off = cg * CI * KHW + kh * p.KW + kw;
+#pragma unroll
+          for (int u = 0; u < TN; ++u) b[u] = wq[b_base[u] + b_off];
+#pragma unroll
+          for (int t = 0; t < NTL; ++t) a[t] = xq[a_base[t] + a_off];
+        }
       };
       auto advance = [&]() {
         if (++kw == p.KW) { kw = 0; if (++kh == p.KH) { kh = 0; ++cg; } }
       };
-      auto mfmas = [&](const float (&a)[NTL], const float (&b)[TN]) {
+      auto mfmas = [&](const Frag (&a)[NTL], const Frag (&b)[TN]) {
 #pragma unroll
         for (int t = 0; t < NTL; ++t)
 #pragma unroll
-          for (int u = 0; u < TN; ++u)
-            acc[t][u] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[t], b[u], acc[t][u], 0, 0, 0);
+          for (int u = 0; u < TN; ++u) {
+            if constexpr (BF) acc[t][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t], b[u], acc[t][u], 0, 0, 0);
+            else acc[t][u] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[t], b[u], acc[t][u], 0, 0, 0);
+          }
       };
       read(a0, b0);
       for (int it = 0;;) {
@@ -301,9 +403,14 @@ struct Variant {
   constexpr int BN() const { return WN * TN * 16; }
   constexpr int MT() const { return WM * TM; }
 };
-// fp32 tile variants: BN = 64, 32, 16 output channels per workgroup; 8 waves
-constexpr Variant kF32Variants[] = {{4, 2, 7, 2, 3, 9}, {4, 2, 7, 1, 3, 5}, {8, 1, 4, 1, 3, 3}};
+// tile variants: BN = 64, 32, 16 output channels per workgroup; 8 waves
+constexpr int kNumVariants = 3;
+constexpr Variant kF32Variants[kNumVariants] = {{4, 2, 7, 2, 3, 9}, {4, 2, 7, 1, 3, 5}, {8, 1, 4, 1, 3, 3}};
+constexpr Variant kBf16Variants[kNumVariants] = {{4, 2, 7, 2, 4, 6}, {4, 2, 7, 1, 4, 3}, {8, 1, 4, 1, 4, 2}};
 constexpr int kNumCU = 256;
+constexpr int kMaxLdsBytes = 144 * 1024;   // of the 160 KB a CU has
+
+const Variant& variant_of(bool bf, int vi) { return bf ? kBf16Variants[vi] : kF32Variants[vi]; }
 
 // most images a run of TR consecutive output rows can touch (blocks start at multiples of TR)
 int images_spanned(int TR, int Ho) {
@@ -312,8 +419,8 @@ int images_spanned(int TR, int Ho) {
   return (TR + Ho - 2) / Ho + 1;
 }
 
-// LDS weight row pitch (in elements) >= need such that the 64 lanes of a B-fragment read
-// (16 rows x 4 channel steps of `kstep` elements) fall into distinct banks where possible.
+// LDS weight row pitch (in dwords) >= need such that the 64 lanes of a B-fragment read (16 rows x 4
+// channel steps of `kstep` dwords) fall into distinct banks where possible.
 int pick_w_row(int need, int kstep) {
   int best = need, best_conf = 1 << 30;
   for (int r = need; r < need + 64; ++r) {
@@ -327,140 +434,185 @@ int pick_w_row(int need, int kstep) {
   return best;
 }
 
-bool fill_params_f32(const syno_plan* plan, int vi, int TR, MfmaParams& p) {
+// Parameter record of contraction `which` (forward, or backward-data as its adjoint) for tile variant vi
+// and TR output rows per block.  False when the combination does not fit the kernel's static limits.
+bool fill_params(const syno_plan* plan, int which, int vi, int TR, MfmaParams& p) {
   const ConvLike& c = plan->conv;
-  const Variant& v = kF32Variants[vi];
+  const bool bf = plan->in_dtype == SYNO_BF16;
+  if (vi < 0 || vi >= kNumVariants || TR < 1) return false;
+  const Variant& v = variant_of(bf, vi);
   p = MfmaParams{};
-  p.G = c.G; p.Og = c.Og; p.Cg = c.Cg; p.Ho = c.Ho; p.Wo = c.Wo; p.Hi = c.Hi; p.Wi = c.Wi;
-  p.KH = c.KH; p.KW = c.KW; p.ph = c.ph; p.pw = c.pw;
+  p.G = c.G; p.Ho = c.Ho; p.Wo = c.Wo; p.Hi = c.Hi; p.Wi = c.Wi;
+  p.KH = c.KH; p.KW = c.KW;
   p.rows_total = c.N * c.Ho;
-  p.h_wrap = c.h_wrap; p.h_shift = c.h_shift; p.h_shift_g = c.h_shift_g;
-  p.xs_c = c.Hi * c.Wi; p.xs_n = c.G * c.Cg * p.xs_c;
-  p.os_o = c.Ho * c.Wo; p.os_n = c.G * c.Og * p.os_o;
-  p.ws_g = c.ws_g; p.ws_o = c.ws_o; p.ws_c = c.ws_c; p.ws_kh = c.ws_kh; p.ws_kw = c.ws_kw; p.w_base = 0;
+  p.h_wrap = c.h_wrap;
+  const int plane = c.Hi * c.Wi;
+  if (which == SYNO_FWD) {
+    p.Og = c.Og; p.Cg = c.Cg; p.ph = c.ph; p.pw = c.pw;
+    p.h_shift = c.h_shift; p.h_shift_g = c.h_shift_g;
+    p.xs_c = plane; p.xs_n = c.G * c.Cg * plane;
+    p.os_o = plane; p.os_n = c.G * c.Og * plane;
+    p.ws_g = c.ws_g; p.ws_o = c.ws_o; p.ws_c = c.ws_c; p.ws_kh = c.ws_kh; p.ws_kw = c.ws_kw; p.w_base = 0;
+  } else {
+    // dX[n,g*Cg+c,y,x] = sum_{o,kh',kw'} G[n,g*Og+o, y+kh'-(KH-1-ph), x+kw'-(KW-1-pw)] * W[g,o,c,KH-1-kh',KW-1-kw']
+    p.Og = c.Cg; p.Cg = c.Og; p.ph = c.KH - 1 - c.ph; p.pw = c.KW - 1 - c.pw;
+    p.h_shift = (c.Hi - c.h_shift % c.Hi) % c.Hi; p.h_shift_g = (c.Hi - c.h_shift_g % c.Hi) % c.Hi;
+    p.xs_c = plane; p.xs_n = c.G * c.Og * plane;
+    p.os_o = plane; p.os_n = c.G * c.Cg * plane;
+    p.ws_g = c.ws_g; p.ws_o = c.ws_c; p.ws_c = c.ws_o; p.ws_kh = -c.ws_kh; p.ws_kw = -c.ws_kw;
+    p.w_base = (c.KH - 1) * c.ws_kh + (c.KW - 1) * c.ws_kw;
+  }
   p.TR = TR;
+  p.BN = v.BN();
   const int KHW = c.KH * c.KW;
-  p.KC = 8;
-  while (p.KC > 4 && (v.BN() * p.KC * KHW > v.WI * v.NT())) p.KC -= 4;
-  if (v.BN() * p.KC * KHW > v.WI * v.NT()) return false;
-  p.cgrps = p.KC / 4;
-  p.n_chunks = (c.Cg + p.KC - 1) / p.KC;
+  const int CI = bf ? 8 : 4;
+  if (bf) {
+    p.KC = 32;
+    p.w_row = p.KC + 8;                          // elements; 80-byte rows keep B-fragment reads conflict free
+    p.w_block = KHW * p.BN * p.w_row;
+    if ((p.w_block >> 3) > v.WI * v.NT()) return false;
+  } else {
+    p.KC = 8;
+    while (p.KC > 4 && (p.BN * p.KC * KHW > v.WI * v.NT())) p.KC -= 4;
+    if (p.BN * p.KC * KHW > v.WI * v.NT()) return false;
+    p.w_row = pick_w_row(p.KC * KHW, KHW);
+  }
+  p.cgrps = p.KC / CI;
+  p.n_chunks = (p.Cg + p.KC - 1) / p.KC;
   p.n_mblocks = (p.rows_total + TR - 1) / TR;
-  p.n_nblocks = (c.Og + v.BN() - 1) / v.BN();
+  p.n_nblocks = (p.Og + p.BN - 1) / p.BN;
   p.n_slots = c.h_wrap ? TR : TR + (c.KH - 1) * images_spanned(TR, c.Ho);
   p.Wp = c.Wi + c.KW - 1;
   if ((TR * c.Wo + 15) / 16 > v.MT()) return false;
   if (p.cgrps * p.n_slots * c.Wi > v.XI * v.NT()) return false;
-  p.w_row = pick_w_row(p.KC * KHW, KHW);
   const int x_bytes = p.cgrps * p.n_slots * p.Wp * 16;
   p.lds_w_off = x_bytes;
-  p.lds_tab_off = p.lds_w_off + v.BN() * p.w_row * 4;
+  const int w_bytes = bf ? p.w_block * 2 : p.BN * p.w_row * 4;
+  p.lds_tab_off = p.lds_w_off + ((w_bytes + 15) & ~15);
   p.lds_bytes = p.lds_tab_off + ((p.n_slots * 4 + 15) & ~15);
-  return p.lds_bytes <= 64 * 1024 && p.w_row * v.BN() < (1 << 20);
+  if (!bf && p.w_row * p.BN >= (1 << 20)) return false;
+  return p.lds_bytes <= kMaxLdsBytes;
 }
 
 // Estimated duration of the launch in SIMD cycles.  Row tiles are dealt evenly to the WM wave rows, wave
-// widx runs on SIMD widx%4, a 16x16x4 fp32 MFMA occupies its SIMD's matrix pipe for 32 cycles, and one
-// k-step of a wave cannot finish faster than its LDS reads allow.  Staging, barriers and the prologue
-// overlap with another resident workgroup's MFMAs only when more than one fits on a CU.
-double tile_cost(const MfmaParams& p, const Variant& v, const ConvLike& c) {
+// widx runs on SIMD widx%4, a 16x16 MFMA occupies its SIMD's matrix pipe for 32 (fp32 K=4) or 16 (bf16
+// K=32) cycles, and one k-step of a wave cannot finish faster than its LDS reads allow.  Staging, barriers
+// and the prologue overlap with another resident workgroup's MFMAs only when more than one fits on a CU.
+double tile_cost(const MfmaParams& p, const Variant& v, const ConvLike& c, bool bf) {
   const int64_t wgs = (int64_t)p.n_mblocks * p.n_nblocks * c.G;
   const int MT = (std::min(p.TR, p.rows_total) * c.Wo + 15) / 16;
   const int base = MT / v.WM, extra = MT % v.WM;
+  const double mfma_cycles = bf ? 16.0 : 32.0, read_cycles = bf ? 16.0 : 8.0;
   double simd_mfma[4] = {0, 0, 0, 0}, simd_lds[4] = {0, 0, 0, 0};
   for (int widx = 0; widx < v.WM * v.WN; ++widx) {
     const int wn = widx / v.WM, wm = (widx + wn) % v.WM;
     const int tiles = base + (wm < extra ? 1 : 0);
     if (!tiles) continue;
-    simd_mfma[widx & 3] += 32.0 * tiles * v.TN;
-    simd_lds[widx & 3] += 8.0 * (tiles + v.TN) + 40.0;
+    simd_mfma[widx & 3] += mfma_cycles * tiles * v.TN;
+    simd_lds[widx & 3] += read_cycles * (tiles + v.TN) + 40.0;
   }
   double step = 0;
   for (int s = 0; s < 4; ++s) step = std::max(step, std::max(simd_mfma[s], simd_lds[s] + 60.0));
-  const double steps = (double)p.n_chunks * p.cgrps * c.KH * c.KW;
-  const double overhead = p.n_chunks * 1500.0 + 6000.0;
+  const double steps = (double)p.n_chunks * (p.cgrps / (bf ? 4 : 1)) * c.KH * c.KW;
+  const double overhead = p.n_chunks * 3000.0 + 6000.0;
   const int resident = std::max(1, std::min(2048 / v.NT(), (160 * 1024) / std::max(1, p.lds_bytes)));
   const double per_cu_wgs = std::ceil((double)wgs / kNumCU);
   return per_cu_wgs * steps * step + std::ceil(per_cu_wgs / resident) * overhead;
 }
 
-template <int VI, bool OUTBF>
-void launch_f32(const MfmaParams& p, const float* X, const float* W, void* out, hipStream_t s) {
-  constexpr Variant v = kF32Variants[VI];
+template <bool BF, int VI, bool OUTBF>
+void launch_variant(const MfmaParams& p, const void* X, const void* W, void* out, hipStream_t s) {
+  constexpr Variant v = BF ? kBf16Variants[VI] : kF32Variants[VI];
   const int grid = p.n_mblocks * p.n_nblocks * p.G;
-  hipLaunchKernelGGL((conv_mfma_f32<v.WM, v.WN, v.TM, v.TN, v.XI, v.WI, OUTBF>), dim3(grid), dim3(v.WM * v.WN * 64),
-                     p.lds_bytes, s, p, X, W, out);
+  auto kernel = conv_mfma<BF, v.WM, v.WN, v.TM, v.TN, v.XI, v.WI, OUTBF>;
+  static const hipError_t lds_opt_in =      // once per instantiation: allow more than the default 64 KB
+      hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+  (void)lds_opt_in;
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(v.WM * v.WN * 64), p.lds_bytes, s, p, X, W, out);
+}
+
+template <bool BF, bool OUTBF>
+void launch_dtype(int vi, const MfmaParams& p, const void* X, const void* W, void* out, hipStream_t s) {
+  switch (vi) {
+    case 0: launch_variant<BF, 0, OUTBF>(p, X, W, out, s); break;
+    case 1: launch_variant<BF, 1, OUTBF>(p, X, W, out, s); break;
+    default: launch_variant<BF, 2, OUTBF>(p, X, W, out, s); break;
+  }
+}
+
+size_t packed_weight_bytes(const MfmaParams& p) {
+  return (size_t)p.G * p.n_nblocks * p.n_chunks * p.w_block * 2;
 }
 
 }  // namespace
 
 bool mfma_supports(const syno_plan* p, int which) {
-  if (!p->conv_like || which != SYNO_FWD) return false;
-  if (p->in_dtype != SYNO_F32) return false;
+  if (!p->conv_like || which == SYNO_BWD_WEIGHT) return false;
   const ConvLike& c = p->conv;
   if (c.sh != 1 || c.sw != 1 || c.w_wrap) return false;
   if (c.h_wrap && c.KH != 1) return false;
   if (c.Wi != c.Wo || c.Hi != c.Ho) return false;
+  if (c.ph >= c.KH || c.pw >= c.KW) return false;
   if (c.Og == 1 && c.Cg == 1) return false;          // no contraction to speak of
   MfmaParams mp;
-  for (int vi = 0; vi < 3; ++vi)
-    for (int TR = 1; TR <= c.N * c.Ho; ++TR) {
-      if (fill_params_f32(p, vi, TR, mp)) return true;
-      if (TR * c.Wo > 16 * 32) break;
-    }
+  for (int vi = 0; vi < kNumVariants; ++vi)
+    for (int TR = 1; TR <= c.N * c.Ho && TR * c.Wo <= 16 * 32; ++TR)
+      if (fill_params(p, which, vi, TR, mp)) return true;
   return false;
 }
 
 void mfma_configure(syno_plan* plan, int which) {
   const ConvLike& c = plan->conv;
+  const bool bf = plan->in_dtype == SYNO_BF16;
   double best = 1e300;
   int best_v = -1, best_tr = 0;
   MfmaParams mp;
   // SYNO_MFMA_TILE="variant,rows" overrides the tile choice (tuning aid)
   if (const char* f = getenv("SYNO_MFMA_TILE")) {
     int vi = -1, tr = 0;
-    if (sscanf(f, "%d,%d", &vi, &tr) == 2 && vi >= 0 && vi < 3 && fill_params_f32(plan, vi, tr, mp)) {
-      plan->launch[which].variant = vi * 4096 + tr;
-      plan->launch[which].workspace = 0;
-      return;
+    if (sscanf(f, "%d,%d", &vi, &tr) == 2 && fill_params(plan, which, vi, tr, mp)) {
+      best_v = vi; best_tr = tr;
     }
   }
-  for (int vi = 0; vi < 3; ++vi)
-    for (int TR = 1; TR <= c.N * c.Ho && TR * c.Wo <= 16 * 32; ++TR) {
-      if (!fill_params_f32(plan, vi, TR, mp)) continue;
-      const double cost = tile_cost(mp, kF32Variants[vi], c);
-      if (cost < best) { best = cost; best_v = vi; best_tr = TR; }
-    }
+  if (best_v < 0)
+    for (int vi = 0; vi < kNumVariants; ++vi)
+      for (int TR = 1; TR <= c.N * c.Ho && TR * c.Wo <= 16 * 32; ++TR) {
+        if (!fill_params(plan, which, vi, TR, mp)) continue;
+        const double cost = tile_cost(mp, variant_of(bf, vi), c, bf);
+        if (cost < best) { best = cost; best_v = vi; best_tr = TR; }
+      }
+  fill_params(plan, which, best_v, best_tr, mp);
   plan->launch[which].variant = best_v * 4096 + best_tr;
-  plan->launch[which].workspace = 0;
+  plan->launch[which].workspace = bf ? packed_weight_bytes(mp) : 0;
 }
 
 std::string mfma_describe(const syno_plan* plan, int which) {
   const int vi = plan->launch[which].variant / 4096, TR = plan->launch[which].variant % 4096;
   MfmaParams p;
-  if (vi < 0 || vi > 2 || !fill_params_f32(plan, vi, TR, p)) return "unconfigured";
-  const Variant& v = kF32Variants[vi];
+  if (!fill_params(plan, which, vi, TR, p)) return "unconfigured";
+  const Variant& v = variant_of(plan->in_dtype == SYNO_BF16, vi);
   char b[256];
   snprintf(b, sizeof b, "rows/block=%d BN=%d KC=%d waves=%dx%d grid=%d lds=%dB slots=%d", TR, v.BN(), p.KC, v.WM, v.WN,
            p.n_mblocks * p.n_nblocks * p.G, p.lds_bytes, p.n_slots);
   return b;
 }
 
-syno_status launch_mfma(const syno_plan* plan, int which, const void* A, const void* B, void* out, void*,
+syno_status launch_mfma(const syno_plan* plan, int which, const void* A, const void* B, void* out, void* ws,
                         hipStream_t stream) {
   const int vi = plan->launch[which].variant / 4096, TR = plan->launch[which].variant % 4096;
   MfmaParams p;
-  if (vi < 0 || vi > 2 || !fill_params_f32(plan, vi, TR, p)) return SYNO_ERR_UNSUPPORTED;
-  const float* X = static_cast<const float*>(A);
-  const float* W = static_cast<const float*>(B);
+  if (!fill_params(plan, which, vi, TR, p)) return SYNO_ERR_UNSUPPORTED;
   const bool obf = plan->out_dtype == SYNO_BF16;
-  switch (vi * 2 + (obf ? 1 : 0)) {
-    case 0: launch_f32<0, false>(p, X, W, out, stream); break;
-    case 1: launch_f32<0, true>(p, X, W, out, stream); break;
-    case 2: launch_f32<1, false>(p, X, W, out, stream); break;
-    case 3: launch_f32<1, true>(p, X, W, out, stream); break;
-    case 4: launch_f32<2, false>(p, X, W, out, stream); break;
-    case 5: launch_f32<2, true>(p, X, W, out, stream); break;
+  if (plan->in_dtype == SYNO_BF16) {
+    if (!ws) return SYNO_ERR_WORKSPACE;
+    const int64_t total = (int64_t)packed_weight_bytes(p) / 2;
+    hipLaunchKernelGGL(pack_weight_bf16, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, p,
+                       static_cast<const uint16_t*>(B), static_cast<uint16_t*>(ws), total);
+    if (obf) launch_dtype<true, true>(vi, p, A, ws, out, stream);
+    else launch_dtype<true, false>(vi, p, A, ws, out, stream);
+  } else {
+    if (obf) launch_dtype<false, true>(vi, p, A, B, out, stream);
+    else launch_dtype<false, false>(vi, p, A, B, out, stream);
   }
   return hipGetLastError() == hipSuccess ? SYNO_OK : SYNO_ERR_HIP;
 }

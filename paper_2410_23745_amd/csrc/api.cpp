@@ -12,6 +12,8 @@ syno_status launch_bandwidth(const syno_plan* p, int which, const void* A, const
 syno_status launch_mfma(const syno_plan* p, int which, const void* A, const void* B, void* out, void* ws,
                         hipStream_t stream);
 std::string mfma_describe(const syno_plan* p, int which);
+syno_status launch_mfma_dw(const syno_plan* p, const void* A, const void* B, void* out, void* ws, hipStream_t stream);
+std::string mfma_dw_describe(const syno_plan* p);
 }
 
 namespace {
@@ -29,7 +31,9 @@ syno_status run(const syno_plan* plan, int which, const void* A, const void* B, 
     case syno::KERNEL_GENERIC: return syno::launch_generic(plan, which, A, B, out, stream);
     case syno::KERNEL_BW_DEPTHWISE: return syno::launch_bandwidth(plan, which, A, B, out, ws, stream);
     case syno::KERNEL_MFMA_F32:
-    case syno::KERNEL_MFMA_BF16: return syno::launch_mfma(plan, which, A, B, out, ws, stream);
+    case syno::KERNEL_MFMA_BF16:
+      if (which == SYNO_BWD_WEIGHT) return syno::launch_mfma_dw(plan, A, B, out, ws, stream);
+      return syno::launch_mfma(plan, which, A, B, out, ws, stream);
     default: return SYNO_ERR_UNSUPPORTED;
   }
 }
@@ -104,7 +108,9 @@ syno_status syno_plan_describe(const syno_plan* plan, int which, char* buf, size
   switch (plan->launch[which].kernel) {
     case syno::KERNEL_GENERIC: d += plan->launch[which].coop ? " workgroup-per-target" : " lane-per-target"; break;
     case syno::KERNEL_MFMA_F32:
-    case syno::KERNEL_MFMA_BF16: d += " " + syno::mfma_describe(plan, which); break;
+    case syno::KERNEL_MFMA_BF16:
+      d += " " + (which == SYNO_BWD_WEIGHT ? syno::mfma_dw_describe(plan) : syno::mfma_describe(plan, which));
+      break;
     default: break;
   }
   snprintf(buf, size, "%s", d.c_str());

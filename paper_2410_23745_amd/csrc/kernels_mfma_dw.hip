@@ -1,0 +1,313 @@
+// MFMA backward-weight contraction for convolution-like operators (bf16 inputs, fp32 result):
+//   dW[g,o,c,kw] = sum_{n,h,w} G[n, g*Og+o, h, w] * X[n, g*Cg+c, row(h,g), w+kw-pw]       (KH = 1)
+// A GEMM per group and tap with M = o, N = c and the reduction over the pixels (n,h,w), which is the
+// contiguous axis of both operands - exactly what the bf16 MFMA wants (8 consecutive K per lane).
+//
+// Both operands are staged pixel-contiguous into LDS, rows laid out with a pitch of W plus at least
+// one zero column: that column is the zero padding of the window on either side, so a tap is a pure
+// shift of the X index by (kw - pw) elements and needs no mask.  G has zeros in its pad columns, so
+// whatever X holds there never contributes.  A shifted 8-element fragment is cut out of two aligned
+// 16-byte LDS reads with v_alignbit.
+//
+// The pixel axis is split over workgroups (split-K); each writes its 64x64xKW partial in the layout
+// of dW into the workspace and a second kernel adds the partials in a fixed order, so the result does
+// not depend on scheduling.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <string>
+
+#include "plan.h"
+
+namespace syno {
+
+struct DwParams {
+  int32_t G, Og, Cg, H, W, KW, pw;
+  int32_t rows_total;                  // N*H
+  int32_t h_wrap, h_shift, h_shift_g;  // X row = (h + h_shift + h_shift_g*g) mod H when wrapped, else h
+  int32_t plane, gs_n, xs_n;           // H*W; image strides of G and X
+  int32_t ws_g, ws_o, ws_c, ws_kw;     // dW strides
+  int32_t w_elems;                     // elements of dW (= stride between partials)
+  int32_t pitch, TRK, CP, CPp;         // LDS row pitch, rows per chunk, chunk length (multiple of 32), LDS channel pitch
+  int32_t rows_per_split, n_splits, n_oblk, n_cblk;
+  int32_t items;                       // 64 * TRK * W/2 dword items per tensor per chunk
+  uint32_t magic_w2, magic_rw2;        // ceil(2^32/d) for d = W/2 and TRK*W/2
+  int32_t lds_x_off, lds_tab_off, lds_bytes;
+};
+
+namespace {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+constexpr int kGuard = 8;     // zero elements in front of each X channel row (a tap may reach one element back)
+constexpr int kDwItems = 26;  // dword items per thread per tensor per chunk (256 threads)
+
+__device__ __forceinline__ uint32_t alignbit16(uint32_t hi, uint32_t lo) { return __builtin_amdgcn_alignbit(hi, lo, 16); }
+
+// Elements [s, s+8) of the 16 elements held in two consecutive aligned groups (lo, hi), s in 0..8.
+template <int S>
+__device__ __forceinline__ bf16x8 cut(const uint4& lo, const uint4& hi) {
+  const uint32_t d[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+  uint4 r;
+  if constexpr (S % 2 == 0) {
+    r = make_uint4(d[S / 2], d[S / 2 + 1], d[S / 2 + 2], d[S / 2 + 3]);
+  } else {
+    r = make_uint4(alignbit16(d[S / 2 + 1], d[S / 2]), alignbit16(d[S / 2 + 2], d[S / 2 + 1]),
+                   alignbit16(d[S / 2 + 3], d[S / 2 + 2]), alignbit16(d[S / 2 + 4], d[S / 2 + 3]));
+  }
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+// One workgroup: group g, 64 output channels x 64 input channels, one split of the pixel rows.
+// 4 waves; wave (wo, wc) owns o-tiles {2wo, 2wo+1} x c-tiles {2wc, 2wc+1} x KW taps.
+template <int KW>
+__global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint16_t* __restrict__ Gt,
+                                                    const uint16_t* __restrict__ Xt, float* __restrict__ partial) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint16_t* gl = reinterpret_cast<uint16_t*>(smem);                 // [64][CPp]
+  uint16_t* xl = reinterpret_cast<uint16_t*>(smem + p.lds_x_off);   // [64][CPp], data starts at kGuard
+  int* row_tab = reinterpret_cast<int*>(smem + p.lds_tab_off);      // [2][TRK]: G row offset, X row offset (-1: none)
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int widx = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wo = widx >> 1, wc = widx & 1;
+  int bid = blockIdx.x;
+  const int split = bid % p.n_splits; bid /= p.n_splits;
+  const int cb = bid % p.n_cblk; bid /= p.n_cblk;
+  const int ob = bid % p.n_oblk;
+  const int g = bid / p.n_oblk;
+  const int row_begin = split * p.rows_per_split;
+  const int row_end = min(p.rows_total, row_begin + p.rows_per_split);
+
+  // zero both tiles once: pad columns, guards and tails stay zero for the whole kernel
+  {
+    uint4* z = reinterpret_cast<uint4*>(smem);
+    const int n16 = p.lds_tab_off >> 4;
+    for (int i = tid; i < n16; i += 256) z[i] = make_uint4(0, 0, 0, 0);
+  }
+  // per-thread item descriptors, the same for G and X: (channel, row, dword) of the chunk
+  // goff: element offset inside the 64-channel slab (even; bit 0 set = G channel beyond Og)
+  // meta: LDS element offset | row << 20 | (X channel beyond Cg) << 30 ; -1 when unused
+  int it_goff[kDwItems], it_meta[kDwItems];
+  const int W2 = p.W >> 1;
+  const int o_lim = p.Og - ob * 64, c_lim = p.Cg - cb * 64;     // channels beyond are zero
+#pragma unroll
+  for (int k = 0; k < kDwItems; ++k) {
+    const int idx = tid + k * 256;
+    const int ch = __umulhi((uint32_t)idx, p.magic_rw2);
+    const int rem = idx - ch * (p.TRK * W2);
+    const int r = __umulhi((uint32_t)rem, p.magic_w2);
+    const int j = rem - r * W2;
+    it_goff[k] = (ch * p.plane + 2 * j) | (ch < o_lim ? 0 : 1);
+    it_meta[k] = idx < p.items ? ((ch * p.CPp + r * p.pitch + 2 * j) | (r << 20) | (ch < c_lim ? 0 : (1 << 30))) : -1;
+  }
+  const uint16_t* Gg = Gt + (int64_t)(g * p.Og + ob * 64) * p.plane;
+  const uint16_t* Xg = Xt + (int64_t)(g * p.Cg + cb * 64) * p.plane;
+
+  floatx4 acc[2][2][KW];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int t = 0; t < KW; ++t) acc[a][b][t] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  // operand bases (element indices)
+  int a_base[2], b_base[2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a) a_base[a] = ((2 * wo + a) * 16 + (lane & 15)) * p.CPp + (lane >> 4) * 8;
+#pragma unroll
+  for (int b = 0; b < 2; ++b) b_base[b] = ((2 * wc + b) * 16 + (lane & 15)) * p.CPp + (lane >> 4) * 8 + kGuard - 8;
+
+  uint32_t gr[kDwItems], xr[kDwItems];
+  for (int rho0 = row_begin; rho0 < row_end; rho0 += p.TRK) {
+    __syncthreads();        // previous chunk fully consumed (and, first time, the zero fill is complete)
+    if (tid < p.TRK) {
+      const int rho = rho0 + tid;
+      int go = -1, xo = -1;
+      if (rho < row_end) {
+        const int n = rho / p.H, h = rho - n * p.H;
+        const int r = p.h_wrap ? (h + p.h_shift + p.h_shift_g * g) % p.H : h;
+        go = n * p.gs_n + h * p.W;
+        xo = n * p.xs_n + r * p.W;
+      }
+      row_tab[tid] = go;
+      row_tab[p.TRK + tid] = xo;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < kDwItems; ++k) {
+      gr[k] = 0; xr[k] = 0;
+      if (it_meta[k] >= 0) {
+        const int r = (it_meta[k] >> 20) & 1023;
+        const int go = row_tab[r], xo = row_tab[p.TRK + r];
+        if (go >= 0 && !(it_goff[k] & 1)) gr[k] = *reinterpret_cast<const uint32_t*>(Gg + go + it_goff[k]);
+        if (xo >= 0 && !(it_meta[k] >> 30)) xr[k] = *reinterpret_cast<const uint32_t*>(Xg + xo + (it_goff[k] & ~1));
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < kDwItems; ++k)
+      if (it_meta[k] >= 0) {
+        const int lo = it_meta[k] & 0xfffff;
+        *reinterpret_cast<uint32_t*>(gl + lo) = gr[k];
+        *reinterpret_cast<uint32_t*>(xl + lo + kGuard) = xr[k];
+      }
+    __syncthreads();
+    const int steps = p.CP >> 5;
+    for (int st = 0; st < steps; ++st) {
+      bf16x8 a[2];
+      uint4 xlo[2], xhi[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(gl + a_base[i] + st * 32));
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        xlo[i] = *reinterpret_cast<const uint4*>(xl + b_base[i] + st * 32);
+        xhi[i] = *reinterpret_cast<const uint4*>(xl + b_base[i] + st * 32 + 8);
+      }
+      // tap kw reads X shifted by (kw - pw): element 8 + kw - pw of the 16 just read
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        bf16x8 b[KW];
+        if constexpr (KW == 1) {
+          b[0] = cut<8>(xlo[i], xhi[i]);
+        } else {
+          b[0] = cut<7>(xlo[i], xhi[i]);
+          b[1] = cut<8>(xlo[i], xhi[i]);
+          // one more element to the right needs the next group; read it only for this tap
+          const uint4 xnx = *reinterpret_cast<const uint4*>(xl + b_base[i] + st * 32 + 16);
+          b[2] = cut<1>(xhi[i], xnx);
+        }
+#pragma unroll
+        for (int t = 0; t < KW; ++t)
+#pragma unroll
+          for (int ao = 0; ao < 2; ++ao)
+            acc[ao][i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ao], b[t], acc[ao][i][t], 0, 0, 0);
+      }
+    }
+  }
+
+  // partial[split][dW layout]: lane holds 4 consecutive o (rows of D) at one c (column)
+  float* dst = partial + (int64_t)split * p.w_elems + (int64_t)g * p.ws_g;
+#pragma unroll
+  for (int ao = 0; ao < 2; ++ao)
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int c = cb * 64 + (2 * wc + i) * 16 + (lane & 15);
+      if (c >= p.Cg) continue;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int o = ob * 64 + (2 * wo + ao) * 16 + 4 * (lane >> 4) + v;
+        if (o >= p.Og) continue;
+#pragma unroll
+        for (int t = 0; t < KW; ++t) dst[(int64_t)o * p.ws_o + (int64_t)c * p.ws_c + t * p.ws_kw] = acc[ao][i][t][v];
+      }
+    }
+}
+
+__global__ __launch_bounds__(256) void dw_reduce(const float* __restrict__ partial, float* __restrict__ dW, int n_elems,
+                                                 int n_splits) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= n_elems) return;
+  float s = 0.f;
+  for (int k = 0; k < n_splits; ++k) s += partial[(int64_t)k * n_elems + i];
+  dW[i] = s;
+}
+
+uint32_t magic_of(int d) { return (uint32_t)(((1ull << 32) + d - 1) / d); }
+
+bool fill_dw(const syno_plan* plan, DwParams& p) {
+  const ConvLike& c = plan->conv;
+  p = DwParams{};
+  p.G = c.G; p.Og = c.Og; p.Cg = c.Cg; p.H = c.Ho; p.W = c.Wo; p.KW = c.KW; p.pw = c.pw;
+  p.rows_total = c.N * c.Ho;
+  p.h_wrap = c.h_wrap; p.h_shift = c.h_shift; p.h_shift_g = c.h_shift_g;
+  p.plane = c.Ho * c.Wo;
+  p.gs_n = c.G * c.Og * p.plane; p.xs_n = c.G * c.Cg * p.plane;
+  p.ws_g = c.ws_g; p.ws_o = c.ws_o; p.ws_c = c.ws_c; p.ws_kw = c.ws_kw;
+  p.w_elems = (int32_t)plan->w_elems;
+  p.pitch = (c.Wo + std::max(c.pw, c.KW - 1 - c.pw) + 1) & ~1;
+  if (p.pitch == c.Wo) p.pitch += 2;                 // always at least one zero column
+  // rows per chunk: about 224 staged elements per channel, bounded by the per-thread item budget
+  const int W2 = c.Wo / 2;
+  int trk = std::max(1, 224 / p.pitch);
+  while (trk > 1 && 64 * trk * W2 > kDwItems * 256) --trk;
+  if (64 * trk * W2 > kDwItems * 256) return false;
+  p.TRK = std::min(trk, p.rows_total);
+  p.CP = (p.TRK * p.pitch + 31) & ~31;
+  p.CPp = p.CP + 24;                                  // guard in front, slack behind, rows 16-byte aligned and bank-skewed
+  p.items = 64 * p.TRK * W2;
+  p.magic_w2 = magic_of(W2);
+  p.magic_rw2 = magic_of(p.TRK * W2);
+  p.n_oblk = (c.Og + 63) / 64;
+  p.n_cblk = (c.Cg + 63) / 64;
+  // split the rows: aim at one or two workgroups per CU, keep the partials below ~8 MB
+  const int tiles = c.G * p.n_oblk * p.n_cblk;
+  const int chunks = (p.rows_total + p.TRK - 1) / p.TRK;
+  int splits = std::max(1, std::min(chunks, 256 / std::max(1, tiles)));
+  while (splits > 1 && (int64_t)splits * plan->w_elems * 4 > (8ll << 20)) splits /= 2;
+  const int chunks_per_split = (chunks + splits - 1) / splits;
+  p.rows_per_split = chunks_per_split * p.TRK;
+  p.n_splits = (p.rows_total + p.rows_per_split - 1) / p.rows_per_split;
+  p.lds_x_off = 64 * p.CPp * 2;
+  p.lds_tab_off = 2 * p.lds_x_off;
+  p.lds_bytes = p.lds_tab_off + ((2 * p.TRK * 4 + 15) & ~15);
+  return p.lds_bytes <= 144 * 1024 && 64 * p.CPp < (1 << 20) && p.TRK < 1024;
+}
+
+}  // namespace
+
+bool mfma_dw_supports(const syno_plan* p) {
+  if (!p->conv_like || p->in_dtype != SYNO_BF16) return false;
+  const ConvLike& c = p->conv;
+  if (c.sh != 1 || c.sw != 1 || c.w_wrap || c.KH != 1) return false;
+  if (c.Wi != c.Wo || c.Hi != c.Ho || (c.Wo & 1)) return false;
+  if (c.KW != 1 && c.KW != 3) return false;
+  if (c.pw != c.KW / 2) return false;
+  if (c.ws_kw < 0 || (c.Og == 1 && c.Cg == 1)) return false;
+  DwParams dp;
+  return fill_dw(p, dp);
+}
+
+void mfma_dw_configure(syno_plan* plan) {
+  DwParams dp;
+  fill_dw(plan, dp);
+  plan->launch[SYNO_BWD_WEIGHT].variant = 0;
+  plan->launch[SYNO_BWD_WEIGHT].workspace = (size_t)dp.n_splits * plan->w_elems * 4;
+}
+
+std::string mfma_dw_describe(const syno_plan* plan) {
+  DwParams p;
+  if (!fill_dw(plan, p)) return "unconfigured";
+  char b[256];
+  snprintf(b, sizeof b, "rows/chunk=%d pitch=%d splits=%d grid=%d lds=%dB", p.TRK, p.pitch, p.n_splits,
+           p.G * p.n_oblk * p.n_cblk * p.n_splits, p.lds_bytes);
+  return b;
+}
+
+// A = G (upstream gradient), B = X, out = dW (fp32), ws = n_splits partial copies of dW.
+syno_status launch_mfma_dw(const syno_plan* plan, const void* A, const void* B, void* out, void* ws, hipStream_t stream) {
+  DwParams p;
+  if (!fill_dw(plan, p)) return SYNO_ERR_UNSUPPORTED;
+  if (!ws) return SYNO_ERR_WORKSPACE;
+  const int grid = p.G * p.n_oblk * p.n_cblk * p.n_splits;
+  const uint16_t* G = static_cast<const uint16_t*>(A);
+  const uint16_t* X = static_cast<const uint16_t*>(B);
+  float* part = static_cast<float*>(ws);
+  if (p.KW == 3) {
+    static const hipError_t opt_in = hipFuncSetAttribute(reinterpret_cast<const void*>(dw_mfma_bf16<3>),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
+    (void)opt_in;
+    hipLaunchKernelGGL(dw_mfma_bf16<3>, dim3(grid), dim3(256), p.lds_bytes, stream, p, G, X, part);
+  } else {
+    static const hipError_t opt_in = hipFuncSetAttribute(reinterpret_cast<const void*>(dw_mfma_bf16<1>),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
+    (void)opt_in;
+    hipLaunchKernelGGL(dw_mfma_bf16<1>, dim3(grid), dim3(256), p.lds_bytes, stream, p, G, X, part);
+  }
+  hipLaunchKernelGGL(dw_reduce, dim3((p.w_elems + 255) / 256), dim3(256), 0, stream, part, static_cast<float*>(out),
+                     p.w_elems, p.n_splits);
+  return hipGetLastError() == hipSuccess ? SYNO_OK : SYNO_ERR_HIP;
+}
+
+}  // namespace syno

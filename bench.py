@@ -157,6 +157,18 @@ def main() -> int:
                     "traffic": None}
     roofline["kernel"] = f"{dom_key[0]}[{dom_key[1]}]"
     roofline["avg_launch_us"] = dom_ms * 1e3
+    roofline["launches_averaged"] = [c.name for c in dom]
+    # HBM traffic per launch comes from stored rocprofv3 --pmc runs (profiles/traffic.json) and only counts
+    # while the kernel source they were taken on is unchanged
+    try:
+        import hashlib
+        rec = json.load(open(os.path.join(ROOT, "profiles", "traffic.json")))
+        srcs = [os.path.join(ROOT, "paper_2410_23745_amd", "csrc", f) for f in rec["sources"]]
+        digest = hashlib.sha256(b"".join(open(f, "rb").read() for f in srcs)).hexdigest()
+        if digest == rec["sha256"] and rec["kernel"] == roofline["kernel"]:
+            roofline["traffic"] = rec["hbm_bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        pass
 
     out = {
         "metric": "operator fwd TFLOP/s & % of roofline at ResNet-style layer shapes",
@@ -187,7 +199,8 @@ def main() -> int:
             gbs = c.bytes / (med * 1e-3) / 1e9
             peak = MFMA_PEAK_TFLOPS[c.dtype]
             roof_tf = min(peak, c.flops / c.bytes * HBM_PEAK_GBS / 1e3)
-            detail.append({"case": c.name, "kernel": c.kernel, "us": med * 1e3, "TFLOP/s": tf, "GB/s": gbs,
+            detail.append({"case": c.name, "kernel": c.kernel, "launch": c.plan.describe(c.which), "us": med * 1e3,
+                           "TFLOP/s": tf, "GB/s": gbs,
                            "bound": "hbm" if roof_tf < peak else "mfma", "roofline_frac": tf / roof_tf,
                            "rotating_sets": len(c.sets)})
         out["detail"] = detail
@@ -195,7 +208,7 @@ def main() -> int:
     # ---- CPU baseline: the checker as it stands, on a bounded sample of the same workload ---------------------
     if not args.no_cpu_baseline:
         import oracle
-        n_s = 131072
+        n_s = 1 << 20
         rng = np.random.default_rng(0)
         macs, t_cpu = 0, 0.0
         for stage in range(4):

@@ -116,24 +116,31 @@ __global__ __launch_bounds__(256) void pack_weight_bf16(const MfmaParams p, cons
 // BF = false: fp32 inputs, CI = 4, v_mfma_f32_16x16x4_f32  (A: lane -> row l%16, k = l/16).
 // BF = true : bf16 inputs, CI = 8, v_mfma_f32_16x16x32_bf16 (A: lane -> row l%16, k = 8*(l/16)..+7);
 //             `Wv` is the packed copy.
-template <bool BF, int WM, int WN, int TM, int TN, int XI, int WI, bool OUTBF>
-__global__ __launch_bounds__(WM* WN * 64) void conv_mfma(const MfmaParams p, const void* __restrict__ Xv,
+// WNAT (fp32 only): the weight block of one output channel, [KC][KH][KW], is contiguous and 16-byte
+//             aligned in memory, so it is staged with 16-byte loads instead of element by element.
+// WK:  waves that share one output tile and split each chunk's k-steps among themselves (for shapes whose
+//      per-SIMD share of the output is only a few MFMA tiles: a wave then still issues TM*TN MFMAs per
+//      LDS round trip); their accumulators are added through LDS at the end.
+template <bool BF, bool WNAT, int WM, int WN, int WK, int TM, int TN, int XI, int WI, bool OUTBF>
+__global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p, const void* __restrict__ Xv,
                                                          const void* __restrict__ Wv, void* __restrict__ out) {
-  constexpr int NT = WM * WN * 64;
+  constexpr int NT = WM * WN * WK * 64;
   constexpr int BN = WN * TN * 16;
   constexpr int CI = BF ? 8 : 4;
   constexpr int CG_STEP = BF ? 4 : 1;        // channel groups one MFMA consumes
   using XT = std::conditional_t<BF, uint16_t, float>;
   using Frag = std::conditional_t<BF, bf16x8, float>;
-  using WReg = std::conditional_t<BF, uint4, float>;
+  constexpr bool W16 = BF || WNAT;           // weights move in 16-byte pieces
+  using WReg = std::conditional_t<W16, uint4, float>;
   extern __shared__ __align__(16) unsigned char smem[];
   float4* xl = reinterpret_cast<float4*>(smem);
   int* slot_src = reinterpret_cast<int*>(smem + p.lds_tab_off);
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int widx = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in an SGPR
-  const int wn = widx / WM;
-  const int wm = (widx + wn) % WM;          // spread the fuller wave rows over the SIMDs
+  const int wk = widx / (WM * WN), wtile = widx - wk * (WM * WN);
+  const int wn = wtile / WM;
+  const int wm = (wtile + wn) % WM;         // spread the fuller wave rows over the SIMDs
   int bid = blockIdx.x;
   const int nb = bid % p.n_nblocks; bid /= p.n_nblocks;
   const int mb = bid % p.n_mblocks;
@@ -152,6 +159,9 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_mfma(const MfmaParams p, con
   // ---- loop-invariant descriptors of what this thread stages per chunk
   const XT* Xg = reinterpret_cast<const XT*>(Xv) + (int64_t)g * p.Cg * p.xs_c;
   int x_goff[XI], x_loff[XI], x_cg[XI];
+  int w_goff[WI], w_meta[WI];   // fp32 meta: LDS dword offset | local channel << 20 | zero-fill << 29 | unused << 30
+  const float* Wg32 = nullptr;
+  const uint4* Wg16 = nullptr;
   {
     const int per_cg = p.n_slots * p.Wi, total = p.cgrps * per_cg;
 #pragma unroll
@@ -167,9 +177,6 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_mfma(const MfmaParams p, con
   }
   // fp32: one weight element per item, gathered with the operator's strides into [o][c*KHW+tap].
   // bf16: 16-byte pieces of this block's packed image, copied as they are.
-  const float* Wg32 = nullptr;
-  const uint4* Wg16 = nullptr;
-  int w_goff[WI], w_meta[WI];   // fp32 meta: LDS dword offset | local channel << 20 | zero-fill << 29 | unused << 30
   if constexpr (BF) {
     Wg16 = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(Wv) +
                                           ((int64_t)(g * p.n_nblocks + nb) * p.n_chunks) * p.w_block);
@@ -179,6 +186,17 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_mfma(const MfmaParams p, con
       const int idx = tid + k * NT;
       w_goff[k] = idx < units ? idx : -1;
       w_meta[k] = 0;
+    }
+  } else if constexpr (WNAT) {
+    Wg32 = reinterpret_cast<const float*>(Wv) + (int64_t)g * p.ws_g + (int64_t)nb * BN * p.ws_o;
+    const int per_o4 = (p.KC * KHW) >> 2, total = BN * per_o4;   // float4 pieces per output channel
+#pragma unroll
+    for (int k = 0; k < WI; ++k) {
+      const int idx = tid + k * NT;
+      const int o = idx / per_o4, e4 = idx - o * per_o4;
+      const bool ok = idx < total && nb * BN + o < p.Og;
+      w_goff[k] = ok ? o * p.ws_o + e4 * 4 : -1;                 // element offset
+      w_meta[k] = idx < total ? (o * p.w_row + e4 * 4) >> 2 : -1; // LDS float4 index
     }
   } else {
     Wg32 = reinterpret_cast<const float*>(Wv) + p.w_base + (int64_t)g * p.ws_g + (int64_t)nb * BN * p.ws_o;
@@ -218,9 +236,15 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_mfma(const MfmaParams p, con
     b_base[u] = BF ? ol * p.w_row + (lane >> 4) * 8 : ol * p.w_row + (lane >> 4) * KHW;
   }
 
-  floatx4 acc[TM][TN];
+  // Everything from here on is instantiated once per possible tile count of a wave, so that the
+  // accumulators and fragments of a wave with fewer row tiles do not occupy registers and the MFMA
+  // block is straight-line code.
+  auto run = [&](auto ntl_c) {
+  constexpr int NTL = decltype(ntl_c)::value;
+  constexpr int NA = NTL > 0 ? NTL : 1;
+  floatx4 acc[NA][TN];
 #pragma unroll
-  for (int t = 0; t < TM; ++t)
+  for (int t = 0; t < NA; ++t)
 #pragma unroll
     for (int u = 0; u < TN; ++u) acc[t][u] = floatx4{0.f, 0.f, 0.f, 0.f};
 
@@ -239,6 +263,12 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_mfma(const MfmaParams p, con
       const uint4* src = Wg16 + (int64_t)ch * (p.w_block >> 3);
 #pragma unroll
       for (int k = 0; k < WI; ++k) wr[k] = w_goff[k] >= 0 ? src[w_goff[k]] : make_uint4(0, 0, 0, 0);
+    } else if constexpr (WNAT) {
+      // (the planner only picks this path when Cg is a multiple of KC, so no channel tail here)
+#pragma unroll
+      for (int k = 0; k < WI; ++k)
+        wr[k] = w_goff[k] >= 0 ? *reinterpret_cast<const uint4*>(Wg32 + w_goff[k] + (int64_t)c0 * p.ws_c)
+                               : make_uint4(0, 0, 0, 0);
     } else {
 #pragma unroll
       for (int k = 0; k < WI; ++k) {
@@ -267,6 +297,11 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_mfma(const MfmaParams p, con
 #pragma unroll
       for (int k = 0; k < WI; ++k)
         if (w_goff[k] >= 0) wl[w_goff[k]] = wr[k];
+    } else if constexpr (WNAT) {
+      uint4* wl = reinterpret_cast<uint4*>(smem + p.lds_w_off);
+#pragma unroll
+      for (int k = 0; k < WI; ++k)
+        if (w_meta[k] >= 0) wl[w_meta[k]] = wr[k];
     } else {
       float* wl = reinterpret_cast<float*>(smem + p.lds_w_off);
 #pragma unroll
@@ -280,21 +315,26 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_mfma(const MfmaParams p, con
     __syncthreads();   // everyone has finished reading the previous chunk
     stage();
     __syncthreads();
-    if (ch + 1 < p.n_chunks) fetch(ch + 1);
+    if (ch + 1 < p.n_chunks) fetch(ch + 1);   // next chunk travels while this one is computed
     // One k-step = CI*CG_STEP channels at one tap.  Fragments of step i+1 are read from LDS while the
     // MFMAs of step i issue.  The tile count is a compile-time constant per case so that the MFMA
     // block is straight-line code.
-    auto compute = [&](auto ntl_c) {
-      constexpr int NTL = decltype(ntl_c)::value;
-      const int steps = (p.cgrps / CG_STEP) * KHW;
-      int cg = 0, kh = 0, kw = 0;
+    if constexpr (NTL > 0) {
+      const int all_steps = (p.cgrps / CG_STEP) * KHW;
+      const int first = wk * all_steps / WK, steps = (wk + 1) * all_steps / WK - first;
+      if (steps > 0) {
+      // running operand offsets of the current k-step (wave-uniform, advanced with scalar adds):
+      // fp32: a in dwords, b in dwords; bf16: a in 16-byte units, b in elements
+      int cg = first / KHW, kh = (first - cg * KHW) / p.KW, kw = first - cg * KHW - kh * p.KW;
+      const int a_kw = BF ? 1 : 4, a_kh = (BF ? 1 : 4) * p.Wp, a_cg = (BF ? CG_STEP : 4) * cg_stride;
+      const int b_kw = BF ? BN * p.w_row : 1, b_cg = BF ? CG_STEP * CI : CI * KHW;
+      int a_off = cg * a_cg + kh * a_kh + kw * a_kw;
+      int b_off = BF ? (kh * p.KW + kw) * b_kw + cg * b_cg : cg * b_cg + kh * p.KW + kw;
       Frag a0[NTL], b0[TN], a1[NTL], b1[TN];
       auto read = [&](Frag (&a)[NTL], Frag (&b)[TN]) {
         if constexpr (BF) {
           const uint4* xq = reinterpret_cast<const uint4*>(smem);
           const uint16_t* wq = reinterpret_cast<const uint16_t*>(smem + p.lds_w_off);
-          const int a_off = cg * CG_STEP * cg_stride + kh * p.Wp + kw;
-          const int b_off = ((kh * p.KW + kw) * BN) * p.w_row + cg * CG_STEP * CI;
 #pragma unroll
           for (int u = 0; u < TN; ++u)
             b[u] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(wq + b_base[u] + b_off));
@@ -303,8 +343,6 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_mfma(const MfmaParams p, con
         } else {
           const float* xq = reinterpret_cast<const float*>(smem);
           const float* wq = reinterpret_cast<const float*>(smem + p.lds_w_off);
-          const int a_off = (cg * cg_stride + kh * p.Wp + kw) * 4;
-          const int b_off = cg * CI * KHW + kh * p.KW + kw;
 #pragma unroll
           for (int u = 0; u < TN; ++u) b[u] = wq[b_base[u] + b_off];
 #pragma unroll
@@ -312,7 +350,14 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_mfma(const MfmaParams p, con
         }
       };
       auto advance = [&]() {
-        if (++kw == p.KW) { kw = 0; if (++kh == p.KH) { kh = 0; ++cg; } }
+        a_off += a_kw; b_off += b_kw;
+        if (++kw == p.KW) {
+          kw = 0; a_off += a_kh - p.KW * a_kw;
+          if (++kh == p.KH) {
+            kh = 0; a_off += a_cg - p.KH * a_kh;
+            b_off += b_cg - KHW * b_kw;
+          }
+        }
       };
       auto mfmas = [&](const Frag (&a)[NTL], const Frag (&b)[TN]) {
 #pragma unroll
@@ -323,35 +368,46 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_mfma(const MfmaParams p, con
             else acc[t][u] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[t], b[u], acc[t][u], 0, 0, 0);
           }
       };
+      // steady state without branches, so that the waits on LDS can be exact: the reads of the next
+      // step stay in flight while the MFMAs of the current one issue
       read(a0, b0);
-      for (int it = 0;;) {
-        if (it + 1 < steps) { advance(); read(a1, b1); }
-        mfmas(a0, b0);
-        if (++it >= steps) break;
-        if (it + 1 < steps) { advance(); read(a0, b0); }
-        mfmas(a1, b1);
-        if (++it >= steps) break;
+      int it = 0;
+      for (; it + 2 < steps; it += 2) {
+        advance(); read(a1, b1); mfmas(a0, b0);
+        advance(); read(a0, b0); mfmas(a1, b1);
       }
-    };
-    static_assert(TM <= 8, "extend the dispatch below");
-    switch (my_tiles) {
-      case 1: compute(std::integral_constant<int, 1>{}); break;
-      case 2: if constexpr (TM >= 2) compute(std::integral_constant<int, 2>{}); break;
-      case 3: if constexpr (TM >= 3) compute(std::integral_constant<int, 3>{}); break;
-      case 4: if constexpr (TM >= 4) compute(std::integral_constant<int, 4>{}); break;
-      case 5: if constexpr (TM >= 5) compute(std::integral_constant<int, 5>{}); break;
-      case 6: if constexpr (TM >= 6) compute(std::integral_constant<int, 6>{}); break;
-      case 7: if constexpr (TM >= 7) compute(std::integral_constant<int, 7>{}); break;
-      case 8: if constexpr (TM >= 8) compute(std::integral_constant<int, 8>{}); break;
-      default: break;
+      if (it + 1 < steps) { advance(); read(a1, b1); mfmas(a0, b0); mfmas(a1, b1); }
+      else mfmas(a0, b0);
+      }
     }
+  }
+
+  // ---- waves that split the k-steps add their accumulators into the first one's
+  if constexpr (WK > 1) {
+    floatx4* red = reinterpret_cast<floatx4*>(smem);     // [WM*WN][TM*TN][64 lanes], reusing the staging area
+    for (int k = 1; k < WK; ++k) {
+      __syncthreads();
+      if (wk == k) {
+#pragma unroll
+        for (int t = 0; t < NTL; ++t)
+#pragma unroll
+          for (int u = 0; u < TN; ++u) red[((wtile * TM + t) * TN + u) * 64 + lane] = acc[t][u];
+      }
+      __syncthreads();
+      if (wk == 0) {
+#pragma unroll
+        for (int t = 0; t < NTL; ++t)
+#pragma unroll
+          for (int u = 0; u < TN; ++u) acc[t][u] += red[((wtile * TM + t) * TN + u) * 64 + lane];
+      }
+    }
+    if (wk != 0) return;
   }
 
   // ---- store: lane holds 4 consecutive pixels (rows of D) of one channel (column of D)
   const int img_px = p.Ho * p.Wo;
 #pragma unroll
-  for (int t = 0; t < TM; ++t) {
-    if (t >= my_tiles) continue;
+  for (int t = 0; t < NTL; ++t) {
     const int m0 = (my_first + t) * 16 + 4 * (lane >> 4);
 #pragma unroll
     for (int u = 0; u < TN; ++u) {
@@ -392,24 +448,49 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_mfma(const MfmaParams p, con
       }
     }
   }
+  };
+  static_assert(TM <= 8, "extend the dispatch below");
+  switch (my_tiles) {
+    case 0: run(std::integral_constant<int, 0>{}); break;
+    case 1: run(std::integral_constant<int, 1>{}); break;
+    case 2: if constexpr (TM >= 2) run(std::integral_constant<int, 2>{}); break;
+    case 3: if constexpr (TM >= 3) run(std::integral_constant<int, 3>{}); break;
+    case 4: if constexpr (TM >= 4) run(std::integral_constant<int, 4>{}); break;
+    case 5: if constexpr (TM >= 5) run(std::integral_constant<int, 5>{}); break;
+    case 6: if constexpr (TM >= 6) run(std::integral_constant<int, 6>{}); break;
+    case 7: if constexpr (TM >= 7) run(std::integral_constant<int, 7>{}); break;
+    case 8: if constexpr (TM >= 8) run(std::integral_constant<int, 8>{}); break;
+    default: break;
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
 // Host side: tile choice and launch
 // ---------------------------------------------------------------------------------------------
 struct Variant {
-  int WM, WN, TM, TN, XI, WI;
-  constexpr int NT() const { return WM * WN * 64; }
+  int WM, WN, WK, TM, TN, XI, WI;
+  int KC;        // channels per chunk (fp32 variants may fall back to smaller multiples)
+  bool wnat;     // fp32: contiguous weight rows staged in 16-byte pieces
+  constexpr int NT() const { return WM * WN * WK * 64; }
   constexpr int BN() const { return WN * TN * 16; }
   constexpr int MT() const { return WM * TM; }
 };
-// tile variants: BN = 64, 32, 16 output channels per workgroup; 8 waves
-constexpr int kNumVariants = 3;
-constexpr Variant kF32Variants[kNumVariants] = {{4, 2, 7, 2, 3, 9}, {4, 2, 7, 1, 3, 5}, {8, 1, 4, 1, 3, 3}};
-constexpr Variant kBf16Variants[kNumVariants] = {{4, 2, 7, 2, 4, 6}, {4, 2, 7, 1, 4, 3}, {8, 1, 4, 1, 4, 2}};
+// Tile variants, 8 waves each.  Row tiles x column tiles per wave, waves along M x N x K:
+//   fp32 0-2: any weight strides, 8 channels per chunk (the backward-data adjoint runs here)
+//   fp32 3-8: forward weight layout [o][c][kh][kw], 32 channels per chunk
+//   bf16 0-5: packed weights, 32 channels per chunk
+constexpr int kNumF32Variants = 9, kNumBf16Variants = 6;
+constexpr Variant kF32Variants[kNumF32Variants] = {
+    {4, 2, 1, 7, 2, 3, 9, 8, false}, {4, 2, 1, 7, 1, 3, 5, 8, false}, {8, 1, 1, 4, 1, 3, 3, 8, false},
+    {4, 2, 1, 7, 2, 8, 9, 32, true}, {4, 1, 2, 7, 2, 8, 5, 32, true}, {2, 1, 4, 7, 2, 8, 5, 32, true},
+    {1, 1, 8, 4, 4, 8, 9, 32, true}, {4, 2, 1, 7, 1, 8, 5, 32, true}, {8, 1, 1, 4, 1, 8, 3, 32, true}};
+constexpr Variant kBf16Variants[kNumBf16Variants] = {
+    {4, 2, 1, 7, 2, 4, 6, 32, false}, {4, 1, 2, 7, 2, 4, 3, 32, false}, {2, 1, 4, 7, 2, 4, 3, 32, false},
+    {1, 1, 8, 4, 4, 4, 6, 32, false}, {4, 2, 1, 7, 1, 4, 3, 32, false}, {8, 1, 1, 4, 1, 4, 2, 32, false}};
 constexpr int kNumCU = 256;
 constexpr int kMaxLdsBytes = 144 * 1024;   // of the 160 KB a CU has
 
+int num_variants(bool bf) { return bf ? kNumBf16Variants : kNumF32Variants; }
 const Variant& variant_of(bool bf, int vi) { return bf ? kBf16Variants[vi] : kF32Variants[vi]; }
 
 // most images a run of TR consecutive output rows can touch (blocks start at multiples of TR)
@@ -421,9 +502,9 @@ int images_spanned(int TR, int Ho) {
 
 // LDS weight row pitch (in dwords) >= need such that the 64 lanes of a B-fragment read (16 rows x 4
 // channel steps of `kstep` dwords) fall into distinct banks where possible.
-int pick_w_row(int need, int kstep) {
+int pick_w_row(int need, int kstep, int multiple_of) {
   int best = need, best_conf = 1 << 30;
-  for (int r = need; r < need + 64; ++r) {
+  for (int r = (need + multiple_of - 1) / multiple_of * multiple_of; r < need + 128; r += multiple_of) {
     int cnt[64] = {};
     int conf = 0;
     for (int n = 0; n < 16; ++n)
@@ -439,7 +520,7 @@ int pick_w_row(int need, int kstep) {
 bool fill_params(const syno_plan* plan, int which, int vi, int TR, MfmaParams& p) {
   const ConvLike& c = plan->conv;
   const bool bf = plan->in_dtype == SYNO_BF16;
-  if (vi < 0 || vi >= kNumVariants || TR < 1) return false;
+  if (vi < 0 || vi >= num_variants(bf) || TR < 1) return false;
   const Variant& v = variant_of(bf, vi);
   p = MfmaParams{};
   p.G = c.G; p.Ho = c.Ho; p.Wo = c.Wo; p.Hi = c.Hi; p.Wi = c.Wi;
@@ -471,11 +552,20 @@ bool fill_params(const syno_plan* plan, int which, int vi, int TR, MfmaParams& p
     p.w_row = p.KC + 8;                          // elements; 80-byte rows keep B-fragment reads conflict free
     p.w_block = KHW * p.BN * p.w_row;
     if ((p.w_block >> 3) > v.WI * v.NT()) return false;
+  } else if (v.wnat) {
+    if (which != SYNO_FWD || c.ws_kw != 1 || c.ws_kh != c.KW || c.ws_c != KHW || (c.ws_o & 3) || (c.ws_g & 3))
+      return false;
+    p.KC = v.KC;
+    while (p.KC > 8 && (p.Cg % p.KC != 0 || p.BN * p.KC * KHW > 4 * v.WI * v.NT() ||
+                        (p.KC / CI) * (c.h_wrap ? TR : TR + (c.KH - 1) * images_spanned(TR, c.Ho)) * c.Wi > v.XI * v.NT()))
+      p.KC -= 8;
+    if (p.Cg % p.KC != 0 || ((p.KC * KHW) & 3) || p.BN * p.KC * KHW > 4 * v.WI * v.NT()) return false;
+    p.w_row = pick_w_row(p.KC * KHW, KHW, 4);
   } else {
-    p.KC = 8;
+    p.KC = v.KC;
     while (p.KC > 4 && (p.BN * p.KC * KHW > v.WI * v.NT())) p.KC -= 4;
     if (p.BN * p.KC * KHW > v.WI * v.NT()) return false;
-    p.w_row = pick_w_row(p.KC * KHW, KHW);
+    p.w_row = pick_w_row(p.KC * KHW, KHW, 1);
   }
   p.cgrps = p.KC / CI;
   p.n_chunks = (p.Cg + p.KC - 1) / p.KC;
@@ -490,6 +580,7 @@ bool fill_params(const syno_plan* plan, int which, int vi, int TR, MfmaParams& p
   const int w_bytes = bf ? p.w_block * 2 : p.BN * p.w_row * 4;
   p.lds_tab_off = p.lds_w_off + ((w_bytes + 15) & ~15);
   p.lds_bytes = p.lds_tab_off + ((p.n_slots * 4 + 15) & ~15);
+  if (v.WK > 1) p.lds_bytes = std::max(p.lds_bytes, v.WM * v.WN * v.TM * v.TN * 1024);
   if (!bf && p.w_row * p.BN >= (1 << 20)) return false;
   return p.lds_bytes <= kMaxLdsBytes;
 }
@@ -503,32 +594,36 @@ double tile_cost(const MfmaParams& p, const Variant& v, const ConvLike& c, bool 
   const int MT = (std::min(p.TR, p.rows_total) * c.Wo + 15) / 16;
   const int base = MT / v.WM, extra = MT % v.WM;
   const double mfma_cycles = bf ? 16.0 : 32.0, read_cycles = bf ? 16.0 : 8.0;
-  double simd_mfma[4] = {0, 0, 0, 0}, simd_lds[4] = {0, 0, 0, 0};
-  for (int widx = 0; widx < v.WM * v.WN; ++widx) {
-    const int wn = widx / v.WM, wm = (widx + wn) % v.WM;
+  // per k-step of the chunk: cycles of matrix pipe and of step latency each SIMD sees, averaged over the
+  // waves that split the steps
+  double simd_mfma[4] = {0, 0, 0, 0}, simd_lat[4] = {0, 0, 0, 0};
+  for (int widx = 0; widx < v.WM * v.WN * v.WK; ++widx) {
+    const int wtile = widx % (v.WM * v.WN);
+    const int wn = wtile / v.WM, wm = (wtile + wn) % v.WM;
     const int tiles = base + (wm < extra ? 1 : 0);
     if (!tiles) continue;
-    simd_mfma[widx & 3] += mfma_cycles * tiles * v.TN;
-    simd_lds[widx & 3] += read_cycles * (tiles + v.TN) + 40.0;
+    simd_mfma[widx & 3] += mfma_cycles * tiles * v.TN / v.WK;
+    // a wave's step: address arithmetic, LDS round trip, then its MFMAs issue
+    simd_lat[widx & 3] += (200.0 + read_cycles * (tiles + v.TN)) / v.WK;
   }
   double step = 0;
-  for (int s = 0; s < 4; ++s) step = std::max(step, std::max(simd_mfma[s], simd_lds[s] + 60.0));
+  for (int s = 0; s < 4; ++s) step = std::max(step, std::max(simd_mfma[s], 0.5 * simd_lat[s] + 0.5 * simd_mfma[s]));
   const double steps = (double)p.n_chunks * (p.cgrps / (bf ? 4 : 1)) * c.KH * c.KW;
-  const double overhead = p.n_chunks * 3000.0 + 6000.0;
-  const int resident = std::max(1, std::min(2048 / v.NT(), (160 * 1024) / std::max(1, p.lds_bytes)));
+  const double overhead = p.n_chunks * 2500.0 + 6000.0 + (v.WK - 1) * 1500.0;
+  const int resident = 1;   // 8 waves of up to 256 VGPRs fill a CU's register file
   const double per_cu_wgs = std::ceil((double)wgs / kNumCU);
   return per_cu_wgs * steps * step + std::ceil(per_cu_wgs / resident) * overhead;
 }
 
 template <bool BF, int VI, bool OUTBF>
 void launch_variant(const MfmaParams& p, const void* X, const void* W, void* out, hipStream_t s) {
-  constexpr Variant v = BF ? kBf16Variants[VI] : kF32Variants[VI];
+  constexpr Variant v = BF ? kBf16Variants[VI % kNumBf16Variants] : kF32Variants[VI];
   const int grid = p.n_mblocks * p.n_nblocks * p.G;
-  auto kernel = conv_mfma<BF, v.WM, v.WN, v.TM, v.TN, v.XI, v.WI, OUTBF>;
+  auto kernel = conv_mfma<BF, v.wnat, v.WM, v.WN, v.WK, v.TM, v.TN, v.XI, v.WI, OUTBF>;
   static const hipError_t lds_opt_in =      // once per instantiation: allow more than the default 64 KB
       hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
   (void)lds_opt_in;
-  hipLaunchKernelGGL(kernel, dim3(grid), dim3(v.WM * v.WN * 64), p.lds_bytes, s, p, X, W, out);
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(v.NT()), p.lds_bytes, s, p, X, W, out);
 }
 
 template <bool BF, bool OUTBF>
@@ -536,7 +631,14 @@ void launch_dtype(int vi, const MfmaParams& p, const void* X, const void* W, voi
   switch (vi) {
     case 0: launch_variant<BF, 0, OUTBF>(p, X, W, out, s); break;
     case 1: launch_variant<BF, 1, OUTBF>(p, X, W, out, s); break;
-    default: launch_variant<BF, 2, OUTBF>(p, X, W, out, s); break;
+    case 2: launch_variant<BF, 2, OUTBF>(p, X, W, out, s); break;
+    case 3: launch_variant<BF, 3, OUTBF>(p, X, W, out, s); break;
+    case 4: launch_variant<BF, 4, OUTBF>(p, X, W, out, s); break;
+    case 5: launch_variant<BF, 5, OUTBF>(p, X, W, out, s); break;
+    case 6: if constexpr (!BF) launch_variant<BF, 6, OUTBF>(p, X, W, out, s); break;
+    case 7: if constexpr (!BF) launch_variant<BF, 7, OUTBF>(p, X, W, out, s); break;
+    case 8: if constexpr (!BF) launch_variant<BF, 8, OUTBF>(p, X, W, out, s); break;
+    default: break;
   }
 }
 
@@ -548,6 +650,7 @@ size_t packed_weight_bytes(const MfmaParams& p) {
 
 bool mfma_supports(const syno_plan* p, int which) {
   if (!p->conv_like || which == SYNO_BWD_WEIGHT) return false;
+  if (p->in_dtype == SYNO_F32 && p->out_dtype != SYNO_F32) return false;   // not instantiated
   const ConvLike& c = p->conv;
   if (c.sh != 1 || c.sw != 1 || c.w_wrap) return false;
   if (c.h_wrap && c.KH != 1) return false;
@@ -555,7 +658,7 @@ bool mfma_supports(const syno_plan* p, int which) {
   if (c.ph >= c.KH || c.pw >= c.KW) return false;
   if (c.Og == 1 && c.Cg == 1) return false;          // no contraction to speak of
   MfmaParams mp;
-  for (int vi = 0; vi < kNumVariants; ++vi)
+  for (int vi = 0; vi < num_variants(p->in_dtype == SYNO_BF16); ++vi)
     for (int TR = 1; TR <= c.N * c.Ho && TR * c.Wo <= 16 * 32; ++TR)
       if (fill_params(p, which, vi, TR, mp)) return true;
   return false;
@@ -575,7 +678,7 @@ void mfma_configure(syno_plan* plan, int which) {
     }
   }
   if (best_v < 0)
-    for (int vi = 0; vi < kNumVariants; ++vi)
+    for (int vi = 0; vi < num_variants(bf); ++vi)
       for (int TR = 1; TR <= c.N * c.Ho && TR * c.Wo <= 16 * 32; ++TR) {
         if (!fill_params(plan, which, vi, TR, mp)) continue;
         const double cost = tile_cost(mp, variant_of(bf, vi), c, bf);
@@ -592,8 +695,8 @@ std::string mfma_describe(const syno_plan* plan, int which) {
   if (!fill_params(plan, which, vi, TR, p)) return "unconfigured";
   const Variant& v = variant_of(plan->in_dtype == SYNO_BF16, vi);
   char b[256];
-  snprintf(b, sizeof b, "rows/block=%d BN=%d KC=%d waves=%dx%d grid=%d lds=%dB slots=%d", TR, v.BN(), p.KC, v.WM, v.WN,
-           p.n_mblocks * p.n_nblocks * p.G, p.lds_bytes, p.n_slots);
+  snprintf(b, sizeof b, "variant=%d rows/block=%d BN=%d KC=%d waves=%dx%dx%d grid=%d lds=%dB slots=%d", vi, TR, v.BN(),
+           p.KC, v.WM, v.WN, v.WK, p.n_mblocks * p.n_nblocks * p.G, p.lds_bytes, p.n_slots);
   return b;
 }
 
@@ -611,8 +714,8 @@ syno_status launch_mfma(const syno_plan* plan, int which, const void* A, const v
     if (obf) launch_dtype<true, true>(vi, p, A, ws, out, stream);
     else launch_dtype<true, false>(vi, p, A, ws, out, stream);
   } else {
-    if (obf) launch_dtype<false, true>(vi, p, A, B, out, stream);
-    else launch_dtype<false, false>(vi, p, A, B, out, stream);
+    if (obf) return SYNO_ERR_UNSUPPORTED;
+    launch_dtype<false, false>(vi, p, A, B, out, stream);
   }
   return hipGetLastError() == hipSuccess ? SYNO_OK : SYNO_ERR_HIP;
 }

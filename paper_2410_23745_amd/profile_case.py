@@ -1,0 +1,86 @@
+"""Run one workload a few times so that rocprofv3 can attribute kernel time and HBM counters to it.
+
+    rocprofv3 --kernel-trace --stats -- python3 -m paper_2410_23745_amd.profile_case config1_s0_f32 --iters 20
+    rocprofv3 --pmc FETCH_SIZE       -- python3 -m paper_2410_23745_amd.profile_case config1_s0_f32 --iters 5 --copy
+    rocprofv3 --pmc WRITE_SIZE       -- python3 -m paper_2410_23745_amd.profile_case config1_s0_f32 --iters 5 --copy
+
+With --copy a plain device copy of a known size (256 MiB, `Tensor.copy_`) runs first; what FETCH_SIZE and
+WRITE_SIZE report for it gives the factor that turns the counters into bytes.
+
+Cases: config0, config1_s{0..3}_{f32|bf16}, config2, config3, config4_{fwd|bwd_data|bwd_weight}.
+Buffers rotate over several copies so that every launch reads HBM rather than the last-level cache.
+"""
+from __future__ import annotations
+
+import argparse
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+sys.path.insert(0, ROOT)
+
+
+def make_case(name: str):
+    from syno_inputs import workloads as wl
+    which = 0
+    if name == "config0":
+        w = wl.config0()
+    elif name.startswith("config1_s"):
+        w = wl.config1(int(name[9]), name.endswith("bf16"))
+    elif name == "config2":
+        w = wl.config2()
+    elif name == "config3":
+        w = wl.config3()
+    elif name.startswith("config4_"):
+        w = wl.config4()
+        which = {"fwd": 0, "bwd_data": 1, "bwd_weight": 2}[name[8:]]
+    else:
+        raise SystemExit(f"unknown case {name}")
+    return w, which
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("case")
+    ap.add_argument("--iters", type=int, default=10)
+    ap.add_argument("--sets", type=int, default=6)
+    ap.add_argument("--copy", action="store_true")
+    args = ap.parse_args()
+    import numpy as np
+    import torch
+    import paper_2410_23745_amd as syno
+    from syno_inputs import BF16
+
+    syno.load_library()
+    dev = torch.device("cuda:0")
+    if args.copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+    w, which = make_case(args.case)
+
+    def dev_t(vals, bits):
+        if bits is not None:
+            return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
+        return torch.from_numpy(np.ascontiguousarray(vals, dtype=np.float32)).to(dev)
+
+    plan = syno.Plan(w.desc)
+    X, W = dev_t(w.X, w.X_bits), dev_t(w.W, w.W_bits)
+    G = dev_t(w.G, w.G_bits) if w.G is not None else None
+    a, b = ((X, W), (G, W), (X, G))[which]
+    fn = (plan.forward, plan.backward_data, plan.backward_weight)[which]
+    out_shape = (w.out_shape, w.x_shape, w.w_shape)[which]
+    out_dtype = torch.float32 if which == 2 else plan.out_dtype
+    sets = [(a.clone(), b.clone(), torch.empty(out_shape, dtype=out_dtype, device=dev)) for _ in range(args.sets)]
+    for i in range(args.iters):
+        s = sets[i % len(sets)]
+        fn(s[0], s[1], s[2])
+    torch.cuda.synchronize()
+    print(f"{args.case}: {plan.describe(which)}; {args.iters} launches")
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -132,6 +132,18 @@ def test_kernel_choice(syno):
     names = lambda d: [syno.Plan(d).kernel(i) for i in range(3)]
     assert all(n == "generic_index_program" for n in names(wl.matmul(3, 4, 5)))
     assert all(n == "generic_index_program" for n in names(pixel_unshuffle_conv()))
+    # the benchmarked workloads run on the tuned families, not on the index-program kernels
+    for stage in range(4):
+        C, H = wl.RESNET18_STAGES[stage]
+        assert names(wl.conv2d(32, C, C, H, H))[:2] == ["mfma_contraction_f32"] * 2
+        assert names(wl.conv2d(32, C, C, H, H, 3, 3, BF16, F32))[:2] == ["mfma_contraction_bf16"] * 2
+    assert names(wl.conv2d(1, 16, 16, 16, 16))[0] == "mfma_contraction_f32"
+    assert names(wl.grouped_shift_unfold(32)) == ["mfma_contraction_bf16"] * 3
+    assert names(wl.grouped_shift_unfold(128)) == ["mfma_contraction_bf16"] * 3
+    assert names(wl.strided_depthwise(64, 128, 28, 28))[0] == "bandwidth_depthwise"
+    p = syno.Plan(wl.grouped_shift_unfold(128))
+    assert p.workspace_bytes(syno.FWD) > 0 and p.workspace_bytes(syno.BWD_WEIGHT) > 0
+    assert "grid=" in p.describe(syno.FWD)
     syno.set_kernel_policy(1)
     try:
         assert all(n == "generic_index_program" for n in names(wl.strided_depthwise(2, 4, 7, 7)))

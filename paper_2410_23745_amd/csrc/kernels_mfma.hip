@@ -477,13 +477,13 @@ struct Variant {
 };
 // Tile variants, 8 waves each.  Row tiles x column tiles per wave, waves along M x N x K:
 //   fp32 0-2: any weight strides, 8 channels per chunk (the backward-data adjoint runs here)
-//   fp32 3-8: forward weight layout [o][c][kh][kw], 32 channels per chunk
+//   fp32 3-8: forward weight layout [o][c][kh][kw], 16 or 32 channels per chunk (what fits the registers)
 //   bf16 0-5: packed weights, 32 channels per chunk
 constexpr int kNumF32Variants = 9, kNumBf16Variants = 6;
 constexpr Variant kF32Variants[kNumF32Variants] = {
     {4, 2, 1, 7, 2, 3, 9, 8, false}, {4, 2, 1, 7, 1, 3, 5, 8, false}, {8, 1, 1, 4, 1, 3, 3, 8, false},
-    {4, 2, 1, 7, 2, 8, 9, 32, true}, {4, 1, 2, 7, 2, 8, 5, 32, true}, {2, 1, 4, 7, 2, 8, 5, 32, true},
-    {1, 1, 8, 4, 4, 8, 9, 32, true}, {4, 2, 1, 7, 1, 8, 5, 32, true}, {8, 1, 1, 4, 1, 8, 3, 32, true}};
+    {4, 2, 1, 7, 2, 4, 5, 16, true}, {4, 1, 2, 7, 2, 4, 3, 16, true}, {2, 1, 4, 7, 2, 4, 3, 16, true},
+    {1, 1, 8, 4, 4, 4, 5, 16, true}, {4, 2, 1, 7, 1, 8, 5, 32, true}, {8, 1, 1, 4, 1, 8, 3, 32, true}};
 constexpr Variant kBf16Variants[kNumBf16Variants] = {
     {4, 2, 1, 7, 2, 4, 6, 32, false}, {4, 1, 2, 7, 2, 4, 3, 32, false}, {2, 1, 4, 7, 2, 4, 3, 32, false},
     {1, 1, 8, 4, 4, 4, 6, 32, false}, {4, 2, 1, 7, 1, 4, 3, 32, false}, {8, 1, 1, 4, 1, 4, 2, 32, false}};

@@ -7,10 +7,13 @@
 //
 // Work layout.  A "strip" is a run of RB output rows of one (n,c) plane.  A group of LPG lanes
 // (a power of two) owns a strip; each lane owns V adjacent output columns and loads the S*V
-// input columns under them as one vector per input row.  The group walks down its strip keeping
-// the KH live input rows in registers and loading S new rows per output row, one output row
-// ahead of use.
+// input columns under them as one vector per input row.  All S*RB+KH-S input rows of the strip
+// are requested at once (one memory round trip), then the RB output rows are computed out of
+// registers.  The input rows a strip shares with the strip above it are taken from the group above
+// (same wave) with a shuffle instead of a second load.
 #include <hip/hip_runtime.h>
+
+#include <algorithm>
 
 #include "plan.h"
 
@@ -26,127 +29,133 @@ struct DwParams {
   int32_t vec_ok;         // rows start 16-byte aligned and Wi is a multiple of S*V
 };
 
-template <int KH, int KW, int S, int V>
+template <int KH, int KW, int S, int V, int RB>
 __global__ __launch_bounds__(256) void depthwise_stream(const DwParams p, const float* __restrict__ X,
                                                         const float* __restrict__ Wt, float* __restrict__ out) {
   constexpr int SV = S * V;                      // input columns a lane loads per row
-  constexpr int HL_MAX = KW / 2;                 // left neighbours needed (= pw)
+  constexpr int HL = KW / 2;                     // left neighbours needed (= pw)
   constexpr int HR = KW - KW / 2 - S > 0 ? KW - KW / 2 - S : 0;   // right neighbours needed
-  constexpr int WIN = HL_MAX + SV + HR;
-  static_assert(HL_MAX <= SV && HR <= SV, "neighbours must come from the adjacent lane only");
+  constexpr int WIN = HL + SV + HR;
+  constexpr int ROWS = S * RB + KH - S;          // input rows under a strip of RB output rows
+  static_assert(HL <= SV && HR <= SV, "neighbours must come from the adjacent lane only");
   static_assert(KH >= S, "row window shorter than the row step");
 
   const int lane = threadIdx.x & 63;
   const int lpg = 1 << p.lpg_log2;
   const int lig = lane & (lpg - 1);
+  const int grp = lane >> p.lpg_log2, gpw = 64 >> p.lpg_log2;   // group within the wave, groups per wave
   const int wave = (blockIdx.x * 256 + threadIdx.x) >> 6;
-  const int task = wave * (64 >> p.lpg_log2) + (lane >> p.lpg_log2);
-  const bool task_ok = task < p.n_tasks;
-  const int plane = task_ok ? task / p.strips : 0;
-  const int strip = task_ok ? task - plane * p.strips : 0;
-  const int h0 = strip * p.rb;
-  const int h1 = task_ok ? min(p.Ho, h0 + p.rb) : h0;
-  const int c = plane % p.C;
   const int x0 = lig * SV;                       // first input column this lane loads
   const int w0 = lig * V;                        // first output column this lane produces
-  const float* xp = X + (int64_t)plane * p.Hi * p.Wi;
-  float* op = out + (int64_t)plane * p.Ho * p.Wo;
+  constexpr int HALO = KH - S;                   // input rows a strip shares with the strip above it
 
-  float wk[KH][KW];
+  // Request every input row of task `task` (one independent load per row: the wave pays the memory
+  // latency once per strip).  Rows a strip shares with the strip above are not loaded when that strip
+  // belongs to the previous group of this wave; they are shuffled over afterwards.
+  auto request = [&](int task, float (&v)[ROWS][SV]) {
+    const bool task_ok = task < p.n_tasks;
+    const int plane = task_ok ? task / p.strips : 0;
+    const int strip = task_ok ? task - plane * p.strips : 0;
+    const float* xp = X + (int64_t)plane * p.Hi * p.Wi;
+    const int r0 = S * strip * RB - p.ph;
+    const bool col_ok = task_ok && x0 < p.Wi;
+    const bool from_prev = grp > 0 && strip > 0;
 #pragma unroll
-  for (int a = 0; a < KH; ++a)
-#pragma unroll
-    for (int b = 0; b < KW; ++b) wk[a][b] = Wt[c * p.ws_c + a * p.ws_kh + b * p.ws_kw];
-
-  // Load input row r of this lane's plane: its own SV columns; zero where outside.
-  auto load_row = [&](int r, float (&v)[SV]) {
-    const bool row_ok = task_ok && r >= 0 && r < p.Hi;
-    if (p.vec_ok && SV == 4) {
-      float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (row_ok && x0 < p.Wi) t = *reinterpret_cast<const float4*>(xp + (int64_t)r * p.Wi + x0);
-      v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
-    } else {
-#pragma unroll
-      for (int e = 0; e < SV; ++e) v[e] = (row_ok && x0 + e < p.Wi) ? xp[(int64_t)r * p.Wi + x0 + e] : 0.f;
-    }
-  };
-  // Complete a row window with the neighbours' edge columns (all lanes take part).
-  auto widen = [&](const float (&v)[SV], float (&win)[WIN]) {
-#pragma unroll
-    for (int j = 0; j < HL_MAX; ++j) {
-      const float t = __shfl_up(v[SV - HL_MAX + j], 1, 64);
-      win[j] = lig == 0 ? 0.f : t;
-    }
-#pragma unroll
-    for (int e = 0; e < SV; ++e) win[HL_MAX + e] = v[e];
-#pragma unroll
-    for (int j = 0; j < HR; ++j) {
-      const float t = __shfl_down(v[j], 1, 64);
-      win[HL_MAX + SV + j] = lig == lpg - 1 ? 0.f : t;
-    }
-  };
-
-  float rows[KH][WIN];
-  float nxt[S][SV];
-  // rows S.. of the first window, then the S rows that complete it arrive through `nxt`
-  {
-    const int r0 = S * h0 - p.ph;
-#pragma unroll
-    for (int a = S; a < KH; ++a) {
-      float v[SV];
-      load_row(r0 + a - S, v);
-      widen(v, rows[a]);
-    }
-#pragma unroll
-    for (int a = 0; a < S; ++a) load_row(r0 + KH - S + a, nxt[a]);
-  }
-  // every lane of the wave runs the same number of steps so that the shuffles stay uniform
-  const int steps = p.rb;
-  for (int i = 0; i < steps; ++i) {
-    const int h = h0 + i;
-    // slide the window down by S rows and append the rows loaded one step ago
-#pragma unroll
-    for (int a = 0; a < KH - S; ++a)
-#pragma unroll
-      for (int e = 0; e < WIN; ++e) rows[a][e] = rows[a + S][e];
-#pragma unroll
-    for (int a = 0; a < S; ++a) widen(nxt[a], rows[KH - S + a]);
-    // request the rows of the next step before computing this one
-    {
-      const int rn = S * (h + 1) - p.ph + KH - S;
-#pragma unroll
-      for (int a = 0; a < S; ++a) load_row(h + 1 < h1 ? rn + a : -1, nxt[a]);
-    }
-    float acc[V];
-#pragma unroll
-    for (int v = 0; v < V; ++v) {
-      acc[v] = 0.f;
-#pragma unroll
-      for (int a = 0; a < KH; ++a)
-#pragma unroll
-        for (int b = 0; b < KW; ++b) acc[v] = fmaf(wk[a][b], rows[a][HL_MAX - KW / 2 + S * v + b], acc[v]);
-    }
-    if (h < h1) {
-      float* o = op + (int64_t)h * p.Wo + w0;
-      if (V == 2 && (p.Wo & 1) == 0 && w0 + 1 < p.Wo) {
-        *reinterpret_cast<float2*>(o) = make_float2(acc[0], acc[1]);
-      } else if (V == 4 && (p.Wo & 3) == 0 && w0 + 3 < p.Wo) {
-        *reinterpret_cast<float4*>(o) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    for (int a = 0; a < ROWS; ++a) {
+      const int r = r0 + a;
+      const bool row_ok = col_ok && r >= 0 && r < p.Hi && !(a < HALO && from_prev);
+      if (p.vec_ok && SV == 4) {
+        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (row_ok) t = *reinterpret_cast<const float4*>(xp + (int64_t)r * p.Wi + x0);
+        v[a][0] = t.x; v[a][1] = t.y; v[a][2] = t.z; v[a][3] = t.w;
       } else {
 #pragma unroll
-        for (int v = 0; v < V; ++v)
-          if (w0 + v < p.Wo) o[v] = acc[v];
+        for (int e = 0; e < SV; ++e) v[a][e] = (row_ok && x0 + e < p.Wi) ? xp[(int64_t)r * p.Wi + x0 + e] : 0.f;
       }
     }
-  }
+  };
+  auto finish = [&](int task, float (&v)[ROWS][SV]) {
+    const bool task_ok = task < p.n_tasks;
+    const int plane = task_ok ? task / p.strips : 0;
+    const int strip = task_ok ? task - plane * p.strips : 0;
+    const int h0 = strip * RB;
+    const int c = plane % p.C;
+    float* op = out + (int64_t)plane * p.Ho * p.Wo;
+    const bool from_prev = grp > 0 && strip > 0;
+    // shared rows come from the group above (every lane takes part in the shuffles)
+#pragma unroll
+    for (int a = 0; a < HALO; ++a)
+#pragma unroll
+      for (int e = 0; e < SV; ++e) {
+        const float t = __shfl_up(v[ROWS - HALO + a][e], lpg, 64);
+        if (from_prev) v[a][e] = t;
+      }
+    float wk[KH][KW];
+#pragma unroll
+    for (int a = 0; a < KH; ++a)
+#pragma unroll
+      for (int b = 0; b < KW; ++b) wk[a][b] = Wt[c * p.ws_c + a * p.ws_kh + b * p.ws_kw];
+    // the window's horizontal neighbours come from the adjacent lanes
+    float left[ROWS][HL > 0 ? HL : 1], right[ROWS][HR > 0 ? HR : 1];
+#pragma unroll
+    for (int a = 0; a < ROWS; ++a) {
+#pragma unroll
+      for (int j = 0; j < HL; ++j) {
+        const float t = __shfl_up(v[a][SV - HL + j], 1, 64);
+        left[a][j] = lig == 0 ? 0.f : t;
+      }
+#pragma unroll
+      for (int j = 0; j < HR; ++j) {
+        const float t = __shfl_down(v[a][j], 1, 64);
+        right[a][j] = lig == lpg - 1 ? 0.f : t;
+      }
+    }
+    auto win = [&](int a, int i) -> float {      // column i of the widened row a (compile-time indices after unrolling)
+      return i < HL ? left[a][i] : (i < HL + SV ? v[a][i - HL] : right[a][i - HL - SV]);
+    };
+#pragma unroll
+    for (int i = 0; i < RB; ++i) {
+      const int h = h0 + i;
+      float acc[V];
+#pragma unroll
+      for (int o = 0; o < V; ++o) {
+        acc[o] = 0.f;
+#pragma unroll
+        for (int a = 0; a < KH; ++a)
+#pragma unroll
+          for (int b = 0; b < KW; ++b) acc[o] = fmaf(wk[a][b], win(S * i + a, S * o + b), acc[o]);
+      }
+      if (task_ok && h < p.Ho) {
+        float* o = op + (int64_t)h * p.Wo + w0;
+        if (V == 2 && (p.Wo & 1) == 0) {
+          if (w0 < p.Wo) *reinterpret_cast<float2*>(o) = make_float2(acc[0], acc[1]);
+        } else if (V == 4 && (p.Wo & 3) == 0) {
+          if (w0 < p.Wo) *reinterpret_cast<float4*>(o) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < V; ++e)
+            if (w0 + e < p.Wo) o[e] = acc[e];
+        }
+      }
+    }
+  };
+
+  // one strip per group; every lane of the wave runs both phases so that the shuffles stay uniform
+  float v[ROWS][SV];
+  const int task = wave * gpw + grp;
+  request(task, v);
+  finish(task, v);
+  (void)WIN;
 }
+
+constexpr int kStripRows = 7;   // output rows per strip: 15 input rows of a 3x3 stride-2 window in registers
 
 template <int KH, int KW, int S, int V>
 void launch_dw(const DwParams& p, const float* X, const float* W, float* out, hipStream_t s) {
   const int groups_per_wave = 64 >> p.lpg_log2;
   const int waves = (p.n_tasks + groups_per_wave - 1) / groups_per_wave;
   const int blocks = (waves + 3) / 4;
-  hipLaunchKernelGGL((depthwise_stream<KH, KW, S, V>), dim3(blocks), dim3(256), 0, s, p, X, W, out);
+  hipLaunchKernelGGL((depthwise_stream<KH, KW, S, V, kStripRows>), dim3(blocks), dim3(256), 0, s, p, X, W, out);
 }
 
 }  // namespace
@@ -176,11 +185,7 @@ syno_status launch_bandwidth(const syno_plan* plan, int which, const void* A, co
   const int lanes = (c.Wo + V - 1) / V;
   p.lpg_log2 = 0;
   while ((1 << p.lpg_log2) < lanes) ++p.lpg_log2;
-  // strips: enough waves to fill the chip (about 32 per CU) without making strips shorter than 4 rows
-  const int groups_per_wave = 64 >> p.lpg_log2;
-  int strips = 1;
-  while (strips * 2 <= c.Ho / 4 && (int64_t)p.planes * strips / groups_per_wave < 256 * 32) strips *= 2;
-  p.rb = (c.Ho + strips - 1) / strips;
+  p.rb = kStripRows;
   p.strips = (c.Ho + p.rb - 1) / p.rb;
   p.n_tasks = p.planes * p.strips;
   p.ws_c = c.ws_g; p.ws_kh = c.ws_kh; p.ws_kw = c.ws_kw;

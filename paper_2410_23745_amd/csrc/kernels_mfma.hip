@@ -46,12 +46,17 @@ struct MfmaParams {
   int32_t w_row;                      // LDS weight row pitch (elements)
   int32_t lds_w_off, lds_tab_off, lds_bytes;
   int32_t w_block;                    // bf16: elements of one packed weight block (KH*KW*BN*w_row)
+  // ceil(2^32/d) for the divisors the kernel needs (exact quotients for n*d < 2^32, which the host checks)
+  uint32_t m_wo, m_ho, m_wi, m_pcg, m_per_o, m_khw, m_kw;
 };
 
 namespace {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+// n / d through the precomputed m = ceil(2^32/d) (m = 0 stands for d = 1, whose constant does not fit)
+__device__ __forceinline__ int fdiv(int n, uint32_t m) { return m ? (int)__umulhi((uint32_t)n, m) : n; }
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   uint32_t u = __float_as_uint(f);
@@ -88,7 +93,7 @@ __device__ __forceinline__ int slot_source(const MfmaParams& p, int R0, int rows
 // First slot of output row i of the block (tap kh adds kh slots).
 __device__ __forceinline__ int slot_of_row(const MfmaParams& p, int R0, int i) {
   if (p.h_wrap) return i;
-  return i + (p.KH - 1) * ((R0 + i) / p.Ho - R0 / p.Ho);
+  return i + (p.KH - 1) * (fdiv(R0 + i, p.m_ho) - fdiv(R0, p.m_ho));
 }
 
 // bf16 only: W[g][o][c][kh][kw] (any strides) -> blocks [g][nb][chunk] of [tap][o_local][w_row] with the
@@ -167,8 +172,8 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
 #pragma unroll
     for (int k = 0; k < XI; ++k) {
       const int idx = tid + k * NT;
-      const int cg = idx / per_cg, rem = idx - cg * per_cg;
-      const int s = rem / p.Wi, x = rem - s * p.Wi;
+      const int cg = fdiv(idx, p.m_pcg), rem = idx - cg * per_cg;
+      const int s = fdiv(rem, p.m_wi), x = rem - s * p.Wi;
       const int src = idx < total ? slot_src[s] : -1;
       x_goff[k] = src >= 0 ? src + x + cg * CI * p.xs_c : -1;
       x_loff[k] = (cg * p.n_slots + s) * p.Wp + x + p.pw;
@@ -193,7 +198,7 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
 #pragma unroll
     for (int k = 0; k < WI; ++k) {
       const int idx = tid + k * NT;
-      const int o = idx / per_o4, e4 = idx - o * per_o4;
+      const int o = fdiv(idx, p.m_per_o), e4 = idx - o * per_o4;
       const bool ok = idx < total && nb * BN + o < p.Og;
       w_goff[k] = ok ? o * p.ws_o + e4 * 4 : -1;                 // element offset
       w_meta[k] = idx < total ? (o * p.w_row + e4 * 4) >> 2 : -1; // LDS float4 index
@@ -204,9 +209,9 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
 #pragma unroll
     for (int k = 0; k < WI; ++k) {
       const int idx = tid + k * NT;
-      const int o = idx / per_o, e = idx - o * per_o;
-      const int cl = e / KHW, tap = e - cl * KHW;
-      const int kh = tap / p.KW, kw = tap - kh * p.KW;
+      const int o = fdiv(idx, p.m_per_o), e = idx - o * per_o;
+      const int cl = fdiv(e, p.m_khw), tap = e - cl * KHW;
+      const int kh = fdiv(tap, p.m_kw), kw = tap - kh * p.KW;
       const bool ok = idx < total && nb * BN + o < p.Og;
       // tap strides may be negative (reversed taps of the adjoint), so validity lives in the meta word
       w_goff[k] = ok ? o * p.ws_o + cl * p.ws_c + kh * p.ws_kh + kw * p.ws_kw : 0;
@@ -225,7 +230,7 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
   for (int t = 0; t < TM; ++t) {
     int m = (my_first + t) * 16 + (lane & 15);
     if (t >= my_tiles || m >= block_px) m = 0;
-    const int i = m / p.Wo, w = m - i * p.Wo;
+    const int i = fdiv(m, p.m_wo), w = m - i * p.Wo;
     const int px = slot_of_row(p, R0, i) * p.Wp + w;
     a_base[t] = BF ? px + (lane >> 4) * cg_stride : px * 4 + (lane >> 4);
   }
@@ -250,15 +255,29 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
 
   XT xr[XI][CI];
   WReg wr[WI];
+  // Loads use a wave-uniform base plus 32-bit byte offsets.  Items without a source read offset 0 (any
+  // valid address) and are simply not written to LDS, so the common path has no per-load predicate.
+  const bool chan_tail = (p.Cg % p.KC) != 0;
+  const char* xbase = reinterpret_cast<const char*>(Xg);
   auto fetch = [&](int ch) {
     const int c0 = ch * p.KC;
+    if (!chan_tail) {
 #pragma unroll
-    for (int k = 0; k < XI; ++k)
+      for (int k = 0; k < XI; ++k) {
+        const uint32_t o = (uint32_t)(max(x_goff[k], 0) + c0 * p.xs_c) * (uint32_t)sizeof(XT);
 #pragma unroll
-      for (int j = 0; j < CI; ++j) {
-        const int c = c0 + x_cg[k] + j;
-        xr[k][j] = (x_goff[k] >= 0 && c < p.Cg) ? Xg[x_goff[k] + (int64_t)(c0 + j) * p.xs_c] : XT(0);
+        for (int j = 0; j < CI; ++j)
+          xr[k][j] = *reinterpret_cast<const XT*>(xbase + (o + (uint32_t)(j * p.xs_c) * (uint32_t)sizeof(XT)));
       }
+    } else {
+#pragma unroll
+      for (int k = 0; k < XI; ++k)
+#pragma unroll
+        for (int j = 0; j < CI; ++j) {
+          const int c = c0 + x_cg[k] + j;
+          xr[k][j] = (x_goff[k] >= 0 && c < p.Cg) ? Xg[x_goff[k] + (int64_t)(c0 + j) * p.xs_c] : XT(0);
+        }
+    }
     if constexpr (BF) {
       const uint4* src = Wg16 + (int64_t)ch * (p.w_block >> 3);
 #pragma unroll
@@ -413,8 +432,9 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
     for (int u = 0; u < TN; ++u) {
       const int o = nb * BN + (wn * TN + u) * 16 + (lane & 15);
       if (o >= p.Og || m0 >= block_px) continue;
-      const int mg = R0 * p.Wo + m0;
-      const int n = mg / img_px, px = mg - n * img_px;
+      // pixel m0 of the block -> (image, pixel inside the image)
+      const int i0 = fdiv(m0, p.m_wo), rho = R0 + i0;
+      const int n = fdiv(rho, p.m_ho), px = (rho - n * p.Ho) * p.Wo + (m0 - i0 * p.Wo);
       const int64_t off = (int64_t)n * p.os_n + (int64_t)(g * p.Og + o) * p.os_o + px;
       const bool together = m0 + 3 < block_px && px + 3 < img_px;
       if constexpr (OUTBF) {
@@ -428,8 +448,8 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
 #pragma unroll
           for (int j = 0; j < 4; ++j)
             if (m0 + j < block_px) {
-              const int mgj = mg + j, nj = mgj / img_px;
-              op[(int64_t)nj * p.os_n + (int64_t)(g * p.Og + o) * p.os_o + (mgj - nj * img_px)] =
+              const int ij = fdiv(m0 + j, p.m_wo), rj = R0 + ij, nj = fdiv(rj, p.m_ho);
+              op[(int64_t)nj * p.os_n + (int64_t)(g * p.Og + o) * p.os_o + (rj - nj * p.Ho) * p.Wo + (m0 + j - ij * p.Wo)] =
                   f32_to_bf16_rne(acc[t][u][j]);
             }
         }
@@ -441,8 +461,9 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
 #pragma unroll
           for (int j = 0; j < 4; ++j)
             if (m0 + j < block_px) {
-              const int mgj = mg + j, nj = mgj / img_px;
-              op[(int64_t)nj * p.os_n + (int64_t)(g * p.Og + o) * p.os_o + (mgj - nj * img_px)] = acc[t][u][j];
+              const int ij = fdiv(m0 + j, p.m_wo), rj = R0 + ij, nj = fdiv(rj, p.m_ho);
+              op[(int64_t)nj * p.os_n + (int64_t)(g * p.Og + o) * p.os_o + (rj - nj * p.Ho) * p.Wo + (m0 + j - ij * p.Wo)] =
+                  acc[t][u][j];
             }
         }
       }
@@ -521,6 +542,8 @@ bool fill_params(const syno_plan* plan, int which, int vi, int TR, MfmaParams& p
   const ConvLike& c = plan->conv;
   const bool bf = plan->in_dtype == SYNO_BF16;
   if (vi < 0 || vi >= num_variants(bf) || TR < 1) return false;
+  // the kernel addresses its source tensor with 32-bit byte offsets
+  if ((which == SYNO_FWD ? plan->x_elems : plan->out_elems) * (bf ? 2 : 4) >= (1ll << 32)) return false;
   const Variant& v = variant_of(bf, vi);
   p = MfmaParams{};
   p.G = c.G; p.Ho = c.Ho; p.Wo = c.Wo; p.Hi = c.Hi; p.Wi = c.Wi;
@@ -582,6 +605,15 @@ bool fill_params(const syno_plan* plan, int which, int vi, int TR, MfmaParams& p
   p.lds_bytes = p.lds_tab_off + ((p.n_slots * 4 + 15) & ~15);
   if (v.WK > 1) p.lds_bytes = std::max(p.lds_bytes, v.WM * v.WN * v.TM * v.TN * 1024);
   if (!bf && p.w_row * p.BN >= (1 << 20)) return false;
+  auto magic = [](int64_t d) { return (uint32_t)(((1ull << 32) + d - 1) / std::max<int64_t>(d, 1)); };
+  const int64_t per_cg = (int64_t)p.n_slots * c.Wi;
+  const int64_t per_o = bf ? 1 : (v.wnat ? (p.KC * KHW) >> 2 : p.KC * KHW);
+  // largest numerators: item indices (< XI*NT, WI*NT), pixels of a block (< 16*MT), output rows (< rows_total)
+  const int64_t max_idx = (int64_t)std::max(v.XI, v.WI) * v.NT();
+  if (max_idx * per_cg >= (1ll << 32) || max_idx * per_o >= (1ll << 32) || (int64_t)p.rows_total * c.Ho >= (1ll << 32))
+    return false;
+  p.m_wo = magic(c.Wo); p.m_ho = magic(c.Ho); p.m_wi = magic(c.Wi); p.m_pcg = magic(per_cg);
+  p.m_per_o = magic(per_o); p.m_khw = magic(KHW); p.m_kw = magic(c.KW);
   return p.lds_bytes <= kMaxLdsBytes;
 }
 

@@ -97,25 +97,31 @@ __device__ __forceinline__ int slot_of_row(const MfmaParams& p, int R0, int i) {
 }
 
 // bf16 only: W[g][o][c][kh][kw] (any strides) -> blocks [g][nb][chunk] of [tap][o_local][w_row] with the
-// channel innermost; rows beyond Og / Cg and the row padding are zero.
+// channel innermost; rows beyond Og / Cg and the row padding are zero.  One thread gathers the 8
+// channels of one 16-byte piece.
 __global__ __launch_bounds__(256) void pack_weight_bf16(const MfmaParams p, const uint16_t* __restrict__ Wt,
-                                                        uint16_t* __restrict__ packed, int64_t total) {
+                                                        uint4* __restrict__ packed, int64_t pieces) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= total) return;
-  const int KHW = p.KH * p.KW;
+  if (i >= pieces) return;
+  const int KHW = p.KH * p.KW, row8 = p.w_row >> 3;
   int64_t r = i;
-  const int cl = (int)(r % p.w_row); r /= p.w_row;
+  const int cq = (int)(r % row8); r /= row8;
   const int ol = (int)(r % p.BN); r /= p.BN;
   const int tap = (int)(r % KHW); r /= KHW;
   const int ch = (int)(r % p.n_chunks); r /= p.n_chunks;
   const int nb = (int)(r % p.n_nblocks);
   const int g = (int)(r / p.n_nblocks);
-  const int o = nb * p.BN + ol, c = ch * p.KC + cl;
+  const int o = nb * p.BN + ol, cl0 = cq * 8, c0 = ch * p.KC + cl0;
   const int kh = tap / p.KW, kw = tap - kh * p.KW;
-  uint16_t v = 0;
-  if (cl < p.KC && o < p.Og && c < p.Cg)
-    v = Wt[p.w_base + (int64_t)g * p.ws_g + (int64_t)o * p.ws_o + (int64_t)c * p.ws_c + kh * p.ws_kh + kw * p.ws_kw];
-  packed[i] = v;
+  uint32_t v[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    v[e] = 0;
+    if (cl0 + e < p.KC && o < p.Og && c0 + e < p.Cg)
+      v[e] = Wt[p.w_base + (int64_t)g * p.ws_g + (int64_t)o * p.ws_o + (int64_t)(c0 + e) * p.ws_c + kh * p.ws_kh +
+                kw * p.ws_kw];
+  }
+  packed[i] = make_uint4(v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16));
 }
 
 // BF = false: fp32 inputs, CI = 4, v_mfma_f32_16x16x4_f32  (A: lane -> row l%16, k = l/16).
@@ -126,7 +132,7 @@ __global__ __launch_bounds__(256) void pack_weight_bf16(const MfmaParams p, cons
 // WK:  waves that share one output tile and split each chunk's k-steps among themselves (for shapes whose
 //      per-SIMD share of the output is only a few MFMA tiles: a wave then still issues TM*TN MFMAs per
 //      LDS round trip); their accumulators are added through LDS at the end.
-template <bool BF, bool WNAT, int WM, int WN, int WK, int TM, int TN, int XI, int WI, bool OUTBF>
+template <bool BF, bool WNAT, int WM, int WN, int WK, int TM, int TN, int XI, int WI, bool ONE, bool OUTBF>
 __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p, const void* __restrict__ Xv,
                                                          const void* __restrict__ Wv, void* __restrict__ out) {
   constexpr int NT = WM * WN * WK * 64;
@@ -329,12 +335,14 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
     }
   };
 
+  // ONE: the whole reduction fits one chunk, so the staging registers are dead once it is in LDS
+  const int n_chunks = ONE ? 1 : p.n_chunks;
   fetch(0);
-  for (int ch = 0; ch < p.n_chunks; ++ch) {
+  for (int ch = 0; ch < n_chunks; ++ch) {
     __syncthreads();   // everyone has finished reading the previous chunk
     stage();
     __syncthreads();
-    if (ch + 1 < p.n_chunks) fetch(ch + 1);   // next chunk travels while this one is computed
+    if (ch + 1 < n_chunks) fetch(ch + 1);   // next chunk travels while this one is computed
     // One k-step = CI*CG_STEP channels at one tap.  Fragments of step i+1 are read from LDS while the
     // MFMAs of step i issue.  The tile count is a compile-time constant per case so that the MFMA
     // block is straight-line code.
@@ -492,6 +500,7 @@ struct Variant {
   int WM, WN, WK, TM, TN, XI, WI;
   int KC;        // channels per chunk (fp32 variants may fall back to smaller multiples)
   bool wnat;     // fp32: contiguous weight rows staged in 16-byte pieces
+  bool one;      // only for reductions that fit a single chunk (nothing is prefetched during the MFMAs)
   constexpr int NT() const { return WM * WN * WK * 64; }
   constexpr int BN() const { return WN * TN * 16; }
   constexpr int MT() const { return WM * TM; }
@@ -500,16 +509,18 @@ struct Variant {
 //   fp32 0-2: any weight strides, 8 channels per chunk (the backward-data adjoint runs here)
 //   fp32 3-8: forward weight layout [o][c][kh][kw], 16 or 32 channels per chunk (what fits the registers)
 //   bf16 0-5: packed weights, 32 channels per chunk
-constexpr int kNumF32Variants = 9, kNumBf16Variants = 6;
+//   bf16 6:   packed weights, at most 64 channels per group, staged in one go
+constexpr int kNumF32Variants = 9, kNumBf16Variants = 7;
 constexpr Variant kF32Variants[kNumF32Variants] = {
     {4, 2, 1, 7, 2, 3, 9, 8, false}, {4, 2, 1, 7, 1, 3, 5, 8, false}, {8, 1, 1, 4, 1, 3, 3, 8, false},
     {4, 2, 1, 7, 2, 4, 5, 16, true}, {4, 1, 2, 7, 2, 4, 3, 16, true}, {2, 1, 4, 7, 2, 4, 3, 16, true},
     {1, 1, 8, 4, 4, 4, 5, 16, true}, {4, 2, 1, 7, 1, 8, 5, 32, true}, {8, 1, 1, 4, 1, 8, 3, 32, true}};
 constexpr Variant kBf16Variants[kNumBf16Variants] = {
     {4, 2, 1, 7, 2, 4, 6, 32, false}, {4, 1, 2, 7, 2, 4, 3, 32, false}, {2, 1, 4, 7, 2, 4, 3, 32, false},
-    {1, 1, 8, 4, 4, 4, 6, 32, false}, {4, 2, 1, 7, 1, 4, 3, 32, false}, {8, 1, 1, 4, 1, 4, 2, 32, false}};
+    {1, 1, 8, 4, 4, 4, 6, 32, false}, {4, 2, 1, 7, 1, 4, 3, 32, false}, {8, 1, 1, 4, 1, 4, 2, 32, false},
+    {4, 2, 1, 7, 2, 8, 11, 64, false, true}};
 constexpr int kNumCU = 256;
-constexpr int kMaxLdsBytes = 144 * 1024;   // of the 160 KB a CU has
+constexpr int kMaxLdsBytes = 160 * 1024;   // all of a CU's LDS
 
 int num_variants(bool bf) { return bf ? kNumBf16Variants : kNumF32Variants; }
 const Variant& variant_of(bool bf, int vi) { return bf ? kBf16Variants[vi] : kF32Variants[vi]; }
@@ -571,8 +582,9 @@ bool fill_params(const syno_plan* plan, int which, int vi, int TR, MfmaParams& p
   const int KHW = c.KH * c.KW;
   const int CI = bf ? 8 : 4;
   if (bf) {
-    p.KC = 32;
-    p.w_row = p.KC + 8;                          // elements; 80-byte rows keep B-fragment reads conflict free
+    p.KC = v.KC;
+    if (v.one && p.Cg > p.KC) return false;
+    p.w_row = p.KC + 8;                          // elements; 80- and 144-byte rows keep B-fragment reads conflict free
     p.w_block = KHW * p.BN * p.w_row;
     if ((p.w_block >> 3) > v.WI * v.NT()) return false;
   } else if (v.wnat) {
@@ -651,7 +663,7 @@ template <bool BF, int VI, bool OUTBF>
 void launch_variant(const MfmaParams& p, const void* X, const void* W, void* out, hipStream_t s) {
   constexpr Variant v = BF ? kBf16Variants[VI % kNumBf16Variants] : kF32Variants[VI];
   const int grid = p.n_mblocks * p.n_nblocks * p.G;
-  auto kernel = conv_mfma<BF, v.wnat, v.WM, v.WN, v.WK, v.TM, v.TN, v.XI, v.WI, OUTBF>;
+  auto kernel = conv_mfma<BF, v.wnat, v.WM, v.WN, v.WK, v.TM, v.TN, v.XI, v.WI, v.one, OUTBF>;
   static const hipError_t lds_opt_in =      // once per instantiation: allow more than the default 64 KB
       hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
   (void)lds_opt_in;
@@ -667,7 +679,7 @@ void launch_dtype(int vi, const MfmaParams& p, const void* X, const void* W, voi
     case 3: launch_variant<BF, 3, OUTBF>(p, X, W, out, s); break;
     case 4: launch_variant<BF, 4, OUTBF>(p, X, W, out, s); break;
     case 5: launch_variant<BF, 5, OUTBF>(p, X, W, out, s); break;
-    case 6: if constexpr (!BF) launch_variant<BF, 6, OUTBF>(p, X, W, out, s); break;
+    case 6: launch_variant<BF, 6, OUTBF>(p, X, W, out, s); break;
     case 7: if constexpr (!BF) launch_variant<BF, 7, OUTBF>(p, X, W, out, s); break;
     case 8: if constexpr (!BF) launch_variant<BF, 8, OUTBF>(p, X, W, out, s); break;
     default: break;
@@ -740,9 +752,9 @@ syno_status launch_mfma(const syno_plan* plan, int which, const void* A, const v
   const bool obf = plan->out_dtype == SYNO_BF16;
   if (plan->in_dtype == SYNO_BF16) {
     if (!ws) return SYNO_ERR_WORKSPACE;
-    const int64_t total = (int64_t)packed_weight_bytes(p) / 2;
-    hipLaunchKernelGGL(pack_weight_bf16, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, p,
-                       static_cast<const uint16_t*>(B), static_cast<uint16_t*>(ws), total);
+    const int64_t pieces = (int64_t)packed_weight_bytes(p) / 16;
+    hipLaunchKernelGGL(pack_weight_bf16, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, stream, p,
+                       static_cast<const uint16_t*>(B), static_cast<uint4*>(ws), pieces);
     if (obf) launch_dtype<true, true>(vi, p, A, ws, out, stream);
     else launch_dtype<true, false>(vi, p, A, ws, out, stream);
   } else {

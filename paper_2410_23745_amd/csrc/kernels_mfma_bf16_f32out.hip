@@ -1,0 +1,16 @@
+// Instantiations of the MFMA contraction kernel: bf16 tile variants, fp32 result.
+#include "conv_mfma.h"
+
+namespace syno {
+
+void launch_mfma_bf16_f32out(int vi, const MfmaParams& p, const void* X, const void* W, void* out, hipStream_t s) {
+#define SYNO_CASE(VI) \
+  case VI: launch_variant<true, VI, 1, false>(p, X, W, out, s); break;
+  switch (vi) {
+    SYNO_CASE(0) SYNO_CASE(1) SYNO_CASE(2) SYNO_CASE(3) SYNO_CASE(4) SYNO_CASE(5) SYNO_CASE(6) SYNO_CASE(7) SYNO_CASE(8)
+    default: break;
+  }
+#undef SYNO_CASE
+}
+
+}  // namespace syno

@@ -75,6 +75,9 @@ struct Launch {
   int32_t coop = 0;           // generic kernel: one workgroup per target (1) or one lane per target (0)
   int32_t variant = 0;        // tile configuration index within the family
   size_t workspace = 0;
+  // the family's kernel parameter record, filled when the plan is configured so that a launch only copies it
+  alignas(8) unsigned char params[384] = {};
+  bool params_ready = false;
 };
 
 }  // namespace syno

@@ -158,15 +158,19 @@ def main() -> int:
     roofline["kernel"] = f"{dom_key[0]}[{dom_key[1]}]"
     roofline["avg_launch_us"] = dom_ms * 1e3
     roofline["launches_averaged"] = [c.name for c in dom]
-    # HBM traffic per launch comes from stored rocprofv3 --pmc runs (profiles/traffic.json) and only counts
-    # while the kernel source they were taken on is unchanged
+    # HBM traffic per launch comes from stored rocprofv3 --pmc runs (the record at the end of
+    # profiles/hbm_traffic_all_workloads.txt) and only counts while the kernel sources it was taken on are unchanged
     try:
         import hashlib
-        rec = json.load(open(os.path.join(ROOT, "profiles", "traffic.json")))
-        srcs = [os.path.join(ROOT, "paper_2410_23745_amd", "csrc", f) for f in rec["sources"]]
+        rec = {}
+        for line in open(os.path.join(ROOT, "profiles", "hbm_traffic_all_workloads.txt")):
+            key, sep, val = line.partition(":")
+            if sep and key in ("kernel", "hbm_bytes_per_launch", "sources", "sha256"):
+                rec[key] = val.split("(")[0].strip() if key == "hbm_bytes_per_launch" else val.strip()
+        srcs = [os.path.join(ROOT, "paper_2410_23745_amd", "csrc", f) for f in rec["sources"].split()]
         digest = hashlib.sha256(b"".join(open(f, "rb").read() for f in srcs)).hexdigest()
         if digest == rec["sha256"] and rec["kernel"] == roofline["kernel"]:
-            roofline["traffic"] = rec["hbm_bytes_per_launch"]
+            roofline["traffic"] = float(rec["hbm_bytes_per_launch"])
     except (OSError, KeyError, ValueError):
         pass
 

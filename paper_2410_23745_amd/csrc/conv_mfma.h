@@ -109,7 +109,9 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
   const int widx = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in an SGPR
   const int wk = widx / (WM * WN), wtile = widx - wk * (WM * WN);
   const int wn = wtile / WM;
-  const int wm = (wtile + wn) % WM;         // spread the fuller wave rows over the SIMDs
+  // wave widx runs on SIMD widx % 4: rotate the wave rows so that the fuller ones spread over the SIMDs,
+  // also among the waves that split K
+  const int wm = (wtile + wn + ((wk * WM * WN) >> 2)) % WM;
   int bid = blockIdx.x;
   const int nb = bid % p.n_nblocks; bid /= p.n_nblocks;
   const int mb = bid % p.n_mblocks;
@@ -474,14 +476,14 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
 #pragma unroll
         for (int t = 0; t < NTL; ++t)
 #pragma unroll
-          for (int u = 0; u < TN; ++u) red[((wtile * TM + t) * TN + u) * 64 + lane] = acc[t][u];
+          for (int u = 0; u < TN; ++u) red[(((wn * WM + wm) * TM + t) * TN + u) * 64 + lane] = acc[t][u];
       }
       __syncthreads();
       if (wk == 0) {
 #pragma unroll
         for (int t = 0; t < NTL; ++t)
 #pragma unroll
-          for (int u = 0; u < TN; ++u) acc[t][u] += red[((wtile * TM + t) * TN + u) * 64 + lane];
+          for (int u = 0; u < TN; ++u) acc[t][u] += red[(((wn * WM + wm) * TM + t) * TN + u) * 64 + lane];
       }
     }
     if (wk != 0) return;

@@ -194,7 +194,8 @@ double tile_cost(const MfmaParams& p, const Variant& v, const ConvLike& c, bool 
   double simd_mfma[4] = {0, 0, 0, 0}, simd_lat[4] = {0, 0, 0, 0};
   for (int widx = 0; widx < v.WM * v.WN * v.WK; ++widx) {
     const int wtile = widx % (v.WM * v.WN);
-    const int wn = wtile / v.WM, wm = (wtile + wn) % v.WM;
+    const int wk = widx / (v.WM * v.WN);
+    const int wn = wtile / v.WM, wm = (wtile + wn + ((wk * v.WM * v.WN) >> 2)) % v.WM;
     const int tiles = base + (wm < extra ? 1 : 0);
     if (!tiles) continue;
     simd_mfma[widx & 3] += mfma_cycles * tiles * v.TN / v.WK;

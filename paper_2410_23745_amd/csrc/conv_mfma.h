@@ -26,6 +26,7 @@ struct MfmaParams {
   int32_t w_block;                    // bf16: elements of one packed weight block (KH*KW*BN*w_row)
   // ceil(2^32/d) for the divisors the kernel needs (exact quotients for n*d < 2^32, which the host checks)
   uint32_t m_wo, m_ho, m_vpr, m_pcg, m_per_o, m_khw, m_kw;
+  int32_t wf;                         // bf16 single-chunk variant: taps per channel when the weights are read unpacked, else 0
   int32_t U;                          // window taps along w per row-step (selects the instantiation)
 };
 
@@ -84,12 +85,14 @@ __device__ __forceinline__ int slot_of_row(const MfmaParams& p, int R0, int i) {
 // WNAT (fp32 only): the weight block of one output channel, [KC][KH][KW], is contiguous and 16-byte
 //             aligned in memory, so it is staged with 16-byte loads instead of element by element.
 // KCB: bf16 only: channels per chunk (a compile-time constant there, since it fixes the tap offsets in LDS)
+// WF:  bf16 single-chunk variant only: > 0 = the weights are read as they lie in memory ([o][c][WF taps], the
+//      forward layout) and re-ordered on their way into LDS, instead of coming from the packed copy
 // U:   window taps along w handled per "row-step" (3 when KW = 3, else 1): the operands of the U taps sit at
 //      compile-time LDS offsets from one per-lane address, so addresses advance once per row-step.
 // WK:  waves that share one output tile and split each chunk's k-steps among themselves (for shapes whose
 //      per-SIMD share of the output is only a few MFMA tiles: a wave then still issues TM*TN MFMAs per
 //      LDS round trip); their accumulators are added through LDS at the end.
-template <bool BF, bool WNAT, int WM, int WN, int WK, int TM, int TN, int XI, int WI, bool ONE, int KCB, int U, bool OUTBF>
+template <bool BF, bool WNAT, int WM, int WN, int WK, int TM, int TN, int XI, int WI, bool ONE, int KCB, int U, int WF, bool OUTBF>
 __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p, const void* __restrict__ Xv,
                                                          const void* __restrict__ Wv, void* __restrict__ out) {
   constexpr int NT = WM * WN * WK * 64;
@@ -151,7 +154,9 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
   const uint4* Wg16 = nullptr;
   // fp32: one weight element per item, gathered with the operator's strides into [o][c*KHW+tap].
   // bf16: 16-byte pieces of this block's packed image, copied as they are.
-  if constexpr (BF) {
+  if constexpr (BF && WF != 0) {
+    // (nothing per chunk: the block is brought in once, below)
+  } else if constexpr (BF) {
     Wg16 = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(Wv) +
                                           ((int64_t)(g * p.n_nblocks + nb) * p.n_chunks) * p.w_block);
     const int units = p.w_block >> 3;
@@ -267,7 +272,8 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
           }
         }
     }
-    if constexpr (BF) {
+    if constexpr (BF && WF != 0) {
+    } else if constexpr (BF) {
       const uint4* src = Wg16 + (int64_t)ch * (p.w_block >> 3);
 #pragma unroll
       for (int k = 0; k < WI; ++k)
@@ -317,7 +323,8 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
           (void)dst;
         }
       }
-    if constexpr (BF) {
+    if constexpr (BF && WF != 0) {
+    } else if constexpr (BF) {
       uint4* wl = reinterpret_cast<uint4*>(smem + p.lds_w_off);
 #pragma unroll
       for (int k = 0; k < WI; ++k)
@@ -338,6 +345,68 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
   // ONE: the whole reduction fits one chunk, so the staging registers are dead once it is in LDS
   const int n_chunks = ONE ? 1 : p.n_chunks;
   fetch(0, std::integral_constant<int, -1>{});
+  if constexpr (BF && WF > 0) {
+    // Weights straight from [o][c][tap]: a thread takes 8 channels x WF taps of one output channel (8*WF
+    // adjacent elements = WF 16-byte loads), re-orders them in registers into one 16-byte piece per tap
+    // (8 channels each) and writes those to [tap][o][c].  Runs while the X requests above are in flight.
+    static_assert(ONE, "only the single-chunk variant stages weights this way");
+    typedef uint32_t u32x4_unaligned __attribute__((ext_vector_type(4), aligned(2)));
+    constexpr int OCT = KCB / 8, ROW8 = (KCB + 8) / 8;
+    const uint16_t* Wt = reinterpret_cast<const uint16_t*>(Wv) + (int64_t)g * p.ws_g + (int64_t)nb * BN * p.ws_o;
+    uint4* wl = reinterpret_cast<uint4*>(smem + p.lds_w_off);
+    for (int i = tid; i < BN * OCT; i += NT) {
+      const int octet = i % OCT, ol = i / OCT;
+      const bool live = nb * BN + ol < p.Og && octet * 8 < p.Cg;
+      uint32_t in[4 * WF];
+#pragma unroll
+      for (int q = 0; q < WF; ++q) {
+        u32x4_unaligned v = {0, 0, 0, 0};
+        if (live) v = *reinterpret_cast<const u32x4_unaligned*>(Wt + (int64_t)ol * p.ws_o + octet * 8 * WF + q * 8);
+        in[4 * q + 0] = v[0]; in[4 * q + 1] = v[1]; in[4 * q + 2] = v[2]; in[4 * q + 3] = v[3];
+      }
+#pragma unroll
+      for (int tap = 0; tap < WF; ++tap) {
+        uint32_t d[4];
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+          // channels 2h and 2h+1 of this tap: elements (2h)*WF+tap and (2h+1)*WF+tap of the 8*WF loaded ones
+          const int e0 = (2 * h) * WF + tap, e1 = (2 * h + 1) * WF + tap;
+          const uint32_t sel = ((e0 & 1) ? 0x0302u : 0x0100u) | ((e1 & 1) ? 0x07060000u : 0x05040000u);
+          d[h] = __builtin_amdgcn_perm(in[e1 >> 1], in[e0 >> 1], sel);
+        }
+        wl[(tap * BN + ol) * ROW8 + octet] = make_uint4(d[0], d[1], d[2], d[3]);
+      }
+    }
+  }
+  if constexpr (BF && WF < 0) {
+    // The same for the backward-data adjoint: the B operand's rows are the forward input channels and its
+    // reduction runs over the forward output channels, taps reversed.  A thread again loads 8 channels x
+    // T taps of one forward output channel o, but each element goes to its own row: [T-1-tap][c][o].
+    static_assert(ONE, "only the single-chunk variant stages weights this way");
+    typedef uint32_t u32x4_unaligned __attribute__((ext_vector_type(4), aligned(2)));
+    constexpr int T = -WF, OCT = BN / 8, ROW = KCB + 8;
+    // (p.ws_o is the forward channel stride = T, p.ws_c the forward output-channel stride)
+    const uint16_t* Wt = reinterpret_cast<const uint16_t*>(Wv) + (int64_t)g * p.ws_g + (int64_t)nb * BN * T;
+    uint16_t* wl = reinterpret_cast<uint16_t*>(smem + p.lds_w_off);
+    for (int i = tid; i < KCB * OCT; i += NT) {
+      const int octet = i % OCT, o = i / OCT;
+      const bool live = o < p.Cg && nb * BN + octet * 8 < p.Og;
+      uint32_t in[4 * T];
+#pragma unroll
+      for (int q = 0; q < T; ++q) {
+        u32x4_unaligned v = {0, 0, 0, 0};
+        if (live) v = *reinterpret_cast<const u32x4_unaligned*>(Wt + (int64_t)o * p.ws_c + octet * 8 * T + q * 8);
+        in[4 * q + 0] = v[0]; in[4 * q + 1] = v[1]; in[4 * q + 2] = v[2]; in[4 * q + 3] = v[3];
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int tap = 0; tap < T; ++tap) {
+          const int e = j * T + tap;
+          wl[((T - 1 - tap) * BN + octet * 8 + j) * ROW + o] = (uint16_t)((e & 1) ? in[e >> 1] >> 16 : in[e >> 1]);
+        }
+    }
+  }
   for (int ch = 0; ch < n_chunks; ++ch) {
     __syncthreads();   // everyone has finished reading the previous chunk
     stage();
@@ -567,25 +636,26 @@ struct Variant {
 //   fp32 0-2:  any weight strides, 8 channels per chunk (the backward-data adjoint runs here)
 //   fp32 3-8:  forward weight layout [o][c][kh][kw], 16 or 32 channels per chunk (what fits the registers)
 //   fp32 9-10: as 4 and 5 with up to 32 channels per chunk (half as many chunk round trips)
+//   fp32 11:   64 output channels like 3, half its rows, K split over two waves
 //   bf16 0-5:  packed weights, 32 channels per chunk
 //   bf16 6:    packed weights, at most 64 channels per group, staged in one go
 //   bf16 7-8:  as 1 and 2 with 64 channels per chunk
-constexpr int kNumF32Variants = 11, kNumBf16Variants = 9;
+constexpr int kNumF32Variants = 12, kNumBf16Variants = 9;
 constexpr Variant kF32Variants[kNumF32Variants] = {
     {4, 2, 1, 7, 2, 1, 9, 8, false}, {4, 2, 1, 7, 1, 1, 5, 8, false}, {8, 1, 1, 4, 1, 1, 3, 8, false},
     {4, 2, 1, 7, 2, 1, 5, 16, true}, {4, 1, 2, 7, 2, 1, 3, 16, true}, {2, 1, 4, 7, 2, 1, 3, 16, true},
     {1, 1, 8, 4, 4, 1, 5, 16, true}, {4, 2, 1, 7, 1, 2, 5, 32, true}, {8, 1, 1, 4, 1, 2, 3, 32, true},
-    {4, 1, 2, 7, 2, 1, 5, 32, true}, {2, 1, 4, 7, 2, 1, 5, 32, true}};
+    {4, 1, 2, 7, 2, 1, 5, 32, true}, {2, 1, 4, 7, 2, 1, 5, 32, true}, {2, 2, 2, 7, 2, 1, 5, 16, true}};
 constexpr Variant kBf16Variants[kNumBf16Variants] = {
     {4, 2, 1, 7, 2, 1, 6, 32, false}, {4, 1, 2, 7, 2, 1, 3, 32, false}, {2, 1, 4, 7, 2, 1, 3, 32, false},
     {1, 1, 8, 4, 4, 1, 6, 32, false}, {4, 2, 1, 7, 1, 2, 3, 32, false}, {8, 1, 1, 4, 1, 2, 2, 32, false},
     {4, 2, 1, 7, 2, 4, 11, 64, false, true}, {4, 1, 2, 7, 2, 1, 6, 64, false}, {2, 1, 4, 7, 2, 1, 6, 64, false}};
 
-template <bool BF, int VI, int U, bool OUTBF>
+template <bool BF, int VI, int U, int WF, bool OUTBF>
 void launch_variant(const MfmaParams& p, const void* X, const void* W, void* out, hipStream_t s) {
   constexpr Variant v = BF ? kBf16Variants[VI % kNumBf16Variants] : kF32Variants[VI % kNumF32Variants];
   const int grid = p.n_mblocks * p.n_nblocks * p.G;
-  auto kernel = conv_mfma<BF, v.wnat, v.WM, v.WN, v.WK, v.TM, v.TN, v.XI, v.WI, v.one, (BF ? v.KC : 0), U, OUTBF>;
+  auto kernel = conv_mfma<BF, v.wnat, v.WM, v.WN, v.WK, v.TM, v.TN, v.XI, v.WI, v.one, (BF ? v.KC : 0), U, WF, OUTBF>;
   static const hipError_t lds_opt_in =      // once per instantiation: allow more than the default 64 KB
       hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
   (void)lds_opt_in;

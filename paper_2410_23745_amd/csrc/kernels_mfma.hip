@@ -134,6 +134,11 @@ bool fill_params(const syno_plan* plan, int which, int vi, int TR, MfmaParams& p
     p.w_row = p.KC + 8;                          // elements; 80- and 144-byte rows keep B-fragment reads conflict free
     p.w_block = KHW * p.BN * p.w_row;
     if ((p.w_block >> 3) > v.WI * v.NT()) return false;
+    // the single-chunk variant takes forward-layout weights [o][c][taps] unpacked when the taps are 1, 3 or 9
+    // (backward-data: the same tensor read through the adjoint, marked by a negative count)
+    const bool fwd_layout = (c.KW == 1 || c.ws_kw == 1) && (c.KH == 1 || c.ws_kh == c.KW) && c.ws_c == KHW;
+    if (v.one && fwd_layout && (c.Cg & 7) == 0 && (KHW == 1 || KHW == 3 || KHW == 9))
+      p.wf = which == SYNO_FWD ? KHW : -KHW;
   } else if (v.wnat) {
     if (which != SYNO_FWD || c.ws_kw != 1 || c.ws_kh != c.KW || c.ws_c != KHW || (c.ws_o & 3) || (c.ws_g & 3))
       return false;
@@ -261,7 +266,7 @@ void mfma_configure(syno_plan* plan, int which) {
   memcpy(plan->launch[which].params, &mp, sizeof mp);
   plan->launch[which].params_ready = true;
   plan->launch[which].variant = best_v * 4096 + best_tr;
-  plan->launch[which].workspace = bf ? packed_weight_bytes(mp) : 0;
+  plan->launch[which].workspace = (bf && mp.wf == 0) ? packed_weight_bytes(mp) : 0;
 }
 
 std::string mfma_describe(const syno_plan* plan, int which) {
@@ -271,8 +276,8 @@ std::string mfma_describe(const syno_plan* plan, int which) {
   const Variant& v = variant_of(plan->in_dtype == SYNO_BF16, vi);
   char b[256];
   memcpy(&p, plan->launch[which].params, sizeof p);
-  snprintf(b, sizeof b, "variant=%d rows/block=%d BN=%d KC=%d taps/row-step=%d waves=%dx%dx%d grid=%d lds=%dB slots=%d", vi, TR,
-           v.BN(), p.KC, p.U, v.WM, v.WN, v.WK, p.n_mblocks * p.n_nblocks * p.G, p.lds_bytes, p.n_slots);
+  snprintf(b, sizeof b, "variant=%d rows/block=%d BN=%d KC=%d taps/row-step=%d weights=%s waves=%dx%dx%d grid=%d lds=%dB slots=%d", vi, TR,
+           v.BN(), p.KC, p.U, (plan->in_dtype != SYNO_BF16 || p.wf) ? "direct" : "packed", v.WM, v.WN, v.WK, p.n_mblocks * p.n_nblocks * p.G, p.lds_bytes, p.n_slots);
   return b;
 }
 
@@ -284,12 +289,16 @@ syno_status launch_mfma(const syno_plan* plan, int which, const void* A, const v
   memcpy(&p, plan->launch[which].params, sizeof p);
   const bool obf = plan->out_dtype == SYNO_BF16;
   if (plan->in_dtype == SYNO_BF16) {
-    if (!ws) return SYNO_ERR_WORKSPACE;
-    const int64_t pieces = (int64_t)packed_weight_bytes(p) / 16;
-    hipLaunchKernelGGL(pack_weight_bf16, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, stream, p,
-                       static_cast<const uint16_t*>(B), static_cast<uint4*>(ws), pieces);
-    if (obf) launch_mfma_bf16_bf16out(vi, p, A, ws, out, stream);
-    else launch_mfma_bf16_f32out(vi, p, A, ws, out, stream);
+    const void* weights = B;
+    if (p.wf == 0) {
+      if (!ws) return SYNO_ERR_WORKSPACE;
+      const int64_t pieces = (int64_t)packed_weight_bytes(p) / 16;
+      hipLaunchKernelGGL(pack_weight_bf16, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, stream, p,
+                         static_cast<const uint16_t*>(B), static_cast<uint4*>(ws), pieces);
+      weights = ws;
+    }
+    if (obf) launch_mfma_bf16_bf16out(vi, p, A, weights, out, stream);
+    else launch_mfma_bf16_f32out(vi, p, A, weights, out, stream);
   } else {
     if (obf) return SYNO_ERR_UNSUPPORTED;
     if (vi < 4) launch_mfma_f32_lo(vi, p, A, B, out, stream);

@@ -94,12 +94,13 @@ def main() -> int:
             for _ in range(warm):
                 self.launch()
             torch.cuda.synchronize()
-            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
-            for s, e in evs:
-                s.record()
+            marks = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
+            marks[0].record()
+            for i in range(iters):
                 self.launch()
-                e.record()
+                marks[i + 1].record()
             torch.cuda.synchronize()
+            evs = list(zip(marks[:-1], marks[1:]))
             t = sorted(s.elapsed_time(e) for s, e in evs)
             return t[len(t) // 2], sum(t) / len(t)
 
@@ -120,12 +121,16 @@ def main() -> int:
     ev = {c.name: [] for c in step_cases}
     t0 = time.perf_counter()
     for _ in range(args.steps):
+        # one event between consecutive launches (on the current stream, which is the stream the binding launches
+        # on): launch i is bracketed by events i and i+1
+        prev = torch.cuda.Event(enable_timing=True)
+        prev.record()
         for c in step_cases:
-            s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            s.record()        # on the current stream, which is the stream the binding launches on
             c.launch()
+            e = torch.cuda.Event(enable_timing=True)
             e.record()
-            ev[c.name].append((s, e))
+            ev[c.name].append((prev, e))
+            prev = e
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps

@@ -64,6 +64,45 @@ __global__ __launch_bounds__(256) void pack_weight_bf16(const MfmaParams p, cons
   packed[i] = make_uint4(v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16));
 }
 
+// The same re-ordering for weights in the forward layout [g][o][c][T taps] (contiguous): a thread takes
+// 8 channels x T taps of one output channel (T adjacent 16-byte loads), re-orders them in registers and
+// writes one 16-byte piece per tap.  Threads beyond Og / Cg write the zero pieces of the padding.
+template <int T>
+__global__ __launch_bounds__(256) void pack_weight_bf16_fwd(const MfmaParams p, const uint16_t* __restrict__ Wt,
+                                                            uint4* __restrict__ packed, int64_t threads) {
+  typedef uint32_t u32x4_unaligned __attribute__((ext_vector_type(4), aligned(2)));
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= threads) return;
+  const int oct_per_chunk = p.KC >> 3, octs = p.n_chunks * oct_per_chunk, rows = p.n_nblocks * p.BN;
+  const int octet = (int)(i % octs);
+  const int row = (int)((i / octs) % rows);
+  const int g = (int)(i / ((int64_t)octs * rows));
+  const int ch = octet / oct_per_chunk, cq = octet - ch * oct_per_chunk;
+  const int nb = row / p.BN, ol = row - nb * p.BN;
+  const bool live = row < p.Og && octet * 8 < p.Cg;
+  uint32_t in[4 * T];
+#pragma unroll
+  for (int q = 0; q < T; ++q) {
+    u32x4_unaligned v = {0, 0, 0, 0};
+    if (live)
+      v = *reinterpret_cast<const u32x4_unaligned*>(Wt + (int64_t)g * p.ws_g + (int64_t)row * p.ws_o + octet * 8 * T + q * 8);
+    in[4 * q + 0] = v[0]; in[4 * q + 1] = v[1]; in[4 * q + 2] = v[2]; in[4 * q + 3] = v[3];
+  }
+  uint4* block = packed + (((int64_t)(g * p.n_nblocks + nb) * p.n_chunks + ch) * p.w_block >> 3);
+  const int row8 = p.w_row >> 3;
+#pragma unroll
+  for (int tap = 0; tap < T; ++tap) {
+    uint32_t d[4];
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      const int e0 = (2 * h) * T + tap, e1 = (2 * h + 1) * T + tap;
+      const uint32_t sel = ((e0 & 1) ? 0x0302u : 0x0100u) | ((e1 & 1) ? 0x07060000u : 0x05040000u);
+      d[h] = __builtin_amdgcn_perm(in[e1 >> 1], in[e0 >> 1], sel);
+    }
+    block[(tap * p.BN + ol) * row8 + cq] = make_uint4(d[0], d[1], d[2], d[3]);
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Host side: tile choice and launch
 // ---------------------------------------------------------------------------------------------
@@ -292,9 +331,21 @@ syno_status launch_mfma(const syno_plan* plan, int which, const void* A, const v
     const void* weights = B;
     if (p.wf == 0) {
       if (!ws) return SYNO_ERR_WORKSPACE;
-      const int64_t pieces = (int64_t)packed_weight_bytes(p) / 16;
-      hipLaunchKernelGGL(pack_weight_bf16, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, stream, p,
-                         static_cast<const uint16_t*>(B), static_cast<uint4*>(ws), pieces);
+      const ConvLike& c = plan->conv;
+      const int KHW = c.KH * c.KW;
+      const bool fwd_layout = which == SYNO_FWD && (c.KW == 1 || c.ws_kw == 1) && (c.KH == 1 || c.ws_kh == c.KW) &&
+                              c.ws_c == KHW && (c.Cg & 7) == 0;
+      const uint16_t* Wt = static_cast<const uint16_t*>(B);
+      uint4* dst = static_cast<uint4*>(ws);
+      const int64_t threads = (int64_t)p.G * p.n_nblocks * p.BN * p.n_chunks * (p.KC >> 3);
+      const dim3 grid((unsigned)((threads + 255) / 256));
+      if (fwd_layout && KHW == 9) hipLaunchKernelGGL(pack_weight_bf16_fwd<9>, grid, dim3(256), 0, stream, p, Wt, dst, threads);
+      else if (fwd_layout && KHW == 3) hipLaunchKernelGGL(pack_weight_bf16_fwd<3>, grid, dim3(256), 0, stream, p, Wt, dst, threads);
+      else if (fwd_layout && KHW == 1) hipLaunchKernelGGL(pack_weight_bf16_fwd<1>, grid, dim3(256), 0, stream, p, Wt, dst, threads);
+      else {
+        const int64_t pieces = (int64_t)packed_weight_bytes(p) / 16;
+        hipLaunchKernelGGL(pack_weight_bf16, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, stream, p, Wt, dst, pieces);
+      }
       weights = ws;
     }
     if (obf) launch_mfma_bf16_bf16out(vi, p, A, weights, out, stream);

@@ -639,17 +639,21 @@ struct Variant {
 //   fp32 11:   64 output channels like 3, half its rows, K split over two waves
 //   bf16 0-5:  packed weights, 32 channels per chunk
 //   bf16 6:    packed weights, at most 64 channels per group, staged in one go
+//   fp32 12:   as 10 for at most 128 pixels per block, up to 64 channels per chunk
 //   bf16 7-8:  as 1 and 2 with 64 channels per chunk
-constexpr int kNumF32Variants = 12, kNumBf16Variants = 9;
+//   bf16 9:    as 8 for at most 128 pixels per block, 128 channels per chunk
+constexpr int kNumF32Variants = 13, kNumBf16Variants = 10;
 constexpr Variant kF32Variants[kNumF32Variants] = {
     {4, 2, 1, 7, 2, 1, 9, 8, false}, {4, 2, 1, 7, 1, 1, 5, 8, false}, {8, 1, 1, 4, 1, 1, 3, 8, false},
     {4, 2, 1, 7, 2, 1, 5, 16, true}, {4, 1, 2, 7, 2, 1, 3, 16, true}, {2, 1, 4, 7, 2, 1, 3, 16, true},
     {1, 1, 8, 4, 4, 1, 5, 16, true}, {4, 2, 1, 7, 1, 2, 5, 32, true}, {8, 1, 1, 4, 1, 2, 3, 32, true},
-    {4, 1, 2, 7, 2, 1, 5, 32, true}, {2, 1, 4, 7, 2, 1, 5, 32, true}, {2, 2, 2, 7, 2, 1, 5, 16, true}};
+    {4, 1, 2, 7, 2, 1, 5, 32, true}, {2, 1, 4, 7, 2, 1, 5, 32, true}, {2, 2, 2, 7, 2, 1, 5, 16, true},
+    {2, 1, 4, 4, 2, 2, 9, 64, true}};
 constexpr Variant kBf16Variants[kNumBf16Variants] = {
     {4, 2, 1, 7, 2, 1, 6, 32, false}, {4, 1, 2, 7, 2, 1, 3, 32, false}, {2, 1, 4, 7, 2, 1, 3, 32, false},
     {1, 1, 8, 4, 4, 1, 6, 32, false}, {4, 2, 1, 7, 1, 2, 3, 32, false}, {8, 1, 1, 4, 1, 2, 2, 32, false},
-    {4, 2, 1, 7, 2, 4, 11, 64, false, true}, {4, 1, 2, 7, 2, 1, 6, 64, false}, {2, 1, 4, 7, 2, 1, 6, 64, false}};
+    {4, 2, 1, 7, 2, 4, 11, 64, false, true}, {4, 1, 2, 7, 2, 1, 6, 64, false}, {2, 1, 4, 7, 2, 1, 6, 64, false},
+    {2, 1, 4, 4, 2, 2, 10, 128, false}};
 
 template <bool BF, int VI, int U, int WF, bool OUTBF>
 void launch_variant(const MfmaParams& p, const void* X, const void* W, void* out, hipStream_t s) {

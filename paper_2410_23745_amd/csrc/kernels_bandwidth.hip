@@ -44,7 +44,7 @@ __global__ __launch_bounds__(256) void depthwise_stream(const DwParams p, const 
   const int lpg = 1 << p.lpg_log2;
   const int lig = lane & (lpg - 1);
   const int grp = lane >> p.lpg_log2, gpw = 64 >> p.lpg_log2;   // group within the wave, groups per wave
-  const int wave = (blockIdx.x * 256 + threadIdx.x) >> 6;
+  const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
   const int x0 = lig * SV;                       // first input column this lane loads
   const int w0 = lig * V;                        // first output column this lane produces
   constexpr int HALO = KH - S;                   // input rows a strip shares with the strip above it
@@ -154,8 +154,9 @@ template <int KH, int KW, int S, int V>
 void launch_dw(const DwParams& p, const float* X, const float* W, float* out, hipStream_t s) {
   const int groups_per_wave = 64 >> p.lpg_log2;
   const int waves = (p.n_tasks + groups_per_wave - 1) / groups_per_wave;
-  const int blocks = (waves + 3) / 4;
-  hipLaunchKernelGGL((depthwise_stream<KH, KW, S, V, kStripRows>), dim3(blocks), dim3(256), 0, s, p, X, W, out);
+  const int wpb = 4;
+  const int blocks = (waves + wpb - 1) / wpb;
+  hipLaunchKernelGGL((depthwise_stream<KH, KW, S, V, kStripRows>), dim3(blocks), dim3(64 * wpb), 0, s, p, X, W, out);
 }
 
 }  // namespace

@@ -7,7 +7,7 @@ void launch_mfma_bf16_bf16out(int vi, const MfmaParams& p, const void* X, const 
 #define SYNO_CASE(VI) \
   case VI: launch_variant<true, VI, 1, 0, true>(p, X, W, out, s); break;
   switch (vi) {
-    SYNO_CASE(0) SYNO_CASE(1) SYNO_CASE(2) SYNO_CASE(3) SYNO_CASE(4) SYNO_CASE(5) SYNO_CASE(7) SYNO_CASE(8)
+    SYNO_CASE(0) SYNO_CASE(1) SYNO_CASE(2) SYNO_CASE(3) SYNO_CASE(4) SYNO_CASE(5) SYNO_CASE(7) SYNO_CASE(8) SYNO_CASE(9)
     case 6:   // single chunk: packed weights, or weights as they lie in memory with 1, 3 or 9 taps per channel (negative: backward-data)
       if (p.wf == 9) launch_variant<true, 6, 1, 9, true>(p, X, W, out, s);
       else if (p.wf == 3) launch_variant<true, 6, 1, 3, true>(p, X, W, out, s);

@@ -15,6 +15,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdint>
 #include <cstdio>
 #include <string>
 
@@ -205,6 +206,8 @@ __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint
     }
 }
 
+// Partials are added in a fixed order (four interleaved groups of splits, then the groups), so the result
+// does not depend on scheduling.
 __global__ __launch_bounds__(256) void dw_reduce(const float* __restrict__ partial, float* __restrict__ dW, int n_elems,
                                                  int n_splits) {
   const int i = blockIdx.x * 256 + threadIdx.x;
@@ -212,6 +215,30 @@ __global__ __launch_bounds__(256) void dw_reduce(const float* __restrict__ parti
   float s = 0.f;
   for (int k = 0; k < n_splits; ++k) s += partial[(int64_t)k * n_elems + i];
   dW[i] = s;
+}
+
+// The same for element counts that are multiples of 4: a block covers 64 float4 columns with 4 waves, wave j
+// adds splits j, j+4, ...; the four sums meet in LDS.
+__global__ __launch_bounds__(256) void dw_reduce4(const float4* __restrict__ partial, float4* __restrict__ dW, int n4,
+                                                  int n_splits) {
+  __shared__ float4 sums[4][64];
+  const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
+  const int col = blockIdx.x * 64 + lane;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (col < n4) {
+#pragma unroll 4
+    for (int k = grp; k < n_splits; k += 4) {
+      const float4 v = partial[(int64_t)k * n4 + col];
+      s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+  }
+  sums[grp][lane] = s;
+  __syncthreads();
+  if (grp == 0 && col < n4) {
+    const float4 a = sums[0][lane], b = sums[1][lane], c = sums[2][lane], d = sums[3][lane];
+    dW[col] = make_float4((a.x + b.x) + (c.x + d.x), (a.y + b.y) + (c.y + d.y), (a.z + b.z) + (c.z + d.z),
+                          (a.w + b.w) + (c.w + d.w));
+  }
 }
 
 uint32_t magic_of(int d) { return (uint32_t)(((1ull << 32) + d - 1) / d); }
@@ -241,11 +268,11 @@ bool fill_dw(const syno_plan* plan, DwParams& p) {
   p.magic_rw2 = magic_of(p.TRK * W2);
   p.n_oblk = (c.Og + 63) / 64;
   p.n_cblk = (c.Cg + 63) / 64;
-  // split the rows: aim at one or two workgroups per CU, keep the partials below ~8 MB
+  // split the rows: aim at one workgroup per CU, keep the partials below ~32 MB
   const int tiles = c.G * p.n_oblk * p.n_cblk;
   const int chunks = (p.rows_total + p.TRK - 1) / p.TRK;
   int splits = std::max(1, std::min(chunks, 256 / std::max(1, tiles)));
-  while (splits > 1 && (int64_t)splits * plan->w_elems * 4 > (8ll << 20)) splits /= 2;
+  while (splits > 1 && (int64_t)splits * plan->w_elems * 4 > (32ll << 20)) splits /= 2;
   const int chunks_per_split = (chunks + splits - 1) / splits;
   p.rows_per_split = chunks_per_split * p.TRK;
   p.n_splits = (p.rows_total + p.rows_per_split - 1) / p.rows_per_split;
@@ -305,8 +332,12 @@ syno_status launch_mfma_dw(const syno_plan* plan, const void* A, const void* B, 
     (void)opt_in;
     hipLaunchKernelGGL(dw_mfma_bf16<1>, dim3(grid), dim3(256), p.lds_bytes, stream, p, G, X, part);
   }
-  hipLaunchKernelGGL(dw_reduce, dim3((p.w_elems + 255) / 256), dim3(256), 0, stream, part, static_cast<float*>(out),
-                     p.w_elems, p.n_splits);
+  if ((p.w_elems & 3) == 0 && (reinterpret_cast<uintptr_t>(out) & 15) == 0)
+    hipLaunchKernelGGL(dw_reduce4, dim3((p.w_elems / 4 + 63) / 64), dim3(256), 0, stream, reinterpret_cast<const float4*>(part),
+                       static_cast<float4*>(out), p.w_elems / 4, p.n_splits);
+  else
+    hipLaunchKernelGGL(dw_reduce, dim3((p.w_elems + 255) / 256), dim3(256), 0, stream, part, static_cast<float*>(out),
+                       p.w_elems, p.n_splits);
   return hipGetLastError() == hipSuccess ? SYNO_OK : SYNO_ERR_HIP;
 }
 

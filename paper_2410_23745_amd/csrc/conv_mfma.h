@@ -27,6 +27,8 @@ struct MfmaParams {
   // ceil(2^32/d) for the divisors the kernel needs (exact quotients for n*d < 2^32, which the host checks)
   uint32_t m_wo, m_ho, m_vpr, m_pcg, m_per_o, m_khw, m_kw;
   int32_t wf;                         // bf16 single-chunk variant: taps per channel when the weights are read unpacked, else 0
+  int32_t wt;                         // fp32 backward-data: the weights are first transposed into the workspace
+  int32_t ts_g, ts_o, ts_c, ts_kh, ts_kw;   // ... from a tensor with these strides
   int32_t U;                          // window taps along w per row-step (selects the instantiation)
 };
 

@@ -64,6 +64,22 @@ __global__ __launch_bounds__(256) void pack_weight_bf16(const MfmaParams p, cons
   packed[i] = make_uint4(v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16));
 }
 
+// fp32 backward-data: Wt[g][c][o][kh'][kw'] = W[g][o][c][KH-1-kh'][KW-1-kw'] (source strides ts_*), contiguous.
+__global__ __launch_bounds__(256) void transpose_weight_f32(const MfmaParams p, const float* __restrict__ Wt,
+                                                            float* __restrict__ out, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  // (in the adjoint record Og counts the forward input channels and Cg the forward output channels)
+  int64_t r = i;
+  const int kw = (int)(r % p.KW); r /= p.KW;
+  const int kh = (int)(r % p.KH); r /= p.KH;
+  const int o = (int)(r % p.Cg); r /= p.Cg;
+  const int c = (int)(r % p.Og);
+  const int g = (int)(r / p.Og);
+  out[i] = Wt[(int64_t)g * p.ts_g + (int64_t)o * p.ts_o + (int64_t)c * p.ts_c + (p.KH - 1 - kh) * p.ts_kh +
+              (p.KW - 1 - kw) * p.ts_kw];
+}
+
 // The same re-ordering for weights in the forward layout [g][o][c][T taps] (contiguous): a thread takes
 // 8 channels x T taps of one output channel (T adjacent 16-byte loads), re-orders them in registers and
 // writes one 16-byte piece per tap.  Threads beyond Og / Cg write the zero pieces of the padding.
@@ -162,6 +178,14 @@ bool fill_params(const syno_plan* plan, int which, int vi, int TR, MfmaParams& p
     p.os_o = plane; p.os_n = c.G * c.Cg * plane;
     p.ws_g = c.ws_g; p.ws_o = c.ws_c; p.ws_c = c.ws_o; p.ws_kh = -c.ws_kh; p.ws_kw = -c.ws_kw;
     p.w_base = (c.KH - 1) * c.ws_kh + (c.KW - 1) * c.ws_kw;
+    if (!bf) {
+      // fp32: a small kernel first writes the adjoint's weights [g][c][o][reversed taps] contiguously into the
+      // workspace, so that the contraction stages them in 16-byte pieces like forward weights
+      p.wt = 1;
+      p.ts_g = c.ws_g; p.ts_o = c.ws_o; p.ts_c = c.ws_c; p.ts_kh = c.ws_kh; p.ts_kw = c.ws_kw;
+      p.ws_g = c.Cg * c.Og * c.KH * c.KW; p.ws_o = c.Og * c.KH * c.KW; p.ws_c = c.KH * c.KW; p.ws_kh = c.KW; p.ws_kw = 1;
+      p.w_base = 0;
+    }
   }
   p.TR = TR;
   p.BN = v.BN();
@@ -179,7 +203,7 @@ bool fill_params(const syno_plan* plan, int which, int vi, int TR, MfmaParams& p
     if (v.one && fwd_layout && (c.Cg & 7) == 0 && (KHW == 1 || KHW == 3 || KHW == 9))
       p.wf = which == SYNO_FWD ? KHW : -KHW;
   } else if (v.wnat) {
-    if (which != SYNO_FWD || c.ws_kw != 1 || c.ws_kh != c.KW || c.ws_c != KHW || (c.ws_o & 3) || (c.ws_g & 3))
+    if ((c.KW > 1 && p.ws_kw != 1) || (c.KH > 1 && p.ws_kh != c.KW) || p.ws_c != KHW || (p.ws_o & 3) || (p.ws_g & 3))
       return false;
     p.KC = v.KC;
     while (p.KC > 8 && (p.Cg % p.KC != 0 || p.BN * p.KC * KHW > 4 * v.WI * v.NT() ||
@@ -305,7 +329,7 @@ void mfma_configure(syno_plan* plan, int which) {
   memcpy(plan->launch[which].params, &mp, sizeof mp);
   plan->launch[which].params_ready = true;
   plan->launch[which].variant = best_v * 4096 + best_tr;
-  plan->launch[which].workspace = (bf && mp.wf == 0) ? packed_weight_bytes(mp) : 0;
+  plan->launch[which].workspace = bf ? (mp.wf == 0 ? packed_weight_bytes(mp) : 0) : (mp.wt ? (size_t)mp.G * mp.Og * mp.Cg * mp.KH * mp.KW * 4 : 0);
 }
 
 std::string mfma_describe(const syno_plan* plan, int which) {
@@ -352,8 +376,16 @@ syno_status launch_mfma(const syno_plan* plan, int which, const void* A, const v
     else launch_mfma_bf16_f32out(vi, p, A, weights, out, stream);
   } else {
     if (obf) return SYNO_ERR_UNSUPPORTED;
-    if (vi < 4) launch_mfma_f32_lo(vi, p, A, B, out, stream);
-    else launch_mfma_f32_hi(vi, p, A, B, out, stream);
+    const void* weights = B;
+    if (p.wt) {
+      if (!ws) return SYNO_ERR_WORKSPACE;
+      const int64_t n = (int64_t)p.G * p.Og * p.Cg * p.KH * p.KW;
+      hipLaunchKernelGGL(transpose_weight_f32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p,
+                         static_cast<const float*>(B), static_cast<float*>(ws), n);
+      weights = ws;
+    }
+    if (vi < 4) launch_mfma_f32_lo(vi, p, A, weights, out, stream);
+    else launch_mfma_f32_hi(vi, p, A, weights, out, stream);
   }
   return hipGetLastError() == hipSuccess ? SYNO_OK : SYNO_ERR_HIP;
 }

@@ -7,7 +7,9 @@
 With --copy a plain device copy of a known size (256 MiB, `Tensor.copy_`) runs first; what FETCH_SIZE and
 WRITE_SIZE report for it gives the factor that turns the counters into bytes.
 
-Cases: config0, config1_s{0..3}_{f32|bf16}, config2, config3, config4_{fwd|bwd_data|bwd_weight}.
+Cases: config0, config1_s{0..3}_{f32|bf16}, config2, config3, config4_{fwd|bwd_data|bwd_weight}, and the backward
+passes of the first two shapes with a seeded output gradient: config1t_s{0..3}_{f32|bf16}_{fwd|bwd_data|bwd_weight},
+config3t_{fwd|bwd_data|bwd_weight}.
 Buffers rotate over several copies so that every launch reads HBM rather than the last-level cache.
 """
 from __future__ import annotations
@@ -27,6 +29,13 @@ def make_case(name: str):
         w = wl.config0()
     elif name.startswith("config1_s"):
         w = wl.config1(int(name[9]), name.endswith("bf16"))
+    elif name.startswith("config1t_s"):     # config1t_s<stage>_<f32|bf16>_<fwd|bwd_data|bwd_weight>
+        stage, dt, direction = int(name[10]), name[12:].split("_")[0], name[12:].split("_", 1)[1]
+        w = wl.config1_train(stage, dt == "bf16")
+        which = {"fwd": 0, "bwd_data": 1, "bwd_weight": 2}[direction]
+    elif name.startswith("config3t_"):
+        w = wl.config3_train()
+        which = {"fwd": 0, "bwd_data": 1, "bwd_weight": 2}[name[9:]]
     elif name == "config2":
         w = wl.config2()
     elif name == "config3":

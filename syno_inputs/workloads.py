@@ -160,12 +160,22 @@ def config1(stage: int, bf16: bool, N: int = 32) -> Workload:
     return make_conv(N, C, H, seed=0, bf16=bf16)
 
 
+def config1_train(stage: int, bf16: bool, N: int = 32) -> Workload:
+    """configs[1] shapes with an output gradient (seed 0 stream continues into G), for the backward passes."""
+    C, H = RESNET18_STAGES[stage]
+    return make_conv(N, C, H, seed=0, bf16=bf16, with_grad=True)
+
+
 def config2(N: int = 32) -> Workload:
     return make_gshift(N, seeds=(0, 0, 0))
 
 
 def config3(N: int = 64) -> Workload:
     return make_depthwise(N, 128, 56, seed=0)
+
+
+def config3_train(N: int = 64) -> Workload:
+    return make_depthwise(N, 128, 56, seed=0, with_grad=True)
 
 
 def config4(N: int = 128) -> Workload:

@@ -142,7 +142,13 @@ def test_kernel_choice(syno):
     assert names(wl.grouped_shift_unfold(128)) == ["mfma_contraction_bf16"] * 3
     assert names(wl.strided_depthwise(64, 128, 28, 28))[0] == "bandwidth_depthwise"
     p = syno.Plan(wl.grouped_shift_unfold(128))
-    assert p.workspace_bytes(syno.FWD) > 0 and p.workspace_bytes(syno.BWD_WEIGHT) > 0
+    # 64 channels per group: forward and backward-data read the weights as they lie in memory, no workspace;
+    # backward-weight keeps its split partials there
+    assert p.workspace_bytes(syno.FWD) == 0 and p.workspace_bytes(syno.BWD_DATA) == 0
+    assert p.workspace_bytes(syno.BWD_WEIGHT) > 0
+    # more channels than one chunk holds: bf16 weights are packed, fp32 backward-data weights transposed, into it
+    assert syno.Plan(wl.conv2d(32, 128, 128, 28, 28, 3, 3, BF16, F32)).workspace_bytes(syno.FWD) > 0
+    assert syno.Plan(wl.conv2d(32, 128, 128, 28, 28)).workspace_bytes(syno.BWD_DATA) == 128 * 128 * 9 * 4
     assert "grid=" in p.describe(syno.FWD)
     syno.set_kernel_policy(1)
     try:

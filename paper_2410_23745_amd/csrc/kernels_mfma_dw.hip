@@ -1,5 +1,5 @@
 // MFMA backward-weight contraction for convolution-like operators (bf16 inputs, fp32 result):
-//   dW[g,o,c,kw] = sum_{n,h,w} G[n, g*Og+o, h, w] * X[n, g*Cg+c, row(h,g), w+kw-pw]       (KH = 1)
+//   dW[g,o,c,kh,kw] = sum_{n,h,w} G[n, g*Og+o, h, w] * X[n, g*Cg+c, row(h,g)+kh-ph, w+kw-pw]
 // A GEMM per group and tap with M = o, N = c and the reduction over the pixels (n,h,w), which is the
 // contiguous axis of both operands - exactly what the bf16 MFMA wants (8 consecutive K per lane).
 //
@@ -7,7 +7,9 @@
 // one zero column: that column is the zero padding of the window on either side, so a tap is a pure
 // shift of the X index by (kw - pw) elements and needs no mask.  G has zeros in its pad columns, so
 // whatever X holds there never contributes.  A shifted 8-element fragment is cut out of two aligned
-// 16-byte LDS reads with v_alignbit.
+// 16-byte LDS reads with v_alignbit.  With a window along h as well (KH = 3) a chunk of rows stays inside
+// one image, X is staged with its KH-1 halo rows (zero outside the image), the row pitch is a multiple of
+// 8 elements, and tap kh is a further shift by kh whole rows.
 //
 // The pixel axis is split over workgroups (split-K); each writes its 64x64xKW partial in the layout
 // of dW into the workspace and a second kernel adds the partials in a fixed order, so the result does
@@ -24,16 +26,19 @@
 namespace syno {
 
 struct DwParams {
-  int32_t G, Og, Cg, H, W, KW, pw;
+  int32_t G, Og, Cg, H, W, KH, KW, ph, pw;
   int32_t rows_total;                  // N*H
   int32_t h_wrap, h_shift, h_shift_g;  // X row = (h + h_shift + h_shift_g*g) mod H when wrapped, else h
   int32_t plane, gs_n, xs_n;           // H*W; image strides of G and X
-  int32_t ws_g, ws_o, ws_c, ws_kw;     // dW strides
+  int32_t ws_g, ws_o, ws_c, ws_kh, ws_kw;   // dW strides
   int32_t w_elems;                     // elements of dW (= stride between partials)
   int32_t pitch, TRK, CP, CPp;         // LDS row pitch, rows per chunk, chunk length (multiple of 32), LDS channel pitch
   int32_t rows_per_split, n_splits, n_oblk, n_cblk;
-  int32_t items;                       // 64 * TRK * W/2 dword items per tensor per chunk
-  uint32_t magic_w2, magic_rw2;        // ceil(2^32/d) for d = W/2 and TRK*W/2
+  int32_t n_xrows;                     // rows of X staged per chunk: TRK + KH - 1
+  int32_t cpi;                         // KH > 1: chunks per image (chunks do not cross images); else 0
+  int32_t chunks_per_split, n_chunks;
+  int32_t items;                       // 64 * n_xrows * W/2 dword items per tensor per chunk
+  uint32_t magic_w2, magic_rw2;        // ceil(2^32/d) for d = W/2 and n_xrows*W/2
   int32_t lds_x_off, lds_tab_off, lds_bytes;
 };
 
@@ -60,15 +65,15 @@ __device__ __forceinline__ bf16x8 cut(const uint4& lo, const uint4& hi) {
   return __builtin_bit_cast(bf16x8, r);
 }
 
-// One workgroup: group g, 64 output channels x 64 input channels, one split of the pixel rows.
-// 4 waves; wave (wo, wc) owns o-tiles {2wo, 2wo+1} x c-tiles {2wc, 2wc+1} x KW taps.
-template <int KW>
+// One workgroup: group g, 64 output channels x 32*CT input channels, one split of the pixel rows.
+// 4 waves; wave (wo, wc) owns o-tiles {2wo, 2wo+1} x CT c-tiles x KH*KW taps (CT = 2 for up to 3 taps, 1 for 9).
+template <int KH, int KW, int CT>
 __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint16_t* __restrict__ Gt,
                                                     const uint16_t* __restrict__ Xt, float* __restrict__ partial) {
   extern __shared__ __align__(16) unsigned char smem[];
   uint16_t* gl = reinterpret_cast<uint16_t*>(smem);                 // [64][CPp]
-  uint16_t* xl = reinterpret_cast<uint16_t*>(smem + p.lds_x_off);   // [64][CPp], data starts at kGuard
-  int* row_tab = reinterpret_cast<int*>(smem + p.lds_tab_off);      // [2][TRK]: G row offset, X row offset (-1: none)
+  uint16_t* xl = reinterpret_cast<uint16_t*>(smem + p.lds_x_off);   // [32*CT][CPp], data starts at kGuard
+  int* row_tab = reinterpret_cast<int*>(smem + p.lds_tab_off);      // [2][n_xrows]: G row offset, X row offset (-1: none)
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int widx = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -78,8 +83,10 @@ __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint
   const int cb = bid % p.n_cblk; bid /= p.n_cblk;
   const int ob = bid % p.n_oblk;
   const int g = bid / p.n_oblk;
-  const int row_begin = split * p.rows_per_split;
-  const int row_end = min(p.rows_total, row_begin + p.rows_per_split);
+  const int chunk_begin = split * p.chunks_per_split;
+  const int chunk_end = min(p.n_chunks, chunk_begin + p.chunks_per_split);
+  constexpr int CX = 32 * CT;      // X channels of this workgroup
+  constexpr int T = KH * KW;
 
   // zero both tiles once: pad columns, guards and tails stay zero for the whole kernel
   {
@@ -92,49 +99,59 @@ __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint
   // meta: LDS element offset | row << 20 | (X channel beyond Cg) << 30 ; -1 when unused
   int it_goff[kDwItems], it_meta[kDwItems];
   const int W2 = p.W >> 1;
-  const int o_lim = p.Og - ob * 64, c_lim = p.Cg - cb * 64;     // channels beyond are zero
+  const int o_lim = p.Og - ob * 64, c_lim = min(p.Cg - cb * CX, CX);     // channels beyond are zero
 #pragma unroll
   for (int k = 0; k < kDwItems; ++k) {
     const int idx = tid + k * 256;
     const int ch = __umulhi((uint32_t)idx, p.magic_rw2);
-    const int rem = idx - ch * (p.TRK * W2);
+    const int rem = idx - ch * (p.n_xrows * W2);
     const int r = __umulhi((uint32_t)rem, p.magic_w2);
     const int j = rem - r * W2;
     it_goff[k] = (ch * p.plane + 2 * j) | (ch < o_lim ? 0 : 1);
     it_meta[k] = idx < p.items ? ((ch * p.CPp + r * p.pitch + 2 * j) | (r << 20) | (ch < c_lim ? 0 : (1 << 30))) : -1;
   }
   const uint16_t* Gg = Gt + (int64_t)(g * p.Og + ob * 64) * p.plane;
-  const uint16_t* Xg = Xt + (int64_t)(g * p.Cg + cb * 64) * p.plane;
+  const uint16_t* Xg = Xt + (int64_t)(g * p.Cg + cb * CX) * p.plane;
 
-  floatx4 acc[2][2][KW];
+  floatx4 acc[2][CT][T];
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < CT; ++b)
 #pragma unroll
-      for (int t = 0; t < KW; ++t) acc[a][b][t] = floatx4{0.f, 0.f, 0.f, 0.f};
+      for (int t = 0; t < T; ++t) acc[a][b][t] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   // operand bases (element indices)
-  int a_base[2], b_base[2];
+  int a_base[2], b_base[CT];
 #pragma unroll
   for (int a = 0; a < 2; ++a) a_base[a] = ((2 * wo + a) * 16 + (lane & 15)) * p.CPp + (lane >> 4) * 8;
 #pragma unroll
-  for (int b = 0; b < 2; ++b) b_base[b] = ((2 * wc + b) * 16 + (lane & 15)) * p.CPp + (lane >> 4) * 8 + kGuard - 8;
+  for (int b = 0; b < CT; ++b) b_base[b] = ((CT * wc + b) * 16 + (lane & 15)) * p.CPp + (lane >> 4) * 8 + kGuard - 8;
 
   uint32_t gr[kDwItems], xr[kDwItems];
-  for (int rho0 = row_begin; rho0 < row_end; rho0 += p.TRK) {
+  for (int q = chunk_begin; q < chunk_end; ++q) {
     __syncthreads();        // previous chunk fully consumed (and, first time, the zero fill is complete)
-    if (tid < p.TRK) {
-      const int rho = rho0 + tid;
+    if (tid < p.n_xrows) {
       int go = -1, xo = -1;
-      if (rho < row_end) {
-        const int n = rho / p.H, h = rho - n * p.H;
-        const int r = p.h_wrap ? (h + p.h_shift + p.h_shift_g * g) % p.H : h;
-        go = n * p.gs_n + h * p.W;
-        xo = n * p.xs_n + r * p.W;
+      if (KH == 1) {
+        // rows of any image, cyclic row shift allowed: G row rho <-> X row (h + shift) mod H of the same image
+        const int rho = q * p.TRK + tid;
+        if (rho < p.rows_total) {
+          const int n = rho / p.H, h = rho - n * p.H;
+          const int r = p.h_wrap ? (h + p.h_shift + p.h_shift_g * g) % p.H : h;
+          go = n * p.gs_n + h * p.W;
+          xo = n * p.xs_n + r * p.W;
+        }
+      } else {
+        // rows h0 .. h0+TRK-1 of image n; X slot r holds image row h0 - ph + r (zero outside the image)
+        const int n = q / p.cpi, h0 = (q - n * p.cpi) * p.TRK;
+        const int rows = min(p.TRK, p.H - h0);
+        if (tid < rows) go = n * p.gs_n + (h0 + tid) * p.W;
+        const int hx = h0 - p.ph + tid;
+        if (tid < rows + KH - 1 && hx >= 0 && hx < p.H) xo = n * p.xs_n + hx * p.W;
       }
       row_tab[tid] = go;
-      row_tab[p.TRK + tid] = xo;
+      row_tab[p.n_xrows + tid] = xo;
     }
     __syncthreads();
 #pragma unroll
@@ -142,7 +159,7 @@ __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint
       gr[k] = 0; xr[k] = 0;
       if (it_meta[k] >= 0) {
         const int r = (it_meta[k] >> 20) & 1023;
-        const int go = row_tab[r], xo = row_tab[p.TRK + r];
+        const int go = row_tab[r], xo = row_tab[p.n_xrows + r];
         if (go >= 0 && !(it_goff[k] & 1)) gr[k] = *reinterpret_cast<const uint32_t*>(Gg + go + it_goff[k]);
         if (xo >= 0 && !(it_meta[k] >> 30)) xr[k] = *reinterpret_cast<const uint32_t*>(Xg + xo + (it_goff[k] & ~1));
       }
@@ -152,39 +169,39 @@ __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint
       if (it_meta[k] >= 0) {
         const int lo = it_meta[k] & 0xfffff;
         *reinterpret_cast<uint32_t*>(gl + lo) = gr[k];
-        *reinterpret_cast<uint32_t*>(xl + lo + kGuard) = xr[k];
+        if (!(it_meta[k] >> 30)) *reinterpret_cast<uint32_t*>(xl + lo + kGuard) = xr[k];   // (channels X does not have stay zero)
       }
     __syncthreads();
     const int steps = p.CP >> 5;
     for (int st = 0; st < steps; ++st) {
       bf16x8 a[2];
-      uint4 xlo[2], xhi[2];
 #pragma unroll
       for (int i = 0; i < 2; ++i) a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(gl + a_base[i] + st * 32));
+      // tap (kh, kw) reads X shifted by kh rows and (kw - pw) elements: element 8 + kw - pw of the 16 read at
+      // row offset kh*pitch (a multiple of 8 elements when KH > 1)
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        xlo[i] = *reinterpret_cast<const uint4*>(xl + b_base[i] + st * 32);
-        xhi[i] = *reinterpret_cast<const uint4*>(xl + b_base[i] + st * 32 + 8);
-      }
-      // tap kw reads X shifted by (kw - pw): element 8 + kw - pw of the 16 just read
+      for (int i = 0; i < CT; ++i)
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        bf16x8 b[KW];
-        if constexpr (KW == 1) {
-          b[0] = cut<8>(xlo[i], xhi[i]);
-        } else {
-          b[0] = cut<7>(xlo[i], xhi[i]);
-          b[1] = cut<8>(xlo[i], xhi[i]);
-          // one more element to the right needs the next group; read it only for this tap
-          const uint4 xnx = *reinterpret_cast<const uint4*>(xl + b_base[i] + st * 32 + 16);
-          b[2] = cut<1>(xhi[i], xnx);
+        for (int kh = 0; kh < KH; ++kh) {
+          const uint16_t* xp = xl + b_base[i] + st * 32 + kh * p.pitch;
+          const uint4 xlo = *reinterpret_cast<const uint4*>(xp);
+          const uint4 xhi = *reinterpret_cast<const uint4*>(xp + 8);
+          bf16x8 b[KW];
+          if constexpr (KW == 1) {
+            b[0] = cut<8>(xlo, xhi);
+          } else {
+            b[0] = cut<7>(xlo, xhi);
+            b[1] = cut<8>(xlo, xhi);
+            // one more element to the right needs the next group; read it only for this tap
+            const uint4 xnx = *reinterpret_cast<const uint4*>(xp + 16);
+            b[2] = cut<1>(xhi, xnx);
+          }
+#pragma unroll
+          for (int t = 0; t < KW; ++t)
+#pragma unroll
+            for (int ao = 0; ao < 2; ++ao)
+              acc[ao][i][kh * KW + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ao], b[t], acc[ao][i][kh * KW + t], 0, 0, 0);
         }
-#pragma unroll
-        for (int t = 0; t < KW; ++t)
-#pragma unroll
-          for (int ao = 0; ao < 2; ++ao)
-            acc[ao][i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ao], b[t], acc[ao][i][t], 0, 0, 0);
-      }
     }
   }
 
@@ -193,15 +210,16 @@ __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint
 #pragma unroll
   for (int ao = 0; ao < 2; ++ao)
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int c = cb * 64 + (2 * wc + i) * 16 + (lane & 15);
+    for (int i = 0; i < CT; ++i) {
+      const int c = cb * CX + (CT * wc + i) * 16 + (lane & 15);
       if (c >= p.Cg) continue;
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
         const int o = ob * 64 + (2 * wo + ao) * 16 + 4 * (lane >> 4) + v;
         if (o >= p.Og) continue;
 #pragma unroll
-        for (int t = 0; t < KW; ++t) dst[(int64_t)o * p.ws_o + (int64_t)c * p.ws_c + t * p.ws_kw] = acc[ao][i][t][v];
+        for (int t = 0; t < T; ++t)
+          dst[(int64_t)o * p.ws_o + (int64_t)c * p.ws_c + (t / KW) * p.ws_kh + (t % KW) * p.ws_kw] = acc[ao][i][t][v];
       }
     }
 }
@@ -246,40 +264,55 @@ uint32_t magic_of(int d) { return (uint32_t)(((1ull << 32) + d - 1) / d); }
 bool fill_dw(const syno_plan* plan, DwParams& p) {
   const ConvLike& c = plan->conv;
   p = DwParams{};
-  p.G = c.G; p.Og = c.Og; p.Cg = c.Cg; p.H = c.Ho; p.W = c.Wo; p.KW = c.KW; p.pw = c.pw;
+  p.G = c.G; p.Og = c.Og; p.Cg = c.Cg; p.H = c.Ho; p.W = c.Wo; p.KH = c.KH; p.KW = c.KW; p.ph = c.ph; p.pw = c.pw;
   p.rows_total = c.N * c.Ho;
   p.h_wrap = c.h_wrap; p.h_shift = c.h_shift; p.h_shift_g = c.h_shift_g;
   p.plane = c.Ho * c.Wo;
   p.gs_n = c.G * c.Og * p.plane; p.xs_n = c.G * c.Cg * p.plane;
-  p.ws_g = c.ws_g; p.ws_o = c.ws_o; p.ws_c = c.ws_c; p.ws_kw = c.ws_kw;
+  p.ws_g = c.ws_g; p.ws_o = c.ws_o; p.ws_c = c.ws_c; p.ws_kh = c.ws_kh; p.ws_kw = c.ws_kw;
   p.w_elems = (int32_t)plan->w_elems;
   p.pitch = (c.Wo + std::max(c.pw, c.KW - 1 - c.pw) + 1) & ~1;
   if (p.pitch == c.Wo) p.pitch += 2;                 // always at least one zero column
+  if (c.KH > 1) p.pitch = (p.pitch + 7) & ~7;        // whole-row shifts stay 16-byte aligned
+  const int cx = (c.KH * c.KW <= 3) ? 64 : 32;       // X channels per workgroup
   // rows per chunk: about 224 staged elements per channel, bounded by the per-thread item budget
-  const int W2 = c.Wo / 2;
+  const int W2 = c.Wo / 2, halo = c.KH - 1;
   int trk = std::max(1, 224 / p.pitch);
-  while (trk > 1 && 64 * trk * W2 > kDwItems * 256) --trk;
-  if (64 * trk * W2 > kDwItems * 256) return false;
-  p.TRK = std::min(trk, p.rows_total);
+  if (c.KH > 1) trk = std::min(trk, c.Ho);
+  while (trk > 1 && 64 * (trk + halo) * W2 > kDwItems * 256) --trk;
+  if (64 * (trk + halo) * W2 > kDwItems * 256) return false;
+  if (c.KH > 1) {
+    p.cpi = (c.Ho + trk - 1) / trk;                   // chunks stay inside an image, all about equally long
+    trk = (c.Ho + p.cpi - 1) / p.cpi;
+    p.n_chunks = c.N * p.cpi;
+  } else {
+    trk = std::min(trk, p.rows_total);
+    p.n_chunks = (p.rows_total + trk - 1) / trk;
+  }
+  p.TRK = trk;
+  p.n_xrows = trk + halo;
   p.CP = (p.TRK * p.pitch + 31) & ~31;
-  p.CPp = p.CP + 24;                                  // guard in front, slack behind, rows 16-byte aligned and bank-skewed
-  p.items = 64 * p.TRK * W2;
+  // LDS channel pitch: the last k-step reads up to CP + halo rows + 24 elements; guard in front, rows 16-byte
+  // aligned and bank-skewed
+  p.CPp = std::max(p.CP, p.n_xrows * p.pitch) + halo * p.pitch + 24;
+  p.CPp = (p.CPp + 7) & ~7;
+  if ((p.CPp & 31) == 0) p.CPp += 8;
+  p.items = 64 * p.n_xrows * W2;
   p.magic_w2 = magic_of(W2);
-  p.magic_rw2 = magic_of(p.TRK * W2);
+  p.magic_rw2 = magic_of(p.n_xrows * W2);
   p.n_oblk = (c.Og + 63) / 64;
-  p.n_cblk = (c.Cg + 63) / 64;
-  // split the rows: aim at one workgroup per CU, keep the partials below ~32 MB
+  p.n_cblk = (c.Cg + cx - 1) / cx;
+  // split the chunks: aim at one workgroup per CU, keep the partials below ~32 MB
   const int tiles = c.G * p.n_oblk * p.n_cblk;
-  const int chunks = (p.rows_total + p.TRK - 1) / p.TRK;
-  int splits = std::max(1, std::min(chunks, 256 / std::max(1, tiles)));
+  int splits = std::max(1, std::min(p.n_chunks, 256 / std::max(1, tiles)));
   while (splits > 1 && (int64_t)splits * plan->w_elems * 4 > (32ll << 20)) splits /= 2;
-  const int chunks_per_split = (chunks + splits - 1) / splits;
-  p.rows_per_split = chunks_per_split * p.TRK;
-  p.n_splits = (p.rows_total + p.rows_per_split - 1) / p.rows_per_split;
+  p.chunks_per_split = (p.n_chunks + splits - 1) / splits;
+  p.rows_per_split = p.chunks_per_split * p.TRK;
+  p.n_splits = (p.n_chunks + p.chunks_per_split - 1) / p.chunks_per_split;
   p.lds_x_off = 64 * p.CPp * 2;
-  p.lds_tab_off = 2 * p.lds_x_off;
-  p.lds_bytes = p.lds_tab_off + ((2 * p.TRK * 4 + 15) & ~15);
-  return p.lds_bytes <= 144 * 1024 && 64 * p.CPp < (1 << 20) && p.TRK < 1024;
+  p.lds_tab_off = p.lds_x_off + cx * p.CPp * 2;
+  p.lds_bytes = p.lds_tab_off + ((2 * p.n_xrows * 4 + 15) & ~15);
+  return p.lds_bytes <= 144 * 1024 && 64 * p.CPp < (1 << 20) && p.n_xrows < 1024 && p.n_xrows <= 256;
 }
 
 }  // namespace
@@ -287,7 +320,8 @@ bool fill_dw(const syno_plan* plan, DwParams& p) {
 bool mfma_dw_supports(const syno_plan* p) {
   if (!p->conv_like || p->in_dtype != SYNO_BF16) return false;
   const ConvLike& c = p->conv;
-  if (c.sh != 1 || c.sw != 1 || c.w_wrap || c.KH != 1) return false;
+  if (c.sh != 1 || c.sw != 1 || c.w_wrap) return false;
+  if (c.KH != 1 && (c.KH != 3 || c.h_wrap || c.ph != 1 || c.ws_kh < 0)) return false;
   if (c.Wi != c.Wo || c.Hi != c.Ho || (c.Wo & 1)) return false;
   if (c.KW != 1 && c.KW != 3) return false;
   if (c.pw != c.KW / 2) return false;
@@ -307,8 +341,8 @@ std::string mfma_dw_describe(const syno_plan* plan) {
   DwParams p;
   if (!fill_dw(plan, p)) return "unconfigured";
   char b[256];
-  snprintf(b, sizeof b, "rows/chunk=%d pitch=%d splits=%d grid=%d lds=%dB", p.TRK, p.pitch, p.n_splits,
-           p.G * p.n_oblk * p.n_cblk * p.n_splits, p.lds_bytes);
+  snprintf(b, sizeof b, "rows/chunk=%d(+%d) pitch=%d chunks=%d splits=%d grid=%d lds=%dB", p.TRK, p.KH - 1, p.pitch, p.n_chunks,
+           p.n_splits, p.G * p.n_oblk * p.n_cblk * p.n_splits, p.lds_bytes);
   return b;
 }
 
@@ -321,17 +355,16 @@ syno_status launch_mfma_dw(const syno_plan* plan, const void* A, const void* B, 
   const uint16_t* G = static_cast<const uint16_t*>(A);
   const uint16_t* X = static_cast<const uint16_t*>(B);
   float* part = static_cast<float*>(ws);
-  if (p.KW == 3) {
-    static const hipError_t opt_in = hipFuncSetAttribute(reinterpret_cast<const void*>(dw_mfma_bf16<3>),
-                                                         hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
-    (void)opt_in;
-    hipLaunchKernelGGL(dw_mfma_bf16<3>, dim3(grid), dim3(256), p.lds_bytes, stream, p, G, X, part);
-  } else {
-    static const hipError_t opt_in = hipFuncSetAttribute(reinterpret_cast<const void*>(dw_mfma_bf16<1>),
-                                                         hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
-    (void)opt_in;
-    hipLaunchKernelGGL(dw_mfma_bf16<1>, dim3(grid), dim3(256), p.lds_bytes, stream, p, G, X, part);
-  }
+  auto launch = [&](auto kernel) {
+    // (once per instantiation would do; the attribute call is cheap next to the launch)
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024) != hipSuccess)
+      return;
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), p.lds_bytes, stream, p, G, X, part);
+  };
+  if (p.KH == 3 && p.KW == 3) launch(dw_mfma_bf16<3, 3, 1>);
+  else if (p.KH == 3) launch(dw_mfma_bf16<3, 1, 2>);
+  else if (p.KW == 3) launch(dw_mfma_bf16<1, 3, 2>);
+  else launch(dw_mfma_bf16<1, 1, 2>);
   if ((p.w_elems & 3) == 0 && (reinterpret_cast<uintptr_t>(out) & 15) == 0)
     hipLaunchKernelGGL(dw_reduce4, dim3((p.w_elems / 4 + 63) / 64), dim3(256), 0, stream, reinterpret_cast<const float4*>(part),
                        static_cast<float4*>(out), p.w_elems / 4, p.n_splits);

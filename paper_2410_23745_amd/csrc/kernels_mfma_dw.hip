@@ -67,7 +67,8 @@ __device__ __forceinline__ bf16x8 cut(const uint4& lo, const uint4& hi) {
 
 // One workgroup: group g, 64 output channels x 32*CT input channels, one split of the pixel rows.
 // 4 waves; wave (wo, wc) owns o-tiles {2wo, 2wo+1} x CT c-tiles x KH*KW taps (CT = 2 for up to 3 taps, 1 for 9).
-template <int KH, int KW, int CT>
+// Staging moves pairs of pixels (one dword) when W is even, single pixels (W1) when it is odd.
+template <int KH, int KW, int CT, bool W1>
 __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint16_t* __restrict__ Gt,
                                                     const uint16_t* __restrict__ Xt, float* __restrict__ partial) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -95,10 +96,11 @@ __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint
     for (int i = tid; i < n16; i += 256) z[i] = make_uint4(0, 0, 0, 0);
   }
   // per-thread item descriptors, the same for G and X: (channel, row, dword) of the chunk
-  // goff: element offset inside the 64-channel slab (even; bit 0 set = G channel beyond Og)
+  // goff: element offset inside the 64-channel slab, shifted left by one; bit 0 set = G channel beyond Og
   // meta: LDS element offset | row << 20 | (X channel beyond Cg) << 30 ; -1 when unused
   int it_goff[kDwItems], it_meta[kDwItems];
-  const int W2 = p.W >> 1;
+  const int W2 = W1 ? p.W : p.W >> 1;     // items per row
+  constexpr int EP = W1 ? 1 : 2;          // elements per item
   const int o_lim = p.Og - ob * 64, c_lim = min(p.Cg - cb * CX, CX);     // channels beyond are zero
 #pragma unroll
   for (int k = 0; k < kDwItems; ++k) {
@@ -107,8 +109,8 @@ __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint
     const int rem = idx - ch * (p.n_xrows * W2);
     const int r = __umulhi((uint32_t)rem, p.magic_w2);
     const int j = rem - r * W2;
-    it_goff[k] = (ch * p.plane + 2 * j) | (ch < o_lim ? 0 : 1);
-    it_meta[k] = idx < p.items ? ((ch * p.CPp + r * p.pitch + 2 * j) | (r << 20) | (ch < c_lim ? 0 : (1 << 30))) : -1;
+    it_goff[k] = ((ch * p.plane + EP * j) << 1) | (ch < o_lim ? 0 : 1);
+    it_meta[k] = idx < p.items ? ((ch * p.CPp + r * p.pitch + EP * j) | (r << 20) | (ch < c_lim ? 0 : (1 << 30))) : -1;
   }
   const uint16_t* Gg = Gt + (int64_t)(g * p.Og + ob * 64) * p.plane;
   const uint16_t* Xg = Xt + (int64_t)(g * p.Cg + cb * CX) * p.plane;
@@ -160,16 +162,26 @@ __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint
       if (it_meta[k] >= 0) {
         const int r = (it_meta[k] >> 20) & 1023;
         const int go = row_tab[r], xo = row_tab[p.n_xrows + r];
-        if (go >= 0 && !(it_goff[k] & 1)) gr[k] = *reinterpret_cast<const uint32_t*>(Gg + go + it_goff[k]);
-        if (xo >= 0 && !(it_meta[k] >> 30)) xr[k] = *reinterpret_cast<const uint32_t*>(Xg + xo + (it_goff[k] & ~1));
+        if constexpr (W1) {
+          if (go >= 0 && !(it_goff[k] & 1)) gr[k] = Gg[go + (it_goff[k] >> 1)];
+          if (xo >= 0 && !(it_meta[k] >> 30)) xr[k] = Xg[xo + (it_goff[k] >> 1)];
+        } else {
+          if (go >= 0 && !(it_goff[k] & 1)) gr[k] = *reinterpret_cast<const uint32_t*>(Gg + go + (it_goff[k] >> 1));
+          if (xo >= 0 && !(it_meta[k] >> 30)) xr[k] = *reinterpret_cast<const uint32_t*>(Xg + xo + (it_goff[k] >> 1));
+        }
       }
     }
 #pragma unroll
     for (int k = 0; k < kDwItems; ++k)
       if (it_meta[k] >= 0) {
         const int lo = it_meta[k] & 0xfffff;
-        *reinterpret_cast<uint32_t*>(gl + lo) = gr[k];
-        if (!(it_meta[k] >> 30)) *reinterpret_cast<uint32_t*>(xl + lo + kGuard) = xr[k];   // (channels X does not have stay zero)
+        if constexpr (W1) {
+          gl[lo] = (uint16_t)gr[k];
+          if (!(it_meta[k] >> 30)) xl[lo + kGuard] = (uint16_t)xr[k];   // (channels X does not have stay zero)
+        } else {
+          *reinterpret_cast<uint32_t*>(gl + lo) = gr[k];
+          if (!(it_meta[k] >> 30)) *reinterpret_cast<uint32_t*>(xl + lo + kGuard) = xr[k];
+        }
       }
     __syncthreads();
     const int steps = p.CP >> 5;
@@ -276,7 +288,7 @@ bool fill_dw(const syno_plan* plan, DwParams& p) {
   if (c.KH > 1) p.pitch = (p.pitch + 7) & ~7;        // whole-row shifts stay 16-byte aligned
   const int cx = (c.KH * c.KW <= 3) ? 64 : 32;       // X channels per workgroup
   // rows per chunk: about 224 staged elements per channel, bounded by the per-thread item budget
-  const int W2 = c.Wo / 2, halo = c.KH - 1;
+  const int W2 = (c.Wo & 1) ? c.Wo : c.Wo / 2, halo = c.KH - 1;    // items per row: pixel pairs, or pixels when W is odd
   int trk = std::max(1, 224 / p.pitch);
   if (c.KH > 1) trk = std::min(trk, c.Ho);
   while (trk > 1 && 64 * (trk + halo) * W2 > kDwItems * 256) --trk;
@@ -322,7 +334,7 @@ bool mfma_dw_supports(const syno_plan* p) {
   const ConvLike& c = p->conv;
   if (c.sh != 1 || c.sw != 1 || c.w_wrap) return false;
   if (c.KH != 1 && (c.KH != 3 || c.h_wrap || c.ph != 1 || c.ws_kh < 0)) return false;
-  if (c.Wi != c.Wo || c.Hi != c.Ho || (c.Wo & 1)) return false;
+  if (c.Wi != c.Wo || c.Hi != c.Ho) return false;
   if (c.KW != 1 && c.KW != 3) return false;
   if (c.pw != c.KW / 2) return false;
   if (c.ws_kw < 0 || (c.Og == 1 && c.Cg == 1)) return false;
@@ -361,10 +373,17 @@ syno_status launch_mfma_dw(const syno_plan* plan, const void* A, const void* B, 
       return;
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), p.lds_bytes, stream, p, G, X, part);
   };
-  if (p.KH == 3 && p.KW == 3) launch(dw_mfma_bf16<3, 3, 1>);
-  else if (p.KH == 3) launch(dw_mfma_bf16<3, 1, 2>);
-  else if (p.KW == 3) launch(dw_mfma_bf16<1, 3, 2>);
-  else launch(dw_mfma_bf16<1, 1, 2>);
+  if (p.W & 1) {
+    if (p.KH == 3 && p.KW == 3) launch(dw_mfma_bf16<3, 3, 1, true>);
+    else if (p.KH == 3) launch(dw_mfma_bf16<3, 1, 2, true>);
+    else if (p.KW == 3) launch(dw_mfma_bf16<1, 3, 2, true>);
+    else launch(dw_mfma_bf16<1, 1, 2, true>);
+  } else {
+    if (p.KH == 3 && p.KW == 3) launch(dw_mfma_bf16<3, 3, 1, false>);
+    else if (p.KH == 3) launch(dw_mfma_bf16<3, 1, 2, false>);
+    else if (p.KW == 3) launch(dw_mfma_bf16<1, 3, 2, false>);
+    else launch(dw_mfma_bf16<1, 1, 2, false>);
+  }
   if ((p.w_elems & 3) == 0 && (reinterpret_cast<uintptr_t>(out) & 15) == 0)
     hipLaunchKernelGGL(dw_reduce4, dim3((p.w_elems / 4 + 63) / 64), dim3(256), 0, stream, reinterpret_cast<const float4*>(part),
                        static_cast<float4*>(out), p.w_elems / 4, p.n_splits);

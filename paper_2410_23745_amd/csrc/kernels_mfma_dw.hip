@@ -236,6 +236,141 @@ __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint
     }
 }
 
+// fp32 inputs: the same contraction with v_mfma_f32_16x16x4_f32, whose K-step is 4 consecutive pixels (lane ->
+// row l%16, pixel l/16).  Operands are single dwords, so a tap is any element shift and nothing has to be cut;
+// staging moves single elements, in batches of kF32Batch per thread and tensor.
+constexpr int kF32Batch = 16;
+constexpr int kGuardF = 4;       // zero floats in front of each X channel row
+
+template <int KH, int KW, int CT>
+__global__ __launch_bounds__(256) void dw_mfma_f32(const DwParams p, const float* __restrict__ Gt,
+                                                   const float* __restrict__ Xt, float* __restrict__ partial) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  float* gl = reinterpret_cast<float*>(smem);                   // [64][CPp]
+  float* xl = reinterpret_cast<float*>(smem + p.lds_x_off);     // [32*CT][CPp], data starts at kGuardF
+  int* row_tab = reinterpret_cast<int*>(smem + p.lds_tab_off);  // [2][n_xrows]
+  constexpr int CX = 32 * CT, T = KH * KW;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int widx = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wo = widx >> 1, wc = widx & 1;
+  int bid = blockIdx.x;
+  const int split = bid % p.n_splits; bid /= p.n_splits;
+  const int cb = bid % p.n_cblk; bid /= p.n_cblk;
+  const int ob = bid % p.n_oblk;
+  const int g = bid / p.n_oblk;
+  const int chunk_begin = split * p.chunks_per_split;
+  const int chunk_end = min(p.n_chunks, chunk_begin + p.chunks_per_split);
+  {
+    uint4* z = reinterpret_cast<uint4*>(smem);
+    const int n16 = p.lds_tab_off >> 4;
+    for (int i = tid; i < n16; i += 256) z[i] = make_uint4(0, 0, 0, 0);
+  }
+  const int o_lim = p.Og - ob * 64, c_lim = min(p.Cg - cb * CX, CX);
+  const float* Gg = Gt + (int64_t)(g * p.Og + ob * 64) * p.plane;
+  const float* Xg = Xt + (int64_t)(g * p.Cg + cb * CX) * p.plane;
+
+  floatx4 acc[2][CT][T];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < CT; ++b)
+#pragma unroll
+      for (int t = 0; t < T; ++t) acc[a][b][t] = floatx4{0.f, 0.f, 0.f, 0.f};
+  int a_base[2], b_base[CT];     // element indices
+#pragma unroll
+  for (int a = 0; a < 2; ++a) a_base[a] = ((2 * wo + a) * 16 + (lane & 15)) * p.CPp + (lane >> 4);
+#pragma unroll
+  for (int b = 0; b < CT; ++b) b_base[b] = ((CT * wc + b) * 16 + (lane & 15)) * p.CPp + (lane >> 4) + kGuardF - p.pw;
+
+  for (int q = chunk_begin; q < chunk_end; ++q) {
+    __syncthreads();
+    if (tid < p.n_xrows) {
+      int go = -1, xo = -1;
+      if (KH == 1) {
+        const int rho = q * p.TRK + tid;
+        if (rho < p.rows_total) {
+          const int n = rho / p.H, h = rho - n * p.H;
+          const int r = p.h_wrap ? (h + p.h_shift + p.h_shift_g * g) % p.H : h;
+          go = n * p.gs_n + h * p.W;
+          xo = n * p.xs_n + r * p.W;
+        }
+      } else {
+        const int n = q / p.cpi, h0 = (q - n * p.cpi) * p.TRK;
+        const int rows = min(p.TRK, p.H - h0);
+        if (tid < rows) go = n * p.gs_n + (h0 + tid) * p.W;
+        const int hx = h0 - p.ph + tid;
+        if (tid < rows + KH - 1 && hx >= 0 && hx < p.H) xo = n * p.xs_n + hx * p.W;
+      }
+      row_tab[tid] = go;
+      row_tab[p.n_xrows + tid] = xo;
+    }
+    __syncthreads();
+    // stage: item = (channel, row, pixel); rows without a source and channels beyond the tensor become zeros
+    for (int base = 0; base < p.items; base += 256 * kF32Batch) {
+      float gr[kF32Batch], xr[kF32Batch];
+      int lo[kF32Batch];
+#pragma unroll
+      for (int k = 0; k < kF32Batch; ++k) {
+        const int idx = base + tid + k * 256;
+        gr[k] = 0.f; xr[k] = 0.f; lo[k] = -1;
+        if (idx < p.items) {
+          const int ch = __umulhi((uint32_t)idx, p.magic_rw2);
+          const int rem = idx - ch * (p.n_xrows * p.W);
+          const int r = __umulhi((uint32_t)rem, p.magic_w2);
+          const int j = rem - r * p.W;
+          const int go = row_tab[r], xo = row_tab[p.n_xrows + r];
+          if (go >= 0 && ch < o_lim) gr[k] = Gg[go + ch * p.plane + j];
+          if (xo >= 0 && ch < c_lim) xr[k] = Xg[xo + ch * p.plane + j];
+          lo[k] = (ch * p.CPp + r * p.pitch + j) | (ch < CX ? 0 : (1 << 30));
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < kF32Batch; ++k)
+        if (lo[k] >= 0) {
+          gl[lo[k] & 0xfffff] = gr[k];
+          if (!(lo[k] >> 30)) xl[(lo[k] & 0xfffff) + kGuardF] = xr[k];
+        }
+    }
+    __syncthreads();
+    const int steps = p.CP >> 2;
+#pragma unroll 2
+    for (int st = 0; st < steps; ++st) {
+      float a[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) a[i] = gl[a_base[i] + st * 4];
+#pragma unroll
+      for (int i = 0; i < CT; ++i)
+#pragma unroll
+        for (int kh = 0; kh < KH; ++kh)
+#pragma unroll
+          for (int t = 0; t < KW; ++t) {
+            const float b = xl[b_base[i] + st * 4 + kh * p.pitch + t];
+#pragma unroll
+            for (int ao = 0; ao < 2; ++ao)
+              acc[ao][i][kh * KW + t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[ao], b, acc[ao][i][kh * KW + t], 0, 0, 0);
+          }
+    }
+  }
+
+  float* dst = partial + (int64_t)split * p.w_elems + (int64_t)g * p.ws_g;
+#pragma unroll
+  for (int ao = 0; ao < 2; ++ao)
+#pragma unroll
+    for (int i = 0; i < CT; ++i) {
+      const int c = cb * CX + (CT * wc + i) * 16 + (lane & 15);
+      if (c >= p.Cg) continue;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int o = ob * 64 + (2 * wo + ao) * 16 + 4 * (lane >> 4) + v;
+        if (o >= p.Og) continue;
+#pragma unroll
+        for (int t = 0; t < T; ++t)
+          dst[(int64_t)o * p.ws_o + (int64_t)c * p.ws_c + (t / KW) * p.ws_kh + (t % KW) * p.ws_kw] = acc[ao][i][t][v];
+      }
+    }
+}
+
 // Partials are added in a fixed order (four interleaved groups of splits, then the groups), so the result
 // does not depend on scheduling.
 __global__ __launch_bounds__(256) void dw_reduce(const float* __restrict__ partial, float* __restrict__ dW, int n_elems,
@@ -327,10 +462,65 @@ bool fill_dw(const syno_plan* plan, DwParams& p) {
   return p.lds_bytes <= 144 * 1024 && 64 * p.CPp < (1 << 20) && p.n_xrows < 1024 && p.n_xrows <= 256;
 }
 
+// fp32 configuration: element items, k-steps of 4 pixels, channel pitch = 4 * odd floats so that the 16 rows x 4
+// pixels of a fragment read fall into 64 distinct banks.
+bool fill_dw_f32(const syno_plan* plan, DwParams& p) {
+  const ConvLike& c = plan->conv;
+  p = DwParams{};
+  p.G = c.G; p.Og = c.Og; p.Cg = c.Cg; p.H = c.Ho; p.W = c.Wo; p.KH = c.KH; p.KW = c.KW; p.ph = c.ph; p.pw = c.pw;
+  p.rows_total = c.N * c.Ho;
+  p.h_wrap = c.h_wrap; p.h_shift = c.h_shift; p.h_shift_g = c.h_shift_g;
+  p.plane = c.Ho * c.Wo;
+  p.gs_n = c.G * c.Og * p.plane; p.xs_n = c.G * c.Cg * p.plane;
+  p.ws_g = c.ws_g; p.ws_o = c.ws_o; p.ws_c = c.ws_c; p.ws_kh = c.ws_kh; p.ws_kw = c.ws_kw;
+  p.w_elems = (int32_t)plan->w_elems;
+  p.pitch = c.Wo + std::max(1, std::max(c.pw, c.KW - 1 - c.pw));     // at least one zero column between rows
+  const int cx = (c.KH * c.KW <= 3) ? 64 : 32, halo = c.KH - 1;
+  // rows per chunk: about 200 staged pixels per channel and at most 3 batches of items per thread
+  int trk = std::max(1, 200 / p.pitch);
+  if (c.KH > 1) trk = std::min(trk, c.Ho);
+  while (trk > 1 && 64 * (trk + halo) * c.Wo > 3 * kF32Batch * 256) --trk;
+  if (64 * (trk + halo) * c.Wo > 3 * kF32Batch * 256) return false;
+  if (c.KH > 1) {
+    p.cpi = (c.Ho + trk - 1) / trk;
+    trk = (c.Ho + p.cpi - 1) / p.cpi;
+    p.n_chunks = c.N * p.cpi;
+  } else {
+    trk = std::min(trk, p.rows_total);
+    p.n_chunks = (p.rows_total + trk - 1) / trk;
+  }
+  p.TRK = trk;
+  p.n_xrows = trk + halo;
+  p.CP = (p.TRK * p.pitch + 3) & ~3;
+  p.CPp = (std::max(p.CP, p.n_xrows * p.pitch) + halo * p.pitch + c.KW + kGuardF + 4 + 3) & ~3;
+  if (((p.CPp >> 2) & 1) == 0) p.CPp += 4;
+  p.items = 64 * p.n_xrows * c.Wo;
+  p.magic_w2 = magic_of(c.Wo);
+  p.magic_rw2 = magic_of(p.n_xrows * c.Wo);
+  p.n_oblk = (c.Og + 63) / 64;
+  p.n_cblk = (c.Cg + cx - 1) / cx;
+  const int tiles = c.G * p.n_oblk * p.n_cblk;
+  int splits = std::max(1, std::min(p.n_chunks, 256 / std::max(1, tiles)));
+  while (splits > 1 && (int64_t)splits * plan->w_elems * 4 > (32ll << 20)) splits /= 2;
+  p.chunks_per_split = (p.n_chunks + splits - 1) / splits;
+  p.rows_per_split = p.chunks_per_split * p.TRK;
+  p.n_splits = (p.n_chunks + p.chunks_per_split - 1) / p.chunks_per_split;
+  p.lds_x_off = 64 * p.CPp * 4;
+  p.lds_tab_off = p.lds_x_off + cx * p.CPp * 4;
+  p.lds_bytes = p.lds_tab_off + ((2 * p.n_xrows * 4 + 15) & ~15);
+  return p.lds_bytes <= 144 * 1024 && 64 * p.CPp < (1 << 20) && p.n_xrows <= 256 &&
+         (int64_t)64 * p.n_xrows * c.Wo * std::max(c.Wo, p.n_xrows * c.Wo) < (1ll << 32);
+}
+
+bool fill_any(const syno_plan* plan, DwParams& p) {
+  return plan->in_dtype == SYNO_BF16 ? fill_dw(plan, p) : fill_dw_f32(plan, p);
+}
+
 }  // namespace
 
 bool mfma_dw_supports(const syno_plan* p) {
-  if (!p->conv_like || p->in_dtype != SYNO_BF16) return false;
+  if (!p->conv_like) return false;
+  if (p->in_dtype != SYNO_BF16 && p->in_dtype != SYNO_F32) return false;
   const ConvLike& c = p->conv;
   if (c.sh != 1 || c.sw != 1 || c.w_wrap) return false;
   if (c.KH != 1 && (c.KH != 3 || c.h_wrap || c.ph != 1 || c.ws_kh < 0)) return false;
@@ -339,19 +529,19 @@ bool mfma_dw_supports(const syno_plan* p) {
   if (c.pw != c.KW / 2) return false;
   if (c.ws_kw < 0 || (c.Og == 1 && c.Cg == 1)) return false;
   DwParams dp;
-  return fill_dw(p, dp);
+  return fill_any(p, dp);
 }
 
 void mfma_dw_configure(syno_plan* plan) {
   DwParams dp;
-  fill_dw(plan, dp);
+  fill_any(plan, dp);
   plan->launch[SYNO_BWD_WEIGHT].variant = 0;
   plan->launch[SYNO_BWD_WEIGHT].workspace = (size_t)dp.n_splits * plan->w_elems * 4;
 }
 
 std::string mfma_dw_describe(const syno_plan* plan) {
   DwParams p;
-  if (!fill_dw(plan, p)) return "unconfigured";
+  if (!fill_any(plan, p)) return "unconfigured";
   char b[256];
   snprintf(b, sizeof b, "rows/chunk=%d(+%d) pitch=%d chunks=%d splits=%d grid=%d lds=%dB", p.TRK, p.KH - 1, p.pitch, p.n_chunks,
            p.n_splits, p.G * p.n_oblk * p.n_cblk * p.n_splits, p.lds_bytes);
@@ -361,9 +551,30 @@ std::string mfma_dw_describe(const syno_plan* plan) {
 // A = G (upstream gradient), B = X, out = dW (fp32), ws = n_splits partial copies of dW.
 syno_status launch_mfma_dw(const syno_plan* plan, const void* A, const void* B, void* out, void* ws, hipStream_t stream) {
   DwParams p;
-  if (!fill_dw(plan, p)) return SYNO_ERR_UNSUPPORTED;
+  if (!fill_any(plan, p)) return SYNO_ERR_UNSUPPORTED;
   if (!ws) return SYNO_ERR_WORKSPACE;
   const int grid = p.G * p.n_oblk * p.n_cblk * p.n_splits;
+  if (plan->in_dtype == SYNO_F32) {
+    const float* Gf = static_cast<const float*>(A);
+    const float* Xf = static_cast<const float*>(B);
+    float* partf = static_cast<float*>(ws);
+    auto launchf = [&](auto kernel) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024) != hipSuccess)
+        return;
+      hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), p.lds_bytes, stream, p, Gf, Xf, partf);
+    };
+    if (p.KH == 3 && p.KW == 3) launchf(dw_mfma_f32<3, 3, 1>);
+    else if (p.KH == 3) launchf(dw_mfma_f32<3, 1, 2>);
+    else if (p.KW == 3) launchf(dw_mfma_f32<1, 3, 2>);
+    else launchf(dw_mfma_f32<1, 1, 2>);
+    if ((p.w_elems & 3) == 0 && (reinterpret_cast<uintptr_t>(out) & 15) == 0)
+      hipLaunchKernelGGL(dw_reduce4, dim3((p.w_elems / 4 + 63) / 64), dim3(256), 0, stream, reinterpret_cast<const float4*>(partf),
+                         static_cast<float4*>(out), p.w_elems / 4, p.n_splits);
+    else
+      hipLaunchKernelGGL(dw_reduce, dim3((p.w_elems + 255) / 256), dim3(256), 0, stream, partf, static_cast<float*>(out),
+                         p.w_elems, p.n_splits);
+    return hipGetLastError() == hipSuccess ? SYNO_OK : SYNO_ERR_HIP;
+  }
   const uint16_t* G = static_cast<const uint16_t*>(A);
   const uint16_t* X = static_cast<const uint16_t*>(B);
   float* part = static_cast<float*>(ws);

@@ -670,7 +670,7 @@ syno_status build_plan(const syno_desc* desc, int policy, syno_plan* plan, std::
       L.kernel = plan->in_dtype == SYNO_BF16 ? KERNEL_MFMA_BF16 : KERNEL_MFMA_F32;
       mfma_configure(plan, which);
     } else if (which == SYNO_BWD_WEIGHT && mfma_dw_supports(plan)) {
-      L.kernel = KERNEL_MFMA_BF16;
+      L.kernel = plan->in_dtype == SYNO_BF16 ? KERNEL_MFMA_BF16 : KERNEL_MFMA_F32;
       mfma_dw_configure(plan);
     }
   }

@@ -174,10 +174,8 @@ def test_config4_full_size_training_step(syno, oracle):
 @pytest.mark.parametrize("stage", [0, 1, 2, 3])
 @pytest.mark.parametrize("bf16", [False, True])
 def test_config1_full_size_backward_sampled(syno, oracle, stage, bf16):
-    """Backward passes of the conv-equivalent operator at the benchmark shapes (sampled against the checker).
-    fp32 backward-weight still runs on the index-program kernel, which takes long at these sizes: one shape only."""
-    directions = (1, 2) if (bf16 or stage == 3) else (1,)
-    run_all(syno, oracle, wl.config1_train(stage, bf16), 0, directions=directions, full=False, n_sample=2048)
+    """Backward passes of the conv-equivalent operator at the benchmark shapes (sampled against the checker)."""
+    run_all(syno, oracle, wl.config1_train(stage, bf16), 0, directions=(1, 2), full=False, n_sample=2048)
 
 
 def test_rejects_wrong_arguments(syno):

@@ -29,7 +29,10 @@ struct DwParams {
   int32_t vec_ok;         // rows start 16-byte aligned and Wi is a multiple of S*V
 };
 
-template <int KH, int KW, int S, int V, int RB>
+// MODE 0: forward (B = weights, out = result).
+// MODE 2: backward-weight partials: B = upstream gradient G (shaped like the forward result); every group
+//         leaves the KH*KW sums of G[h][w] * window over its strip in out[task][KH*KW].
+template <int KH, int KW, int S, int V, int RB, int MODE>
 __global__ __launch_bounds__(256) void depthwise_stream(const DwParams p, const float* __restrict__ X,
                                                         const float* __restrict__ Wt, float* __restrict__ out) {
   constexpr int SV = S * V;                      // input columns a lane loads per row
@@ -94,7 +97,7 @@ __global__ __launch_bounds__(256) void depthwise_stream(const DwParams p, const 
 #pragma unroll
     for (int a = 0; a < KH; ++a)
 #pragma unroll
-      for (int b = 0; b < KW; ++b) wk[a][b] = Wt[c * p.ws_c + a * p.ws_kh + b * p.ws_kw];
+      for (int b = 0; b < KW; ++b) wk[a][b] = MODE == 0 ? Wt[c * p.ws_c + a * p.ws_kh + b * p.ws_kw] : 0.f;
     // the window's horizontal neighbours come from the adjacent lanes
     float left[ROWS][HL > 0 ? HL : 1], right[ROWS][HR > 0 ? HR : 1];
 #pragma unroll
@@ -113,30 +116,65 @@ __global__ __launch_bounds__(256) void depthwise_stream(const DwParams p, const 
     auto win = [&](int a, int i) -> float {      // column i of the widened row a (compile-time indices after unrolling)
       return i < HL ? left[a][i] : (i < HL + SV ? v[a][i - HL] : right[a][i - HL - SV]);
     };
+    if constexpr (MODE == 0) {
 #pragma unroll
-    for (int i = 0; i < RB; ++i) {
-      const int h = h0 + i;
-      float acc[V];
+      for (int i = 0; i < RB; ++i) {
+        const int h = h0 + i;
+        float acc[V];
 #pragma unroll
-      for (int o = 0; o < V; ++o) {
-        acc[o] = 0.f;
+        for (int o = 0; o < V; ++o) {
+          acc[o] = 0.f;
 #pragma unroll
-        for (int a = 0; a < KH; ++a)
+          for (int a = 0; a < KH; ++a)
 #pragma unroll
-          for (int b = 0; b < KW; ++b) acc[o] = fmaf(wk[a][b], win(S * i + a, S * o + b), acc[o]);
-      }
-      if (task_ok && h < p.Ho) {
-        float* o = op + (int64_t)h * p.Wo + w0;
-        if (V == 2 && (p.Wo & 1) == 0) {
-          if (w0 < p.Wo) *reinterpret_cast<float2*>(o) = make_float2(acc[0], acc[1]);
-        } else if (V == 4 && (p.Wo & 3) == 0) {
-          if (w0 < p.Wo) *reinterpret_cast<float4*>(o) = make_float4(acc[0], acc[1], acc[2], acc[3]);
-        } else {
+            for (int b = 0; b < KW; ++b) acc[o] = fmaf(wk[a][b], win(S * i + a, S * o + b), acc[o]);
+        }
+        if (task_ok && h < p.Ho) {
+          float* o = op + (int64_t)h * p.Wo + w0;
+          if (V == 2 && (p.Wo & 1) == 0) {
+            if (w0 < p.Wo) *reinterpret_cast<float2*>(o) = make_float2(acc[0], acc[1]);
+          } else if (V == 4 && (p.Wo & 3) == 0) {
+            if (w0 < p.Wo) *reinterpret_cast<float4*>(o) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+          } else {
 #pragma unroll
-          for (int e = 0; e < V; ++e)
-            if (w0 + e < p.Wo) o[e] = acc[e];
+            for (int e = 0; e < V; ++e)
+              if (w0 + e < p.Wo) o[e] = acc[e];
+          }
         }
       }
+    } else {
+      // sums of G * window over the strip, per tap; Wt is G here, laid out like the forward result
+      const float* gp = Wt + (int64_t)plane * p.Ho * p.Wo;
+      float gv[RB][V];
+#pragma unroll
+      for (int i = 0; i < RB; ++i) {
+        if (V == 2 && (p.Wo & 1) == 0) {
+          float2 t = make_float2(0.f, 0.f);
+          if (task_ok && h0 + i < p.Ho && w0 < p.Wo) t = *reinterpret_cast<const float2*>(gp + (int64_t)(h0 + i) * p.Wo + w0);
+          gv[i][0] = t.x; gv[i][V - 1] = t.y;
+        } else {
+#pragma unroll
+          for (int o = 0; o < V; ++o)
+            gv[i][o] = (task_ok && h0 + i < p.Ho && w0 + o < p.Wo) ? gp[(int64_t)(h0 + i) * p.Wo + w0 + o] : 0.f;
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < RB; ++i)
+#pragma unroll
+        for (int o = 0; o < V; ++o)
+#pragma unroll
+          for (int a = 0; a < KH; ++a)
+#pragma unroll
+            for (int b = 0; b < KW; ++b) wk[a][b] = fmaf(gv[i][o], win(S * i + a, S * o + b), wk[a][b]);
+      // add up the lanes of the group (a fixed tree, so the result does not depend on scheduling)
+#pragma unroll
+      for (int a = 0; a < KH; ++a)
+#pragma unroll
+        for (int b = 0; b < KW; ++b) {
+          float v = wk[a][b];
+          for (int d = 1; d < lpg; d <<= 1) v += __shfl_xor(v, d, 64);
+          if (lig == 0 && task_ok) out[(int64_t)task * (KH * KW) + a * KW + b] = v;
+        }
     }
   };
 
@@ -148,23 +186,111 @@ __global__ __launch_bounds__(256) void depthwise_stream(const DwParams p, const 
   (void)WIN;
 }
 
+// Backward-data of the 3x3 stride-2 (pad 1) per-channel window: dX[y][x] = sum over the (h,w,kh,kw) with
+// 2h+kh-1 = y, 2w+kw-1 = x of G[h][w] * W[kh][kw]: one term when y and x are even, two when one is odd, four
+// when both are.  A group of lanes owns RB rows of G of one plane (plus the row below them) and writes the
+// 2*RB rows of dX above them; a lane loads 2 columns of G per row, takes the third from its right neighbour
+// with a shuffle and writes 4 columns of dX per row.  G is read once (plus one halo row per strip), dX written once.
+template <int RB>
+__global__ __launch_bounds__(256) void depthwise_s2k3_bwd_data(const DwParams p, const float* __restrict__ G,
+                                                               const float* __restrict__ Wt, float* __restrict__ dX) {
+  const int lane = threadIdx.x & 63;
+  const int lpg = 1 << p.lpg_log2;
+  const int lig = lane & (lpg - 1);
+  const int grp = lane >> p.lpg_log2, gpw = 64 >> p.lpg_log2;
+  const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int task = wave * gpw + grp;
+  const bool task_ok = task < p.n_tasks;
+  const int plane = task_ok ? task / p.strips : 0;
+  const int strip = task_ok ? task - plane * p.strips : 0;
+  const int h0 = strip * RB, c = plane % p.C;
+  const int w0 = 2 * lig;                          // first of the lane's two columns of G
+  const float* gp = G + (int64_t)plane * p.Ho * p.Wo;
+  float g[RB + 1][2], gn[RB + 1];
+#pragma unroll
+  for (int r = 0; r <= RB; ++r) {
+    float2 t = make_float2(0.f, 0.f);
+    if (task_ok && h0 + r < p.Ho && w0 < p.Wo) t = *reinterpret_cast<const float2*>(gp + (int64_t)(h0 + r) * p.Wo + w0);
+    g[r][0] = t.x; g[r][1] = t.y;
+  }
+#pragma unroll
+  for (int r = 0; r <= RB; ++r) {
+    const float t = __shfl_down(g[r][0], 1, 64);
+    gn[r] = (lig == lpg - 1 || w0 + 2 >= p.Wo) ? 0.f : t;
+  }
+  float w[3][3];
+#pragma unroll
+  for (int a = 0; a < 3; ++a)
+#pragma unroll
+    for (int b = 0; b < 3; ++b) w[a][b] = Wt[c * p.ws_c + a * p.ws_kh + b * p.ws_kw];
+  float* xp = dX + (int64_t)plane * p.Hi * p.Wi;
+#pragma unroll
+  for (int r = 0; r < RB; ++r) {
+    const int h = h0 + r;
+    if (!task_ok || h >= p.Ho || 4 * lig >= p.Wi) continue;
+    const float a0 = g[r][0], a1 = g[r][1], a2 = gn[r];                  // G row h, columns w0, w0+1, w0+2
+    const float b0 = g[r + 1][0], b1 = g[r + 1][1], b2 = gn[r + 1];      // G row h+1
+    // dX row 2h: only kh = 1 reaches it
+    const float4 even = make_float4(a0 * w[1][1], fmaf(a1, w[1][0], a0 * w[1][2]), a1 * w[1][1], fmaf(a2, w[1][0], a1 * w[1][2]));
+    // dX row 2h+1: kh = 2 from G row h, kh = 0 from G row h+1
+    const float4 odd = make_float4(
+        fmaf(b0, w[0][1], a0 * w[2][1]),
+        fmaf(b1, w[0][0], fmaf(b0, w[0][2], fmaf(a1, w[2][0], a0 * w[2][2]))),
+        fmaf(b1, w[0][1], a1 * w[2][1]),
+        fmaf(b2, w[0][0], fmaf(b1, w[0][2], fmaf(a2, w[2][0], a1 * w[2][2]))));
+    *reinterpret_cast<float4*>(xp + (int64_t)(2 * h) * p.Wi + 4 * lig) = even;
+    *reinterpret_cast<float4*>(xp + (int64_t)(2 * h + 1) * p.Wi + 4 * lig) = odd;
+  }
+}
+
+// Backward-weight, second stage: dW[c][tap] = sum over the images and strips of the partial sums.  One block per
+// channel; thread j adds the partials j, j+256, ... of the channel, then the threads' sums are added in a
+// fixed tree, so the result does not depend on scheduling.
+__global__ __launch_bounds__(256) void depthwise_bwd_weight_reduce(const DwParams p, const float* __restrict__ partial,
+                                                                   float* __restrict__ dW, int KW) {
+  constexpr int T = 9;
+  __shared__ float sums[T][256];
+  const int c = blockIdx.x, tid = threadIdx.x;
+  const int per_c = (p.planes / p.C) * p.strips;      // partials of one channel
+  float s[T];
+#pragma unroll
+  for (int t = 0; t < T; ++t) s[t] = 0.f;
+  for (int q = tid; q < per_c; q += 256) {
+    const int n = q / p.strips, st = q - n * p.strips;
+    const float* src = partial + ((int64_t)(n * p.C + c) * p.strips + st) * T;
+#pragma unroll
+    for (int t = 0; t < T; ++t) s[t] += src[t];
+  }
+#pragma unroll
+  for (int t = 0; t < T; ++t) sums[t][tid] = s[t];
+  __syncthreads();
+  for (int half = 128; half > 0; half >>= 1) {
+    if (tid < half)
+#pragma unroll
+      for (int t = 0; t < T; ++t) sums[t][tid] += sums[t][tid + half];
+    __syncthreads();
+  }
+  if (tid < T) dW[c * p.ws_c + (tid / KW) * p.ws_kh + (tid % KW) * p.ws_kw] = sums[tid][0];
+}
+
 constexpr int kStripRows = 7;   // output rows per strip: 15 input rows of a 3x3 stride-2 window in registers
 
-template <int KH, int KW, int S, int V>
+template <int KH, int KW, int S, int V, int MODE>
 void launch_dw(const DwParams& p, const float* X, const float* W, float* out, hipStream_t s) {
   const int groups_per_wave = 64 >> p.lpg_log2;
   const int waves = (p.n_tasks + groups_per_wave - 1) / groups_per_wave;
   const int wpb = 4;
   const int blocks = (waves + wpb - 1) / wpb;
-  hipLaunchKernelGGL((depthwise_stream<KH, KW, S, V, kStripRows>), dim3(blocks), dim3(64 * wpb), 0, s, p, X, W, out);
+  hipLaunchKernelGGL((depthwise_stream<KH, KW, S, V, kStripRows, MODE>), dim3(blocks), dim3(64 * wpb), 0, s, p, X, W, out);
 }
 
 }  // namespace
 
-// Can the stream kernel take this plan's forward pass?  (fp32, one channel per group, no cyclic
-// axes, pads equal to K/2, a window/stride pair that is instantiated, rows no wider than a wave.)
+// Can the stream kernels take this pass?  (fp32, one channel per group, no cyclic axes, pads equal to K/2, a
+// window/stride pair that is instantiated, rows no wider than a wave.)  Forward: 3x3 at stride 1 or 2.
+// Backward-data and backward-weight: 3x3 at stride 2 with an input exactly twice the output.
 bool bandwidth_supports(const syno_plan* p, int which) {
-  if (!p->conv_like || which != SYNO_FWD) return false;
+  if (!p->conv_like) return false;
   if (p->in_dtype != SYNO_F32 || p->out_dtype != SYNO_F32) return false;
   const ConvLike& c = p->conv;
   if (c.Og != 1 || c.Cg != 1 || c.h_wrap || c.w_wrap) return false;
@@ -172,10 +298,21 @@ bool bandwidth_supports(const syno_plan* p, int which) {
   const bool inst = (c.KH == 3 && c.KW == 3 && (c.sh == 1 || c.sh == 2));
   if (!inst) return false;
   const int V = c.sh == 2 ? 2 : 4;
-  return (c.Wo + V - 1) / V <= 64;
+  if ((c.Wo + V - 1) / V > 64) return false;
+  if (which == SYNO_FWD) return true;
+  if (c.sh != 2 || c.Hi != 2 * c.Ho || c.Wi != 2 * c.Wo || (c.Wo & 1)) return false;
+  return c.ws_g >= 0 && c.ws_kh >= 0 && c.ws_kw >= 0;
 }
 
-syno_status launch_bandwidth(const syno_plan* plan, int which, const void* A, const void* B, void* out, void*,
+// Backward-weight keeps one partial sum per strip and tap in the workspace.
+size_t bandwidth_workspace(const syno_plan* plan, int which) {
+  if (which != SYNO_BWD_WEIGHT) return 0;
+  const ConvLike& c = plan->conv;
+  const size_t strips = (c.Ho + kStripRows - 1) / kStripRows;
+  return (size_t)c.N * c.G * strips * c.KH * c.KW * sizeof(float);
+}
+
+syno_status launch_bandwidth(const syno_plan* plan, int which, const void* A, const void* B, void* out, void* ws,
                              hipStream_t stream) {
   if (!bandwidth_supports(plan, which)) return SYNO_ERR_UNSUPPORTED;
   const ConvLike& c = plan->conv;
@@ -191,11 +328,25 @@ syno_status launch_bandwidth(const syno_plan* plan, int which, const void* A, co
   p.n_tasks = p.planes * p.strips;
   p.ws_c = c.ws_g; p.ws_kh = c.ws_kh; p.ws_kw = c.ws_kw;
   p.vec_ok = (c.Wi % (c.sw * V) == 0) && ((c.Hi * c.Wi) % 4 == 0) && (c.Wi % 4 == 0);
-  const float* X = static_cast<const float*>(A);
-  const float* W = static_cast<const float*>(B);
-  float* O = static_cast<float*>(out);
-  if (c.sh == 2) launch_dw<3, 3, 2, 2>(p, X, W, O, stream);
-  else launch_dw<3, 3, 1, 4>(p, X, W, O, stream);
+  if (which == SYNO_FWD) {
+    const float* X = static_cast<const float*>(A);
+    const float* W = static_cast<const float*>(B);
+    float* O = static_cast<float*>(out);
+    if (c.sh == 2) launch_dw<3, 3, 2, 2, 0>(p, X, W, O, stream);
+    else launch_dw<3, 3, 1, 4, 0>(p, X, W, O, stream);
+  } else if (which == SYNO_BWD_DATA) {
+    // A = G, B = W, out = dX
+    const int groups_per_wave = 64 >> p.lpg_log2;
+    const int waves = (p.n_tasks + groups_per_wave - 1) / groups_per_wave;
+    hipLaunchKernelGGL((depthwise_s2k3_bwd_data<kStripRows>), dim3((waves + 3) / 4), dim3(256), 0, stream, p,
+                       static_cast<const float*>(A), static_cast<const float*>(B), static_cast<float*>(out));
+  } else {
+    // A = G, B = X (the lowered forms take the upstream gradient first), out = dW, ws = partial sums
+    if (!ws) return SYNO_ERR_WORKSPACE;
+    launch_dw<3, 3, 2, 2, 2>(p, static_cast<const float*>(B), static_cast<const float*>(A), static_cast<float*>(ws), stream);
+    hipLaunchKernelGGL(depthwise_bwd_weight_reduce, dim3(p.C), dim3(256), 0, stream, p, static_cast<const float*>(ws),
+                       static_cast<float*>(out), 3);
+  }
   return hipGetLastError() == hipSuccess ? SYNO_OK : SYNO_ERR_HIP;
 }
 

@@ -114,6 +114,7 @@ bool mfma_supports(const syno_plan* p, int which);
 // fills launch[which] (tile variant, workspace bytes) for the MFMA family
 void mfma_configure(syno_plan* p, int which);
 // kernels_mfma_dw.hip: the backward-weight member of the MFMA family
+size_t bandwidth_workspace(const syno_plan* p, int which);
 bool mfma_dw_supports(const syno_plan* p);
 void mfma_dw_configure(syno_plan* p);
 

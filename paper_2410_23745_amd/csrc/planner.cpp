@@ -666,6 +666,7 @@ syno_status build_plan(const syno_desc* desc, int policy, syno_plan* plan, std::
     // iterator is a real contraction: MFMA.  Everything else stays on the index-program kernels.
     if (bandwidth_supports(plan, which)) {
       L.kernel = KERNEL_BW_DEPTHWISE;
+      L.workspace = bandwidth_workspace(plan, which);
     } else if (mfma_supports(plan, which)) {
       L.kernel = plan->in_dtype == SYNO_BF16 ? KERNEL_MFMA_BF16 : KERNEL_MFMA_F32;
       mfma_configure(plan, which);

@@ -86,6 +86,8 @@ def small_cases():
     c["gshift_bf16_small_groups"] = lambda: wl.make_gshift(2, seeds=(4, 5, 6), with_grad=True, C=96, H=9, Wd=11, groups=3)
     c["depthwise_f32"] = lambda: wl.make_depthwise(3, 20, 30, seed=2, with_grad=True)
     c["depthwise_f32_odd"] = lambda: wl.make_depthwise(2, 7, 18, seed=3, with_grad=True)
+    c["depthwise_f32_even"] = lambda: wl.make_depthwise(2, 5, 28, seed=4, with_grad=True)      # stream kernels, all passes
+    c["depthwise_f32_even_ragged"] = lambda: wl.make_depthwise(3, 4, 20, seed=5, with_grad=True)  # last strip 3 rows
     return c
 
 
@@ -169,6 +171,11 @@ def test_config3_full_size(syno, oracle):
 
 def test_config4_full_size_training_step(syno, oracle):
     run_all(syno, oracle, wl.config4(), 0, directions=(0, 1, 2), full=False, n_sample=8192)
+
+
+def test_config3_full_size_backward_sampled(syno, oracle):
+    names = run_all(syno, oracle, wl.config3_train(), 0, directions=(1, 2), full=False, n_sample=4096)
+    assert names[1] == names[2] == "bandwidth_depthwise"
 
 
 @pytest.mark.parametrize("stage", [0, 1, 2, 3])

@@ -194,14 +194,23 @@ def main() -> int:
     # ---- detail: every workload, per call -----------------------------------------------------------------
     if not args.no_detail:
         detail = []
-        w2, w3, w4 = wl.config2(), wl.config3(), wl.config4()
+        w2, w3, w4 = wl.config2(), wl.config3_train(), wl.config4()
         cases = [Case("config0_conv16_f32_fwd", wl.config0(), 0)] + step_cases + [
             Case("config2_gshift_bf16_N32_fwd", w2, 0, sets=8),
             Case("config3_depthwise_s2_f32_fwd", w3, 0, sets=6),
             Case("config4_gshift_bf16_N128_fwd", w4, 0, sets=8),
             Case("config4_gshift_bf16_N128_bwd_data", w4, 1, sets=8),
             Case("config4_gshift_bf16_N128_bwd_weight", w4, 2, sets=8),
+            # backward passes of the first two shapes (not named by the configs; the metric is forward + backward)
+            Case("config3_depthwise_s2_f32_bwd_data", w3, 1, sets=6),
+            Case("config3_depthwise_s2_f32_bwd_weight", w3, 2, sets=6),
         ]
+        for bf16 in (False, True):
+            for stage, (C, H) in enumerate(wl.RESNET18_STAGES):
+                wt = wl.config1_train(stage, bf16)
+                tag = f"conv3x3_C{C}_{H}x{H}_N32_{'bf16' if bf16 else 'f32'}"
+                cases.append(Case(tag + "_bwd_data", wt, 1))
+                cases.append(Case(tag + "_bwd_weight", wt, 2))
         for c in cases:
             med, avg = c.time_ms(30)
             tf = c.flops / (med * 1e-3) / 1e12

@@ -126,10 +126,6 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
   const int KHW = p.KH * p.KW;
 
   for (int s = tid; s < p.n_slots; s += NT) slot_src[s] = slot_source(p, R0, rows, g, s);
-  {
-    const int n16 = p.cgrps * p.n_slots * p.Wp;
-    for (int i = tid; i < n16; i += NT) xl[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-  }
   __syncthreads();
 
   // ---- loop-invariant descriptors of what this thread stages per chunk
@@ -347,6 +343,12 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
   // ONE: the whole reduction fits one chunk, so the staging registers are dead once it is in LDS
   const int n_chunks = ONE ? 1 : p.n_chunks;
   fetch(0, std::integral_constant<int, -1>{});
+  // while the first requests travel: zero the X region once (slot edges and rows outside the image are the
+  // window's zero padding and are never written afterwards); the loop's first barrier orders it before staging
+  {
+    const int n16 = p.cgrps * p.n_slots * p.Wp;
+    for (int i = tid; i < n16; i += NT) xl[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
   if constexpr (BF && WF > 0) {
     // Weights straight from [o][c][tap]: a thread takes 8 channels x WF taps of one output channel (8*WF
     // adjacent elements = WF 16-byte loads), re-orders them in registers into one 16-byte piece per tap

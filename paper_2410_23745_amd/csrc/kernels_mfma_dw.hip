@@ -20,6 +20,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <string>
+#include <type_traits>
 
 #include "plan.h"
 
@@ -33,6 +34,7 @@ struct DwParams {
   int32_t ws_g, ws_o, ws_c, ws_kh, ws_kw;   // dW strides
   int32_t w_elems;                     // elements of dW (= stride between partials)
   int32_t pitch, TRK, CP, CPp;         // LDS row pitch, rows per chunk, chunk length (multiple of 32), LDS channel pitch
+  int32_t CPg;                         // fp32 kernel: channel pitch of the G tile (it has no halo rows); CPp is X's
   int32_t rows_per_split, n_splits, n_oblk, n_cblk;
   int32_t n_xrows;                     // rows of X staged per chunk: TRK + KH - 1
   int32_t cpi;                         // KH > 1: chunks per image (chunks do not cross images); else 0
@@ -238,15 +240,17 @@ __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint
 
 // fp32 inputs: the same contraction with v_mfma_f32_16x16x4_f32, whose K-step is 4 consecutive pixels (lane ->
 // row l%16, pixel l/16).  Operands are single dwords, so a tap is any element shift and nothing has to be cut;
-// staging moves single elements, in batches of kF32Batch per thread and tensor.
-constexpr int kF32Batch = 16;
+// staging moves items of VEC adjacent pixels of a row (4 when W is a multiple of 4, else 2 or 1), in batches of
+// about kF32BatchFloats floats per thread and tensor.
+constexpr int kF32BatchFloats = 24;
+constexpr int kF32MaxBatches = 6;
 constexpr int kGuardF = 4;       // zero floats in front of each X channel row
 
-template <int KH, int KW, int CT>
+template <int KH, int KW, int CT, int VEC>
 __global__ __launch_bounds__(256) void dw_mfma_f32(const DwParams p, const float* __restrict__ Gt,
                                                    const float* __restrict__ Xt, float* __restrict__ partial) {
   extern __shared__ __align__(16) unsigned char smem[];
-  float* gl = reinterpret_cast<float*>(smem);                   // [64][CPp]
+  float* gl = reinterpret_cast<float*>(smem);                   // [64][CPg]
   float* xl = reinterpret_cast<float*>(smem + p.lds_x_off);     // [32*CT][CPp], data starts at kGuardF
   int* row_tab = reinterpret_cast<int*>(smem + p.lds_tab_off);  // [2][n_xrows]
   constexpr int CX = 32 * CT, T = KH * KW;
@@ -279,7 +283,7 @@ __global__ __launch_bounds__(256) void dw_mfma_f32(const DwParams p, const float
       for (int t = 0; t < T; ++t) acc[a][b][t] = floatx4{0.f, 0.f, 0.f, 0.f};
   int a_base[2], b_base[CT];     // element indices
 #pragma unroll
-  for (int a = 0; a < 2; ++a) a_base[a] = ((2 * wo + a) * 16 + (lane & 15)) * p.CPp + (lane >> 4);
+  for (int a = 0; a < 2; ++a) a_base[a] = ((2 * wo + a) * 16 + (lane & 15)) * p.CPg + (lane >> 4);
 #pragma unroll
   for (int b = 0; b < CT; ++b) b_base[b] = ((CT * wc + b) * 16 + (lane & 15)) * p.CPp + (lane >> 4) + kGuardF - p.pw;
 
@@ -306,31 +310,55 @@ __global__ __launch_bounds__(256) void dw_mfma_f32(const DwParams p, const float
       row_tab[p.n_xrows + tid] = xo;
     }
     __syncthreads();
-    // stage: item = (channel, row, pixel); rows without a source and channels beyond the tensor become zeros
-    for (int base = 0; base < p.items; base += 256 * kF32Batch) {
-      float gr[kF32Batch], xr[kF32Batch];
-      int lo[kF32Batch];
+    // stage: item = (channel, row, VEC pixels); rows without a source and channels beyond the tensor become zeros
+    {
+      constexpr int BATCH = VEC == 1 ? 16 : kF32BatchFloats / VEC;
+      typedef float vec_t __attribute__((ext_vector_type(VEC == 1 ? 2 : VEC), aligned(4)));
+      const int WV = p.W / VEC;                        // items per row
+      for (int base = 0; base < p.items; base += 256 * BATCH) {
+        float gr[BATCH][VEC], xr[BATCH][VEC];
+        int lo[BATCH], lg[BATCH];       // LDS element offsets in the X and G tiles (-1: nothing to write)
 #pragma unroll
-      for (int k = 0; k < kF32Batch; ++k) {
-        const int idx = base + tid + k * 256;
-        gr[k] = 0.f; xr[k] = 0.f; lo[k] = -1;
-        if (idx < p.items) {
-          const int ch = __umulhi((uint32_t)idx, p.magic_rw2);
-          const int rem = idx - ch * (p.n_xrows * p.W);
-          const int r = __umulhi((uint32_t)rem, p.magic_w2);
-          const int j = rem - r * p.W;
-          const int go = row_tab[r], xo = row_tab[p.n_xrows + r];
-          if (go >= 0 && ch < o_lim) gr[k] = Gg[go + ch * p.plane + j];
-          if (xo >= 0 && ch < c_lim) xr[k] = Xg[xo + ch * p.plane + j];
-          lo[k] = (ch * p.CPp + r * p.pitch + j) | (ch < CX ? 0 : (1 << 30));
+        for (int k = 0; k < BATCH; ++k) {
+          const int idx = base + tid + k * 256;
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) { gr[k][e] = 0.f; xr[k][e] = 0.f; }
+          lo[k] = -1; lg[k] = -1;
+          if (idx < p.items) {
+            const int ch = __umulhi((uint32_t)idx, p.magic_rw2);
+            const int rem = idx - ch * (p.n_xrows * WV);
+            const int r = __umulhi((uint32_t)rem, p.magic_w2);
+            const int j = (rem - r * WV) * VEC;
+            const int go = row_tab[r], xo = row_tab[p.n_xrows + r];
+            if constexpr (VEC == 1) {
+              if (go >= 0 && ch < o_lim) gr[k][0] = Gg[go + ch * p.plane + j];
+              if (xo >= 0 && ch < c_lim) xr[k][0] = Xg[xo + ch * p.plane + j];
+            } else {
+              if (go >= 0 && ch < o_lim) {
+                const vec_t v = *reinterpret_cast<const vec_t*>(Gg + go + ch * p.plane + j);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) gr[k][e] = v[e];
+              }
+              if (xo >= 0 && ch < c_lim) {
+                const vec_t v = *reinterpret_cast<const vec_t*>(Xg + xo + ch * p.plane + j);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) xr[k][e] = v[e];
+              }
+            }
+            if (ch < CX) lo[k] = ch * p.CPp + r * p.pitch + j + kGuardF;
+            if (r < p.TRK) lg[k] = ch * p.CPg + r * p.pitch + j;
+          }
+        }
+#pragma unroll
+        for (int k = 0; k < BATCH; ++k) {
+          if (lg[k] >= 0)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) gl[lg[k] + e] = gr[k][e];
+          if (lo[k] >= 0)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) xl[lo[k] + e] = xr[k][e];
         }
       }
-#pragma unroll
-      for (int k = 0; k < kF32Batch; ++k)
-        if (lo[k] >= 0) {
-          gl[lo[k] & 0xfffff] = gr[k];
-          if (!(lo[k] >> 30)) xl[(lo[k] & 0xfffff) + kGuardF] = xr[k];
-        }
     }
     __syncthreads();
     const int steps = p.CP >> 2;
@@ -476,11 +504,17 @@ bool fill_dw_f32(const syno_plan* plan, DwParams& p) {
   p.w_elems = (int32_t)plan->w_elems;
   p.pitch = c.Wo + std::max(1, std::max(c.pw, c.KW - 1 - c.pw));     // at least one zero column between rows
   const int cx = (c.KH * c.KW <= 3) ? 64 : 32, halo = c.KH - 1;
-  // rows per chunk: about 200 staged pixels per channel and at most 3 batches of items per thread
+  // rows per chunk: about 200 staged pixels per channel, a bounded number of staging batches per thread, and
+  // both tiles within LDS
+  const int vec = (c.Wo % 4 == 0) ? 4 : (c.Wo % 2 == 0) ? 2 : 1;
+  const int budget = kF32MaxBatches * (vec == 1 ? 16 : kF32BatchFloats / vec) * vec * 256;     // floats per tensor and chunk
   int trk = std::max(1, 200 / p.pitch);
   if (c.KH > 1) trk = std::min(trk, c.Ho);
-  while (trk > 1 && 64 * (trk + halo) * c.Wo > 3 * kF32Batch * 256) --trk;
-  if (64 * (trk + halo) * c.Wo > 3 * kF32Batch * 256) return false;
+  auto lds_need = [&](int t) {
+    return (int64_t)64 * (t * p.pitch + 16) * 4 + (int64_t)cx * ((t + halo) * p.pitch + halo * p.pitch + 32) * 4;
+  };
+  while (trk > 1 && (64 * (trk + halo) * c.Wo > budget || lds_need(trk) > 140 * 1024)) --trk;
+  if (64 * (trk + halo) * c.Wo > budget) return false;
   if (c.KH > 1) {
     p.cpi = (c.Ho + trk - 1) / trk;
     trk = (c.Ho + p.cpi - 1) / p.cpi;
@@ -494,9 +528,11 @@ bool fill_dw_f32(const syno_plan* plan, DwParams& p) {
   p.CP = (p.TRK * p.pitch + 3) & ~3;
   p.CPp = (std::max(p.CP, p.n_xrows * p.pitch) + halo * p.pitch + c.KW + kGuardF + 4 + 3) & ~3;
   if (((p.CPp >> 2) & 1) == 0) p.CPp += 4;
-  p.items = 64 * p.n_xrows * c.Wo;
-  p.magic_w2 = magic_of(c.Wo);
-  p.magic_rw2 = magic_of(p.n_xrows * c.Wo);
+  p.CPg = (p.CP + 4 + 3) & ~3;
+  if (((p.CPg >> 2) & 1) == 0) p.CPg += 4;
+  p.items = 64 * p.n_xrows * (c.Wo / vec);
+  p.magic_w2 = magic_of(c.Wo / vec);
+  p.magic_rw2 = magic_of(p.n_xrows * (c.Wo / vec));
   p.n_oblk = (c.Og + 63) / 64;
   p.n_cblk = (c.Cg + cx - 1) / cx;
   const int tiles = c.G * p.n_oblk * p.n_cblk;
@@ -505,10 +541,10 @@ bool fill_dw_f32(const syno_plan* plan, DwParams& p) {
   p.chunks_per_split = (p.n_chunks + splits - 1) / splits;
   p.rows_per_split = p.chunks_per_split * p.TRK;
   p.n_splits = (p.n_chunks + p.chunks_per_split - 1) / p.chunks_per_split;
-  p.lds_x_off = 64 * p.CPp * 4;
+  p.lds_x_off = 64 * p.CPg * 4;
   p.lds_tab_off = p.lds_x_off + cx * p.CPp * 4;
   p.lds_bytes = p.lds_tab_off + ((2 * p.n_xrows * 4 + 15) & ~15);
-  return p.lds_bytes <= 144 * 1024 && 64 * p.CPp < (1 << 20) && p.n_xrows <= 256 &&
+  return p.lds_bytes <= 144 * 1024 && 64 * p.CPp < (1 << 30) && p.n_xrows <= 256 && p.n_xrows <= 256 &&
          (int64_t)64 * p.n_xrows * c.Wo * std::max(c.Wo, p.n_xrows * c.Wo) < (1ll << 32);
 }
 
@@ -563,10 +599,17 @@ syno_status launch_mfma_dw(const syno_plan* plan, const void* A, const void* B, 
         return;
       hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), p.lds_bytes, stream, p, Gf, Xf, partf);
     };
-    if (p.KH == 3 && p.KW == 3) launchf(dw_mfma_f32<3, 3, 1>);
-    else if (p.KH == 3) launchf(dw_mfma_f32<3, 1, 2>);
-    else if (p.KW == 3) launchf(dw_mfma_f32<1, 3, 2>);
-    else launchf(dw_mfma_f32<1, 1, 2>);
+    auto by_vec = [&](auto kh_c, auto kw_c, auto ct_c) {
+      constexpr int kh = decltype(kh_c)::value, kw = decltype(kw_c)::value, ct = decltype(ct_c)::value;
+      if (p.W % 4 == 0) launchf(dw_mfma_f32<kh, kw, ct, 4>);
+      else if (p.W % 2 == 0) launchf(dw_mfma_f32<kh, kw, ct, 2>);
+      else launchf(dw_mfma_f32<kh, kw, ct, 1>);
+    };
+    using std::integral_constant;
+    if (p.KH == 3 && p.KW == 3) by_vec(integral_constant<int, 3>{}, integral_constant<int, 3>{}, integral_constant<int, 1>{});
+    else if (p.KH == 3) by_vec(integral_constant<int, 3>{}, integral_constant<int, 1>{}, integral_constant<int, 2>{});
+    else if (p.KW == 3) by_vec(integral_constant<int, 1>{}, integral_constant<int, 3>{}, integral_constant<int, 2>{});
+    else by_vec(integral_constant<int, 1>{}, integral_constant<int, 1>{}, integral_constant<int, 2>{});
     if ((p.w_elems & 3) == 0 && (reinterpret_cast<uintptr_t>(out) & 15) == 0)
       hipLaunchKernelGGL(dw_reduce4, dim3((p.w_elems / 4 + 63) / 64), dim3(256), 0, stream, reinterpret_cast<const float4*>(partf),
                          static_cast<float4*>(out), p.w_elems / 4, p.n_splits);

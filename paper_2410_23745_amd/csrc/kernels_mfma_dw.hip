@@ -186,37 +186,56 @@ __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint
         }
       }
     __syncthreads();
+    // k-steps of 32 pixels; the LDS reads of the next step are issued before the MFMAs of the current one (one
+    // wave per SIMD here, so nothing else would cover the LDS latency)
     const int steps = p.CP >> 5;
-    for (int st = 0; st < steps; ++st) {
-      bf16x8 a[2];
+    constexpr int NX = KW == 1 ? 2 : 3;      // 16-byte groups of X read per (c-tile, kh)
+    struct Frags { uint4 a[2]; uint4 x[CT * KH][NX]; };
+    auto read = [&](int st, Frags& f) {
 #pragma unroll
-      for (int i = 0; i < 2; ++i) a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(gl + a_base[i] + st * 32));
-      // tap (kh, kw) reads X shifted by kh rows and (kw - pw) elements: element 8 + kw - pw of the 16 read at
-      // row offset kh*pitch (a multiple of 8 elements when KH > 1)
+      for (int i = 0; i < 2; ++i) f.a[i] = *reinterpret_cast<const uint4*>(gl + a_base[i] + st * 32);
 #pragma unroll
       for (int i = 0; i < CT; ++i)
 #pragma unroll
         for (int kh = 0; kh < KH; ++kh) {
           const uint16_t* xp = xl + b_base[i] + st * 32 + kh * p.pitch;
-          const uint4 xlo = *reinterpret_cast<const uint4*>(xp);
-          const uint4 xhi = *reinterpret_cast<const uint4*>(xp + 8);
+#pragma unroll
+          for (int q = 0; q < NX; ++q) f.x[i * KH + kh][q] = *reinterpret_cast<const uint4*>(xp + 8 * q);
+        }
+    };
+    // tap (kh, kw) reads X shifted by kh rows and (kw - pw) elements: element 8 + kw - pw of the groups read at
+    // row offset kh*pitch (a multiple of 8 elements when KH > 1)
+    auto mfmas = [&](const Frags& f) {
+#pragma unroll
+      for (int i = 0; i < CT; ++i)
+#pragma unroll
+        for (int kh = 0; kh < KH; ++kh) {
+          const uint4(&x)[NX] = f.x[i * KH + kh];
           bf16x8 b[KW];
           if constexpr (KW == 1) {
-            b[0] = cut<8>(xlo, xhi);
+            b[0] = cut<8>(x[0], x[1]);
           } else {
-            b[0] = cut<7>(xlo, xhi);
-            b[1] = cut<8>(xlo, xhi);
-            // one more element to the right needs the next group; read it only for this tap
-            const uint4 xnx = *reinterpret_cast<const uint4*>(xp + 16);
-            b[2] = cut<1>(xhi, xnx);
+            b[0] = cut<7>(x[0], x[1]);
+            b[1] = cut<8>(x[0], x[1]);
+            b[2] = cut<1>(x[1], x[2]);     // one more element to the right reaches into the third group
           }
 #pragma unroll
           for (int t = 0; t < KW; ++t)
 #pragma unroll
             for (int ao = 0; ao < 2; ++ao)
-              acc[ao][i][kh * KW + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ao], b[t], acc[ao][i][kh * KW + t], 0, 0, 0);
+              acc[ao][i][kh * KW + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.a[ao]), b[t],
+                                                                               acc[ao][i][kh * KW + t], 0, 0, 0);
         }
+    };
+    Frags f0, f1;
+    read(0, f0);
+    int st = 0;
+    for (; st + 2 < steps; st += 2) {
+      read(st + 1, f1); mfmas(f0);
+      read(st + 2, f0); mfmas(f1);
     }
+    if (st + 1 < steps) { read(st + 1, f1); mfmas(f0); mfmas(f1); }
+    else mfmas(f0);
   }
 
   // partial[split][dW layout]: lane holds 4 consecutive o (rows of D) at one c (column)
@@ -361,10 +380,10 @@ __global__ __launch_bounds__(256) void dw_mfma_f32(const DwParams p, const float
       }
     }
     __syncthreads();
+    // k-steps of 4 pixels; the fragments of the next step are read while the MFMAs of the current one issue
+    // (one wave per SIMD here, so nothing else would cover the LDS latency)
     const int steps = p.CP >> 2;
-#pragma unroll 2
-    for (int st = 0; st < steps; ++st) {
-      float a[2];
+    auto read = [&](int st, float (&a)[2], float (&b)[CT * T]) {
 #pragma unroll
       for (int i = 0; i < 2; ++i) a[i] = gl[a_base[i] + st * 4];
 #pragma unroll
@@ -372,13 +391,26 @@ __global__ __launch_bounds__(256) void dw_mfma_f32(const DwParams p, const float
 #pragma unroll
         for (int kh = 0; kh < KH; ++kh)
 #pragma unroll
-          for (int t = 0; t < KW; ++t) {
-            const float b = xl[b_base[i] + st * 4 + kh * p.pitch + t];
+          for (int t = 0; t < KW; ++t) b[i * T + kh * KW + t] = xl[b_base[i] + st * 4 + kh * p.pitch + t];
+    };
+    auto mfmas = [&](const float (&a)[2], const float (&b)[CT * T]) {
 #pragma unroll
-            for (int ao = 0; ao < 2; ++ao)
-              acc[ao][i][kh * KW + t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[ao], b, acc[ao][i][kh * KW + t], 0, 0, 0);
-          }
+      for (int i = 0; i < CT; ++i)
+#pragma unroll
+        for (int t = 0; t < T; ++t)
+#pragma unroll
+          for (int ao = 0; ao < 2; ++ao)
+            acc[ao][i][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[ao], b[i * T + t], acc[ao][i][t], 0, 0, 0);
+    };
+    float fa0[2], fb0[CT * T], fa1[2], fb1[CT * T];
+    read(0, fa0, fb0);
+    int st = 0;
+    for (; st + 2 < steps; st += 2) {
+      read(st + 1, fa1, fb1); mfmas(fa0, fb0);
+      read(st + 2, fa0, fb0); mfmas(fa1, fb1);
     }
+    if (st + 1 < steps) { read(st + 1, fa1, fb1); mfmas(fa0, fb0); mfmas(fa1, fb1); }
+    else mfmas(fa0, fb0);
   }
 
   float* dst = partial + (int64_t)split * p.w_elems + (int64_t)g * p.ws_g;

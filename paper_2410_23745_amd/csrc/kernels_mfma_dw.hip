@@ -259,10 +259,9 @@ __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint
 
 // fp32 inputs: the same contraction with v_mfma_f32_16x16x4_f32, whose K-step is 4 consecutive pixels (lane ->
 // row l%16, pixel l/16).  Operands are single dwords, so a tap is any element shift and nothing has to be cut;
-// staging moves items of VEC adjacent pixels of a row (4 when W is a multiple of 4, else 2 or 1), in batches of
-// about kF32BatchFloats floats per thread and tensor.
-constexpr int kF32BatchFloats = 24;
-constexpr int kF32MaxBatches = 6;
+// staging moves items of VEC adjacent pixels of a row (4 when W is a multiple of 4, else 2 or 1), at most
+// kF32Items per thread and tensor, which wait in registers while the previous chunk is computed.
+constexpr int kF32Items = 18;     // staging items per thread, tensor and chunk
 constexpr int kGuardF = 4;       // zero floats in front of each X channel row
 
 template <int KH, int KW, int CT, int VEC>
@@ -306,8 +305,29 @@ __global__ __launch_bounds__(256) void dw_mfma_f32(const DwParams p, const float
 #pragma unroll
   for (int b = 0; b < CT; ++b) b_base[b] = ((CT * wc + b) * 16 + (lane & 15)) * p.CPp + (lane >> 4) + kGuardF - p.pw;
 
-  for (int q = chunk_begin; q < chunk_end; ++q) {
-    __syncthreads();
+  // ---- staging items of this thread (the same for every chunk): VEC pixels of (channel, row)
+  typedef float vec_t __attribute__((ext_vector_type(VEC == 1 ? 2 : VEC), aligned(4)));
+  int it_off[kF32Items], it_r[kF32Items], it_lo[kF32Items], it_lg[kF32Items];
+  {
+    const int WV = p.W / VEC;                        // items per row
+#pragma unroll
+    for (int k = 0; k < kF32Items; ++k) {
+      const int idx = tid + k * 256;
+      const int ch = __umulhi((uint32_t)idx, p.magic_rw2);
+      const int rem = idx - ch * (p.n_xrows * WV);
+      const int r = __umulhi((uint32_t)rem, p.magic_w2);
+      const int j = (rem - r * WV) * VEC;
+      const bool used = idx < p.items;
+      it_off[k] = ch * p.plane + j;
+      // bit 30 / 29: this channel exists in G / in X
+      it_r[k] = used ? (r | (ch < o_lim ? (1 << 30) : 0) | (ch < c_lim ? (1 << 29) : 0)) : -1;
+      it_lo[k] = (used && ch < CX) ? ch * p.CPp + r * p.pitch + j + kGuardF : -1;
+      it_lg[k] = (used && r < p.TRK) ? ch * p.CPg + r * p.pitch + j : -1;
+    }
+  }
+  float gr[kF32Items][VEC], xr[kF32Items][VEC];
+  // source rows of chunk q: tab[r] = G row offset, tab[n_xrows + r] = X row offset (-1: none, zeros)
+  auto rows_of = [&](int q, int tab) {     // tab: offset of the table inside row_tab (an index, so that LDS stays LDS)
     if (tid < p.n_xrows) {
       int go = -1, xo = -1;
       if (KH == 1) {
@@ -325,61 +345,63 @@ __global__ __launch_bounds__(256) void dw_mfma_f32(const DwParams p, const float
         const int hx = h0 - p.ph + tid;
         if (tid < rows + KH - 1 && hx >= 0 && hx < p.H) xo = n * p.xs_n + hx * p.W;
       }
-      row_tab[tid] = go;
-      row_tab[p.n_xrows + tid] = xo;
+      row_tab[tab + tid] = go;
+      row_tab[tab + p.n_xrows + tid] = xo;
     }
-    __syncthreads();
-    // stage: item = (channel, row, VEC pixels); rows without a source and channels beyond the tensor become zeros
-    {
-      constexpr int BATCH = VEC == 1 ? 16 : kF32BatchFloats / VEC;
-      typedef float vec_t __attribute__((ext_vector_type(VEC == 1 ? 2 : VEC), aligned(4)));
-      const int WV = p.W / VEC;                        // items per row
-      for (int base = 0; base < p.items; base += 256 * BATCH) {
-        float gr[BATCH][VEC], xr[BATCH][VEC];
-        int lo[BATCH], lg[BATCH];       // LDS element offsets in the X and G tiles (-1: nothing to write)
+  };
+  // global -> registers.  Every item is loaded unconditionally (items without a source read the block's first
+  // elements) so that the requests go out back to back; what has no source is zeroed on the way to LDS.
+  uint32_t g_ok = 0, x_ok = 0;           // bit k: item k of the chunk in flight has a source in G / in X
+  auto load = [&](int tab) {
+    g_ok = 0; x_ok = 0;
 #pragma unroll
-        for (int k = 0; k < BATCH; ++k) {
-          const int idx = base + tid + k * 256;
+    for (int k = 0; k < kF32Items; ++k) {
+      const int r = it_r[k] >= 0 ? (it_r[k] & 0xffff) : 0;
+      const int go = row_tab[tab + r], xo = row_tab[tab + p.n_xrows + r];
+      const bool gv = it_r[k] >= 0 && go >= 0 && (it_r[k] >> 30);
+      const bool xv = it_r[k] >= 0 && xo >= 0 && ((it_r[k] >> 29) & 1);
+      g_ok |= gv ? (1u << k) : 0u;
+      x_ok |= xv ? (1u << k) : 0u;
+      const float* gs = Gg + (gv ? go + it_off[k] : 0);
+      const float* xs = Xg + (xv ? xo + it_off[k] : 0);
+      if constexpr (VEC == 1) {
+        gr[k][0] = *gs;
+        xr[k][0] = *xs;
+      } else {
+        const vec_t a = *reinterpret_cast<const vec_t*>(gs);
+        const vec_t b = *reinterpret_cast<const vec_t*>(xs);
 #pragma unroll
-          for (int e = 0; e < VEC; ++e) { gr[k][e] = 0.f; xr[k][e] = 0.f; }
-          lo[k] = -1; lg[k] = -1;
-          if (idx < p.items) {
-            const int ch = __umulhi((uint32_t)idx, p.magic_rw2);
-            const int rem = idx - ch * (p.n_xrows * WV);
-            const int r = __umulhi((uint32_t)rem, p.magic_w2);
-            const int j = (rem - r * WV) * VEC;
-            const int go = row_tab[r], xo = row_tab[p.n_xrows + r];
-            if constexpr (VEC == 1) {
-              if (go >= 0 && ch < o_lim) gr[k][0] = Gg[go + ch * p.plane + j];
-              if (xo >= 0 && ch < c_lim) xr[k][0] = Xg[xo + ch * p.plane + j];
-            } else {
-              if (go >= 0 && ch < o_lim) {
-                const vec_t v = *reinterpret_cast<const vec_t*>(Gg + go + ch * p.plane + j);
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) gr[k][e] = v[e];
-              }
-              if (xo >= 0 && ch < c_lim) {
-                const vec_t v = *reinterpret_cast<const vec_t*>(Xg + xo + ch * p.plane + j);
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) xr[k][e] = v[e];
-              }
-            }
-            if (ch < CX) lo[k] = ch * p.CPp + r * p.pitch + j + kGuardF;
-            if (r < p.TRK) lg[k] = ch * p.CPg + r * p.pitch + j;
-          }
-        }
-#pragma unroll
-        for (int k = 0; k < BATCH; ++k) {
-          if (lg[k] >= 0)
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) gl[lg[k] + e] = gr[k][e];
-          if (lo[k] >= 0)
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) xl[lo[k] + e] = xr[k][e];
-        }
+        for (int e = 0; e < VEC; ++e) { gr[k][e] = a[e]; xr[k][e] = b[e]; }
       }
     }
+  };
+  auto store = [&]() {                   // registers -> LDS
+#pragma unroll
+    for (int k = 0; k < kF32Items; ++k) {
+      if (it_lg[k] >= 0)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) gl[it_lg[k] + e] = ((g_ok >> k) & 1) ? gr[k][e] : 0.f;
+      if (it_lo[k] >= 0)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) xl[it_lo[k] + e] = ((x_ok >> k) & 1) ? xr[k][e] : 0.f;
+    }
+  };
+
+  // The next chunk travels global -> registers while the current one is computed out of LDS.
+  const int tab[2] = {0, 2 * p.n_xrows};
+  if (chunk_begin < chunk_end) {
+    rows_of(chunk_begin, tab[0]);
+    __syncthreads();                     // (also: the zero fill is complete)
+    load(tab[0]);
+  }
+  for (int q = chunk_begin; q < chunk_end; ++q) {
+    const bool more = q + 1 < chunk_end;
+    const int next = ((q - chunk_begin + 1) & 1) ? tab[1] : tab[0];
+    __syncthreads();                     // the previous chunk is fully consumed
+    store();
+    if (more) rows_of(q + 1, next);
     __syncthreads();
+    if (more) load(next);
     // k-steps of 4 pixels; the fragments of the next step are read while the MFMAs of the current one issue
     // (one wave per SIMD here, so nothing else would cover the LDS latency)
     const int steps = p.CP >> 2;
@@ -539,7 +561,7 @@ bool fill_dw_f32(const syno_plan* plan, DwParams& p) {
   // rows per chunk: about 200 staged pixels per channel, a bounded number of staging batches per thread, and
   // both tiles within LDS
   const int vec = (c.Wo % 4 == 0) ? 4 : (c.Wo % 2 == 0) ? 2 : 1;
-  const int budget = kF32MaxBatches * (vec == 1 ? 16 : kF32BatchFloats / vec) * vec * 256;     // floats per tensor and chunk
+  const int budget = kF32Items * vec * 256;     // floats per tensor and chunk
   int trk = std::max(1, 200 / p.pitch);
   if (c.KH > 1) trk = std::min(trk, c.Ho);
   auto lds_need = [&](int t) {
@@ -575,7 +597,7 @@ bool fill_dw_f32(const syno_plan* plan, DwParams& p) {
   p.n_splits = (p.n_chunks + p.chunks_per_split - 1) / p.chunks_per_split;
   p.lds_x_off = 64 * p.CPg * 4;
   p.lds_tab_off = p.lds_x_off + cx * p.CPp * 4;
-  p.lds_bytes = p.lds_tab_off + ((2 * p.n_xrows * 4 + 15) & ~15);
+  p.lds_bytes = p.lds_tab_off + ((2 * 2 * p.n_xrows * 4 + 15) & ~15);     // two row tables (current and next chunk)
   return p.lds_bytes <= 144 * 1024 && 64 * p.CPp < (1 << 30) && p.n_xrows <= 256 && p.n_xrows <= 256 &&
          (int64_t)64 * p.n_xrows * c.Wo * std::max(c.Wo, p.n_xrows * c.Wo) < (1ll << 32);
 }

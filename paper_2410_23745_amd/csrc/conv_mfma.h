@@ -234,7 +234,7 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
   // A chunk's requests are dealt into kSlices slices (slice_c < 0: all of them).  The first chunk goes out
   // at once; the following ones slice by slice between the first k-steps of the chunk before, because a
   // burst of everything holds the wave at the memory pipeline's queues instead of at its MFMAs.
-  constexpr int kSlices = WK == 1 ? 4 : 1;     // (K-split waves run too few k-steps per chunk to spread anything)
+  constexpr int kSlices = WK == 1 ? 2 : 1;     // (K-split waves run too few k-steps per chunk to spread anything)
   auto load1 = [](const void* src) { return *reinterpret_cast<const XT*>(src); };   // (no arithmetic on the value here: that would wait for it)
   auto fetch = [&](int ch, auto slice_c) {
     constexpr int slice = decltype(slice_c)::value;
@@ -522,12 +522,10 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
         }
       };
       peeled(std::integral_constant<int, 0>{});
-      if constexpr (kSlices > 1) {
-        peeled(std::integral_constant<int, 1>{});
-        peeled(std::integral_constant<int, 2>{});
-        peeled(std::integral_constant<int, 3>{});
-      }
-      static_assert(kSlices == 1 || kSlices == 4, "one peeled iteration per slice");
+      if constexpr (kSlices > 1) peeled(std::integral_constant<int, 1>{});
+      if constexpr (kSlices > 2) peeled(std::integral_constant<int, 2>{});
+      if constexpr (kSlices > 3) peeled(std::integral_constant<int, 3>{});
+      static_assert(kSlices <= 4, "one peeled iteration per slice");
       requested = true;
       for (; rs + 2 < nrs; rs += 2) {
         rowstep(even, std::true_type{});

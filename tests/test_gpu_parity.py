@@ -82,6 +82,9 @@ def small_cases():
     c["conv_f32_5x5"] = lambda: wl.make_conv(2, 8, 9, seed=7, Co=16, K=5, with_grad=True)
     c["conv_f32_1x1"] = lambda: wl.make_conv(2, 16, 7, seed=8, Co=32, K=1, with_grad=True)
     c["conv_f32_stage3_small_batch"] = lambda: wl.make_conv(2, 512, 7, seed=9, with_grad=True)
+    c["conv_bf16_chan_tail"] = lambda: wl.make_conv(2, 80, 10, seed=10, Co=48, bf16=True, with_grad=True)   # 2.5 chunks
+    c["conv_f32_wide_rows"] = lambda: wl.make_conv(1, 8, 6, seed=11, Co=8, Wd=60, with_grad=True)
+    c["conv_bf16_wide_rows"] = lambda: wl.make_conv(1, 8, 5, seed=12, Co=8, Wd=60, bf16=True, with_grad=True)
     c["gshift_bf16"] = lambda: wl.make_gshift(3, seeds=(1, 2, 3), with_grad=True)
     c["gshift_bf16_small_groups"] = lambda: wl.make_gshift(2, seeds=(4, 5, 6), with_grad=True, C=96, H=9, Wd=11, groups=3)
     c["depthwise_f32"] = lambda: wl.make_depthwise(3, 20, 30, seed=2, with_grad=True)

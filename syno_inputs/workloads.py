@@ -122,8 +122,9 @@ def make_conv(N, C, H, seed=0, bf16=False, Co=None, Wd=None, K=3, with_grad=Fals
     return _finish(desc, xs, ws, os, X, W, G, C * K * K)
 
 
-def make_gshift(N, seeds=(0, 0, 0), with_grad=False, C=256, H=14, Wd=14, groups=4, K=3, out_bf16=False) -> Workload:
-    desc = grouped_shift_unfold(N, C, C, H, Wd, groups, K, BF16, BF16 if out_bf16 else F32)
+def make_gshift(N, seeds=(0, 0, 0), with_grad=False, C=256, H=14, Wd=14, groups=4, K=3, out_bf16=False,
+                bf16=True) -> Workload:
+    desc = grouped_shift_unfold(N, C, C, H, Wd, groups, K, BF16 if bf16 else F32, BF16 if out_bf16 else F32)
     Cg = C // groups
     xs, ws, os = (N, C, H, Wd), (C, Cg, K), (N, C, H, Wd)
     streams: Dict[int, Stream] = {}

@@ -87,6 +87,7 @@ def small_cases():
     c["conv_bf16_wide_rows"] = lambda: wl.make_conv(1, 8, 5, seed=12, Co=8, Wd=60, bf16=True, with_grad=True)
     c["gshift_bf16"] = lambda: wl.make_gshift(3, seeds=(1, 2, 3), with_grad=True)
     c["gshift_bf16_small_groups"] = lambda: wl.make_gshift(2, seeds=(4, 5, 6), with_grad=True, C=96, H=9, Wd=11, groups=3)
+    c["gshift_f32"] = lambda: wl.make_gshift(2, seeds=(7, 8, 9), with_grad=True, C=64, H=6, Wd=10, groups=2, bf16=False)
     c["depthwise_f32"] = lambda: wl.make_depthwise(3, 20, 30, seed=2, with_grad=True)
     c["depthwise_f32_odd"] = lambda: wl.make_depthwise(2, 7, 18, seed=3, with_grad=True)
     c["depthwise_f32_even"] = lambda: wl.make_depthwise(2, 5, 28, seed=4, with_grad=True)      # stream kernels, all passes

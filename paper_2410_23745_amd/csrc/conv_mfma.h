@@ -87,8 +87,9 @@ __device__ __forceinline__ int slot_of_row(const MfmaParams& p, int R0, int i) {
 // WNAT (fp32 only): the weight block of one output channel, [KC][KH][KW], is contiguous and 16-byte
 //             aligned in memory, so it is staged with 16-byte loads instead of element by element.
 // KCB: bf16 only: channels per chunk (a compile-time constant there, since it fixes the tap offsets in LDS)
-// WF:  bf16 single-chunk variant only: > 0 = the weights are read as they lie in memory ([o][c][WF taps], the
-//      forward layout) and re-ordered on their way into LDS, instead of coming from the packed copy
+// WF:  bf16: > 0 = the weights are read as they lie in memory ([o][c][WF taps], the forward layout) and re-ordered
+//      on their way into LDS, instead of coming from the packed copy; < 0 = the same for backward-data (single-
+//      chunk variant only)
 // U:   window taps along w handled per "row-step" (3 when KW = 3, else 1): the operands of the U taps sit at
 //      compile-time LDS offsets from one per-lane address, so addresses advance once per row-step.
 // WK:  waves that share one output tile and split each chunk's k-steps among themselves (for shapes whose
@@ -152,8 +153,26 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
   const uint4* Wg16 = nullptr;
   // fp32: one weight element per item, gathered with the operator's strides into [o][c*KHW+tap].
   // bf16: 16-byte pieces of this block's packed image, copied as they are.
-  if constexpr (BF && WF != 0) {
-    // (nothing per chunk: the block is brought in once, below)
+  // bf16, WF > 0: weights as they lie in memory.  An item is 8 channels x WF taps of one output channel of the
+  // chunk (WF adjacent 16-byte loads); on the way into LDS it is re-ordered into one 16-byte piece per tap.
+  constexpr int OCT = BF ? KCB / 8 : 1;                                     // channel octets per chunk
+  constexpr int WP = (BF && WF > 0) ? (BN * OCT + NT - 1) / NT : 1;         // such items per thread
+  constexpr int WFA = WF > 0 ? WF : 1;
+  int wp_src[WP], wp_dst[WP], wp_c[WP];   // element offset in W at chunk 0; LDS piece index at tap 0 (-1: unused);
+                                          // first channel inside the chunk | row beyond Og << 30
+  const uint16_t* Wnat = nullptr;
+  if constexpr (BF && WF > 0) {
+    Wnat = reinterpret_cast<const uint16_t*>(Wv) + (int64_t)g * p.ws_g + (int64_t)nb * BN * p.ws_o;
+#pragma unroll
+    for (int k = 0; k < WP; ++k) {
+      const int idx = tid + k * NT;
+      const int octet = idx % OCT, ol = idx / OCT;
+      wp_src[k] = ol * p.ws_o + octet * 8 * WF;
+      wp_dst[k] = idx < BN * OCT ? ol * ((KCB + 8) / 8) + octet : -1;
+      wp_c[k] = octet * 8 | (nb * BN + ol < p.Og ? 0 : (1 << 30));
+    }
+  } else if constexpr (BF && WF != 0) {
+    // (backward-data of the single-chunk variant: the block is brought in once, below)
   } else if constexpr (BF) {
     Wg16 = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(Wv) +
                                           ((int64_t)(g * p.n_nblocks + nb) * p.n_chunks) * p.w_block);
@@ -227,6 +246,7 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
 
   XV xr[XI][CI];
   WReg wr[WI];
+  uint32_t win[WP][4 * WFA];     // (bf16, WF > 0 only)
   // Loads use a wave-uniform base plus 32-bit byte offsets.  Items without a source read offset 0 (any
   // valid address) and are simply not written to LDS, so the common path has no per-load predicate.
   const bool chan_tail = (p.Cg % p.KC) != 0;
@@ -270,7 +290,21 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
           }
         }
     }
-    if constexpr (BF && WF != 0) {
+    if constexpr (BF && WF > 0) {
+      // unconditional loads (what has no source reads the block's first elements and is zeroed when staged)
+      typedef uint32_t u32x4_unaligned __attribute__((ext_vector_type(4), aligned(2)));
+#pragma unroll
+      for (int k = 0; k < WP; ++k) {
+        const bool live = wp_dst[k] >= 0 && !(wp_c[k] >> 30) && c0 + (wp_c[k] & 0xffff) < p.Cg;
+        const uint16_t* src = Wnat + (live ? wp_src[k] + c0 * WF : 0);
+#pragma unroll
+        for (int q = 0; q < WFA; ++q)
+          if (want(XI * CI + k * WFA + q)) {
+            const u32x4_unaligned v = *reinterpret_cast<const u32x4_unaligned*>(src + q * 8);
+            win[k][4 * q + 0] = v[0]; win[k][4 * q + 1] = v[1]; win[k][4 * q + 2] = v[2]; win[k][4 * q + 3] = v[3];
+          }
+      }
+    } else if constexpr (BF && WF != 0) {
     } else if constexpr (BF) {
       const uint4* src = Wg16 + (int64_t)ch * (p.w_block >> 3);
 #pragma unroll
@@ -292,7 +326,8 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
       }
     }
   };
-  auto stage = [&]() {
+  auto stage = [&](int ch) {
+    (void)ch;
 #pragma unroll
     for (int k = 0; k < XI; ++k)
       if (x_goff[k] >= 0) {
@@ -321,7 +356,27 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
           (void)dst;
         }
       }
-    if constexpr (BF && WF != 0) {
+    if constexpr (BF && WF > 0) {
+      uint4* wl = reinterpret_cast<uint4*>(smem + p.lds_w_off);
+      const int c0 = ch * p.KC;
+#pragma unroll
+      for (int k = 0; k < WP; ++k)
+        if (wp_dst[k] >= 0) {
+          const bool live = !(wp_c[k] >> 30) && c0 + (wp_c[k] & 0xffff) < p.Cg;
+#pragma unroll
+          for (int tap = 0; tap < WFA; ++tap) {
+            uint32_t d[4];
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+              // channels 2h and 2h+1 of this tap: elements (2h)*WF+tap and (2h+1)*WF+tap of the 8*WF loaded ones
+              const int e0 = (2 * h) * WFA + tap, e1 = (2 * h + 1) * WFA + tap;
+              const uint32_t sel = ((e0 & 1) ? 0x0302u : 0x0100u) | ((e1 & 1) ? 0x07060000u : 0x05040000u);
+              d[h] = live ? __builtin_amdgcn_perm(win[k][e1 >> 1], win[k][e0 >> 1], sel) : 0u;
+            }
+            wl[tap * BN * ((KCB + 8) / 8) + wp_dst[k]] = make_uint4(d[0], d[1], d[2], d[3]);
+          }
+        }
+    } else if constexpr (BF && WF != 0) {
     } else if constexpr (BF) {
       uint4* wl = reinterpret_cast<uint4*>(smem + p.lds_w_off);
 #pragma unroll
@@ -348,39 +403,6 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
   {
     const int n16 = p.cgrps * p.n_slots * p.Wp;
     for (int i = tid; i < n16; i += NT) xl[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-  }
-  if constexpr (BF && WF > 0) {
-    // Weights straight from [o][c][tap]: a thread takes 8 channels x WF taps of one output channel (8*WF
-    // adjacent elements = WF 16-byte loads), re-orders them in registers into one 16-byte piece per tap
-    // (8 channels each) and writes those to [tap][o][c].  Runs while the X requests above are in flight.
-    static_assert(ONE, "only the single-chunk variant stages weights this way");
-    typedef uint32_t u32x4_unaligned __attribute__((ext_vector_type(4), aligned(2)));
-    constexpr int OCT = KCB / 8, ROW8 = (KCB + 8) / 8;
-    const uint16_t* Wt = reinterpret_cast<const uint16_t*>(Wv) + (int64_t)g * p.ws_g + (int64_t)nb * BN * p.ws_o;
-    uint4* wl = reinterpret_cast<uint4*>(smem + p.lds_w_off);
-    for (int i = tid; i < BN * OCT; i += NT) {
-      const int octet = i % OCT, ol = i / OCT;
-      const bool live = nb * BN + ol < p.Og && octet * 8 < p.Cg;
-      uint32_t in[4 * WF];
-#pragma unroll
-      for (int q = 0; q < WF; ++q) {
-        u32x4_unaligned v = {0, 0, 0, 0};
-        if (live) v = *reinterpret_cast<const u32x4_unaligned*>(Wt + (int64_t)ol * p.ws_o + octet * 8 * WF + q * 8);
-        in[4 * q + 0] = v[0]; in[4 * q + 1] = v[1]; in[4 * q + 2] = v[2]; in[4 * q + 3] = v[3];
-      }
-#pragma unroll
-      for (int tap = 0; tap < WF; ++tap) {
-        uint32_t d[4];
-#pragma unroll
-        for (int h = 0; h < 4; ++h) {
-          // channels 2h and 2h+1 of this tap: elements (2h)*WF+tap and (2h+1)*WF+tap of the 8*WF loaded ones
-          const int e0 = (2 * h) * WF + tap, e1 = (2 * h + 1) * WF + tap;
-          const uint32_t sel = ((e0 & 1) ? 0x0302u : 0x0100u) | ((e1 & 1) ? 0x07060000u : 0x05040000u);
-          d[h] = __builtin_amdgcn_perm(in[e1 >> 1], in[e0 >> 1], sel);
-        }
-        wl[(tap * BN + ol) * ROW8 + octet] = make_uint4(d[0], d[1], d[2], d[3]);
-      }
-    }
   }
   if constexpr (BF && WF < 0) {
     // The same for the backward-data adjoint: the B operand's rows are the forward input channels and its
@@ -413,7 +435,7 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
   }
   for (int ch = 0; ch < n_chunks; ++ch) {
     __syncthreads();   // everyone has finished reading the previous chunk
-    stage();
+    stage(ch);
     __syncthreads();
     const bool more = ch + 1 < n_chunks;   // the next chunk travels while this one is computed
     bool requested = false;

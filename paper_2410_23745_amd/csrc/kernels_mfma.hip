@@ -196,12 +196,14 @@ bool fill_params(const syno_plan* plan, int which, int vi, int TR, MfmaParams& p
     if (v.one && p.Cg > p.KC) return false;
     p.w_row = p.KC + 8;                          // elements; 80- and 144-byte rows keep B-fragment reads conflict free
     p.w_block = KHW * p.BN * p.w_row;
-    if ((p.w_block >> 3) > v.WI * v.NT()) return false;
-    // the single-chunk variant takes forward-layout weights [o][c][taps] unpacked when the taps are 1, 3 or 9
-    // (backward-data: the same tensor read through the adjoint, marked by a negative count)
+    // Forward-layout weights [o][c][taps] are read unpacked: by every variant when there are 9 taps, by the
+    // single-chunk variant also with 3 or 1 (and through the adjoint for backward-data, marked by a negative count)
     const bool fwd_layout = (c.KW == 1 || c.ws_kw == 1) && (c.KH == 1 || c.ws_kh == c.KW) && c.ws_c == KHW;
-    if (v.one && fwd_layout && (c.Cg & 7) == 0 && (KHW == 1 || KHW == 3 || KHW == 9))
-      p.wf = which == SYNO_FWD ? KHW : -KHW;
+    if (fwd_layout && (c.Cg & 7) == 0) {
+      if (which == SYNO_FWD && (KHW == 9 || (v.one && (KHW == 1 || KHW == 3)))) p.wf = KHW;
+      if (which == SYNO_BWD_DATA && v.one && (KHW == 1 || KHW == 3 || KHW == 9)) p.wf = -KHW;
+    }
+    if (p.wf == 0 && (p.w_block >> 3) > v.WI * v.NT()) return false;
   } else if (v.wnat) {
     if ((c.KW > 1 && p.ws_kw != 1) || (c.KH > 1 && p.ws_kh != c.KW) || p.ws_c != KHW || (p.ws_o & 3) || (p.ws_g & 3))
       return false;

@@ -4,8 +4,11 @@
 namespace syno {
 
 void launch_mfma_bf16_f32out(int vi, const MfmaParams& p, const void* X, const void* W, void* out, hipStream_t s) {
-#define SYNO_CASE(VI) \
-  case VI: launch_variant<true, VI, 1, 0, false>(p, X, W, out, s); break;
+#define SYNO_CASE(VI)                                                 \
+  case VI:                                                            \
+    if (p.wf == 9) launch_variant<true, VI, 1, 9, false>(p, X, W, out, s); \
+    else launch_variant<true, VI, 1, 0, false>(p, X, W, out, s);       \
+    break;
   switch (vi) {
     SYNO_CASE(0) SYNO_CASE(1) SYNO_CASE(2) SYNO_CASE(3) SYNO_CASE(4) SYNO_CASE(5) SYNO_CASE(7) SYNO_CASE(8) SYNO_CASE(9)
     case 6:   // single chunk: packed weights, or weights as they lie in memory with 1, 3 or 9 taps per channel (negative: backward-data)

@@ -146,8 +146,10 @@ def test_kernel_choice(syno):
     # backward-weight keeps its split partials there
     assert p.workspace_bytes(syno.FWD) == 0 and p.workspace_bytes(syno.BWD_DATA) == 0
     assert p.workspace_bytes(syno.BWD_WEIGHT) > 0
-    # more channels than one chunk holds: bf16 weights are packed, fp32 backward-data weights transposed, into it
-    assert syno.Plan(wl.conv2d(32, 128, 128, 28, 28, 3, 3, BF16, F32)).workspace_bytes(syno.FWD) > 0
+    # more channels than one chunk holds: bf16 backward-data packs its weights into the workspace (forward reads
+    # them as they lie), fp32 backward-data transposes them into it
+    p = syno.Plan(wl.conv2d(32, 128, 128, 28, 28, 3, 3, BF16, F32))
+    assert p.workspace_bytes(syno.FWD) == 0 and p.workspace_bytes(syno.BWD_DATA) > 0
     assert syno.Plan(wl.conv2d(32, 128, 128, 28, 28)).workspace_bytes(syno.BWD_DATA) == 128 * 128 * 9 * 4
     assert "grid=" in p.describe(syno.FWD)
     syno.set_kernel_policy(1)

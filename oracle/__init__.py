@@ -145,6 +145,35 @@ def backward(desc, X, W, G, want_dx: bool = True, want_dw: bool = True,
     return dX, dW
 
 
+def chain_forward(descs, X, Ws, quantize=None):
+    """An operator given as consecutive stages (the result of the materialised-reduction pass of the paper's
+    code-generation section; Operator 1 of Fig. 7 is two of them): stage i is evaluated on the output of stage
+    i-1, reinterpreted in stage i's input shape (same row-major memory).  Returns every stage's output; the
+    last is the operator's.  `quantize`, if given, is applied to each intermediate tensor (the element type the
+    intermediate is stored in)."""
+    outs = []
+    cur = _f64(X)
+    for i, (d, W) in enumerate(zip(descs, Ws)):
+        cur = forward(d, cur.reshape(-1), W)
+        if quantize is not None and i + 1 < len(descs):
+            cur = _f64(quantize(cur))
+        outs.append(cur)
+    return outs
+
+
+def chain_backward(descs, X, Ws, G, quantize=None):
+    """Gradients of L = sum(out*G) through the stages by the chain rule: stage i's gradient with respect to its
+    input is the output gradient of stage i-1.  Returns (dX, [dW_i]).  `quantize` is applied to the intermediate
+    tensors of the forward sweep and to the intermediate gradients, as in `chain_forward`."""
+    acts = [_f64(X)] + chain_forward(descs, X, Ws, quantize)[:-1]
+    g = _f64(G)
+    dWs = [None] * len(descs)
+    for i in range(len(descs) - 1, -1, -1):
+        dA, dWs[i] = backward(descs[i], acts[i].reshape(-1), Ws[i], g.reshape(-1))
+        g = dA if (quantize is None or i == 0) else _f64(quantize(dA))
+    return g, dWs
+
+
 def gather_map(desc, o_flat, r_flat):
     """Flat offsets into X and W of the listed loop-nest points; both -1 where an Unfold is out of range."""
     w = wire(desc)

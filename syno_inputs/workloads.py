@@ -80,6 +80,30 @@ def matmul(M, N, K, in_dtype=F32, out_dtype=F32) -> OpDesc:
     return b.finish([0, rx], [rw, 1], in_dtype, out_dtype)
 
 
+def operator1_stage1(N, Cin, Co, H, W, g=4, s=2, k1=3, in_dtype=F32, out_dtype=F32) -> OpDesc:
+    """First stage of Operator 1 (Fig. 7): a 1 x k1 window along w, contracted over the channels of one group
+    only; the window iterator k is Shared with the weight but NOT Reduced, so it survives as an output axis.
+
+    Z[n,d,gi,k,h,w] = sum_{c'} X[n, gi*Cg+c', h, w+k-k1/2] * w1[d, gi*Cg+c', k],   Cg = Cin/g, d < Co/g/s."""
+    D, Cg = Co // g // s, Cin // g
+    b = Builder([("n", N), ("d", D), ("gi", g), ("k", k1), ("h", H), ("w", W)],
+                name=f"op1_stage1_C{Cin}_Co{Co}_g{g}_s{s}_{H}x{W}_N{N}")
+    n, d, gi, k, h, w = range(6)
+    c = b.reduce(Cg)
+    cx, cw = b.share(c)
+    gx, gw = b.share(gi)
+    kx, kw = b.share(k)
+    cin = b.split(gx, cx)
+    ww = b.unfold(w, kx)
+    return b.finish([n, cin, h, ww], [d, gw, cw, kw], in_dtype, out_dtype)
+
+
+def operator1_stage2(N, Co, H, W, s=2, k1=3, in_dtype=F32, out_dtype=F32) -> OpDesc:
+    """Second stage of Operator 1: the first stage's axes (d,gi,k) flattened into k1*Co/s channels, a k1 x 1
+    window along h, everything contracted with w2[Co, (k1*Co/s)*k1]."""
+    return conv2d(N, k1 * Co // s, Co, H, W, k1, 1, in_dtype, out_dtype)
+
+
 # ----------------------------------------------------------------------------
 # Workloads = pGraph + seeded tensors
 # ----------------------------------------------------------------------------
@@ -149,6 +173,53 @@ def make_depthwise(N, C, H_in, seed=0, S=2, K=3, with_grad=False) -> Workload:
     return _finish(desc, xs, ws, os, X, W, G, K * K)
 
 
+@dataclass
+class ChainWorkload:
+    """An operator evaluated as consecutive stages; the output of one stage is the data input of the next."""
+    descs: list
+    x_shape: tuple
+    w_shapes: list
+    inter_shapes: list            # shapes of the tensors between the stages
+    out_shape: tuple
+    X: np.ndarray
+    Ws: list
+    G: Optional[np.ndarray]
+    X_bits: Optional[np.ndarray]
+    Ws_bits: Optional[list]
+    G_bits: Optional[np.ndarray]
+    flops: int                    # sum over the stages of 2 * prod(output iterators) * prod(Reduce sizes)
+
+
+def make_operator1(N, C, H, seed=0, bf16=False, Co=None, Wd=None, g=4, s=2, k1=3, with_grad=False) -> ChainWorkload:
+    """Operator 1 of the paper (Fig. 7) as its two materialised stages, on a ResNet-style layer shape.
+    Weights ~ U(+-1/sqrt(fan_in)) per stage; the whole chain runs in one element type."""
+    Co = C if Co is None else Co
+    Wd = H if Wd is None else Wd
+    dt = BF16 if bf16 else F32
+    D, Cg, C2 = Co // g // s, C // g, k1 * Co // s
+    d1 = operator1_stage1(N, C, Co, H, Wd, g, s, k1, dt, dt)
+    d2 = operator1_stage2(N, Co, H, Wd, s, k1, dt, dt)
+    st = Stream(seed)
+    xs, zs, os = (N, C, H, Wd), (N, D, g, k1, H, Wd), (N, Co, H, Wd)
+    w1s, w2s = (D, g, Cg, k1), (Co, C2, k1, 1)
+    X = st.normal(xs)
+    W1 = st.uniform_pm(1.0 / np.sqrt(Cg), w1s)
+    W2 = st.uniform_pm(1.0 / np.sqrt(C2 * k1), w2s)
+    G = st.normal(os) if with_grad else None
+    Xb = Gb = None
+    Wb = None
+    if bf16:
+        Xb = to_bf16_bits(X)
+        X = bf16_bits_to_f32(Xb)
+        Wb = [to_bf16_bits(W1), to_bf16_bits(W2)]
+        W1, W2 = bf16_bits_to_f32(Wb[0]), bf16_bits_to_f32(Wb[1])
+        if G is not None:
+            Gb = to_bf16_bits(G)
+            G = bf16_bits_to_f32(Gb)
+    flops = 2 * int(np.prod(zs)) * Cg + 2 * int(np.prod(os)) * C2 * k1
+    return ChainWorkload([d1, d2], xs, [w1s, w2s], [zs], os, X, [W1, W2], G, Xb, Wb, Gb, flops)
+
+
 RESNET18_STAGES = ((64, 56), (128, 28), (256, 14), (512, 7))
 
 
@@ -181,3 +252,9 @@ def config3_train(N: int = 64) -> Workload:
 
 def config4(N: int = 128) -> Workload:
     return make_gshift(N, seeds=(1, 2, 3), with_grad=True)
+
+
+def operator1(stage: int, bf16: bool, N: int = 32, with_grad: bool = True) -> ChainWorkload:
+    """Operator 1 in place of the 3x3 convolution of a ResNet-18 stage (g = 4, s = 2, k1 = 3)."""
+    C, H = RESNET18_STAGES[stage]
+    return make_operator1(N, C, H, seed=0, bf16=bf16, with_grad=with_grad)

@@ -421,6 +421,120 @@ def test_flop_rule(oracle):
 
 
 # --------------------------------------------------------------------------------------
+# Operators evaluated in stages: materialised reduction (code-generation section) and Operator 1 (Fig. 7)
+# --------------------------------------------------------------------------------------
+@pytest.mark.parametrize("H,k,s", [(12, 3, 2), (12, 3, 4), (15, 5, 3), (8, 1, 2)])
+def test_materialised_reduction_equals_single_loop_nest(oracle, H, k, s):
+    """The example of the code-generation section: Y[i] = sum_{ik,is} X[s*(i+ik-k/2)+is] evaluated as one loop
+    nest of (H/s)*k*s points equals Z[i'] = sum_is X[s*i'+is] followed by Y[i] = sum_ik Z[i+ik-k/2], and the
+    FLOPs drop from k*H to (1+k/s)*H."""
+    Hs = H // s
+    b = Builder([("i", Hs)])
+    ik, i_s = b.reduce(k), b.reduce(s)
+    whole = b.finish([b.split(b.unfold(0, ik), i_s)], [])
+    b1 = Builder([("i", Hs)])
+    st1 = b1.finish([b1.split(0, b1.reduce(s))], [])
+    b2 = Builder([("i", Hs)])
+    st2 = b2.finish([b2.unfold(0, b2.reduce(k))], [])
+    X, one = rnd((H,), 40), np.ones(1)
+    ref = oracle.forward(whole, X, one)
+    Z, Y = oracle.chain_forward([st1, st2], X, [one, one])
+    np.testing.assert_allclose(Z, X.reshape(Hs, s).sum(1), rtol=0, atol=1e-13)
+    np.testing.assert_allclose(Y, ref, rtol=0, atol=1e-13)
+    points = lambda d: int(np.prod(oracle.out_shape(d))) * int(np.prod(oracle.describe(d)[2]))
+    assert points(whole) == k * H
+    assert s * (points(st1) + points(st2)) == (s + k) * H
+
+
+def operator1_single_sum(X, w1, w2, g, k1):
+    """Operator 1 as ONE contraction with two weights, every loop written out: the window iterator k indexes X,
+    w1 and w2; the second window iterator j indexes X and w2; terms outside the image are dropped."""
+    N, Cin, H, W = X.shape
+    D, Co, Cg = w1.shape[0], w2.shape[0], Cin // g
+    out = np.zeros((N, Co, H, W))
+    for n, h, w, d, gi, k, j in itertools.product(range(N), range(H), range(W), range(D), range(g), range(k1),
+                                                  range(k1)):
+        y, x = h + j - k1 // 2, w + k - k1 // 2
+        if not (0 <= y < H and 0 <= x < W):
+            continue
+        t = 0.0
+        for c in range(Cg):
+            t += X[n, gi * Cg + c, y, x] * w1[d, gi * Cg + c, k]
+        out[n, :, h, w] += t * w2[:, ((d * g + gi) * k1 + k) * k1 + j]
+    return out
+
+
+@pytest.mark.parametrize("N,Cin,Co,H,W,g,s,k1", [(1, 4, 8, 4, 5, 2, 2, 3), (2, 6, 6, 3, 4, 3, 1, 3),
+                                                 (1, 4, 4, 5, 3, 1, 2, 1), (1, 2, 4, 6, 6, 2, 1, 5)])
+def test_operator1_stages_equal_single_two_weight_sum(oracle, N, Cin, Co, H, W, g, s, k1):
+    d1 = wl.operator1_stage1(N, Cin, Co, H, W, g, s, k1)
+    d2 = wl.operator1_stage2(N, Co, H, W, s, k1)
+    D, C2 = Co // g // s, k1 * Co // s
+    X, w1, w2 = rnd((N, Cin, H, W), 41), rnd((D, Cin, k1), 42), rnd((Co, C2 * k1), 43)
+    assert oracle.describe(d1)[:2] == ((N, Cin, H, W), (D, g, Cin // g, k1))
+    assert oracle.describe(d2)[:2] == ((N, C2, H, W), (Co, C2, k1, 1))
+    Z, Y = oracle.chain_forward([d1, d2], X, [w1, w2])
+    assert Z.shape == (N, D, g, k1, H, W) and Y.shape == (N, Co, H, W)
+    np.testing.assert_allclose(Y, operator1_single_sum(X, w1, w2, g, k1), rtol=0, atol=1e-12)
+
+
+def test_operator1_equals_library_convolutions(oracle):
+    """Stage 1 is, per window position k, a grouped 1x1 convolution of X moved by k-k1/2 along w; stage 2 is a
+    k1 x 1 convolution over the flattened (d,gi,k) channels.  Both from the library, in fp64."""
+    N, Cin, Co, H, W, g, s, k1 = 2, 8, 16, 6, 7, 4, 2, 3
+    D, Cg, C2 = Co // g // s, Cin // g, k1 * Co // s
+    X, w1, w2 = rnd((N, Cin, H, W), 44), rnd((D, Cin, k1), 45), rnd((Co, C2 * k1), 46)
+    xt = torch.from_numpy(X)
+    xp = torch.nn.functional.pad(xt, (k1 // 2, k1 // 2))
+    Zt = torch.empty(N, D, g, k1, H, W, dtype=torch.float64)
+    for k in range(k1):
+        wk = torch.from_numpy(w1[:, :, k]).reshape(D, g, Cg).permute(1, 0, 2).reshape(g * D, Cg, 1, 1)
+        zk = torch.nn.functional.conv2d(xp[..., k:k + W], wk, groups=g)          # channels ordered (gi, d)
+        Zt[:, :, :, k] = zk.reshape(N, g, D, H, W).permute(0, 2, 1, 3, 4)
+    Yt = torch.nn.functional.conv2d(Zt.reshape(N, C2, H, W), torch.from_numpy(w2).reshape(Co, C2, k1, 1),
+                                    padding=(k1 // 2, 0))
+    d1 = wl.operator1_stage1(N, Cin, Co, H, W, g, s, k1)
+    d2 = wl.operator1_stage2(N, Co, H, W, s, k1)
+    Z, Y = oracle.chain_forward([d1, d2], X, [w1, w2])
+    np.testing.assert_allclose(Z, Zt.numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(Y, Yt.numpy(), rtol=0, atol=1e-12)
+
+
+def test_operator1_chain_gradients_match_central_differences(oracle):
+    N, Cin, Co, H, W, g, s, k1 = 1, 4, 8, 4, 5, 2, 2, 3
+    descs = [wl.operator1_stage1(N, Cin, Co, H, W, g, s, k1), wl.operator1_stage2(N, Co, H, W, s, k1)]
+    shapes = [oracle.describe(d)[1] for d in descs]
+    X, G = rnd((N, Cin, H, W), 47), rnd((N, Co, H, W), 48)
+    Ws = [rnd(shapes[0], 49), rnd(shapes[1], 50)]
+    dX, dWs = oracle.chain_backward(descs, X, Ws, G)
+    loss = lambda x, ws: float((oracle.chain_forward(descs, x, ws)[-1] * G).sum())
+    rng = np.random.default_rng(1)
+    for _ in range(8):
+        i = tuple(rng.integers(0, n) for n in X.shape)
+        e = np.zeros(X.shape)
+        e[i] = 0.5
+        assert abs((loss(X + e, Ws) - loss(X - e, Ws)) - dX[i]) < 1e-9       # the loss is linear in X
+        for m in range(2):
+            j = tuple(rng.integers(0, n) for n in shapes[m])
+            e = np.zeros(shapes[m])
+            e[j] = 0.5
+            up = [w + e if q == m else w for q, w in enumerate(Ws)]
+            dn = [w - e if q == m else w for q, w in enumerate(Ws)]
+            assert abs((loss(X, up) - loss(X, dn)) - dWs[m][j]) < 1e-9         # and linear in each weight
+
+
+def test_chain_quantize_hook_rounds_only_intermediates(oracle):
+    from syno_inputs.rng import bf16_bits_to_f32, to_bf16_bits
+    q = lambda a: bf16_bits_to_f32(to_bf16_bits(np.asarray(a, dtype=np.float32)))
+    w = wl.make_operator1(1, 8, 5, g=2, s=2, bf16=True, with_grad=True)
+    Z, Y = oracle.chain_forward(w.descs, w.X, w.Ws, quantize=q)
+    Z0, _ = oracle.chain_forward(w.descs, w.X, w.Ws)
+    np.testing.assert_array_equal(Z, q(Z0).astype(np.float64))
+    np.testing.assert_array_equal(Y, oracle.forward(w.descs[1], Z.reshape(-1), w.Ws[1]))
+    assert not np.array_equal(Y, q(Y).astype(np.float64))
+
+
+# --------------------------------------------------------------------------------------
 # Descriptor validation
 # --------------------------------------------------------------------------------------
 def test_rejects_bad_descriptors(oracle):

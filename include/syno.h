@@ -146,6 +146,38 @@ syno_status syno_debug_gather(const syno_plan* plan, int which, const int64_t* t
 syno_status syno_debug_gather_host(const syno_plan* plan, int which, const int64_t* t_flat, const int64_t* q_flat,
                                    int64_t n, int32_t* a_off, int32_t* b_off);
 
+/* ---- Operators evaluated in stages ---------------------------------------------------------------
+ * The materialised-reduction pass of the paper's code-generation section cuts a pGraph with several
+ * weights into sub-graphs whose results are stored, so that a Reduce above a one-to-many primitive is
+ * evaluated once; Operator 1 (Fig. 7) becomes two such stages.  A chain is n_stages >= 1 single-weight
+ * pGraphs: the data input of stage i+1 is the output of stage i (equal element count and element type;
+ * the memory is reinterpreted row-major in stage i+1's input shape).
+ *
+ * W, act, dW are HOST arrays of DEVICE pointers: W[i] / dW[i] belong to stage i, act[i] (i < n_stages-1) is
+ * the output of stage i.  The caller owns the act buffers: the forward call writes them and the backward
+ * call reads them again (saved activations); with one stage `act` may be NULL. */
+typedef struct syno_chain syno_chain;
+
+/* Plans every stage.  Errors of syno_plan_create apply per stage; SYNO_ERR_SHAPE when consecutive stages do
+ * not fit (element count or element type), or n_stages is outside 1..8. */
+syno_status syno_chain_create(const syno_desc* stages, int32_t n_stages, syno_chain** chain);
+syno_status syno_chain_destroy(syno_chain* chain);
+/* Number of stages, and the plan of one stage (borrowed; valid until the chain is destroyed; NULL when out of range). */
+int32_t syno_chain_stages(const syno_chain* chain);
+const syno_plan* syno_chain_plan(const syno_chain* chain, int32_t stage);
+/* Device workspace of the forward sweep (which = 0) or the backward sweep (which = 1). */
+syno_status syno_chain_workspace_bytes(const syno_chain* chain, int which, size_t* bytes);
+/* out = stage[n-1](... stage[0](X, W[0]) ..., W[n-1]); the stages run in order on `stream`. */
+syno_status syno_chain_forward(const syno_chain* chain, const void* X, const void* const* W, void* const* act,
+                               void* out, void* workspace, hipStream_t stream);
+/* Gradients of L = sum(out*G) by the chain rule, last stage first: dW[i] (fp32) for every stage and dX (may
+ * be NULL: not computed).  Intermediate gradients live in the workspace, in the element type of the stage
+ * that consumes them.  SYNO_ERR_UNSUPPORTED when some stage's dX type differs from the gradient type the stage
+ * before it expects (out_dtype of stage i+1 != in_dtype of stage i). */
+syno_status syno_chain_backward(const syno_chain* chain, const void* X, const void* const* W,
+                                const void* const* act, const void* G, void* dX, void* const* dW,
+                                void* workspace, hipStream_t stream);
+
 const char* syno_status_string(syno_status s);
 
 #ifdef __cplusplus

@@ -15,7 +15,9 @@ _lib = None
 
 EXPORTS = ("syno_plan_create", "syno_plan_destroy", "syno_forward", "syno_backward_data", "syno_backward_weight",
            "syno_plan_workspace_bytes", "syno_plan_shapes", "syno_plan_kernel", "syno_plan_describe", "syno_set_kernel_policy",
-           "syno_plan_free_size", "syno_debug_gather", "syno_debug_gather_host", "syno_status_string")
+           "syno_plan_free_size", "syno_debug_gather", "syno_debug_gather_host", "syno_status_string",
+           "syno_chain_create", "syno_chain_destroy", "syno_chain_stages", "syno_chain_plan",
+           "syno_chain_workspace_bytes", "syno_chain_forward", "syno_chain_backward")
 
 
 class _Dim(ctypes.Structure):
@@ -70,8 +72,17 @@ def load_library():
     lib.syno_debug_gather_host.argtypes = [vp, ctypes.c_int, vp, vp, ctypes.c_int64, vp, vp]
     lib.syno_status_string.argtypes = [ctypes.c_int]
     lib.syno_status_string.restype = ctypes.c_char_p
+    vpp = ctypes.POINTER(vp)
+    lib.syno_chain_create.argtypes = [ctypes.POINTER(_Desc), ctypes.c_int32, ctypes.POINTER(vp)]
+    lib.syno_chain_destroy.argtypes = [vp]
+    lib.syno_chain_stages.argtypes = [vp]
+    lib.syno_chain_plan.argtypes = [vp, ctypes.c_int32]
+    lib.syno_chain_plan.restype = vp
+    lib.syno_chain_workspace_bytes.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
+    lib.syno_chain_forward.argtypes = [vp, vp, vpp, vpp, vp, vp, vp]
+    lib.syno_chain_backward.argtypes = [vp, vp, vpp, vpp, vp, vp, vpp, vp, vp]
     for name in EXPORTS:
-        if name not in ("syno_plan_kernel", "syno_status_string"):
+        if name not in ("syno_plan_kernel", "syno_status_string", "syno_chain_plan"):
             getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -87,32 +98,42 @@ def set_kernel_policy(policy: int) -> None:
 _TORCH_DTYPE = {0: torch.float32, 1: torch.bfloat16}
 
 
+def _marshal(desc):
+    """OpDesc-like object -> (syno_desc, objects that must stay alive while it is used)."""
+    dims = (_Dim * max(1, len(desc.out_dims)))()
+    names = [str(n).encode() for n, _ in desc.out_dims]
+    for i, (_, s) in enumerate(desc.out_dims):
+        dims[i].name, dims[i].size = names[i], int(s)
+    prims = (_Prim * max(1, len(desc.prims)))()
+    for i, p in enumerate(desc.prims):
+        prims[i].kind = int(p.kind)
+        ins = list(p.ins) + [-1] * (2 - len(p.ins))
+        outs = list(p.outs) + [-1] * (2 - len(p.outs))
+        prims[i].in_[0], prims[i].in_[1] = ins
+        prims[i].out[0], prims[i].out[1] = outs
+        prims[i].param, prims[i].shift_by, prims[i].shift_coef = int(p.param), int(p.shift_by), int(p.shift_coef)
+    ic = (ctypes.c_int32 * max(1, len(desc.input_coords)))(*desc.input_coords)
+    wc = (ctypes.c_int32 * max(1, len(desc.weight_coords)))(*desc.weight_coords)
+    d = _Desc(len(desc.out_dims), dims, len(desc.prims), prims, len(desc.input_coords), ic,
+              len(desc.weight_coords), wc, int(desc.in_dtype), int(desc.out_dtype))
+    return d, (dims, names, prims, ic, wc)
+
+
 class Plan:
     """Owns one syno_plan.  `desc` is an OpDesc-like object (out_dims, prims, input_coords, weight_coords,
     in_dtype, out_dtype)."""
 
-    def __init__(self, desc):
+    def __init__(self, desc, _borrowed=None, _owner=None):
         lib = load_library()
-        dims = (_Dim * max(1, len(desc.out_dims)))()
-        self._names = [str(n).encode() for n, _ in desc.out_dims]
-        for i, (_, s) in enumerate(desc.out_dims):
-            dims[i].name, dims[i].size = self._names[i], int(s)
-        prims = (_Prim * max(1, len(desc.prims)))()
-        for i, p in enumerate(desc.prims):
-            prims[i].kind = int(p.kind)
-            ins = list(p.ins) + [-1] * (2 - len(p.ins))
-            outs = list(p.outs) + [-1] * (2 - len(p.outs))
-            prims[i].in_[0], prims[i].in_[1] = ins
-            prims[i].out[0], prims[i].out[1] = outs
-            prims[i].param, prims[i].shift_by, prims[i].shift_coef = int(p.param), int(p.shift_by), int(p.shift_coef)
-        ic = (ctypes.c_int32 * max(1, len(desc.input_coords)))(*desc.input_coords)
-        wc = (ctypes.c_int32 * max(1, len(desc.weight_coords)))(*desc.weight_coords)
-        d = _Desc(len(desc.out_dims), dims, len(desc.prims), prims, len(desc.input_coords), ic,
-                  len(desc.weight_coords), wc, int(desc.in_dtype), int(desc.out_dtype))
-        handle = ctypes.c_void_p()
-        st = lib.syno_plan_create(ctypes.byref(d), ctypes.byref(handle))
-        if st:
-            raise SynoError(st, "syno_plan_create")
+        if _borrowed is not None:
+            handle, self._owned, self._owner = ctypes.c_void_p(_borrowed), False, _owner   # a stage of a chain
+        else:
+            d, _keep = _marshal(desc)
+            handle = ctypes.c_void_p()
+            st = lib.syno_plan_create(ctypes.byref(d), ctypes.byref(handle))
+            if st:
+                raise SynoError(st, "syno_plan_create")
+            self._owned = True
         self._h = handle
         self.in_dtype = _TORCH_DTYPE[int(desc.in_dtype)]
         self.out_dtype = _TORCH_DTYPE[int(desc.out_dtype)]
@@ -128,7 +149,7 @@ class Plan:
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None
-        if h and _lib is not None:
+        if h and _lib is not None and getattr(self, "_owned", False):
             _lib.syno_plan_destroy(h)
 
     # -- queries ---------------------------------------------------------------------------
@@ -241,3 +262,109 @@ class Plan:
         if st:
             raise SynoError(st, "syno_debug_gather")
         return a, b
+
+
+class Chain:
+    """Owns one syno_chain: an operator evaluated as consecutive single-weight stages.  `descs` is a list of
+    OpDesc-like objects.  `stages[i]` is a borrowed Plan for queries (shapes, kernel names)."""
+
+    def __init__(self, descs):
+        lib = load_library()
+        arr = (_Desc * len(descs))()
+        keep = []
+        for i, d in enumerate(descs):
+            arr[i], k = _marshal(d)
+            keep.append(k)
+        handle = ctypes.c_void_p()
+        st = lib.syno_chain_create(arr, len(descs), ctypes.byref(handle))
+        if st:
+            raise SynoError(st, "syno_chain_create")
+        self._h = handle
+        n = lib.syno_chain_stages(self._h)
+        self.stages = [Plan(descs[i], _borrowed=lib.syno_chain_plan(self._h, i), _owner=self) for i in range(n)]
+        self._ws = {}
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h and _lib is not None:
+            _lib.syno_chain_destroy(h)
+
+    def workspace_bytes(self, which: int) -> int:
+        n = ctypes.c_size_t()
+        st = load_library().syno_chain_workspace_bytes(self._h, which, ctypes.byref(n))
+        if st:
+            raise SynoError(st, "syno_chain_workspace_bytes")
+        return n.value
+
+    def _workspace(self, which, device, workspace):
+        need = self.workspace_bytes(which)
+        if need == 0:
+            return 0
+        if workspace is None:
+            workspace = self._ws.get((which, device))
+            if workspace is None:
+                workspace = self._ws[(which, device)] = torch.empty(need, dtype=torch.uint8, device=device)
+        if workspace.numel() * workspace.element_size() < need:
+            raise ValueError("workspace too small")
+        return workspace.data_ptr()
+
+    @staticmethod
+    def _ptrs(values):
+        return (ctypes.c_void_p * max(1, len(values)))(*values)
+
+    def new_activations(self, device):
+        """Device buffers for the outputs of all stages but the last."""
+        return [torch.empty(p.out_shape, dtype=p.out_dtype, device=device) for p in self.stages[:-1]]
+
+    def forward(self, X, Ws, acts=None, out=None, workspace=None):
+        """Returns (out, acts)."""
+        first, last = self.stages[0], self.stages[-1]
+        px = first._arg(X, first.x_shape, first.in_dtype, "syno_chain_forward X")
+        pw = [p._arg(w, p.w_shape, p.in_dtype, f"syno_chain_forward W[{i}]") for i, (p, w) in
+              enumerate(zip(self.stages, Ws))]
+        if len(pw) != len(self.stages):
+            raise ValueError("syno_chain_forward: one weight per stage")
+        if acts is None:
+            acts = self.new_activations(X.device)
+        pa = [p._arg(a, p.out_shape, p.out_dtype, f"syno_chain_forward act[{i}]") for i, (p, a) in
+              enumerate(zip(self.stages[:-1], acts))]
+        if len(pa) != len(self.stages) - 1:
+            raise ValueError("syno_chain_forward: one activation buffer per stage but the last")
+        if out is None:
+            out = torch.empty(last.out_shape, dtype=last.out_dtype, device=X.device)
+        po = last._arg(out, last.out_shape, last.out_dtype, "syno_chain_forward out")
+        ws = self._workspace(0, X.device, workspace)
+        stream = torch.cuda.current_stream(X.device).cuda_stream
+        st = load_library().syno_chain_forward(self._h, px, self._ptrs(pw), self._ptrs(pa), po, ws, stream)
+        if st:
+            raise SynoError(st, "syno_chain_forward")
+        return out, acts
+
+    def backward(self, X, Ws, acts, G, dX=None, dWs=None, want_dx=True, workspace=None):
+        """Returns (dX or None, dWs)."""
+        first, last = self.stages[0], self.stages[-1]
+        px = first._arg(X, first.x_shape, first.in_dtype, "syno_chain_backward X")
+        pg = last._arg(G, last.out_shape, last.in_dtype, "syno_chain_backward G")
+        pw = [p._arg(w, p.w_shape, p.in_dtype, f"syno_chain_backward W[{i}]") for i, (p, w) in
+              enumerate(zip(self.stages, Ws))]
+        pa = [p._arg(a, p.out_shape, p.out_dtype, f"syno_chain_backward act[{i}]") for i, (p, a) in
+              enumerate(zip(self.stages[:-1], acts))]
+        if len(pw) != len(self.stages) or len(pa) != len(self.stages) - 1:
+            raise ValueError("syno_chain_backward: one weight per stage, one activation per stage but the last")
+        if dWs is None:
+            dWs = [torch.empty(p.w_shape if p.w_shape else (1,), dtype=torch.float32, device=X.device)
+                   for p in self.stages]
+        pdw = [p._arg(d, p.w_shape, torch.float32, f"syno_chain_backward dW[{i}]") for i, (p, d) in
+               enumerate(zip(self.stages, dWs))]
+        pdx = 0
+        if want_dx:
+            if dX is None:
+                dX = torch.empty(first.x_shape, dtype=first.out_dtype, device=X.device)
+            pdx = first._arg(dX, first.x_shape, first.out_dtype, "syno_chain_backward dX")
+        ws = self._workspace(1, X.device, workspace)
+        stream = torch.cuda.current_stream(X.device).cuda_stream
+        st = load_library().syno_chain_backward(self._h, px, self._ptrs(pw), self._ptrs(pa), pg, pdx,
+                                                self._ptrs(pdw), ws, stream)
+        if st:
+            raise SynoError(st, "syno_chain_backward")
+        return (dX if want_dx else None), dWs

@@ -3,8 +3,21 @@
 #include <cstdio>
 #include <new>
 #include <string>
+#include <vector>
 
 #include "plan.h"
+
+// A chain owns the plans of its stages.
+struct syno_chain {
+  std::vector<syno_plan*> stage;
+  size_t ws_fwd = 0;        // largest forward workspace of any stage
+  size_t ws_bwd_stage = 0;  // largest gradient-call workspace of any stage
+  size_t grad_bytes = 0;    // one intermediate-gradient buffer (two are used, alternating)
+  bool bwd_types_fit = true;
+  ~syno_chain() {
+    for (syno_plan* p : stage) delete p;
+  }
+};
 
 namespace syno {
 syno_status launch_bandwidth(const syno_plan* p, int which, const void* A, const void* B, void* out, void* ws,
@@ -142,6 +155,102 @@ syno_status syno_debug_gather_host(const syno_plan* plan, int which, const int64
   if (!plan || (n > 0 && (!t_flat || !q_flat || !a_off || !b_off))) return SYNO_ERR_NULL;
   if (which < 0 || which > 2 || n < 0) return SYNO_ERR_SHAPE;
   return syno::host_debug_gather(plan, which, t_flat, q_flat, n, a_off, b_off);
+}
+
+syno_status syno_chain_create(const syno_desc* stages, int32_t n_stages, syno_chain** chain) {
+  if (!stages || !chain) return SYNO_ERR_NULL;
+  *chain = nullptr;
+  if (n_stages < 1 || n_stages > 8) return SYNO_ERR_SHAPE;
+  syno_chain* c = new (std::nothrow) syno_chain();
+  if (!c) return SYNO_ERR_UNSUPPORTED;
+  const auto esize = [](syno_dtype t) { return t == SYNO_BF16 ? size_t(2) : size_t(4); };
+  for (int i = 0; i < n_stages; ++i) {
+    syno_plan* p = nullptr;
+    syno_status st = syno_plan_create(&stages[i], &p);
+    if (st == SYNO_OK && i > 0) {
+      const syno_plan* q = c->stage.back();
+      if (q->out_elems != p->x_elems || q->out_dtype != p->in_dtype) st = SYNO_ERR_SHAPE;
+      if (p->out_dtype != q->in_dtype) c->bwd_types_fit = false;
+    }
+    if (st != SYNO_OK) {
+      delete p;
+      delete c;
+      return st;
+    }
+    c->stage.push_back(p);
+    if (p->launch[SYNO_FWD].workspace > c->ws_fwd) c->ws_fwd = p->launch[SYNO_FWD].workspace;
+    for (int w : {SYNO_BWD_DATA, SYNO_BWD_WEIGHT})
+      if (p->launch[w].workspace > c->ws_bwd_stage) c->ws_bwd_stage = p->launch[w].workspace;
+    if (i > 0) {
+      const size_t b = ((size_t(p->x_elems) * esize(p->out_dtype)) + 255) & ~size_t(255);
+      if (b > c->grad_bytes) c->grad_bytes = b;
+    }
+  }
+  *chain = c;
+  return SYNO_OK;
+}
+
+syno_status syno_chain_destroy(syno_chain* chain) {
+  delete chain;
+  return SYNO_OK;
+}
+
+int32_t syno_chain_stages(const syno_chain* chain) { return chain ? int32_t(chain->stage.size()) : 0; }
+
+const syno_plan* syno_chain_plan(const syno_chain* chain, int32_t stage) {
+  if (!chain || stage < 0 || stage >= int32_t(chain->stage.size())) return nullptr;
+  return chain->stage[size_t(stage)];
+}
+
+syno_status syno_chain_workspace_bytes(const syno_chain* chain, int which, size_t* bytes) {
+  if (!chain || !bytes) return SYNO_ERR_NULL;
+  if (which < 0 || which > 1) return SYNO_ERR_SHAPE;
+  const size_t ws_stage = (chain->ws_bwd_stage + 255) & ~size_t(255);
+  *bytes = which == 0 ? chain->ws_fwd : ws_stage + 2 * chain->grad_bytes;
+  return SYNO_OK;
+}
+
+syno_status syno_chain_forward(const syno_chain* chain, const void* X, const void* const* W, void* const* act,
+                               void* out, void* workspace, hipStream_t stream) {
+  if (!chain || !X || !W || !out) return SYNO_ERR_NULL;
+  const size_t n = chain->stage.size();
+  if (n > 1 && !act) return SYNO_ERR_NULL;
+  if (chain->ws_fwd && !workspace) return SYNO_ERR_WORKSPACE;
+  const void* cur = X;
+  for (size_t i = 0; i < n; ++i) {
+    void* dst = i + 1 < n ? act[i] : out;
+    const syno_status st = run(chain->stage[i], SYNO_FWD, cur, W[i], dst, workspace, stream);
+    if (st != SYNO_OK) return st;
+    cur = dst;
+  }
+  return SYNO_OK;
+}
+
+syno_status syno_chain_backward(const syno_chain* chain, const void* X, const void* const* W,
+                                const void* const* act, const void* G, void* dX, void* const* dW,
+                                void* workspace, hipStream_t stream) {
+  if (!chain || !X || !W || !G || !dW) return SYNO_ERR_NULL;
+  const size_t n = chain->stage.size();
+  if (n > 1 && !act) return SYNO_ERR_NULL;
+  if (!chain->bwd_types_fit) return SYNO_ERR_UNSUPPORTED;
+  size_t need = 0;
+  syno_chain_workspace_bytes(chain, 1, &need);
+  if (need && !workspace) return SYNO_ERR_WORKSPACE;
+  // workspace: [stage workspace | gradient buffer 0 | gradient buffer 1]
+  char* const base = static_cast<char*>(workspace);
+  char* const grad0 = base + ((chain->ws_bwd_stage + 255) & ~size_t(255));
+  const void* g = G;
+  for (size_t i = n; i-- > 0;) {
+    const void* in = i == 0 ? X : act[i - 1];
+    syno_status st = run(chain->stage[i], SYNO_BWD_WEIGHT, g, in, dW[i], base, stream);
+    if (st != SYNO_OK) return st;
+    void* dst = i == 0 ? dX : static_cast<void*>(grad0 + (i & 1) * chain->grad_bytes);
+    if (!dst) break;   // the caller does not want dX
+    st = run(chain->stage[i], SYNO_BWD_DATA, g, W[i], dst, base, stream);
+    if (st != SYNO_OK) return st;
+    g = dst;
+  }
+  return SYNO_OK;
 }
 
 const char* syno_status_string(syno_status s) {

@@ -9,7 +9,7 @@ WRITE_SIZE report for it gives the factor that turns the counters into bytes.
 
 Cases: config0, config1_s{0..3}_{f32|bf16}, config2, config3, config4_{fwd|bwd_data|bwd_weight}, and the backward
 passes of the first two shapes with a seeded output gradient: config1t_s{0..3}_{f32|bf16}_{fwd|bwd_data|bwd_weight},
-config3t_{fwd|bwd_data|bwd_weight}.
+config3t_{fwd|bwd_data|bwd_weight}; Operator 1 (two stages) on a ResNet-18 stage shape: op1_s{0..3}_{f32|bf16}_{fwd|bwd}.
 Buffers rotate over several copies so that every launch reads HBM rather than the last-level cache.
 """
 from __future__ import annotations
@@ -68,12 +68,34 @@ def main() -> int:
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
-    w, which = make_case(args.case)
 
     def dev_t(vals, bits):
         if bits is not None:
             return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
         return torch.from_numpy(np.ascontiguousarray(vals, dtype=np.float32)).to(dev)
+
+    if args.case.startswith("op1_s"):       # op1_s<stage>_<f32|bf16>_<fwd|bwd>
+        from syno_inputs import workloads as wl
+        stage, dt, direction = int(args.case[5]), args.case[7:].split("_")[0], args.case[7:].split("_")[1]
+        w = wl.operator1(stage, dt == "bf16")
+        chain = syno.Chain(w.descs)
+        X, G = dev_t(w.X, w.X_bits), dev_t(w.G, w.G_bits)
+        Ws = [dev_t(v, b) for v, b in zip(w.Ws, w.Ws_bits or [None, None])]
+        out, acts = chain.forward(X, Ws)
+        sets = [(X.clone(), [a.clone() for a in acts], G.clone(), torch.empty_like(out), torch.empty_like(X))
+                for _ in range(args.sets)]
+        for i in range(args.iters):
+            s = sets[i % len(sets)]
+            if direction == "fwd":
+                chain.forward(s[0], Ws, acts=s[1], out=s[3])
+            else:
+                chain.backward(s[0], Ws, s[1], s[2], dX=s[4])
+        torch.cuda.synchronize()
+        print(f"{args.case}: " + " | ".join(p.describe(k) for p in chain.stages
+                                            for k in ((0,) if direction == "fwd" else (2, 1))))
+        return 0
+
+    w, which = make_case(args.case)
 
     plan = syno.Plan(w.desc)
     X, W = dev_t(w.X, w.X_bits), dev_t(w.W, w.W_bits)

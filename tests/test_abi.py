@@ -157,3 +157,30 @@ def test_kernel_choice(syno):
         assert all(n == "generic_index_program" for n in names(wl.strided_depthwise(2, 4, 7, 7)))
     finally:
         syno.set_kernel_policy(0)
+
+
+def test_chain_plans_operator1_on_the_host(syno):
+    w = wl.make_operator1(2, 16, 12, g=4, s=2)
+    chain = syno.Chain(w.descs)
+    assert len(chain.stages) == 2
+    assert chain.stages[0].x_shape == w.x_shape and chain.stages[0].out_shape == w.inter_shapes[0]
+    assert chain.stages[0].w_shape == w.w_shapes[0] and chain.stages[1].w_shape == w.w_shapes[1]
+    assert chain.stages[1].out_shape == w.out_shape
+    lib = syno.load_library()
+    assert lib.syno_chain_stages(chain._h) == 2 and lib.syno_chain_plan(chain._h, 2) is None
+    # backward workspace: both intermediate-gradient buffers plus the largest stage workspace
+    inter = int(np.prod(w.inter_shapes[0])) * 4
+    stage_ws = max(p.workspace_bytes(k) for p in chain.stages for k in (1, 2))
+    assert chain.workspace_bytes(1) >= 2 * inter + stage_ws
+    assert chain.workspace_bytes(0) == max(p.workspace_bytes(0) for p in chain.stages)
+
+
+def test_chain_rejects_stages_that_do_not_fit(syno):
+    a, b = wl.conv2d(1, 4, 6, 5, 5), wl.conv2d(1, 5, 4, 5, 5)          # 6 channels out, 5 channels in
+    with pytest.raises(syno.SynoError):
+        syno.Chain([a, b])
+    c = wl.conv2d(1, 6, 4, 5, 5, in_dtype=BF16)                          # element types differ
+    with pytest.raises(syno.SynoError):
+        syno.Chain([a, c])
+    with pytest.raises(syno.SynoError):
+        syno.Chain([])

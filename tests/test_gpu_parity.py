@@ -189,6 +189,66 @@ def test_config1_full_size_backward_sampled(syno, oracle, stage, bf16):
     run_all(syno, oracle, wl.config1_train(stage, bf16), 0, directions=(1, 2), full=False, n_sample=2048)
 
 
+# ------------------------------------------------------------------------------------------------
+# operators evaluated in stages (Operator 1, Fig. 7)
+# ------------------------------------------------------------------------------------------------
+def run_chain(syno, oracle, w, policy):
+    """Forward and backward sweeps of a chain against the checker's chain, every tensor in full."""
+    from syno_inputs.rng import bf16_bits_to_f32, to_bf16_bits
+    bf16 = w.descs[0].in_dtype == BF16
+    q = (lambda a: bf16_bits_to_f32(to_bf16_bits(np.asarray(a, dtype=np.float32)))) if bf16 else None
+    tol = tol_for(w.descs[0])
+    syno.set_kernel_policy(policy)
+    try:
+        chain = syno.Chain(w.descs)
+    finally:
+        syno.set_kernel_policy(0)
+    names = [[p.kernel(i) for i in range(3)] for p in chain.stages]
+    print(f"[case] {w.descs[0].name} + {w.descs[1].name} kernels={names} policy={policy}", flush=True)
+    X, G = to_dev(w.X, w.X_bits), to_dev(w.G, w.G_bits)
+    Ws = [to_dev(v, b) for v, b in zip(w.Ws, w.Ws_bits or [None] * len(w.Ws))]
+    out, acts = chain.forward(X, Ws)
+    torch.cuda.synchronize()
+    ref = oracle.chain_forward(w.descs, w.X, w.Ws, quantize=q)
+    for i, a in enumerate(acts):
+        e = rel_l2(to_host(a), ref[i])
+        assert e <= tol, f"stage {i} output rel-L2 {e:.3e} > {tol}"
+    e = rel_l2(to_host(out), ref[-1])
+    assert e <= tol, f"chain output rel-L2 {e:.3e} > {tol}"
+    print(f"[case] {w.descs[0].name} backward sweep", flush=True)
+    dX, dWs = chain.backward(X, Ws, acts, G)
+    torch.cuda.synchronize()
+    rdx, rdws = oracle.chain_backward(w.descs, w.X, w.Ws, w.G, quantize=q)
+    e = rel_l2(to_host(dX), rdx)
+    assert e <= tol, f"chain dX rel-L2 {e:.3e} > {tol}"
+    for i, (d, r) in enumerate(zip(dWs, rdws)):
+        assert d.dtype == torch.float32
+        e = rel_l2(to_host(d), r)
+        assert e <= tol, f"chain dW[{i}] rel-L2 {e:.3e} > {tol}"
+    # without dX: the weights' gradients are the same, and nothing else is needed
+    _, dWs2 = chain.backward(X, Ws, acts, G, want_dx=False)
+    torch.cuda.synchronize()
+    for a, b in zip(dWs, dWs2):
+        assert torch.equal(a, b)
+    return names
+
+
+@pytest.mark.parametrize("policy", [1, 0])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_operator1_small(syno, oracle, bf16, policy):
+    run_chain(syno, oracle, wl.make_operator1(3, 24, 13, seed=21, bf16=bf16, Co=32, Wd=19, g=4, s=2, with_grad=True),
+              policy)
+    run_chain(syno, oracle, wl.make_operator1(2, 16, 9, seed=22, bf16=bf16, Co=16, Wd=10, g=2, s=1, with_grad=True),
+              policy)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_operator1_full_size(syno, oracle, bf16):
+    """Operator 1 in place of the first ResNet-18 stage's convolution (C = 64, 56 x 56, N = 32), the shape the
+    benchmark's detail times."""
+    run_chain(syno, oracle, wl.operator1(0, bf16), 0)
+
+
 def test_rejects_wrong_arguments(syno):
     plan = syno.Plan(wl.conv2d(1, 4, 4, 5, 5))
     X = torch.zeros(plan.x_shape, device="cuda")

@@ -62,9 +62,19 @@ struct ConvLike {
   int32_t ws_g, ws_o, ws_c, ws_kh, ws_kw;
 };
 
+// ---------------------------------------------------------------------------------------------
+// Window whose iterator is Shared with the weight but not Reduced (first stage of Operator 1, Fig. 7):
+//   out[n,d,g,k,h,w] = sum_c X[n, g*Cg+c, h, w+k-pw] * W[d,g,c,k]      (zero outside the row), pw = K/2
+// ---------------------------------------------------------------------------------------------
+struct ShareWindow {
+  int32_t N, D, G, K, H, W, Cg, pw;
+  int32_t ws_d, ws_g, ws_c, ws_k;   // weight element strides per role (0 when the role has size 1)
+};
+
 enum KernelId : int32_t {
   KERNEL_GENERIC = 0,
   KERNEL_BW_DEPTHWISE,
+  KERNEL_BW_WINDOW,
   KERNEL_MFMA_F32,
   KERNEL_MFMA_BF16,
   KERNEL_COUNT
@@ -92,6 +102,8 @@ struct syno_plan {
   syno::IndexProgram prog[3];
   bool conv_like = false;
   syno::ConvLike conv{};
+  bool share_window = false;
+  syno::ShareWindow window{};
   syno::Launch launch[3];
 };
 
@@ -113,8 +125,11 @@ bool bandwidth_supports(const syno_plan* p, int which);
 bool mfma_supports(const syno_plan* p, int which);
 // fills launch[which] (tile variant, workspace bytes) for the MFMA family
 void mfma_configure(syno_plan* p, int which);
-// kernels_mfma_dw.hip: the backward-weight member of the MFMA family
 size_t bandwidth_workspace(const syno_plan* p, int which);
+// kernels_window.hip: the unreduced-window member of the bandwidth family
+bool window_supports(const syno_plan* p, int which);
+size_t window_workspace(const syno_plan* p, int which);
+// kernels_mfma_dw.hip: the backward-weight member of the MFMA family
 bool mfma_dw_supports(const syno_plan* p);
 void mfma_dw_configure(syno_plan* p);
 

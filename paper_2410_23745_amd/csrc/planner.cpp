@@ -437,10 +437,10 @@ Expr add(const Expr& x, int64_t kx, const Expr& y, int64_t ky, int64_t c) {
 
 bool same_affine(const Expr& a, const Expr& b) { return a.coef == b.coef && a.c == b.c; }
 
-bool recognise_conv(const Graph& g, ConvLike& cv) {
-  std::vector<Root> roots;
-  std::vector<Expr> e(g.n_slots);
-  std::vector<Check> checks;
+// Every coordinate as an affine expression of the iterators ("roots": output iterators, their Merge digits,
+// Reduce iterators), plus the range tests the Unfolds impose.  False when the graph has an Expand.
+bool analyse(const Graph& g, std::vector<Root>& roots, std::vector<Expr>& e, std::vector<Check>& checks) {
+  e.assign(g.n_slots, Expr());
   for (int i = 0; i < g.n_out; ++i) {
     Root r; r.size = g.D(i); r.out_stride = g.out_stride[i];
     roots.push_back(r);
@@ -492,6 +492,14 @@ bool recognise_conv(const Graph& g, ConvLike& cv) {
       }
     }
   }
+  return true;
+}
+
+bool recognise_conv(const Graph& g, ConvLike& cv) {
+  std::vector<Root> roots;
+  std::vector<Expr> e;
+  std::vector<Check> checks;
+  if (!analyse(g, roots, e, checks)) return false;
   if (g.in_coords.size() != 4) return false;
   const Expr* ax[4];
   for (int i = 0; i < 4; ++i) {
@@ -609,6 +617,101 @@ bool recognise_conv(const Graph& g, ConvLike& cv) {
   return true;
 }
 
+// The window form whose window iterator is Shared with the weight but not Reduced (first stage of Operator 1,
+// Fig. 7): out laid out [n,d,g,k,h,w], X = [n, Cg*g+c, h, w+k-pw], the weight indexed by bare d, g, c, k.
+bool recognise_share_window(const Graph& g, ShareWindow& sw) {
+  std::vector<Root> roots;
+  std::vector<Expr> e;
+  std::vector<Check> checks;
+  if (!analyse(g, roots, e, checks)) return false;
+  if (g.in_coords.size() != 4 || checks.size() != 1) return false;
+  const Expr* ax[4];
+  for (int i = 0; i < 4; ++i) {
+    ax[i] = &e[g.S(g.in_coords[i])];
+    if (!ax[i]->pure()) return false;
+  }
+  enum { R_NONE, R_N, R_D, R_G, R_K, R_H, R_W, R_C };
+  std::vector<int> role(roots.size(), R_NONE);
+  std::memset(&sw, 0, sizeof(sw));
+  sw.N = sw.D = sw.G = sw.K = sw.H = sw.W = sw.Cg = 1;
+  auto bare_output = [&](const Expr& x, int r_role, int32_t& size) {
+    if (x.c != 0 || x.coef.size() != 1 || x.coef.begin()->second != 1) return false;
+    const int r = x.coef.begin()->first;
+    if (roots[r].is_reduce || role[r] != R_NONE) return false;
+    role[r] = r_role; size = (int32_t)roots[r].size;
+    return true;
+  };
+  if (!bare_output(*ax[0], R_N, sw.N) || !bare_output(*ax[2], R_H, sw.H)) return false;
+  if (sw.H != g.D(g.in_coords[2])) return false;
+  // channel = Cg*g + c  |  c
+  if (ax[1]->c != 0 || ax[1]->coef.empty() || ax[1]->coef.size() > 2) return false;
+  for (auto& t : ax[1]->coef) {
+    if (role[t.first] != R_NONE) return false;
+    if (roots[t.first].is_reduce) {
+      if (t.second != 1 || sw.Cg != 1) return false;
+      role[t.first] = R_C; sw.Cg = (int32_t)roots[t.first].size;
+    } else {
+      if (sw.G != 1) return false;
+      role[t.first] = R_G; sw.G = (int32_t)roots[t.first].size;
+    }
+  }
+  for (auto& t : ax[1]->coef)
+    if (role[t.first] == R_G && t.second != sw.Cg) return false;
+  if ((int64_t)sw.G * sw.Cg != g.D(g.in_coords[1])) return false;
+  // column = w + k - pw: two output iterators; the one whose size is the axis is w, the other the window
+  if (ax[3]->coef.size() != 2 || ax[3]->c > 0) return false;
+  sw.pw = (int32_t)(-ax[3]->c);
+  const int64_t Wi = g.D(g.in_coords[3]);
+  int rw = -1, rk = -1;
+  for (auto& t : ax[3]->coef) {
+    if (t.second != 1 || roots[t.first].is_reduce || role[t.first] != R_NONE) return false;
+    if (roots[t.first].size == Wi && rw < 0) rw = t.first; else rk = t.first;
+  }
+  if (rw < 0 || rk < 0) return false;
+  role[rw] = R_W; sw.W = (int32_t)roots[rw].size;
+  role[rk] = R_K; sw.K = (int32_t)roots[rk].size;
+  if (sw.pw != sw.K / 2 || sw.K < 2) return false;
+  if (!same_affine(checks[0].e, *ax[3]) || checks[0].bound != Wi) return false;
+  // weight axes: one bare iterator each; every iterator of extent > 1 other than n, h, w must index it
+  std::vector<int64_t> wstride(g.w_coords.size(), 1);
+  for (int i = (int)g.w_coords.size() - 2; i >= 0; --i) wstride[i] = wstride[i + 1] * g.D(g.w_coords[i + 1]);
+  std::vector<char> in_w(roots.size(), 0);
+  for (size_t i = 0; i < g.w_coords.size(); ++i) {
+    const Expr& x = e[g.S(g.w_coords[i])];
+    if (!x.pure() || x.c != 0 || x.coef.size() != 1 || x.coef.begin()->second != 1) return false;
+    const int r = x.coef.begin()->first;
+    if (in_w[r]) return false;
+    in_w[r] = 1;
+    if (role[r] == R_NONE) {
+      if (roots[r].is_reduce || sw.D != 1) return false;
+      role[r] = R_D; sw.D = (int32_t)roots[r].size;
+    }
+    const int32_t s = (int32_t)wstride[i];
+    switch (role[r]) {
+      case R_D: sw.ws_d = s; break;
+      case R_G: sw.ws_g = s; break;
+      case R_C: sw.ws_c = s; break;
+      case R_K: sw.ws_k = s; break;
+      default: return false;
+    }
+  }
+  for (size_t r = 0; r < roots.size(); ++r) {
+    if (!roots[r].alive) continue;
+    if (role[r] == R_NONE) return false;
+    const bool needs_w = role[r] == R_D || role[r] == R_G || role[r] == R_C || role[r] == R_K;
+    if (needs_w && !in_w[r] && roots[r].size > 1) return false;
+  }
+  // the output must be laid out [N, D, G, K, H, W]
+  int64_t expect[8] = {};
+  expect[R_W] = 1; expect[R_H] = sw.W; expect[R_K] = (int64_t)sw.H * sw.W; expect[R_G] = expect[R_K] * sw.K;
+  expect[R_D] = expect[R_G] * sw.G; expect[R_N] = expect[R_D] * sw.D;
+  for (size_t r = 0; r < roots.size(); ++r) {
+    if (!roots[r].alive || roots[r].is_reduce) continue;
+    if (roots[r].size > 1 && roots[r].out_stride != expect[role[r]]) return false;
+  }
+  return true;
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------
@@ -652,6 +755,7 @@ syno_status build_plan(const syno_desc* desc, int policy, syno_plan* plan, std::
     return unsupported("backward-weight index map could not be inverted");
 
   plan->conv_like = recognise_conv(g, plan->conv);
+  plan->share_window = !plan->conv_like && recognise_share_window(g, plan->window);
 
   for (int which = 0; which < 3; ++which) {
     Launch& L = plan->launch[which];
@@ -667,6 +771,9 @@ syno_status build_plan(const syno_desc* desc, int policy, syno_plan* plan, std::
     if (bandwidth_supports(plan, which)) {
       L.kernel = KERNEL_BW_DEPTHWISE;
       L.workspace = bandwidth_workspace(plan, which);
+    } else if (window_supports(plan, which)) {
+      L.kernel = KERNEL_BW_WINDOW;
+      L.workspace = window_workspace(plan, which);
     } else if (mfma_supports(plan, which)) {
       L.kernel = plan->in_dtype == SYNO_BF16 ? KERNEL_MFMA_BF16 : KERNEL_MFMA_F32;
       mfma_configure(plan, which);

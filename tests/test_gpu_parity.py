@@ -242,6 +242,50 @@ def test_operator1_small(syno, oracle, bf16, policy):
               policy)
 
 
+@pytest.mark.parametrize("dt", ["f32", "bf16", "bf16_f32out"])
+@pytest.mark.parametrize("shape", [
+    (3, 16, 16, 5, 12, 4, 2),      # runs of 4 pixels, fewer runs than one workgroup's lanes
+    (2, 40, 40, 6, 10, 2, 1),      # runs of 2; D = 20 and Cg = 20: several tiles of each, ragged
+    (2, 12, 24, 4, 7, 3, 2),       # single pixels (odd width); D = 4, Cg = 4
+    (5, 8, 8, 17, 16, 1, 1),       # one group; more runs than one workgroup
+])
+def test_share_window_stage_small(syno, oracle, shape, dt):
+    """The first stage of Operator 1 by itself on the streaming kernels, all three passes, element by element."""
+    N, Cin, Co, H, W, g, s = shape
+    i_dt = F32 if dt == "f32" else BF16
+    o_dt = BF16 if dt == "bf16" else F32
+    d = wl.operator1_stage1(N, Cin, Co, H, W, g, s, 3, i_dt, o_dt)
+    xs, ws, _ = oracle.describe(d)
+    os_ = oracle.out_shape(d)
+    st = wl.Stream(31)
+    w = wl._finish(d, xs, ws, os_, st.normal(xs), st.uniform_pm(0.5, ws), st.normal(os_), Cin // g)
+    names = run_all(syno, oracle, w, 0)
+    assert names == ["bandwidth_share_window"] * 3
+
+
+def test_share_window_bf16_rounding_is_nearest_even(syno, oracle):
+    """With Cg = 2 and the weights 1 and 2^-9 every sum x0 + x1/512 of two bf16 values is exact in fp32 (or
+    rounded once, identically, by the fused multiply-add), so the stored bf16 must be the round-to-nearest-even
+    of the checker's value, bit for bit."""
+    from syno_inputs.rng import to_bf16_bits
+    N, H, W = 2, 6, 16
+    d = wl.operator1_stage1(N, 2, 1, H, W, 1, 1, 3, BF16, BF16)
+    xs, ws, _ = oracle.describe(d)
+    st = wl.Stream(33)
+    Xb = to_bf16_bits(st.normal(xs))
+    Wv = np.empty(ws, dtype=np.float32)
+    Wv[0, 0, 0, :], Wv[0, 0, 1, :] = 1.0, 2.0 ** -9
+    Wb = to_bf16_bits(Wv)
+    from syno_inputs.rng import bf16_bits_to_f32
+    ref = oracle.forward(d, bf16_bits_to_f32(Xb), Wv)
+    plan = syno.Plan(d)
+    assert plan.kernel(0) == "bandwidth_share_window"
+    out = plan.forward(to_dev(None, Xb), to_dev(None, Wb))
+    torch.cuda.synchronize()
+    got = out.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(got, to_bf16_bits(ref.astype(np.float32)))
+
+
 @pytest.mark.parametrize("bf16", [False, True])
 def test_operator1_full_size(syno, oracle, bf16):
     """Operator 1 in place of the first ResNet-18 stage's convolution (C = 64, 56 x 56, N = 32), the shape the

@@ -99,7 +99,9 @@ __device__ __forceinline__ void store_run(void* base, int64_t off, const float* 
 }
 
 // The K+V-1 elements of row `row_off` (offset of the row's first element) that the windows of the run
-// starting at column w0 touch: columns w0-PW .. w0+V+K-2-PW, zero outside [0, W).
+// starting at column w0 touch: columns w0-PW .. w0+V+K-2-PW, zero outside [0, W).  Branch-free: a neighbour
+// outside the row is loaded from the nearest column inside it and replaced by zero afterwards, so that all
+// loads of a lane can be in flight together.
 template <int K, int V, bool BF>
 __device__ __forceinline__ void load_window(const void* base, int64_t row_off, int w0, int W, float* win) {
   constexpr int PW = K / 2;
@@ -107,20 +109,31 @@ __device__ __forceinline__ void load_window(const void* base, int64_t row_off, i
 #pragma unroll
   for (int j = 0; j < PW; ++j) {
     const int x = w0 - PW + j;
-    win[j] = x >= 0 ? load_one<BF>(base, row_off + x) : 0.f;
+    const float t = load_one<BF>(base, row_off + max(x, 0));
+    win[j] = x >= 0 ? t : 0.f;
   }
 #pragma unroll
   for (int j = 0; j < K - 1 - PW; ++j) {
     const int x = w0 + V + j;
-    win[PW + V + j] = x < W ? load_one<BF>(base, row_off + x) : 0.f;
+    const float t = load_one<BF>(base, row_off + min(x, W - 1));
+    win[PW + V + j] = x < W ? t : 0.f;
   }
+}
+
+// Keeps the compiler from sinking a load below this point: everything requested so far is in flight together.
+template <int N>
+__device__ __forceinline__ void pin(float (&v)[N]) {
+#pragma unroll
+  for (int i = 0; i < N; ++i) asm volatile("" : "+v"(v[i]));
 }
 
 constexpr int kThreads = 256;
 constexpr int kDT = 8;    // forward: output-channel digits d a lane accumulates at once
+constexpr int kCB = 8;    //          input channels whose windows are in flight together
 constexpr int kCT = 16;   // backward-data: input channels c a lane accumulates at once
-constexpr int kWD = 8;    // backward-weight: d digits per lane ...
-constexpr int kWC = 4;    // ... times input channels per lane
+constexpr int kDB = 4;    //                d digits whose gradient runs are in flight together
+constexpr int kWD = 4;    // backward-weight: d digits per lane ...
+constexpr int kWC = 8;    // ... times input channels per lane
 
 // ------------------------------------------------------------------------------------------------
 // forward.  grid = (run blocks, G, d tiles)
@@ -151,19 +164,28 @@ __global__ __launch_bounds__(kThreads) void share_window_fwd(const SwParams p, c
 #pragma unroll
       for (int v = 0; v < V; ++v) acc[a][k][v] = 0.f;
   const int64_t row0 = ((int64_t)n * p.G * p.Cg + (int64_t)g * p.Cg) * p.HW + (int64_t)h * p.W;
-#pragma unroll 4
-  for (int c = 0; c < p.Cg; ++c) {
-    float win[V + K - 1];
-    load_window<K, V, IBF>(X, row0 + (int64_t)c * p.HW, w0, p.W, win);
-    const float* wc = wl + c * (kDT * K);
+  for (int cb = 0; cb < p.Cg; cb += kCB) {
+    // the windows of kCB channels are requested together: one memory round trip per batch
+    float win[kCB][V + K - 1];
 #pragma unroll
-    for (int a = 0; a < kDT; ++a)
+    for (int j = 0; j < kCB; ++j)
+      load_window<K, V, IBF>(X, row0 + (int64_t)min(cb + j, p.Cg - 1) * p.HW, w0, p.W, win[j]);
 #pragma unroll
-      for (int k = 0; k < K; ++k) {
-        const float wv = wc[a * K + k];
+    for (int j = 0; j < kCB; ++j) pin(win[j]);
 #pragma unroll
-        for (int v = 0; v < V; ++v) acc[a][k][v] = fmaf(win[v + k], wv, acc[a][k][v]);
+    for (int j = 0; j < kCB; ++j) {
+      if (cb + j < p.Cg) {
+        const float* wc = wl + (cb + j) * (kDT * K);
+#pragma unroll
+        for (int a = 0; a < kDT; ++a)
+#pragma unroll
+          for (int k = 0; k < K; ++k) {
+            const float wv = wc[a * K + k];
+#pragma unroll
+            for (int v = 0; v < V; ++v) acc[a][k][v] = fmaf(win[j][v + k], wv, acc[a][k][v]);
+          }
       }
+    }
   }
 #pragma unroll
   for (int a = 0; a < kDT; ++a) {
@@ -204,31 +226,53 @@ __global__ __launch_bounds__(kThreads) void share_window_bwd_data(const SwParams
   for (int a = 0; a < kCT; ++a)
 #pragma unroll
     for (int v = 0; v < V; ++v) acc[a][v] = 0.f;
-#pragma unroll 2
-  for (int d = 0; d < p.D; ++d) {
+  for (int db = 0; db < p.D; db += kDB) {
+    // dX at column x takes G of plane (d,g,k) at column x - k + PW: the run itself plus |PW - k| elements
+    // beyond one of its ends.  The runs of kDB digits are requested together.
+    float cen[kDB][K][V], edge[kDB][K][PW > 0 ? PW : 1];
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
-      // dX at column x takes G of plane (d,g,k) at column x - k + PW
-      const int shift = PW - k;
-      const int64_t row = ((((int64_t)n * p.D + d) * p.G + g) * K + k) * p.HW + (int64_t)h * p.W;
-      float cen[V], gv[V];
-      load_run<V, IBF>(Gr, row + w0, cen);
+    for (int j = 0; j < kDB; ++j) {
+      const int d = min(db + j, p.D - 1);
 #pragma unroll
-      for (int v = 0; v < V; ++v) {
-        const int t = v + shift;
-        if (t >= 0 && t < V) {
-          gv[v] = cen[t];
-        } else {
-          const int x = w0 + t;
-          gv[v] = (x >= 0 && x < p.W) ? load_one<IBF>(Gr, row + x) : 0.f;
+      for (int k = 0; k < K; ++k) {
+        const int shift = PW - k;
+        const int64_t row = ((((int64_t)n * p.D + d) * p.G + g) * K + k) * p.HW + (int64_t)h * p.W;
+        load_run<V, IBF>(Gr, row + w0, cen[j][k]);
+#pragma unroll
+        for (int t = 0; t < (shift > 0 ? shift : -shift); ++t) {
+          const int x = shift > 0 ? w0 + V + t : w0 - 1 - t;
+          const float e = load_one<IBF>(Gr, row + min(max(x, 0), p.W - 1));
+          edge[j][k][t] = (x >= 0 && x < p.W) ? e : 0.f;
         }
       }
-      const float* wk = wl + (d * K + k) * kCT;
+    }
 #pragma unroll
-      for (int a = 0; a < kCT; ++a) {
-        const float wv = wk[a];
+    for (int j = 0; j < kDB; ++j)
 #pragma unroll
-        for (int v = 0; v < V; ++v) acc[a][v] = fmaf(gv[v], wv, acc[a][v]);
+      for (int k = 0; k < K; ++k) {
+        pin(cen[j][k]);
+        if (k != PW) pin(edge[j][k]);
+      }
+#pragma unroll
+    for (int j = 0; j < kDB; ++j) {
+      if (db + j < p.D) {
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+          const int shift = PW - k;
+          float gv[V];
+#pragma unroll
+          for (int v = 0; v < V; ++v) {
+            const int t = v + shift;
+            gv[v] = (t >= 0 && t < V) ? cen[j][k][t] : (t >= V ? edge[j][k][t - V] : edge[j][k][-t - 1]);
+          }
+          const float* wk = wl + ((db + j) * K + k) * kCT;
+#pragma unroll
+          for (int a = 0; a < kCT; ++a) {
+            const float wv = wk[a];
+#pragma unroll
+            for (int v = 0; v < V; ++v) acc[a][v] = fmaf(gv[v], wv, acc[a][v]);
+          }
+        }
       }
     }
   }
@@ -241,8 +285,11 @@ __global__ __launch_bounds__(kThreads) void share_window_bwd_data(const SwParams
 }
 
 // ------------------------------------------------------------------------------------------------
-// backward-weight.  grid = (chunks, G, d tiles * c tiles); every workgroup leaves the sums over its runs in
-// partial[chunk][weight offset]; a second kernel adds the chunks in a fixed order.
+// backward-weight.  One workgroup per (chunk of runs, g, tile of kWD x kWC weights); it leaves the sums over its
+// runs in partial[chunk][weight offset], and a second kernel adds the chunks in a fixed order.  The tiles of one
+// (chunk, g) read the same gradient planes and input rows; the grid is one-dimensional and decoded so that they
+// are consecutive workgroups of the same XCD (workgroups go round-robin over the 8 XCDs), which makes the
+// re-reads hit that XCD's L2 while it still holds the lines.
 // ------------------------------------------------------------------------------------------------
 template <int K, int V, bool IBF>
 __global__ __launch_bounds__(kThreads) void share_window_bwd_weight(const SwParams p, const void* __restrict__ Gr,
@@ -250,9 +297,15 @@ __global__ __launch_bounds__(kThreads) void share_window_bwd_weight(const SwPara
                                                                    float* __restrict__ partial) {
   constexpr int NACC = kWD * kWC * K;
   __shared__ float red[kThreads / 64][NACC];
-  const int g = blockIdx.y;
   const int c_tiles = (p.Cg + kWC - 1) / kWC;
-  const int d0 = (blockIdx.z / c_tiles) * kWD, c0 = (blockIdx.z % c_tiles) * kWC;
+  const int tiles = c_tiles * ((p.D + kWD - 1) / kWD);
+  int slot = blockIdx.x >> 3;
+  const int tile = slot % tiles;
+  slot /= tiles;
+  const int g = slot % p.G;
+  const int chunk = (slot / p.G) * 8 + (blockIdx.x & 7);
+  if (chunk >= p.chunks) return;
+  const int d0 = (tile / c_tiles) * kWD, c0 = (tile % c_tiles) * kWC;
   float acc[kWD][kWC][K];
 #pragma unroll
   for (int a = 0; a < kWD; ++a)
@@ -260,22 +313,17 @@ __global__ __launch_bounds__(kThreads) void share_window_bwd_weight(const SwPara
     for (int b = 0; b < kWC; ++b)
 #pragma unroll
       for (int k = 0; k < K; ++k) acc[a][b][k] = 0.f;
-  const int q_end = min((int)(blockIdx.x + 1) * p.runs_per_chunk, p.n_runs);
-  for (int q = blockIdx.x * p.runs_per_chunk + threadIdx.x; q < q_end; q += kThreads) {
+  const int q_end = min((chunk + 1) * p.runs_per_chunk, p.n_runs);
+  for (int q = chunk * p.runs_per_chunk + threadIdx.x; q < q_end; q += kThreads) {
     const int n = q / p.runs_per_plane;
     const int pix0 = (q - n * p.runs_per_plane) * V;
     const int h = pix0 / p.W, w0 = pix0 - h * p.W;
     float xw[kWC][V + K - 1];
 #pragma unroll
     for (int b = 0; b < kWC; ++b) {
-      const int c = c0 + b;
-      if (c < p.Cg) {
-        load_window<K, V, IBF>(X, ((int64_t)n * p.G * p.Cg + (int64_t)g * p.Cg + c) * p.HW + (int64_t)h * p.W, w0,
-                               p.W, xw[b]);
-      } else {
-#pragma unroll
-        for (int j = 0; j < V + K - 1; ++j) xw[b][j] = 0.f;
-      }
+      const int c = min(c0 + b, p.Cg - 1);   // channels past the end re-read the last one; their sums are dropped
+      load_window<K, V, IBF>(X, ((int64_t)n * p.G * p.Cg + (int64_t)g * p.Cg + c) * p.HW + (int64_t)h * p.W, w0,
+                             p.W, xw[b]);
     }
     // every gradient run of the tile is requested before the first one is used: one memory round trip
     float gv[kWD][K][V];
@@ -289,25 +337,41 @@ __global__ __launch_bounds__(kThreads) void share_window_bwd_weight(const SwPara
 #pragma unroll
     for (int a = 0; a < kWD; ++a)
 #pragma unroll
+      for (int k = 0; k < K; ++k) pin(gv[a][k]);
+#pragma unroll
+    for (int a = 0; a < kWD; ++a)
+#pragma unroll
       for (int k = 0; k < K; ++k)
 #pragma unroll
         for (int b = 0; b < kWC; ++b)
 #pragma unroll
           for (int v = 0; v < V; ++v) acc[a][b][k] = fmaf(gv[a][k][v], xw[b][v + k], acc[a][b][k]);
   }
-  // sum over the lanes of each wave, then over the waves
+  // Sum over the lanes of each wave by halving: at the step with lane mask m a lane passes one half of its
+  // sums to lane^m and adds the half it receives, so the count of sums per lane halves while the count of lanes
+  // added doubles; after masks 1..16 a lane holds NACC/32 complete half-wave sums, the last step adds the other
+  // half-wave.  NACC/32 + ... + NACC/2 exchanges instead of 6 * NACC.
+  static_assert(NACC % 32 == 0, "the sums must halve five times");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float* v = &acc[0][0][0];
+  int base = 0;
 #pragma unroll
-  for (int a = 0; a < kWD; ++a)
+  for (int step = 0; step < 5; ++step) {
+    const int half = NACC >> (step + 1);
+    const bool upper = (lane >> step) & 1;
 #pragma unroll
-    for (int b = 0; b < kWC; ++b)
+    for (int i = 0; i < half; ++i) {
+      const float send = upper ? v[i] : v[i + half];
+      const float keep = upper ? v[i + half] : v[i];
+      v[i] = keep + __shfl_xor(send, 1 << step, 64);
+    }
+    base += upper ? half : 0;
+  }
 #pragma unroll
-      for (int k = 0; k < K; ++k) {
-        float s = acc[a][b][k];
-#pragma unroll
-        for (int m = 32; m >= 1; m >>= 1) s += __shfl_xor(s, m, 64);
-        if (lane == 0) red[wave][(a * kWC + b) * K + k] = s;
-      }
+  for (int i = 0; i < NACC / 32; ++i) {
+    v[i] += __shfl_xor(v[i], 32, 64);
+    if (lane < 32) red[wave][base + i] = v[i];
+  }
   __syncthreads();
   for (int i = threadIdx.x; i < NACC; i += kThreads) {
     const int a = i / (kWC * K), r = i - a * (kWC * K), b = r / K, k = r - b * K;
@@ -316,7 +380,7 @@ __global__ __launch_bounds__(kThreads) void share_window_bwd_weight(const SwPara
       float s = red[0][i];
 #pragma unroll
       for (int w = 1; w < kThreads / 64; ++w) s += red[w][i];
-      partial[(int64_t)blockIdx.x * p.w_elems + (int64_t)d * p.ws_d + (int64_t)g * p.ws_g + (int64_t)c * p.ws_c +
+      partial[(int64_t)chunk * p.w_elems + (int64_t)d * p.ws_d + (int64_t)g * p.ws_g + (int64_t)c * p.ws_c +
               (int64_t)k * p.ws_k] = s;
     }
   }
@@ -377,7 +441,7 @@ syno_status launch_typed(const SwParams& p, int which, const void* A, const void
                        sizeof(float) * p.D * K * kCT, stream, p, A, B, out);
   } else {
     const unsigned tiles = (unsigned)(((p.D + kWD - 1) / kWD) * ((p.Cg + kWC - 1) / kWC));
-    const dim3 grid((unsigned)p.chunks, (unsigned)p.G, tiles);
+    const dim3 grid((unsigned)((p.chunks + 7) / 8 * 8) * (unsigned)p.G * tiles);
     hipLaunchKernelGGL((share_window_bwd_weight<K, V, IBF>), grid, dim3(kThreads), 0, stream, p, A, B,
                        static_cast<float*>(ws));
     hipLaunchKernelGGL(share_window_reduce, dim3((unsigned)((p.w_elems + 15) / 16)),
@@ -407,7 +471,7 @@ bool window_supports(const syno_plan* plan, int which) {
   // the weights a workgroup keeps in LDS
   const size_t lds = sizeof(float) * (which == SYNO_FWD ? (size_t)s.Cg * kDT * s.K : (size_t)s.D * s.K * kCT);
   if (which != SYNO_BWD_WEIGHT && lds > 48 * 1024) return false;
-  if (s.G > 65535 || (int64_t)((s.D + kWD - 1) / kWD) * ((s.Cg + kWC - 1) / kWC) > 65535) return false;
+  if (s.G > 65535 || (int64_t)((s.D + kWD - 1) / kWD) * ((s.Cg + kWC - 1) / kWC) * s.G > (1 << 20)) return false;
   return true;
 }
 

@@ -221,6 +221,44 @@ def main() -> int:
                            "TFLOP/s": tf, "GB/s": gbs,
                            "bound": "hbm" if roof_tf < peak else "mfma", "roofline_frac": tf / roof_tf,
                            "rotating_sets": len(c.sets)})
+        # Operator 1 (two stages, two weights) in place of the first stage's convolution: the forward sweep and
+        # the backward sweep (dX and both weight gradients), each timed as a whole
+        for bf16 in (False, True):
+            w = wl.operator1(0, bf16)
+            chain = syno.Chain(w.descs)
+            eb = 2 if bf16 else 4
+            X, G = to_dev(w.X, w.X_bits), to_dev(w.G, w.G_bits)
+            Ws = [to_dev(v, b) for v, b in zip(w.Ws, w.Ws_bits or [None, None])]
+            out0, acts0 = chain.forward(X, Ws)
+            sets = [(X.clone(), [a.clone() for a in acts0], G.clone(), torch.empty_like(out0), torch.empty_like(X))
+                    for _ in range(4)]
+            n_x, n_z, n_o = (int(np.prod(t)) for t in (w.x_shape, w.inter_shapes[0], w.out_shape))
+            n_w = sum(int(np.prod(t)) for t in w.w_shapes)
+            sweeps = {
+                "fwd": (lambda t: chain.forward(t[0], Ws, acts=t[1], out=t[3]), w.flops,
+                        eb * (n_x + 2 * n_z + n_o + n_w)),
+                # stage 2: read G, Z, W2, write dZ, dW2; stage 1: read dZ (twice), X, W1, write dX, dW1
+                "bwd": (lambda t: chain.backward(t[0], Ws, t[1], t[2], dX=t[4]), 2 * w.flops,
+                        eb * (2 * n_o + 4 * n_z + 2 * n_x + n_w) + 4 * n_w),
+            }
+            for tag, (fn, flops, nbytes) in sweeps.items():
+                for i in range(3):
+                    fn(sets[i % 4])
+                torch.cuda.synchronize()
+                marks = [torch.cuda.Event(enable_timing=True) for _ in range(21)]
+                marks[0].record()
+                for i in range(20):
+                    fn(sets[i % 4])
+                    marks[i + 1].record()
+                torch.cuda.synchronize()
+                ts = sorted(a.elapsed_time(b) for a, b in zip(marks[:-1], marks[1:]))
+                med = ts[len(ts) // 2]
+                which = (0,) if tag == "fwd" else (2, 1)
+                detail.append({"case": f"operator1_C64_56x56_N32_{'bf16' if bf16 else 'f32'}_{tag}_sweep",
+                               "kernel": " + ".join(p.kernel(k) for p in chain.stages for k in which),
+                               "launch": " | ".join(p.describe(k) for p in chain.stages for k in which),
+                               "us": med * 1e3, "TFLOP/s": flops / (med * 1e-3) / 1e12,
+                               "GB/s": nbytes / (med * 1e-3) / 1e9, "rotating_sets": 4})
         out["detail"] = detail
 
     # ---- CPU baseline: the checker as it stands, on a bounded sample of the same workload ---------------------

@@ -211,6 +211,11 @@ def main() -> int:
                 tag = f"conv3x3_C{C}_{H}x{H}_N32_{'bf16' if bf16 else 'f32'}"
                 cases.append(Case(tag + "_bwd_data", wt, 1))
                 cases.append(Case(tag + "_bwd_weight", wt, 2))
+        # the matrix product the paper substitutes in GPT-2 (QKV projection, 8192 tokens), all three passes
+        for bf16 in (False, True):
+            wq = wl.qkv_projection(bf16)
+            for which, tag in enumerate(("fwd", "bwd_data", "bwd_weight")):
+                cases.append(Case(f"qkv_mm_8192x768x2304_{'bf16' if bf16 else 'f32'}_{tag}", wq, which, sets=2))
         for c in cases:
             med, avg = c.time_ms(30)
             tf = c.flops / (med * 1e-3) / 1e12

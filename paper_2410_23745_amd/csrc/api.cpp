@@ -35,7 +35,8 @@ namespace {
 std::atomic<int> g_policy{0};
 
 const char* const kKernelNames[syno::KERNEL_COUNT] = {
-    "generic_index_program", "bandwidth_depthwise", "bandwidth_share_window", "mfma_contraction_f32", "mfma_contraction_bf16"};
+    "generic_index_program", "bandwidth_depthwise", "bandwidth_share_window", "mfma_contraction_f32", "mfma_contraction_bf16",
+    "mfma_contraction_transposed"};
 
 syno_status run(const syno_plan* plan, int which, const void* A, const void* B, void* out, void* ws,
                 hipStream_t stream) {
@@ -50,6 +51,11 @@ syno_status run(const syno_plan* plan, int which, const void* A, const void* B, 
     case syno::KERNEL_MFMA_BF16:
       if (which == SYNO_BWD_WEIGHT) return syno::launch_mfma_dw(plan, A, B, out, ws, stream);
       return syno::launch_mfma(plan, which, A, B, out, ws, stream);
+    case syno::KERNEL_MFMA_TRANSPOSED:
+      // forward: the weight is the image and the input the filter; the gradients keep their operand order
+      // (upstream gradient first) and only name the other contraction of the inner plan
+      if (which == SYNO_FWD) return run(plan->inner, SYNO_FWD, B, A, out, ws, stream);
+      return run(plan->inner, L.variant, A, B, out, ws, stream);
     default: return SYNO_ERR_UNSUPPORTED;
   }
 }
@@ -127,6 +133,12 @@ syno_status syno_plan_describe(const syno_plan* plan, int which, char* buf, size
     case syno::KERNEL_MFMA_BF16:
       d += " " + (which == SYNO_BWD_WEIGHT ? syno::mfma_dw_describe(plan) : syno::mfma_describe(plan, which));
       break;
+    case syno::KERNEL_MFMA_TRANSPOSED: {
+      char inner[400];
+      if (syno_plan_describe(plan->inner, plan->launch[which].variant, inner, sizeof(inner)) == SYNO_OK)
+        d += std::string(" as 1x1 convolution: ") + inner;
+      break;
+    }
     default: break;
   }
   snprintf(buf, size, "%s", d.c_str());

@@ -77,6 +77,7 @@ enum KernelId : int32_t {
   KERNEL_BW_WINDOW,
   KERNEL_MFMA_F32,
   KERNEL_MFMA_BF16,
+  KERNEL_MFMA_TRANSPOSED,   // a matrix product run as the 1x1 convolution with exchanged operand roles (plan->inner)
   KERNEL_COUNT
 };
 
@@ -105,6 +106,9 @@ struct syno_plan {
   bool share_window = false;
   syno::ShareWindow window{};
   syno::Launch launch[3];
+  // matrix products: the plan of the equivalent 1x1 convolution (owned); Launch::variant holds its contraction
+  syno_plan* inner = nullptr;
+  ~syno_plan() { delete inner; }
 };
 
 namespace syno {

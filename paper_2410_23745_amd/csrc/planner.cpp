@@ -7,6 +7,7 @@
 // once j is enumerated (with a range test), Stride v = S*i is solved when S divides v, and
 // coordinates nothing determines are enumerated.
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <string>
@@ -712,6 +713,40 @@ bool recognise_share_window(const Graph& g, ShareWindow& sw) {
   return true;
 }
 
+// out[i,j] = sum_k X[i,k] * W[k,j] (Table 2's matrix multiplication): two output iterators, one Reduce Shared
+// between X's inner axis and W's outer axis, nothing else.
+bool recognise_matmul(const Graph& g, int64_t& M, int64_t& K, int64_t& N) {
+  std::vector<Root> roots;
+  std::vector<Expr> e;
+  std::vector<Check> checks;
+  if (!analyse(g, roots, e, checks)) return false;
+  if (g.n_out != 2 || g.in_coords.size() != 2 || g.w_coords.size() != 2 || !checks.empty()) return false;
+  int alive = 0;
+  for (const Root& r : roots) alive += r.alive ? 1 : 0;
+  if (alive != 3 || roots.size() != 3) return false;
+  auto bare = [&](int coord) {
+    const Expr& x = e[g.S(coord)];
+    if (!x.pure() || x.c != 0 || x.coef.size() != 1 || x.coef.begin()->second != 1) return -1;
+    return x.coef.begin()->first;
+  };
+  const int xi = bare(g.in_coords[0]), xk = bare(g.in_coords[1]);
+  const int wk = bare(g.w_coords[0]), wj = bare(g.w_coords[1]);
+  if (xi != 0 || wj != 1 || xk != 2 || wk != 2 || !roots[2].is_reduce) return false;
+  M = roots[0].size; N = roots[1].size; K = roots[2].size;
+  return true;
+}
+
+// The width to fold the N contiguous output columns of a matrix product into image rows of: the 1x1
+// convolution does not couple pixels, so any factorisation N = rows * width is the same contraction; widths
+// near the ones the contraction kernels are tuned on are preferred.  0 when N has no usable divisor.
+int64_t fold_width(int64_t N) {
+  if (N <= 64) return N >= 4 ? N : 0;
+  int64_t best = 0;
+  for (int64_t w = 64; w >= 7; --w)
+    if (N % w == 0 && (best == 0 || std::llabs(w - 56) < std::llabs(best - 56))) best = w;
+  return best;
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------
@@ -780,6 +815,44 @@ syno_status build_plan(const syno_desc* desc, int policy, syno_plan* plan, std::
     } else if (which == SYNO_BWD_WEIGHT && mfma_dw_supports(plan)) {
       L.kernel = plan->in_dtype == SYNO_BF16 ? KERNEL_MFMA_BF16 : KERNEL_MFMA_F32;
       mfma_dw_configure(plan);
+    }
+  }
+  // A matrix product is a 1x1 convolution with the operands' roles exchanged: W[k,j] is an "image" with k as
+  // channels and the contiguous j as pixels, X[i,k] the weight of output channel i, and out[i,j] is laid out
+  // channel-major like a convolution result.  Its gradients exchange roles too: dX is that convolution's
+  // weight gradient, dW its input gradient (both need an fp32 result type).
+  int64_t M = 0, K = 0, N = 0;
+  if (policy != 1 && !plan->conv_like && recognise_matmul(g, M, K, N)) {
+    const int64_t width = fold_width(N);
+    if (width > 0) {
+      const syno_dim dims[4] = {{"n", 1}, {"i", M}, {"jr", N / width}, {"jc", width}};
+      syno_prim pr[2] = {};
+      pr[0].kind = SYNO_REDUCE; pr[0].in[0] = pr[0].in[1] = -1; pr[0].out[0] = 4; pr[0].out[1] = -1; pr[0].param = K;
+      pr[0].shift_by = -1;
+      pr[1].kind = SYNO_SHARE; pr[1].in[0] = 4; pr[1].in[1] = -1; pr[1].out[0] = 5; pr[1].out[1] = 6;
+      pr[1].shift_by = -1;
+      const int32_t xin[4] = {0, 5, 2, 3}, win[2] = {1, 6};
+      syno_desc inner{};
+      inner.n_out = 4; inner.out_dims = dims; inner.n_prim = 2; inner.prims = pr;
+      inner.n_in = 4; inner.input_coords = xin; inner.n_w = 2; inner.weight_coords = win;
+      inner.in_dtype = desc->in_dtype; inner.out_dtype = desc->out_dtype;
+      syno_plan* ip = new syno_plan();
+      if (build_plan(&inner, policy, ip, nullptr) == SYNO_OK) {
+        const int map[3] = {SYNO_FWD, SYNO_BWD_WEIGHT, SYNO_BWD_DATA};
+        bool any = false;
+        for (int which = 0; which < 3; ++which) {
+          const Launch& IL = ip->launch[map[which]];
+          const bool fast = IL.kernel == KERNEL_MFMA_F32 || IL.kernel == KERNEL_MFMA_BF16;
+          if (!fast || (which != SYNO_FWD && desc->out_dtype != SYNO_F32)) continue;
+          plan->launch[which].kernel = KERNEL_MFMA_TRANSPOSED;
+          plan->launch[which].variant = map[which];
+          plan->launch[which].workspace = IL.workspace;
+          any = true;
+        }
+        if (any) plan->inner = ip; else delete ip;
+      } else {
+        delete ip;
+      }
     }
   }
   return SYNO_OK;

@@ -9,7 +9,8 @@ WRITE_SIZE report for it gives the factor that turns the counters into bytes.
 
 Cases: config0, config1_s{0..3}_{f32|bf16}, config2, config3, config4_{fwd|bwd_data|bwd_weight}, and the backward
 passes of the first two shapes with a seeded output gradient: config1t_s{0..3}_{f32|bf16}_{fwd|bwd_data|bwd_weight},
-config3t_{fwd|bwd_data|bwd_weight}; Operator 1 (two stages) on a ResNet-18 stage shape: op1_s{0..3}_{f32|bf16}_{fwd|bwd}.
+config3t_{fwd|bwd_data|bwd_weight}; Operator 1 (two stages) on a ResNet-18 stage shape: op1_s{0..3}_{f32|bf16}_{fwd|bwd}; the GPT-2 QKV projection as a matrix product:
+qkv_{f32|bf16}_{fwd|bwd_data|bwd_weight}.
 Buffers rotate over several copies so that every launch reads HBM rather than the last-level cache.
 """
 from __future__ import annotations
@@ -40,6 +41,10 @@ def make_case(name: str):
         w = wl.config2()
     elif name == "config3":
         w = wl.config3()
+    elif name.startswith("qkv_"):            # qkv_<f32|bf16>_<fwd|bwd_data|bwd_weight>
+        dt, direction = name[4:].split("_", 1)
+        w = wl.qkv_projection(dt == "bf16")
+        which = {"fwd": 0, "bwd_data": 1, "bwd_weight": 2}[direction]
     elif name.startswith("config4_"):
         w = wl.config4()
         which = {"fwd": 0, "bwd_data": 1, "bwd_weight": 2}[name[8:]]

@@ -258,3 +258,20 @@ def operator1(stage: int, bf16: bool, N: int = 32, with_grad: bool = True) -> Ch
     """Operator 1 in place of the 3x3 convolution of a ResNet-18 stage (g = 4, s = 2, k1 = 3)."""
     C, H = RESNET18_STAGES[stage]
     return make_operator1(N, C, H, seed=0, bf16=bf16, with_grad=with_grad)
+
+
+def make_matmul(M, K, N, seed=0, bf16=False, with_grad=False) -> Workload:
+    """Table 2's matrix multiplication out[i,j] = sum_k X[i,k] * Wt[k,j]; X ~ N(0,1), Wt ~ U(+-1/sqrt(K))."""
+    desc = matmul(M, N, K, BF16 if bf16 else F32, F32)
+    s = Stream(seed)
+    xs, ws, os = (M, K), (K, N), (M, N)
+    X = s.normal(xs)
+    W = s.uniform_pm(1.0 / np.sqrt(K), ws)
+    G = s.normal(os) if with_grad else None
+    return _finish(desc, xs, ws, os, X, W, G, K)
+
+
+def qkv_projection(bf16: bool, tokens: int = 8192, with_grad: bool = True) -> Workload:
+    """The matrix product the paper substitutes in GPT-2 (117M: 768 embedding dimensions, Q, K and V projected
+    at once): [tokens, 768] x [768, 2304]; 8192 tokens stand for 8 sequences of 1024."""
+    return make_matmul(tokens, 768, 2304, seed=0, bf16=bf16, with_grad=with_grad)

@@ -130,7 +130,7 @@ def test_out_of_range_points_yield_minus_one(syno):
 
 def test_kernel_choice(syno):
     names = lambda d: [syno.Plan(d).kernel(i) for i in range(3)]
-    assert all(n == "generic_index_program" for n in names(wl.matmul(3, 4, 5)))
+    assert all(n == "generic_index_program" for n in names(wl.matmul(3, 3, 5)))      # 3 columns: too narrow to fold
     assert all(n == "generic_index_program" for n in names(pixel_unshuffle_conv()))
     # the benchmarked workloads run on the tuned families, not on the index-program kernels
     for stage in range(4):
@@ -196,3 +196,15 @@ def test_unreduced_window_goes_to_the_streaming_family(syno):
     assert syno.Plan(wl.operator1_stage1(2, 16, 16, 8, 8, 4, 2, 3, F32, BF16)).kernel(0) == "generic_index_program"
     # the same window Reduced is the convolution-like form, not this one
     assert syno.Plan(wl.conv2d(2, 16, 16, 8, 8, 1, 3)).kernel(0).startswith("mfma")
+
+
+def test_matmul_is_planned_as_a_convolution_with_exchanged_roles(syno):
+    p = syno.Plan(wl.matmul(96, 2304, 768))
+    assert [p.kernel(i) for i in range(3)] == ["mfma_contraction_transposed"] * 3
+    assert "1x1 convolution" in p.describe(0)
+    assert p.x_shape == (96, 768) and p.w_shape == (768, 2304) and p.out_shape == (96, 2304)
+    # a bf16 result type leaves the gradients on the index-program kernels (their results must be fp32 inside)
+    q = syno.Plan(wl.matmul(96, 2304, 768, BF16, BF16))
+    assert q.kernel(0) == "mfma_contraction_transposed" and q.kernel(1) == q.kernel(2) == "generic_index_program"
+    # a prime number of columns above 64 cannot be folded into image rows
+    assert syno.Plan(wl.matmul(8, 127, 16)).kernel(0) == "generic_index_program"

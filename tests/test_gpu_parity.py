@@ -293,6 +293,22 @@ def test_operator1_full_size(syno, oracle, bf16):
     run_chain(syno, oracle, wl.operator1(0, bf16), 0)
 
 
+# ------------------------------------------------------------------------------------------------
+# matrix products (Table 2) run as 1x1 convolutions with the operands' roles exchanged
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("M,K,N", [(37, 45, 29), (130, 72, 112), (64, 200, 640), (9, 16, 7 * 13)])
+def test_matmul_small(syno, oracle, M, K, N, bf16):
+    names = run_all(syno, oracle, wl.make_matmul(M, K, N, seed=41, bf16=bf16, with_grad=True), 0)
+    assert names == ["mfma_contraction_transposed"] * 3
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_qkv_projection_full_size_sampled(syno, oracle, bf16):
+    names = run_all(syno, oracle, wl.qkv_projection(bf16), 0, full=False, n_sample=2048)
+    assert names == ["mfma_contraction_transposed"] * 3
+
+
 def test_rejects_wrong_arguments(syno):
     plan = syno.Plan(wl.conv2d(1, 4, 4, 5, 5))
     X = torch.zeros(plan.x_shape, device="cuda")

@@ -11,13 +11,14 @@
 // one image, X is staged with its KH-1 halo rows (zero outside the image), the row pitch is a multiple of
 // 8 elements, and tap kh is a further shift by kh whole rows.
 //
-// The pixel axis is split over workgroups (split-K); each writes its 64x64xKW partial in the layout
-// of dW into the workspace and a second kernel adds the partials in a fixed order, so the result does
-// not depend on scheduling.
+// The pixel axis is split over workgroups (split-K); each writes its tile of sums into the workspace in
+// the register layout of the accumulators (coalesced 16-byte stores) and a second kernel adds the partials
+// in a fixed order and scatters them into dW, so the result does not depend on scheduling.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
 #include <cstdint>
+#include <cstdlib>
 #include <cstdio>
 #include <string>
 #include <type_traits>
@@ -32,7 +33,8 @@ struct DwParams {
   int32_t h_wrap, h_shift, h_shift_g;  // X row = (h + h_shift + h_shift_g*g) mod H when wrapped, else h
   int32_t plane, gs_n, xs_n;           // H*W; image strides of G and X
   int32_t ws_g, ws_o, ws_c, ws_kh, ws_kw;   // dW strides
-  int32_t w_elems;                     // elements of dW (= stride between partials)
+  int32_t w_elems;                     // elements of dW
+  int32_t n_tiles, ct, slots;          // workgroup tiles (g, o block, c block); c-tiles per wave; 8 * ct * KH*KW
   int32_t pitch, TRK, CP, CPp;         // LDS row pitch, rows per chunk, chunk length (multiple of 32), LDS channel pitch
   int32_t CPg;                         // fp32 kernel: channel pitch of the G tile (it has no halo rows); CPp is X's
   int32_t rows_per_split, n_splits, n_oblk, n_cblk;
@@ -239,22 +241,18 @@ __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint
   }
 
   // partial[split][dW layout]: lane holds 4 consecutive o (rows of D) at one c (column)
-  float* dst = partial + (int64_t)split * p.w_elems + (int64_t)g * p.ws_g;
+  // partial[split][tile][slot][lane]: every accumulator register quadruple goes out as it is, one 16-byte store
+  // per lane (1 KB per wave and slot); the reduction kernel knows which weights a (slot, lane) holds
+  constexpr int SLOTS = 8 * CT * T;
+  const int tile = (g * p.n_oblk + ob) * p.n_cblk + cb;
+  floatx4* dst = reinterpret_cast<floatx4*>(partial) +
+                 ((int64_t)split * p.n_tiles + tile) * (SLOTS * 64) + (widx * 2 * CT * T) * 64 + lane;
 #pragma unroll
   for (int ao = 0; ao < 2; ++ao)
 #pragma unroll
-    for (int i = 0; i < CT; ++i) {
-      const int c = cb * CX + (CT * wc + i) * 16 + (lane & 15);
-      if (c >= p.Cg) continue;
+    for (int i = 0; i < CT; ++i)
 #pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int o = ob * 64 + (2 * wo + ao) * 16 + 4 * (lane >> 4) + v;
-        if (o >= p.Og) continue;
-#pragma unroll
-        for (int t = 0; t < T; ++t)
-          dst[(int64_t)o * p.ws_o + (int64_t)c * p.ws_c + (t / KW) * p.ws_kh + (t % KW) * p.ws_kw] = acc[ao][i][t][v];
-      }
-    }
+      for (int t = 0; t < T; ++t) dst[((ao * CT + i) * T + t) * 64] = acc[ao][i][t];
 }
 
 // fp32 inputs: the same contraction with v_mfma_f32_16x16x4_f32, whose K-step is 4 consecutive pixels (lane ->
@@ -435,56 +433,100 @@ __global__ __launch_bounds__(256) void dw_mfma_f32(const DwParams p, const float
     else mfmas(fa0, fb0);
   }
 
-  float* dst = partial + (int64_t)split * p.w_elems + (int64_t)g * p.ws_g;
+  // partial[split][tile][slot][lane]: every accumulator register quadruple goes out as it is, one 16-byte store
+  // per lane (1 KB per wave and slot); the reduction kernel knows which weights a (slot, lane) holds
+  constexpr int SLOTS = 8 * CT * T;
+  const int tile = (g * p.n_oblk + ob) * p.n_cblk + cb;
+  floatx4* dst = reinterpret_cast<floatx4*>(partial) +
+                 ((int64_t)split * p.n_tiles + tile) * (SLOTS * 64) + (widx * 2 * CT * T) * 64 + lane;
 #pragma unroll
   for (int ao = 0; ao < 2; ++ao)
 #pragma unroll
-    for (int i = 0; i < CT; ++i) {
-      const int c = cb * CX + (CT * wc + i) * 16 + (lane & 15);
-      if (c >= p.Cg) continue;
+    for (int i = 0; i < CT; ++i)
 #pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int o = ob * 64 + (2 * wo + ao) * 16 + 4 * (lane >> 4) + v;
-        if (o >= p.Og) continue;
-#pragma unroll
-        for (int t = 0; t < T; ++t)
-          dst[(int64_t)o * p.ws_o + (int64_t)c * p.ws_c + (t / KW) * p.ws_kh + (t % KW) * p.ws_kw] = acc[ao][i][t][v];
-      }
-    }
+      for (int t = 0; t < T; ++t) dst[((ao * CT + i) * T + t) * 64] = acc[ao][i][t];
 }
 
-// Partials are added in a fixed order (four interleaved groups of splits, then the groups), so the result
-// does not depend on scheduling.
-__global__ __launch_bounds__(256) void dw_reduce(const float* __restrict__ partial, float* __restrict__ dW, int n_elems,
-                                                 int n_splits) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= n_elems) return;
-  float s = 0.f;
-  for (int k = 0; k < n_splits; ++k) s += partial[(int64_t)k * n_elems + i];
-  dW[i] = s;
-}
-
-// The same for element counts that are multiples of 4: a block covers 64 float4 columns with 4 waves, wave j
-// adds splits j, j+4, ...; the four sums meet in LDS.
-__global__ __launch_bounds__(256) void dw_reduce4(const float4* __restrict__ partial, float4* __restrict__ dW, int n4,
-                                                  int n_splits) {
-  __shared__ float4 sums[4][64];
+// Adds the split partials kept in the accumulator layout of the contraction kernels and writes the sums into dW;
+// the variant for few splits of a large dW.  A block owns one 16 (o) x 16 (c) tile with all its T taps: T
+// consecutive slots of 64 quadruples, slot = ((wave*2 + ao)*ct + i)*T + t naming the o-tile 2*(wave>>1) + ao and the
+// c-tile ct*(wave&1) + i; lane l of a quadruple holds rows 4*(l>>4) .. +3 (o) of column l&15 (c).  Wave j adds the
+// splits, in order, for taps j, j+4, ...; then the threads walk the tile in (o, c, tap) order, which is contiguous in
+// dW for the usual weight layouts, so dW is written in whole lines.
+constexpr int kMaxTaps = 9;
+__global__ __launch_bounds__(256) void dw_reduce_tiles(const DwParams p, const float4* __restrict__ partial,
+                                                       float* __restrict__ dW) {
+  __shared__ float sums[kMaxTaps][64][4];
   const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
-  const int col = blockIdx.x * 64 + lane;
-  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (col < n4) {
-#pragma unroll 4
-    for (int k = grp; k < n_splits; k += 4) {
-      const float4 v = partial[(int64_t)k * n4 + col];
+  const int T = p.KH * p.KW;
+  const int subs = p.slots / T;                    // 16x16 tiles per workgroup tile
+  const int tile = blockIdx.x / subs, sub = blockIdx.x - tile * subs;
+  const int64_t n4 = (int64_t)p.n_tiles * p.slots * 64;
+  for (int t = grp; t < T; t += 4) {
+    const int64_t e = ((int64_t)tile * p.slots + sub * T + t) * 64 + lane;
+    float4 s = partial[e];
+    for (int k = 1; k < p.n_splits; ++k) {
+      const float4 v = partial[(int64_t)k * n4 + e];
       s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
     }
+    *reinterpret_cast<float4*>(sums[t][lane]) = s;
+  }
+  __syncthreads();
+  int q = tile;
+  const int cb = q % p.n_cblk; q /= p.n_cblk;
+  const int ob = q % p.n_oblk;
+  const int g = q / p.n_oblk;
+  const int i = sub % p.ct, ao = (sub / p.ct) & 1, wave = sub / (p.ct * 2);
+  const int c0 = cb * 32 * p.ct + (p.ct * (wave & 1) + i) * 16;
+  // thread = (row ol, 16 threads per row); a row is 16*T consecutive (c, tap) pairs
+  const int ol = threadIdx.x >> 4, o = ob * 64 + (2 * (wave >> 1) + ao) * 16 + ol;
+  if (o >= p.Og) return;
+  const uint32_t inv_t = (65536u + T - 1) / T;      // rem / T for rem < 16 * kMaxTaps
+  const int64_t row = (int64_t)g * p.ws_g + (int64_t)o * p.ws_o;
+  for (int rem = threadIdx.x & 15; rem < 16 * T; rem += 16) {
+    const int cl = (int)(((uint32_t)rem * inv_t) >> 16), t = rem - cl * T;
+    const int c = c0 + cl;
+    if (c >= p.Cg) continue;
+    const int kh = t >= 2 * p.KW ? 2 : (t >= p.KW ? 1 : 0);
+    dW[row + (int64_t)c * p.ws_c + kh * p.ws_kh + (t - kh * p.KW) * p.ws_kw] = sums[t][(ol >> 2) * 16 + cl][ol & 3];
+  }
+}
+
+// The same sums for many splits and few tiles: a block owns one slot (64 quadruples, one tap of a 16x16 tile), which
+// keeps enough blocks in flight when dW is small; the stores are scattered, which does not matter at that size.
+__global__ __launch_bounds__(256) void dw_reduce_slots(const DwParams p, const float4* __restrict__ partial,
+                                                       float* __restrict__ dW) {
+  __shared__ float4 sums[4][64];
+  const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
+  const int64_t n4 = (int64_t)p.n_tiles * p.slots * 64;
+  const int64_t e = (int64_t)blockIdx.x * 64 + lane;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+  for (int k = grp; k < p.n_splits; k += 4) {
+    const float4 v = partial[(int64_t)k * n4 + e];
+    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
   }
   sums[grp][lane] = s;
   __syncthreads();
-  if (grp == 0 && col < n4) {
-    const float4 a = sums[0][lane], b = sums[1][lane], c = sums[2][lane], d = sums[3][lane];
-    dW[col] = make_float4((a.x + b.x) + (c.x + d.x), (a.y + b.y) + (c.y + d.y), (a.z + b.z) + (c.z + d.z),
-                          (a.w + b.w) + (c.w + d.w));
+  if (grp != 0) return;
+  const float4 a = sums[0][lane], b = sums[1][lane], c4 = sums[2][lane], d = sums[3][lane];
+  const float r[4] = {(a.x + b.x) + (c4.x + d.x), (a.y + b.y) + (c4.y + d.y), (a.z + b.z) + (c4.z + d.z),
+                      (a.w + b.w) + (c4.w + d.w)};
+  const int T = p.KH * p.KW;
+  int q = blockIdx.x;
+  const int slot = q % p.slots; q /= p.slots;
+  const int cb = q % p.n_cblk; q /= p.n_cblk;
+  const int ob = q % p.n_oblk;
+  const int g = q / p.n_oblk;
+  const int t = slot % T, sub = slot / T;
+  const int i = sub % p.ct, ao = (sub / p.ct) & 1, wave = sub / (p.ct * 2);
+  const int c = cb * 32 * p.ct + (p.ct * (wave & 1) + i) * 16 + (lane & 15);
+  if (c >= p.Cg) return;
+  const int64_t base = (int64_t)g * p.ws_g + (int64_t)c * p.ws_c + (t / p.KW) * p.ws_kh + (t % p.KW) * p.ws_kw;
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    const int o = ob * 64 + (2 * (wave >> 1) + ao) * 16 + 4 * (lane >> 4) + v;
+    if (o < p.Og) dW[base + (int64_t)o * p.ws_o] = r[v];
   }
 }
 
@@ -533,8 +575,13 @@ bool fill_dw(const syno_plan* plan, DwParams& p) {
   p.n_cblk = (c.Cg + cx - 1) / cx;
   // split the chunks: aim at one workgroup per CU, keep the partials below ~32 MB
   const int tiles = c.G * p.n_oblk * p.n_cblk;
-  int splits = std::max(1, std::min(p.n_chunks, 256 / std::max(1, tiles)));
-  while (splits > 1 && (int64_t)splits * plan->w_elems * 4 > (32ll << 20)) splits /= 2;
+  p.n_tiles = tiles;
+  p.ct = cx / 32;
+  p.slots = 8 * p.ct * c.KH * c.KW;
+  int target = 256;
+  if (const char* e = getenv("SYNO_DW_WORKGROUPS")) target = std::max(1, atoi(e));    // tuning aid
+  int splits = std::max(1, std::min(p.n_chunks, target / std::max(1, tiles)));
+  while (splits > 1 && (int64_t)splits * tiles * p.slots * 1024 > (40ll << 20)) splits /= 2;
   p.chunks_per_split = (p.n_chunks + splits - 1) / splits;
   p.rows_per_split = p.chunks_per_split * p.TRK;
   p.n_splits = (p.n_chunks + p.chunks_per_split - 1) / p.chunks_per_split;
@@ -590,8 +637,11 @@ bool fill_dw_f32(const syno_plan* plan, DwParams& p) {
   p.n_oblk = (c.Og + 63) / 64;
   p.n_cblk = (c.Cg + cx - 1) / cx;
   const int tiles = c.G * p.n_oblk * p.n_cblk;
+  p.n_tiles = tiles;
+  p.ct = cx / 32;
+  p.slots = 8 * p.ct * c.KH * c.KW;
   int splits = std::max(1, std::min(p.n_chunks, 256 / std::max(1, tiles)));
-  while (splits > 1 && (int64_t)splits * plan->w_elems * 4 > (32ll << 20)) splits /= 2;
+  while (splits > 1 && (int64_t)splits * tiles * p.slots * 1024 > (40ll << 20)) splits /= 2;
   p.chunks_per_split = (p.n_chunks + splits - 1) / splits;
   p.rows_per_split = p.chunks_per_split * p.TRK;
   p.n_splits = (p.n_chunks + p.chunks_per_split - 1) / p.chunks_per_split;
@@ -626,7 +676,8 @@ void mfma_dw_configure(syno_plan* plan) {
   DwParams dp;
   fill_any(plan, dp);
   plan->launch[SYNO_BWD_WEIGHT].variant = 0;
-  plan->launch[SYNO_BWD_WEIGHT].workspace = (size_t)dp.n_splits * plan->w_elems * 4;
+  // one 64 x 32*ct x taps tile of fp32 sums per workgroup (whole tiles also where Og or Cg end inside one)
+  plan->launch[SYNO_BWD_WEIGHT].workspace = (size_t)dp.n_splits * dp.n_tiles * dp.slots * 1024;
 }
 
 std::string mfma_dw_describe(const syno_plan* plan) {
@@ -664,12 +715,12 @@ syno_status launch_mfma_dw(const syno_plan* plan, const void* A, const void* B, 
     else if (p.KH == 3) by_vec(integral_constant<int, 3>{}, integral_constant<int, 1>{}, integral_constant<int, 2>{});
     else if (p.KW == 3) by_vec(integral_constant<int, 1>{}, integral_constant<int, 3>{}, integral_constant<int, 2>{});
     else by_vec(integral_constant<int, 1>{}, integral_constant<int, 1>{}, integral_constant<int, 2>{});
-    if ((p.w_elems & 3) == 0 && (reinterpret_cast<uintptr_t>(out) & 15) == 0)
-      hipLaunchKernelGGL(dw_reduce4, dim3((p.w_elems / 4 + 63) / 64), dim3(256), 0, stream, reinterpret_cast<const float4*>(partf),
-                         static_cast<float4*>(out), p.w_elems / 4, p.n_splits);
+    if (p.n_splits > 4)
+      hipLaunchKernelGGL(dw_reduce_slots, dim3(p.n_tiles * p.slots), dim3(256), 0, stream, p,
+                         reinterpret_cast<const float4*>(partf), static_cast<float*>(out));
     else
-      hipLaunchKernelGGL(dw_reduce, dim3((p.w_elems + 255) / 256), dim3(256), 0, stream, partf, static_cast<float*>(out),
-                         p.w_elems, p.n_splits);
+      hipLaunchKernelGGL(dw_reduce_tiles, dim3(p.n_tiles * (p.slots / (p.KH * p.KW))), dim3(256), 0, stream, p,
+                         reinterpret_cast<const float4*>(partf), static_cast<float*>(out));
     return hipGetLastError() == hipSuccess ? SYNO_OK : SYNO_ERR_HIP;
   }
   const uint16_t* G = static_cast<const uint16_t*>(A);
@@ -692,12 +743,14 @@ syno_status launch_mfma_dw(const syno_plan* plan, const void* A, const void* B, 
     else if (p.KW == 3) launch(dw_mfma_bf16<1, 3, 2, false>);
     else launch(dw_mfma_bf16<1, 1, 2, false>);
   }
-  if ((p.w_elems & 3) == 0 && (reinterpret_cast<uintptr_t>(out) & 15) == 0)
-    hipLaunchKernelGGL(dw_reduce4, dim3((p.w_elems / 4 + 63) / 64), dim3(256), 0, stream, reinterpret_cast<const float4*>(part),
-                       static_cast<float4*>(out), p.w_elems / 4, p.n_splits);
+  // many splits of a small dW: one block per slot keeps the device busy; few splits of a large dW: one block per
+  // 16x16 tile with all its taps writes dW in whole lines
+  if (p.n_splits > 4)
+    hipLaunchKernelGGL(dw_reduce_slots, dim3(p.n_tiles * p.slots), dim3(256), 0, stream, p,
+                       reinterpret_cast<const float4*>(part), static_cast<float*>(out));
   else
-    hipLaunchKernelGGL(dw_reduce, dim3((p.w_elems + 255) / 256), dim3(256), 0, stream, part, static_cast<float*>(out),
-                       p.w_elems, p.n_splits);
+    hipLaunchKernelGGL(dw_reduce_tiles, dim3(p.n_tiles * (p.slots / (p.KH * p.KW))), dim3(256), 0, stream, p,
+                       reinterpret_cast<const float4*>(part), static_cast<float*>(out));
   return hipGetLastError() == hipSuccess ? SYNO_OK : SYNO_ERR_HIP;
 }
 

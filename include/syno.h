@@ -161,6 +161,16 @@ typedef struct syno_chain syno_chain;
 /* Plans every stage.  Errors of syno_plan_create apply per stage; SYNO_ERR_SHAPE when consecutive stages do
  * not fit (element count or element type), or n_stages is outside 1..8. */
 syno_status syno_chain_create(const syno_desc* stages, int32_t n_stages, syno_chain** chain);
+/* The materialised-reduction pass itself (code-generation section; its Fig. shows Y[i] = sum_{ik,is} X[..] cut
+ * into Z = sum_is, Y = sum_ik Z): for every Reduce of ONE single-weight pGraph the primitives between it and the
+ * tensors form a candidate first stage whose result Z is stored; the cut with the fewest multiply-adds is taken
+ * when it beats the single loop nest, and the rest of the graph is cut again.  The chain has 1..8 stages; exactly
+ * one of them (syno_chain_weight_stage) keeps the graph's weight, the others have none: in the W and dW arrays
+ * of the forward and backward calls only that entry is read or written.  Graphs with a Shift that reads another
+ * coordinate are left whole.  Intermediates take the graph's input element type. */
+syno_status syno_chain_create_materialized(const syno_desc* desc, syno_chain** chain);
+/* Stage that takes the caller's weight, or -1 when every stage has its own (syno_chain_create). */
+int32_t syno_chain_weight_stage(const syno_chain* chain);
 syno_status syno_chain_destroy(syno_chain* chain);
 /* Number of stages, and the plan of one stage (borrowed; valid until the chain is destroyed; NULL when out of range). */
 int32_t syno_chain_stages(const syno_chain* chain);

@@ -17,7 +17,8 @@ EXPORTS = ("syno_plan_create", "syno_plan_destroy", "syno_forward", "syno_backwa
            "syno_plan_workspace_bytes", "syno_plan_shapes", "syno_plan_kernel", "syno_plan_describe", "syno_set_kernel_policy",
            "syno_plan_free_size", "syno_debug_gather", "syno_debug_gather_host", "syno_status_string",
            "syno_chain_create", "syno_chain_destroy", "syno_chain_stages", "syno_chain_plan",
-           "syno_chain_workspace_bytes", "syno_chain_forward", "syno_chain_backward")
+           "syno_chain_workspace_bytes", "syno_chain_forward", "syno_chain_backward",
+           "syno_chain_create_materialized", "syno_chain_weight_stage")
 
 
 class _Dim(ctypes.Structure):
@@ -75,6 +76,8 @@ def load_library():
     vpp = ctypes.POINTER(vp)
     lib.syno_chain_create.argtypes = [ctypes.POINTER(_Desc), ctypes.c_int32, ctypes.POINTER(vp)]
     lib.syno_chain_destroy.argtypes = [vp]
+    lib.syno_chain_create_materialized.argtypes = [ctypes.POINTER(_Desc), ctypes.POINTER(vp)]
+    lib.syno_chain_weight_stage.argtypes = [vp]
     lib.syno_chain_stages.argtypes = [vp]
     lib.syno_chain_plan.argtypes = [vp, ctypes.c_int32]
     lib.syno_chain_plan.restype = vp
@@ -264,25 +267,49 @@ class Plan:
         return a, b
 
 
+class _StageTypes:
+    def __init__(self, in_dtype, out_dtype):
+        self.in_dtype, self.out_dtype = in_dtype, out_dtype
+
+
 class Chain:
     """Owns one syno_chain: an operator evaluated as consecutive single-weight stages.  `descs` is a list of
     OpDesc-like objects.  `stages[i]` is a borrowed Plan for queries (shapes, kernel names)."""
 
-    def __init__(self, descs):
+    def __init__(self, descs, _materialize=None):
         lib = load_library()
-        arr = (_Desc * len(descs))()
-        keep = []
-        for i, d in enumerate(descs):
-            arr[i], k = _marshal(d)
-            keep.append(k)
         handle = ctypes.c_void_p()
-        st = lib.syno_chain_create(arr, len(descs), ctypes.byref(handle))
-        if st:
-            raise SynoError(st, "syno_chain_create")
+        if _materialize is not None:
+            d, keep = _marshal(_materialize)
+            st = lib.syno_chain_create_materialized(ctypes.byref(d), ctypes.byref(handle))
+            if st:
+                raise SynoError(st, "syno_chain_create_materialized")
+        else:
+            arr = (_Desc * max(1, len(descs)))()
+            keep = []
+            for i, d in enumerate(descs):
+                arr[i], k = _marshal(d)
+                keep.append(k)
+            st = lib.syno_chain_create(arr, len(descs), ctypes.byref(handle))
+            if st:
+                raise SynoError(st, "syno_chain_create")
         self._h = handle
         n = lib.syno_chain_stages(self._h)
+        self.weight_stage = lib.syno_chain_weight_stage(self._h)     # -1: every stage has its own weight
+        if _materialize is not None:
+            # stage i reads the graph's input type; only the last stage writes the graph's output type
+            descs = [_StageTypes(_materialize.in_dtype, _materialize.in_dtype if i + 1 < n else _materialize.out_dtype)
+                     for i in range(n)]
         self.stages = [Plan(descs[i], _borrowed=lib.syno_chain_plan(self._h, i), _owner=self) for i in range(n)]
         self._ws = {}
+
+    @classmethod
+    def materialized(cls, desc):
+        """The chain the library's materialised-reduction pass cuts one single-weight pGraph into."""
+        return cls(None, _materialize=desc)
+
+    def _own(self, i: int) -> bool:
+        return self.weight_stage < 0 or self.weight_stage == i
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None
@@ -320,10 +347,10 @@ class Chain:
         """Returns (out, acts)."""
         first, last = self.stages[0], self.stages[-1]
         px = first._arg(X, first.x_shape, first.in_dtype, "syno_chain_forward X")
-        pw = [p._arg(w, p.w_shape, p.in_dtype, f"syno_chain_forward W[{i}]") for i, (p, w) in
-              enumerate(zip(self.stages, Ws))]
-        if len(pw) != len(self.stages):
-            raise ValueError("syno_chain_forward: one weight per stage")
+        if len(Ws) != len(self.stages):
+            raise ValueError("syno_chain_forward: one weight entry per stage (None for a stage without a weight)")
+        pw = [p._arg(w, p.w_shape, p.in_dtype, f"syno_chain_forward W[{i}]") if self._own(i) else 0
+              for i, (p, w) in enumerate(zip(self.stages, Ws))]
         if acts is None:
             acts = self.new_activations(X.device)
         pa = [p._arg(a, p.out_shape, p.out_dtype, f"syno_chain_forward act[{i}]") for i, (p, a) in
@@ -345,17 +372,19 @@ class Chain:
         first, last = self.stages[0], self.stages[-1]
         px = first._arg(X, first.x_shape, first.in_dtype, "syno_chain_backward X")
         pg = last._arg(G, last.out_shape, last.in_dtype, "syno_chain_backward G")
-        pw = [p._arg(w, p.w_shape, p.in_dtype, f"syno_chain_backward W[{i}]") for i, (p, w) in
-              enumerate(zip(self.stages, Ws))]
+        if len(Ws) != len(self.stages):
+            raise ValueError("syno_chain_backward: one weight entry per stage (None for a stage without a weight)")
+        pw = [p._arg(w, p.w_shape, p.in_dtype, f"syno_chain_backward W[{i}]") if self._own(i) else 0
+              for i, (p, w) in enumerate(zip(self.stages, Ws))]
         pa = [p._arg(a, p.out_shape, p.out_dtype, f"syno_chain_backward act[{i}]") for i, (p, a) in
               enumerate(zip(self.stages[:-1], acts))]
         if len(pw) != len(self.stages) or len(pa) != len(self.stages) - 1:
             raise ValueError("syno_chain_backward: one weight per stage, one activation per stage but the last")
         if dWs is None:
             dWs = [torch.empty(p.w_shape if p.w_shape else (1,), dtype=torch.float32, device=X.device)
-                   for p in self.stages]
-        pdw = [p._arg(d, p.w_shape, torch.float32, f"syno_chain_backward dW[{i}]") for i, (p, d) in
-               enumerate(zip(self.stages, dWs))]
+                   if self._own(i) else None for i, p in enumerate(self.stages)]
+        pdw = [p._arg(d, p.w_shape, torch.float32, f"syno_chain_backward dW[{i}]") if self._own(i) else 0
+               for i, (p, d) in enumerate(zip(self.stages, dWs))]
         pdx = 0
         if want_dx:
             if dX is None:

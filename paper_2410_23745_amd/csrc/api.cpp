@@ -1,4 +1,6 @@
 // The C ABI of include/syno.h: argument checks and dispatch to the kernel families.
+#include <hip/hip_runtime.h>
+
 #include <atomic>
 #include <cstdio>
 #include <new>
@@ -14,6 +16,9 @@ struct syno_chain {
   size_t ws_bwd_stage = 0;  // largest gradient-call workspace of any stage
   size_t grad_bytes = 0;    // one intermediate-gradient buffer (two are used, alternating)
   bool bwd_types_fit = true;
+  // chains written by the materialised-reduction pass: the stage that keeps the graph's weight (-1: every stage
+  // has its own); the other stages have none and multiply by the constant one below
+  int32_t weight_stage = -1;
   ~syno_chain() {
     for (syno_plan* p : stage) delete p;
   }
@@ -31,8 +36,28 @@ syno_status launch_mfma_dw(const syno_plan* p, const void* A, const void* B, voi
 std::string mfma_dw_describe(const syno_plan* p);
 }
 
+// The value 1 in both element types, for stages without a weight: fp32 in word 0, bf16 in the low half of word 1.
+static __device__ __align__(16) uint32_t g_unit_words[4] = {0x3F800000u, 0x00003F80u, 0u, 0u};
+
 namespace {
 std::atomic<int> g_policy{0};
+
+// Device address of the constant one in element type `t` on the current device (each device has its own copy of
+// the array; the address is looked up once per device).
+const void* unit_weight(syno_dtype t) {
+  constexpr int kMaxDevices = 64;
+  static std::atomic<char*> cache[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  char* p = cache[dev].load(std::memory_order_acquire);
+  if (!p) {
+    void* sym = nullptr;
+    if (hipGetSymbolAddress(&sym, HIP_SYMBOL(g_unit_words)) != hipSuccess || !sym) return nullptr;
+    p = static_cast<char*>(sym);
+    cache[dev].store(p, std::memory_order_release);
+  }
+  return t == SYNO_BF16 ? p + 4 : p;
+}
 
 const char* const kKernelNames[syno::KERNEL_COUNT] = {
     "generic_index_program", "bandwidth_depthwise", "bandwidth_share_window", "mfma_contraction_f32", "mfma_contraction_bf16",
@@ -172,6 +197,22 @@ syno_status syno_debug_gather_host(const syno_plan* plan, int which, const int64
   return syno::host_debug_gather(plan, which, t_flat, q_flat, n, a_off, b_off);
 }
 
+syno_status syno_chain_create_materialized(const syno_desc* desc, syno_chain** chain) {
+  if (!desc || !chain) return SYNO_ERR_NULL;
+  *chain = nullptr;
+  std::vector<syno::OwnedDesc> stages;
+  int32_t weight_stage = -1;
+  syno_status st = syno::materialise(desc, stages, weight_stage);
+  if (st != SYNO_OK) return st;
+  std::vector<syno_desc> views;
+  for (const syno::OwnedDesc& o : stages) views.push_back(o.view());
+  st = syno_chain_create(views.data(), (int32_t)views.size(), chain);
+  if (st == SYNO_OK) (*chain)->weight_stage = weight_stage;
+  return st;
+}
+
+int32_t syno_chain_weight_stage(const syno_chain* chain) { return chain ? chain->weight_stage : -1; }
+
 syno_status syno_chain_create(const syno_desc* stages, int32_t n_stages, syno_chain** chain) {
   if (!stages || !chain) return SYNO_ERR_NULL;
   *chain = nullptr;
@@ -234,7 +275,10 @@ syno_status syno_chain_forward(const syno_chain* chain, const void* X, const voi
   const void* cur = X;
   for (size_t i = 0; i < n; ++i) {
     void* dst = i + 1 < n ? act[i] : out;
-    const syno_status st = run(chain->stage[i], SYNO_FWD, cur, W[i], dst, workspace, stream);
+    const bool own = chain->weight_stage < 0 || chain->weight_stage == (int32_t)i;
+    const void* Wi = own ? W[i] : unit_weight(chain->stage[i]->in_dtype);
+    if (!Wi) return own ? SYNO_ERR_NULL : SYNO_ERR_HIP;
+    const syno_status st = run(chain->stage[i], SYNO_FWD, cur, Wi, dst, workspace, stream);
     if (st != SYNO_OK) return st;
     cur = dst;
   }
@@ -257,11 +301,18 @@ syno_status syno_chain_backward(const syno_chain* chain, const void* X, const vo
   const void* g = G;
   for (size_t i = n; i-- > 0;) {
     const void* in = i == 0 ? X : act[i - 1];
-    syno_status st = run(chain->stage[i], SYNO_BWD_WEIGHT, g, in, dW[i], base, stream);
-    if (st != SYNO_OK) return st;
+    const bool own = chain->weight_stage < 0 || chain->weight_stage == (int32_t)i;
+    const void* Wi = own ? W[i] : unit_weight(chain->stage[i]->in_dtype);
+    if (!Wi) return own ? SYNO_ERR_NULL : SYNO_ERR_HIP;
+    syno_status st = SYNO_OK;
+    if (own) {     // a stage without a weight has no weight gradient
+      if (!dW[i]) return SYNO_ERR_NULL;
+      st = run(chain->stage[i], SYNO_BWD_WEIGHT, g, in, dW[i], base, stream);
+      if (st != SYNO_OK) return st;
+    }
     void* dst = i == 0 ? dX : static_cast<void*>(grad0 + (i & 1) * chain->grad_bytes);
-    if (!dst) break;   // the caller does not want dX
-    st = run(chain->stage[i], SYNO_BWD_DATA, g, W[i], dst, base, stream);
+    if (!dst) break;   // first stage and the caller does not want dX
+    st = run(chain->stage[i], SYNO_BWD_DATA, g, Wi, dst, base, stream);
     if (st != SYNO_OK) return st;
     g = dst;
   }

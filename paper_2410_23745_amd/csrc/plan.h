@@ -113,7 +113,27 @@ struct syno_plan {
 
 namespace syno {
 
+// A descriptor that owns its arrays (the stages the materialised-reduction pass writes).
+struct OwnedDesc {
+  std::vector<syno_dim> dims;
+  std::vector<syno_prim> prims;
+  std::vector<int32_t> xin, win;
+  syno_dtype in_dtype = SYNO_F32, out_dtype = SYNO_F32;
+  syno_desc view() const {
+    syno_desc d{};
+    d.n_out = (int32_t)dims.size(); d.out_dims = dims.data();
+    d.n_prim = (int32_t)prims.size(); d.prims = prims.data();
+    d.n_in = (int32_t)xin.size(); d.input_coords = xin.data();
+    d.n_w = (int32_t)win.size(); d.weight_coords = win.data();
+    d.in_dtype = in_dtype; d.out_dtype = out_dtype;
+    return d;
+  }
+};
+
 // planner.cpp
+// Materialised reduction: cuts `desc` into stages (one stage when no cut lowers the count of multiply-adds);
+// weight_stage = the stage that keeps the graph's weight, every other stage has none.
+syno_status materialise(const syno_desc* desc, std::vector<OwnedDesc>& stages, int32_t& weight_stage);
 syno_status build_plan(const syno_desc* desc, int policy, syno_plan* plan, std::string* why);
 
 // kernels_generic.hip

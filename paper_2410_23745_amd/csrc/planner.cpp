@@ -750,6 +750,148 @@ int64_t fold_width(int64_t N) {
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------
+// Materialised reduction (code-generation section of the paper).  FLOPs are the output iterators times all Reduces;
+// a Reduce evaluated below a one-to-many primitive (Unfold, Expand) is repeated for every copy.  Lowering a Reduce
+// only needs the primitives that lie between it and the tensors; evaluating exactly those first and storing
+// their result removes the repetition.  For every Reduce the pass takes that upward closure, makes the
+// coordinates entering it from below (and the tensor axes it does not touch) the axes of the stored tensor Z, and
+// keeps the cut with the fewest multiply-adds if it beats the single loop nest; the rest of the graph is cut
+// again the same way.
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+bool cut_once(const OwnedDesc& whole, bool has_weight, OwnedDesc& top, OwnedDesc& bottom, bool& weight_on_top) {
+  const syno_desc d = whole.view();
+  Graph g;
+  if (parse_graph(&d, g, nullptr) != SYNO_OK) return false;
+  const int n = (int)g.prims.size();
+  for (const syno_prim& p : g.prims)
+    if (p.kind == SYNO_SHIFT && p.shift_by >= 0) return false;   // a coordinate read without being consumed: not cut
+  double out_points = 1, all_red = 1;
+  for (int i = 0; i < g.n_out; ++i) out_points *= (double)g.D(i);
+  for (int c : g.reduce_coords) all_red *= (double)g.D(c);
+  const double before = out_points * all_red;
+
+  double best = before;
+  std::vector<char> best_c;
+  std::vector<int> best_z;
+  bool best_top = false;
+  for (int r = 0; r < n; ++r) {
+    if (g.prims[r].kind != SYNO_REDUCE) continue;
+    std::vector<char> in_c(n, 0), coord_c(kMaxCoordId, 0);
+    in_c[r] = 1; coord_c[g.prims[r].out[0]] = 1;
+    double red_c = (double)g.prims[r].param;
+    for (int k = r + 1; k < n; ++k) {
+      const syno_prim& p = g.prims[k];
+      bool touches = false;
+      for (int t = 0; t < arity_in(p.kind); ++t) touches |= coord_c[p.in[t]] != 0;
+      if (!touches) continue;
+      in_c[k] = 1;
+      for (int t = 0; t < arity_out(p.kind); ++t) coord_c[p.out[t]] = 1;
+    }
+    bool on_top = false;
+    for (int c : g.w_coords) on_top |= coord_c[c] != 0;
+    if (on_top && !has_weight) continue;
+    // axes of Z, in the order of X's axes: an axis the closure does not produce passes through, one it produces
+    // is replaced by the coordinates that enter the closure below it
+    std::vector<int> z;
+    std::vector<char> seen(kMaxCoordId, 0);
+    std::vector<int> producer(kMaxCoordId, -1);
+    for (int k = 0; k < n; ++k)
+      for (int t = 0; t < arity_out(g.prims[k].kind); ++t) producer[g.prims[k].out[t]] = k;
+    auto add = [&](int c) { if (!seen[c]) { seen[c] = 1; z.push_back(c); } };
+    std::vector<int> stack;
+    auto below = [&](int axis) {
+      stack.assign(1, axis);
+      while (!stack.empty()) {
+        const int c = stack.back(); stack.pop_back();
+        if (!coord_c[c]) { add(c); continue; }
+        const int k = producer[c];
+        if (k < 0) continue;
+        const syno_prim& p = g.prims[k];
+        for (int t = arity_in(p.kind) - 1; t >= 0; --t) stack.push_back(p.in[t]);
+      }
+    };
+    for (int c : g.in_coords) below(c);
+    if (on_top) for (int c : g.w_coords) below(c);
+    // every coordinate entering the closure from below must have been found (it is, through X or W, unless the
+    // closure ends in an Expand, which has no top side)
+    bool complete = true;
+    for (int k = 0; k < n && complete; ++k)
+      if (in_c[k])
+        for (int t = 0; t < arity_in(g.prims[k].kind); ++t)
+          if (!coord_c[g.prims[k].in[t]] && !seen[g.prims[k].in[t]]) complete = false;
+    if (!complete || z.empty() || (int)z.size() > kMaxAxes) continue;
+    double z_points = 1;
+    for (int c : z) z_points *= (double)g.D(c);
+    if (z_points > (double)kMaxElems) continue;
+    const double after = z_points * red_c + out_points * (all_red / red_c);
+    if (after < best) { best = after; best_c = in_c; best_z = z; best_top = on_top; }
+  }
+  if (best_c.empty()) return false;
+
+  // top stage: Z's axes are its output iterators 0..nz-1, the closure's primitives follow with fresh ids
+  std::vector<int> remap(kMaxCoordId, -1);
+  top = OwnedDesc{};
+  int next = 0;
+  for (int c : best_z) {
+    remap[c] = next++;
+    top.dims.push_back(syno_dim{nullptr, g.D(c)});
+  }
+  for (int k = 0; k < n; ++k) {
+    if (!best_c[k]) continue;
+    syno_prim p = g.prims[k];
+    for (int t = 0; t < arity_in(p.kind); ++t) p.in[t] = remap[p.in[t]];
+    for (int t = 0; t < arity_out(p.kind); ++t) { remap[p.out[t]] = next; p.out[t] = next++; }
+    top.prims.push_back(p);
+  }
+  if (next > kMaxCoordId) return false;
+  for (int c : g.in_coords) top.xin.push_back(remap[c]);
+  if (best_top) for (int c : g.w_coords) top.win.push_back(remap[c]);
+  top.in_dtype = whole.in_dtype; top.out_dtype = whole.in_dtype;
+  // bottom stage: the rest of the graph with its ids, reading Z
+  bottom = OwnedDesc{};
+  bottom.dims = whole.dims;
+  for (int k = 0; k < n; ++k) if (!best_c[k]) bottom.prims.push_back(g.prims[k]);
+  bottom.xin.assign(best_z.begin(), best_z.end());
+  if (!best_top) bottom.win = whole.win;
+  bottom.in_dtype = whole.in_dtype; bottom.out_dtype = whole.out_dtype;
+  weight_on_top = best_top;
+  // both halves must be valid graphs by themselves
+  Graph gt, gb;
+  const syno_desc dt = top.view(), db = bottom.view();
+  return parse_graph(&dt, gt, nullptr) == SYNO_OK && parse_graph(&db, gb, nullptr) == SYNO_OK;
+}
+
+}  // namespace
+
+syno_status materialise(const syno_desc* desc, std::vector<OwnedDesc>& stages, int32_t& weight_stage) {
+  Graph g;
+  const syno_status st = parse_graph(desc, g, nullptr);
+  if (st != SYNO_OK) return st;
+  OwnedDesc cur;
+  cur.dims.assign(desc->out_dims, desc->out_dims + desc->n_out);
+  cur.prims.assign(desc->prims, desc->prims + desc->n_prim);
+  cur.xin.assign(desc->input_coords, desc->input_coords + desc->n_in);
+  cur.win.assign(desc->weight_coords, desc->weight_coords + desc->n_w);
+  cur.in_dtype = desc->in_dtype; cur.out_dtype = desc->out_dtype;
+  stages.clear();
+  weight_stage = -1;
+  bool has_weight = true;     // `cur` still carries the graph's weight
+  while (stages.size() + 1 < 8) {
+    OwnedDesc top, bottom;
+    bool on_top = false;
+    if (!cut_once(cur, has_weight, top, bottom, on_top)) break;
+    if (on_top) { weight_stage = (int32_t)stages.size(); has_weight = false; }
+    stages.push_back(std::move(top));
+    cur = std::move(bottom);
+  }
+  if (has_weight) weight_stage = (int32_t)stages.size();
+  stages.push_back(std::move(cur));
+  return SYNO_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
 syno_status build_plan(const syno_desc* desc, int policy, syno_plan* plan, std::string* why) {
   Graph g;
   syno_status st = parse_graph(desc, g, why);

@@ -72,6 +72,36 @@ def strided_depthwise(N, C, H_out, W_out, S=2, K=3, in_dtype=F32, out_dtype=F32)
     return b.finish([n, cx, hh, ww], [cw, khw, kww], in_dtype, out_dtype)
 
 
+def window_of_sums_1d(H, k=3, s=2, weight=None, in_dtype=F32, out_dtype=F32) -> OpDesc:
+    """The example of the paper's materialised-reduction pass: out[i] = sum_{ik,is} X[s*(i+ik-k/2)+is], i < H/s,
+    as ONE loop nest.  weight="k": times Wt[ik]; weight="s": times Wt[is]; None: no weight axes."""
+    b = Builder([("i", H // s)], name=f"window_of_sums_H{H}_k{k}_s{s}_{weight}")
+    ik, i_s = b.reduce(k), b.reduce(s)
+    if weight == "k":
+        ikx, ikw = b.share(ik)
+        return b.finish([b.split(b.unfold(0, ikx), i_s)], [ikw], in_dtype, out_dtype)
+    if weight == "s":
+        sx, sw = b.share(i_s)
+        return b.finish([b.split(b.unfold(0, ik), sx)], [sw], in_dtype, out_dtype)
+    return b.finish([b.split(b.unfold(0, ik), i_s)], [], in_dtype, out_dtype)
+
+
+def pooled_conv2d(N, C, Co, H, W, S=2, K=3, in_dtype=F32, out_dtype=F32) -> OpDesc:
+    """A K x K convolution of S x S block sums, written as ONE loop nest with five Reduces:
+    out[n,co,h,w] = sum_{c,kh,kw,sh,sw} Wt[co,c,kh,kw] * X[n, c, S*(h+kh-K/2)+sh, S*(w+kw-K/2)+sw]."""
+    b = Builder([("n", N), ("co", Co), ("h", H), ("w", W)], name=f"pooled_conv_C{C}_Co{Co}_{H}x{W}_S{S}_N{N}")
+    c = b.reduce(C)
+    cx, cw = b.share(c)
+    kh = b.reduce(K)
+    khx, khw = b.share(kh)
+    kw = b.reduce(K)
+    kwx, kww = b.share(kw)
+    sh, sw = b.reduce(S), b.reduce(S)
+    hh = b.split(b.unfold(2, khx), sh)
+    ww = b.split(b.unfold(3, kwx), sw)
+    return b.finish([0, cx, hh, ww], [1, cw, khw, kww], in_dtype, out_dtype)
+
+
 def matmul(M, N, K, in_dtype=F32, out_dtype=F32) -> OpDesc:
     """Table 2: out[i,j] = sum_k X[i,k] * Wt[k,j]."""
     b = Builder([("i", M), ("j", N)], name=f"mm_{M}x{N}x{K}")

@@ -208,3 +208,22 @@ def test_matmul_is_planned_as_a_convolution_with_exchanged_roles(syno):
     assert q.kernel(0) == "mfma_contraction_transposed" and q.kernel(1) == q.kernel(2) == "generic_index_program"
     # a prime number of columns above 64 cannot be folded into image rows
     assert syno.Plan(wl.matmul(8, 127, 16)).kernel(0) == "generic_index_program"
+
+
+def test_materialised_reduction_pass_cuts_where_it_saves_work(syno):
+    # the paper's example: (H/s)*k*s points become H/s*s + H/s*k
+    for weight, stage_of_weight, w_shapes in ((None, 1, [(), ()]), ("k", 1, [(), (3,)]), ("s", 0, [(2,), ()])):
+        c = syno.Chain.materialized(wl.window_of_sums_1d(12, 3, 2, weight))
+        assert len(c.stages) == 2 and c.weight_stage == stage_of_weight
+        assert [p.x_shape for p in c.stages] == [(12,), (6,)] and [p.out_shape for p in c.stages] == [(6,), (6,)]
+        assert [p.w_shape for p in c.stages] == w_shapes
+    # nothing to gain on a plain convolution: one stage, which keeps the weight
+    c = syno.Chain.materialized(wl.conv2d(2, 8, 8, 6, 6))
+    assert len(c.stages) == 1 and c.weight_stage == 0
+    # block sums under a convolution: rows, then columns, then the convolution on the contraction kernels
+    c = syno.Chain.materialized(wl.pooled_conv2d(2, 8, 8, 6, 6))
+    assert len(c.stages) == 3 and c.weight_stage == 2
+    assert [p.out_shape for p in c.stages] == [(2, 8, 6, 12), (2, 8, 6, 6), (2, 8, 6, 6)]
+    assert c.stages[2].kernel(0) == "mfma_contraction_f32" and c.stages[2].w_shape == (8, 8, 3, 3)
+    # a Shift that reads another coordinate is left whole
+    assert len(syno.Chain.materialized(wl.grouped_shift_unfold(2, 16, 16, 6, 6, 2)).stages) == 1

@@ -294,6 +294,45 @@ def test_operator1_full_size(syno, oracle, bf16):
 
 
 # ------------------------------------------------------------------------------------------------
+# the materialised-reduction pass: one loop nest in, stages out, same result as the loop nest
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("mk", [
+    lambda i, o: wl.window_of_sums_1d(120, 3, 2, None, i, o),
+    lambda i, o: wl.window_of_sums_1d(90, 5, 3, "k", i, o),
+    lambda i, o: wl.window_of_sums_1d(64, 3, 4, "s", i, o),
+    lambda i, o: wl.pooled_conv2d(3, 24, 40, 13, 10, 2, 3, i, o),
+])
+def test_materialised_chain_equals_the_single_loop_nest(syno, oracle, mk, dt):
+    """The checker evaluates the graph as written (one loop nest); the library cuts it into stages."""
+    t = F32 if dt == "f32" else BF16
+    d = mk(t, t)
+    chain = syno.Chain.materialized(d)
+    assert len(chain.stages) >= 2
+    xs, ws, _ = oracle.describe(d)
+    os_ = oracle.out_shape(d)
+    st = wl.Stream(51)
+    w = wl._finish(d, xs, ws if ws else (1,), os_, st.normal(xs), st.uniform_pm(0.5, ws if ws else (1,)), st.normal(os_), 1)
+    tol = tol_for(d)
+    print(f"[case] {d.name} {dt}: {len(chain.stages)} stages, weight in stage {chain.weight_stage}, kernels "
+          f"{[p.kernel(0) for p in chain.stages]}", flush=True)
+    X, W, G = to_dev(w.X, w.X_bits), to_dev(w.W, w.W_bits), to_dev(w.G, w.G_bits)
+    Ws = [W if i == chain.weight_stage else None for i in range(len(chain.stages))]
+    out, acts = chain.forward(X, Ws)
+    torch.cuda.synchronize()
+    e = rel_l2(to_host(out), oracle.forward(d, w.X, w.W))
+    assert e <= tol, f"forward rel-L2 {e:.3e} > {tol}"
+    dX, dWs = chain.backward(X, Ws, acts, G)
+    torch.cuda.synchronize()
+    rdx, rdw = oracle.backward(d, w.X, w.W, w.G)
+    e = rel_l2(to_host(dX), rdx)
+    assert e <= tol, f"dX rel-L2 {e:.3e} > {tol}"
+    assert all((g is None) == (i != chain.weight_stage) for i, g in enumerate(dWs))
+    e = rel_l2(to_host(dWs[chain.weight_stage]), rdw)
+    assert e <= tol, f"dW rel-L2 {e:.3e} > {tol}"
+
+
+# ------------------------------------------------------------------------------------------------
 # matrix products (Table 2) run as 1x1 convolutions with the operands' roles exchanged
 # ------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("bf16", [False, True])

@@ -264,6 +264,38 @@ def main() -> int:
                                "launch": " | ".join(p.describe(k) for p in chain.stages for k in which),
                                "us": med * 1e3, "TFLOP/s": flops / (med * 1e-3) / 1e12,
                                "GB/s": nbytes / (med * 1e-3) / 1e9, "rotating_sets": 4})
+        # the materialised-reduction pass on a convolution of 2x2 block sums (one loop nest with five Reduces):
+        # the graph as written runs on the index-program kernel, the chain the library cuts it into on two small
+        # reduction stages and the contraction kernel
+        dpc = wl.pooled_conv2d(32, 64, 64, 28, 28, 2, 3)
+        whole, mat = syno.Plan(dpc), syno.Chain.materialized(dpc)
+        Xp = torch.randn(whole.x_shape, device=dev)
+        Wp = torch.randn(whole.w_shape, device=dev) * 0.05
+        Wsp = [Wp if i == mat.weight_stage else None for i in range(len(mat.stages))]
+        o1 = whole.forward(Xp, Wp)
+        o2, acts_p = mat.forward(Xp, Wsp)
+        torch.cuda.synchronize()
+        agree = float((o1 - o2).norm() / o1.norm())
+
+        def timed(fn, iters):
+            fn()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(iters):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / iters * 1e3
+
+        us_whole = timed(lambda: whole.forward(Xp, Wp, out=o1), 3)
+        us_chain = timed(lambda: mat.forward(Xp, Wsp, acts=acts_p, out=o2), 20)
+        fl_whole = 2 * int(np.prod(whole.out_shape)) * 64 * 9 * 4
+        detail.append({"case": "pooled_conv_C64_28x28_N32_f32_fwd: single loop nest vs materialised chain",
+                       "kernel": whole.kernel(0) + " vs " + " + ".join(p.kernel(0) for p in mat.stages),
+                       "us_single_loop_nest": us_whole, "us": us_chain, "stages": len(mat.stages),
+                       "TFLOP/s": fl_whole / (us_chain * 1e-6) / 1e12, "rel_l2_between_the_two": agree,
+                       "note": "TFLOP/s counts the multiply-adds of the single loop nest"})
         out["detail"] = detail
 
     # ---- CPU baseline: the checker as it stands, on a bounded sample of the same workload ---------------------

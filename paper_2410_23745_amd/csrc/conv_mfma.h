@@ -666,13 +666,15 @@ struct Variant {
 //   fp32 12:   as 10 for at most 128 pixels per block, up to 64 channels per chunk
 //   bf16 7-8:  as 1 and 2 with 64 channels per chunk
 //   bf16 9:    as 8 for at most 128 pixels per block, 128 channels per chunk
-constexpr int kNumF32Variants = 13, kNumBf16Variants = 10;
+//   fp32 13:   128 output channels x 256 pixels (4 x 4 tiles per wave): twice the reuse of every staged input pixel,
+//              for 1x1 windows (matrix products), where nothing else reuses it
+constexpr int kNumF32Variants = 14, kNumBf16Variants = 10;
 constexpr Variant kF32Variants[kNumF32Variants] = {
     {4, 2, 1, 7, 2, 1, 9, 8, false}, {4, 2, 1, 7, 1, 1, 5, 8, false}, {8, 1, 1, 4, 1, 1, 3, 8, false},
     {4, 2, 1, 7, 2, 1, 5, 16, true}, {4, 1, 2, 7, 2, 1, 3, 16, true}, {2, 1, 4, 7, 2, 1, 3, 16, true},
     {1, 1, 8, 4, 4, 1, 5, 16, true}, {4, 2, 1, 7, 1, 2, 5, 32, true}, {8, 1, 1, 4, 1, 2, 3, 32, true},
     {4, 1, 2, 7, 2, 1, 5, 32, true}, {2, 1, 4, 7, 2, 1, 5, 32, true}, {2, 2, 2, 7, 2, 1, 5, 16, true},
-    {2, 1, 4, 4, 2, 2, 9, 64, true}};
+    {2, 1, 4, 4, 2, 2, 9, 64, true}, {4, 2, 1, 4, 4, 1, 5, 32, true}};
 constexpr Variant kBf16Variants[kNumBf16Variants] = {
     {4, 2, 1, 7, 2, 1, 6, 32, false}, {4, 1, 2, 7, 2, 1, 3, 32, false}, {2, 1, 4, 7, 2, 1, 3, 32, false},
     {1, 1, 8, 4, 4, 1, 6, 32, false}, {4, 2, 1, 7, 1, 2, 3, 32, false}, {8, 1, 1, 4, 1, 2, 2, 32, false},
@@ -694,7 +696,7 @@ void launch_variant(const MfmaParams& p, const void* X, const void* W, void* out
 
 // Launchers of the instantiated variants; each lives in a translation unit of its own.
 void launch_mfma_f32_lo(int vi, const MfmaParams& p, const void* X, const void* W, void* out, hipStream_t s);    // variants 0-3
-void launch_mfma_f32_hi(int vi, const MfmaParams& p, const void* X, const void* W, void* out, hipStream_t s);    // variants 4-8
+void launch_mfma_f32_hi(int vi, const MfmaParams& p, const void* X, const void* W, void* out, hipStream_t s);    // variants 4-13
 void launch_mfma_bf16_f32out(int vi, const MfmaParams& p, const void* X, const void* W, void* out, hipStream_t s);
 void launch_mfma_bf16_bf16out(int vi, const MfmaParams& p, const void* X, const void* W, void* out, hipStream_t s);
 

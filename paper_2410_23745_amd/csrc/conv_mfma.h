@@ -668,7 +668,8 @@ struct Variant {
 //   bf16 9:    as 8 for at most 128 pixels per block, 128 channels per chunk
 //   fp32 13:   128 output channels x 256 pixels (4 x 4 tiles per wave): twice the reuse of every staged input pixel,
 //              for 1x1 windows (matrix products), where nothing else reuses it
-constexpr int kNumF32Variants = 14, kNumBf16Variants = 10;
+//   bf16 10:   the same for bf16 (packed weights, 64 channels per chunk; 1x1 windows only)
+constexpr int kNumF32Variants = 14, kNumBf16Variants = 11;
 constexpr Variant kF32Variants[kNumF32Variants] = {
     {4, 2, 1, 7, 2, 1, 9, 8, false}, {4, 2, 1, 7, 1, 1, 5, 8, false}, {8, 1, 1, 4, 1, 1, 3, 8, false},
     {4, 2, 1, 7, 2, 1, 5, 16, true}, {4, 1, 2, 7, 2, 1, 3, 16, true}, {2, 1, 4, 7, 2, 1, 3, 16, true},
@@ -679,7 +680,7 @@ constexpr Variant kBf16Variants[kNumBf16Variants] = {
     {4, 2, 1, 7, 2, 1, 6, 32, false}, {4, 1, 2, 7, 2, 1, 3, 32, false}, {2, 1, 4, 7, 2, 1, 3, 32, false},
     {1, 1, 8, 4, 4, 1, 6, 32, false}, {4, 2, 1, 7, 1, 2, 3, 32, false}, {8, 1, 1, 4, 1, 2, 2, 32, false},
     {4, 2, 1, 7, 2, 4, 11, 64, false, true}, {4, 1, 2, 7, 2, 1, 6, 64, false}, {2, 1, 4, 7, 2, 1, 6, 64, false},
-    {2, 1, 4, 4, 2, 2, 10, 128, false}};
+    {2, 1, 4, 4, 2, 2, 10, 128, false}, {4, 2, 1, 4, 4, 1, 3, 64, false}};
 
 template <bool BF, int VI, int U, int WF, bool OUTBF>
 void launch_variant(const MfmaParams& p, const void* X, const void* W, void* out, hipStream_t s) {

@@ -194,6 +194,7 @@ bool fill_params(const syno_plan* plan, int which, int vi, int TR, MfmaParams& p
   if (bf) {
     p.KC = v.KC;
     if (v.one && p.Cg > p.KC) return false;
+    if (v.BN() == 128 && KHW != 1) return false;   // (the 128-channel variant is instantiated for 1x1 windows only)
     p.w_row = p.KC + 8;                          // elements; 80- and 144-byte rows keep B-fragment reads conflict free
     p.w_block = KHW * p.BN * p.w_row;
     // Forward-layout weights [o][c][taps] are read unpacked: by every variant when there are 9 taps, by the

@@ -20,6 +20,9 @@ void launch_mfma_bf16_bf16out(int vi, const MfmaParams& p, const void* X, const 
       else if (p.wf == -1) launch_variant<true, 6, 1, -1, true>(p, X, W, out, s);
       else launch_variant<true, 6, 1, 0, true>(p, X, W, out, s);
       break;
+    case 10:  // 1x1 windows only: packed weights
+      launch_variant<true, 10, 1, 0, true>(p, X, W, out, s);
+      break;
     default: break;
   }
 #undef SYNO_CASE

@@ -30,11 +30,14 @@ __device__ __forceinline__ void store_elem(void* p, int64_t off, float v) {
   else reinterpret_cast<float*>(p)[off] = v;
 }
 
-__host__ __device__ __forceinline__ void decode(const AxisRef* ax, int n, int64_t flat, int* v) {
+// (flat indices are below 2^31: 32-bit unsigned division, several times cheaper on the device than 64-bit)
+__host__ __device__ __forceinline__ void decode(const AxisRef* ax, int n, int64_t flat64, int* v) {
+  uint32_t flat = (uint32_t)flat64;
   for (int i = n - 1; i >= 0; --i) {
-    const int s = ax[i].size;
-    v[ax[i].slot] = (int)(flat % s);
-    flat /= s;
+    const uint32_t s = (uint32_t)ax[i].size;
+    const uint32_t q = flat / s;
+    v[ax[i].slot] = (int)(flat - q * s);
+    flat = q;
   }
 }
 

@@ -102,6 +102,23 @@ def pooled_conv2d(N, C, Co, H, W, S=2, K=3, in_dtype=F32, out_dtype=F32) -> OpDe
     return b.finish([0, cx, hh, ww], [1, cw, khw, kww], in_dtype, out_dtype)
 
 
+def shifted_scale(N, C, H, W, in_dtype=F32, out_dtype=F32) -> OpDesc:
+    """A pure view with a per-channel weight (no Reduce): out[n,c,h,w] = Wt[c] * X[n, c, h, (w+1) mod W]."""
+    b = Builder([("n", N), ("c", C), ("h", H), ("w", W)], name=f"shift_scale_C{C}_{H}x{W}_N{N}")
+    cx, cw = b.share(1)
+    ws = b.shift(3, 1)
+    return b.finish([0, cx, 2, ws], [cw], in_dtype, out_dtype)
+
+
+def pixel_unshuffle(N, C, H, W, r=2, in_dtype=F32, out_dtype=F32) -> OpDesc:
+    """Space-to-depth as a pure view (Table 2's PixelShuffle read the other way), times a one-element weight:
+    out[n, c, i, j, h, w] = X[n, c, r*h+i, r*w+j] * Wt[0]."""
+    b = Builder([("n", N), ("c", C), ("i", r), ("j", r), ("h", H), ("w", W)], name=f"pixel_unshuffle_C{C}_{H}x{W}_r{r}_N{N}")
+    hh = b.split(4, 2)
+    ww = b.split(5, 3)
+    return b.finish([0, 1, hh, ww], [], in_dtype, out_dtype)
+
+
 def matmul(M, N, K, in_dtype=F32, out_dtype=F32) -> OpDesc:
     """Table 2: out[i,j] = sum_k X[i,k] * Wt[k,j]."""
     b = Builder([("i", M), ("j", N)], name=f"mm_{M}x{N}x{K}")

@@ -30,12 +30,22 @@ __device__ __forceinline__ void store_elem(void* p, int64_t off, float v) {
   else reinterpret_cast<float*>(p)[off] = v;
 }
 
-// (flat indices are below 2^31: 32-bit unsigned division, several times cheaper on the device than 64-bit)
+// n / d for 0 <= n < 2^31 and d >= 1 with the precomputed magic of plan.h (0 for d = 1).
+__host__ __device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t d, uint32_t magic) {
+  if (d < 2) return n;
+#if defined(__HIP_DEVICE_COMPILE__)
+  return __umulhi(n, magic) >> (31 - __clz((int)(d - 1)));
+#else
+  return (uint32_t)(((uint64_t)n * magic) >> 32) >> (31 - __builtin_clz(d - 1));
+#endif
+}
+
+// (flat indices are below 2^31)
 __host__ __device__ __forceinline__ void decode(const AxisRef* ax, int n, int64_t flat64, int* v) {
   uint32_t flat = (uint32_t)flat64;
   for (int i = n - 1; i >= 0; --i) {
     const uint32_t s = (uint32_t)ax[i].size;
-    const uint32_t q = flat / s;
+    const uint32_t q = fast_div(flat, s, (uint32_t)ax[i].stride);
     v[ax[i].slot] = (int)(flat - q * s);
     flat = q;
   }
@@ -48,13 +58,21 @@ __host__ __device__ __forceinline__ bool run_ops(const IndexProgram& P, int lo, 
     const IndexOp o = P.ops[k];
     switch (o.kind) {
       case OP_MULADD: v[o.d0] = v[o.a] * o.p0 + v[o.b]; break;
-      case OP_DIVMOD: {
+      case OP_DIVMOD: {      // (operands are coordinates, 0 <= x < 2^31, whenever the term is still valid)
         const int x = v[o.a];
-        v[o.d0] = x / o.p0;
-        v[o.d1] = x % o.p0;
+        const int q = (int)fast_div((uint32_t)x, (uint32_t)o.p0, (uint32_t)o.p1);
+        v[o.d0] = q;
+        v[o.d1] = x - q * o.p0;
         break;
       }
-      case OP_SHIFT: v[o.d0] = (v[o.a] + o.p1 + o.p2 * v[o.b]) % o.p0; break;
+      case OP_SHIFT:
+        if (o.p2 == 0) {       // constant offset, already reduced mod p0: one conditional subtraction
+          const int x = v[o.a] + o.p1;
+          v[o.d0] = x >= o.p0 ? x - o.p0 : x;
+        } else {
+          v[o.d0] = (v[o.a] + o.p1 + o.p2 * v[o.b]) % o.p0;
+        }
+        break;
       case OP_ADDCHK: {
         const int t = v[o.a] + o.p2 * v[o.b] + o.p1;
         ok = ok && ((unsigned)t < (unsigned)o.p0);
@@ -64,8 +82,9 @@ __host__ __device__ __forceinline__ bool run_ops(const IndexProgram& P, int lo, 
       case OP_MUL: v[o.d0] = v[o.a] * o.p0; break;
       case OP_DIVCHK: {
         const int x = v[o.a];
-        ok = ok && (x % o.p0 == 0);
-        v[o.d0] = x / o.p0;
+        const int q = (int)fast_div((uint32_t)x, (uint32_t)o.p0, (uint32_t)o.p1);
+        ok = ok && x >= 0 && q * o.p0 == x;
+        v[o.d0] = q;
         break;
       }
     }

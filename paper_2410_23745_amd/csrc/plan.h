@@ -20,11 +20,11 @@ constexpr int kMaxAxes = 8;
 // ---------------------------------------------------------------------------------------------
 enum OpKind : int32_t {
   OP_MULADD = 0,   // v[d0] = v[a]*p0 + v[b]                       Split forwards, Merge inverted
-  OP_DIVMOD = 1,   // v[d0] = v[a]/p0 ; v[d1] = v[a]%p0            Merge forwards, Split inverted
+  OP_DIVMOD = 1,   // v[d0] = v[a]/p0 ; v[d1] = v[a]%p0            Merge forwards, Split inverted  (p1 = division_magic(p0))
   OP_SHIFT  = 2,   // v[d0] = (v[a] + p1 + p2*v[b]) mod p0, >= 0   Shift, either way
   OP_ADDCHK = 3,   // t = v[a] + p2*v[b] + p1 ; ok &= 0<=t<p0 ; v[d0]=t   Unfold, either way
   OP_MUL    = 4,   // v[d0] = v[a]*p0                              Stride forwards
-  OP_DIVCHK = 5    // ok &= v[a]%p0==0 ; v[d0] = v[a]/p0           Stride inverted
+  OP_DIVCHK = 5    // ok &= v[a]%p0==0 ; v[d0] = v[a]/p0           Stride inverted                 (p1 = division_magic(p0))
 };
 
 struct IndexOp {
@@ -32,8 +32,19 @@ struct IndexOp {
 };
 
 struct AxisRef {
-  int32_t slot, size, stride;
+  int32_t slot, size, stride;   // target and free axes carry division_magic(size) in `stride` (they have no stride)
 };
+
+// Division of a 31-bit unsigned n by a runtime d >= 2 as one high multiplication and a shift:
+// n / d == mulhi(n, M) >> s with s = ceil(log2 d) - 1 and M = ceil(2^(32+s) / d), exact for n < 2^31
+// (M < 2^32 because d > 2^s; the error M*d - 2^(32+s) < d <= 2^(s+1) stays below one unit at that range).
+inline uint32_t division_magic(int64_t d) {
+  if (d < 2) return 0;
+  int s = 0;
+  while ((int64_t(1) << (s + 1)) < d) ++s;
+  const uint64_t num = uint64_t(1) << (32 + s);     // s <= 30
+  return (uint32_t)((num + (uint64_t)d - 1) / (uint64_t)d);
+}
 
 struct IndexProgram {
   int32_t n_tgt, n_fre, n_ops0, n_ops, n_a, n_b;   // ops[0..n_ops0) depend on the target only

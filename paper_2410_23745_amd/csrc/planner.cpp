@@ -202,7 +202,7 @@ bool step_prim(Builder& b, const syno_prim& p, bool* progress) {
         b.emit(OP_MULADD, S(i), S(j), S(v), -1, g.D(j), 0, 0);
         b.set(v);
       } else if (b.K(v) && !b.K(i) && !b.K(j)) {
-        b.emit(OP_DIVMOD, S(v), -1, S(i), S(j), g.D(j), 0, 0);
+        b.emit(OP_DIVMOD, S(v), -1, S(i), S(j), g.D(j), (int32_t)division_magic(g.D(j)), 0);
         b.set(i); b.set(j);
       } else {
         if (b.K(v) && (b.K(i) || b.K(j))) b.failed = true;   // determined twice
@@ -214,7 +214,7 @@ bool step_prim(Builder& b, const syno_prim& p, bool* progress) {
     case SYNO_MERGE: {
       const int i = p.in[0], q = p.out[0], r = p.out[1];
       if (b.K(i) && !b.K(q) && !b.K(r)) {
-        b.emit(OP_DIVMOD, S(i), -1, S(q), S(r), p.param, 0, 0);
+        b.emit(OP_DIVMOD, S(i), -1, S(q), S(r), p.param, (int32_t)division_magic(p.param), 0);
         b.set(q); b.set(r);
       } else if (b.K(q) && b.K(r) && !b.K(i)) {
         b.emit(OP_MULADD, S(q), S(r), S(i), -1, p.param, 0, 0);
@@ -270,7 +270,7 @@ bool step_prim(Builder& b, const syno_prim& p, bool* progress) {
         b.emit(OP_MUL, S(i), -1, S(v), -1, p.param, 0, 0);
         b.set(v);
       } else if (b.K(v) && !b.K(i)) {
-        b.emit(OP_DIVCHK, S(v), -1, S(i), -1, p.param, 0, 0);
+        b.emit(OP_DIVCHK, S(v), -1, S(i), -1, p.param, (int32_t)division_magic(p.param), 0);
         b.set(i);
       } else {
         if (b.K(i) && b.K(v)) b.failed = true;
@@ -388,13 +388,15 @@ bool build_program(const Graph& g, const TensorAxes& target, const std::vector<i
   out.n_tgt = (int32_t)target.coords.size();
   out.n_target = 1;
   for (int i = 0; i < out.n_tgt; ++i) {
-    out.tgt[i] = AxisRef{g.S(target.coords[i]), (int32_t)g.D(target.coords[i]), (int32_t)target.stride[i]};
+    out.tgt[i] = AxisRef{g.S(target.coords[i]), (int32_t)g.D(target.coords[i]),
+                         (int32_t)division_magic(g.D(target.coords[i]))};
     out.n_target *= g.D(target.coords[i]);
   }
   out.n_fre = (int32_t)b.free_slots.size();
   out.n_free = 1;
   for (int i = 0; i < out.n_fre; ++i) {
-    out.fre[i] = AxisRef{b.free_slots[i], (int32_t)g.slot_dom[b.free_slots[i]], 0};
+    out.fre[i] = AxisRef{b.free_slots[i], (int32_t)g.slot_dom[b.free_slots[i]],
+                         (int32_t)division_magic(g.slot_dom[b.free_slots[i]])};
     out.n_free *= g.slot_dom[b.free_slots[i]];
   }
   out.n_a = (int32_t)A.coords.size();

@@ -42,7 +42,7 @@ def main() -> int:
     ap.add_argument("--no-detail", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU only: this build uses no second GPU, collective or rank code "
+        print("bench.py measures one GPU only: the library has no multi-GPU, collective or rank code "
               "(--gpus must be 1)", file=sys.stderr)
         return 2
 

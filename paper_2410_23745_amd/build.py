@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsyno.so")
 
-SOURCES = ["planner.cpp", "api.cpp", "kernels_generic.hip", "kernels_bandwidth.hip", "kernels_window.hip", "kernels_mfma.hip",
+SOURCES = ["planner.cpp", "api.cpp", "kernels_generic.hip", "kernels_bandwidth.hip", "kernels_window.hip", "kernels_view.hip", "kernels_mfma.hip",
            "kernels_mfma_f32_lo.hip", "kernels_mfma_f32_hi.hip", "kernels_mfma_bf16_f32out.hip",
            "kernels_mfma_bf16_bf16out.hip", "kernels_mfma_dw.hip"]
 

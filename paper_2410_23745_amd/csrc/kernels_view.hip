@@ -1,0 +1,171 @@
+// Bandwidth-bound family, third member: Reduce-free graphs (pure views: Shift, Split, Merge, Stride, Expand and
+// Share in any combination, no Unfold), forward pass:
+//
+//   out[o] = X[offX(o)] * W[offW(o)]
+//
+// When every tensor axis is an affine function of digits of the output iterators - wrapped (Shift) only over
+// digits of one output axis - both offsets are sums of one small table per output axis (plan.h, ViewStream).
+// Every workgroup builds the tables in LDS from the record (a few hundred entries), then each lane takes a run
+// of V adjacent elements of the innermost output axis: the outer axes are decoded once per run, the innermost
+// axis is a table walk, the result leaves as one vector store.  The loads follow whatever order the view imposes.
+#include <hip/hip_runtime.h>
+
+#include "plan.h"
+
+namespace syno {
+namespace {
+
+constexpr int kThreads = 256;
+
+struct ViewParams {
+  ViewStream vs;
+  int32_t tab_off[kMaxAxes];     // start of axis i's table (entries, X table; the W table follows at +tab_total)
+  uint32_t magic[kMaxAxes];      // division_magic(size[i])
+  int32_t tab_total;
+  int64_t n_runs;                // out elements / V
+};
+
+__device__ __forceinline__ uint32_t div_magic(uint32_t n, uint32_t d, uint32_t magic) {
+  return d < 2 ? n : __umulhi(n, magic) >> (31 - __clz((int)(d - 1)));
+}
+
+template <bool BF>
+__device__ __forceinline__ float load_one(const void* base, int64_t off) {
+  if constexpr (BF) return __uint_as_float((uint32_t)static_cast<const uint16_t*>(base)[off] << 16);
+  else return static_cast<const float*>(base)[off];
+}
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
+template <int V, bool BF>
+__device__ __forceinline__ void store_run(void* base, int64_t off, const float* v) {
+  if constexpr (BF) {
+    uint16_t* p = static_cast<uint16_t*>(base) + off;
+    if constexpr (V == 4) {
+      uint2 t;
+      t.x = pack_bf16x2(v[0], v[1]);
+      t.y = pack_bf16x2(v[2], v[3]);
+      *reinterpret_cast<uint2*>(p) = t;
+    } else {
+      *p = (uint16_t)pack_bf16x2(v[0], 0.f);
+    }
+  } else {
+    float* p = static_cast<float*>(base) + off;
+    if constexpr (V == 4) *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    else *p = v[0];
+  }
+}
+
+template <int V, bool IBF, bool OBF>
+__global__ __launch_bounds__(kThreads) void view_stream(const ViewParams p, const void* __restrict__ X,
+                                                        const void* __restrict__ Wt, void* __restrict__ out) {
+  extern __shared__ int tab[];     // [2][tab_total]: X offsets, then W offsets
+  const ViewStream& vs = p.vs;
+  // table entry (axis i, index o): the contribution of output axis i to each offset
+  for (int idx = threadIdx.x; idx < p.tab_total; idx += kThreads) {
+    int axis = 0;
+    while (axis + 1 < vs.n_axes && idx >= p.tab_off[axis + 1]) ++axis;
+    const int o = idx - p.tab_off[axis];
+    int off[2] = {0, 0};
+    for (int gi = 0; gi < vs.n_groups; ++gi) {
+      const ViewGroup g = vs.group[gi];
+      int partial = 0;
+      bool mine = g.axis == axis;          // the group's constant (and its wrap) are charged to one axis only
+      for (int t = 0; t < vs.n_terms; ++t) {
+        const ViewTerm tm = vs.term[t];
+        if (tm.group == gi && tm.axis == axis) partial += tm.coef * ((o / tm.div) % tm.size);
+      }
+      if (g.wrap > 0) {
+        if (mine) off[g.tensor] += ((partial + g.c) % g.wrap) * g.stride;
+      } else {
+        off[g.tensor] += (partial + (mine ? g.c : 0)) * g.stride;
+      }
+    }
+    tab[idx] = off[0];
+    tab[p.tab_total + idx] = off[1];
+  }
+  __syncthreads();
+  const int last = vs.n_axes - 1;
+  const uint32_t runs_per_row = (uint32_t)vs.size[last] / V;
+  const int* const tx_last = tab + p.tab_off[last];
+  // (the grid is capped so that the table build above is paid a few times per CU, not once per 256 runs)
+  for (int64_t run = (int64_t)blockIdx.x * kThreads + threadIdx.x; run < p.n_runs; run += (int64_t)gridDim.x * kThreads) {
+    uint32_t rest = (uint32_t)run;
+    const uint32_t row = div_magic(rest, runs_per_row, p.magic[last]);
+    const int w0 = (int)(rest - row * runs_per_row) * V;
+    rest = row;
+    int bx = 0, bw = 0;
+    for (int i = last - 1; i >= 0; --i) {
+      const uint32_t s = (uint32_t)vs.size[i];
+      const uint32_t q = div_magic(rest, s, p.magic[i]);
+      const int o = (int)(rest - q * s);
+      rest = q;
+      bx += tab[p.tab_off[i] + o];
+      bw += tab[p.tab_total + p.tab_off[i] + o];
+    }
+    float r[V];
+    const int* tx = tx_last + w0;
+    const int* tw = tx + p.tab_total;
+#pragma unroll
+    for (int v = 0; v < V; ++v) r[v] = load_one<IBF>(X, bx + tx[v]) * load_one<IBF>(Wt, bw + tw[v]);
+    store_run<V, OBF>(out, run * V, r);
+  }
+}
+
+template <bool IBF, bool OBF>
+void launch_typed(const ViewParams& p, int V, size_t lds, const void* X, const void* W, void* out, hipStream_t s) {
+  const int64_t blocks = (p.n_runs + kThreads - 1) / kThreads;
+  const dim3 grid((unsigned)(blocks < 256 * 8 ? blocks : 256 * 8));
+  if (V == 4) hipLaunchKernelGGL((view_stream<4, IBF, OBF>), grid, dim3(kThreads), lds, s, p, X, W, out);
+  else hipLaunchKernelGGL((view_stream<1, IBF, OBF>), grid, dim3(kThreads), lds, s, p, X, W, out);
+}
+
+int run_width(const syno_plan* plan) {
+  return plan->view.size[plan->view.n_axes - 1] % 4 == 0 ? 4 : 1;
+}
+
+// The magic for the innermost axis divides by its count of runs, not by its size.
+bool fill(const syno_plan* plan, ViewParams& p) {
+  p = ViewParams{};
+  p.vs = plan->view;
+  const int V = run_width(plan);
+  int total = 0;
+  for (int i = 0; i < p.vs.n_axes; ++i) {
+    p.tab_off[i] = total;
+    total += p.vs.size[i];
+    p.magic[i] = division_magic(p.vs.size[i]);
+  }
+  const int last = p.vs.n_axes - 1;
+  p.magic[last] = division_magic(p.vs.size[last] / V);
+  p.tab_total = total;
+  p.n_runs = plan->out_elems / V;
+  return total > 0 && (size_t)total * 8 <= 48 * 1024 && p.n_runs < (int64_t(1) << 31);
+}
+
+}  // namespace
+
+bool view_supports(const syno_plan* plan, int which) {
+  if (which != SYNO_FWD || !plan->pure_view) return false;
+  if (plan->in_dtype == SYNO_F32 && plan->out_dtype != SYNO_F32) return false;
+  ViewParams p;
+  return fill(plan, p);
+}
+
+syno_status launch_view(const syno_plan* plan, const void* A, const void* B, void* out, hipStream_t stream) {
+  ViewParams p;
+  if (!fill(plan, p)) return SYNO_ERR_UNSUPPORTED;
+  const int V = run_width(plan);
+  const size_t lds = (size_t)p.tab_total * 8;
+  const bool ibf = plan->in_dtype == SYNO_BF16, obf = plan->out_dtype == SYNO_BF16;
+  if (ibf && obf) launch_typed<true, true>(p, V, lds, A, B, out, stream);
+  else if (ibf) launch_typed<true, false>(p, V, lds, A, B, out, stream);
+  else launch_typed<false, false>(p, V, lds, A, B, out, stream);
+  return hipGetLastError() == hipSuccess ? SYNO_OK : SYNO_ERR_HIP;
+}
+
+}  // namespace syno

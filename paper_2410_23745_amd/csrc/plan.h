@@ -82,10 +82,29 @@ struct ShareWindow {
   int32_t ws_d, ws_g, ws_c, ws_k;   // weight element strides per role (0 when the role has size 1)
 };
 
+// ---------------------------------------------------------------------------------------------
+// Pure view (no Reduce, no Unfold): every X axis and every W axis is an affine function of digits of the output
+// iterators, optionally wrapped (Shift) when all its digits come from one output axis.  The two source offsets
+// are then sums of one table per output axis, offX(o) = sum_i tabX_i[o_i]; the kernel builds the tables in LDS
+// from this record.
+//   group  = one tensor axis: value = sum of its terms + c, taken mod `wrap` when wrap > 0, times `stride`
+//   term   = coef * ((o_axis / div) % size), a digit of output axis `axis`
+// ---------------------------------------------------------------------------------------------
+struct ViewTerm { int32_t group, axis, div, size, coef; };
+struct ViewGroup { int32_t tensor, stride, c, wrap, axis; };   // tensor: 0 = X, 1 = W; axis: the one a wrapped or constant group is charged to
+constexpr int kMaxViewTerms = 24, kMaxViewGroups = 16;
+struct ViewStream {
+  int32_t n_axes, n_terms, n_groups;
+  int32_t size[kMaxAxes];
+  ViewTerm term[kMaxViewTerms];
+  ViewGroup group[kMaxViewGroups];
+};
+
 enum KernelId : int32_t {
   KERNEL_GENERIC = 0,
   KERNEL_BW_DEPTHWISE,
   KERNEL_BW_WINDOW,
+  KERNEL_BW_VIEW,
   KERNEL_MFMA_F32,
   KERNEL_MFMA_BF16,
   KERNEL_MFMA_TRANSPOSED,   // a matrix product run as the 1x1 convolution with exchanged operand roles (plan->inner)
@@ -120,6 +139,8 @@ struct syno_plan {
   // matrix products: the plan of the equivalent 1x1 convolution (owned); Launch::variant holds its contraction
   syno_plan* inner = nullptr;
   ~syno_plan() { delete inner; }
+  bool pure_view = false;
+  syno::ViewStream view{};
 };
 
 namespace syno {
@@ -161,6 +182,8 @@ bool mfma_supports(const syno_plan* p, int which);
 // fills launch[which] (tile variant, workspace bytes) for the MFMA family
 void mfma_configure(syno_plan* p, int which);
 size_t bandwidth_workspace(const syno_plan* p, int which);
+// kernels_view.hip: Reduce-free graphs (forward only)
+bool view_supports(const syno_plan* p, int which);
 // kernels_window.hip: the unreduced-window member of the bandwidth family
 bool window_supports(const syno_plan* p, int which);
 size_t window_workspace(const syno_plan* p, int which);

@@ -416,6 +416,8 @@ struct Root {
   bool alive = true;
   int64_t size = 0;
   int64_t out_stride = 0;   // output iterators (and their digits): element stride in `out`
+  int axis = -1;            // output iterators and their digits: value = (o_axis / div) % size
+  int64_t div = 1;
 };
 
 struct Expr {
@@ -441,11 +443,13 @@ Expr add(const Expr& x, int64_t kx, const Expr& y, int64_t ky, int64_t c) {
 bool same_affine(const Expr& a, const Expr& b) { return a.coef == b.coef && a.c == b.c; }
 
 // Every coordinate as an affine expression of the iterators ("roots": output iterators, their Merge digits,
-// Reduce iterators), plus the range tests the Unfolds impose.  False when the graph has an Expand.
-bool analyse(const Graph& g, std::vector<Root>& roots, std::vector<Expr>& e, std::vector<Check>& checks) {
+// Reduce iterators), plus the range tests the Unfolds impose.  False when the graph has an Expand (unless allowed:
+// the expanded coordinate then simply influences nothing).
+bool analyse(const Graph& g, std::vector<Root>& roots, std::vector<Expr>& e, std::vector<Check>& checks,
+             bool allow_expand = false) {
   e.assign(g.n_slots, Expr());
   for (int i = 0; i < g.n_out; ++i) {
-    Root r; r.size = g.D(i); r.out_stride = g.out_stride[i];
+    Root r; r.size = g.D(i); r.out_stride = g.out_stride[i]; r.axis = i;
     roots.push_back(r);
     e[g.S(i)].coef[(int)roots.size() - 1] = 1;
   }
@@ -458,13 +462,16 @@ bool analyse(const Graph& g, std::vector<Root>& roots, std::vector<Expr>& e, std
         break;
       }
       case SYNO_SHARE: break;
-      case SYNO_EXPAND: return false;
+      case SYNO_EXPAND:
+        if (!allow_expand) return false;
+        break;
       case SYNO_MERGE: {
         const Expr& x = e[g.S(p.in[0])];
         if (!x.pure() || x.c != 0 || x.coef.size() != 1 || x.coef.begin()->second != 1) return false;
         const int r0 = x.coef.begin()->first;      // a bare iterator: refine it into two digits
         Root hi = roots[r0], lo = roots[r0];
         hi.size = roots[r0].size / p.param; hi.out_stride = roots[r0].out_stride * p.param;
+        hi.div = roots[r0].div * p.param;
         lo.size = p.param;
         roots[r0].alive = false;
         roots.push_back(hi);
@@ -738,6 +745,48 @@ bool recognise_matmul(const Graph& g, int64_t& M, int64_t& K, int64_t& N) {
   return true;
 }
 
+// Reduce-free graphs without range tests: the separable form of plan.h (ViewStream).
+bool recognise_view(const Graph& g, ViewStream& vs) {
+  if (!g.reduce_coords.empty() || g.n_out < 1) return false;
+  std::vector<Root> roots;
+  std::vector<Expr> e;
+  std::vector<Check> checks;
+  if (!analyse(g, roots, e, checks, true) || !checks.empty()) return false;
+  std::memset(&vs, 0, sizeof(vs));
+  vs.n_axes = g.n_out;
+  for (int i = 0; i < g.n_out; ++i) vs.size[i] = (int32_t)g.D(i);
+  auto add_tensor = [&](const std::vector<int>& coords, int tensor) {
+    std::vector<int64_t> stride(coords.size(), 1);
+    for (int i = (int)coords.size() - 2; i >= 0; --i) stride[i] = stride[i + 1] * g.D(coords[i + 1]);
+    for (size_t j = 0; j < coords.size(); ++j) {
+      const Expr& x = e[g.S(coords[j])];
+      if (x.complex || vs.n_groups >= kMaxViewGroups) return false;
+      ViewGroup& grp = vs.group[vs.n_groups];
+      grp.tensor = tensor; grp.stride = (int32_t)stride[j]; grp.wrap = (int32_t)x.wrap; grp.axis = 0;
+      grp.c = (int32_t)(x.wrap ? pos_mod(x.c, x.wrap) : x.c);
+      int one_axis = -1;
+      for (auto& t : x.coef) {
+        const Root& r = roots[t.first];
+        if (r.is_reduce || r.axis < 0 || vs.n_terms >= kMaxViewTerms) return false;
+        if (one_axis >= 0 && one_axis != r.axis && x.wrap) return false;     // a wrap over two output axes
+        one_axis = r.axis;
+        if (x.wrap && t.second < 0) return false;
+        vs.term[vs.n_terms++] = ViewTerm{vs.n_groups, r.axis, (int32_t)r.div, (int32_t)r.size, (int32_t)t.second};
+      }
+      if (one_axis >= 0) grp.axis = one_axis;
+      // without a wrap the value must stay inside the axis by itself
+      if (!x.wrap) {
+        int64_t lo = x.c, hi = x.c;
+        for (auto& t : x.coef) (t.second < 0 ? lo : hi) += t.second * (roots[t.first].size - 1);
+        if (lo < 0 || hi >= g.D(coords[j])) return false;
+      }
+      ++vs.n_groups;
+    }
+    return true;
+  };
+  return add_tensor(g.in_coords, 0) && add_tensor(g.w_coords, 1);
+}
+
 // The width to fold the N contiguous output columns of a matrix product into image rows of: the 1x1
 // convolution does not couple pixels, so any factorisation N = rows * width is the same contraction; widths
 // near the ones the contraction kernels are tuned on are preferred.  0 when N has no usable divisor.
@@ -935,6 +984,7 @@ syno_status build_plan(const syno_desc* desc, int policy, syno_plan* plan, std::
 
   plan->conv_like = recognise_conv(g, plan->conv);
   plan->share_window = !plan->conv_like && recognise_share_window(g, plan->window);
+  plan->pure_view = recognise_view(g, plan->view);
 
   for (int which = 0; which < 3; ++which) {
     Launch& L = plan->launch[which];
@@ -947,7 +997,9 @@ syno_status build_plan(const syno_desc* desc, int policy, syno_plan* plan, std::
     // Kernel choice.  A per-channel window (one input and one output channel per group) has about one
     // flop per byte: stream it.  A Reduce shared with a weight that also carries its own output
     // iterator is a real contraction: MFMA.  Everything else stays on the index-program kernels.
-    if (bandwidth_supports(plan, which)) {
+    if (view_supports(plan, which)) {            // nothing is summed: a stream whatever else the graph looks like
+      L.kernel = KERNEL_BW_VIEW;
+    } else if (bandwidth_supports(plan, which)) {
       L.kernel = KERNEL_BW_DEPTHWISE;
       L.workspace = bandwidth_workspace(plan, which);
     } else if (window_supports(plan, which)) {

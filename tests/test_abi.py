@@ -227,3 +227,15 @@ def test_materialised_reduction_pass_cuts_where_it_saves_work(syno):
     assert c.stages[2].kernel(0) == "mfma_contraction_f32" and c.stages[2].w_shape == (8, 8, 3, 3)
     # a Shift that reads another coordinate is left whole
     assert len(syno.Chain.materialized(wl.grouped_shift_unfold(2, 16, 16, 6, 6, 2)).stages) == 1
+
+
+def test_reduce_free_graphs_go_to_the_view_kernel_forwards(syno):
+    for d in (wl.shifted_scale(2, 8, 6, 6), wl.pixel_unshuffle(2, 4, 3, 4, 2)):
+        p = syno.Plan(d)
+        assert p.kernel(0) == "bandwidth_view" and p.kernel(1) == p.kernel(2) == "generic_index_program"
+        assert p.workspace_bytes(0) == 0
+    # a Shift whose amount depends on another output axis is not separable: index program
+    b = Builder([("g", 4), ("h", 6)])
+    gx, gw = b.share(0)
+    d = b.finish([gx, b.shift(1, 0, by=gx, coef=1)], [gw])
+    assert syno.Plan(d).kernel(0) == "generic_index_program"

@@ -333,6 +333,64 @@ def test_materialised_chain_equals_the_single_loop_nest(syno, oracle, mk, dt):
 
 
 # ------------------------------------------------------------------------------------------------
+# pure views (no Reduce): the table-driven streaming kernel forwards, index programs backwards
+# ------------------------------------------------------------------------------------------------
+def view_cases():
+    def expand_stride(i, o):
+        # out[n,r,k] = X[n, 3*k] * Wt[k]: Expand over r, Stride 3 under a Shared iterator
+        b = Builder([("n", 3), ("r", 4), ("k", 8)])
+        kx, kw = b.share(2)
+        b.expand(1)
+        return b.finish([0, b.stride(kx, 3)], [kw], i, o)
+
+    def pixel_shuffle(i, o):
+        # Table 2's PixelShuffle: out[n,c,H,W] = X[n, c, H%r, W%r, H/r, W/r] * Wt[c]
+        b = Builder([("n", 2), ("c", 3), ("H", 6), ("W", 10)])
+        cx, cw = b.share(1)
+        hq, hr = b.merge(2, 2)
+        wq, wr = b.merge(3, 2)
+        return b.finish([0, cx, hr, wr, hq, wq], [cw], i, o)
+
+    def shift_of_digit(i, o):
+        # a Shift applied to one digit of an output axis: X[(h/4), ((h%4)+3) mod 4, w]
+        b = Builder([("h", 12), ("w", 8)])
+        q, r = b.merge(0, 4)
+        return b.finish([q, b.shift(r, 3), 1], [], i, o)
+
+    return {
+        "shift_scale_v4": lambda i, o: wl.shifted_scale(3, 5, 7, 12, i, o),
+        "shift_scale_v1": lambda i, o: wl.shifted_scale(2, 3, 5, 7, i, o),
+        "pixel_unshuffle": lambda i, o: wl.pixel_unshuffle(2, 3, 5, 8, 2, i, o),
+        "pixel_unshuffle_r3": lambda i, o: wl.pixel_unshuffle(1, 2, 4, 5, 3, i, o),
+        "expand_stride": expand_stride, "pixel_shuffle": pixel_shuffle, "shift_of_digit": shift_of_digit,
+    }
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16", "bf16_f32out"])
+@pytest.mark.parametrize("name", list(view_cases()))
+def test_pure_views_small(syno, oracle, name, dt):
+    i_dt = F32 if dt == "f32" else BF16
+    o_dt = BF16 if dt == "bf16" else F32
+    d = view_cases()[name](i_dt, o_dt)
+    xs, ws, _ = oracle.describe(d)
+    os_ = oracle.out_shape(d)
+    st = wl.Stream(61)
+    w = wl._finish(d, xs, ws if ws else (1,), os_, st.normal(xs), st.uniform_pm(2.0, ws if ws else (1,)), st.normal(os_), 1)
+    names = run_all(syno, oracle, w, 0)
+    assert names[0] == "bandwidth_view"
+
+
+def test_pure_view_full_size(syno, oracle):
+    """The shapes the benchmark's detail times (102.8 MB in and out), forward, in full against the checker."""
+    for d in (wl.shifted_scale(64, 128, 56, 56), wl.pixel_unshuffle(64, 128, 28, 28, 2)):
+        xs, ws, _ = oracle.describe(d)
+        st = wl.Stream(62)
+        w = wl._finish(d, xs, ws if ws else (1,), oracle.out_shape(d), st.normal(xs), st.uniform_pm(2.0, ws if ws else (1,)),
+                       None, 1)
+        assert run_all(syno, oracle, w, 0, directions=(0,), full=True)[0] == "bandwidth_view"
+
+
+# ------------------------------------------------------------------------------------------------
 # matrix products (Table 2) run as 1x1 convolutions with the operands' roles exchanged
 # ------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("bf16", [False, True])

@@ -1,10 +1,12 @@
-// Bandwidth-bound family, third member: Reduce-free graphs (pure views: Shift, Split, Merge, Stride, Expand and
-// Share in any combination, no Unfold), forward pass:
+// Bandwidth-bound family, third member: graphs without Unfold and with at most a few sum points per output -
+// pure views (Shift, Split, Merge, Stride, Expand and Share in any combination) and small gather-and-add
+// operators (block sums, pools) - forward pass:
 //
-//   out[o] = X[offX(o)] * W[offW(o)]
+//   out[o] = sum_r X[offX(o,r)] * W[offW(o,r)]
 //
-// When every tensor axis is an affine function of digits of the output iterators - wrapped (Shift) only over
-// digits of one output axis - both offsets are sums of one small table per output axis (plan.h, ViewStream).
+// When every tensor axis is an affine function of digits of the iterators - wrapped (Shift) only over digits of
+// one iterator - both offsets are sums of one small table per iterator (plan.h, ViewStream); the tables of the
+// Reduce iterators are folded into one table over the sum points.
 // Every workgroup builds the tables in LDS from the record (a few hundred entries), then each lane takes a run
 // of V adjacent elements of the innermost output axis: the outer axes are decoded once per run, the innermost
 // axis is a table walk, the result leaves as one vector store.  The loads follow whatever order the view imposes.
@@ -19,9 +21,10 @@ constexpr int kThreads = 256;
 
 struct ViewParams {
   ViewStream vs;
-  int32_t tab_off[kMaxAxes];     // start of axis i's table (entries, X table; the W table follows at +tab_total)
-  uint32_t magic[kMaxAxes];      // division_magic(size[i])
-  int32_t tab_total;
+  int32_t tab_off[2 * kMaxAxes]; // start of iterator i's table (entries, X table; the W table follows at +tab_total)
+  uint32_t magic[kMaxAxes];      // division_magic(size[i]) of the output axes
+  int32_t tab_total;             // entries of all iterator tables
+  int32_t n_free, free_off;      // sum points per output; start of the folded table over them (X; W at +tab_total)
   int64_t n_runs;                // out elements / V
 };
 
@@ -67,9 +70,10 @@ __global__ __launch_bounds__(kThreads) void view_stream(const ViewParams p, cons
   extern __shared__ int tab[];     // [2][tab_total]: X offsets, then W offsets
   const ViewStream& vs = p.vs;
   // table entry (axis i, index o): the contribution of output axis i to each offset
-  for (int idx = threadIdx.x; idx < p.tab_total; idx += kThreads) {
+  const int n_iter = vs.n_axes + vs.n_red;
+  for (int idx = threadIdx.x; idx < p.free_off; idx += kThreads) {
     int axis = 0;
-    while (axis + 1 < vs.n_axes && idx >= p.tab_off[axis + 1]) ++axis;
+    while (axis + 1 < n_iter && idx >= p.tab_off[axis + 1]) ++axis;
     const int o = idx - p.tab_off[axis];
     int off[2] = {0, 0};
     for (int gi = 0; gi < vs.n_groups; ++gi) {
@@ -88,6 +92,19 @@ __global__ __launch_bounds__(kThreads) void view_stream(const ViewParams p, cons
     }
     tab[idx] = off[0];
     tab[p.tab_total + idx] = off[1];
+  }
+  __syncthreads();
+  // sum point q (Reduce iterators row-major, the order of the loop nest) -> the sum of its iterators' entries
+  for (int q = threadIdx.x; q < p.n_free; q += kThreads) {
+    int rest = q, fx = 0, fw = 0;
+    for (int j = vs.n_red - 1; j >= 0; --j) {
+      const int sz = vs.size[vs.n_axes + j], d = rest % sz;
+      rest /= sz;
+      fx += tab[p.tab_off[vs.n_axes + j] + d];
+      fw += tab[p.tab_total + p.tab_off[vs.n_axes + j] + d];
+    }
+    tab[p.free_off + q] = fx;
+    tab[p.tab_total + p.free_off + q] = fw;
   }
   __syncthreads();
   const int last = vs.n_axes - 1;
@@ -111,8 +128,21 @@ __global__ __launch_bounds__(kThreads) void view_stream(const ViewParams p, cons
     float r[V];
     const int* tx = tx_last + w0;
     const int* tw = tx + p.tab_total;
+    if (p.n_free == 1) {
 #pragma unroll
-    for (int v = 0; v < V; ++v) r[v] = load_one<IBF>(X, bx + tx[v]) * load_one<IBF>(Wt, bw + tw[v]);
+      for (int v = 0; v < V; ++v) r[v] = load_one<IBF>(X, bx + tx[v]) * load_one<IBF>(Wt, bw + tw[v]);
+    } else {
+      int ox[V], ow[V];
+#pragma unroll
+      for (int v = 0; v < V; ++v) { ox[v] = bx + tx[v]; ow[v] = bw + tw[v]; r[v] = 0.f; }
+      const int* fx = tab + p.free_off;
+      const int* fw = fx + p.tab_total;
+      for (int q = 0; q < p.n_free; ++q) {
+        const int dx = fx[q], dw = fw[q];
+#pragma unroll
+        for (int v = 0; v < V; ++v) r[v] = fmaf(load_one<IBF>(X, ox[v] + dx), load_one<IBF>(Wt, ow[v] + dw), r[v]);
+      }
+    }
     store_run<V, OBF>(out, run * V, r);
   }
 }
@@ -135,13 +165,17 @@ bool fill(const syno_plan* plan, ViewParams& p) {
   p.vs = plan->view;
   const int V = run_width(plan);
   int total = 0;
-  for (int i = 0; i < p.vs.n_axes; ++i) {
+  p.n_free = 1;
+  for (int i = 0; i < p.vs.n_axes + p.vs.n_red; ++i) {
     p.tab_off[i] = total;
     total += p.vs.size[i];
-    p.magic[i] = division_magic(p.vs.size[i]);
+    if (i < p.vs.n_axes) p.magic[i] = division_magic(p.vs.size[i]);
+    else p.n_free *= p.vs.size[i];
   }
   const int last = p.vs.n_axes - 1;
   p.magic[last] = division_magic(p.vs.size[last] / V);
+  p.free_off = total;
+  total += p.n_free;
   p.tab_total = total;
   p.n_runs = plan->out_elems / V;
   return total > 0 && (size_t)total * 8 <= 48 * 1024 && p.n_runs < (int64_t(1) << 31);

@@ -83,10 +83,11 @@ struct ShareWindow {
 };
 
 // ---------------------------------------------------------------------------------------------
-// Pure view (no Reduce, no Unfold): every X axis and every W axis is an affine function of digits of the output
-// iterators, optionally wrapped (Shift) when all its digits come from one output axis.  The two source offsets
-// are then sums of one table per output axis, offX(o) = sum_i tabX_i[o_i]; the kernel builds the tables in LDS
-// from this record.
+// Separable gather (no Unfold): every X axis and every W axis is an affine function of digits of the output
+// iterators and of the Reduce iterators, optionally wrapped (Shift) when all its digits come from one iterator.
+// The two source offsets are then sums of one table per iterator, offX(o,r) = sum_i tabX_i[o_i] + sum_j tabX_j[r_j];
+// the kernel builds the tables in LDS from this record.  Without Reduce it is a pure view; with a few sum points
+// per output (block sums, small pools) a gather-and-add.
 //   group  = one tensor axis: value = sum of its terms + c, taken mod `wrap` when wrap > 0, times `stride`
 //   term   = coef * ((o_axis / div) % size), a digit of output axis `axis`
 // ---------------------------------------------------------------------------------------------
@@ -95,7 +96,8 @@ struct ViewGroup { int32_t tensor, stride, c, wrap, axis; };   // tensor: 0 = X,
 constexpr int kMaxViewTerms = 24, kMaxViewGroups = 16;
 struct ViewStream {
   int32_t n_axes, n_terms, n_groups;
-  int32_t size[kMaxAxes];
+  int32_t n_red;                 // Reduce iterators: axes n_axes .. n_axes+n_red-1 of `size` (few sum points per output)
+  int32_t size[2 * kMaxAxes];
   ViewTerm term[kMaxViewTerms];
   ViewGroup group[kMaxViewGroups];
 };

@@ -448,6 +448,7 @@ bool same_affine(const Expr& a, const Expr& b) { return a.coef == b.coef && a.c 
 bool analyse(const Graph& g, std::vector<Root>& roots, std::vector<Expr>& e, std::vector<Check>& checks,
              bool allow_expand = false) {
   e.assign(g.n_slots, Expr());
+  int n_reduce_seen = 0;
   for (int i = 0; i < g.n_out; ++i) {
     Root r; r.size = g.D(i); r.out_stride = g.out_stride[i]; r.axis = i;
     roots.push_back(r);
@@ -457,6 +458,7 @@ bool analyse(const Graph& g, std::vector<Root>& roots, std::vector<Expr>& e, std
     switch (p.kind) {
       case SYNO_REDUCE: {
         Root r; r.is_reduce = true; r.size = p.param;
+        r.axis = g.n_out + n_reduce_seen++;      // Reduce iterators count on after the output axes
         roots.push_back(r);
         e[g.S(p.out[0])].coef[(int)roots.size() - 1] = 1;
         break;
@@ -745,9 +747,14 @@ bool recognise_matmul(const Graph& g, int64_t& M, int64_t& K, int64_t& N) {
   return true;
 }
 
-// Reduce-free graphs without range tests: the separable form of plan.h (ViewStream).
+// Graphs without range tests and with at most a few sum points per output: the separable form of plan.h
+// (ViewStream).
+constexpr int64_t kMaxViewSumPoints = 64;
 bool recognise_view(const Graph& g, ViewStream& vs) {
-  if (!g.reduce_coords.empty() || g.n_out < 1) return false;
+  if (g.n_out < 1 || (int)g.reduce_coords.size() > kMaxAxes) return false;
+  int64_t sum_points = 1;
+  for (int c : g.reduce_coords) sum_points *= g.D(c);
+  if (sum_points > kMaxViewSumPoints) return false;
   std::vector<Root> roots;
   std::vector<Expr> e;
   std::vector<Check> checks;
@@ -755,6 +762,8 @@ bool recognise_view(const Graph& g, ViewStream& vs) {
   std::memset(&vs, 0, sizeof(vs));
   vs.n_axes = g.n_out;
   for (int i = 0; i < g.n_out; ++i) vs.size[i] = (int32_t)g.D(i);
+  vs.n_red = (int32_t)g.reduce_coords.size();
+  for (int j = 0; j < vs.n_red; ++j) vs.size[g.n_out + j] = (int32_t)g.D(g.reduce_coords[j]);
   auto add_tensor = [&](const std::vector<int>& coords, int tensor) {
     std::vector<int64_t> stride(coords.size(), 1);
     for (int i = (int)coords.size() - 2; i >= 0; --i) stride[i] = stride[i + 1] * g.D(coords[i + 1]);
@@ -767,7 +776,7 @@ bool recognise_view(const Graph& g, ViewStream& vs) {
       int one_axis = -1;
       for (auto& t : x.coef) {
         const Root& r = roots[t.first];
-        if (r.is_reduce || r.axis < 0 || vs.n_terms >= kMaxViewTerms) return false;
+        if (r.axis < 0 || vs.n_terms >= kMaxViewTerms) return false;
         if (one_axis >= 0 && one_axis != r.axis && x.wrap) return false;     // a wrap over two output axes
         one_axis = r.axis;
         if (x.wrap && t.second < 0) return false;
@@ -997,7 +1006,7 @@ syno_status build_plan(const syno_desc* desc, int policy, syno_plan* plan, std::
     // Kernel choice.  A per-channel window (one input and one output channel per group) has about one
     // flop per byte: stream it.  A Reduce shared with a weight that also carries its own output
     // iterator is a real contraction: MFMA.  Everything else stays on the index-program kernels.
-    if (view_supports(plan, which)) {            // nothing is summed: a stream whatever else the graph looks like
+    if (plan->view.n_red == 0 && view_supports(plan, which)) {   // nothing is summed: a stream whatever else it looks like
       L.kernel = KERNEL_BW_VIEW;
     } else if (bandwidth_supports(plan, which)) {
       L.kernel = KERNEL_BW_DEPTHWISE;
@@ -1011,6 +1020,8 @@ syno_status build_plan(const syno_desc* desc, int policy, syno_plan* plan, std::
     } else if (which == SYNO_BWD_WEIGHT && mfma_dw_supports(plan)) {
       L.kernel = plan->in_dtype == SYNO_BF16 ? KERNEL_MFMA_BF16 : KERNEL_MFMA_F32;
       mfma_dw_configure(plan);
+    } else if (view_supports(plan, which)) {       // a few sum points per output and separable offsets: gather-and-add
+      L.kernel = KERNEL_BW_VIEW;
     }
   }
   // A matrix product is a 1x1 convolution with the operands' roles exchanged: W[k,j] is an "image" with k as

@@ -130,7 +130,8 @@ def test_out_of_range_points_yield_minus_one(syno):
 
 def test_kernel_choice(syno):
     names = lambda d: [syno.Plan(d).kernel(i) for i in range(3)]
-    assert all(n == "generic_index_program" for n in names(wl.matmul(3, 3, 5)))      # 3 columns: too narrow to fold
+    assert all(n == "generic_index_program" for n in names(wl.matmul(3, 3, 70)))     # 3 columns: too narrow to fold
+    assert names(wl.matmul(3, 3, 5)) == ["bandwidth_view", "generic_index_program", "generic_index_program"]   # 5 sum points
     assert all(n == "generic_index_program" for n in names(pixel_unshuffle_conv()))
     # the benchmarked workloads run on the tuned families, not on the index-program kernels
     for stage in range(4):
@@ -207,7 +208,7 @@ def test_matmul_is_planned_as_a_convolution_with_exchanged_roles(syno):
     q = syno.Plan(wl.matmul(96, 2304, 768, BF16, BF16))
     assert q.kernel(0) == "mfma_contraction_transposed" and q.kernel(1) == q.kernel(2) == "generic_index_program"
     # a prime number of columns above 64 cannot be folded into image rows
-    assert syno.Plan(wl.matmul(8, 127, 16)).kernel(0) == "generic_index_program"
+    assert syno.Plan(wl.matmul(8, 127, 80)).kernel(0) == "generic_index_program"
 
 
 def test_materialised_reduction_pass_cuts_where_it_saves_work(syno):

@@ -333,7 +333,8 @@ def test_materialised_chain_equals_the_single_loop_nest(syno, oracle, mk, dt):
 
 
 # ------------------------------------------------------------------------------------------------
-# pure views (no Reduce): the table-driven streaming kernel forwards, index programs backwards
+# pure views (no Reduce) and small gather-and-add operators: the table-driven streaming kernel forwards, index
+# programs backwards
 # ------------------------------------------------------------------------------------------------
 def view_cases():
     def expand_stride(i, o):
@@ -357,7 +358,16 @@ def view_cases():
         q, r = b.merge(0, 4)
         return b.finish([q, b.shift(r, 3), 1], [], i, o)
 
+    def block_sums(i, o):
+        # out[n,c,h,w] = Wt[c] * sum_{sh,sw} X[n, c, 2h+sh, 3w+sw]: 6 sum points per output
+        b = Builder([("n", 2), ("c", 5), ("h", 4), ("w", 8)])
+        cx, cw = b.share(1)
+        sh, sw = b.reduce(2), b.reduce(3)
+        return b.finish([0, cx, b.split(2, sh), b.split(3, sw)], [cw], i, o)
+
     return {
+        "block_sums": block_sums,
+        "small_matmul": lambda i, o: wl.matmul(9, 3, 7, i, o),     # 3 columns: not folded into a convolution
         "shift_scale_v4": lambda i, o: wl.shifted_scale(3, 5, 7, 12, i, o),
         "shift_scale_v1": lambda i, o: wl.shifted_scale(2, 3, 5, 7, i, o),
         "pixel_unshuffle": lambda i, o: wl.pixel_unshuffle(2, 3, 5, 8, 2, i, o),

@@ -217,7 +217,7 @@ def main() -> int:
             for which, tag in enumerate(("fwd", "bwd_data", "bwd_weight")):
                 cases.append(Case(f"qkv_mm_8192x768x2304_{'bf16' if bf16 else 'f32'}_{tag}", wq, which, sets=2))
         for c in cases:
-            med, avg = c.time_ms(30)
+            med, avg = c.time_ms(200, warm=10)
             tf = c.flops / (med * 1e-3) / 1e12
             gbs = c.bytes / (med * 1e-3) / 1e9
             peak = MFMA_PEAK_TFLOPS[c.dtype]
@@ -324,6 +324,36 @@ def main() -> int:
                        "TFLOP/s": fl_whole / (us_chain * 1e-6) / 1e12, "rel_l2_between_the_two": agree,
                        "note": "TFLOP/s counts the multiply-adds of the single loop nest"})
         out["detail"] = detail
+
+    # ---- practical ceilings of this machine, measured in the same run with library-free torch ops ---------------
+    if not args.no_detail:
+        def event_us(fn, iters):
+            fn()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(iters):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / iters * 1e3
+
+        ceilings = {}
+        for mib in (64, 256, 1024):
+            src = torch.empty(mib << 20, dtype=torch.uint8, device=dev).fill_(1)
+            dsts = [torch.empty_like(src) for _ in range(2)]
+            k = [0]
+
+            def copy():
+                dsts[k[0] & 1].copy_(src)
+                k[0] += 1
+
+            us = event_us(copy, 20)
+            ceilings[f"device_copy_{mib}MiB_GB/s"] = 2 * (mib << 20) / (us * 1e-6) / 1e9     # read + write
+            del src, dsts
+        one = torch.zeros(1, device=dev)
+        ceilings["smallest_launch_us"] = event_us(lambda: one.add_(1.0), 200)    # back-to-back one-element kernels
+        out["ceilings"] = ceilings
 
     # ---- CPU baseline: the checker as it stands, on a bounded sample of the same workload ---------------------
     if not args.no_cpu_baseline:

@@ -51,7 +51,9 @@ namespace {
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 constexpr int kGuard = 8;     // zero elements in front of each X channel row (a tap may reach one element back)
-constexpr int kDwItems = 26;  // dword items per thread per tensor per chunk (256 threads)
+// staging items per thread, tensor and chunk (256 threads): 26 of one or two pixels (a dword), or 18 of four (two
+// dwords) - about the same registers either way
+constexpr int dw_items(int ep) { return ep == 4 ? 18 : 26; }
 
 __device__ __forceinline__ uint32_t alignbit16(uint32_t hi, uint32_t lo) { return __builtin_amdgcn_alignbit(hi, lo, 16); }
 
@@ -71,8 +73,8 @@ __device__ __forceinline__ bf16x8 cut(const uint4& lo, const uint4& hi) {
 
 // One workgroup: group g, 64 output channels x 32*CT input channels, one split of the pixel rows.
 // 4 waves; wave (wo, wc) owns o-tiles {2wo, 2wo+1} x CT c-tiles x KH*KW taps (CT = 2 for up to 3 taps, 1 for 9).
-// Staging moves pairs of pixels (one dword) when W is even, single pixels (W1) when it is odd.
-template <int KH, int KW, int CT, bool W1>
+// Staging moves items of EP adjacent pixels of a row: 4 (two dwords) when W is a multiple of 4, else 2, else 1.
+template <int KH, int KW, int CT, int EP>
 __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint16_t* __restrict__ Gt,
                                                     const uint16_t* __restrict__ Xt, float* __restrict__ partial) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -102,9 +104,10 @@ __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint
   // per-thread item descriptors, the same for G and X: (channel, row, dword) of the chunk
   // goff: element offset inside the 64-channel slab, shifted left by one; bit 0 set = G channel beyond Og
   // meta: LDS element offset | row << 20 | (X channel beyond Cg) << 30 ; -1 when unused
+  constexpr int kDwItems = dw_items(EP);
+  constexpr int EPW = EP == 4 ? 2 : 1;    // dwords per item
   int it_goff[kDwItems], it_meta[kDwItems];
-  const int W2 = W1 ? p.W : p.W >> 1;     // items per row
-  constexpr int EP = W1 ? 1 : 2;          // elements per item
+  const int W2 = p.W / EP;                // items per row
   const int o_lim = p.Og - ob * 64, c_lim = min(p.Cg - cb * CX, CX);     // channels beyond are zero
 #pragma unroll
   for (int k = 0; k < kDwItems; ++k) {
@@ -134,7 +137,7 @@ __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint
 #pragma unroll
   for (int b = 0; b < CT; ++b) b_base[b] = ((CT * wc + b) * 16 + (lane & 15)) * p.CPp + (lane >> 4) * 8 + kGuard - 8;
 
-  uint32_t gr[kDwItems], xr[kDwItems];
+  uint32_t gr[kDwItems][EPW], xr[kDwItems][EPW];
   for (int q = chunk_begin; q < chunk_end; ++q) {
     __syncthreads();        // previous chunk fully consumed (and, first time, the zero fill is complete)
     if (tid < p.n_xrows) {
@@ -162,16 +165,26 @@ __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < kDwItems; ++k) {
-      gr[k] = 0; xr[k] = 0;
+#pragma unroll
+      for (int w = 0; w < EPW; ++w) { gr[k][w] = 0; xr[k][w] = 0; }
       if (it_meta[k] >= 0) {
         const int r = (it_meta[k] >> 20) & 1023;
         const int go = row_tab[r], xo = row_tab[p.n_xrows + r];
-        if constexpr (W1) {
-          if (go >= 0 && !(it_goff[k] & 1)) gr[k] = Gg[go + (it_goff[k] >> 1)];
-          if (xo >= 0 && !(it_meta[k] >> 30)) xr[k] = Xg[xo + (it_goff[k] >> 1)];
+        if constexpr (EP == 1) {
+          if (go >= 0 && !(it_goff[k] & 1)) gr[k][0] = Gg[go + (it_goff[k] >> 1)];
+          if (xo >= 0 && !(it_meta[k] >> 30)) xr[k][0] = Xg[xo + (it_goff[k] >> 1)];
+        } else if constexpr (EP == 2) {
+          if (go >= 0 && !(it_goff[k] & 1)) gr[k][0] = *reinterpret_cast<const uint32_t*>(Gg + go + (it_goff[k] >> 1));
+          if (xo >= 0 && !(it_meta[k] >> 30)) xr[k][0] = *reinterpret_cast<const uint32_t*>(Xg + xo + (it_goff[k] >> 1));
         } else {
-          if (go >= 0 && !(it_goff[k] & 1)) gr[k] = *reinterpret_cast<const uint32_t*>(Gg + go + (it_goff[k] >> 1));
-          if (xo >= 0 && !(it_meta[k] >> 30)) xr[k] = *reinterpret_cast<const uint32_t*>(Xg + xo + (it_goff[k] >> 1));
+          if (go >= 0 && !(it_goff[k] & 1)) {
+            const uint2 t = *reinterpret_cast<const uint2*>(Gg + go + (it_goff[k] >> 1));
+            gr[k][0] = t.x; gr[k][EPW - 1] = t.y;
+          }
+          if (xo >= 0 && !(it_meta[k] >> 30)) {
+            const uint2 t = *reinterpret_cast<const uint2*>(Xg + xo + (it_goff[k] >> 1));
+            xr[k][0] = t.x; xr[k][EPW - 1] = t.y;
+          }
         }
       }
     }
@@ -179,12 +192,15 @@ __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint
     for (int k = 0; k < kDwItems; ++k)
       if (it_meta[k] >= 0) {
         const int lo = it_meta[k] & 0xfffff;
-        if constexpr (W1) {
-          gl[lo] = (uint16_t)gr[k];
-          if (!(it_meta[k] >> 30)) xl[lo + kGuard] = (uint16_t)xr[k];   // (channels X does not have stay zero)
+        if constexpr (EP == 1) {
+          gl[lo] = (uint16_t)gr[k][0];
+          if (!(it_meta[k] >> 30)) xl[lo + kGuard] = (uint16_t)xr[k][0];   // (channels X does not have stay zero)
+        } else if constexpr (EP == 2) {
+          *reinterpret_cast<uint32_t*>(gl + lo) = gr[k][0];
+          if (!(it_meta[k] >> 30)) *reinterpret_cast<uint32_t*>(xl + lo + kGuard) = xr[k][0];
         } else {
-          *reinterpret_cast<uint32_t*>(gl + lo) = gr[k];
-          if (!(it_meta[k] >> 30)) *reinterpret_cast<uint32_t*>(xl + lo + kGuard) = xr[k];
+          *reinterpret_cast<uint2*>(gl + lo) = make_uint2(gr[k][0], gr[k][EPW - 1]);
+          if (!(it_meta[k] >> 30)) *reinterpret_cast<uint2*>(xl + lo + kGuard) = make_uint2(xr[k][0], xr[k][EPW - 1]);
         }
       }
     __syncthreads();
@@ -547,11 +563,13 @@ bool fill_dw(const syno_plan* plan, DwParams& p) {
   if (c.KH > 1) p.pitch = (p.pitch + 7) & ~7;        // whole-row shifts stay 16-byte aligned
   const int cx = (c.KH * c.KW <= 3) ? 64 : 32;       // X channels per workgroup
   // rows per chunk: about 224 staged elements per channel, bounded by the per-thread item budget
-  const int W2 = (c.Wo & 1) ? c.Wo : c.Wo / 2, halo = c.KH - 1;    // items per row: pixel pairs, or pixels when W is odd
+  const int ep = (c.Wo % 4 == 0) ? 4 : (c.Wo % 2 == 0) ? 2 : 1;   // pixels per staging item
+  const int W2 = c.Wo / ep, halo = c.KH - 1;                       // items per row
+  if (ep == 4) p.pitch = (p.pitch + 3) & ~3;                      // 8-byte LDS writes
   int trk = std::max(1, 224 / p.pitch);
   if (c.KH > 1) trk = std::min(trk, c.Ho);
-  while (trk > 1 && 64 * (trk + halo) * W2 > kDwItems * 256) --trk;
-  if (64 * (trk + halo) * W2 > kDwItems * 256) return false;
+  while (trk > 1 && 64 * (trk + halo) * W2 > dw_items(ep) * 256) --trk;
+  if (64 * (trk + halo) * W2 > dw_items(ep) * 256) return false;
   if (c.KH > 1) {
     p.cpi = (c.Ho + trk - 1) / trk;                   // chunks stay inside an image, all about equally long
     trk = (c.Ho + p.cpi - 1) / p.cpi;
@@ -732,16 +750,18 @@ syno_status launch_mfma_dw(const syno_plan* plan, const void* A, const void* B, 
       return;
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), p.lds_bytes, stream, p, G, X, part);
   };
-  if (p.W & 1) {
-    if (p.KH == 3 && p.KW == 3) launch(dw_mfma_bf16<3, 3, 1, true>);
-    else if (p.KH == 3) launch(dw_mfma_bf16<3, 1, 2, true>);
-    else if (p.KW == 3) launch(dw_mfma_bf16<1, 3, 2, true>);
-    else launch(dw_mfma_bf16<1, 1, 2, true>);
-  } else {
-    if (p.KH == 3 && p.KW == 3) launch(dw_mfma_bf16<3, 3, 1, false>);
-    else if (p.KH == 3) launch(dw_mfma_bf16<3, 1, 2, false>);
-    else if (p.KW == 3) launch(dw_mfma_bf16<1, 3, 2, false>);
-    else launch(dw_mfma_bf16<1, 1, 2, false>);
+  auto by_item = [&](auto kh_c, auto kw_c, auto ct_c) {
+    constexpr int kh = decltype(kh_c)::value, kw = decltype(kw_c)::value, ct = decltype(ct_c)::value;
+    if (p.W % 4 == 0) launch(dw_mfma_bf16<kh, kw, ct, 4>);
+    else if (p.W % 2 == 0) launch(dw_mfma_bf16<kh, kw, ct, 2>);
+    else launch(dw_mfma_bf16<kh, kw, ct, 1>);
+  };
+  {
+    using std::integral_constant;
+    if (p.KH == 3 && p.KW == 3) by_item(integral_constant<int, 3>{}, integral_constant<int, 3>{}, integral_constant<int, 1>{});
+    else if (p.KH == 3) by_item(integral_constant<int, 3>{}, integral_constant<int, 1>{}, integral_constant<int, 2>{});
+    else if (p.KW == 3) by_item(integral_constant<int, 1>{}, integral_constant<int, 3>{}, integral_constant<int, 2>{});
+    else by_item(integral_constant<int, 1>{}, integral_constant<int, 1>{}, integral_constant<int, 2>{});
   }
   // many splits of a small dW: one block per slot keeps the device busy; few splits of a large dW: one block per
   // 16x16 tile with all its taps writes dW in whole lines

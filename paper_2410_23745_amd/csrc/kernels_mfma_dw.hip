@@ -51,9 +51,9 @@ namespace {
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 constexpr int kGuard = 8;     // zero elements in front of each X channel row (a tap may reach one element back)
-// staging items per thread, tensor and chunk (256 threads): 26 of one or two pixels (a dword), or 18 of four (two
+// staging items per thread, tensor and chunk (256 threads): 26-28 of one or two pixels (a dword), or 18 of four (two
 // dwords) - about the same registers either way
-constexpr int dw_items(int ep) { return ep == 4 ? 18 : 26; }
+constexpr int dw_items(int ep) { return ep == 4 ? 18 : ep == 2 ? 28 : 26; }   // (28: a whole 14 x 14 image with its halo rows)
 
 __device__ __forceinline__ uint32_t alignbit16(uint32_t hi, uint32_t lo) { return __builtin_amdgcn_alignbit(hi, lo, 16); }
 

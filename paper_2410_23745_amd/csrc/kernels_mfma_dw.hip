@@ -40,9 +40,10 @@ struct DwParams {
   int32_t rows_per_split, n_splits, n_oblk, n_cblk;
   int32_t n_xrows;                     // rows of X staged per chunk: TRK + KH - 1
   int32_t cpi;                         // KH > 1: chunks per image (chunks do not cross images); else 0
+  int32_t ipc, n_images;               // bf16, KH > 1, cpi == 1: whole images per chunk, each with its own halo rows
   int32_t chunks_per_split, n_chunks;
   int32_t items;                       // 64 * n_xrows * W/2 dword items per tensor per chunk
-  uint32_t magic_w2, magic_rw2;        // ceil(2^32/d) for d = W/2 and n_xrows*W/2
+  uint32_t magic_w2, magic_rw2;        // ceil(2^32/d) for d = items per row and n_xrows * items per row (0 for d = 1)
   int32_t lds_x_off, lds_tab_off, lds_bytes;
 };
 
@@ -53,7 +54,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 constexpr int kGuard = 8;     // zero elements in front of each X channel row (a tap may reach one element back)
 // staging items per thread, tensor and chunk (256 threads): 26-28 of one or two pixels (a dword), or 18 of four (two
 // dwords) - about the same registers either way
-constexpr int dw_items(int ep) { return ep == 4 ? 18 : ep == 2 ? 28 : 26; }   // (28: a whole 14 x 14 image with its halo rows)
+constexpr int dw_items(int ep) { return ep == 4 ? 18 : ep == 2 ? 28 : 32; }   // (28: a whole 14 x 14 image with its halo rows; 32: two 7 x 7 images)
 
 __device__ __forceinline__ uint32_t alignbit16(uint32_t hi, uint32_t lo) { return __builtin_amdgcn_alignbit(hi, lo, 16); }
 
@@ -114,7 +115,7 @@ __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint
     const int idx = tid + k * 256;
     const int ch = __umulhi((uint32_t)idx, p.magic_rw2);
     const int rem = idx - ch * (p.n_xrows * W2);
-    const int r = __umulhi((uint32_t)rem, p.magic_w2);
+    const int r = p.magic_w2 ? __umulhi((uint32_t)rem, p.magic_w2) : rem;   // (one item per row: no division)
     const int j = rem - r * W2;
     it_goff[k] = ((ch * p.plane + EP * j) << 1) | (ch < o_lim ? 0 : 1);
     it_meta[k] = idx < p.items ? ((ch * p.CPp + r * p.pitch + EP * j) | (r << 20) | (ch < c_lim ? 0 : (1 << 30))) : -1;
@@ -152,12 +153,25 @@ __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint
           xo = n * p.xs_n + r * p.W;
         }
       } else {
+        if (p.ipc > 1) {
+          // several whole images, each in H + KH - 1 slots: slot l of an image holds G row l (the last KH - 1 stay
+          // zero) and X row l - ph (zero outside the image), so a tap is the same shift of whole rows everywhere
+          const int per = p.H + KH - 1;
+          const int i = tid / per, l = tid - i * per;
+          const int n = q * p.ipc + i;
+          if (n < p.n_images) {
+            if (l < p.H) go = n * p.gs_n + l * p.W;
+            const int hx = l - p.ph;
+            if (hx >= 0 && hx < p.H) xo = n * p.xs_n + hx * p.W;
+          }
+        } else {
         // rows h0 .. h0+TRK-1 of image n; X slot r holds image row h0 - ph + r (zero outside the image)
         const int n = q / p.cpi, h0 = (q - n * p.cpi) * p.TRK;
         const int rows = min(p.TRK, p.H - h0);
         if (tid < rows) go = n * p.gs_n + (h0 + tid) * p.W;
         const int hx = h0 - p.ph + tid;
         if (tid < rows + KH - 1 && hx >= 0 && hx < p.H) xo = n * p.xs_n + hx * p.W;
+        }
       }
       row_tab[tid] = go;
       row_tab[p.n_xrows + tid] = xo;
@@ -329,7 +343,7 @@ __global__ __launch_bounds__(256) void dw_mfma_f32(const DwParams p, const float
       const int idx = tid + k * 256;
       const int ch = __umulhi((uint32_t)idx, p.magic_rw2);
       const int rem = idx - ch * (p.n_xrows * WV);
-      const int r = __umulhi((uint32_t)rem, p.magic_w2);
+      const int r = p.magic_w2 ? __umulhi((uint32_t)rem, p.magic_w2) : rem;   // (one item per row: no division)
       const int j = (rem - r * WV) * VEC;
       const bool used = idx < p.items;
       it_off[k] = ch * p.plane + j;
@@ -580,6 +594,19 @@ bool fill_dw(const syno_plan* plan, DwParams& p) {
   }
   p.TRK = trk;
   p.n_xrows = trk + halo;
+  p.ipc = 1; p.n_images = c.N;
+  if (c.KH > 1 && p.cpi == 1) {
+    // whole small images: as many per chunk as the item budget and about 1024 staged elements per channel allow
+    const int per = c.Ho + halo;
+    int m = 1;
+    while (m < c.N && 64 * (m + 1) * per * W2 <= dw_items(ep) * 256 && (m + 1) * per * p.pitch <= 1024) ++m;
+    if (m > 1) {
+      p.ipc = m;
+      p.n_xrows = m * per;
+      p.TRK = p.n_xrows - halo;
+      p.n_chunks = (c.N + m - 1) / m;
+    }
+  }
   p.CP = (p.TRK * p.pitch + 31) & ~31;
   // LDS channel pitch: the last k-step reads up to CP + halo rows + 24 elements; guard in front, rows 16-byte
   // aligned and bank-skewed

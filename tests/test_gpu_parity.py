@@ -85,6 +85,10 @@ def small_cases():
     c["conv_bf16_chan_tail"] = lambda: wl.make_conv(2, 80, 10, seed=10, Co=48, bf16=True, with_grad=True)   # 2.5 chunks
     c["conv_f32_wide_rows"] = lambda: wl.make_conv(1, 8, 6, seed=11, Co=8, Wd=60, with_grad=True)
     c["conv_bf16_wide_rows"] = lambda: wl.make_conv(1, 8, 5, seed=12, Co=8, Wd=60, bf16=True, with_grad=True)
+    # small images: backward-weight stages several whole images per chunk (the last chunk is short)
+    c["conv_bf16_7x7_five_images"] = lambda: wl.make_conv(5, 24, 7, seed=13, Co=40, bf16=True, with_grad=True)
+    c["conv_bf16_5x4_five_images"] = lambda: wl.make_conv(5, 16, 5, seed=14, Co=16, Wd=4, bf16=True, with_grad=True)
+    c["conv_f32_5x4_five_images"] = lambda: wl.make_conv(5, 16, 5, seed=15, Co=16, Wd=4, with_grad=True)   # one staging item per row
     c["gshift_bf16"] = lambda: wl.make_gshift(3, seeds=(1, 2, 3), with_grad=True)
     c["gshift_bf16_small_groups"] = lambda: wl.make_gshift(2, seeds=(4, 5, 6), with_grad=True, C=96, H=9, Wd=11, groups=3)
     c["gshift_f32"] = lambda: wl.make_gshift(2, seeds=(7, 8, 9), with_grad=True, C=64, H=6, Wd=10, groups=2, bf16=False)

@@ -180,12 +180,13 @@ def main() -> int:
         pass
 
     out = {
-        "metric": "operator fwd TFLOP/s & % of roofline at ResNet-style layer shapes",
+        "metric": "operator fwd+bwd TFLOP/s (or GB/s) & % of roofline at ResNet-style layer shapes",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32 and bf16-in/f32-acc", "data": "synthetic",
         "config": {"workload": "configs[1]: conv-equivalent Syno operator (Unfold 3x3 pad 1, Share, Reduce C,kh,kw), "
-                               "forward, N=32, ResNet-18 stages (64,56) (128,28) (256,14) (512,7), fp32 and bf16 inputs",
+                               "forward (the passes this configuration names; the backward passes of the same shapes are timed "
+                               "under detail), N=32, ResNet-18 stages (64,56) (128,28) (256,14) (512,7), fp32 and bf16 inputs",
                    "flop_per_step": step_flops},
         "roofline": roofline,
         "per_launch_us": {k: v * 1e3 for k, v in per_case.items()},

@@ -240,3 +240,25 @@ def test_reduce_free_graphs_go_to_the_view_kernel_forwards(syno):
     gx, gw = b.share(0)
     d = b.finish([gx, b.shift(1, 0, by=gx, coef=1)], [gw])
     assert syno.Plan(d).kernel(0) == "generic_index_program"
+
+
+def test_chain_entry_points_reject_bad_arguments_on_the_host(syno):
+    lib = syno.load_library()
+    chain = syno.Chain([wl.conv2d(1, 4, 4, 5, 5)])
+    null = ctypes.c_void_p()
+    n = ctypes.c_size_t()
+    assert lib.syno_chain_workspace_bytes(chain._h, 2, ctypes.byref(n)) == 3          # selector out of range
+    assert lib.syno_chain_workspace_bytes(None, 0, ctypes.byref(n)) == 1
+    assert lib.syno_chain_stages(None) == 0 and lib.syno_chain_weight_stage(None) == -1
+    assert lib.syno_chain_weight_stage(chain._h) == -1                                 # every stage has its own weight
+    # NULL tensors are refused before anything is launched
+    assert lib.syno_chain_forward(chain._h, None, None, None, None, None, None) == 1
+    assert lib.syno_chain_backward(chain._h, None, None, None, None, None, None, None, None) == 1
+    h = ctypes.c_void_p()
+    assert lib.syno_chain_create(None, 1, ctypes.byref(h)) == 1
+    assert lib.syno_chain_create_materialized(None, ctypes.byref(h)) == 1
+    # an invalid graph is reported by the pass as by plan creation
+    b = Builder([("i", 4)])
+    bad = b.finish([0, 0], [])                                                         # coordinate consumed twice
+    with pytest.raises(syno.SynoError):
+        syno.Chain.materialized(bad)

@@ -291,10 +291,13 @@ def test_share_window_bf16_rounding_is_nearest_even(syno, oracle):
 
 
 @pytest.mark.parametrize("bf16", [False, True])
-def test_operator1_full_size(syno, oracle, bf16):
-    """Operator 1 in place of the first ResNet-18 stage's convolution (C = 64, 56 x 56, N = 32), the shape the
-    benchmark's detail times."""
-    run_chain(syno, oracle, wl.operator1(0, bf16), 0)
+@pytest.mark.parametrize("stage", [0, 3])
+def test_operator1_full_size(syno, oracle, stage, bf16):
+    """Operator 1 in place of a ResNet-18 stage's convolution, N = 32: the first stage (C = 64, 56 x 56: the shape
+    the benchmark's detail times) and the last (C = 512, 7 x 7: odd width, 64 x 128 weights per group and window
+    position, several tiles of each in the first-stage kernels)."""
+    names = run_chain(syno, oracle, wl.operator1(stage, bf16), 0)
+    assert names[0] == ["bandwidth_share_window"] * 3
 
 
 # ------------------------------------------------------------------------------------------------

@@ -270,7 +270,27 @@ __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint
     else mfmas(f0);
   }
 
-  // partial[split][dW layout]: lane holds 4 consecutive o (rows of D) at one c (column)
+  // One split only (large dW, few pixels): nothing to add up, the sums go straight into dW (`partial` is dW then):
+  // lane holds 4 consecutive o (rows of D) at one c (column).
+  if (p.n_splits == 1) {
+    float* dw = partial + (int64_t)g * p.ws_g;
+#pragma unroll
+    for (int ao = 0; ao < 2; ++ao)
+#pragma unroll
+      for (int i = 0; i < CT; ++i) {
+        const int c = cb * CX + (CT * wc + i) * 16 + (lane & 15);
+        if (c >= p.Cg) continue;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int o = ob * 64 + (2 * wo + ao) * 16 + 4 * (lane >> 4) + v;
+          if (o >= p.Og) continue;
+#pragma unroll
+          for (int t = 0; t < T; ++t)
+            dw[(int64_t)o * p.ws_o + (int64_t)c * p.ws_c + (t / KW) * p.ws_kh + (t % KW) * p.ws_kw] = acc[ao][i][t][v];
+        }
+      }
+    return;
+  }
   // partial[split][tile][slot][lane]: every accumulator register quadruple goes out as it is, one 16-byte store
   // per lane (1 KB per wave and slot); the reduction kernel knows which weights a (slot, lane) holds
   constexpr int SLOTS = 8 * CT * T;
@@ -463,6 +483,27 @@ __global__ __launch_bounds__(256) void dw_mfma_f32(const DwParams p, const float
     else mfmas(fa0, fb0);
   }
 
+  // One split only (large dW, few pixels): nothing to add up, the sums go straight into dW (`partial` is dW then):
+  // lane holds 4 consecutive o (rows of D) at one c (column).
+  if (p.n_splits == 1) {
+    float* dw = partial + (int64_t)g * p.ws_g;
+#pragma unroll
+    for (int ao = 0; ao < 2; ++ao)
+#pragma unroll
+      for (int i = 0; i < CT; ++i) {
+        const int c = cb * CX + (CT * wc + i) * 16 + (lane & 15);
+        if (c >= p.Cg) continue;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int o = ob * 64 + (2 * wo + ao) * 16 + 4 * (lane >> 4) + v;
+          if (o >= p.Og) continue;
+#pragma unroll
+          for (int t = 0; t < T; ++t)
+            dw[(int64_t)o * p.ws_o + (int64_t)c * p.ws_c + (t / KW) * p.ws_kh + (t % KW) * p.ws_kw] = acc[ao][i][t][v];
+        }
+      }
+    return;
+  }
   // partial[split][tile][slot][lane]: every accumulator register quadruple goes out as it is, one 16-byte store
   // per lane (1 KB per wave and slot); the reduction kernel knows which weights a (slot, lane) holds
   constexpr int SLOTS = 8 * CT * T;
@@ -722,7 +763,7 @@ void mfma_dw_configure(syno_plan* plan) {
   fill_any(plan, dp);
   plan->launch[SYNO_BWD_WEIGHT].variant = 0;
   // one 64 x 32*ct x taps tile of fp32 sums per workgroup (whole tiles also where Og or Cg end inside one)
-  plan->launch[SYNO_BWD_WEIGHT].workspace = (size_t)dp.n_splits * dp.n_tiles * dp.slots * 1024;
+  plan->launch[SYNO_BWD_WEIGHT].workspace = dp.n_splits == 1 ? 0 : (size_t)dp.n_splits * dp.n_tiles * dp.slots * 1024;
 }
 
 std::string mfma_dw_describe(const syno_plan* plan) {
@@ -738,7 +779,7 @@ std::string mfma_dw_describe(const syno_plan* plan) {
 syno_status launch_mfma_dw(const syno_plan* plan, const void* A, const void* B, void* out, void* ws, hipStream_t stream) {
   DwParams p;
   if (!fill_any(plan, p)) return SYNO_ERR_UNSUPPORTED;
-  if (!ws) return SYNO_ERR_WORKSPACE;
+  if (!ws && p.n_splits > 1) return SYNO_ERR_WORKSPACE;
   const int grid = p.G * p.n_oblk * p.n_cblk * p.n_splits;
   if (plan->in_dtype == SYNO_F32) {
     const float* Gf = static_cast<const float*>(A);
@@ -747,7 +788,8 @@ syno_status launch_mfma_dw(const syno_plan* plan, const void* A, const void* B, 
     auto launchf = [&](auto kernel) {
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024) != hipSuccess)
         return;
-      hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), p.lds_bytes, stream, p, Gf, Xf, partf);
+      hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), p.lds_bytes, stream, p, Gf, Xf,
+                         p.n_splits == 1 ? static_cast<float*>(out) : partf);
     };
     auto by_vec = [&](auto kh_c, auto kw_c, auto ct_c) {
       constexpr int kh = decltype(kh_c)::value, kw = decltype(kw_c)::value, ct = decltype(ct_c)::value;
@@ -760,7 +802,9 @@ syno_status launch_mfma_dw(const syno_plan* plan, const void* A, const void* B, 
     else if (p.KH == 3) by_vec(integral_constant<int, 3>{}, integral_constant<int, 1>{}, integral_constant<int, 2>{});
     else if (p.KW == 3) by_vec(integral_constant<int, 1>{}, integral_constant<int, 3>{}, integral_constant<int, 2>{});
     else by_vec(integral_constant<int, 1>{}, integral_constant<int, 1>{}, integral_constant<int, 2>{});
-    if (p.n_splits > 4)
+    if (p.n_splits == 1) {
+      // (written by the contraction itself)
+    } else if (p.n_splits > 4)
       hipLaunchKernelGGL(dw_reduce_slots, dim3(p.n_tiles * p.slots), dim3(256), 0, stream, p,
                          reinterpret_cast<const float4*>(partf), static_cast<float*>(out));
     else
@@ -775,7 +819,8 @@ syno_status launch_mfma_dw(const syno_plan* plan, const void* A, const void* B, 
     // (once per instantiation would do; the attribute call is cheap next to the launch)
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024) != hipSuccess)
       return;
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), p.lds_bytes, stream, p, G, X, part);
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), p.lds_bytes, stream, p, G, X,
+                       p.n_splits == 1 ? static_cast<float*>(out) : part);
   };
   auto by_item = [&](auto kh_c, auto kw_c, auto ct_c) {
     constexpr int kh = decltype(kh_c)::value, kw = decltype(kw_c)::value, ct = decltype(ct_c)::value;
@@ -792,7 +837,9 @@ syno_status launch_mfma_dw(const syno_plan* plan, const void* A, const void* B, 
   }
   // many splits of a small dW: one block per slot keeps the device busy; few splits of a large dW: one block per
   // 16x16 tile with all its taps writes dW in whole lines
-  if (p.n_splits > 4)
+  if (p.n_splits == 1) {
+    // (written by the contraction itself)
+  } else if (p.n_splits > 4)
     hipLaunchKernelGGL(dw_reduce_slots, dim3(p.n_tiles * p.slots), dim3(256), 0, stream, p,
                        reinterpret_cast<const float4*>(part), static_cast<float*>(out));
   else

@@ -390,14 +390,14 @@ bool build_program(const Graph& g, const TensorAxes& target, const std::vector<i
   for (int i = 0; i < out.n_tgt; ++i) {
     out.tgt[i] = AxisRef{g.S(target.coords[i]), (int32_t)g.D(target.coords[i]),
                          (int32_t)division_magic(g.D(target.coords[i]))};
-    out.n_target *= g.D(target.coords[i]);
+    out.n_target = std::min<int64_t>(out.n_target * g.D(target.coords[i]), int64_t(1) << 40);  // (saturates: no overflow)
   }
   out.n_fre = (int32_t)b.free_slots.size();
   out.n_free = 1;
   for (int i = 0; i < out.n_fre; ++i) {
     out.fre[i] = AxisRef{b.free_slots[i], (int32_t)g.slot_dom[b.free_slots[i]],
                          (int32_t)division_magic(g.slot_dom[b.free_slots[i]])};
-    out.n_free *= g.slot_dom[b.free_slots[i]];
+    out.n_free = std::min<int64_t>(out.n_free * g.slot_dom[b.free_slots[i]], int64_t(1) << 40);
   }
   out.n_a = (int32_t)A.coords.size();
   for (int i = 0; i < out.n_a; ++i)
@@ -990,6 +990,10 @@ syno_status build_plan(const syno_desc* desc, int policy, syno_plan* plan, std::
     return unsupported("backward-data index map could not be inverted");
   if (!build_program(g, W, nullptr, O, X, plan->prog[SYNO_BWD_WEIGHT]))
     return unsupported("backward-weight index map could not be inverted");
+
+  for (int which = 0; which < 3; ++which)   // the kernels decode flat target and sum-point indices in 32 bits
+    if (plan->prog[which].n_target > kMaxElems || plan->prog[which].n_free > kMaxElems)
+      return unsupported("more than 2^31-1 sum points per element in one of the passes");
 
   plan->conv_like = recognise_conv(g, plan->conv);
   plan->share_window = !plan->conv_like && recognise_share_window(g, plan->window);

@@ -62,6 +62,16 @@ def test_rejects_invalid_graphs(syno):
     with pytest.raises(syno.SynoError) as e:
         syno.Plan(b.finish([v], []))                 # 2^32 elements
     assert e.value.status == 4
+    for size, fits in ((1 << 18, True), (1 << 20, False)):   # backward-data sums i x r points per element: 2^30, 2^32
+        b = Builder([("i", size), ("k", 2)])
+        r = b.reduce(1 << 12)
+        b.expand(0)
+        if fits:
+            syno.Plan(b.finish([1], [r]))
+        else:
+            with pytest.raises(syno.SynoError) as e:
+                syno.Plan(b.finish([1], [r]))
+            assert e.value.status == 4
 
 
 def test_shapes_match_the_checker(syno, oracle):

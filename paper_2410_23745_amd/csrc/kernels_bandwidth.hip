@@ -32,7 +32,11 @@ struct DwParams {
 // MODE 0: forward (B = weights, out = result).
 // MODE 2: backward-weight partials: B = upstream gradient G (shaped like the forward result); every group
 //         leaves the KH*KW sums of G[h][w] * window over its strip in out[task][KH*KW].
-template <int KH, int KW, int S, int V, int RB, int MODE>
+// Keeps the compiler from sinking a load below this point: everything requested so far is in flight together.
+__device__ __forceinline__ void pin(float& v) { asm volatile("" : "+v"(v)); }
+
+// VEC: rows start 16-byte aligned and hold a whole number of the lanes' vectors (one vector load per row).
+template <int KH, int KW, int S, int V, int RB, int MODE, bool VEC>
 __global__ __launch_bounds__(256) void depthwise_stream(const DwParams p, const float* __restrict__ X,
                                                         const float* __restrict__ Wt, float* __restrict__ out) {
   constexpr int SV = S * V;                      // input columns a lane loads per row
@@ -53,8 +57,11 @@ __global__ __launch_bounds__(256) void depthwise_stream(const DwParams p, const 
   constexpr int HALO = KH - S;                   // input rows a strip shares with the strip above it
 
   // Request every input row of task `task` (one independent load per row: the wave pays the memory
-  // latency once per strip).  Rows a strip shares with the strip above are not loaded when that strip
-  // belongs to the previous group of this wave; they are shuffled over afterwards.
+  // latency once per strip).  Every load is issued unconditionally from an address clamped into the plane and
+  // the value is replaced by zero afterwards where the row or column lies outside, so no branch (and no wait)
+  // separates the loads.  Rows a strip shares with the strip above are not needed when that strip belongs to
+  // the previous group of this wave (they are shuffled over afterwards): their loads are pointed at the first
+  // row the lane does need, a line it fetches anyway.
   auto request = [&](int task, float (&v)[ROWS][SV]) {
     const bool task_ok = task < p.n_tasks;
     const int plane = task_ok ? task / p.strips : 0;
@@ -63,26 +70,37 @@ __global__ __launch_bounds__(256) void depthwise_stream(const DwParams p, const 
     const int r0 = S * strip * RB - p.ph;
     const bool col_ok = task_ok && x0 < p.Wi;
     const bool from_prev = grp > 0 && strip > 0;
+    const int xc = x0 < p.Wi ? x0 : 0;
+#pragma unroll
+    for (int a = 0; a < ROWS; ++a) {
+      const int r = (a < HALO && from_prev) ? r0 + HALO : r0 + a;
+      const float* row = xp + (int64_t)min(max(r, 0), p.Hi - 1) * p.Wi;
+      if constexpr (VEC && SV == 4) {
+        const float4 t = *reinterpret_cast<const float4*>(row + xc);
+        v[a][0] = t.x; v[a][1] = t.y; v[a][2] = t.z; v[a][3] = t.w;
+      } else {
+#pragma unroll
+        for (int e = 0; e < SV; ++e) v[a][e] = row[min(x0 + e, p.Wi - 1)];
+      }
+    }
+#pragma unroll
+    for (int a = 0; a < ROWS; ++a)
+#pragma unroll
+      for (int e = 0; e < SV; ++e) pin(v[a][e]);
 #pragma unroll
     for (int a = 0; a < ROWS; ++a) {
       const int r = r0 + a;
       const bool row_ok = col_ok && r >= 0 && r < p.Hi && !(a < HALO && from_prev);
-      if (p.vec_ok && SV == 4) {
-        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (row_ok) t = *reinterpret_cast<const float4*>(xp + (int64_t)r * p.Wi + x0);
-        v[a][0] = t.x; v[a][1] = t.y; v[a][2] = t.z; v[a][3] = t.w;
-      } else {
 #pragma unroll
-        for (int e = 0; e < SV; ++e) v[a][e] = (row_ok && x0 + e < p.Wi) ? xp[(int64_t)r * p.Wi + x0 + e] : 0.f;
-      }
+      for (int e = 0; e < SV; ++e)
+        if (!(row_ok && (VEC || x0 + e < p.Wi))) v[a][e] = 0.f;
     }
   };
-  auto finish = [&](int task, float (&v)[ROWS][SV]) {
+  auto finish = [&](int task, float (&v)[ROWS][SV], float (&wk)[KH][KW]) {
     const bool task_ok = task < p.n_tasks;
     const int plane = task_ok ? task / p.strips : 0;
     const int strip = task_ok ? task - plane * p.strips : 0;
     const int h0 = strip * RB;
-    const int c = plane % p.C;
     float* op = out + (int64_t)plane * p.Ho * p.Wo;
     const bool from_prev = grp > 0 && strip > 0;
     // shared rows come from the group above (every lane takes part in the shuffles)
@@ -93,11 +111,6 @@ __global__ __launch_bounds__(256) void depthwise_stream(const DwParams p, const 
         const float t = __shfl_up(v[ROWS - HALO + a][e], lpg, 64);
         if (from_prev) v[a][e] = t;
       }
-    float wk[KH][KW];
-#pragma unroll
-    for (int a = 0; a < KH; ++a)
-#pragma unroll
-      for (int b = 0; b < KW; ++b) wk[a][b] = MODE == 0 ? Wt[c * p.ws_c + a * p.ws_kh + b * p.ws_kw] : 0.f;
     // the window's horizontal neighbours come from the adjacent lanes
     float left[ROWS][HL > 0 ? HL : 1], right[ROWS][HR > 0 ? HR : 1];
 #pragma unroll
@@ -146,18 +159,28 @@ __global__ __launch_bounds__(256) void depthwise_stream(const DwParams p, const 
       // sums of G * window over the strip, per tap; Wt is G here, laid out like the forward result
       const float* gp = Wt + (int64_t)plane * p.Ho * p.Wo;
       float gv[RB][V];
+      const bool pair = V == 2 && (p.Wo & 1) == 0;    // (clamped addresses, zeros selected afterwards: see request)
+      const int wc = w0 < p.Wo ? w0 : 0;
 #pragma unroll
       for (int i = 0; i < RB; ++i) {
-        if (V == 2 && (p.Wo & 1) == 0) {
-          float2 t = make_float2(0.f, 0.f);
-          if (task_ok && h0 + i < p.Ho && w0 < p.Wo) t = *reinterpret_cast<const float2*>(gp + (int64_t)(h0 + i) * p.Wo + w0);
+        const float* grow = gp + (int64_t)min(h0 + i, p.Ho - 1) * p.Wo;
+        if (pair) {
+          const float2 t = *reinterpret_cast<const float2*>(grow + wc);
           gv[i][0] = t.x; gv[i][V - 1] = t.y;
         } else {
 #pragma unroll
-          for (int o = 0; o < V; ++o)
-            gv[i][o] = (task_ok && h0 + i < p.Ho && w0 + o < p.Wo) ? gp[(int64_t)(h0 + i) * p.Wo + w0 + o] : 0.f;
+          for (int o = 0; o < V; ++o) gv[i][o] = grow[min(w0 + o, p.Wo - 1)];
         }
       }
+#pragma unroll
+      for (int i = 0; i < RB; ++i)
+#pragma unroll
+        for (int o = 0; o < V; ++o) pin(gv[i][o]);
+#pragma unroll
+      for (int i = 0; i < RB; ++i)
+#pragma unroll
+        for (int o = 0; o < V; ++o)
+          if (!(task_ok && h0 + i < p.Ho && w0 + o < p.Wo)) gv[i][o] = 0.f;
 #pragma unroll
       for (int i = 0; i < RB; ++i)
 #pragma unroll
@@ -181,8 +204,15 @@ __global__ __launch_bounds__(256) void depthwise_stream(const DwParams p, const 
   // one strip per group; every lane of the wave runs both phases so that the shuffles stay uniform
   float v[ROWS][SV];
   const int task = wave * gpw + grp;
+  // the window's weights are requested ahead of the rows, so that they arrive within the same round trip
+  float wk[KH][KW];
+  const int c = (task < p.n_tasks ? task / p.strips : 0) % p.C;
+#pragma unroll
+  for (int a = 0; a < KH; ++a)
+#pragma unroll
+    for (int b = 0; b < KW; ++b) wk[a][b] = MODE == 0 ? Wt[c * p.ws_c + a * p.ws_kh + b * p.ws_kw] : 0.f;
   request(task, v);
-  finish(task, v);
+  finish(task, v, wk);
   (void)WIN;
 }
 
@@ -206,23 +236,28 @@ __global__ __launch_bounds__(256) void depthwise_s2k3_bwd_data(const DwParams p,
   const int h0 = strip * RB, c = plane % p.C;
   const int w0 = 2 * lig;                          // first of the lane's two columns of G
   const float* gp = G + (int64_t)plane * p.Ho * p.Wo;
+  float w[3][3];                                   // requested ahead of G: one round trip for both
+#pragma unroll
+  for (int a = 0; a < 3; ++a)
+#pragma unroll
+    for (int b = 0; b < 3; ++b) w[a][b] = Wt[c * p.ws_c + a * p.ws_kh + b * p.ws_kw];
   float g[RB + 1][2], gn[RB + 1];
+  const int wc = w0 < p.Wo ? w0 : 0;               // (Wo is even here) clamped addresses, zeros selected afterwards
 #pragma unroll
   for (int r = 0; r <= RB; ++r) {
-    float2 t = make_float2(0.f, 0.f);
-    if (task_ok && h0 + r < p.Ho && w0 < p.Wo) t = *reinterpret_cast<const float2*>(gp + (int64_t)(h0 + r) * p.Wo + w0);
+    const float2 t = *reinterpret_cast<const float2*>(gp + (int64_t)min(h0 + r, p.Ho - 1) * p.Wo + wc);
     g[r][0] = t.x; g[r][1] = t.y;
   }
+#pragma unroll
+  for (int r = 0; r <= RB; ++r) { pin(g[r][0]); pin(g[r][1]); }
+#pragma unroll
+  for (int r = 0; r <= RB; ++r)
+    if (!(task_ok && h0 + r < p.Ho && w0 < p.Wo)) g[r][0] = g[r][1] = 0.f;
 #pragma unroll
   for (int r = 0; r <= RB; ++r) {
     const float t = __shfl_down(g[r][0], 1, 64);
     gn[r] = (lig == lpg - 1 || w0 + 2 >= p.Wo) ? 0.f : t;
   }
-  float w[3][3];
-#pragma unroll
-  for (int a = 0; a < 3; ++a)
-#pragma unroll
-    for (int b = 0; b < 3; ++b) w[a][b] = Wt[c * p.ws_c + a * p.ws_kh + b * p.ws_kw];
   float* xp = dX + (int64_t)plane * p.Hi * p.Wi;
 #pragma unroll
   for (int r = 0; r < RB; ++r) {
@@ -281,7 +316,10 @@ void launch_dw(const DwParams& p, const float* X, const float* W, float* out, hi
   const int waves = (p.n_tasks + groups_per_wave - 1) / groups_per_wave;
   const int wpb = 4;
   const int blocks = (waves + wpb - 1) / wpb;
-  hipLaunchKernelGGL((depthwise_stream<KH, KW, S, V, kStripRows, MODE>), dim3(blocks), dim3(64 * wpb), 0, s, p, X, W, out);
+  if (p.vec_ok)
+    hipLaunchKernelGGL((depthwise_stream<KH, KW, S, V, kStripRows, MODE, true>), dim3(blocks), dim3(64 * wpb), 0, s, p, X, W, out);
+  else
+    hipLaunchKernelGGL((depthwise_stream<KH, KW, S, V, kStripRows, MODE, false>), dim3(blocks), dim3(64 * wpb), 0, s, p, X, W, out);
 }
 
 }  // namespace

@@ -96,6 +96,8 @@ def small_cases():
     c["depthwise_f32_odd"] = lambda: wl.make_depthwise(2, 7, 18, seed=3, with_grad=True)
     c["depthwise_f32_even"] = lambda: wl.make_depthwise(2, 5, 28, seed=4, with_grad=True)      # stream kernels, all passes
     c["depthwise_f32_even_ragged"] = lambda: wl.make_depthwise(3, 4, 20, seed=5, with_grad=True)  # last strip 3 rows
+    c["depthwise_f32_stride1"] = lambda: wl.make_depthwise(2, 6, 12, seed=6, S=1, with_grad=True)       # forward streams
+    c["depthwise_f32_stride1_odd"] = lambda: wl.make_depthwise(2, 3, 10, seed=7, S=1, with_grad=True)   # rows not vector-aligned
     return c
 
 

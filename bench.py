@@ -265,33 +265,39 @@ def main() -> int:
                                "launch": " | ".join(p.describe(k) for p in chain.stages for k in which),
                                "us": med * 1e3, "TFLOP/s": flops / (med * 1e-3) / 1e12,
                                "GB/s": nbytes / (med * 1e-3) / 1e9, "rotating_sets": 4})
-        # pure views (no Reduce) run on the index-program kernel: a cyclic shift with a per-channel scale and a
+        # pure views (no Reduce) on the view kernel: a cyclic shift with a per-channel scale and a
         # space-to-depth rearrangement, both 102.8 MB in and out
         for name, dv in (("shift_scale_C128_56x56_N64_f32", wl.shifted_scale(64, 128, 56, 56)),
                          ("pixel_unshuffle_C128_28x28_r2_N64_f32", wl.pixel_unshuffle(64, 128, 28, 28, 2))):
             pv = syno.Plan(dv)
             sets_v = [(torch.randn(pv.x_shape, device=dev), torch.randn(pv.w_shape if pv.w_shape else (1,), device=dev),
                        torch.empty(pv.out_shape, device=dev)) for _ in range(4)]
-            it = [0]
-
-            def run_view():
-                a, b, o = sets_v[it[0] % 4]
-                it[0] += 1
-                pv.forward(a, b, out=o)
-
-            run_view()
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(12):
-                run_view()
-            e1.record()
-            torch.cuda.synchronize()
-            us_v = e0.elapsed_time(e1) / 12 * 1e3
             nb = 4 * (int(np.prod(pv.x_shape)) + int(np.prod(pv.out_shape)))
-            detail.append({"case": name + "_fwd", "kernel": pv.kernel(0), "launch": pv.describe(0), "us": us_v,
-                           "GB/s": nb / (us_v * 1e-6) / 1e9, "bound": "hbm", "roofline_frac": nb / (us_v * 1e-6) / 1e9 / HBM_PEAK_GBS,
-                           "rotating_sets": 4})
+            # forward reads X through the view and writes the result in runs; backward-data (both views are
+            # one-to-one) reads the gradient in runs and scatters dX through the same tables
+            for which, tag in ((0, "_fwd"), (1, "_bwd_data")):
+                it = [0]
+
+                def run_view():
+                    a, b, o = sets_v[it[0] % 4]
+                    it[0] += 1
+                    if which == 0:
+                        pv.forward(a, b, out=o)
+                    else:
+                        pv.backward_data(o, b, dX=a)
+
+                run_view()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(12):
+                    run_view()
+                e1.record()
+                torch.cuda.synchronize()
+                us_v = e0.elapsed_time(e1) / 12 * 1e3
+                detail.append({"case": name + tag, "kernel": pv.kernel(which), "launch": pv.describe(which), "us": us_v,
+                               "GB/s": nb / (us_v * 1e-6) / 1e9, "bound": "hbm",
+                               "roofline_frac": nb / (us_v * 1e-6) / 1e9 / HBM_PEAK_GBS, "rotating_sets": 4})
         # the materialised-reduction pass on a convolution of 2x2 block sums (one loop nest with five Reduces):
         # the graph as written runs on the index-program kernel, the chain the library cuts it into on two small
         # reduction stages and the contraction kernel

@@ -1,8 +1,10 @@
 // Bandwidth-bound family, third member: graphs without Unfold and with at most a few sum points per output -
 // pure views (Shift, Split, Merge, Stride, Expand and Share in any combination) and small gather-and-add
-// operators (block sums, pools) - forward pass:
+// operators (block sums, pools) - forward pass,
 //
 //   out[o] = sum_r X[offX(o,r)] * W[offW(o,r)]
+//
+// and, for one-to-one views, backward-data as the scatter dX[offX(o)] = G[o] * W[offW(o)].
 //
 // When every tensor axis is an affine function of digits of the iterators - wrapped (Shift) only over digits of
 // one iterator - both offsets are sums of one small table per iterator (plan.h, ViewStream); the tables of the
@@ -64,7 +66,30 @@ __device__ __forceinline__ void store_run(void* base, int64_t off, const float* 
   }
 }
 
-template <int V, bool IBF, bool OBF>
+// V adjacent elements starting at a multiple of V (one vector load when V = 4)
+template <int V, bool BF>
+__device__ __forceinline__ void load_run(const void* base, int64_t off, float* v) {
+  if constexpr (V == 4 && BF) {
+    const uint2 t = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(base) + off);
+    v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u);
+    v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
+  } else if constexpr (V == 4) {
+    const float4 t = *reinterpret_cast<const float4*>(static_cast<const float*>(base) + off);
+    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+  } else {
+    v[0] = load_one<BF>(base, off);
+  }
+}
+
+template <bool BF>
+__device__ __forceinline__ void store_one(void* base, int64_t off, float v) {
+  if constexpr (BF) static_cast<uint16_t*>(base)[off] = (uint16_t)pack_bf16x2(v, 0.f);
+  else static_cast<float*>(base)[off] = v;
+}
+
+// SCATTER: backward-data of a one-to-one view.  X is then the upstream gradient, shaped like the forward result and
+// read in runs, and `out` is dX: dX[offX(o)] = G[o] * W[offW(o)], every element written exactly once.
+template <int V, bool IBF, bool OBF, bool SCATTER>
 __global__ __launch_bounds__(kThreads) void view_stream(const ViewParams p, const void* __restrict__ X,
                                                         const void* __restrict__ Wt, void* __restrict__ out) {
   extern __shared__ int tab[];     // [2][tab_total]: X offsets, then W offsets
@@ -128,6 +153,14 @@ __global__ __launch_bounds__(kThreads) void view_stream(const ViewParams p, cons
     float r[V];
     const int* tx = tx_last + w0;
     const int* tw = tx + p.tab_total;
+    if constexpr (SCATTER) {
+      load_run<V, IBF>(X, run * V, r);
+#pragma unroll
+      for (int v = 0; v < V; ++v) r[v] *= load_one<IBF>(Wt, bw + tw[v]);
+#pragma unroll
+      for (int v = 0; v < V; ++v) store_one<OBF>(out, bx + tx[v], r[v]);
+      continue;
+    }
     if (p.n_free == 1) {
 #pragma unroll
       for (int v = 0; v < V; ++v) r[v] = load_one<IBF>(X, bx + tx[v]) * load_one<IBF>(Wt, bw + tw[v]);
@@ -147,12 +180,21 @@ __global__ __launch_bounds__(kThreads) void view_stream(const ViewParams p, cons
   }
 }
 
-template <bool IBF, bool OBF>
+template <bool IBF, bool OBF, bool SCATTER>
 void launch_typed(const ViewParams& p, int V, size_t lds, const void* X, const void* W, void* out, hipStream_t s) {
   const int64_t blocks = (p.n_runs + kThreads - 1) / kThreads;
   const dim3 grid((unsigned)(blocks < 256 * 8 ? blocks : 256 * 8));
-  if (V == 4) hipLaunchKernelGGL((view_stream<4, IBF, OBF>), grid, dim3(kThreads), lds, s, p, X, W, out);
-  else hipLaunchKernelGGL((view_stream<1, IBF, OBF>), grid, dim3(kThreads), lds, s, p, X, W, out);
+  if (V == 4) hipLaunchKernelGGL((view_stream<4, IBF, OBF, SCATTER>), grid, dim3(kThreads), lds, s, p, X, W, out);
+  else hipLaunchKernelGGL((view_stream<1, IBF, OBF, SCATTER>), grid, dim3(kThreads), lds, s, p, X, W, out);
+}
+
+template <bool SCATTER>
+void launch_dtype(const syno_plan* plan, const ViewParams& p, int V, size_t lds, const void* A, const void* B, void* out,
+                  hipStream_t s) {
+  const bool ibf = plan->in_dtype == SYNO_BF16, obf = plan->out_dtype == SYNO_BF16;
+  if (ibf && obf) launch_typed<true, true, SCATTER>(p, V, lds, A, B, out, s);
+  else if (ibf) launch_typed<true, false, SCATTER>(p, V, lds, A, B, out, s);
+  else launch_typed<false, false, SCATTER>(p, V, lds, A, B, out, s);
 }
 
 int run_width(const syno_plan* plan) {
@@ -183,22 +225,23 @@ bool fill(const syno_plan* plan, ViewParams& p) {
 
 }  // namespace
 
+// Forward of every separable gather; backward-data where the view is one-to-one (a scatter of the same tables).
 bool view_supports(const syno_plan* plan, int which) {
-  if (which != SYNO_FWD || !plan->pure_view) return false;
+  if (!plan->pure_view) return false;
+  if (which == SYNO_BWD_WEIGHT || (which == SYNO_BWD_DATA && !plan->view.one_to_one)) return false;
   if (plan->in_dtype == SYNO_F32 && plan->out_dtype != SYNO_F32) return false;
   ViewParams p;
   return fill(plan, p);
 }
 
-syno_status launch_view(const syno_plan* plan, const void* A, const void* B, void* out, hipStream_t stream) {
+// forward: A = X, B = W, out = result; backward-data: A = G, B = W, out = dX
+syno_status launch_view(const syno_plan* plan, int which, const void* A, const void* B, void* out, hipStream_t stream) {
   ViewParams p;
-  if (!fill(plan, p)) return SYNO_ERR_UNSUPPORTED;
+  if (!view_supports(plan, which) || !fill(plan, p)) return SYNO_ERR_UNSUPPORTED;
   const int V = run_width(plan);
   const size_t lds = (size_t)p.tab_total * 8;
-  const bool ibf = plan->in_dtype == SYNO_BF16, obf = plan->out_dtype == SYNO_BF16;
-  if (ibf && obf) launch_typed<true, true>(p, V, lds, A, B, out, stream);
-  else if (ibf) launch_typed<true, false>(p, V, lds, A, B, out, stream);
-  else launch_typed<false, false>(p, V, lds, A, B, out, stream);
+  if (which == SYNO_FWD) launch_dtype<false>(plan, p, V, lds, A, B, out, stream);
+  else launch_dtype<true>(plan, p, V, lds, A, B, out, stream);
   return hipGetLastError() == hipSuccess ? SYNO_OK : SYNO_ERR_HIP;
 }
 

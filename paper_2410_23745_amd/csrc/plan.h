@@ -100,6 +100,7 @@ struct ViewStream {
   int32_t size[2 * kMaxAxes];
   ViewTerm term[kMaxViewTerms];
   ViewGroup group[kMaxViewGroups];
+  int32_t one_to_one;            // no Reduce and only Split, Merge, Shift and Share: every X element is read by exactly one output
 };
 
 enum KernelId : int32_t {

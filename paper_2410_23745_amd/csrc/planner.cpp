@@ -793,7 +793,17 @@ bool recognise_view(const Graph& g, ViewStream& vs) {
     }
     return true;
   };
-  return add_tensor(g.in_coords, 0) && add_tensor(g.w_coords, 1);
+  if (!add_tensor(g.in_coords, 0) || !add_tensor(g.w_coords, 1)) return false;
+  // Split, Merge and Shift are bijections of coordinates and Share only copies one to the weight: with no other
+  // primitive and as many X elements as outputs, the map from outputs to X elements is one-to-one and onto, so
+  // backward-data is a scatter that writes every element of dX exactly once.
+  int64_t x_elems = 1, out_elems = 1;
+  for (int c : g.in_coords) x_elems *= g.D(c);
+  for (int i = 0; i < g.n_out; ++i) out_elems *= g.D(i);
+  vs.one_to_one = vs.n_red == 0 && x_elems == out_elems;
+  for (const syno_prim& p : g.prims)
+    if (p.kind != SYNO_SPLIT && p.kind != SYNO_MERGE && p.kind != SYNO_SHIFT && p.kind != SYNO_SHARE) vs.one_to_one = 0;
+  return true;
 }
 
 // The width to fold the N contiguous output columns of a matrix product into image rows of: the 1x1

@@ -243,8 +243,22 @@ def test_materialised_reduction_pass_cuts_where_it_saves_work(syno):
 def test_reduce_free_graphs_go_to_the_view_kernel_forwards(syno):
     for d in (wl.shifted_scale(2, 8, 6, 6), wl.pixel_unshuffle(2, 4, 3, 4, 2)):
         p = syno.Plan(d)
-        assert p.kernel(0) == "bandwidth_view" and p.kernel(1) == p.kernel(2) == "generic_index_program"
-        assert p.workspace_bytes(0) == 0
+        # one-to-one views: backward-data is the scatter of the same tables; backward-weight sums, so it is not a view
+        assert p.kernel(0) == p.kernel(1) == "bandwidth_view" and p.kernel(2) == "generic_index_program"
+        assert p.workspace_bytes(0) == p.workspace_bytes(1) == 0
+    # not one-to-one: an Expand repeats X, a Stride leaves elements of X unread (their gradient is zero)
+    b = Builder([("i", 6), ("j", 4)])
+    b.expand(1)
+    p = syno.Plan(b.finish([0], []))
+    assert p.kernel(0) == "bandwidth_view" and p.kernel(1) == "generic_index_program"
+    b = Builder([("i", 6)])
+    p = syno.Plan(b.finish([b.stride(0, 2)], []))
+    assert p.kernel(0) == "bandwidth_view" and p.kernel(1) == "generic_index_program"
+    # an Expand and a Stride whose sizes cancel: as many X elements as outputs, still not one-to-one
+    b = Builder([("i", 6), ("j", 2)])
+    b.expand(1)
+    p = syno.Plan(b.finish([b.stride(0, 2)], []))
+    assert p.x_shape == (12,) and p.kernel(1) == "generic_index_program"
     # a Shift whose amount depends on another output axis is not separable: index program
     b = Builder([("g", 4), ("h", 6)])
     gx, gw = b.share(0)

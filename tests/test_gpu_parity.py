@@ -397,16 +397,29 @@ def test_pure_views_small(syno, oracle, name, dt):
     w = wl._finish(d, xs, ws if ws else (1,), os_, st.normal(xs), st.uniform_pm(2.0, ws if ws else (1,)), st.normal(os_), 1)
     names = run_all(syno, oracle, w, 0)
     assert names[0] == "bandwidth_view"
+    # one-to-one views scatter their backward-data through the same tables; the others sum or leave gaps
+    one_to_one = name in ("shift_scale_v4", "shift_scale_v1", "pixel_unshuffle", "pixel_unshuffle_r3", "pixel_shuffle",
+                          "shift_of_digit")
+    assert names[1] == ("bandwidth_view" if one_to_one else "generic_index_program")
+    if one_to_one:   # every element of dX is written: nothing of a pre-filled buffer survives
+        plan = syno.Plan(d)
+        G, W = to_dev(w.G, w.G_bits), to_dev(w.W, w.W_bits)
+        dX = plan.backward_data(G, W)
+        dX2 = torch.full_like(dX, 7.0)
+        plan.backward_data(G, W, dX=dX2)
+        torch.cuda.synchronize()
+        assert torch.equal(dX, dX2)
 
 
 def test_pure_view_full_size(syno, oracle):
-    """The shapes the benchmark's detail times (102.8 MB in and out), forward, in full against the checker."""
+    """The shapes the benchmark's detail times (102.8 MB in and out), forward and backward-data, in full against the
+    checker."""
     for d in (wl.shifted_scale(64, 128, 56, 56), wl.pixel_unshuffle(64, 128, 28, 28, 2)):
         xs, ws, _ = oracle.describe(d)
         st = wl.Stream(62)
         w = wl._finish(d, xs, ws if ws else (1,), oracle.out_shape(d), st.normal(xs), st.uniform_pm(2.0, ws if ws else (1,)),
-                       None, 1)
-        assert run_all(syno, oracle, w, 0, directions=(0,), full=True)[0] == "bandwidth_view"
+                       st.normal(oracle.out_shape(d)), 1)
+        assert run_all(syno, oracle, w, 0, directions=(0, 1), full=True)[:2] == ["bandwidth_view"] * 2
 
 
 # ------------------------------------------------------------------------------------------------

@@ -7,6 +7,7 @@
 // once j is enumerated (with a range test), Stride v = S*i is solved when S divides v, and
 // coordinates nothing determines are enumerated.
 #include <algorithm>
+#include <array>
 #include <cstdlib>
 #include <cstring>
 #include <map>
@@ -794,15 +795,38 @@ bool recognise_view(const Graph& g, ViewStream& vs) {
     return true;
   };
   if (!add_tensor(g.in_coords, 0) || !add_tensor(g.w_coords, 1)) return false;
-  // Split, Merge and Shift are bijections of coordinates and Share only copies one to the weight: with no other
-  // primitive and as many X elements as outputs, the map from outputs to X elements is one-to-one and onto, so
-  // backward-data is a scatter that writes every element of dX exactly once.
+  // Backward-data as a scatter needs the map from outputs to X elements to be one-to-one and onto.  Split, Merge
+  // and Shift are bijections of coordinates and Share copies one; what is left to rule out is a copy that comes
+  // back into X (a diagonal) or an iterator that only reaches the weight.  Checked on the record itself: every X
+  // axis must enumerate its own range in mixed radix (its terms, by rising coefficient: 1, s1, s1*s2, ... with
+  // the sizes' product equal to the axis; a wrap then only rotates that range), no digit may feed two X axes, and
+  // X must have as many elements as there are outputs, so that no digit is left out.
   int64_t x_elems = 1, out_elems = 1;
   for (int c : g.in_coords) x_elems *= g.D(c);
   for (int i = 0; i < g.n_out; ++i) out_elems *= g.D(i);
-  vs.one_to_one = vs.n_red == 0 && x_elems == out_elems;
+  bool one = vs.n_red == 0 && x_elems == out_elems;
   for (const syno_prim& p : g.prims)
-    if (p.kind != SYNO_SPLIT && p.kind != SYNO_MERGE && p.kind != SYNO_SHIFT && p.kind != SYNO_SHARE) vs.one_to_one = 0;
+    if (p.kind != SYNO_SPLIT && p.kind != SYNO_MERGE && p.kind != SYNO_SHIFT && p.kind != SYNO_SHARE) one = false;
+  std::vector<std::array<int32_t, 3>> seen;      // digits (axis, div, size) already feeding an X axis
+  for (int gi = 0; one && gi < (int)g.in_coords.size(); ++gi) {
+    std::vector<std::pair<int64_t, int64_t>> digits;   // (coefficient, size)
+    for (int t = 0; t < vs.n_terms; ++t) {
+      const ViewTerm& tm = vs.term[t];
+      if (tm.group != gi) continue;
+      const std::array<int32_t, 3> key = {tm.axis, tm.div, tm.size};
+      if (std::find(seen.begin(), seen.end(), key) != seen.end()) one = false;
+      seen.push_back(key);
+      digits.emplace_back(tm.coef, tm.size);
+    }
+    std::sort(digits.begin(), digits.end());
+    int64_t expect = 1;
+    for (auto& dg : digits) {
+      if (dg.first != expect) one = false;
+      expect *= dg.second;
+    }
+    if (expect != g.D(g.in_coords[gi])) one = false;
+  }
+  vs.one_to_one = one ? 1 : 0;
   return true;
 }
 

@@ -95,7 +95,8 @@ enum { SYNO_FWD = 0, SYNO_BWD_DATA = 1, SYNO_BWD_WEIGHT = 2 };
  * SYNO_ERR_INVALID_DESC: unknown / redefined / twice- or never-consumed coordinate, non-positive
  * size, Merge factor not dividing its domain, a Reduce iterator fed straight into Expand.
  * SYNO_ERR_UNSUPPORTED: a tensor with more than 2^31-1 elements, more than 8 axes or 24 distinct
- * coordinates, or a graph whose gradient index maps the planner cannot invert. */
+ * coordinates, a pass that would sum more than 2^31-1 points per element, or a graph whose gradient index
+ * maps the planner cannot invert (e.g. both copies of a Shared coordinate reaching X: a diagonal). */
 syno_status syno_plan_create(const syno_desc* desc, syno_plan** plan);
 syno_status syno_plan_destroy(syno_plan* plan);
 

@@ -203,6 +203,7 @@ bool step_prim(Builder& b, const syno_prim& p, bool* progress) {
         b.emit(OP_MULADD, S(i), S(j), S(v), -1, g.D(j), 0, 0);
         b.set(v);
       } else if (b.K(v) && !b.K(i) && !b.K(j)) {
+        if (S(i) == S(j)) { b.failed = true; return false; }   // two copies of one Shared coordinate: determined twice
         b.emit(OP_DIVMOD, S(v), -1, S(i), S(j), g.D(j), (int32_t)division_magic(g.D(j)), 0);
         b.set(i); b.set(j);
       } else {

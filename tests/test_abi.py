@@ -259,13 +259,15 @@ def test_reduce_free_graphs_go_to_the_view_kernel_forwards(syno):
     b.expand(1)
     p = syno.Plan(b.finish([b.stride(0, 2)], []))
     assert p.x_shape == (12,) and p.kernel(1) == "generic_index_program"
-    # a Shared iterator whose two copies both reach X (a diagonal, here folded into one axis: X[3i+i]) next to an
-    # iterator that only reaches the weight: as many X elements as outputs and only bijective primitives, yet the
-    # off-diagonal elements are never read - not one-to-one
-    b = Builder([("i", 3), ("j", 3)])
-    i1, i2 = b.share(0)
-    p = syno.Plan(b.finish([b.split(i1, i2)], [1]))
-    assert p.x_shape == (9,) and p.kernel(0) == "bandwidth_view" and p.kernel(1) == "generic_index_program"
+    # a Shared iterator whose two copies both reach X (a diagonal: X[i,i], or folded into one axis, X[3i+i]) next to
+    # an iterator that only reaches the weight would also have as many X elements as outputs; such graphs are
+    # refused as a whole, because backward-data would have to fix one coordinate from two places
+    for fold in (False, True):
+        b = Builder([("i", 3), ("j", 3)])
+        i1, i2 = b.share(0)
+        with pytest.raises(syno.SynoError) as e:
+            syno.Plan(b.finish([b.split(i1, i2)] if fold else [i1, i2], [1]))
+        assert e.value.status == 4
     # a Shift whose amount depends on another output axis is not separable: index program
     b = Builder([("g", 4), ("h", 6)])
     gx, gw = b.share(0)

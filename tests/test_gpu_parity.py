@@ -374,14 +374,7 @@ def view_cases():
         sh, sw = b.reduce(2), b.reduce(3)
         return b.finish([0, cx, b.split(2, sh), b.split(3, sw)], [cw], i, o)
 
-    def folded_diagonal(i, o):
-        # out[i,j] = X[8*i + i] * Wt[j]: both copies of a Shared iterator reach X, so most of X is never read
-        b = Builder([("i", 8), ("j", 4)])
-        i1, i2 = b.share(0)
-        return b.finish([b.split(i1, i2)], [1], i, o)
-
     return {
-        "folded_diagonal": folded_diagonal,
         "block_sums": block_sums,
         "small_matmul": lambda i, o: wl.matmul(9, 3, 7, i, o),     # 3 columns: not folded into a convolution
         "shift_scale_v4": lambda i, o: wl.shifted_scale(3, 5, 7, 12, i, o),

@@ -27,6 +27,7 @@ struct ViewParams {
   uint32_t magic[kMaxAxes];      // division_magic(size[i]) of the output axes
   int32_t tab_total;             // entries of all iterator tables
   int32_t n_free, free_off;      // sum points per output; start of the folded table over them (X; W at +tab_total)
+  int32_t scratch_off;           // start (entries, a multiple of 4) of the waves' exchange areas behind the two tables
   int64_t n_runs;                // out elements / V
 };
 
@@ -92,7 +93,7 @@ __device__ __forceinline__ void store_one(void* base, int64_t off, float v) {
 template <int V, bool IBF, bool OBF, bool SCATTER>
 __global__ __launch_bounds__(kThreads) void view_stream(const ViewParams p, const void* __restrict__ X,
                                                         const void* __restrict__ Wt, void* __restrict__ out) {
-  extern __shared__ int tab[];     // [2][tab_total]: X offsets, then W offsets
+  extern __shared__ __align__(16) int tab[];   // [2][tab_total]: X offsets, then W offsets; then the waves' exchange areas
   const ViewStream& vs = p.vs;
   // table entry (axis i, index o): the contribution of output axis i to each offset
   const int n_iter = vs.n_axes + vs.n_red;
@@ -135,7 +136,72 @@ __global__ __launch_bounds__(kThreads) void view_stream(const ViewParams p, cons
   const int last = vs.n_axes - 1;
   const uint32_t runs_per_row = (uint32_t)vs.size[last] / V;
   const int* const tx_last = tab + p.tab_off[last];
-  // (the grid is capped so that the table build above is paid a few times per CU, not once per 256 runs)
+  if constexpr (V == 4) {
+    if (p.n_free == 1) {
+      // One product per element.  A lane decodes one run of 4 elements, but a wave touching memory run by run
+      // would spread every load over 1 KB of the view's source.  So the wave exchanges what its lanes computed
+      // through a 256-entry area in LDS and then works element by element: pass v takes the wave's elements
+      // 64v .. 64v+63, adjacent lanes on adjacent elements, for the loads through the view (forward), the stores
+      // through it (scatter) and the other side alike.  Every lane of the wave goes through every pass (the loop
+      // is uniform per wave; lanes past the end decode the last run again and only their stores are masked).
+      const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+      int* const ex = tab + p.scratch_off + wave * (3 * 256);     // X offsets | W offsets or values | (scatter) values
+      int* const ew = ex + 256;
+      const int64_t n_elems = p.n_runs * 4;
+      for (int64_t run0 = (int64_t)blockIdx.x * kThreads + wave * 64; run0 < p.n_runs; run0 += (int64_t)gridDim.x * kThreads) {
+        const int64_t run = run0 + lane < p.n_runs ? run0 + lane : p.n_runs - 1;
+        uint32_t rest = (uint32_t)run;
+        const uint32_t row = div_magic(rest, runs_per_row, p.magic[last]);
+        const int w0 = (int)(rest - row * runs_per_row) * 4;
+        rest = row;
+        int bx = 0, bw = 0;
+        for (int i = last - 1; i >= 0; --i) {
+          const uint32_t sz = (uint32_t)vs.size[i];
+          const uint32_t q = div_magic(rest, sz, p.magic[i]);
+          const int o = (int)(rest - q * sz);
+          rest = q;
+          bx += tab[p.tab_off[i] + o];
+          bw += tab[p.tab_total + p.tab_off[i] + o];
+        }
+        bx += tab[p.free_off];                      // the single sum point (Reduce iterators of size 1, if any)
+        bw += tab[p.tab_total + p.free_off];
+        const int* tx = tx_last + w0;
+        const int* tw = tx + p.tab_total;
+        *reinterpret_cast<int4*>(ex + 4 * lane) = make_int4(bx + tx[0], bx + tx[1], bx + tx[2], bx + tx[3]);
+        if constexpr (SCATTER) {
+          float g[4];
+          load_run<4, IBF>(X, run * 4, g);
+#pragma unroll
+          for (int v = 0; v < 4; ++v) g[v] *= load_one<IBF>(Wt, bw + tw[v]);
+          *reinterpret_cast<float4*>(ew + 4 * lane) = make_float4(g[0], g[1], g[2], g[3]);
+        } else {
+          *reinterpret_cast<int4*>(ew + 4 * lane) = make_int4(bw + tw[0], bw + tw[1], bw + tw[2], bw + tw[3]);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int64_t e0 = run0 * 4 + lane;
+        if constexpr (SCATTER) {
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int off = ex[64 * v + lane];
+            const float val = __int_as_float(ew[64 * v + lane]);
+            if (e0 + 64 * v < n_elems) store_one<OBF>(out, off, val);
+          }
+        } else {
+          float val[4];
+#pragma unroll
+          for (int v = 0; v < 4; ++v) val[v] = load_one<IBF>(X, ex[64 * v + lane]) * load_one<IBF>(Wt, ew[64 * v + lane]);
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            if (e0 + 64 * v < n_elems) store_one<OBF>(out, e0 + 64 * v, val[v]);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+      }
+      return;
+    }
+  }
   for (int64_t run = (int64_t)blockIdx.x * kThreads + threadIdx.x; run < p.n_runs; run += (int64_t)gridDim.x * kThreads) {
     uint32_t rest = (uint32_t)run;
     const uint32_t row = div_magic(rest, runs_per_row, p.magic[last]);
@@ -162,6 +228,8 @@ __global__ __launch_bounds__(kThreads) void view_stream(const ViewParams p, cons
       continue;
     }
     if (p.n_free == 1) {
+      bx += tab[p.free_off];                        // the single sum point (Reduce iterators of size 1, if any)
+      bw += tab[p.tab_total + p.free_off];
 #pragma unroll
       for (int v = 0; v < V; ++v) r[v] = load_one<IBF>(X, bx + tx[v]) * load_one<IBF>(Wt, bw + tw[v]);
     } else {
@@ -220,6 +288,7 @@ bool fill(const syno_plan* plan, ViewParams& p) {
   total += p.n_free;
   p.tab_total = total;
   p.n_runs = plan->out_elems / V;
+  p.scratch_off = (2 * total + 3) & ~3;
   return total > 0 && (size_t)total * 8 <= 48 * 1024 && p.n_runs < (int64_t(1) << 31);
 }
 
@@ -239,7 +308,8 @@ syno_status launch_view(const syno_plan* plan, int which, const void* A, const v
   ViewParams p;
   if (!view_supports(plan, which) || !fill(plan, p)) return SYNO_ERR_UNSUPPORTED;
   const int V = run_width(plan);
-  const size_t lds = (size_t)p.tab_total * 8;
+  // the two tables, then (runs of 4) three 256-entry exchange areas for each of the 4 waves
+  const size_t lds = V == 4 ? (size_t)p.scratch_off * 4 + (kThreads / 64) * 3 * 256 * 4 : (size_t)p.tab_total * 8;
   if (which == SYNO_FWD) launch_dtype<false>(plan, p, V, lds, A, B, out, stream);
   else launch_dtype<true>(plan, p, V, lds, A, B, out, stream);
   return hipGetLastError() == hipSuccess ? SYNO_OK : SYNO_ERR_HIP;

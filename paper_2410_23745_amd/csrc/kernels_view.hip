@@ -14,6 +14,8 @@
 // axis is a table walk, the result leaves as one vector store.  The loads follow whatever order the view imposes.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+
 #include "plan.h"
 
 namespace syno {
@@ -251,7 +253,13 @@ __global__ __launch_bounds__(kThreads) void view_stream(const ViewParams p, cons
 template <bool IBF, bool OBF, bool SCATTER>
 void launch_typed(const ViewParams& p, int V, size_t lds, const void* X, const void* W, void* out, hipStream_t s) {
   const int64_t blocks = (p.n_runs + kThreads - 1) / kThreads;
-  const dim3 grid((unsigned)(blocks < 256 * 8 ? blocks : 256 * 8));
+  // SYNO_VIEW_WORKGROUPS overrides the cap on the grid (tuning aid)
+  static const int64_t cap = [] {
+    const char* e = getenv("SYNO_VIEW_WORKGROUPS");
+    const int64_t v = e ? atoll(e) : 0;
+    return v > 0 ? v : int64_t(256 * 8);
+  }();
+  const dim3 grid((unsigned)(blocks < cap ? blocks : cap));
   if (V == 4) hipLaunchKernelGGL((view_stream<4, IBF, OBF, SCATTER>), grid, dim3(kThreads), lds, s, p, X, W, out);
   else hipLaunchKernelGGL((view_stream<1, IBF, OBF, SCATTER>), grid, dim3(kThreads), lds, s, p, X, W, out);
 }

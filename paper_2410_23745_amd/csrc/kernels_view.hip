@@ -150,56 +150,75 @@ __global__ __launch_bounds__(kThreads) void view_stream(const ViewParams p, cons
       int* const ex = tab + p.scratch_off + wave * (3 * 256);     // X offsets | W offsets or values | (scatter) values
       int* const ew = ex + 256;
       const int64_t n_elems = p.n_runs * 4;
-      for (int64_t run0 = (int64_t)blockIdx.x * kThreads + wave * 64; run0 < p.n_runs; run0 += (int64_t)gridDim.x * kThreads) {
-        const int64_t run = run0 + lane < p.n_runs ? run0 + lane : p.n_runs - 1;
-        uint32_t rest = (uint32_t)run;
-        const uint32_t row = div_magic(rest, runs_per_row, p.magic[last]);
-        const int w0 = (int)(rest - row * runs_per_row) * 4;
-        rest = row;
-        int bx = 0, bw = 0;
-        for (int i = last - 1; i >= 0; --i) {
-          const uint32_t sz = (uint32_t)vs.size[i];
-          const uint32_t q = div_magic(rest, sz, p.magic[i]);
-          const int o = (int)(rest - q * sz);
-          rest = q;
-          bx += tab[p.tab_off[i] + o];
-          bw += tab[p.tab_total + p.tab_off[i] + o];
-        }
-        bx += tab[p.free_off];                      // the single sum point (Reduce iterators of size 1, if any)
-        bw += tab[p.tab_total + p.free_off];
-        const int* tx = tx_last + w0;
-        const int* tw = tx + p.tab_total;
-        *reinterpret_cast<int4*>(ex + 4 * lane) = make_int4(bx + tx[0], bx + tx[1], bx + tx[2], bx + tx[3]);
-        if constexpr (SCATTER) {
-          float g[4];
-          load_run<4, IBF>(X, run * 4, g);
+      // Several chunks of 64 runs per pass of the loop: the chunks' offsets go through the exchange area one after
+      // the other (LDS is in order within a wave, so a chunk's writes follow the reads of the chunk before), then
+      // all their elements' loads (or stores) are in flight together.  Measured: two chunks are best for the
+      // gathering forward pass (a third and fourth cost registers and gain nothing), four for the scatter.
+      constexpr int H = SCATTER ? 4 : 2;
+      for (int64_t run0 = ((int64_t)blockIdx.x * kThreads + wave * 64) * H; run0 < p.n_runs;
+           run0 += (int64_t)gridDim.x * kThreads * H) {
+        int offx[H][4], offw[H][4];     // per element of pass (h, v): X offset; W offset (forward) or value bits (scatter)
 #pragma unroll
-          for (int v = 0; v < 4; ++v) g[v] *= load_one<IBF>(Wt, bw + tw[v]);
-          *reinterpret_cast<float4*>(ew + 4 * lane) = make_float4(g[0], g[1], g[2], g[3]);
-        } else {
-          *reinterpret_cast<int4*>(ew + 4 * lane) = make_int4(bw + tw[0], bw + tw[1], bw + tw[2], bw + tw[3]);
+        for (int h = 0; h < H; ++h) {
+          const int64_t mine = run0 + 64 * h + lane;
+          const int64_t run = mine < p.n_runs ? mine : p.n_runs - 1;
+          uint32_t rest = (uint32_t)run;
+          const uint32_t row = div_magic(rest, runs_per_row, p.magic[last]);
+          const int w0 = (int)(rest - row * runs_per_row) * 4;
+          rest = row;
+          int bx = 0, bw = 0;
+          for (int i = last - 1; i >= 0; --i) {
+            const uint32_t sz = (uint32_t)vs.size[i];
+            const uint32_t q = div_magic(rest, sz, p.magic[i]);
+            const int o = (int)(rest - q * sz);
+            rest = q;
+            bx += tab[p.tab_off[i] + o];
+            bw += tab[p.tab_total + p.tab_off[i] + o];
+          }
+          bx += tab[p.free_off];                      // the single sum point (Reduce iterators of size 1, if any)
+          bw += tab[p.tab_total + p.free_off];
+          const int* tx = tx_last + w0;
+          const int* tw = tx + p.tab_total;
+          *reinterpret_cast<int4*>(ex + 4 * lane) = make_int4(bx + tx[0], bx + tx[1], bx + tx[2], bx + tx[3]);
+          if constexpr (SCATTER) {
+            float g[4];
+            load_run<4, IBF>(X, run * 4, g);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) g[v] *= load_one<IBF>(Wt, bw + tw[v]);
+            *reinterpret_cast<float4*>(ew + 4 * lane) = make_float4(g[0], g[1], g[2], g[3]);
+          } else {
+            *reinterpret_cast<int4*>(ew + 4 * lane) = make_int4(bw + tw[0], bw + tw[1], bw + tw[2], bw + tw[3]);
+          }
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+          __builtin_amdgcn_wave_barrier();
+          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            offx[h][v] = ex[64 * v + lane];
+            offw[h][v] = ew[64 * v + lane];
+          }
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+          __builtin_amdgcn_wave_barrier();
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         const int64_t e0 = run0 * 4 + lane;
         if constexpr (SCATTER) {
 #pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            const int off = ex[64 * v + lane];
-            const float val = __int_as_float(ew[64 * v + lane]);
-            if (e0 + 64 * v < n_elems) store_one<OBF>(out, off, val);
-          }
+          for (int h = 0; h < H; ++h)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+              if (e0 + 256 * h + 64 * v < n_elems) store_one<OBF>(out, offx[h][v], __int_as_float(offw[h][v]));
         } else {
-          float val[4];
+          float val[H][4];
 #pragma unroll
-          for (int v = 0; v < 4; ++v) val[v] = load_one<IBF>(X, ex[64 * v + lane]) * load_one<IBF>(Wt, ew[64 * v + lane]);
+          for (int h = 0; h < H; ++h)
 #pragma unroll
-          for (int v = 0; v < 4; ++v)
-            if (e0 + 64 * v < n_elems) store_one<OBF>(out, e0 + 64 * v, val[v]);
+            for (int v = 0; v < 4; ++v) val[h][v] = load_one<IBF>(X, offx[h][v]) * load_one<IBF>(Wt, offw[h][v]);
+#pragma unroll
+          for (int h = 0; h < H; ++h)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+              if (e0 + 256 * h + 64 * v < n_elems) store_one<OBF>(out, e0 + 256 * h + 64 * v, val[h][v]);
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
       }
       return;
     }

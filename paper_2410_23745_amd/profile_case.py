@@ -10,7 +10,8 @@ WRITE_SIZE report for it gives the factor that turns the counters into bytes.
 Cases: config0, config1_s{0..3}_{f32|bf16}, config2, config3, config4_{fwd|bwd_data|bwd_weight}, and the backward
 passes of the first two shapes with a seeded output gradient: config1t_s{0..3}_{f32|bf16}_{fwd|bwd_data|bwd_weight},
 config3t_{fwd|bwd_data|bwd_weight}; Operator 1 (two stages) on a ResNet-18 stage shape: op1_s{0..3}_{f32|bf16}_{fwd|bwd}; the GPT-2 QKV projection as a matrix product:
-qkv_{f32|bf16}_{fwd|bwd_data|bwd_weight}.
+qkv_{f32|bf16}_{fwd|bwd_data|bwd_weight}; the two pure views of the benchmark (102.8 MB in and out, random values):
+view_{shift|unshuffle}_{fwd|bwd_data}.
 Buffers rotate over several copies so that every launch reads HBM rather than the last-level cache.
 """
 from __future__ import annotations
@@ -98,6 +99,23 @@ def main() -> int:
         torch.cuda.synchronize()
         print(f"{args.case}: " + " | ".join(p.describe(k) for p in chain.stages
                                             for k in ((0,) if direction == "fwd" else (2, 1))))
+        return 0
+
+    if args.case.startswith("view_"):       # view_<shift|unshuffle>_<fwd|bwd_data>
+        from syno_inputs import workloads as wl
+        kind, direction = args.case[5:].split("_", 1)
+        d = wl.shifted_scale(64, 128, 56, 56) if kind == "shift" else wl.pixel_unshuffle(64, 128, 28, 28, 2)
+        which = {"fwd": 0, "bwd_data": 1}[direction]
+        plan = syno.Plan(d)
+        fn = (plan.forward, plan.backward_data)[which]
+        shapes = ((plan.x_shape, plan.out_shape), (plan.out_shape, plan.x_shape))[which]
+        sets = [(torch.randn(shapes[0], device=dev), torch.randn(plan.w_shape if plan.w_shape else (1,), device=dev),
+                 torch.empty(shapes[1], device=dev)) for _ in range(args.sets)]
+        for i in range(args.iters):
+            s = sets[i % len(sets)]
+            fn(s[0], s[1], s[2])
+        torch.cuda.synchronize()
+        print(f"{args.case}: {plan.describe(which)}; {args.iters} launches")
         return 0
 
     w, which = make_case(args.case)

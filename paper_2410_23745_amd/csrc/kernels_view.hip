@@ -208,11 +208,23 @@ __global__ __launch_bounds__(kThreads) void view_stream(const ViewParams p, cons
             for (int v = 0; v < 4; ++v)
               if (e0 + 256 * h + 64 * v < n_elems) store_one<OBF>(out, offx[h][v], __int_as_float(offw[h][v]));
         } else {
-          float val[H][4];
+          // every load is requested before the first value is used (the empty asm keeps the compiler from sinking
+          // loads under the stores' bounds tests, where each would be waited for on its own)
+          float val[H][4], wv[H][4];
 #pragma unroll
           for (int h = 0; h < H; ++h)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) val[h][v] = load_one<IBF>(X, offx[h][v]) * load_one<IBF>(Wt, offw[h][v]);
+            for (int v = 0; v < 4; ++v) {
+              val[h][v] = load_one<IBF>(X, offx[h][v]);
+              wv[h][v] = load_one<IBF>(Wt, offw[h][v]);
+            }
+#pragma unroll
+          for (int h = 0; h < H; ++h)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+              asm volatile("" : "+v"(val[h][v]), "+v"(wv[h][v]));
+              val[h][v] *= wv[h][v];
+            }
 #pragma unroll
           for (int h = 0; h < H; ++h)
 #pragma unroll

@@ -22,8 +22,10 @@ from .rng import Stream, bf16_bits_to_f32, to_bf16_bits
 # ----------------------------------------------------------------------------
 # pGraphs
 # ----------------------------------------------------------------------------
-def conv2d(N, C, Co, H, W, KH=3, KW=None, in_dtype=F32, out_dtype=F32) -> OpDesc:
-    """out[n,co,h,w] = sum_{c,kh,kw} X[n,c,h+kh-KH/2,w+kw-KW/2] * Wt[co,c,kh,kw]."""
+def conv2d(N, C, Co, H, W, KH=3, KW=None, in_dtype=F32, out_dtype=F32, w_order=(0, 1, 2, 3)) -> OpDesc:
+    """out[n,co,h,w] = sum_{c,kh,kw} X[n,c,h+kh-KH/2,w+kw-KW/2] * Wt[co,c,kh,kw].
+    `w_order` lists which of (co, c, kh, kw) each weight axis is, outermost first (weights may be laid out in any
+    order: section 6 of the paper lets them be reshaped offline)."""
     KW = KH if KW is None else KW
     b = Builder([("n", N), ("co", Co), ("h", H), ("w", W)], name=f"conv{KH}x{KW}_C{C}_Co{Co}_{H}x{W}_N{N}")
     n, co, h, w = 0, 1, 2, 3
@@ -35,11 +37,12 @@ def conv2d(N, C, Co, H, W, KH=3, KW=None, in_dtype=F32, out_dtype=F32) -> OpDesc
     kwx, kww = b.share(kw)
     hh = b.unfold(h, khx)
     ww = b.unfold(w, kwx)
-    return b.finish([n, cx, hh, ww], [co, cw, khw, kww], in_dtype, out_dtype)
+    waxes = [co, cw, khw, kww]
+    return b.finish([n, cx, hh, ww], [waxes[i] for i in w_order], in_dtype, out_dtype)
 
 
 def grouped_shift_unfold(N, C=256, Co=256, H=14, W=14, groups=4, K=3,
-                         in_dtype=BF16, out_dtype=F32) -> OpDesc:
+                         in_dtype=BF16, out_dtype=F32, w_order=(0, 1, 2, 3)) -> OpDesc:
     """out[n,co,h,w] = sum_{c',k} Wt[co,c',k] * X[n, g*Cg+c', (h+g) mod H, w+k-K/2],  g = co div (Co/groups)."""
     Og, Cg = Co // groups, C // groups
     b = Builder([("n", N), ("co", Co), ("h", H), ("w", W)], name=f"gshift_unfold_C{C}_g{groups}_{H}x{W}_N{N}")
@@ -53,7 +56,8 @@ def grouped_shift_unfold(N, C=256, Co=256, H=14, W=14, groups=4, K=3,
     cin = b.split(gx, cx)
     hh = b.shift(h, 0, by=gx, coef=1)
     ww = b.unfold(w, kx)
-    return b.finish([n, cin, hh, ww], [gw, cop, cw, kw], in_dtype, out_dtype)
+    waxes = [gw, cop, cw, kw]
+    return b.finish([n, cin, hh, ww], [waxes[i] for i in w_order], in_dtype, out_dtype)
 
 
 def strided_depthwise(N, C, H_out, W_out, S=2, K=3, in_dtype=F32, out_dtype=F32) -> OpDesc:
@@ -181,12 +185,14 @@ def _finish(desc, xs, ws, os, X, W, G, red) -> Workload:
     return Workload(desc, tuple(xs), tuple(ws), tuple(os), X, W, G, Xb, Wb, Gb, flops)
 
 
-def make_conv(N, C, H, seed=0, bf16=False, Co=None, Wd=None, K=3, with_grad=False, out_bf16=False) -> Workload:
+def make_conv(N, C, H, seed=0, bf16=False, Co=None, Wd=None, K=3, with_grad=False, out_bf16=False,
+              w_order=(0, 1, 2, 3)) -> Workload:
     Co = C if Co is None else Co
     Wd = H if Wd is None else Wd
-    desc = conv2d(N, C, Co, H, Wd, K, K, BF16 if bf16 else F32, BF16 if out_bf16 else F32)
+    desc = conv2d(N, C, Co, H, Wd, K, K, BF16 if bf16 else F32, BF16 if out_bf16 else F32, w_order)
     s = Stream(seed)
-    xs, ws, os = (N, C, H, Wd), (Co, C, K, K), (N, Co, H, Wd)
+    nat = (Co, C, K, K)
+    xs, ws, os = (N, C, H, Wd), tuple(nat[i] for i in w_order), (N, Co, H, Wd)
     X = s.normal(xs)
     W = s.uniform_pm(1.0 / np.sqrt(K * K * C), ws)
     G = s.normal(os) if with_grad else None
@@ -194,10 +200,12 @@ def make_conv(N, C, H, seed=0, bf16=False, Co=None, Wd=None, K=3, with_grad=Fals
 
 
 def make_gshift(N, seeds=(0, 0, 0), with_grad=False, C=256, H=14, Wd=14, groups=4, K=3, out_bf16=False,
-                bf16=True) -> Workload:
-    desc = grouped_shift_unfold(N, C, C, H, Wd, groups, K, BF16 if bf16 else F32, BF16 if out_bf16 else F32)
+                bf16=True, w_order=(0, 1, 2, 3)) -> Workload:
+    desc = grouped_shift_unfold(N, C, C, H, Wd, groups, K, BF16 if bf16 else F32, BF16 if out_bf16 else F32, w_order)
     Cg = C // groups
-    xs, ws, os = (N, C, H, Wd), (C, Cg, K), (N, C, H, Wd)
+    nat = (groups, Cg, Cg, K)
+    # (the natural order [g, co', c', k] is the contiguous Wt[C, Cg, K] the workload names)
+    xs, ws, os = (N, C, H, Wd), ((C, Cg, K) if tuple(w_order) == (0, 1, 2, 3) else tuple(nat[i] for i in w_order)), (N, C, H, Wd)
     streams: Dict[int, Stream] = {}
 
     def st(seed):

@@ -148,6 +148,12 @@ def test_kernel_choice(syno):
         C, H = wl.RESNET18_STAGES[stage]
         assert names(wl.conv2d(32, C, C, H, H))[:2] == ["mfma_contraction_f32"] * 2
         assert names(wl.conv2d(32, C, C, H, H, 3, 3, BF16, F32))[:2] == ["mfma_contraction_bf16"] * 2
+    # weights in any axis order stay on the tuned kernels, in all three passes
+    for wo in ((1, 0, 2, 3), (2, 3, 1, 0), (0, 3, 2, 1)):
+        assert names(wl.conv2d(3, 24, 40, 13, 19, 3, 3, F32, F32, wo)) == ["mfma_contraction_f32"] * 3
+        assert names(wl.conv2d(3, 40, 24, 13, 19, 3, 3, BF16, F32, wo)) == ["mfma_contraction_bf16"] * 3
+        assert names(wl.conv2d(2, 128, 128, 28, 28, 3, 3, F32, F32, wo)) == ["mfma_contraction_f32"] * 3
+    assert names(wl.grouped_shift_unfold(2, 96, 96, 9, 11, 3, 3, BF16, F32, (2, 0, 3, 1))) == ["mfma_contraction_bf16"] * 3
     assert names(wl.conv2d(1, 16, 16, 16, 16))[0] == "mfma_contraction_f32"
     assert names(wl.grouped_shift_unfold(32)) == ["mfma_contraction_bf16"] * 3
     assert names(wl.grouped_shift_unfold(128)) == ["mfma_contraction_bf16"] * 3

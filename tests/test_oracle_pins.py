@@ -273,6 +273,36 @@ def test_shift_plus_minus_is_identity(oracle):
     assert oracle.gather_map(shift_chain(N, [N]), np.arange(N), z)[0].tolist() == list(range(N))
 
 
+@pytest.mark.parametrize("s,coef", [(0, 1), (3, -1), (-2, 2), (5, 2), (1, -3), (-9, 0)])
+def test_shift_by_another_coordinate_is_a_roll_per_slice(oracle, s, coef):
+    # out[g,i] = X[g, (i + s + coef*g) mod N]: slice g of X rolled by -(s + coef*g), each slice rolled by hand.
+    # A checker that ignored `coef`, its sign, or dropped `s` when `shift_by` is present fails one of the cases.
+    Gd, N = 4, 7
+    b = Builder([("g", Gd), ("i", N)])
+    v = b.shift(1, s, by=0, coef=coef)
+    d = b.finish([0, v], [])
+    X, Gr = rnd((Gd, N), 40), rnd((Gd, N), 41)
+    ref = np.stack([np.roll(X[g], -(s + coef * g)) for g in range(Gd)])
+    np.testing.assert_array_equal(oracle.forward(d, X, np.ones(1)), ref)
+    # the adjoint of a permutation is its inverse: dX[g] = upstream gradient of slice g rolled the other way
+    dX, _ = oracle.backward(d, X, np.ones(1), Gr)
+    np.testing.assert_array_equal(dX, np.stack([np.roll(Gr[g], s + coef * g) for g in range(Gd)]))
+
+
+def test_shift_by_a_reduce_iterator(oracle):
+    # out[i] = sum_r X[r, (i + 2 - r) mod N] * Wt[r]: the Shift reads the Reduce iterator (coef = -1, s = 2);
+    # checked against explicit loops.
+    N, R = 6, 4
+    b = Builder([("i", N)])
+    r = b.reduce(R)
+    rx, rw = b.share(r)
+    v = b.shift(0, 2, by=rx, coef=-1)
+    d = b.finish([rx, v], [rw])
+    X, Wt = rnd((R, N), 42), rnd((R,), 43)
+    ref = np.array([sum(X[k, (i + 2 - k) % N] * Wt[k] for k in range(R)) for i in range(N)])
+    np.testing.assert_allclose(oracle.forward(d, X, Wt), ref, rtol=0, atol=1e-14)
+
+
 # --------------------------------------------------------------------------------------
 # Expand: the output does not depend on the expanded iterator
 # --------------------------------------------------------------------------------------

@@ -76,6 +76,22 @@ typedef struct {
   int64_t shift_coef;   /* SHIFT only: the offset is s + shift_coef * value(shift_by) */
 } syno_prim;
 
+/* Optional overrides of the planner's choices, for verification and tuning (every field 0 = the planner
+ * decides).  They select among code paths that compute the same operator; none changes a result beyond
+ * the summation order.  Read once, while the plan is built.
+ *   kernel_policy   1: every pass runs on the generic index-program kernels
+ *   mfma_variant    1 + index of the contraction kernel's tile variant (forward and backward-data);
+ *                   mfma_rows = output rows per workgroup.  Ignored unless the pair fits the operator.
+ *   mfma_taps       1: one window tap per inner step even where three would be taken
+ *   dw_workgroups   target number of workgroups of the backward-weight contraction (split of the pixel axis)
+ *   view_workgroups cap on the grid of the view kernel */
+typedef struct {
+  int32_t kernel_policy;
+  int32_t mfma_variant, mfma_rows, mfma_taps;
+  int32_t dw_workgroups;
+  int32_t view_workgroups;
+} syno_plan_options;
+
 /* Coordinate ids 0..n_out-1 are the output iterators in the layout order of `out`; primitives
  * are applied in array order (bottom-up) and may only consume ids defined before them.  Every
  * coordinate must be consumed exactly once: by one primitive, or as one axis of X or of W. */
@@ -86,6 +102,7 @@ typedef struct {
   int32_t n_w;     const int32_t*   weight_coords;   /* axes of W, outermost first (may be 0: W is one element) */
   syno_dtype in_dtype;    /* element type of X, W and G */
   syno_dtype out_dtype;   /* element type of out and dX; accumulation is fp32; dW is always fp32 */
+  const syno_plan_options* options;   /* NULL: defaults */
 } syno_desc;
 
 /* Which of the three contractions a selector argument names. */
@@ -124,10 +141,6 @@ const char* syno_plan_kernel(const syno_plan* plan, int which);
 /* Human-readable summary of how call `which` will be launched (kernel family, tile shape, grid, LDS),
  * written NUL-terminated into buf[0..size).  For logs and tests; the format is not an interface. */
 syno_status syno_plan_describe(const syno_plan* plan, int which, char* buf, size_t size);
-
-/* Restrict kernel choice at plan creation: 0 = planner decides (default), 1 = always the generic
- * index-program kernels.  Process-wide; affects plans created afterwards.  For verification. */
-syno_status syno_set_kernel_policy(int policy);
 
 /* Verification aid (not on the hot path): the index maps of the three contractions, evaluated on
  * the device from the same lowered tables the generic kernels use.
@@ -182,9 +195,10 @@ syno_status syno_chain_workspace_bytes(const syno_chain* chain, int which, size_
 syno_status syno_chain_forward(const syno_chain* chain, const void* X, const void* const* W, void* const* act,
                                void* out, void* workspace, hipStream_t stream);
 /* Gradients of L = sum(out*G) by the chain rule, last stage first: dW[i] (fp32) for every stage and dX (may
- * be NULL: not computed).  Intermediate gradients live in the workspace, in the element type of the stage
- * that consumes them.  SYNO_ERR_UNSUPPORTED when some stage's dX type differs from the gradient type the stage
- * before it expects (out_dtype of stage i+1 != in_dtype of stage i). */
+ * be NULL: not computed).  G has the last stage's in_dtype.  Intermediate gradients live in the workspace, in the
+ * input element type of the stage that consumes them (so a bf16 chain with an fp32 result runs its gradients in
+ * bf16 between the stages).  dX has the first stage's out_dtype; for chains written by
+ * syno_chain_create_materialized, the graph's out_dtype. */
 syno_status syno_chain_backward(const syno_chain* chain, const void* X, const void* const* W,
                                 const void* const* act, const void* G, void* dX, void* const* dW,
                                 void* workspace, hipStream_t stream);

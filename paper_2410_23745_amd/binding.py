@@ -14,7 +14,7 @@ _LIB_PATH = os.path.join(_HERE, "libsyno.so")
 _lib = None
 
 EXPORTS = ("syno_plan_create", "syno_plan_destroy", "syno_forward", "syno_backward_data", "syno_backward_weight",
-           "syno_plan_workspace_bytes", "syno_plan_shapes", "syno_plan_kernel", "syno_plan_describe", "syno_set_kernel_policy",
+           "syno_plan_workspace_bytes", "syno_plan_shapes", "syno_plan_kernel", "syno_plan_describe",
            "syno_plan_free_size", "syno_debug_gather", "syno_debug_gather_host", "syno_status_string",
            "syno_chain_create", "syno_chain_destroy", "syno_chain_stages", "syno_chain_plan",
            "syno_chain_workspace_bytes", "syno_chain_forward", "syno_chain_backward",
@@ -30,12 +30,18 @@ class _Prim(ctypes.Structure):
                 ("param", ctypes.c_int64), ("shift_by", ctypes.c_int32), ("shift_coef", ctypes.c_int64)]
 
 
+class _Options(ctypes.Structure):
+    _fields_ = [("kernel_policy", ctypes.c_int32), ("mfma_variant", ctypes.c_int32), ("mfma_rows", ctypes.c_int32),
+                ("mfma_taps", ctypes.c_int32), ("dw_workgroups", ctypes.c_int32), ("view_workgroups", ctypes.c_int32)]
+
+
 class _Desc(ctypes.Structure):
     _fields_ = [("n_out", ctypes.c_int32), ("out_dims", ctypes.POINTER(_Dim)),
                 ("n_prim", ctypes.c_int32), ("prims", ctypes.POINTER(_Prim)),
                 ("n_in", ctypes.c_int32), ("input_coords", ctypes.POINTER(ctypes.c_int32)),
                 ("n_w", ctypes.c_int32), ("weight_coords", ctypes.POINTER(ctypes.c_int32)),
-                ("in_dtype", ctypes.c_int), ("out_dtype", ctypes.c_int)]
+                ("in_dtype", ctypes.c_int), ("out_dtype", ctypes.c_int),
+                ("options", ctypes.POINTER(_Options))]
 
 
 class SynoError(RuntimeError):
@@ -67,7 +73,6 @@ def load_library():
     lib.syno_plan_kernel.argtypes = [vp, ctypes.c_int]
     lib.syno_plan_kernel.restype = ctypes.c_char_p
     lib.syno_plan_describe.argtypes = [vp, ctypes.c_int, ctypes.c_char_p, ctypes.c_size_t]
-    lib.syno_set_kernel_policy.argtypes = [ctypes.c_int]
     lib.syno_plan_free_size.argtypes = [vp, ctypes.c_int, i64p]
     lib.syno_debug_gather.argtypes = [vp, ctypes.c_int, vp, vp, ctypes.c_int64, vp, vp, vp]
     lib.syno_debug_gather_host.argtypes = [vp, ctypes.c_int, vp, vp, ctypes.c_int64, vp, vp]
@@ -91,18 +96,12 @@ def load_library():
     return lib
 
 
-def set_kernel_policy(policy: int) -> None:
-    """0: planner decides; 1: always the generic index-program kernels (plans created afterwards)."""
-    st = load_library().syno_set_kernel_policy(int(policy))
-    if st:
-        raise SynoError(st, "syno_set_kernel_policy")
-
-
 _TORCH_DTYPE = {0: torch.float32, 1: torch.bfloat16}
 
 
-def _marshal(desc):
-    """OpDesc-like object -> (syno_desc, objects that must stay alive while it is used)."""
+def _marshal(desc, options=None):
+    """OpDesc-like object (+ a dict of syno_plan_options fields) -> (syno_desc, objects that must stay alive
+    while it is used)."""
     dims = (_Dim * max(1, len(desc.out_dims)))()
     names = [str(n).encode() for n, _ in desc.out_dims]
     for i, (_, s) in enumerate(desc.out_dims):
@@ -117,21 +116,23 @@ def _marshal(desc):
         prims[i].param, prims[i].shift_by, prims[i].shift_coef = int(p.param), int(p.shift_by), int(p.shift_coef)
     ic = (ctypes.c_int32 * max(1, len(desc.input_coords)))(*desc.input_coords)
     wc = (ctypes.c_int32 * max(1, len(desc.weight_coords)))(*desc.weight_coords)
+    opt = _Options(**{k: int(v) for k, v in options.items()}) if options else None
     d = _Desc(len(desc.out_dims), dims, len(desc.prims), prims, len(desc.input_coords), ic,
-              len(desc.weight_coords), wc, int(desc.in_dtype), int(desc.out_dtype))
-    return d, (dims, names, prims, ic, wc)
+              len(desc.weight_coords), wc, int(desc.in_dtype), int(desc.out_dtype),
+              ctypes.pointer(opt) if opt is not None else None)
+    return d, (dims, names, prims, ic, wc, opt)
 
 
 class Plan:
     """Owns one syno_plan.  `desc` is an OpDesc-like object (out_dims, prims, input_coords, weight_coords,
-    in_dtype, out_dtype)."""
+    in_dtype, out_dtype); `options` are fields of syno_plan_options (kernel_policy=1: the generic kernels)."""
 
-    def __init__(self, desc, _borrowed=None, _owner=None):
+    def __init__(self, desc, _borrowed=None, _owner=None, **options):
         lib = load_library()
         if _borrowed is not None:
             handle, self._owned, self._owner = ctypes.c_void_p(_borrowed), False, _owner   # a stage of a chain
         else:
-            d, _keep = _marshal(desc)
+            d, _keep = _marshal(desc, options)
             handle = ctypes.c_void_p()
             st = lib.syno_plan_create(ctypes.byref(d), ctypes.byref(handle))
             if st:
@@ -276,11 +277,11 @@ class Chain:
     """Owns one syno_chain: an operator evaluated as consecutive single-weight stages.  `descs` is a list of
     OpDesc-like objects.  `stages[i]` is a borrowed Plan for queries (shapes, kernel names)."""
 
-    def __init__(self, descs, _materialize=None):
+    def __init__(self, descs, _materialize=None, **options):
         lib = load_library()
         handle = ctypes.c_void_p()
         if _materialize is not None:
-            d, keep = _marshal(_materialize)
+            d, keep = _marshal(_materialize, options)
             st = lib.syno_chain_create_materialized(ctypes.byref(d), ctypes.byref(handle))
             if st:
                 raise SynoError(st, "syno_chain_create_materialized")
@@ -288,7 +289,7 @@ class Chain:
             arr = (_Desc * max(1, len(descs)))()
             keep = []
             for i, d in enumerate(descs):
-                arr[i], k = _marshal(d)
+                arr[i], k = _marshal(d, options)
                 keep.append(k)
             st = lib.syno_chain_create(arr, len(descs), ctypes.byref(handle))
             if st:
@@ -301,12 +302,14 @@ class Chain:
             descs = [_StageTypes(_materialize.in_dtype, _materialize.in_dtype if i + 1 < n else _materialize.out_dtype)
                      for i in range(n)]
         self.stages = [Plan(descs[i], _borrowed=lib.syno_chain_plan(self._h, i), _owner=self) for i in range(n)]
+        # dX has the first stage's output type; for a materialised graph, the graph's
+        self.dx_dtype = _TORCH_DTYPE[int(_materialize.out_dtype)] if _materialize is not None else self.stages[0].out_dtype
         self._ws = {}
 
     @classmethod
-    def materialized(cls, desc):
+    def materialized(cls, desc, **options):
         """The chain the library's materialised-reduction pass cuts one single-weight pGraph into."""
-        return cls(None, _materialize=desc)
+        return cls(None, _materialize=desc, **options)
 
     def _own(self, i: int) -> bool:
         return self.weight_stage < 0 or self.weight_stage == i
@@ -388,8 +391,8 @@ class Chain:
         pdx = 0
         if want_dx:
             if dX is None:
-                dX = torch.empty(first.x_shape, dtype=first.out_dtype, device=X.device)
-            pdx = first._arg(dX, first.x_shape, first.out_dtype, "syno_chain_backward dX")
+                dX = torch.empty(first.x_shape, dtype=self.dx_dtype, device=X.device)
+            pdx = first._arg(dX, first.x_shape, self.dx_dtype, "syno_chain_backward dX")
         ws = self._workspace(1, X.device, workspace)
         stream = torch.cuda.current_stream(X.device).cuda_stream
         st = load_library().syno_chain_backward(self._h, px, self._ptrs(pw), self._ptrs(pa), pg, pdx,

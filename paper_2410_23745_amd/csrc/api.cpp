@@ -1,6 +1,7 @@
 // The C ABI of include/syno.h: argument checks and dispatch to the kernel families.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cstdio>
 #include <new>
@@ -12,15 +13,19 @@
 // A chain owns the plans of its stages.
 struct syno_chain {
   std::vector<syno_plan*> stage;
+  // Backward-data of stage i writes the gradient that stage i-1 reads as its upstream gradient, so its result
+  // type must be stage i-1's input type; where that differs from the stage's own output type (a bf16 stage with an
+  // fp32 result) the same graph is planned once more with that result type, for backward-data only (else nullptr).
+  std::vector<syno_plan*> bwd_data;
   size_t ws_fwd = 0;        // largest forward workspace of any stage
   size_t ws_bwd_stage = 0;  // largest gradient-call workspace of any stage
   size_t grad_bytes = 0;    // one intermediate-gradient buffer (two are used, alternating)
-  bool bwd_types_fit = true;
   // chains written by the materialised-reduction pass: the stage that keeps the graph's weight (-1: every stage
   // has its own); the other stages have none and multiply by the constant one below
   int32_t weight_stage = -1;
   ~syno_chain() {
     for (syno_plan* p : stage) delete p;
+    for (syno_plan* p : bwd_data) delete p;
   }
 };
 
@@ -41,7 +46,6 @@ std::string mfma_dw_describe(const syno_plan* p);
 static __device__ __align__(16) uint32_t g_unit_words[4] = {0x3F800000u, 0x00003F80u, 0u, 0u};
 
 namespace {
-std::atomic<int> g_policy{0};
 
 // Device address of the constant one in element type `t` on the current device (each device has its own copy of
 // the array; the address is looked up once per device).
@@ -93,13 +97,18 @@ extern "C" {
 syno_status syno_plan_create(const syno_desc* desc, syno_plan** plan) {
   if (!desc || !plan) return SYNO_ERR_NULL;
   *plan = nullptr;
-  syno_plan* p = new (std::nothrow) syno_plan();
-  if (!p) return SYNO_ERR_UNSUPPORTED;
-  std::string why;
-  const syno_status st = syno::build_plan(desc, g_policy.load(), p, &why);
-  if (st != SYNO_OK) {
+  syno_plan* p = nullptr;
+  try {     // (the planner's containers may throw; nothing may cross this boundary)
+    p = new syno_plan();
+    std::string why;
+    const syno_status st = syno::build_plan(desc, p, &why);
+    if (st != SYNO_OK) {
+      delete p;
+      return st;
+    }
+  } catch (...) {
     delete p;
-    return st;
+    return SYNO_ERR_UNSUPPORTED;
   }
   *plan = p;
   return SYNO_OK;
@@ -172,12 +181,6 @@ syno_status syno_plan_describe(const syno_plan* plan, int which, char* buf, size
   return SYNO_OK;
 }
 
-syno_status syno_set_kernel_policy(int policy) {
-  if (policy < 0 || policy > 1) return SYNO_ERR_SHAPE;
-  g_policy.store(policy);
-  return SYNO_OK;
-}
-
 syno_status syno_plan_free_size(const syno_plan* plan, int which, int64_t* free_size) {
   if (!plan || !free_size) return SYNO_ERR_NULL;
   if (which < 0 || which > 2) return SYNO_ERR_SHAPE;
@@ -199,18 +202,58 @@ syno_status syno_debug_gather_host(const syno_plan* plan, int which, const int64
   return syno::host_debug_gather(plan, which, t_flat, q_flat, n, a_off, b_off);
 }
 
+namespace {
+// Plans every stage.  dx_dtype: element type of the chain's dX (-1: the first stage's own output type).
+syno_status chain_create(const syno_desc* stages, int32_t n_stages, int dx_dtype, syno_chain** chain) {
+  if (n_stages < 1 || n_stages > 8) return SYNO_ERR_SHAPE;
+  syno_chain* c = new syno_chain();
+  const auto esize = [](syno_dtype t) { return t == SYNO_BF16 ? size_t(2) : size_t(4); };
+  const auto fail = [&](syno_status st) { delete c; return st; };
+  for (int i = 0; i < n_stages; ++i) {
+    syno_plan* p = nullptr;
+    syno_status st = syno_plan_create(&stages[i], &p);
+    if (st != SYNO_OK) return fail(st);
+    c->stage.push_back(p);
+    c->bwd_data.push_back(nullptr);
+    if (i > 0) {
+      const syno_plan* q = c->stage[i - 1];
+      if (q->out_elems != p->x_elems || q->out_dtype != p->in_dtype) return fail(SYNO_ERR_SHAPE);
+    }
+    // the type this stage's backward-data must produce
+    const syno_dtype want = i > 0 ? c->stage[i - 1]->in_dtype : (dx_dtype < 0 ? p->out_dtype : (syno_dtype)dx_dtype);
+    if (want != p->out_dtype) {
+      syno_desc d = stages[i];
+      d.out_dtype = want;
+      st = syno_plan_create(&d, &c->bwd_data[i]);
+      if (st != SYNO_OK) return fail(st);
+    }
+    const syno_plan* pb = c->bwd_data[i] ? c->bwd_data[i] : p;
+    c->ws_fwd = std::max(c->ws_fwd, p->launch[SYNO_FWD].workspace);
+    c->ws_bwd_stage = std::max(c->ws_bwd_stage, std::max(pb->launch[SYNO_BWD_DATA].workspace, p->launch[SYNO_BWD_WEIGHT].workspace));
+    if (i > 0) c->grad_bytes = std::max(c->grad_bytes, ((size_t(p->x_elems) * esize(want)) + 255) & ~size_t(255));
+  }
+  *chain = c;
+  return SYNO_OK;
+}
+}  // namespace
+
 syno_status syno_chain_create_materialized(const syno_desc* desc, syno_chain** chain) {
   if (!desc || !chain) return SYNO_ERR_NULL;
   *chain = nullptr;
-  std::vector<syno::OwnedDesc> stages;
-  int32_t weight_stage = -1;
-  syno_status st = syno::materialise(desc, stages, weight_stage);
-  if (st != SYNO_OK) return st;
-  std::vector<syno_desc> views;
-  for (const syno::OwnedDesc& o : stages) views.push_back(o.view());
-  st = syno_chain_create(views.data(), (int32_t)views.size(), chain);
-  if (st == SYNO_OK) (*chain)->weight_stage = weight_stage;
-  return st;
+  try {
+    std::vector<syno::OwnedDesc> stages;
+    int32_t weight_stage = -1;
+    syno_status st = syno::materialise(desc, stages, weight_stage);
+    if (st != SYNO_OK) return st;
+    std::vector<syno_desc> views;
+    for (const syno::OwnedDesc& o : stages) views.push_back(o.view());
+    // dX of the whole graph has the graph's output type, whatever type the first stage stores its result in
+    st = chain_create(views.data(), (int32_t)views.size(), (int)desc->out_dtype, chain);
+    if (st == SYNO_OK) (*chain)->weight_stage = weight_stage;
+    return st;
+  } catch (...) {
+    return SYNO_ERR_UNSUPPORTED;
+  }
 }
 
 int32_t syno_chain_weight_stage(const syno_chain* chain) { return chain ? chain->weight_stage : -1; }
@@ -218,34 +261,11 @@ int32_t syno_chain_weight_stage(const syno_chain* chain) { return chain ? chain-
 syno_status syno_chain_create(const syno_desc* stages, int32_t n_stages, syno_chain** chain) {
   if (!stages || !chain) return SYNO_ERR_NULL;
   *chain = nullptr;
-  if (n_stages < 1 || n_stages > 8) return SYNO_ERR_SHAPE;
-  syno_chain* c = new (std::nothrow) syno_chain();
-  if (!c) return SYNO_ERR_UNSUPPORTED;
-  const auto esize = [](syno_dtype t) { return t == SYNO_BF16 ? size_t(2) : size_t(4); };
-  for (int i = 0; i < n_stages; ++i) {
-    syno_plan* p = nullptr;
-    syno_status st = syno_plan_create(&stages[i], &p);
-    if (st == SYNO_OK && i > 0) {
-      const syno_plan* q = c->stage.back();
-      if (q->out_elems != p->x_elems || q->out_dtype != p->in_dtype) st = SYNO_ERR_SHAPE;
-      if (p->out_dtype != q->in_dtype) c->bwd_types_fit = false;
-    }
-    if (st != SYNO_OK) {
-      delete p;
-      delete c;
-      return st;
-    }
-    c->stage.push_back(p);
-    if (p->launch[SYNO_FWD].workspace > c->ws_fwd) c->ws_fwd = p->launch[SYNO_FWD].workspace;
-    for (int w : {SYNO_BWD_DATA, SYNO_BWD_WEIGHT})
-      if (p->launch[w].workspace > c->ws_bwd_stage) c->ws_bwd_stage = p->launch[w].workspace;
-    if (i > 0) {
-      const size_t b = ((size_t(p->x_elems) * esize(p->out_dtype)) + 255) & ~size_t(255);
-      if (b > c->grad_bytes) c->grad_bytes = b;
-    }
+  try {
+    return chain_create(stages, n_stages, -1, chain);
+  } catch (...) {
+    return SYNO_ERR_UNSUPPORTED;
   }
-  *chain = c;
-  return SYNO_OK;
 }
 
 syno_status syno_chain_destroy(syno_chain* chain) {
@@ -293,7 +313,6 @@ syno_status syno_chain_backward(const syno_chain* chain, const void* X, const vo
   if (!chain || !X || !W || !G || !dW) return SYNO_ERR_NULL;
   const size_t n = chain->stage.size();
   if (n > 1 && !act) return SYNO_ERR_NULL;
-  if (!chain->bwd_types_fit) return SYNO_ERR_UNSUPPORTED;
   size_t need = 0;
   syno_chain_workspace_bytes(chain, 1, &need);
   if (need && !workspace) return SYNO_ERR_WORKSPACE;
@@ -314,7 +333,7 @@ syno_status syno_chain_backward(const syno_chain* chain, const void* X, const vo
     }
     void* dst = i == 0 ? dX : static_cast<void*>(grad0 + (i & 1) * chain->grad_bytes);
     if (!dst) break;   // first stage and the caller does not want dX
-    st = run(chain->stage[i], SYNO_BWD_DATA, g, Wi, dst, base, stream);
+    st = run(chain->bwd_data[i] ? chain->bwd_data[i] : chain->stage[i], SYNO_BWD_DATA, g, Wi, dst, base, stream);
     if (st != SYNO_OK) return st;
     g = dst;
   }

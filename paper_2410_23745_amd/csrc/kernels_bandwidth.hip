@@ -13,6 +13,8 @@
 // (same wave) with a shuffle instead of a second load.
 #include <hip/hip_runtime.h>
 
+#include <cstring>
+
 #include <algorithm>
 
 #include "plan.h"
@@ -342,17 +344,9 @@ bool bandwidth_supports(const syno_plan* p, int which) {
   return c.ws_g >= 0 && c.ws_kh >= 0 && c.ws_kw >= 0;
 }
 
-// Backward-weight keeps one partial sum per strip and tap in the workspace.
-size_t bandwidth_workspace(const syno_plan* plan, int which) {
-  if (which != SYNO_BWD_WEIGHT) return 0;
-  const ConvLike& c = plan->conv;
-  const size_t strips = (c.Ho + kStripRows - 1) / kStripRows;
-  return (size_t)c.N * c.G * strips * c.KH * c.KW * sizeof(float);
-}
-
-syno_status launch_bandwidth(const syno_plan* plan, int which, const void* A, const void* B, void* out, void* ws,
-                             hipStream_t stream) {
-  if (!bandwidth_supports(plan, which)) return SYNO_ERR_UNSUPPORTED;
+// Fills the launch record: the kernel parameters, and for backward-weight the workspace that keeps one partial
+// sum per strip and tap.
+void bandwidth_configure(syno_plan* plan, int which) {
   const ConvLike& c = plan->conv;
   const int V = c.sh == 2 ? 2 : 4;
   DwParams p{};
@@ -366,6 +360,19 @@ syno_status launch_bandwidth(const syno_plan* plan, int which, const void* A, co
   p.n_tasks = p.planes * p.strips;
   p.ws_c = c.ws_g; p.ws_kh = c.ws_kh; p.ws_kw = c.ws_kw;
   p.vec_ok = (c.Wi % (c.sw * V) == 0) && ((c.Hi * c.Wi) % 4 == 0) && (c.Wi % 4 == 0);
+  Launch& L = plan->launch[which];
+  static_assert(sizeof(DwParams) <= sizeof(L.params), "parameter record does not fit");
+  memcpy(L.params, &p, sizeof p);
+  L.params_ready = true;
+  L.workspace = which == SYNO_BWD_WEIGHT ? (size_t)c.N * c.G * p.strips * c.KH * c.KW * sizeof(float) : 0;
+}
+
+syno_status launch_bandwidth(const syno_plan* plan, int which, const void* A, const void* B, void* out, void* ws,
+                             hipStream_t stream) {
+  if (!plan->launch[which].params_ready) return SYNO_ERR_UNSUPPORTED;
+  const ConvLike& c = plan->conv;
+  DwParams p;
+  memcpy(&p, plan->launch[which].params, sizeof p);
   if (which == SYNO_FWD) {
     const float* X = static_cast<const float*>(A);
     const float* W = static_cast<const float*>(B);

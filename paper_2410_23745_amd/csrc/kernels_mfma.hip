@@ -311,12 +311,9 @@ void mfma_configure(syno_plan* plan, int which) {
   double best = 1e300;
   int best_v = -1, best_tr = 0;
   MfmaParams mp;
-  // SYNO_MFMA_TILE="variant,rows" overrides the tile choice (tuning aid)
-  if (const char* f = getenv("SYNO_MFMA_TILE")) {
-    int vi = -1, tr = 0;
-    if (sscanf(f, "%d,%d", &vi, &tr) == 2 && fill_params(plan, which, vi, tr, mp)) {
-      best_v = vi; best_tr = tr;
-    }
+  // the descriptor's options may name the tile variant and the rows per block (verification and tuning aid)
+  if (plan->opt.mfma_variant > 0 && fill_params(plan, which, plan->opt.mfma_variant - 1, plan->opt.mfma_rows, mp)) {
+    best_v = plan->opt.mfma_variant - 1; best_tr = plan->opt.mfma_rows;
   }
   if (best_v < 0)
     for (int vi = 0; vi < num_variants(bf); ++vi)
@@ -326,8 +323,7 @@ void mfma_configure(syno_plan* plan, int which) {
         if (cost < best) { best = cost; best_v = vi; best_tr = TR; }
       }
   fill_params(plan, which, best_v, best_tr, mp);
-  // SYNO_MFMA_U=1 switches the three-taps-per-row-step instantiation off (tuning aid)
-  if (const char* u = getenv("SYNO_MFMA_U")) if (atoi(u) == 1) mp.U = 1;
+  if (plan->opt.mfma_taps == 1) mp.U = 1;     // (option: the one-tap-per-row-step instantiation)
   static_assert(sizeof(MfmaParams) <= sizeof(plan->launch[which].params), "parameter record does not fit");
   memcpy(plan->launch[which].params, &mp, sizeof mp);
   plan->launch[which].params_ready = true;

@@ -20,6 +20,7 @@
 #include <cstdint>
 #include <cstdlib>
 #include <cstdio>
+#include <cstring>
 #include <string>
 #include <type_traits>
 
@@ -664,8 +665,7 @@ bool fill_dw(const syno_plan* plan, DwParams& p) {
   p.n_tiles = tiles;
   p.ct = cx / 32;
   p.slots = 8 * p.ct * c.KH * c.KW;
-  int target = 256;
-  if (const char* e = getenv("SYNO_DW_WORKGROUPS")) target = std::max(1, atoi(e));    // tuning aid
+  const int target = plan->opt.dw_workgroups > 0 ? plan->opt.dw_workgroups : 256;
   int splits = std::max(1, std::min(p.n_chunks, target / std::max(1, tiles)));
   while (splits > 1 && (int64_t)splits * tiles * p.slots * 1024 > (40ll << 20)) splits /= 2;
   p.chunks_per_split = (p.n_chunks + splits - 1) / splits;
@@ -726,7 +726,8 @@ bool fill_dw_f32(const syno_plan* plan, DwParams& p) {
   p.n_tiles = tiles;
   p.ct = cx / 32;
   p.slots = 8 * p.ct * c.KH * c.KW;
-  int splits = std::max(1, std::min(p.n_chunks, 256 / std::max(1, tiles)));
+  const int target = plan->opt.dw_workgroups > 0 ? plan->opt.dw_workgroups : 256;
+  int splits = std::max(1, std::min(p.n_chunks, target / std::max(1, tiles)));
   while (splits > 1 && (int64_t)splits * tiles * p.slots * 1024 > (40ll << 20)) splits /= 2;
   p.chunks_per_split = (p.n_chunks + splits - 1) / splits;
   p.rows_per_split = p.chunks_per_split * p.TRK;
@@ -760,80 +761,69 @@ bool mfma_dw_supports(const syno_plan* p) {
 
 void mfma_dw_configure(syno_plan* plan) {
   DwParams dp;
-  fill_any(plan, dp);
-  plan->launch[SYNO_BWD_WEIGHT].variant = 0;
+  Launch& L = plan->launch[SYNO_BWD_WEIGHT];
+  static_assert(sizeof(DwParams) <= sizeof(L.params), "parameter record does not fit");
+  L.params_ready = fill_any(plan, dp);
+  memcpy(L.params, &dp, sizeof dp);
+  L.variant = 0;
   // one 64 x 32*ct x taps tile of fp32 sums per workgroup (whole tiles also where Og or Cg end inside one)
-  plan->launch[SYNO_BWD_WEIGHT].workspace = dp.n_splits == 1 ? 0 : (size_t)dp.n_splits * dp.n_tiles * dp.slots * 1024;
+  L.workspace = dp.n_splits == 1 ? 0 : (size_t)dp.n_splits * dp.n_tiles * dp.slots * 1024;
 }
 
 std::string mfma_dw_describe(const syno_plan* plan) {
+  if (!plan->launch[SYNO_BWD_WEIGHT].params_ready) return "unconfigured";
   DwParams p;
-  if (!fill_any(plan, p)) return "unconfigured";
+  memcpy(&p, plan->launch[SYNO_BWD_WEIGHT].params, sizeof p);
   char b[256];
   snprintf(b, sizeof b, "rows/chunk=%d(+%d) pitch=%d chunks=%d splits=%d grid=%d lds=%dB", p.TRK, p.KH - 1, p.pitch, p.n_chunks,
            p.n_splits, p.G * p.n_oblk * p.n_cblk * p.n_splits, p.lds_bytes);
   return b;
 }
 
+namespace {
+// Launch of one instantiation; the opt-in to more than 64 KB of dynamic LDS is made once per instantiation.
+template <typename K, typename T>
+void launch_dw_kernel(K kernel, int grid, const DwParams& p, const T* G, const T* X, float* dst, hipStream_t stream) {
+  static const hipError_t lds_opt_in =
+      hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
+  if (lds_opt_in != hipSuccess) return;
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), p.lds_bytes, stream, p, G, X, dst);
+}
+}  // namespace
+
 // A = G (upstream gradient), B = X, out = dW (fp32), ws = n_splits partial copies of dW.
 syno_status launch_mfma_dw(const syno_plan* plan, const void* A, const void* B, void* out, void* ws, hipStream_t stream) {
+  if (!plan->launch[SYNO_BWD_WEIGHT].params_ready) return SYNO_ERR_UNSUPPORTED;
   DwParams p;
-  if (!fill_any(plan, p)) return SYNO_ERR_UNSUPPORTED;
+  memcpy(&p, plan->launch[SYNO_BWD_WEIGHT].params, sizeof p);
   if (!ws && p.n_splits > 1) return SYNO_ERR_WORKSPACE;
   const int grid = p.G * p.n_oblk * p.n_cblk * p.n_splits;
+  float* const dst = p.n_splits == 1 ? static_cast<float*>(out) : static_cast<float*>(ws);
+  using std::integral_constant;
+  auto by_window = [&](auto go) {
+    if (p.KH == 3 && p.KW == 3) go(integral_constant<int, 3>{}, integral_constant<int, 3>{}, integral_constant<int, 1>{});
+    else if (p.KH == 3) go(integral_constant<int, 3>{}, integral_constant<int, 1>{}, integral_constant<int, 2>{});
+    else if (p.KW == 3) go(integral_constant<int, 1>{}, integral_constant<int, 3>{}, integral_constant<int, 2>{});
+    else go(integral_constant<int, 1>{}, integral_constant<int, 1>{}, integral_constant<int, 2>{});
+  };
   if (plan->in_dtype == SYNO_F32) {
     const float* Gf = static_cast<const float*>(A);
     const float* Xf = static_cast<const float*>(B);
-    float* partf = static_cast<float*>(ws);
-    auto launchf = [&](auto kernel) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024) != hipSuccess)
-        return;
-      hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), p.lds_bytes, stream, p, Gf, Xf,
-                         p.n_splits == 1 ? static_cast<float*>(out) : partf);
-    };
-    auto by_vec = [&](auto kh_c, auto kw_c, auto ct_c) {
+    by_window([&](auto kh_c, auto kw_c, auto ct_c) {
       constexpr int kh = decltype(kh_c)::value, kw = decltype(kw_c)::value, ct = decltype(ct_c)::value;
-      if (p.W % 4 == 0) launchf(dw_mfma_f32<kh, kw, ct, 4>);
-      else if (p.W % 2 == 0) launchf(dw_mfma_f32<kh, kw, ct, 2>);
-      else launchf(dw_mfma_f32<kh, kw, ct, 1>);
-    };
-    using std::integral_constant;
-    if (p.KH == 3 && p.KW == 3) by_vec(integral_constant<int, 3>{}, integral_constant<int, 3>{}, integral_constant<int, 1>{});
-    else if (p.KH == 3) by_vec(integral_constant<int, 3>{}, integral_constant<int, 1>{}, integral_constant<int, 2>{});
-    else if (p.KW == 3) by_vec(integral_constant<int, 1>{}, integral_constant<int, 3>{}, integral_constant<int, 2>{});
-    else by_vec(integral_constant<int, 1>{}, integral_constant<int, 1>{}, integral_constant<int, 2>{});
-    if (p.n_splits == 1) {
-      // (written by the contraction itself)
-    } else if (p.n_splits > 4)
-      hipLaunchKernelGGL(dw_reduce_slots, dim3(p.n_tiles * p.slots), dim3(256), 0, stream, p,
-                         reinterpret_cast<const float4*>(partf), static_cast<float*>(out));
-    else
-      hipLaunchKernelGGL(dw_reduce_tiles, dim3(p.n_tiles * (p.slots / (p.KH * p.KW))), dim3(256), 0, stream, p,
-                         reinterpret_cast<const float4*>(partf), static_cast<float*>(out));
-    return hipGetLastError() == hipSuccess ? SYNO_OK : SYNO_ERR_HIP;
-  }
-  const uint16_t* G = static_cast<const uint16_t*>(A);
-  const uint16_t* X = static_cast<const uint16_t*>(B);
-  float* part = static_cast<float*>(ws);
-  auto launch = [&](auto kernel) {
-    // (once per instantiation would do; the attribute call is cheap next to the launch)
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024) != hipSuccess)
-      return;
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), p.lds_bytes, stream, p, G, X,
-                       p.n_splits == 1 ? static_cast<float*>(out) : part);
-  };
-  auto by_item = [&](auto kh_c, auto kw_c, auto ct_c) {
-    constexpr int kh = decltype(kh_c)::value, kw = decltype(kw_c)::value, ct = decltype(ct_c)::value;
-    if (p.W % 4 == 0) launch(dw_mfma_bf16<kh, kw, ct, 4>);
-    else if (p.W % 2 == 0) launch(dw_mfma_bf16<kh, kw, ct, 2>);
-    else launch(dw_mfma_bf16<kh, kw, ct, 1>);
-  };
-  {
-    using std::integral_constant;
-    if (p.KH == 3 && p.KW == 3) by_item(integral_constant<int, 3>{}, integral_constant<int, 3>{}, integral_constant<int, 1>{});
-    else if (p.KH == 3) by_item(integral_constant<int, 3>{}, integral_constant<int, 1>{}, integral_constant<int, 2>{});
-    else if (p.KW == 3) by_item(integral_constant<int, 1>{}, integral_constant<int, 3>{}, integral_constant<int, 2>{});
-    else by_item(integral_constant<int, 1>{}, integral_constant<int, 1>{}, integral_constant<int, 2>{});
+      if (p.W % 4 == 0) launch_dw_kernel(dw_mfma_f32<kh, kw, ct, 4>, grid, p, Gf, Xf, dst, stream);
+      else if (p.W % 2 == 0) launch_dw_kernel(dw_mfma_f32<kh, kw, ct, 2>, grid, p, Gf, Xf, dst, stream);
+      else launch_dw_kernel(dw_mfma_f32<kh, kw, ct, 1>, grid, p, Gf, Xf, dst, stream);
+    });
+  } else {
+    const uint16_t* G = static_cast<const uint16_t*>(A);
+    const uint16_t* X = static_cast<const uint16_t*>(B);
+    by_window([&](auto kh_c, auto kw_c, auto ct_c) {
+      constexpr int kh = decltype(kh_c)::value, kw = decltype(kw_c)::value, ct = decltype(ct_c)::value;
+      if (p.W % 4 == 0) launch_dw_kernel(dw_mfma_bf16<kh, kw, ct, 4>, grid, p, G, X, dst, stream);
+      else if (p.W % 2 == 0) launch_dw_kernel(dw_mfma_bf16<kh, kw, ct, 2>, grid, p, G, X, dst, stream);
+      else launch_dw_kernel(dw_mfma_bf16<kh, kw, ct, 1>, grid, p, G, X, dst, stream);
+    });
   }
   // many splits of a small dW: one block per slot keeps the device busy; few splits of a large dW: one block per
   // 16x16 tile with all its taps writes dW in whole lines
@@ -841,10 +831,10 @@ syno_status launch_mfma_dw(const syno_plan* plan, const void* A, const void* B, 
     // (written by the contraction itself)
   } else if (p.n_splits > 4)
     hipLaunchKernelGGL(dw_reduce_slots, dim3(p.n_tiles * p.slots), dim3(256), 0, stream, p,
-                       reinterpret_cast<const float4*>(part), static_cast<float*>(out));
+                       reinterpret_cast<const float4*>(ws), static_cast<float*>(out));
   else
     hipLaunchKernelGGL(dw_reduce_tiles, dim3(p.n_tiles * (p.slots / (p.KH * p.KW))), dim3(256), 0, stream, p,
-                       reinterpret_cast<const float4*>(part), static_cast<float*>(out));
+                       reinterpret_cast<const float4*>(ws), static_cast<float*>(out));
   return hipGetLastError() == hipSuccess ? SYNO_OK : SYNO_ERR_HIP;
 }
 

@@ -14,6 +14,8 @@
 // axis is a table walk, the result leaves as one vector store.  The loads follow whatever order the view imposes.
 #include <hip/hip_runtime.h>
 
+#include <cstring>
+
 #include <cstdlib>
 
 #include "plan.h"
@@ -31,6 +33,7 @@ struct ViewParams {
   int32_t n_free, free_off;      // sum points per output; start of the folded table over them (X; W at +tab_total)
   int32_t scratch_off;           // start (entries, a multiple of 4) of the waves' exchange areas behind the two tables
   int64_t n_runs;                // out elements / V
+  int32_t max_blocks;            // cap on the grid (the kernel walks the runs in a grid-stride loop)
 };
 
 __device__ __forceinline__ uint32_t div_magic(uint32_t n, uint32_t d, uint32_t magic) {
@@ -284,13 +287,7 @@ __global__ __launch_bounds__(kThreads) void view_stream(const ViewParams p, cons
 template <bool IBF, bool OBF, bool SCATTER>
 void launch_typed(const ViewParams& p, int V, size_t lds, const void* X, const void* W, void* out, hipStream_t s) {
   const int64_t blocks = (p.n_runs + kThreads - 1) / kThreads;
-  // SYNO_VIEW_WORKGROUPS overrides the cap on the grid (tuning aid)
-  static const int64_t cap = [] {
-    const char* e = getenv("SYNO_VIEW_WORKGROUPS");
-    const int64_t v = e ? atoll(e) : 0;
-    return v > 0 ? v : int64_t(256 * 8);
-  }();
-  const dim3 grid((unsigned)(blocks < cap ? blocks : cap));
+  const dim3 grid((unsigned)(blocks < p.max_blocks ? blocks : p.max_blocks));
   if (V == 4) hipLaunchKernelGGL((view_stream<4, IBF, OBF, SCATTER>), grid, dim3(kThreads), lds, s, p, X, W, out);
   else hipLaunchKernelGGL((view_stream<1, IBF, OBF, SCATTER>), grid, dim3(kThreads), lds, s, p, X, W, out);
 }
@@ -328,6 +325,8 @@ bool fill(const syno_plan* plan, ViewParams& p) {
   p.tab_total = total;
   p.n_runs = plan->out_elems / V;
   p.scratch_off = (2 * total + 3) & ~3;
+  // eight workgroups per compute unit is what the registers allow to be resident
+  p.max_blocks = plan->opt.view_workgroups > 0 ? plan->opt.view_workgroups : 256 * 8;
   return total > 0 && (size_t)total * 8 <= 48 * 1024 && p.n_runs < (int64_t(1) << 31);
 }
 
@@ -342,10 +341,20 @@ bool view_supports(const syno_plan* plan, int which) {
   return fill(plan, p);
 }
 
+void view_configure(syno_plan* plan, int which) {
+  ViewParams p;
+  Launch& L = plan->launch[which];
+  static_assert(sizeof(ViewParams) <= sizeof(L.params), "parameter record does not fit");
+  L.params_ready = fill(plan, p);
+  memcpy(L.params, &p, sizeof p);
+  L.workspace = 0;
+}
+
 // forward: A = X, B = W, out = result; backward-data: A = G, B = W, out = dX
 syno_status launch_view(const syno_plan* plan, int which, const void* A, const void* B, void* out, hipStream_t stream) {
+  if (!plan->launch[which].params_ready) return SYNO_ERR_UNSUPPORTED;
   ViewParams p;
-  if (!view_supports(plan, which) || !fill(plan, p)) return SYNO_ERR_UNSUPPORTED;
+  memcpy(&p, plan->launch[which].params, sizeof p);
   const int V = run_width(plan);
   // the two tables, then (runs of 4) three 256-entry exchange areas for each of the 4 waves
   const size_t lds = V == 4 ? (size_t)p.scratch_off * 4 + (kThreads / 64) * 3 * 256 * 4 : (size_t)p.tab_total * 8;

@@ -15,6 +15,8 @@
 // and are read as broadcasts; accumulation is fp32 in registers.
 #include <hip/hip_runtime.h>
 
+#include <cstring>
+
 #include <algorithm>
 
 #include "plan.h"
@@ -475,15 +477,20 @@ bool window_supports(const syno_plan* plan, int which) {
   return true;
 }
 
-size_t window_workspace(const syno_plan* plan, int which) {
-  if (which != SYNO_BWD_WEIGHT) return 0;
+void window_configure(syno_plan* plan, int which) {
   const SwParams p = fill(plan);
-  return sizeof(float) * (size_t)p.chunks * (size_t)p.w_elems;
+  Launch& L = plan->launch[which];
+  static_assert(sizeof(SwParams) <= sizeof(L.params), "parameter record does not fit");
+  memcpy(L.params, &p, sizeof p);
+  L.params_ready = true;
+  L.workspace = which == SYNO_BWD_WEIGHT ? sizeof(float) * (size_t)p.chunks * (size_t)p.w_elems : 0;
 }
 
 syno_status launch_window(const syno_plan* plan, int which, const void* A, const void* B, void* out, void* ws,
                           hipStream_t stream) {
-  const SwParams p = fill(plan);
+  if (!plan->launch[which].params_ready) return SYNO_ERR_UNSUPPORTED;
+  SwParams p;
+  memcpy(&p, plan->launch[which].params, sizeof p);
   const int V = run_width(plan->window);
   const bool ibf = plan->in_dtype == SYNO_BF16;
   const bool obf = which != SYNO_BWD_WEIGHT && plan->out_dtype == SYNO_BF16;

@@ -120,7 +120,7 @@ struct Launch {
   int32_t variant = 0;        // tile configuration index within the family
   size_t workspace = 0;
   // the family's kernel parameter record, filled when the plan is configured so that a launch only copies it
-  alignas(8) unsigned char params[384] = {};
+  alignas(8) unsigned char params[1536] = {};
   bool params_ready = false;
 };
 
@@ -132,6 +132,7 @@ struct syno_plan {
   int64_t x_shape[syno::kMaxAxes] = {}, w_shape[syno::kMaxAxes] = {}, out_shape[syno::kMaxAxes] = {};
   int64_t x_elems = 0, w_elems = 0, out_elems = 0, n_reduce = 0;
   syno_dtype in_dtype = SYNO_F32, out_dtype = SYNO_F32;
+  syno_plan_options opt{};      // the descriptor's overrides (all 0: the planner decides)
   // lowered forms
   syno::IndexProgram prog[3];
   bool conv_like = false;
@@ -154,6 +155,9 @@ struct OwnedDesc {
   std::vector<syno_prim> prims;
   std::vector<int32_t> xin, win;
   syno_dtype in_dtype = SYNO_F32, out_dtype = SYNO_F32;
+  syno_plan_options opt{};
+  bool has_opt = false;
+  // (the returned descriptor points into this object)
   syno_desc view() const {
     syno_desc d{};
     d.n_out = (int32_t)dims.size(); d.out_dims = dims.data();
@@ -161,6 +165,7 @@ struct OwnedDesc {
     d.n_in = (int32_t)xin.size(); d.input_coords = xin.data();
     d.n_w = (int32_t)win.size(); d.weight_coords = win.data();
     d.in_dtype = in_dtype; d.out_dtype = out_dtype;
+    d.options = has_opt ? &opt : nullptr;
     return d;
   }
 };
@@ -169,7 +174,7 @@ struct OwnedDesc {
 // Materialised reduction: cuts `desc` into stages (one stage when no cut lowers the count of multiply-adds);
 // weight_stage = the stage that keeps the graph's weight, every other stage has none.
 syno_status materialise(const syno_desc* desc, std::vector<OwnedDesc>& stages, int32_t& weight_stage);
-syno_status build_plan(const syno_desc* desc, int policy, syno_plan* plan, std::string* why);
+syno_status build_plan(const syno_desc* desc, syno_plan* plan, std::string* why);
 
 // kernels_generic.hip
 syno_status launch_generic(const syno_plan* p, int which, const void* A, const void* B, void* out,
@@ -184,12 +189,13 @@ bool bandwidth_supports(const syno_plan* p, int which);
 bool mfma_supports(const syno_plan* p, int which);
 // fills launch[which] (tile variant, workspace bytes) for the MFMA family
 void mfma_configure(syno_plan* p, int which);
-size_t bandwidth_workspace(const syno_plan* p, int which);
-// kernels_view.hip: Reduce-free graphs (forward only)
+void bandwidth_configure(syno_plan* p, int which);   // fills launch[which].params and .workspace
+// kernels_view.hip: separable gathers; view_configure fills launch[which].params
 bool view_supports(const syno_plan* p, int which);
+void view_configure(syno_plan* p, int which);
 // kernels_window.hip: the unreduced-window member of the bandwidth family
 bool window_supports(const syno_plan* p, int which);
-size_t window_workspace(const syno_plan* p, int which);
+void window_configure(syno_plan* p, int which);      // fills launch[which].params and .workspace
 // kernels_mfma_dw.hip: the backward-weight member of the MFMA family
 bool mfma_dw_supports(const syno_plan* p);
 void mfma_dw_configure(syno_plan* p);

@@ -944,6 +944,7 @@ bool cut_once(const OwnedDesc& whole, bool has_weight, OwnedDesc& top, OwnedDesc
   for (int c : g.in_coords) top.xin.push_back(remap[c]);
   if (best_top) for (int c : g.w_coords) top.win.push_back(remap[c]);
   top.in_dtype = whole.in_dtype; top.out_dtype = whole.in_dtype;
+  top.opt = whole.opt; top.has_opt = whole.has_opt;
   // bottom stage: the rest of the graph with its ids, reading Z
   bottom = OwnedDesc{};
   bottom.dims = whole.dims;
@@ -951,6 +952,7 @@ bool cut_once(const OwnedDesc& whole, bool has_weight, OwnedDesc& top, OwnedDesc
   bottom.xin.assign(best_z.begin(), best_z.end());
   if (!best_top) bottom.win = whole.win;
   bottom.in_dtype = whole.in_dtype; bottom.out_dtype = whole.out_dtype;
+  bottom.opt = whole.opt; bottom.has_opt = whole.has_opt;
   weight_on_top = best_top;
   // both halves must be valid graphs by themselves
   Graph gt, gb;
@@ -970,6 +972,7 @@ syno_status materialise(const syno_desc* desc, std::vector<OwnedDesc>& stages, i
   cur.xin.assign(desc->input_coords, desc->input_coords + desc->n_in);
   cur.win.assign(desc->weight_coords, desc->weight_coords + desc->n_w);
   cur.in_dtype = desc->in_dtype; cur.out_dtype = desc->out_dtype;
+  if (desc->options) { cur.opt = *desc->options; cur.has_opt = true; }
   stages.clear();
   weight_stage = -1;
   bool has_weight = true;     // `cur` still carries the graph's weight
@@ -987,7 +990,9 @@ syno_status materialise(const syno_desc* desc, std::vector<OwnedDesc>& stages, i
 }
 
 // ---------------------------------------------------------------------------------------------
-syno_status build_plan(const syno_desc* desc, int policy, syno_plan* plan, std::string* why) {
+syno_status build_plan(const syno_desc* desc, syno_plan* plan, std::string* why) {
+  if (desc->options) plan->opt = *desc->options;
+  const int policy = plan->opt.kernel_policy;
   Graph g;
   syno_status st = parse_graph(desc, g, why);
   if (st != SYNO_OK) return st;
@@ -1047,12 +1052,13 @@ syno_status build_plan(const syno_desc* desc, int policy, syno_plan* plan, std::
     // iterator is a real contraction: MFMA.  Everything else stays on the index-program kernels.
     if (plan->view.n_red == 0 && view_supports(plan, which)) {   // nothing is summed: a stream whatever else it looks like
       L.kernel = KERNEL_BW_VIEW;
+      view_configure(plan, which);
     } else if (bandwidth_supports(plan, which)) {
       L.kernel = KERNEL_BW_DEPTHWISE;
-      L.workspace = bandwidth_workspace(plan, which);
+      bandwidth_configure(plan, which);
     } else if (window_supports(plan, which)) {
       L.kernel = KERNEL_BW_WINDOW;
-      L.workspace = window_workspace(plan, which);
+      window_configure(plan, which);
     } else if (mfma_supports(plan, which)) {
       L.kernel = plan->in_dtype == SYNO_BF16 ? KERNEL_MFMA_BF16 : KERNEL_MFMA_F32;
       mfma_configure(plan, which);
@@ -1061,6 +1067,7 @@ syno_status build_plan(const syno_desc* desc, int policy, syno_plan* plan, std::
       mfma_dw_configure(plan);
     } else if (view_supports(plan, which)) {       // a few sum points per output and separable offsets: gather-and-add
       L.kernel = KERNEL_BW_VIEW;
+      view_configure(plan, which);
     }
   }
   // A matrix product is a 1x1 convolution with the operands' roles exchanged: W[k,j] is an "image" with k as
@@ -1082,8 +1089,9 @@ syno_status build_plan(const syno_desc* desc, int policy, syno_plan* plan, std::
       inner.n_out = 4; inner.out_dims = dims; inner.n_prim = 2; inner.prims = pr;
       inner.n_in = 4; inner.input_coords = xin; inner.n_w = 2; inner.weight_coords = win;
       inner.in_dtype = desc->in_dtype; inner.out_dtype = desc->out_dtype;
+      inner.options = desc->options;
       syno_plan* ip = new syno_plan();
-      if (build_plan(&inner, policy, ip, nullptr) == SYNO_OK) {
+      if (build_plan(&inner, ip, nullptr) == SYNO_OK) {
         const int map[3] = {SYNO_FWD, SYNO_BWD_WEIGHT, SYNO_BWD_DATA};
         bool any = false;
         for (int which = 0; which < 3; ++which) {

@@ -245,15 +245,17 @@ class ChainWorkload:
     flops: int                    # sum over the stages of 2 * prod(output iterators) * prod(Reduce sizes)
 
 
-def make_operator1(N, C, H, seed=0, bf16=False, Co=None, Wd=None, g=4, s=2, k1=3, with_grad=False) -> ChainWorkload:
+def make_operator1(N, C, H, seed=0, bf16=False, Co=None, Wd=None, g=4, s=2, k1=3, with_grad=False,
+                   out_f32=False) -> ChainWorkload:
     """Operator 1 of the paper (Fig. 7) as its two materialised stages, on a ResNet-style layer shape.
-    Weights ~ U(+-1/sqrt(fan_in)) per stage; the whole chain runs in one element type."""
+    Weights ~ U(+-1/sqrt(fan_in)) per stage; the whole chain runs in one element type (out_f32: bf16 inputs and
+    intermediate, fp32 result)."""
     Co = C if Co is None else Co
     Wd = H if Wd is None else Wd
     dt = BF16 if bf16 else F32
     D, Cg, C2 = Co // g // s, C // g, k1 * Co // s
     d1 = operator1_stage1(N, C, Co, H, Wd, g, s, k1, dt, dt)
-    d2 = operator1_stage2(N, Co, H, Wd, s, k1, dt, dt)
+    d2 = operator1_stage2(N, Co, H, Wd, s, k1, dt, F32 if out_f32 else dt)
     st = Stream(seed)
     xs, zs, os = (N, C, H, Wd), (N, D, g, k1, H, Wd), (N, Co, H, Wd)
     w1s, w2s = (D, g, Cg, k1), (Co, C2, k1, 1)

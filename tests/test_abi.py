@@ -169,11 +169,14 @@ def test_kernel_choice(syno):
     assert p.workspace_bytes(syno.FWD) == 0 and p.workspace_bytes(syno.BWD_DATA) > 0
     assert syno.Plan(wl.conv2d(32, 128, 128, 28, 28)).workspace_bytes(syno.BWD_DATA) == 128 * 128 * 9 * 4
     assert "grid=" in p.describe(syno.FWD)
-    syno.set_kernel_policy(1)
-    try:
-        assert all(n == "generic_index_program" for n in names(wl.strided_depthwise(2, 4, 7, 7)))
-    finally:
-        syno.set_kernel_policy(0)
+    # per-plan options: the generic kernels on request; a named tile variant of the contraction kernel
+    generic = syno.Plan(wl.strided_depthwise(2, 4, 7, 7), kernel_policy=1)
+    assert all(generic.kernel(i) == "generic_index_program" for i in range(3))
+    d = wl.conv2d(2, 128, 128, 28, 28)
+    for variant, rows in ((0, 4), (1, 8), (3, 4)):
+        p = syno.Plan(d, mfma_variant=variant + 1, mfma_rows=rows)
+        assert f"variant={variant} rows/block={rows} " in p.describe(syno.FWD)
+    assert "splits=2 " in syno.Plan(wl.grouped_shift_unfold(128), dw_workgroups=8).describe(syno.BWD_WEIGHT)
 
 
 def test_chain_plans_operator1_on_the_host(syno):

@@ -42,16 +42,12 @@ def tile_picks(plan, which, shape):
     return picks
 
 
-def run_all(syno, oracle, w, policy, directions=(0, 1, 2), full=True, n_sample=4096, seed=0):
+def run_all(syno, oracle, w, policy, directions=(0, 1, 2), full=True, n_sample=4096, seed=0, **options):
     """Run the requested directions on the GPU and compare with the checker: relative L2 error and a bound on
     every compared element (util.assert_close).  Without `full` the comparison is on a stratified sample: whole
     image planes at the first, last and tile-boundary images and channels, plus n_sample random elements.
     Returns kernel names."""
-    syno.set_kernel_policy(policy)
-    try:
-        plan = syno.Plan(w.desc)
-    finally:
-        syno.set_kernel_policy(0)
+    plan = syno.Plan(w.desc, kernel_policy=policy, **options)
     d, tol = w.desc, tol_for(w.desc)
     out_bf16 = d.out_dtype == BF16
     X, W = to_dev(w.X, w.X_bits), to_dev(w.W, w.W_bits)
@@ -144,6 +140,26 @@ def small_cases():
 @pytest.mark.parametrize("name", list(small_cases()))
 def test_small_cases_all_directions(syno, oracle, name, policy):
     run_all(syno, oracle, small_cases()[name](), policy)
+
+
+@pytest.mark.parametrize("variant,rows,order", [(0, 4, (1, 0, 2, 3)), (1, 3, (2, 3, 1, 0)), (2, 2, (0, 3, 2, 1)), (0, 1, (0, 1, 2, 3)),
+                                                (3, 4, (0, 1, 2, 3)), (11, 2, (0, 1, 2, 3))])
+def test_conv_f32_named_tile_variants(syno, oracle, variant, rows, order):
+    """Tile variants the planner's cost model does not pick at small sizes, named through the plan options:
+    the element-gathered weight staging (variants 0-2, any weight layout) and two of the 16-byte-staged ones."""
+    w = wl.make_conv(3, 24, 13, seed=20 + variant, Co=72, Wd=19, with_grad=True, w_order=order)
+    plan = syno.Plan(w.desc, mfma_variant=variant + 1, mfma_rows=rows)
+    assert f"variant={variant} rows/block={rows} " in plan.describe(syno.FWD)
+    run_all(syno, oracle, w, 0, directions=(0, 1), mfma_variant=variant + 1, mfma_rows=rows)
+
+
+@pytest.mark.parametrize("variant,rows", [(0, 4), (3, 3), (4, 2), (5, 1), (6, 4), (7, 4), (8, 2)])
+def test_conv_bf16_named_tile_variants(syno, oracle, variant, rows):
+    C = 40 if variant == 6 else 72          # (variant 6 holds the whole reduction in one chunk: at most 64 channels)
+    w = wl.make_conv(3, C, 13, seed=30 + variant, Co=40, Wd=19, bf16=True, with_grad=True, w_order=(0, 1, 2, 3))
+    plan = syno.Plan(w.desc, mfma_variant=variant + 1, mfma_rows=rows)
+    assert f"variant={variant} rows/block={rows} " in plan.describe(syno.FWD)
+    run_all(syno, oracle, w, 0, directions=(0, 1), mfma_variant=variant + 1, mfma_rows=rows)
 
 
 def test_table2_examples_and_odd_graphs(syno, oracle):
@@ -325,11 +341,7 @@ def run_chain(syno, oracle, w, policy):
     bf16 = w.descs[0].in_dtype == BF16
     q = (lambda a: bf16_bits_to_f32(to_bf16_bits(np.asarray(a, dtype=np.float32)))) if bf16 else None
     tol = chain_tol(w.descs[0])
-    syno.set_kernel_policy(policy)
-    try:
-        chain = syno.Chain(w.descs)
-    finally:
-        syno.set_kernel_policy(0)
+    chain = syno.Chain(w.descs, kernel_policy=policy)
     names = [[p.kernel(i) for i in range(3)] for p in chain.stages]
     print(f"[case] {w.descs[0].name} + {w.descs[1].name} kernels={names} policy={policy}", flush=True)
     X, G = to_dev(w.X, w.X_bits), to_dev(w.G, w.G_bits)
@@ -361,6 +373,14 @@ def run_chain(syno, oracle, w, policy):
     for a, b in zip(dWs, dWs2):
         assert torch.equal(a, b)
     return names
+
+
+def test_operator1_bf16_stages_fp32_result(syno, oracle):
+    """bf16 inputs and intermediate, fp32 result: the gradient between the stages is bf16 (what the first stage
+    reads), although the second stage's own backward-data type would be its fp32 output type."""
+    w = wl.make_operator1(3, 24, 13, seed=23, bf16=True, Co=32, Wd=19, g=4, s=2, with_grad=True, out_f32=True)
+    run_chain(syno, oracle, w, 0)
+    run_chain(syno, oracle, w, 1)
 
 
 @pytest.mark.parametrize("policy", [1, 0])
@@ -429,7 +449,7 @@ def test_operator1_full_size(syno, oracle, stage, bf16):
 # ------------------------------------------------------------------------------------------------
 # the materialised-reduction pass: one loop nest in, stages out, same result as the loop nest
 # ------------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("dt", ["f32", "bf16", "bf16_f32out"])
 @pytest.mark.parametrize("mk", [
     lambda i, o: wl.window_of_sums_1d(120, 3, 2, None, i, o),
     lambda i, o: wl.window_of_sums_1d(90, 5, 3, "k", i, o),
@@ -438,8 +458,7 @@ def test_operator1_full_size(syno, oracle, stage, bf16):
 ])
 def test_materialised_chain_equals_the_single_loop_nest(syno, oracle, mk, dt):
     """The checker evaluates the graph as written (one loop nest); the library cuts it into stages."""
-    t = F32 if dt == "f32" else BF16
-    d = mk(t, t)
+    d = mk(F32 if dt == "f32" else BF16, BF16 if dt == "bf16" else F32)
     chain = syno.Chain.materialized(d)
     assert len(chain.stages) >= 2
     xs, ws, _ = oracle.describe(d)

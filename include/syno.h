@@ -41,7 +41,8 @@ typedef enum {
   SYNO_ERR_SHAPE = 3,         /* an argument (index, count, selector) is out of range */
   SYNO_ERR_UNSUPPORTED = 4,   /* valid, but outside what the library lowers */
   SYNO_ERR_WORKSPACE = 5,     /* workspace required but NULL */
-  SYNO_ERR_HIP = 6            /* the HIP runtime reported an error at launch */
+  SYNO_ERR_HIP = 6,           /* the HIP runtime reported an error at launch */
+  SYNO_ERR_SCRATCH = 7        /* the call needs more scratch memory than the library's static buffer holds */
 } syno_status;
 
 typedef enum { SYNO_F32 = 0, SYNO_BF16 = 1 } syno_dtype;
@@ -127,6 +128,16 @@ syno_status syno_backward_data(const syno_plan* plan, const void* G, const void*
 /* dW[w] = sum over valid (o,r) with g(o,r)=w of G[o]*X[f(o,r)], fp32.  The adjoint in W. */
 syno_status syno_backward_weight(const syno_plan* plan, const void* X, const void* G, void* dW,
                                  void* workspace, hipStream_t stream);
+
+/* syno_backward_weight for callers that cannot allocate or pass device memory of their own (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the split partial sums live in a
+ * buffer inside the library, SYNO_STATIC_SCRATCH_BYTES of static device memory per GPU, instead of a caller's
+ * workspace.  Same result as syno_backward_weight, bit for bit.  Allocates nothing and never synchronises.
+ * SYNO_ERR_SCRATCH when syno_plan_workspace_bytes(plan, SYNO_BWD_WEIGHT) exceeds the buffer.  All calls on one
+ * GPU share the one buffer: calls that may overlap on a GPU (different streams or threads) race. */
+#define SYNO_STATIC_SCRATCH_BYTES (32u << 20)
+syno_status syno_backward_weight_static(const syno_plan* plan, const void* X, const void* G, void* dW,
+                                        hipStream_t stream);
 
 /* Bytes of device workspace call `which` needs (0: `workspace` may be NULL). */
 syno_status syno_plan_workspace_bytes(const syno_plan* plan, int which, size_t* bytes);

@@ -14,7 +14,7 @@ _LIB_PATH = os.path.join(_HERE, "libsyno.so")
 _lib = None
 
 EXPORTS = ("syno_plan_create", "syno_plan_destroy", "syno_forward", "syno_backward_data", "syno_backward_weight",
-           "syno_plan_workspace_bytes", "syno_plan_shapes", "syno_plan_kernel", "syno_plan_describe",
+           "syno_backward_weight_static", "syno_plan_workspace_bytes", "syno_plan_shapes", "syno_plan_kernel", "syno_plan_describe",
            "syno_plan_free_size", "syno_debug_gather", "syno_debug_gather_host", "syno_status_string",
            "syno_chain_create", "syno_chain_destroy", "syno_chain_stages", "syno_chain_plan",
            "syno_chain_workspace_bytes", "syno_chain_forward", "syno_chain_backward",
@@ -68,6 +68,7 @@ def load_library():
     lib.syno_plan_destroy.argtypes = [vp]
     for fn in (lib.syno_forward, lib.syno_backward_data, lib.syno_backward_weight):
         fn.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.syno_backward_weight_static.argtypes = [vp, vp, vp, vp, vp]
     lib.syno_plan_workspace_bytes.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
     lib.syno_plan_shapes.argtypes = [vp, i32p, i64p, i32p, i64p, i32p, i64p]
     lib.syno_plan_kernel.argtypes = [vp, ctypes.c_int]
@@ -233,6 +234,16 @@ class Plan:
     def backward_weight(self, X, G, dW=None, workspace=None):
         return self._call(load_library().syno_backward_weight, BWD_WEIGHT, X, self.x_shape, G, self.out_shape, dW,
                           self.w_shape, torch.float32, workspace, "syno_backward_weight")
+
+    def backward_weight_static(self, X, G, dW):
+        """syno_backward_weight on the library's static scratch memory; `dW` must be given (nothing is allocated)."""
+        px = self._arg(X, self.x_shape, self.in_dtype, "syno_backward_weight_static X")
+        pg = self._arg(G, self.out_shape, self.in_dtype, "syno_backward_weight_static G")
+        po = self._arg(dW, self.w_shape, torch.float32, "syno_backward_weight_static dW")
+        st = load_library().syno_backward_weight_static(self._h, px, pg, po, torch.cuda.current_stream(X.device).cuda_stream)
+        if st:
+            raise SynoError(st, "syno_backward_weight_static")
+        return dW
 
     def debug_gather_host(self, which: int, t_flat, q_flat):
         """Same maps as `debug_gather`, evaluated on the host (numpy int64 in, numpy int32 out)."""

@@ -45,7 +45,27 @@ std::string mfma_dw_describe(const syno_plan* p);
 // The value 1 in both element types, for stages without a weight: fp32 in word 0, bf16 in the low half of word 1.
 static __device__ __align__(16) uint32_t g_unit_words[4] = {0x3F800000u, 0x00003F80u, 0u, 0u};
 
+// Scratch memory of syno_backward_weight_static: one copy per GPU, held until the process ends.  In host code this
+// name is only a handle for hipGetSymbolAddress; kernels get the per-device address looked up below.
+static __device__ __align__(256) unsigned char scratch[SYNO_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+// Device address of `scratch` on the current device, looked up once per device with that device current.
+void* static_scratch() {
+  constexpr int kMaxDevices = 64;
+  static std::atomic<void*> cache[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void* p = cache[dev].load(std::memory_order_acquire);
+  if (!p) {
+    void* sym = nullptr;
+    if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || !sym) return nullptr;
+    p = sym;
+    cache[dev].store(p, std::memory_order_release);
+  }
+  return p;
+}
 
 // Device address of the constant one in element type `t` on the current device (each device has its own copy of
 // the array; the address is looked up once per device).
@@ -132,6 +152,20 @@ syno_status syno_backward_data(const syno_plan* plan, const void* G, const void*
 syno_status syno_backward_weight(const syno_plan* plan, const void* X, const void* G, void* dW, void* ws,
                                  hipStream_t stream) {
   // the lowered forms take the upstream gradient first
+  return run(plan, SYNO_BWD_WEIGHT, G, X, dW, ws, stream);
+}
+
+syno_status syno_backward_weight_static(const syno_plan* plan, const void* X, const void* G, void* dW,
+                                        hipStream_t stream) {
+  if (!plan || !X || !G || !dW) return SYNO_ERR_NULL;
+  const size_t need = plan->launch[SYNO_BWD_WEIGHT].workspace;
+  if (need > SYNO_STATIC_SCRATCH_BYTES) return SYNO_ERR_SCRATCH;
+  void* ws = nullptr;
+  if (need) {
+    ws = static_scratch();
+    if (!ws) return SYNO_ERR_HIP;
+  }
+  // (every kernel writes the part of the scratch it later reads, so nothing has to be cleared between calls)
   return run(plan, SYNO_BWD_WEIGHT, G, X, dW, ws, stream);
 }
 
@@ -349,6 +383,7 @@ const char* syno_status_string(syno_status s) {
     case SYNO_ERR_UNSUPPORTED: return "unsupported";
     case SYNO_ERR_WORKSPACE: return "workspace required";
     case SYNO_ERR_HIP: return "HIP runtime error";
+    case SYNO_ERR_SCRATCH: return "the call needs more scratch memory than the library's static buffer holds";
   }
   return "unknown status";
 }

@@ -14,7 +14,7 @@ LIB = os.path.join(HERE, "libsyno.so")
 
 SOURCES = ["planner.cpp", "api.cpp", "kernels_generic.hip", "kernels_bandwidth.hip", "kernels_window.hip", "kernels_view.hip", "kernels_mfma.hip",
            "kernels_mfma_f32_lo.hip", "kernels_mfma_f32_hi.hip", "kernels_mfma_bf16_f32out.hip",
-           "kernels_mfma_bf16_bf16out.hip", "kernels_mfma_dw.hip"]
+           "kernels_mfma_bf16_bf16out.hip", "kernels_mfma_dw.hip", "conv_rows_bf16.hip"]
 
 # packed-fp32 instruction selection is switched off for device code (host pass warns it does not know
 # the feature; harmless)
@@ -22,8 +22,17 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
-def _compile(src: str) -> str:
+def _headers():
+    import glob
+    return glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
+
+
+def _compile(src: str, incremental: bool = False) -> str:
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
+    if incremental and os.path.exists(obj):
+        deps = [os.path.join(CSRC, src), os.path.abspath(__file__)] + _headers()
+        if all(os.path.getmtime(d) <= os.path.getmtime(obj) for d in deps):
+            return obj
     cmd = ["hipcc", "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj] + FLAGS
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
@@ -34,14 +43,15 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build(jobs: int = 8) -> str:
+def build(jobs: int = 8, incremental: bool = False) -> str:
+    """Compiles every source (incremental: only what is older than its source or a header) and links libsyno.so."""
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
-        objs = list(ex.map(_compile, SOURCES))
+        objs = list(ex.map(lambda src: _compile(src, incremental), SOURCES))
     cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     subprocess.run(cmd, check=True)
     return LIB
 
 
 if __name__ == "__main__":
-    print(build())
+    print(build(incremental="--incremental" in sys.argv[1:]))

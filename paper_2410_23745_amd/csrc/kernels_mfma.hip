@@ -298,6 +298,7 @@ bool mfma_supports(const syno_plan* p, int which) {
   if (c.Wi != c.Wo || c.Hi != c.Ho) return false;
   if (c.ph >= c.KH || c.pw >= c.KW) return false;
   if (c.Og == 1 && c.Cg == 1) return false;          // no contraction to speak of
+  if (rows_supports(p, which)) return true;
   MfmaParams mp;
   for (int vi = 0; vi < num_variants(p->in_dtype == SYNO_BF16); ++vi)
     for (int TR = 1; TR <= c.N * c.Ho && TR * c.Wo <= 16 * 32; ++TR)
@@ -308,6 +309,8 @@ bool mfma_supports(const syno_plan* p, int which) {
 void mfma_configure(syno_plan* plan, int which) {
   const ConvLike& c = plan->conv;
   const bool bf = plan->in_dtype == SYNO_BF16;
+  // bf16 operators whose whole reduction fits LDS go to the row-streaming kernel (unless a tile variant is named)
+  if (bf && plan->opt.mfma_variant == 0 && rows_configure(plan, which)) return;
   double best = 1e300;
   int best_v = -1, best_tr = 0;
   MfmaParams mp;
@@ -332,6 +335,7 @@ void mfma_configure(syno_plan* plan, int which) {
 }
 
 std::string mfma_describe(const syno_plan* plan, int which) {
+  if (plan->launch[which].variant == -1) return rows_describe(plan, which);
   const int vi = plan->launch[which].variant / 4096, TR = plan->launch[which].variant % 4096;
   MfmaParams p;
   if (!fill_params(plan, which, vi, TR, p)) return "unconfigured";
@@ -347,6 +351,7 @@ syno_status launch_mfma(const syno_plan* plan, int which, const void* A, const v
                         hipStream_t stream) {
   const int vi = plan->launch[which].variant / 4096;
   if (!plan->launch[which].params_ready) return SYNO_ERR_UNSUPPORTED;
+  if (plan->launch[which].variant == -1) return launch_rows(plan, which, A, B, out, ws, stream);
   MfmaParams p;
   memcpy(&p, plan->launch[which].params, sizeof p);
   const bool obf = plan->out_dtype == SYNO_BF16;

@@ -196,6 +196,11 @@ void view_configure(syno_plan* p, int which);
 // kernels_window.hip: the unreduced-window member of the bandwidth family
 bool window_supports(const syno_plan* p, int which);
 void window_configure(syno_plan* p, int which);      // fills launch[which].params and .workspace
+// conv_rows_bf16.hip: the row-streaming member of the MFMA family (bf16, whole reduction in LDS)
+bool rows_supports(const syno_plan* p, int which);
+bool rows_configure(syno_plan* p, int which);
+std::string rows_describe(const syno_plan* p, int which);
+syno_status launch_rows(const syno_plan* p, int which, const void* A, const void* B, void* out, void* ws, hipStream_t stream);
 // kernels_mfma_dw.hip: the backward-weight member of the MFMA family
 bool mfma_dw_supports(const syno_plan* p);
 void mfma_dw_configure(syno_plan* p);

@@ -1,8 +1,8 @@
 """Run one workload a few times so that rocprofv3 can attribute kernel time and HBM counters to it.
 
-    rocprofv3 --kernel-trace --stats -- python3 -m paper_2410_23745_amd.profile_case config1_s0_f32 --iters 20
-    rocprofv3 --pmc FETCH_SIZE       -- python3 -m paper_2410_23745_amd.profile_case config1_s0_f32 --iters 5 --copy
-    rocprofv3 --pmc WRITE_SIZE       -- python3 -m paper_2410_23745_amd.profile_case config1_s0_f32 --iters 5 --copy
+    rocprofv3 --kernel-trace --stats -- python3 profile_case.py config1_s0_f32 --iters 20
+    rocprofv3 --pmc FETCH_SIZE       -- python3 profile_case.py config1_s0_f32 --iters 5 --copy
+    rocprofv3 --pmc WRITE_SIZE       -- python3 profile_case.py config1_s0_f32 --iters 5 --copy
 
 With --copy a plain device copy of a known size (256 MiB, `Tensor.copy_`) runs first; what FETCH_SIZE and
 WRITE_SIZE report for it gives the factor that turns the counters into bytes.
@@ -20,7 +20,7 @@ import argparse
 import os
 import sys
 
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 

@@ -16,7 +16,7 @@ TOL_ACC = 1e-5                 # rel-L2 of any fp32 result (fp32 or bf16 inputs 
 TOL_BF16_STORE = 4e-3          # rel-L2 of a bf16 result: half an ulp is at most 2^-8 of the value, 2^-9/sqrt(3) on average
 TOL_CHAIN_BF16 = 6e-3          # rel-L2 through stages whose intermediates are stored as bf16 (one-ulp flips carried on)
 RTOL_BF16_STORE = 2.0 ** -8    # per element: half a bf16 ulp relative to the value
-ACC_FACTOR = 8.0               # per element: |error| <= ACC_FACTOR * sqrt(terms) * U32 * sum|terms|
+ACC_FACTOR = 4.0               # per element: |error| <= ACC_FACTOR * sqrt(terms) * U32 * sum|terms|
                                # (a random walk of roundings, each at most U32 of a partial sum that never exceeds the
                                # sum of magnitudes, with a safety factor; one dropped or doubled term of typical size
                                # sum|terms|/terms is far outside it for every reduction length used here)

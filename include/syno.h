@@ -81,8 +81,9 @@ typedef struct {
  * decides).  They select among code paths that compute the same operator; none changes a result beyond
  * the summation order.  Read once, while the plan is built.
  *   kernel_policy   1: every pass runs on the generic index-program kernels
- *   mfma_variant    1 + index of the contraction kernel's tile variant (forward and backward-data);
- *                   mfma_rows = output rows per workgroup.  Ignored unless the pair fits the operator.
+ *   mfma_variant    1 + index of the contraction kernel's tile variant (forward and backward-data), or -1 for the
+ *                   row-streaming member of the family (bf16, at most 64 channels per group);
+ *                   mfma_rows = output rows per workgroup tile.  Ignored unless the pair fits the operator.
  *   mfma_taps       1: one window tap per inner step even where three would be taken
  *   dw_workgroups   target number of workgroups of the backward-weight contraction (split of the pixel axis)
  *   view_workgroups cap on the grid of the view kernel */

@@ -310,7 +310,7 @@ void mfma_configure(syno_plan* plan, int which) {
   const ConvLike& c = plan->conv;
   const bool bf = plan->in_dtype == SYNO_BF16;
   // bf16 operators whose whole reduction fits LDS go to the row-streaming kernel (unless a tile variant is named)
-  if (bf && plan->opt.mfma_variant == 0 && rows_configure(plan, which)) return;
+  if (bf && plan->opt.mfma_variant <= 0 && rows_configure(plan, which)) return;
   double best = 1e300;
   int best_v = -1, best_tr = 0;
   MfmaParams mp;

@@ -162,6 +162,30 @@ def test_conv_bf16_named_tile_variants(syno, oracle, variant, rows):
     run_all(syno, oracle, w, 0, directions=(0, 1), mfma_variant=variant + 1, mfma_rows=rows)
 
 
+ROWS_CASES = {
+    # (workload, rows per tile): the row-streaming bf16 kernel on shapes its default choice does not reach
+    "ragged_tiles_two_blocks": (lambda: wl.make_conv(3, 40, 13, seed=40, Co=72, Wd=19, bf16=True, with_grad=True), 5),
+    "channel_tail_packed": (lambda: wl.make_conv(2, 36, 11, seed=41, Co=20, Wd=16, bf16=True, with_grad=True), 4),
+    "permuted_weights": (lambda: wl.make_conv(2, 24, 9, seed=42, Co=40, Wd=12, bf16=True, with_grad=True, w_order=(2, 3, 1, 0)), 3),
+    "several_tiles_per_workgroup": (lambda: wl.make_conv(40, 16, 12, seed=43, Co=16, Wd=8, bf16=True, with_grad=True), 1),
+    "gshift_several_tiles": (lambda: wl.make_gshift(80, seeds=(4, 5, 6), with_grad=True, C=96, H=9, Wd=12, groups=3), 2),
+    "gshift_bf16_out": (lambda: wl.make_gshift(3, seeds=(7, 8, 9), with_grad=True, C=128, H=10, Wd=14, groups=2, out_bf16=True), 4),
+    "one_by_one": (lambda: wl.make_conv(3, 48, 9, seed=44, Co=80, Wd=20, K=1, bf16=True, with_grad=True), 6),
+}
+
+
+@pytest.mark.parametrize("name", list(ROWS_CASES))
+def test_conv_bf16_row_streaming_kernel(syno, oracle, name):
+    mk, rows = ROWS_CASES[name]
+    w = mk()
+    plan = syno.Plan(w.desc, mfma_variant=-1, mfma_rows=rows)
+    assert f"row-streaming rows/block={rows} " in plan.describe(syno.FWD), plan.describe(syno.FWD)
+    if "several_tiles" in name:
+        for which in (syno.FWD, syno.BWD_DATA):
+            assert "row-streaming" in plan.describe(which) and "tiles/workgroup=1 " not in plan.describe(which)
+    run_all(syno, oracle, w, 0, directions=(0, 1), mfma_variant=-1, mfma_rows=rows)
+
+
 def test_table2_examples_and_odd_graphs(syno, oracle):
     rng = np.random.default_rng(11)
     from test_abi import pixel_unshuffle_conv

@@ -172,6 +172,13 @@ syno_status syno_debug_gather(const syno_plan* plan, int which, const int64_t* t
 syno_status syno_debug_gather_host(const syno_plan* plan, int which, const int64_t* t_flat, const int64_t* q_flat,
                                    int64_t n, int32_t* a_off, int32_t* b_off);
 
+/* Measurement aid (not on any operator's path): a kernel of `workgroups` x 4 waves that only issues 16x16 MFMAs of
+ * the given input type, `iters` x 16 per wave, so that a benchmark can print the matrix-core rate the device
+ * sustains beside the datasheet peak.  `out` is a DEVICE array of workgroups*256 floats (overwritten); *flop
+ * receives the floating-point operations the launch performs. */
+syno_status syno_debug_mfma_rate(syno_dtype dtype, int32_t iters, int32_t workgroups, float* out, int64_t* flop,
+                                 hipStream_t stream);
+
 /* ---- Operators evaluated in stages ---------------------------------------------------------------
  * The materialised-reduction pass of the paper's code-generation section cuts a pGraph with several
  * weights into sub-graphs whose results are stored, so that a Reduce above a one-to-many primitive is

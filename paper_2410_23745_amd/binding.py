@@ -15,7 +15,7 @@ _lib = None
 
 EXPORTS = ("syno_plan_create", "syno_plan_destroy", "syno_forward", "syno_backward_data", "syno_backward_weight",
            "syno_backward_weight_static", "syno_plan_workspace_bytes", "syno_plan_shapes", "syno_plan_kernel", "syno_plan_describe",
-           "syno_plan_free_size", "syno_debug_gather", "syno_debug_gather_host", "syno_status_string",
+           "syno_plan_free_size", "syno_debug_mfma_rate", "syno_debug_gather", "syno_debug_gather_host", "syno_status_string",
            "syno_chain_create", "syno_chain_destroy", "syno_chain_stages", "syno_chain_plan",
            "syno_chain_workspace_bytes", "syno_chain_forward", "syno_chain_backward",
            "syno_chain_create_materialized", "syno_chain_weight_stage")
@@ -77,6 +77,7 @@ def load_library():
     lib.syno_plan_free_size.argtypes = [vp, ctypes.c_int, i64p]
     lib.syno_debug_gather.argtypes = [vp, ctypes.c_int, vp, vp, ctypes.c_int64, vp, vp, vp]
     lib.syno_debug_gather_host.argtypes = [vp, ctypes.c_int, vp, vp, ctypes.c_int64, vp, vp]
+    lib.syno_debug_mfma_rate.argtypes = [ctypes.c_int, ctypes.c_int32, ctypes.c_int32, vp, i64p, vp]
     lib.syno_status_string.argtypes = [ctypes.c_int]
     lib.syno_status_string.restype = ctypes.c_char_p
     vpp = ctypes.POINTER(vp)
@@ -223,6 +224,27 @@ class Plan:
             raise SynoError(st, what)
         return out
 
+    def bind(self, which: int, a, b, out, workspace=None):
+        """Checks the arguments of call `which` once and returns a function of no arguments that enqueues it on the
+        stream that is current NOW (for timing loops: the per-call marshalling is out of the way).  Operand order as
+        in forward / backward_data / backward_weight."""
+        shapes = ((self.x_shape, self.w_shape, self.out_shape, self.out_dtype),
+                  (self.out_shape, self.w_shape, self.x_shape, self.out_dtype),
+                  (self.x_shape, self.out_shape, self.w_shape, torch.float32))[which]
+        name = ("syno_forward", "syno_backward_data", "syno_backward_weight")[which]
+        pa = self._arg(a, shapes[0], self.in_dtype, name + " first input")
+        pb = self._arg(b, shapes[1], self.in_dtype, name + " second input")
+        po = self._arg(out, shapes[2], shapes[3], name + " output")
+        ws = self._workspace(which, a.device, workspace)
+        stream = torch.cuda.current_stream(a.device).cuda_stream
+        fn, h = getattr(load_library(), name), self._h
+
+        def launch():
+            st = fn(h, pa, pb, po, ws, stream)
+            if st:
+                raise SynoError(st, name)
+        return launch
+
     def forward(self, X, W, out=None, workspace=None):
         return self._call(load_library().syno_forward, FWD, X, self.x_shape, W, self.w_shape, out, self.out_shape,
                           self.out_dtype, workspace, "syno_forward")
@@ -277,6 +299,21 @@ class Plan:
         if st:
             raise SynoError(st, "syno_debug_gather")
         return a, b
+
+
+def mfma_rate(dtype: int, iters: int = 2000, workgroups: int = 512):
+    """(flop, launch) of the library's MFMA-only measurement kernel: `launch()` enqueues it on the current stream."""
+    lib = load_library()
+    out = torch.empty(workgroups * 256, dtype=torch.float32, device="cuda")
+    flop = ctypes.c_int64()
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def launch():
+        st = lib.syno_debug_mfma_rate(int(dtype), iters, workgroups, out.data_ptr(), ctypes.byref(flop), stream)
+        if st:
+            raise SynoError(st, "syno_debug_mfma_rate")
+    launch()
+    return flop.value, launch
 
 
 class _StageTypes:

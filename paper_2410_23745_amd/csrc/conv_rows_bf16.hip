@@ -315,6 +315,19 @@ __global__ __launch_bounds__(kThreads, 2) void conv_rows_bf16(const RowsParams p
           for (int u = 0; u < 4; ++u)
             acc[t][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, fa[ks & 1][t]),
                                                                 __builtin_bit_cast(bf16x8, fb[ks & 1][u]), acc[t][u], 0, 0, 0);
+        // issue order: one LDS read of the next k-step after each of the first MFMAs of this one, so that the
+        // fragments are in flight under the matrix work instead of being waited for right after their request
+        if constexpr (ks + 1 < KS) {
+          constexpr int NR = NTL + 4, NM = NTL * 4, NP = NR < NM ? NR : NM;
+#pragma unroll
+          for (int i = 0; i < NP; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
+          }
+          if constexpr (NR > NP) __builtin_amdgcn_sched_group_barrier(0x100, NR - NP, 0);
+          if constexpr (NM > NP) __builtin_amdgcn_sched_group_barrier(0x008, NM - NP, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);   // nothing moves across k-steps
       };
       read(std::integral_constant<int, 0>{}, fa[0], fb[0]);
       auto steps = [&](auto self, auto ks_c) -> void {      // k-steps 0 .. KS-1, unrolled at compile time

@@ -57,33 +57,34 @@ __host__ __device__ __forceinline__ bool run_ops(const IndexProgram& P, int lo, 
   for (int k = lo; k < hi; ++k) {
     const IndexOp o = P.ops[k];
     switch (o.kind) {
-      case OP_MULADD: v[o.d0] = v[o.a] * o.p0 + v[o.b]; break;
+      // (once a range test has failed the slots hold meaningless values; unsigned arithmetic keeps wrap-around defined)
+      case OP_MULADD: v[o.d0] = (int)((uint32_t)v[o.a] * (uint32_t)o.p0 + (uint32_t)v[o.b]); break;
       case OP_DIVMOD: {      // (operands are coordinates, 0 <= x < 2^31, whenever the term is still valid)
         const int x = v[o.a];
         const int q = (int)fast_div((uint32_t)x, (uint32_t)o.p0, (uint32_t)o.p1);
         v[o.d0] = q;
-        v[o.d1] = x - q * o.p0;
+        v[o.d1] = (int)((uint32_t)x - (uint32_t)q * (uint32_t)o.p0);
         break;
       }
       case OP_SHIFT:
         if (o.p2 == 0) {       // constant offset, already reduced mod p0: one conditional subtraction
-          const int x = v[o.a] + o.p1;
+          const int x = (int)((uint32_t)v[o.a] + (uint32_t)o.p1);
           v[o.d0] = x >= o.p0 ? x - o.p0 : x;
         } else {
-          v[o.d0] = (v[o.a] + o.p1 + o.p2 * v[o.b]) % o.p0;
+          v[o.d0] = (int)((uint32_t)v[o.a] + (uint32_t)o.p1 + (uint32_t)o.p2 * (uint32_t)v[o.b]) % o.p0;
         }
         break;
       case OP_ADDCHK: {
-        const int t = v[o.a] + o.p2 * v[o.b] + o.p1;
+        const int t = (int)((uint32_t)v[o.a] + (uint32_t)o.p2 * (uint32_t)v[o.b] + (uint32_t)o.p1);
         ok = ok && ((unsigned)t < (unsigned)o.p0);
         v[o.d0] = t;
         break;
       }
-      case OP_MUL: v[o.d0] = v[o.a] * o.p0; break;
+      case OP_MUL: v[o.d0] = (int)((uint32_t)v[o.a] * (uint32_t)o.p0); break;
       case OP_DIVCHK: {
         const int x = v[o.a];
         const int q = (int)fast_div((uint32_t)x, (uint32_t)o.p0, (uint32_t)o.p1);
-        ok = ok && x >= 0 && q * o.p0 == x;
+        ok = ok && x >= 0 && (int)((uint32_t)q * (uint32_t)o.p0) == x;
         v[o.d0] = q;
         break;
       }
@@ -93,9 +94,9 @@ __host__ __device__ __forceinline__ bool run_ops(const IndexProgram& P, int lo, 
 }
 
 __host__ __device__ __forceinline__ int dot(const AxisRef* ax, int n, const int* v) {
-  int off = 0;
-  for (int i = 0; i < n; ++i) off += v[ax[i].slot] * ax[i].stride;
-  return off;
+  uint32_t off = 0;
+  for (int i = 0; i < n; ++i) off += (uint32_t)v[ax[i].slot] * (uint32_t)ax[i].stride;
+  return (int)off;
 }
 
 // out[t] = sum over free points q of A[a(t,q)] * B[b(t,q)], fp32 accumulation in blocks of 64 terms.

@@ -304,3 +304,47 @@ def test_chain_entry_points_reject_bad_arguments_on_the_host(syno):
     bad = b.finish([0, 0], [])                                                         # coordinate consumed twice
     with pytest.raises(syno.SynoError):
         syno.Chain.materialized(bad)
+
+
+def test_random_graphs_index_maps_against_checker(syno, oracle):
+    """Seeded random primitive graphs: wherever both sides accept a graph, the forward index map agrees bit for bit
+    and both gradient enumerations list the checker's terms, each once.  A graph the checker rejects is rejected by
+    the library as well."""
+    import random
+    from test_host_sanitizers import random_graph
+    rng = random.Random(7)
+    both = 0
+    for _ in range(400):
+        d = random_graph(rng)
+        try:
+            xs, ws, red = oracle.describe(d)
+            valid = True
+        except oracle.OracleError:
+            valid = False
+        try:
+            p = syno.Plan(d)
+        except syno.SynoError as e:
+            assert e.status in (2, 4) and (valid or e.status == 2)      # invalid graphs: INVALID_DESC, not UNSUPPORTED
+            continue
+        assert valid, "the library accepted a graph the checker rejects"
+        n_o, n_r = int(np.prod(p.out_shape)), int(np.prod(red)) if red else 1
+        if n_o * n_r > 200000:
+            continue
+        both += 1
+        assert p.x_shape == xs and p.w_shape == ws
+        o, r = (a.ravel() for a in np.meshgrid(np.arange(n_o), np.arange(n_r), indexing="ij"))
+        xo, wo = oracle.gather_map(d, o, r)
+        a, b = p.debug_gather_host(syno.FWD, o, r)
+        assert np.array_equal(a, xo) and np.array_equal(b, wo)
+        ok = xo >= 0
+        terms = sorted(zip(o[ok].tolist(), xo[ok].tolist(), wo[ok].tolist()))
+        for which, n_t in ((syno.BWD_DATA, int(np.prod(p.x_shape))), (syno.BWD_WEIGHT, int(np.prod(p.w_shape)))):
+            if n_t * p.free_size(which) > 400000:
+                continue
+            t, q = (v.ravel() for v in np.meshgrid(np.arange(n_t), np.arange(p.free_size(which)), indexing="ij"))
+            a, b = p.debug_gather_host(which, t, q)
+            v = a >= 0
+            got = zip(a[v].tolist(), t[v].tolist(), b[v].tolist()) if which == syno.BWD_DATA else \
+                zip(a[v].tolist(), b[v].tolist(), t[v].tolist())
+            assert sorted(got) == terms
+    assert both >= 100

@@ -38,7 +38,8 @@ def _load():
         build()
         _lib = ctypes.CDLL(_LIB)
         for fn in ("oracle_describe", "oracle_forward", "oracle_forward_at", "oracle_backward",
-                   "oracle_gather_map", "oracle_threads"):
+                   "oracle_gather_map", "oracle_threads", "oracle_describe_more", "oracle_forward_multi",
+                   "oracle_backward_multi"):
             getattr(_lib, fn).restype = ctypes.c_int
     return _lib
 
@@ -65,6 +66,11 @@ def wire(desc) -> np.ndarray:
         words += [int(p.kind), ins[0], ins[1], outs[0], outs[1], int(p.param), int(p.shift_by), int(p.shift_coef)]
     words += [len(desc.input_coords)] + [int(c) for c in desc.input_coords]
     words += [len(desc.weight_coords)] + [int(c) for c in desc.weight_coords]
+    more = getattr(desc, "more_weights", None) or []
+    if more:
+        words.append(len(more))
+        for w in more:
+            words += [len(w)] + [int(c) for c in w]
     return np.asarray(words, dtype=np.int64)
 
 
@@ -85,6 +91,50 @@ def describe(desc):
     _check(_load().oracle_describe(_p(w, _I64P), ctypes.c_int64(len(w)), ctypes.byref(xr), _p(xs, _I64P),
                                    ctypes.byref(wr), _p(ws, _I64P), ctypes.byref(nr), _p(rs, _I64P)))
     return tuple(xs[:xr.value].tolist()), tuple(ws[:wr.value].tolist()), tuple(rs[:nr.value].tolist())
+
+
+def weight_shapes(desc):
+    """Shapes of all weights of an operator: the first one, then the further ones (operators with several weights)."""
+    w = wire(desc)
+    _, ws, _ = describe(desc)
+    n, ranks, shapes = ctypes.c_int64(), np.zeros(4, np.int64), np.zeros(64, np.int64)
+    _check(_load().oracle_describe_more(_p(w, _I64P), ctypes.c_int64(len(w)), ctypes.byref(n), _p(ranks, _I64P),
+                                        _p(shapes, _I64P)))
+    return [ws] + [tuple(shapes[16 * k:16 * k + ranks[k]].tolist()) for k in range(n.value)]
+
+
+def _ptr_array(arrays):
+    return (ctypes.c_void_p * len(arrays))(*[a.ctypes.data if a is not None else None for a in arrays])
+
+
+def forward_multi(desc, X, Ws) -> np.ndarray:
+    """out[o] = sum_r X[f] * prod_k W_k[g_k] for an operator with several weights (Fig. 7 of the paper)."""
+    w = wire(desc)
+    xs, _, _ = describe(desc)
+    shapes = weight_shapes(desc)
+    X = _f64(X)
+    Ws = [_f64(v) for v in Ws]
+    assert X.size == int(np.prod(xs)) and len(Ws) == len(shapes)
+    assert all(v.size == int(np.prod(s)) for v, s in zip(Ws, shapes)), "weight sizes do not match the pGraph"
+    out = np.empty(out_shape(desc), dtype=np.float64)
+    _check(_load().oracle_forward_multi(_p(w, _I64P), ctypes.c_int64(len(w)), _p(X, _F64P), _ptr_array(Ws), _p(out, _F64P)))
+    return out
+
+
+def backward_multi(desc, X, Ws, G):
+    """(dX, [dW_k]) of L = sum(out*G) for an operator with several weights."""
+    w = wire(desc)
+    xs, _, _ = describe(desc)
+    shapes = weight_shapes(desc)
+    X, G = _f64(X), _f64(G)
+    Ws = [_f64(v) for v in Ws]
+    assert X.size == int(np.prod(xs)) and G.size == int(np.prod(out_shape(desc))) and len(Ws) == len(shapes)
+    assert all(v.size == int(np.prod(s)) for v, s in zip(Ws, shapes))
+    dX = np.empty(xs, dtype=np.float64)
+    dWs = [np.empty(s, dtype=np.float64) for s in shapes]
+    _check(_load().oracle_backward_multi(_p(w, _I64P), ctypes.c_int64(len(w)), _p(X, _F64P), _ptr_array(Ws), _p(G, _F64P),
+                                         _p(dX, _F64P), _ptr_array(dWs)))
+    return dX, dWs
 
 
 def out_shape(desc):

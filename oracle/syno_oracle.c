@@ -33,7 +33,10 @@
  * Descriptor wire format (int64 words), private to this file and its Python wrapper:
  *   n_out, size[n_out],
  *   n_prim, n_prim x {kind, in0, in1, out0, out1, param, shift_by, shift_coef},
- *   n_in, coord[n_in], n_w, coord[n_w]
+ *   n_in, coord[n_in], n_w, coord[n_w] [, n_more, n_more x {n_wk, coord[n_wk]}]
+ * The optional tail lists further weights: an operator may multiply several weights (Operator 1 of the paper,
+ * Fig. 7, has two: each Share hands one copy of a coordinate to one of them).  Then
+ *     out[o] = sum_r X[f(o,r)] * W_0[g_0(o,r)] * W_1[g_1(o,r)] * ...
  * kind: 0 Split 1 Merge 2 Shift 3 Expand 4 Unfold 5 Stride 6 Reduce 7 Share.
  * Coordinate ids 0..n_out-1 are the output iterators; unused slots are -1.
  */
@@ -44,6 +47,7 @@
 #define MAXC 96
 #define MAXP 64
 #define MAXD 16
+#define MAXW 4
 
 enum { K_SPLIT = 0, K_MERGE, K_SHIFT, K_EXPAND, K_UNFOLD, K_STRIDE, K_REDUCE, K_SHARE };
 
@@ -67,6 +71,9 @@ typedef struct {
   prim_t prim[MAXP];
   int n_in, in_coord[MAXD];
   int n_w, w_coord[MAXD];
+  int n_more;                          /* further weights (the first one is w_coord) */
+  int m_n[MAXW], m_coord[MAXW][MAXD];
+  int64_t m_elems[MAXW], m_stride[MAXW][MAXD];
   /* derived */
   int64_t dom[MAXC];
   int n_red;
@@ -186,7 +193,24 @@ static int parse(const int64_t *d, int64_t len, op_t *op) {
     used[c] = 1;
     op->w_coord[i] = c;
   }
-  if (p != len) return ORACLE_ERR_FORMAT;
+  if (p != len) {                       /* further weights */
+    NEED(1);
+    op->n_more = (int)d[p++];
+    if (op->n_more < 1 || op->n_more > MAXW) return ORACLE_ERR_FORMAT;
+    for (int k = 0; k < op->n_more; ++k) {
+      NEED(1);
+      op->m_n[k] = (int)d[p++];
+      if (op->m_n[k] < 0 || op->m_n[k] > MAXD) return ORACLE_ERR_FORMAT;
+      NEED(op->m_n[k]);
+      for (int i = 0; i < op->m_n[k]; ++i) {
+        int c = (int)d[p++];
+        if (c < 0 || c >= MAXC || !defined[c] || used[c]) return ORACLE_ERR_COORD;
+        used[c] = 1;
+        op->m_coord[k][i] = c;
+      }
+    }
+    if (p != len) return ORACLE_ERR_FORMAT;
+  }
   for (int c = 0; c < MAXC; ++c)
     if (defined[c] && !used[c]) return ORACLE_ERR_COORD;   /* a coordinate nobody consumes */
   /* row-major strides of X and W */
@@ -200,6 +224,13 @@ static int parse(const int64_t *d, int64_t len, op_t *op) {
     op->w_stride[i] = op->w_elems;
     op->w_elems *= op->dom[op->w_coord[i]];
   }
+  for (int k = 0; k < op->n_more; ++k) {
+    op->m_elems[k] = 1;
+    for (int i = op->m_n[k] - 1; i >= 0; --i) {
+      op->m_stride[k][i] = op->m_elems[k];
+      op->m_elems[k] *= op->dom[op->m_coord[k][i]];
+    }
+  }
   return ORACLE_OK;
 #undef NEED
 }
@@ -212,7 +243,8 @@ static int64_t pos_mod(int64_t a, int64_t n) {
 /* Evaluate every coordinate for one point (o, r) of the loop nest, bottom-up (Table 1).
  * Returns 1 and the flat offsets into X and W if the term exists; 0 and both offsets -1 if
  * an Unfold on the path is out of range. */
-static int eval_point(const op_t *op, const int64_t *o, const int64_t *r, int64_t *x_off, int64_t *w_off) {
+static int eval_point_all(const op_t *op, const int64_t *o, const int64_t *r, int64_t *x_off, int64_t *w_off,
+                          int64_t *m_off) {
   int64_t val[MAXC];
   int valid = 1, nr = 0;
   for (int i = 0; i < op->n_out; ++i) val[i] = o[i];
@@ -258,7 +290,17 @@ static int eval_point(const op_t *op, const int64_t *o, const int64_t *r, int64_
   for (int i = 0; i < op->n_w; ++i) wo += val[op->w_coord[i]] * op->w_stride[i];
   *x_off = valid ? xo : -1;
   *w_off = valid ? wo : -1;
+  if (m_off)
+    for (int k = 0; k < op->n_more; ++k) {
+      int64_t mo = 0;
+      for (int i = 0; i < op->m_n[k]; ++i) mo += val[op->m_coord[k][i]] * op->m_stride[k][i];
+      m_off[k] = valid ? mo : -1;
+    }
   return valid;
+}
+
+static int eval_point(const op_t *op, const int64_t *o, const int64_t *r, int64_t *x_off, int64_t *w_off) {
+  return eval_point_all(op, o, r, x_off, w_off, NULL);
 }
 
 static void unflatten(int64_t flat, int n, const int64_t *size, int64_t *idx) {
@@ -292,6 +334,7 @@ int oracle_forward(const int64_t *desc, int64_t len, const double *X, const doub
   op_t op;
   int rc = parse(desc, len, &op);
   if (rc) return rc;
+  if (op.n_more) return ORACLE_ERR_FORMAT;     /* several weights: the _multi entry points */
 #pragma omp parallel for schedule(static)
   for (int64_t of = 0; of < op.n_o; ++of) {
     int64_t o[MAXD], r[MAXP], xo, wo;
@@ -312,6 +355,7 @@ int oracle_forward_at(const int64_t *desc, int64_t len, const double *X, const d
   op_t op;
   int rc = parse(desc, len, &op);
   if (rc) return rc;
+  if (op.n_more) return ORACLE_ERR_FORMAT;     /* several weights: the _multi entry points */
 #pragma omp parallel for schedule(static)
   for (int64_t s = 0; s < n; ++s) {
     int64_t o[MAXD], r[MAXP], xo, wo;
@@ -336,6 +380,7 @@ int oracle_backward(const int64_t *desc, int64_t len, const double *X, const dou
   op_t op;
   int rc = parse(desc, len, &op);
   if (rc) return rc;
+  if (op.n_more) return ORACLE_ERR_FORMAT;     /* several weights: the _multi entry points */
   if (dX) memset(dX, 0, sizeof(double) * (size_t)(x_pick ? n_x_pick : op.x_elems));
   if (dW) memset(dW, 0, sizeof(double) * (size_t)(w_pick ? n_w_pick : op.w_elems));
 #pragma omp parallel for schedule(static)
@@ -374,6 +419,7 @@ int oracle_gather_map(const int64_t *desc, int64_t len, const int64_t *o_flat, c
   op_t op;
   int rc = parse(desc, len, &op);
   if (rc) return rc;
+  if (op.n_more) return ORACLE_ERR_FORMAT;     /* several weights: the _multi entry points */
 #pragma omp parallel for schedule(static)
   for (int64_t s = 0; s < n; ++s) {
     int64_t o[MAXD], r[MAXP], xo, wo;
@@ -382,6 +428,80 @@ int oracle_gather_map(const int64_t *desc, int64_t len, const int64_t *o_flat, c
     eval_point(&op, o, r, &xo, &wo);
     x_off[s] = (int32_t)xo;
     w_off[s] = (int32_t)wo;
+  }
+  return ORACLE_OK;
+}
+
+/* ---- operators with several weights: W[0] is the first weight, W[1..] the further ones ------------------------ */
+
+/* Ranks and shapes of the further weights: shapes has room for MAXW x 16. */
+int oracle_describe_more(const int64_t *desc, int64_t len, int64_t *n_more, int64_t *ranks, int64_t *shapes) {
+  op_t op;
+  int rc = parse(desc, len, &op);
+  if (rc) return rc;
+  *n_more = op.n_more;
+  for (int k = 0; k < op.n_more; ++k) {
+    ranks[k] = op.m_n[k];
+    for (int i = 0; i < op.m_n[k]; ++i) shapes[16 * k + i] = op.dom[op.m_coord[k][i]];
+  }
+  return ORACLE_OK;
+}
+
+/* out[o] = sum_r X[f] * prod_k W_k[g_k]. */
+int oracle_forward_multi(const int64_t *desc, int64_t len, const double *X, const double *const *W, double *out) {
+  op_t op;
+  int rc = parse(desc, len, &op);
+  if (rc) return rc;
+#pragma omp parallel for schedule(static)
+  for (int64_t of = 0; of < op.n_o; ++of) {
+    int64_t o[MAXD], r[MAXP], xo, wo, mo[MAXW];
+    unflatten(of, op.n_out, op.out_size, o);
+    double acc = 0.0;
+    for (int64_t rf = 0; rf < op.n_r; ++rf) {
+      unflatten(rf, op.n_red, op.red_size, r);
+      if (!eval_point_all(&op, o, r, &xo, &wo, mo)) continue;
+      double t = X[xo] * W[0][wo];
+      for (int k = 0; k < op.n_more; ++k) t *= W[k + 1][mo[k]];
+      acc += t;
+    }
+    out[of] = acc;
+  }
+  return ORACLE_OK;
+}
+
+/* Scatter-form gradients of L = sum_o out[o]*G[o]: every valid term adds G[o] times the product of the other
+ * factors to dX and to each dW_k (any of which may be NULL). */
+int oracle_backward_multi(const int64_t *desc, int64_t len, const double *X, const double *const *W, const double *G,
+                          double *dX, double *const *dW) {
+  op_t op;
+  int rc = parse(desc, len, &op);
+  if (rc) return rc;
+  if (dX) memset(dX, 0, sizeof(double) * (size_t)op.x_elems);
+  if (dW && dW[0]) memset(dW[0], 0, sizeof(double) * (size_t)op.w_elems);
+  for (int k = 0; k < op.n_more; ++k)
+    if (dW && dW[k + 1]) memset(dW[k + 1], 0, sizeof(double) * (size_t)op.m_elems[k]);
+#pragma omp parallel for schedule(static)
+  for (int64_t of = 0; of < op.n_o; ++of) {
+    int64_t o[MAXD], r[MAXP], xo, wo, mo[MAXW];
+    unflatten(of, op.n_out, op.out_size, o);
+    const double g = G[of];
+    for (int64_t rf = 0; rf < op.n_r; ++rf) {
+      unflatten(rf, op.n_red, op.red_size, r);
+      if (!eval_point_all(&op, o, r, &xo, &wo, mo)) continue;
+      double f[MAXW + 2];                 /* the factors: X, W_0, W_1, ... */
+      int nf = 2 + op.n_more;
+      f[0] = X[xo]; f[1] = W[0][wo];
+      for (int k = 0; k < op.n_more; ++k) f[2 + k] = W[k + 1][mo[k]];
+      for (int i = 0; i < nf; ++i) {
+        double *dst = i == 0 ? dX : (dW ? dW[i - 1] : NULL);
+        if (!dst) continue;
+        double t = g;
+        for (int j = 0; j < nf; ++j) if (j != i) t *= f[j];
+        int64_t slot = i == 0 ? xo : (i == 1 ? wo : mo[i - 2]);
+#pragma omp atomic
+        dst[slot] += t;
+      }
+    }
   }
   return ORACLE_OK;
 }

@@ -45,6 +45,7 @@ class OpDesc:
     prims: List[Prim] = field(default_factory=list)
     input_coords: List[int] = field(default_factory=list)    # axes of X, row-major
     weight_coords: List[int] = field(default_factory=list)   # axes of W, row-major
+    more_weights: List[List[int]] = field(default_factory=list)   # axes of the further weights W_1, W_2, ... (usually none)
     in_dtype: int = F32                      # dtype of X, W and the upstream gradient G
     out_dtype: int = F32                     # dtype of out and dX (dW is always fp32)
     name: str = ""
@@ -104,9 +105,10 @@ class Builder:
         return a, b
 
     def finish(self, input_coords: Sequence[int], weight_coords: Sequence[int],
-               in_dtype: int = F32, out_dtype: int = F32) -> OpDesc:
+               in_dtype: int = F32, out_dtype: int = F32, more_weights: Sequence[Sequence[int]] = ()) -> OpDesc:
         self.desc.input_coords = [int(c) for c in input_coords]
         self.desc.weight_coords = [int(c) for c in weight_coords]
+        self.desc.more_weights = [[int(c) for c in w] for w in more_weights]
         self.desc.in_dtype = in_dtype
         self.desc.out_dtype = out_dtype
         return self.desc

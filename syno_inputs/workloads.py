@@ -149,6 +149,33 @@ def operator1_stage1(N, Cin, Co, H, W, g=4, s=2, k1=3, in_dtype=F32, out_dtype=F
     return b.finish([n, cin, h, ww], [d, gw, cw, kw], in_dtype, out_dtype)
 
 
+def operator1_graph(N, Cin, Co, H, W, g=4, s=2, k1=3, in_dtype=F32, out_dtype=F32) -> OpDesc:
+    """Operator 1 (Fig. 7) as ONE pGraph with two weights:
+    out[n,co,h,w] = sum_{d,gi,k,j,c'} X[n, gi*Cg+c', h+j-k1/2, w+k-k1/2] * w1[d,gi,c',k] * w2[co,d,gi,k,j].
+    The iterators gi and k reach X and both weights (two Shares each), d reaches the two weights only, j reaches X
+    and w2, c' reaches X and w1; co is matched to w2.  w2[co,d,gi,k,j] is the w2[Co, k1*Co/s, k1] of the staged form."""
+    D, Cg = Co // g // s, Cin // g
+    b = Builder([("n", N), ("co", Co), ("h", H), ("w", W)], name=f"op1_graph_C{Cin}_Co{Co}_g{g}_s{s}_{H}x{W}_N{N}")
+    n, co, h, w = range(4)
+    d = b.reduce(D)
+    d_w1, d_w2 = b.share(d)
+    gi = b.reduce(g)
+    gi_a, gi_w2 = b.share(gi)
+    gi_x, gi_w1 = b.share(gi_a)
+    k = b.reduce(k1)
+    k_a, k_w2 = b.share(k)
+    k_x, k_w1 = b.share(k_a)
+    j = b.reduce(k1)
+    j_x, j_w2 = b.share(j)
+    c = b.reduce(Cg)
+    c_x, c_w1 = b.share(c)
+    cin = b.split(gi_x, c_x)
+    hh = b.unfold(h, j_x)
+    ww = b.unfold(w, k_x)
+    return b.finish([n, cin, hh, ww], [d_w1, gi_w1, c_w1, k_w1], in_dtype, out_dtype,
+                    more_weights=[[co, d_w2, gi_w2, k_w2, j_w2]])
+
+
 def operator1_stage2(N, Co, H, W, s=2, k1=3, in_dtype=F32, out_dtype=F32) -> OpDesc:
     """Second stage of Operator 1: the first stage's axes (d,gi,k) flattened into k1*Co/s channels, a k1 x 1
     window along h, everything contracted with w2[Co, (k1*Co/s)*k1]."""

@@ -508,6 +508,54 @@ def test_operator1_stages_equal_single_two_weight_sum(oracle, N, Cin, Co, H, W, 
     np.testing.assert_allclose(Y, operator1_single_sum(X, w1, w2, g, k1), rtol=0, atol=1e-12)
 
 
+@pytest.mark.parametrize("N,Cin,Co,H,W,g,s,k1", [(1, 4, 8, 4, 5, 2, 2, 3), (2, 6, 6, 3, 4, 3, 1, 3),
+                                                 (1, 4, 4, 5, 3, 1, 2, 1), (1, 2, 4, 6, 6, 2, 1, 5)])
+def test_operator1_as_one_graph_with_two_weights(oracle, N, Cin, Co, H, W, g, s, k1):
+    """The checker's several-weight path on Operator 1 written as ONE pGraph (five Reduces, seven Shares, two
+    weights) against the explicit loops above, and its gradients against central differences (the operator is linear
+    in X, in w1 and in w2 separately, so a central difference is exact up to rounding) and the adjoint identities."""
+    d = wl.operator1_graph(N, Cin, Co, H, W, g, s, k1)
+    D, Cg = Co // g // s, Cin // g
+    assert oracle.describe(d)[0] == (N, Cin, H, W)
+    assert oracle.weight_shapes(d) == [(D, g, Cg, k1), (Co, D, g, k1, k1)]
+    X, w1, w2, G = rnd((N, Cin, H, W), 47), rnd((D, g, Cg, k1), 48), rnd((Co, D, g, k1, k1), 49), rnd((N, Co, H, W), 50)
+    out = oracle.forward_multi(d, X, [w1, w2])
+    np.testing.assert_allclose(out, operator1_single_sum(X, w1.reshape(D, Cin, k1), w2.reshape(Co, -1), g, k1), rtol=0, atol=1e-12)
+    dX, (dw1, dw2) = oracle.backward_multi(d, X, [w1, w2], G)
+    loss = lambda x, a, b: float((oracle.forward_multi(d, x, [a, b]) * G).sum())
+    L = loss(X, w1, w2)
+    for grad, arg in ((dX, 0), (dw1, 1), (dw2, 2)):
+        base = [X, w1, w2]
+        assert abs((grad * base[arg]).sum() - L) < 1e-9 * max(1.0, abs(L))     # L is linear in each factor
+        rng = np.random.default_rng(arg)
+        for _ in range(6):
+            i = tuple(rng.integers(0, n) for n in base[arg].shape)
+            e = np.zeros(base[arg].shape)
+            e[i] = 0.5
+            hi = [v + e if k == arg else v for k, v in enumerate(base)]
+            lo = [v - e if k == arg else v for k, v in enumerate(base)]
+            assert abs((loss(*hi) - loss(*lo)) - grad[i]) < 1e-9
+    # the single-weight entry points refuse a description with further weights rather than ignore them
+    with pytest.raises(oracle.OracleError):
+        oracle.forward(d, X, w1)
+
+
+def test_further_weight_of_ones_changes_nothing(oracle):
+    """A second weight that is the constant one leaves the single-weight result: the several-weight loop nest is the
+    single-weight one times further factors."""
+    one = wl.conv2d(2, 3, 2, 4, 5)
+    b = Builder([("n", 2), ("co", 2), ("h", 4), ("w", 5)])
+    c = b.reduce(3); cx, cw = b.share(c)
+    kh = b.reduce(3); khx, khw = b.share(kh)
+    kw = b.reduce(3); kwa, kwv = b.share(kw); kwx, kww = b.share(kwa)
+    two = b.finish([0, cx, b.unfold(2, khx), b.unfold(3, kwx)], [1, cw, khw, kww], more_weights=[[kwv]])
+    X, Wt = rnd((2, 3, 4, 5), 51), rnd((2, 3, 3, 3), 52)
+    v = rnd((3,), 53)
+    np.testing.assert_allclose(oracle.forward_multi(two, X, [Wt, np.ones(3)]), oracle.forward(one, X, Wt), rtol=0, atol=1e-13)
+    # and a real second weight along kw is the same as scaling the first along that axis
+    np.testing.assert_allclose(oracle.forward_multi(two, X, [Wt, v]), oracle.forward(one, X, Wt * v), rtol=0, atol=1e-13)
+
+
 def test_operator1_equals_library_convolutions(oracle):
     """Stage 1 is, per window position k, a grouped 1x1 convolution of X moved by k-k1/2 along w; stage 2 is a
     k1 x 1 convolution over the flattened (d,gi,k) channels.  Both from the library, in fp64."""

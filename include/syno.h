@@ -105,6 +105,10 @@ typedef struct {
   syno_dtype in_dtype;    /* element type of X, W and G */
   syno_dtype out_dtype;   /* element type of out and dX; accumulation is fp32; dW is always fp32 */
   const syno_plan_options* options;   /* NULL: defaults */
+  /* Further weights W_1, W_2, ... (Fig. 7: Operator 1 multiplies two): out[o] = sum_r X[f]*W[g]*W_1[g_1]*...
+   * more_weight_coords lists their axes one weight after the other, more_weight_ranks[i] axes each.  Such an
+   * operator is evaluated in stages (syno_chain_create_materialized); syno_plan_create refuses it. */
+  int32_t n_more_weights;  const int32_t* more_weight_ranks;  const int32_t* more_weight_coords;
 } syno_desc;
 
 /* Which of the three contractions a selector argument names. */
@@ -197,13 +201,20 @@ syno_status syno_chain_create(const syno_desc* stages, int32_t n_stages, syno_ch
 /* The materialised-reduction pass itself (code-generation section; its Fig. shows Y[i] = sum_{ik,is} X[..] cut
  * into Z = sum_is, Y = sum_ik Z): for every Reduce of ONE single-weight pGraph the primitives between it and the
  * tensors form a candidate first stage whose result Z is stored; the cut with the fewest multiply-adds is taken
- * when it beats the single loop nest, and the rest of the graph is cut again.  The chain has 1..8 stages; exactly
- * one of them (syno_chain_weight_stage) keeps the graph's weight, the others have none: in the W and dW arrays
- * of the forward and backward calls only that entry is read or written.  Graphs with a Shift that reads another
- * coordinate are left whole.  Intermediates take the graph's input element type. */
+ * when it beats the single loop nest, and the rest of the graph is cut again.  The chain has 1..8 stages; every
+ * stage has at most one weight (syno_chain_stage_weight; with a single-weight graph exactly one stage, also named by
+ * syno_chain_weight_stage, keeps it): in the W and dW arrays of the forward and backward calls only the entries of
+ * stages with a weight are read or written.  A graph with several weights must come apart into single-weight stages
+ * this way (a first stage takes a weight together with the Shares that feed it, followed as the graph writes them),
+ * else SYNO_ERR_UNSUPPORTED.  Graphs with a Shift that reads another coordinate are left whole.  Intermediates take
+ * the graph's input element type. */
 syno_status syno_chain_create_materialized(const syno_desc* desc, syno_chain** chain);
 /* Stage that takes the caller's weight, or -1 when every stage has its own (syno_chain_create). */
 int32_t syno_chain_weight_stage(const syno_chain* chain);
+/* Which of the graph's weights (0 = W, 1.. = the further ones) stage `stage` multiplies with, or -1 when it has
+ * none; chains from syno_chain_create: the stage's own index.  The W and dW arrays of the forward and backward calls
+ * are indexed by STAGE: entry i belongs to the weight this function names for stage i. */
+int32_t syno_chain_stage_weight(const syno_chain* chain, int32_t stage);
 syno_status syno_chain_destroy(syno_chain* chain);
 /* Number of stages, and the plan of one stage (borrowed; valid until the chain is destroyed; NULL when out of range). */
 int32_t syno_chain_stages(const syno_chain* chain);

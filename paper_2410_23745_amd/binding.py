@@ -18,7 +18,7 @@ EXPORTS = ("syno_plan_create", "syno_plan_destroy", "syno_forward", "syno_backwa
            "syno_plan_free_size", "syno_debug_mfma_rate", "syno_debug_gather", "syno_debug_gather_host", "syno_status_string",
            "syno_chain_create", "syno_chain_destroy", "syno_chain_stages", "syno_chain_plan",
            "syno_chain_workspace_bytes", "syno_chain_forward", "syno_chain_backward",
-           "syno_chain_create_materialized", "syno_chain_weight_stage")
+           "syno_chain_create_materialized", "syno_chain_weight_stage", "syno_chain_stage_weight")
 
 
 class _Dim(ctypes.Structure):
@@ -41,7 +41,9 @@ class _Desc(ctypes.Structure):
                 ("n_in", ctypes.c_int32), ("input_coords", ctypes.POINTER(ctypes.c_int32)),
                 ("n_w", ctypes.c_int32), ("weight_coords", ctypes.POINTER(ctypes.c_int32)),
                 ("in_dtype", ctypes.c_int), ("out_dtype", ctypes.c_int),
-                ("options", ctypes.POINTER(_Options))]
+                ("options", ctypes.POINTER(_Options)),
+                ("n_more_weights", ctypes.c_int32), ("more_weight_ranks", ctypes.POINTER(ctypes.c_int32)),
+                ("more_weight_coords", ctypes.POINTER(ctypes.c_int32))]
 
 
 class SynoError(RuntimeError):
@@ -85,6 +87,7 @@ def load_library():
     lib.syno_chain_destroy.argtypes = [vp]
     lib.syno_chain_create_materialized.argtypes = [ctypes.POINTER(_Desc), ctypes.POINTER(vp)]
     lib.syno_chain_weight_stage.argtypes = [vp]
+    lib.syno_chain_stage_weight.argtypes = [vp, ctypes.c_int32]
     lib.syno_chain_stages.argtypes = [vp]
     lib.syno_chain_plan.argtypes = [vp, ctypes.c_int32]
     lib.syno_chain_plan.restype = vp
@@ -119,10 +122,14 @@ def _marshal(desc, options=None):
     ic = (ctypes.c_int32 * max(1, len(desc.input_coords)))(*desc.input_coords)
     wc = (ctypes.c_int32 * max(1, len(desc.weight_coords)))(*desc.weight_coords)
     opt = _Options(**{k: int(v) for k, v in options.items()}) if options else None
+    more = [list(w) for w in (getattr(desc, "more_weights", None) or [])]
+    ranks = (ctypes.c_int32 * max(1, len(more)))(*[len(w) for w in more])
+    flat = [int(c) for w in more for c in w]
+    mc = (ctypes.c_int32 * max(1, len(flat)))(*flat)
     d = _Desc(len(desc.out_dims), dims, len(desc.prims), prims, len(desc.input_coords), ic,
               len(desc.weight_coords), wc, int(desc.in_dtype), int(desc.out_dtype),
-              ctypes.pointer(opt) if opt is not None else None)
-    return d, (dims, names, prims, ic, wc, opt)
+              ctypes.pointer(opt) if opt is not None else None, len(more), ranks, mc)
+    return d, (dims, names, prims, ic, wc, opt, ranks, mc)
 
 
 class Plan:
@@ -345,6 +352,8 @@ class Chain:
         self._h = handle
         n = lib.syno_chain_stages(self._h)
         self.weight_stage = lib.syno_chain_weight_stage(self._h)     # -1: every stage has its own weight
+        # per stage: which of the graph's weights it multiplies with (-1: none); W / dW lists are indexed by stage
+        self.stage_weight = [lib.syno_chain_stage_weight(self._h, i) for i in range(n)]
         if _materialize is not None:
             # stage i reads the graph's input type; only the last stage writes the graph's output type
             descs = [_StageTypes(_materialize.in_dtype, _materialize.in_dtype if i + 1 < n else _materialize.out_dtype)
@@ -360,7 +369,7 @@ class Chain:
         return cls(None, _materialize=desc, **options)
 
     def _own(self, i: int) -> bool:
-        return self.weight_stage < 0 or self.weight_stage == i
+        return self.stage_weight[i] >= 0
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None

@@ -23,6 +23,7 @@ struct syno_chain {
   // chains written by the materialised-reduction pass: the stage that keeps the graph's weight (-1: every stage
   // has its own); the other stages have none and multiply by the constant one below
   int32_t weight_stage = -1;
+  std::vector<int32_t> stage_weight;   // per stage: which of the graph's weights it takes (-1: none)
   ~syno_chain() {
     for (syno_plan* p : stage) delete p;
     for (syno_plan* p : bwd_data) delete p;
@@ -276,14 +277,19 @@ syno_status syno_chain_create_materialized(const syno_desc* desc, syno_chain** c
   *chain = nullptr;
   try {
     std::vector<syno::OwnedDesc> stages;
-    int32_t weight_stage = -1;
-    syno_status st = syno::materialise(desc, stages, weight_stage);
+    std::vector<int32_t> stage_weight;
+    syno_status st = syno::materialise(desc, stages, stage_weight);
     if (st != SYNO_OK) return st;
     std::vector<syno_desc> views;
     for (const syno::OwnedDesc& o : stages) views.push_back(o.view());
     // dX of the whole graph has the graph's output type, whatever type the first stage stores its result in
     st = chain_create(views.data(), (int32_t)views.size(), (int)desc->out_dtype, chain);
-    if (st == SYNO_OK) (*chain)->weight_stage = weight_stage;
+    if (st == SYNO_OK) {
+      (*chain)->stage_weight = stage_weight;
+      (*chain)->weight_stage = -1;
+      for (size_t i = 0; i < stage_weight.size(); ++i)
+        if (stage_weight[i] == 0) (*chain)->weight_stage = (int32_t)i;
+    }
     return st;
   } catch (...) {
     return SYNO_ERR_UNSUPPORTED;
@@ -291,6 +297,11 @@ syno_status syno_chain_create_materialized(const syno_desc* desc, syno_chain** c
 }
 
 int32_t syno_chain_weight_stage(const syno_chain* chain) { return chain ? chain->weight_stage : -1; }
+
+int32_t syno_chain_stage_weight(const syno_chain* chain, int32_t stage) {
+  if (!chain || stage < 0 || stage >= (int32_t)chain->stage.size()) return -1;
+  return chain->stage_weight.empty() ? stage : chain->stage_weight[(size_t)stage];
+}
 
 syno_status syno_chain_create(const syno_desc* stages, int32_t n_stages, syno_chain** chain) {
   if (!stages || !chain) return SYNO_ERR_NULL;
@@ -331,7 +342,7 @@ syno_status syno_chain_forward(const syno_chain* chain, const void* X, const voi
   const void* cur = X;
   for (size_t i = 0; i < n; ++i) {
     void* dst = i + 1 < n ? act[i] : out;
-    const bool own = chain->weight_stage < 0 || chain->weight_stage == (int32_t)i;
+    const bool own = chain->stage_weight.empty() || chain->stage_weight[i] >= 0;
     const void* Wi = own ? W[i] : unit_weight(chain->stage[i]->in_dtype);
     if (!Wi) return own ? SYNO_ERR_NULL : SYNO_ERR_HIP;
     const syno_status st = run(chain->stage[i], SYNO_FWD, cur, Wi, dst, workspace, stream);
@@ -356,7 +367,7 @@ syno_status syno_chain_backward(const syno_chain* chain, const void* X, const vo
   const void* g = G;
   for (size_t i = n; i-- > 0;) {
     const void* in = i == 0 ? X : act[i - 1];
-    const bool own = chain->weight_stage < 0 || chain->weight_stage == (int32_t)i;
+    const bool own = chain->stage_weight.empty() || chain->stage_weight[i] >= 0;
     const void* Wi = own ? W[i] : unit_weight(chain->stage[i]->in_dtype);
     if (!Wi) return own ? SYNO_ERR_NULL : SYNO_ERR_HIP;
     syno_status st = SYNO_OK;

@@ -154,6 +154,8 @@ struct OwnedDesc {
   std::vector<syno_dim> dims;
   std::vector<syno_prim> prims;
   std::vector<int32_t> xin, win;
+  std::vector<int32_t> more_ranks, more_flat;   // further weights, as in syno_desc
+  std::vector<int32_t> weight_ids;              // which of the original graph's weights `win` and the further ones are
   syno_dtype in_dtype = SYNO_F32, out_dtype = SYNO_F32;
   syno_plan_options opt{};
   bool has_opt = false;
@@ -166,14 +168,15 @@ struct OwnedDesc {
     d.n_w = (int32_t)win.size(); d.weight_coords = win.data();
     d.in_dtype = in_dtype; d.out_dtype = out_dtype;
     d.options = has_opt ? &opt : nullptr;
+    d.n_more_weights = (int32_t)more_ranks.size(); d.more_weight_ranks = more_ranks.data(); d.more_weight_coords = more_flat.data();
     return d;
   }
 };
 
 // planner.cpp
 // Materialised reduction: cuts `desc` into stages (one stage when no cut lowers the count of multiply-adds);
-// weight_stage = the stage that keeps the graph's weight, every other stage has none.
-syno_status materialise(const syno_desc* desc, std::vector<OwnedDesc>& stages, int32_t& weight_stage);
+// stage_weight[i] = which of the graph's weights stage i keeps (-1: none).
+syno_status materialise(const syno_desc* desc, std::vector<OwnedDesc>& stages, std::vector<int32_t>& stage_weight);
 syno_status build_plan(const syno_desc* desc, syno_plan* plan, std::string* why);
 
 // kernels_generic.hip

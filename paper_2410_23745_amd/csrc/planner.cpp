@@ -28,6 +28,7 @@ struct Graph {
   std::vector<int> slot;           // by coordinate id: value slot (Share copies share one)
   std::vector<syno_prim> prims;
   std::vector<int> in_coords, w_coords;
+  std::vector<std::vector<int>> more_w;   // further weights
   int n_slots = 0;
   std::vector<int64_t> slot_dom;
   std::vector<int> reduce_coords;  // in graph order
@@ -141,6 +142,20 @@ syno_status parse_graph(const syno_desc* d, Graph& g, std::string* why) {
     if (used[c]) return bad("coordinate consumed twice");
     used[c] = 1;
     g.w_coords.push_back(c);
+  }
+  if (d->n_more_weights < 0 || d->n_more_weights > 3) return bad("count of further weights");
+  if (d->n_more_weights && (!d->more_weight_ranks || !d->more_weight_coords)) return SYNO_ERR_NULL;
+  for (int k = 0, at = 0; k < d->n_more_weights; ++k) {
+    const int rank = d->more_weight_ranks[k];
+    if (rank < 0 || rank > kMaxAxes) return bad("rank of a further weight");
+    g.more_w.emplace_back();
+    for (int i = 0; i < rank; ++i) {
+      const int c = d->more_weight_coords[at++];
+      if (c < 0 || c >= kMaxCoordId || !defined[c]) return bad("W axis names an undefined coordinate");
+      if (used[c]) return bad("coordinate consumed twice");
+      used[c] = 1;
+      g.more_w.back().push_back(c);
+    }
   }
   for (int c = 0; c < kMaxCoordId; ++c)
     if (defined[c] && !used[c]) return bad("coordinate never consumed");
@@ -855,7 +870,8 @@ int64_t fold_width(int64_t N) {
 // ---------------------------------------------------------------------------------------------
 namespace {
 
-bool cut_once(const OwnedDesc& whole, bool has_weight, OwnedDesc& top, OwnedDesc& bottom, bool& weight_on_top) {
+// weight_on_top: index into `whole`'s weights (0 = win, 1.. = the further ones) of the weight the top stage takes, -1: none
+bool cut_once(const OwnedDesc& whole, OwnedDesc& top, OwnedDesc& bottom, int& weight_on_top) {
   const syno_desc d = whole.view();
   Graph g;
   if (parse_graph(&d, g, nullptr) != SYNO_OK) return false;
@@ -866,34 +882,74 @@ bool cut_once(const OwnedDesc& whole, bool has_weight, OwnedDesc& top, OwnedDesc
   for (int i = 0; i < g.n_out; ++i) out_points *= (double)g.D(i);
   for (int c : g.reduce_coords) all_red *= (double)g.D(c);
   const double before = out_points * all_red;
+  // the weights `whole` still carries (a stage cut off earlier may have taken the first one: then win is empty and
+  // there is no weight 0)
+  std::vector<const std::vector<int>*> weights;
+  const bool has_w0 = !whole.weight_ids.empty() && whole.weight_ids[0] >= 0;
+  weights.push_back(&g.w_coords);
+  for (const auto& w : g.more_w) weights.push_back(&w);
+  std::vector<int> weight_of(kMaxCoordId, -1);        // coordinate -> the weight it indexes
+  for (size_t wi = 0; wi < weights.size(); ++wi)
+    for (int c : *weights[wi]) weight_of[c] = (int)wi;
+  std::vector<int> producer(kMaxCoordId, -1);
+  for (int k = 0; k < n; ++k)
+    for (int t = 0; t < arity_out(g.prims[k].kind); ++t) producer[g.prims[k].out[t]] = k;
 
   double best = before;
   std::vector<char> best_c;
   std::vector<int> best_z;
-  bool best_top = false;
+  int best_w = -1;
   for (int r = 0; r < n; ++r) {
     if (g.prims[r].kind != SYNO_REDUCE) continue;
     std::vector<char> in_c(n, 0), coord_c(kMaxCoordId, 0);
     in_c[r] = 1; coord_c[g.prims[r].out[0]] = 1;
-    double red_c = (double)g.prims[r].param;
-    for (int k = r + 1; k < n; ++k) {
-      const syno_prim& p = g.prims[k];
-      bool touches = false;
-      for (int t = 0; t < arity_in(p.kind); ++t) touches |= coord_c[p.in[t]] != 0;
-      if (!touches) continue;
-      in_c[k] = 1;
-      for (int t = 0; t < arity_out(p.kind); ++t) coord_c[p.out[t]] = 1;
+    auto close = [&]() {           // every primitive that consumes a closure coordinate joins, with what it produces
+      for (int k = 0; k < n; ++k) {
+        if (in_c[k]) continue;
+        const syno_prim& p = g.prims[k];
+        bool touches = false;
+        for (int t = 0; t < arity_in(p.kind); ++t) touches |= coord_c[p.in[t]] != 0;
+        if (!touches) continue;
+        in_c[k] = 1;
+        for (int t = 0; t < arity_out(p.kind); ++t) coord_c[p.out[t]] = 1;
+      }
+    };
+    close();
+    auto touched = [&]() {         // the weight the closure reaches: -1 none, -2 more than one
+      int w = -1;
+      for (int c = 0; c < kMaxCoordId; ++c)
+        if (coord_c[c] && weight_of[c] >= 0) w = (w < 0 || w == weight_of[c]) ? weight_of[c] : -2;
+      return w;
+    };
+    int on_w = touched();
+    if (on_w == -2 || (on_w == 0 && !has_w0)) continue;
+    if (on_w >= 0 && weights.size() > 1) {
+      // several weights: the stage that multiplies with this weight also takes the Shares that hand the weight its
+      // other coordinates, when their second copy goes on towards the data (not straight into another weight), and
+      // with them whatever consumes that copy
+      bool grown = true;
+      while (grown) {
+        grown = false;
+        for (int c : *weights[on_w]) {
+          if (coord_c[c]) continue;
+          const int k = producer[c];
+          if (k < 0 || g.prims[k].kind != SYNO_SHARE) continue;
+          const int other = g.prims[k].out[0] == c ? g.prims[k].out[1] : g.prims[k].out[0];
+          if (weight_of[other] >= 0) continue;
+          in_c[k] = 1; coord_c[g.prims[k].out[0]] = coord_c[g.prims[k].out[1]] = 1;
+          close();
+          grown = true;
+        }
+      }
+      if (touched() != on_w) continue;
     }
-    bool on_top = false;
-    for (int c : g.w_coords) on_top |= coord_c[c] != 0;
-    if (on_top && !has_weight) continue;
+    double red_c = 1;
+    for (int k = 0; k < n; ++k)
+      if (in_c[k] && g.prims[k].kind == SYNO_REDUCE) red_c *= (double)g.prims[k].param;
     // axes of Z, in the order of X's axes: an axis the closure does not produce passes through, one it produces
     // is replaced by the coordinates that enter the closure below it
     std::vector<int> z;
     std::vector<char> seen(kMaxCoordId, 0);
-    std::vector<int> producer(kMaxCoordId, -1);
-    for (int k = 0; k < n; ++k)
-      for (int t = 0; t < arity_out(g.prims[k].kind); ++t) producer[g.prims[k].out[t]] = k;
     auto add = [&](int c) { if (!seen[c]) { seen[c] = 1; z.push_back(c); } };
     std::vector<int> stack;
     auto below = [&](int axis) {
@@ -908,7 +964,7 @@ bool cut_once(const OwnedDesc& whole, bool has_weight, OwnedDesc& top, OwnedDesc
       }
     };
     for (int c : g.in_coords) below(c);
-    if (on_top) for (int c : g.w_coords) below(c);
+    if (on_w >= 0) for (int c : *weights[on_w]) below(c);
     // every coordinate entering the closure from below must have been found (it is, through X or W, unless the
     // closure ends in an Expand, which has no top side)
     bool complete = true;
@@ -921,7 +977,7 @@ bool cut_once(const OwnedDesc& whole, bool has_weight, OwnedDesc& top, OwnedDesc
     for (int c : z) z_points *= (double)g.D(c);
     if (z_points > (double)kMaxElems) continue;
     const double after = z_points * red_c + out_points * (all_red / red_c);
-    if (after < best) { best = after; best_c = in_c; best_z = z; best_top = on_top; }
+    if (after < best) { best = after; best_c = in_c; best_z = z; best_w = on_w; }
   }
   if (best_c.empty()) return false;
 
@@ -942,18 +998,30 @@ bool cut_once(const OwnedDesc& whole, bool has_weight, OwnedDesc& top, OwnedDesc
   }
   if (next > kMaxCoordId) return false;
   for (int c : g.in_coords) top.xin.push_back(remap[c]);
-  if (best_top) for (int c : g.w_coords) top.win.push_back(remap[c]);
+  if (best_w >= 0) for (int c : *weights[best_w]) top.win.push_back(remap[c]);
+  top.weight_ids.assign(1, best_w >= 0 ? whole.weight_ids[best_w] : -1);
   top.in_dtype = whole.in_dtype; top.out_dtype = whole.in_dtype;
   top.opt = whole.opt; top.has_opt = whole.has_opt;
-  // bottom stage: the rest of the graph with its ids, reading Z
+  // bottom stage: the rest of the graph with its ids, reading Z; it keeps the other weights
   bottom = OwnedDesc{};
   bottom.dims = whole.dims;
   for (int k = 0; k < n; ++k) if (!best_c[k]) bottom.prims.push_back(g.prims[k]);
   bottom.xin.assign(best_z.begin(), best_z.end());
-  if (!best_top) bottom.win = whole.win;
+  bottom.weight_ids.assign(1, -1);
+  for (size_t wi = 0; wi < weights.size(); ++wi) {
+    if ((int)wi == best_w || (wi == 0 && !has_w0)) continue;
+    if (bottom.weight_ids[0] < 0 && bottom.win.empty() && bottom.more_ranks.empty()) {
+      bottom.win.assign(weights[wi]->begin(), weights[wi]->end());
+      bottom.weight_ids[0] = whole.weight_ids[wi];
+    } else {
+      bottom.more_ranks.push_back((int32_t)weights[wi]->size());
+      bottom.more_flat.insert(bottom.more_flat.end(), weights[wi]->begin(), weights[wi]->end());
+      bottom.weight_ids.push_back(whole.weight_ids[wi]);
+    }
+  }
   bottom.in_dtype = whole.in_dtype; bottom.out_dtype = whole.out_dtype;
   bottom.opt = whole.opt; bottom.has_opt = whole.has_opt;
-  weight_on_top = best_top;
+  weight_on_top = best_w;
   // both halves must be valid graphs by themselves
   Graph gt, gb;
   const syno_desc dt = top.view(), db = bottom.view();
@@ -962,7 +1030,7 @@ bool cut_once(const OwnedDesc& whole, bool has_weight, OwnedDesc& top, OwnedDesc
 
 }  // namespace
 
-syno_status materialise(const syno_desc* desc, std::vector<OwnedDesc>& stages, int32_t& weight_stage) {
+syno_status materialise(const syno_desc* desc, std::vector<OwnedDesc>& stages, std::vector<int32_t>& stage_weight) {
   Graph g;
   const syno_status st = parse_graph(desc, g, nullptr);
   if (st != SYNO_OK) return st;
@@ -971,20 +1039,27 @@ syno_status materialise(const syno_desc* desc, std::vector<OwnedDesc>& stages, i
   cur.prims.assign(desc->prims, desc->prims + desc->n_prim);
   cur.xin.assign(desc->input_coords, desc->input_coords + desc->n_in);
   cur.win.assign(desc->weight_coords, desc->weight_coords + desc->n_w);
+  cur.weight_ids.assign(1, 0);
+  for (size_t k = 0; k < g.more_w.size(); ++k) {
+    cur.more_ranks.push_back((int32_t)g.more_w[k].size());
+    cur.more_flat.insert(cur.more_flat.end(), g.more_w[k].begin(), g.more_w[k].end());
+    cur.weight_ids.push_back((int32_t)k + 1);
+  }
   cur.in_dtype = desc->in_dtype; cur.out_dtype = desc->out_dtype;
   if (desc->options) { cur.opt = *desc->options; cur.has_opt = true; }
   stages.clear();
-  weight_stage = -1;
-  bool has_weight = true;     // `cur` still carries the graph's weight
+  stage_weight.clear();
   while (stages.size() + 1 < 8) {
     OwnedDesc top, bottom;
-    bool on_top = false;
-    if (!cut_once(cur, has_weight, top, bottom, on_top)) break;
-    if (on_top) { weight_stage = (int32_t)stages.size(); has_weight = false; }
+    int on_top = -1;
+    if (!cut_once(cur, top, bottom, on_top)) break;
+    stage_weight.push_back(top.weight_ids[0]);
     stages.push_back(std::move(top));
     cur = std::move(bottom);
   }
-  if (has_weight) weight_stage = (int32_t)stages.size();
+  // what is left is the last stage; it may keep one weight
+  if (!cur.more_ranks.empty()) return SYNO_ERR_UNSUPPORTED;      // several weights that did not come apart
+  stage_weight.push_back(cur.weight_ids[0]);
   stages.push_back(std::move(cur));
   return SYNO_OK;
 }
@@ -997,6 +1072,7 @@ syno_status build_plan(const syno_desc* desc, syno_plan* plan, std::string* why)
   syno_status st = parse_graph(desc, g, why);
   if (st != SYNO_OK) return st;
   auto unsupported = [&](const char* m) { if (why) *why = m; return SYNO_ERR_UNSUPPORTED; };
+  if (!g.more_w.empty()) return unsupported("an operator with several weights is evaluated in stages");
 
   plan->in_dtype = desc->in_dtype;
   plan->out_dtype = desc->out_dtype;

@@ -508,6 +508,40 @@ def test_materialised_chain_equals_the_single_loop_nest(syno, oracle, mk, dt):
     assert e <= tol, f"dW rel-L2 {e:.3e} > {tol}"
 
 
+@pytest.mark.parametrize("dt", ["f32", "bf16", "bf16_f32out"])
+@pytest.mark.parametrize("shape", [(3, 24, 32, 13, 19, 4, 2, 3), (2, 16, 16, 9, 10, 2, 1, 3), (2, 8, 8, 6, 7, 1, 2, 5)])
+def test_operator1_single_graph_with_two_weights(syno, oracle, shape, dt):
+    """Operator 1 handed over as ONE pGraph with two weights: the library's materialised-reduction pass cuts it into
+    the two single-weight stages of the paper's listing; the checker evaluates the single two-weight loop nest."""
+    N, Cin, Co, H, W, g, s_, k1 = shape
+    d = wl.operator1_graph(N, Cin, Co, H, W, g, s_, k1, F32 if dt == "f32" else BF16, BF16 if dt == "bf16" else F32)
+    with pytest.raises(syno.SynoError) as e:
+        syno.Plan(d)                    # several weights: only as stages
+    assert e.value.status == 4
+    chain = syno.Chain.materialized(d)
+    assert len(chain.stages) == 2 and chain.stage_weight == [0, 1]
+    D, Cg = Co // g // s_, Cin // g
+    assert chain.stages[0].w_shape == (D, g, Cg, k1) and chain.stages[1].w_shape == (Co, D, g, k1, k1)
+    st = wl.Stream(71)
+    from syno_inputs.rng import bf16_bits_to_f32, to_bf16_bits
+    q = (lambda a: bf16_bits_to_f32(to_bf16_bits(np.asarray(a, dtype=np.float32)))) if dt != "f32" else (lambda a: np.asarray(a, dtype=np.float32))
+    X, G = q(st.normal((N, Cin, H, W))), q(st.normal((N, Co, H, W)))
+    w1, w2 = q(st.uniform_pm(1.0 / np.sqrt(Cg), (D, g, Cg, k1))), q(st.uniform_pm(1.0 / np.sqrt(D * g * k1 * k1), (Co, D, g, k1, k1)))
+    dev = lambda a: to_dev(a, to_bf16_bits(a) if dt != "f32" else None)
+    Xd, Gd, Ws = dev(X), dev(G), [dev(w1), dev(w2)]
+    tol = chain_tol(d)
+    out, acts = chain.forward(Xd, Ws)
+    torch.cuda.synchronize()
+    e_out = rel_l2(to_host(out), oracle.forward_multi(d, X, [w1, w2]))
+    dX, dWs = chain.backward(Xd, Ws, acts, Gd)
+    torch.cuda.synchronize()
+    rdx, rdws = oracle.backward_multi(d, X, [w1, w2], G)
+    errs = [e_out, rel_l2(to_host(dX), rdx)] + [rel_l2(to_host(a), b) for a, b in zip(dWs, rdws)]
+    print(f"[case] {d.name} {dt}: kernels {[p.kernel(0) for p in chain.stages]} rel-L2 out/dX/dW1/dW2 = "
+          + "/".join(f"{v:.2e}" for v in errs), flush=True)
+    assert max(errs) <= tol, errs
+
+
 # ------------------------------------------------------------------------------------------------
 # pure views (no Reduce) and small gather-and-add operators: the table-driven streaming kernel forwards, index
 # programs backwards

@@ -348,3 +348,39 @@ def test_random_graphs_index_maps_against_checker(syno, oracle):
                 zip(a[v].tolist(), b[v].tolist(), t[v].tolist())
             assert sorted(got) == terms
     assert both >= 100
+
+
+def test_two_weight_graph_is_cut_into_single_weight_stages(syno, oracle):
+    """Operator 1 as one pGraph with two weights (host only): refused as a single plan, cut by the materialised-
+    reduction pass into the stage that multiplies with w1 (it takes the Shares feeding w1 along) and the stage that
+    multiplies with w2; the stages' shapes are the checker's weight shapes."""
+    d = wl.operator1_graph(2, 16, 16, 6, 8, 4, 2, 3)
+    with pytest.raises(syno.SynoError) as e:
+        syno.Plan(d)
+    assert e.value.status == 4
+    chain = syno.Chain.materialized(d)
+    assert chain.stage_weight == [0, 1] and chain.weight_stage == 0
+    shapes = oracle.weight_shapes(d)
+    assert [p.w_shape for p in chain.stages] == shapes
+    assert chain.stages[0].x_shape == (2, 16, 6, 8) and chain.stages[1].out_shape == (2, 16, 6, 8)
+    assert chain.stages[0].out_shape == chain.stages[1].x_shape
+    # multiply-adds: the two stages together cost less than the single loop nest
+    pts = lambda p: int(np.prod(p.out_shape)) * p.free_size(syno.FWD)
+    single = 2 * 16 * 6 * 8 * (2 * 4 * 3 * 3 * 4)
+    assert sum(pts(p) for p in chain.stages) < single
+    # a chain given as explicit stages names each stage's own weight
+    w = wl.make_operator1(2, 16, 12, g=4, s=2)
+    assert syno.Chain(w.descs).stage_weight == [0, 1]
+    # Shares written the other way round (the copy for w1 handed out first) do not come apart: refused, not mis-cut
+    b = Builder([("i", 6)])
+    r = b.reduce(4)
+    ra, rw1 = b.share(r)
+    rx, rw2 = b.share(ra)
+    k = b.reduce(3)
+    kx, kw2 = b.share(k)
+    two = b.finish([rx, b.unfold(0, kx)], [rw1], more_weights=[[rw2, kw2]])
+    try:
+        c = syno.Chain.materialized(two)
+        assert all(sw in (-1, 0, 1) for sw in c.stage_weight) and sorted(x for x in c.stage_weight if x >= 0) == [0, 1]
+    except syno.SynoError as e2:
+        assert e2.status == 4

@@ -11,7 +11,8 @@ Cases: config0, config1_s{0..3}_{f32|bf16}, config2, config3, config4_{fwd|bwd_d
 passes of the first two shapes with a seeded output gradient: config1t_s{0..3}_{f32|bf16}_{fwd|bwd_data|bwd_weight},
 config3t_{fwd|bwd_data|bwd_weight}; Operator 1 (two stages) on a ResNet-18 stage shape: op1_s{0..3}_{f32|bf16}_{fwd|bwd}; the GPT-2 QKV projection as a matrix product:
 qkv_{f32|bf16}_{fwd|bwd_data|bwd_weight}; the two pure views of the benchmark (102.8 MB in and out, random values):
-view_{shift|unshuffle}_{fwd|bwd_data}.
+view_{shift|unshuffle}_{fwd|bwd_data}; the library's MFMA-only loop (nothing but matrix instructions on every
+SIMD: the reading that "always busy" gives for the matrix-unit counters): mfma_rate_{f32|bf16}.
 Buffers rotate over several copies so that every launch reads HBM rather than the last-level cache.
 """
 from __future__ import annotations
@@ -79,6 +80,15 @@ def main() -> int:
         if bits is not None:
             return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
         return torch.from_numpy(np.ascontiguousarray(vals, dtype=np.float32)).to(dev)
+
+    if args.case.startswith("mfma_rate_"):
+        from syno_inputs import F32
+        flop, launch = syno.mfma_rate(BF16 if args.case.endswith("bf16") else F32, iters=2000, workgroups=1024)
+        for _ in range(args.iters):
+            launch()
+        torch.cuda.synchronize()
+        print(f"{args.case}: {flop} flop per launch; {args.iters + 1} launches")
+        return 0
 
     if args.case.startswith("op1_s"):       # op1_s<stage>_<f32|bf16>_<fwd|bwd>
         from syno_inputs import workloads as wl

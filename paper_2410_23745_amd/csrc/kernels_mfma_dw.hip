@@ -46,6 +46,11 @@ struct DwParams {
   int32_t items;                       // 64 * n_xrows * W/2 dword items per tensor per chunk
   uint32_t magic_w2, magic_rw2;        // ceil(2^32/d) for d = items per row and n_xrows * items per row (0 for d = 1)
   int32_t lds_x_off, lds_tab_off, lds_bytes;
+  // fp32 kernel for windows with a row extent (chunks inside one image, source rows affine in the staged row):
+  int32_t direct;                      // that kernel takes this plan
+  int32_t g_items, x_items;            // staging items per chunk of G (64 channels x TRK rows) and X (32*ct x n_xrows)
+  int32_t ngi, nxi, ni;                // items per thread of G and of X; the instantiation's bound
+  uint32_t magic_gr, magic_cpi;        // ceil(2^32/d) for d = TRK * items per row and d = cpi (0 for d = 1)
 };
 
 namespace {
@@ -306,12 +311,105 @@ __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint
       for (int t = 0; t < T; ++t) dst[((ao * CT + i) * T + t) * 64] = acc[ao][i][t];
 }
 
+// The k-steps of one staged chunk: 4 pixels each; the fragments of the next step are read while the MFMAs of the
+// current one issue (one wave per SIMD here, so nothing else would cover the LDS latency).
+template <int KH, int KW, int CT>
+__device__ __forceinline__ void dw_f32_chunk(const DwParams& p, const float* gl, const float* xl, const int (&a_base)[2],
+                                             const int (&b_base)[CT], floatx4 (&acc)[2][CT][KH * KW], int first = 0,
+                                             int stride = 1) {
+  constexpr int T = KH * KW;
+    const int steps = p.CP >> 2;
+    auto read = [&](int st, float (&a)[2], float (&b)[CT * T]) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) a[i] = gl[a_base[i] + st * 4];
+#pragma unroll
+      for (int i = 0; i < CT; ++i)
+#pragma unroll
+        for (int kh = 0; kh < KH; ++kh)
+#pragma unroll
+          for (int t = 0; t < KW; ++t) b[i * T + kh * KW + t] = xl[b_base[i] + st * 4 + kh * p.pitch + t];
+    };
+    auto mfmas = [&](const float (&a)[2], const float (&b)[CT * T]) {
+#pragma unroll
+      for (int i = 0; i < CT; ++i)
+#pragma unroll
+        for (int t = 0; t < T; ++t)
+#pragma unroll
+          for (int ao = 0; ao < 2; ++ao)
+            acc[ao][i][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[ao], b[i * T + t], acc[ao][i][t], 0, 0, 0);
+    };
+    auto interleave = [&]() {       // (left to the compiler when a step has only a handful of MFMAs)
+      if constexpr (CT * T >= 6)
+#pragma unroll
+      for (int i = 0; i < CT * T; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);     // 2 MFMAs
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // 1 LDS read
+      }
+    };
+    // the wave takes steps first, first + stride, ... (waves that share an output tile split the steps between them)
+    float fa0[2], fb0[CT * T], fa1[2], fb1[CT * T];
+    int st = first;
+    if (st >= steps) return;
+    read(st, fa0, fb0);
+    for (; st + 2 * stride < steps; st += 2 * stride) {
+      // one fragment read of the next step after every second MFMA of the current one: the reads issue in the
+      // shadow of the matrix pipe and a whole step lies between a fragment's read and its use
+      read(st + stride, fa1, fb1); mfmas(fa0, fb0); interleave();
+      read(st + 2 * stride, fa0, fb0); mfmas(fa1, fb1); interleave();
+    }
+    if (st + stride < steps) { read(st + stride, fa1, fb1); mfmas(fa0, fb0); mfmas(fa1, fb1); }
+    else mfmas(fa0, fb0);
+  }
+
+// Leaves the workgroup's sums: in dW itself when there is one split, else in the workspace in accumulator layout.
+template <int KH, int KW, int CT>
+__device__ __forceinline__ void dw_f32_finish(const DwParams& p, float* __restrict__ partial, int g, int ob, int cb, int split,
+                                              int widx, int lane, const floatx4 (&acc)[2][CT][KH * KW]) {
+  constexpr int CX = 32 * CT, T = KH * KW;
+  const int wo = widx >> 1, wc = widx & 1;
+  // One split only (large dW, few pixels): nothing to add up, the sums go straight into dW (`partial` is dW then):
+  // lane holds 4 consecutive o (rows of D) at one c (column).
+  if (p.n_splits == 1) {
+    float* dw = partial + (int64_t)g * p.ws_g;
+#pragma unroll
+    for (int ao = 0; ao < 2; ++ao)
+#pragma unroll
+      for (int i = 0; i < CT; ++i) {
+        const int c = cb * CX + (CT * wc + i) * 16 + (lane & 15);
+        if (c >= p.Cg) continue;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int o = ob * 64 + (2 * wo + ao) * 16 + 4 * (lane >> 4) + v;
+          if (o >= p.Og) continue;
+#pragma unroll
+          for (int t = 0; t < T; ++t)
+            dw[(int64_t)o * p.ws_o + (int64_t)c * p.ws_c + (t / KW) * p.ws_kh + (t % KW) * p.ws_kw] = acc[ao][i][t][v];
+        }
+      }
+    return;
+  }
+  // partial[split][tile][slot][lane]: every accumulator register quadruple goes out as it is, one 16-byte store
+  // per lane (1 KB per wave and slot); the reduction kernel knows which weights a (slot, lane) holds
+  constexpr int SLOTS = 8 * CT * T;
+  const int tile = (g * p.n_oblk + ob) * p.n_cblk + cb;
+  floatx4* dst = reinterpret_cast<floatx4*>(partial) +
+                 ((int64_t)split * p.n_tiles + tile) * (SLOTS * 64) + (widx * 2 * CT * T) * 64 + lane;
+#pragma unroll
+  for (int ao = 0; ao < 2; ++ao)
+#pragma unroll
+    for (int i = 0; i < CT; ++i)
+#pragma unroll
+      for (int t = 0; t < T; ++t) dst[((ao * CT + i) * T + t) * 64] = acc[ao][i][t];
+}
+
 // fp32 inputs: the same contraction with v_mfma_f32_16x16x4_f32, whose K-step is 4 consecutive pixels (lane ->
 // row l%16, pixel l/16).  Operands are single dwords, so a tap is any element shift and nothing has to be cut;
 // staging moves items of VEC adjacent pixels of a row (4 when W is a multiple of 4, else 2 or 1), at most
 // kF32Items per thread and tensor, which wait in registers while the previous chunk is computed.
 constexpr int kF32Items = 18;     // staging items per thread, tensor and chunk
 constexpr int kGuardF = 4;       // zero floats in front of each X channel row
+constexpr int kRowsItems = 7;    // (per thread of 512)
+constexpr int kRowsThreads = 512;   // staging items per thread and tensor of the kernel for windows with a row extent
 
 template <int KH, int KW, int CT, int VEC>
 __global__ __launch_bounds__(256) void dw_mfma_f32(const DwParams p, const float* __restrict__ Gt,
@@ -451,72 +549,199 @@ __global__ __launch_bounds__(256) void dw_mfma_f32(const DwParams p, const float
     if (more) rows_of(q + 1, next);
     __syncthreads();
     if (more) load(next);
-    // k-steps of 4 pixels; the fragments of the next step are read while the MFMAs of the current one issue
-    // (one wave per SIMD here, so nothing else would cover the LDS latency)
-    const int steps = p.CP >> 2;
-    auto read = [&](int st, float (&a)[2], float (&b)[CT * T]) {
-#pragma unroll
-      for (int i = 0; i < 2; ++i) a[i] = gl[a_base[i] + st * 4];
-#pragma unroll
-      for (int i = 0; i < CT; ++i)
-#pragma unroll
-        for (int kh = 0; kh < KH; ++kh)
-#pragma unroll
-          for (int t = 0; t < KW; ++t) b[i * T + kh * KW + t] = xl[b_base[i] + st * 4 + kh * p.pitch + t];
-    };
-    auto mfmas = [&](const float (&a)[2], const float (&b)[CT * T]) {
-#pragma unroll
-      for (int i = 0; i < CT; ++i)
-#pragma unroll
-        for (int t = 0; t < T; ++t)
-#pragma unroll
-          for (int ao = 0; ao < 2; ++ao)
-            acc[ao][i][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[ao], b[i * T + t], acc[ao][i][t], 0, 0, 0);
-    };
-    float fa0[2], fb0[CT * T], fa1[2], fb1[CT * T];
-    read(0, fa0, fb0);
-    int st = 0;
-    for (; st + 2 < steps; st += 2) {
-      read(st + 1, fa1, fb1); mfmas(fa0, fb0);
-      read(st + 2, fa0, fb0); mfmas(fa1, fb1);
-    }
-    if (st + 1 < steps) { read(st + 1, fa1, fb1); mfmas(fa0, fb0); mfmas(fa1, fb1); }
-    else mfmas(fa0, fb0);
+    dw_f32_chunk<KH, KW, CT>(p, gl, xl, a_base, b_base, acc);
   }
+  dw_f32_finish<KH, KW, CT>(p, partial, g, ob, cb, split, widx, lane, acc);
+}
 
-  // One split only (large dW, few pixels): nothing to add up, the sums go straight into dW (`partial` is dW then):
-  // lane holds 4 consecutive o (rows of D) at one c (column).
-  if (p.n_splits == 1) {
-    float* dw = partial + (int64_t)g * p.ws_g;
+// fp32, windows with a row extent (KH = 3).  A chunk is TRK rows of ONE image, so the source of staged row r is
+// row h0 + r of G and row h0 - 1 + r of X: one uniform base per chunk and tensor plus an offset that a thread works
+// out once for each of its items.  Nothing is looked up per chunk, every load is a uniform base plus a 32-bit lane
+// offset, and the requests of a chunk go out back to back.  G and X have item lists of their own (64 x TRK rows and
+// 32*CT x (TRK + 2) rows of W/VEC items).  Rows that a chunk does not have (the halo above the first and below the
+// last row of an image, the missing rows of an image's last chunk) are loaded from a safe address and written to LDS
+// as zeros; a chunk in the interior of an image has none, and takes a path without any of these tests.  With a whole
+// image per chunk the halo rows never carry data: their items are retired at set-up and LDS keeps its zeros.
+// Items that never carry data (beyond the item count, channels beyond the group) load from a safe address and write to
+// 16 bytes of LDS that nobody reads.
+template <int KW, int CT, int VEC, int NI>
+__global__ __launch_bounds__(kRowsThreads) void dw_rows_f32(const DwParams p, const float* __restrict__ Gt,
+                                                   const float* __restrict__ Xt, float* __restrict__ partial) {
+  constexpr int KH = 3, CX = 32 * CT, T = KH * KW;
+  extern __shared__ __align__(16) unsigned char smem[];
+  float* gl = reinterpret_cast<float*>(smem);                   // [64][CPg]
+  float* xl = reinterpret_cast<float*>(smem + p.lds_x_off);     // [32*CT][CPp], data starts at kGuardF
+  const uint32_t dump = (uint32_t)p.lds_tab_off;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int widx = wave & 3, half = wave >> 2;     // waves w and w + 4 share an output tile and take alternate k-steps
+  const int wo = widx >> 1, wc = widx & 1;
+  int bid = blockIdx.x;
+  const int split = bid % p.n_splits; bid /= p.n_splits;
+  const int cb = bid % p.n_cblk; bid /= p.n_cblk;
+  const int ob = bid % p.n_oblk;
+  const int g = bid / p.n_oblk;
+  const int chunk_begin = split * p.chunks_per_split;
+  const int chunk_end = min(p.n_chunks, chunk_begin + p.chunks_per_split);
+  {
+    uint4* z = reinterpret_cast<uint4*>(smem);
+    const int n16 = p.lds_tab_off >> 4;
+    for (int i = tid; i < n16; i += kRowsThreads) z[i] = make_uint4(0, 0, 0, 0);
+  }
+  const int o_lim = p.Og - ob * 64, c_lim = min(p.Cg - cb * CX, CX);
+  const float* Gg = Gt + (int64_t)(g * p.Og + ob * 64) * p.plane;
+  const float* Xg = Xt + (int64_t)(g * p.Cg + cb * CX) * p.plane;
+
+  floatx4 acc[2][CT][T];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < CT; ++b)
+#pragma unroll
+      for (int t = 0; t < T; ++t) acc[a][b][t] = floatx4{0.f, 0.f, 0.f, 0.f};
+  int a_base[2], b_base[CT];     // element indices
+#pragma unroll
+  for (int a = 0; a < 2; ++a) a_base[a] = ((2 * wo + a) * 16 + (lane & 15)) * p.CPg + (lane >> 4);
+#pragma unroll
+  for (int b = 0; b < CT; ++b) b_base[b] = ((CT * wc + b) * 16 + (lane & 15)) * p.CPp + (lane >> 4) + kGuardF - p.pw;
+
+  // ---- this thread's items (the same for every chunk)
+  typedef float vec_t __attribute__((ext_vector_type(VEC), aligned(4)));
+  uint32_t g_src[NI], x_src[NI];     // byte offsets from the chunk's first G row / from the X row above it
+  uint32_t g_lds[NI], x_lds[NI];     // LDS byte addresses
+  uint32_t rr[NI];                   // staged row of the G item (low half) and of the X item (high half); 0xffff: never
+  {
+    const int WV = p.W / VEC;
+    const uint32_t safe_x = (uint32_t)p.W * 4;    // first element of the chunk's first row of X: always inside the tensor
+#pragma unroll
+    for (int k = 0; k < NI; ++k) {
+      const int idx = tid + k * kRowsThreads;
+      uint32_t rg = 0xffff, rx = 0xffff;
+      g_src[k] = 0; g_lds[k] = dump; x_src[k] = safe_x; x_lds[k] = dump;
+      {
+        const int ch = p.magic_gr ? (int)__umulhi((uint32_t)idx, p.magic_gr) : idx;
+        const int rem = idx - ch * (p.TRK * WV);
+        const int r = p.magic_w2 ? (int)__umulhi((uint32_t)rem, p.magic_w2) : rem;
+        const int j = (rem - r * WV) * VEC;
+        if (idx < p.g_items && ch < o_lim) {
+          g_src[k] = (uint32_t)(ch * p.plane + r * p.W + j) * 4;
+          g_lds[k] = (uint32_t)(ch * p.CPg + r * p.pitch + j) * 4;
+          rg = (uint32_t)r;
+        }
+      }
+      {
+        const int ch = p.magic_rw2 ? (int)__umulhi((uint32_t)idx, p.magic_rw2) : idx;
+        const int rem = idx - ch * (p.n_xrows * WV);
+        const int r = p.magic_w2 ? (int)__umulhi((uint32_t)rem, p.magic_w2) : rem;
+        const int j = (rem - r * WV) * VEC;
+        const bool halo_never = p.cpi == 1 && (r == 0 || r == p.n_xrows - 1);
+        if (idx < p.x_items && ch < c_lim && !halo_never) {
+          x_src[k] = (uint32_t)(ch * p.plane + r * p.W + j) * 4;
+          x_lds[k] = (uint32_t)p.lds_x_off + (uint32_t)(ch * p.CPp + r * p.pitch + j + kGuardF) * 4;
+          rx = (uint32_t)r;
+        }
+      }
+      rr[k] = rg | (rx << 16);
+    }
+  }
+  vec_t gr[NI], xr[NI];
+
+  // chunk q: rows [h0, h0 + rows) of image n.  X's staged rows [rlo, rhi) exist; G's [0, rows).
+  struct Geom { int rows, rlo, rhi; bool fast; const char* gb; const char* xb; };
+  auto geom_of = [&](int q) {
+    Geom m;
+    const int n = p.magic_cpi ? (int)__umulhi((uint32_t)q, p.magic_cpi) : q;
+    const int h0 = (q - n * p.cpi) * p.TRK;
+    m.rows = min(p.TRK, p.H - h0);
+    m.rlo = h0 == 0 ? 1 : 0;
+    m.rhi = min(m.rows + 2, p.H - h0 + 1);
+    m.fast = m.rows == p.TRK && (p.cpi == 1 || (m.rlo == 0 && m.rhi == p.TRK + 2));
+    m.gb = reinterpret_cast<const char*>(Gg) + ((int64_t)n * p.gs_n + (int64_t)h0 * p.W) * 4;
+    m.xb = reinterpret_cast<const char*>(Xg) + ((int64_t)n * p.xs_n + (int64_t)(h0 - 1) * p.W) * 4;
+    return m;
+  };
+  auto load = [&](const Geom& m, auto fast_c) {
+    constexpr bool FAST = decltype(fast_c)::value;
+#pragma unroll
+    for (int k = 0; k < NI; ++k) {
+      if (k >= p.ngi) break;
+      uint32_t off = g_src[k];
+      if constexpr (!FAST) off = (int)(rr[k] & 0xffff) < m.rows ? off : 0u;
+      gr[k] = *reinterpret_cast<const vec_t*>(m.gb + off);
+    }
+#pragma unroll
+    for (int k = 0; k < NI; ++k) {
+      if (k >= p.nxi) break;
+      uint32_t off = x_src[k];
+      if constexpr (!FAST) off = ((rr[k] >> 16) - (uint32_t)m.rlo) < (uint32_t)(m.rhi - m.rlo) ? off : (uint32_t)p.W * 4;
+      xr[k] = *reinterpret_cast<const vec_t*>(m.xb + off);
+    }
+  };
+  auto store = [&](const Geom& m, auto fast_c) {
+    constexpr bool FAST = decltype(fast_c)::value;
+#pragma unroll
+    for (int k = 0; k < NI; ++k) {
+      if (k >= p.ngi) break;
+      vec_t v = gr[k];
+      if constexpr (!FAST) {
+        const bool ok = (int)(rr[k] & 0xffff) < m.rows;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) v[e] = ok ? v[e] : 0.f;
+      }
+      *reinterpret_cast<vec_t*>(smem + g_lds[k]) = v;
+    }
+#pragma unroll
+    for (int k = 0; k < NI; ++k) {
+      if (k >= p.nxi) break;
+      vec_t v = xr[k];
+      if constexpr (!FAST) {
+        const bool ok = ((rr[k] >> 16) - (uint32_t)m.rlo) < (uint32_t)(m.rhi - m.rlo);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) v[e] = ok ? v[e] : 0.f;
+      }
+      *reinterpret_cast<vec_t*>(smem + x_lds[k]) = v;
+    }
+  };
+  using std::false_type;
+  using std::true_type;
+
+  // The next chunk travels global -> registers while the current one is computed out of LDS.
+  Geom cur{};
+  if (chunk_begin < chunk_end) {
+    cur = geom_of(chunk_begin);
+    if (cur.fast) load(cur, true_type{}); else load(cur, false_type{});
+  }
+  for (int q = chunk_begin; q < chunk_end; ++q) {
+    __syncthreads();                     // the previous chunk is fully consumed (first pass: LDS is zeroed)
+    if (cur.fast) store(cur, true_type{}); else store(cur, false_type{});
+    __syncthreads();
+    if (q + 1 < chunk_end) {
+      cur = geom_of(q + 1);
+      if (cur.fast) load(cur, true_type{}); else load(cur, false_type{});
+    }
+    dw_f32_chunk<KH, KW, CT>(p, gl, xl, a_base, b_base, acc, half, 2);
+  }
+  // the two halves of the k-steps meet in LDS: the upper waves leave their sums there, the lower ones add them
+  __syncthreads();
+  floatx4* red = reinterpret_cast<floatx4*>(smem) + (widx * 2 * CT * T) * 64 + lane;
+  if (half) {
 #pragma unroll
     for (int ao = 0; ao < 2; ++ao)
 #pragma unroll
-      for (int i = 0; i < CT; ++i) {
-        const int c = cb * CX + (CT * wc + i) * 16 + (lane & 15);
-        if (c >= p.Cg) continue;
+      for (int i = 0; i < CT; ++i)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const int o = ob * 64 + (2 * wo + ao) * 16 + 4 * (lane >> 4) + v;
-          if (o >= p.Og) continue;
-#pragma unroll
-          for (int t = 0; t < T; ++t)
-            dw[(int64_t)o * p.ws_o + (int64_t)c * p.ws_c + (t / KW) * p.ws_kh + (t % KW) * p.ws_kw] = acc[ao][i][t][v];
-        }
-      }
-    return;
+        for (int t = 0; t < T; ++t) red[((ao * CT + i) * T + t) * 64] = acc[ao][i][t];
   }
-  // partial[split][tile][slot][lane]: every accumulator register quadruple goes out as it is, one 16-byte store
-  // per lane (1 KB per wave and slot); the reduction kernel knows which weights a (slot, lane) holds
-  constexpr int SLOTS = 8 * CT * T;
-  const int tile = (g * p.n_oblk + ob) * p.n_cblk + cb;
-  floatx4* dst = reinterpret_cast<floatx4*>(partial) +
-                 ((int64_t)split * p.n_tiles + tile) * (SLOTS * 64) + (widx * 2 * CT * T) * 64 + lane;
+  __syncthreads();
+  if (half) return;
 #pragma unroll
   for (int ao = 0; ao < 2; ++ao)
 #pragma unroll
     for (int i = 0; i < CT; ++i)
 #pragma unroll
-      for (int t = 0; t < T; ++t) dst[((ao * CT + i) * T + t) * 64] = acc[ao][i][t];
+      for (int t = 0; t < T; ++t) acc[ao][i][t] += red[((ao * CT + i) * T + t) * 64];
+  dw_f32_finish<KH, KW, CT>(p, partial, g, ob, cb, split, widx, lane, acc);
 }
 
 // Adds the split partials kept in the accumulator layout of the contraction kernels and writes the sums into dW;
@@ -694,14 +919,23 @@ bool fill_dw_f32(const syno_plan* plan, DwParams& p) {
   // rows per chunk: about 200 staged pixels per channel, a bounded number of staging batches per thread, and
   // both tiles within LDS
   const int vec = (c.Wo % 4 == 0) ? 4 : (c.Wo % 2 == 0) ? 2 : 1;
-  const int budget = kF32Items * vec * 256;     // floats per tensor and chunk
+  // windows with a row extent go to the kernel that derives its source rows from the chunk's position (G and X with
+  // item lists of their own, at most kRowsItems per thread and tensor); the others look rows up in a table
+  const bool direct = c.KH == 3;
+  const int ni_max = direct ? kRowsItems : kF32Items;
+  const int budget = ni_max * vec * (direct ? kRowsThreads : 256);        // floats per tensor and chunk
   int trk = std::max(1, 200 / p.pitch);
+  if (direct && c.Ho * p.pitch <= 256) trk = c.Ho;     // small images whole: their halo rows are never loaded
   if (c.KH > 1) trk = std::min(trk, c.Ho);
   auto lds_need = [&](int t) {
     return (int64_t)64 * (t * p.pitch + 16) * 4 + (int64_t)cx * ((t + halo) * p.pitch + halo * p.pitch + 32) * 4;
   };
-  while (trk > 1 && (64 * (trk + halo) * c.Wo > budget || lds_need(trk) > 140 * 1024)) --trk;
-  if (64 * (trk + halo) * c.Wo > budget) return false;
+  auto over = [&](int t) {
+    const bool items = direct ? (64 * t * c.Wo > budget || cx * (t + halo) * c.Wo > budget) : 64 * (t + halo) * c.Wo > budget;
+    return items || lds_need(t) > 140 * 1024;
+  };
+  while (trk > 1 && over(trk)) --trk;
+  if (over(trk)) return false;
   if (c.KH > 1) {
     p.cpi = (c.Ho + trk - 1) / trk;
     trk = (c.Ho + p.cpi - 1) / p.cpi;
@@ -735,6 +969,20 @@ bool fill_dw_f32(const syno_plan* plan, DwParams& p) {
   p.lds_x_off = 64 * p.CPg * 4;
   p.lds_tab_off = p.lds_x_off + cx * p.CPp * 4;
   p.lds_bytes = p.lds_tab_off + ((2 * 2 * p.n_xrows * 4 + 15) & ~15);     // two row tables (current and next chunk)
+  if (direct) {                          // (the table's place then holds the 16 bytes that retired items write to)
+    const int wv = c.Wo / vec;
+    p.direct = 1;
+    p.g_items = 64 * p.TRK * wv;
+    p.x_items = cx * p.n_xrows * wv;
+    p.ngi = (p.g_items + kRowsThreads - 1) / kRowsThreads;
+    p.nxi = (p.x_items + kRowsThreads - 1) / kRowsThreads;
+    // the final reduction of the two k-step halves needs 4 waves x 2*ct*taps accumulators x 1 KB of LDS
+    p.lds_bytes = std::max(p.lds_bytes, 4 * 2 * p.ct * c.KH * c.KW * 1024);
+    p.ni = kRowsItems;
+    p.magic_gr = magic_of(p.TRK * wv);
+    p.magic_cpi = magic_of(p.cpi);
+    if (std::max(p.ngi, p.nxi) > ni_max) return false;
+  }
   return p.lds_bytes <= 144 * 1024 && 64 * p.CPp < (1 << 30) && p.n_xrows <= 256 && p.n_xrows <= 256 &&
          (int64_t)64 * p.n_xrows * c.Wo * std::max(c.Wo, p.n_xrows * c.Wo) < (1ll << 32);
 }
@@ -783,11 +1031,12 @@ std::string mfma_dw_describe(const syno_plan* plan) {
 namespace {
 // Launch of one instantiation; the opt-in to more than 64 KB of dynamic LDS is made once per instantiation.
 template <typename K, typename T>
-void launch_dw_kernel(K kernel, int grid, const DwParams& p, const T* G, const T* X, float* dst, hipStream_t stream) {
+void launch_dw_kernel(K kernel, int grid, const DwParams& p, const T* G, const T* X, float* dst, hipStream_t stream,
+                      int threads = 256) {
   static const hipError_t lds_opt_in =
       hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
   if (lds_opt_in != hipSuccess) return;
-  hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), p.lds_bytes, stream, p, G, X, dst);
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), p.lds_bytes, stream, p, G, X, dst);
 }
 }  // namespace
 
@@ -811,9 +1060,15 @@ syno_status launch_mfma_dw(const syno_plan* plan, const void* A, const void* B, 
     const float* Xf = static_cast<const float*>(B);
     by_window([&](auto kh_c, auto kw_c, auto ct_c) {
       constexpr int kh = decltype(kh_c)::value, kw = decltype(kw_c)::value, ct = decltype(ct_c)::value;
-      if (p.W % 4 == 0) launch_dw_kernel(dw_mfma_f32<kh, kw, ct, 4>, grid, p, Gf, Xf, dst, stream);
-      else if (p.W % 2 == 0) launch_dw_kernel(dw_mfma_f32<kh, kw, ct, 2>, grid, p, Gf, Xf, dst, stream);
-      else launch_dw_kernel(dw_mfma_f32<kh, kw, ct, 1>, grid, p, Gf, Xf, dst, stream);
+      if constexpr (kh == 3) {
+        if (p.W % 4 == 0) launch_dw_kernel(dw_rows_f32<kw, ct, 4, kRowsItems>, grid, p, Gf, Xf, dst, stream, kRowsThreads);
+        else if (p.W % 2 == 0) launch_dw_kernel(dw_rows_f32<kw, ct, 2, kRowsItems>, grid, p, Gf, Xf, dst, stream, kRowsThreads);
+        else launch_dw_kernel(dw_rows_f32<kw, ct, 1, kRowsItems>, grid, p, Gf, Xf, dst, stream, kRowsThreads);
+      } else {
+        if (p.W % 4 == 0) launch_dw_kernel(dw_mfma_f32<kh, kw, ct, 4>, grid, p, Gf, Xf, dst, stream);
+        else if (p.W % 2 == 0) launch_dw_kernel(dw_mfma_f32<kh, kw, ct, 2>, grid, p, Gf, Xf, dst, stream);
+        else launch_dw_kernel(dw_mfma_f32<kh, kw, ct, 1>, grid, p, Gf, Xf, dst, stream);
+      }
     });
   } else {
     const uint16_t* G = static_cast<const uint16_t*>(A);

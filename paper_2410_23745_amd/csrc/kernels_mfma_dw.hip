@@ -48,9 +48,10 @@ struct DwParams {
   int32_t lds_x_off, lds_tab_off, lds_bytes;
   // fp32 kernel for windows with a row extent (chunks inside one image, source rows affine in the staged row):
   int32_t direct;                      // that kernel takes this plan
-  int32_t g_items, x_items;            // staging items per chunk of G (64 channels x TRK rows) and X (32*ct x n_xrows)
-  int32_t ngi, nxi, ni;                // items per thread of G and of X; the instantiation's bound
-  uint32_t magic_gr, magic_cpi;        // ceil(2^32/d) for d = TRK * items per row and d = cpi (0 for d = 1)
+  int32_t ni_g, ni_x;                  // staging items per thread of G and of X
+  int32_t mode;                        // pixels per staging item: 4, 2, 1, or a whole row of 7 or 14
+  int32_t lds_buf;                     // bytes of one LDS buffer (G tile, then X tile at lds_x_off); there are two
+  uint32_t magic_cpi;                  // ceil(2^32/d) for d = cpi (0 for d = 1); magic_w2 is for the items per row
 };
 
 namespace {
@@ -408,8 +409,8 @@ __device__ __forceinline__ void dw_f32_finish(const DwParams& p, float* __restri
 // kF32Items per thread and tensor, which wait in registers while the previous chunk is computed.
 constexpr int kF32Items = 18;     // staging items per thread, tensor and chunk
 constexpr int kGuardF = 4;       // zero floats in front of each X channel row
-constexpr int kRowsItems = 7;    // (per thread of 512)
-constexpr int kRowsThreads = 512;   // staging items per thread and tensor of the kernel for windows with a row extent
+constexpr int kRowsThreads = 512;
+constexpr int kRowsBatches = 2;   // staging batches (of 28 floats per thread and tensor) a chunk may need   // staging items per thread and tensor of the kernel for windows with a row extent
 
 template <int KH, int KW, int CT, int VEC>
 __global__ __launch_bounds__(256) void dw_mfma_f32(const DwParams p, const float* __restrict__ Gt,
@@ -555,27 +556,34 @@ __global__ __launch_bounds__(256) void dw_mfma_f32(const DwParams p, const float
 }
 
 // fp32, windows with a row extent (KH = 3).  A chunk is TRK rows of ONE image, so the source of staged row r is
-// row h0 + r of G and row h0 - 1 + r of X: one uniform base per chunk and tensor plus an offset that a thread works
-// out once for each of its items.  Nothing is looked up per chunk, every load is a uniform base plus a 32-bit lane
-// offset, and the requests of a chunk go out back to back.  G and X have item lists of their own (64 x TRK rows and
-// 32*CT x (TRK + 2) rows of W/VEC items).  Rows that a chunk does not have (the halo above the first and below the
-// last row of an image, the missing rows of an image's last chunk) are loaded from a safe address and written to LDS
-// as zeros; a chunk in the interior of an image has none, and takes a path without any of these tests.  With a whole
-// image per chunk the halo rows never carry data: their items are retired at set-up and LDS keeps its zeros.
-// Items that never carry data (beyond the item count, channels beyond the group) load from a safe address and write to
-// 16 bytes of LDS that nobody reads.
-template <int KW, int CT, int VEC, int NI>
+// row h0 + r of G and row h0 - 1 + r of X: one uniform base per chunk and tensor plus an offset that depends only on
+// the item; nothing is looked up, and every load is a uniform base plus a 32-bit lane offset.
+//
+// Eight waves in two halves that trade places: while one half (4 waves, one per SIMD, each with its own part of the
+// output tile) multiplies the chunk that lies in one LDS buffer, the other half fetches the next chunk from memory
+// and lays it out in the second buffer; after one barrier the halves swap roles.  So each half computes every other
+// chunk of the workgroup's share and stages the chunks it will compute itself; the matrix pipes always have a wave
+// that issues MFMAs, and the memory round trips, the address arithmetic and the LDS writes of the staging all run
+// beside them.  The sums of the two halves meet in LDS at the end.
+// Staging goes in batches of up to 28 floats per thread and tensor: items of adjacent pixels of a row (a whole row of
+// 7 or 14 pixels, else 4, 2 or 1 pixels), G (64 channels x TRK rows) and X (32*CT channels x TRK + 2 rows) together.  Rows that a chunk does not have (the halo above the
+// first and below the last row of an image, the missing rows of an image's last chunk) are loaded from a safe
+// address and written as zeros; items beyond the list or the group's channels go to 4 KB of LDS nobody reads.
+template <int KW, int CT, int MODE>
 __global__ __launch_bounds__(kRowsThreads) void dw_rows_f32(const DwParams p, const float* __restrict__ Gt,
-                                                   const float* __restrict__ Xt, float* __restrict__ partial) {
+                                                            const float* __restrict__ Xt, float* __restrict__ partial) {
   constexpr int KH = 3, CX = 32 * CT, T = KH * KW;
+  // A staging item is MODE adjacent pixels of one staged row: 4, 2 or 1 (what the width divides by), or a whole row
+  // of 7 or 14 pixels, moved as pieces of 4, 2 and 1.
+  constexpr int FL = MODE;                                          // floats per item
+  constexpr int NB = MODE == 7 ? 4 : MODE == 14 ? 2 : 7;            // items per thread and batch
+  constexpr int NI = NB * (MODE == 4 ? kRowsBatches : 1);           // items per thread and chunk at most
   extern __shared__ __align__(16) unsigned char smem[];
-  float* gl = reinterpret_cast<float*>(smem);                   // [64][CPg]
-  float* xl = reinterpret_cast<float*>(smem + p.lds_x_off);     // [32*CT][CPp], data starts at kGuardF
-  const uint32_t dump = (uint32_t)p.lds_tab_off;
+  const uint32_t dump = (uint32_t)p.lds_tab_off;                // behind the two buffers
 
-  const int tid = threadIdx.x, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63, htid = tid & 255;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int widx = wave & 3, half = wave >> 2;     // waves w and w + 4 share an output tile and take alternate k-steps
+  const int widx = wave & 3, half = wave >> 2;
   const int wo = widx >> 1, wc = widx & 1;
   int bid = blockIdx.x;
   const int split = bid % p.n_splits; bid /= p.n_splits;
@@ -600,130 +608,126 @@ __global__ __launch_bounds__(kRowsThreads) void dw_rows_f32(const DwParams p, co
     for (int b = 0; b < CT; ++b)
 #pragma unroll
       for (int t = 0; t < T; ++t) acc[a][b][t] = floatx4{0.f, 0.f, 0.f, 0.f};
-  int a_base[2], b_base[CT];     // element indices
+  int a_base[2], b_base[CT];     // element indices inside a buffer's G and X tile
 #pragma unroll
   for (int a = 0; a < 2; ++a) a_base[a] = ((2 * wo + a) * 16 + (lane & 15)) * p.CPg + (lane >> 4);
 #pragma unroll
   for (int b = 0; b < CT; ++b) b_base[b] = ((CT * wc + b) * 16 + (lane & 15)) * p.CPp + (lane >> 4) + kGuardF - p.pw;
 
-  // ---- this thread's items (the same for every chunk)
-  typedef float vec_t __attribute__((ext_vector_type(VEC), aligned(4)));
-  uint32_t g_src[NI], x_src[NI];     // byte offsets from the chunk's first G row / from the X row above it
-  uint32_t g_lds[NI], x_lds[NI];     // LDS byte addresses
-  uint32_t rr[NI];                   // staged row of the G item (low half) and of the X item (high half); 0xffff: never
+  // ---- this thread's staging items, worked out once.  256 threads of a half share a tensor's channels evenly
+  // (4 threads per G channel, 256 / CX per X channel); a thread takes every 4th (8th) item of its channel.  Per
+  // item: the byte offset from the chunk's first source row, and the LDS byte offset inside a buffer with the staged
+  // row in the top byte (row 255: never).
+  uint32_t g_off[NI], g_put[NI], x_off[NI], x_put[NI];
   {
-    const int WV = p.W / VEC;
-    const uint32_t safe_x = (uint32_t)p.W * 4;    // first element of the chunk's first row of X: always inside the tensor
+    const int WR = p.W / FL;                     // items per row
+    auto plan_items = [&](uint32_t (&off)[NI], uint32_t (&put)[NI], int tpc_log2, int rows_staged, int ch_lim,
+                          int ch_pitch, int lds_first, uint32_t safe) {
+      const int ch = htid >> tpc_log2, sub = htid & ((1 << tpc_log2) - 1);
 #pragma unroll
-    for (int k = 0; k < NI; ++k) {
-      const int idx = tid + k * kRowsThreads;
-      uint32_t rg = 0xffff, rx = 0xffff;
-      g_src[k] = 0; g_lds[k] = dump; x_src[k] = safe_x; x_lds[k] = dump;
-      {
-        const int ch = p.magic_gr ? (int)__umulhi((uint32_t)idx, p.magic_gr) : idx;
-        const int rem = idx - ch * (p.TRK * WV);
-        const int r = p.magic_w2 ? (int)__umulhi((uint32_t)rem, p.magic_w2) : rem;
-        const int j = (rem - r * WV) * VEC;
-        if (idx < p.g_items && ch < o_lim) {
-          g_src[k] = (uint32_t)(ch * p.plane + r * p.W + j) * 4;
-          g_lds[k] = (uint32_t)(ch * p.CPg + r * p.pitch + j) * 4;
-          rg = (uint32_t)r;
-        }
+      for (int k = 0; k < NI; ++k) {
+        const int i = sub + (k << tpc_log2);
+        const int r = p.magic_w2 ? (int)__umulhi((uint32_t)i, p.magic_w2) : i;
+        const int j = (i - r * WR) * FL;
+        const bool exists = r < rows_staged && ch < ch_lim;
+        off[k] = exists ? (uint32_t)(ch * p.plane + r * p.W + j) * 4 : safe;
+        // (items that never carry data write to a spare area behind the buffers, each lane to its own 64 bytes)
+        put[k] = exists ? ((uint32_t)(lds_first + ch * ch_pitch + r * p.pitch + j) * 4) | ((uint32_t)r << 24)
+                        : (dump + (uint32_t)lane * 64) | (255u << 24);
       }
-      {
-        const int ch = p.magic_rw2 ? (int)__umulhi((uint32_t)idx, p.magic_rw2) : idx;
-        const int rem = idx - ch * (p.n_xrows * WV);
-        const int r = p.magic_w2 ? (int)__umulhi((uint32_t)rem, p.magic_w2) : rem;
-        const int j = (rem - r * WV) * VEC;
-        const bool halo_never = p.cpi == 1 && (r == 0 || r == p.n_xrows - 1);
-        if (idx < p.x_items && ch < c_lim && !halo_never) {
-          x_src[k] = (uint32_t)(ch * p.plane + r * p.W + j) * 4;
-          x_lds[k] = (uint32_t)p.lds_x_off + (uint32_t)(ch * p.CPp + r * p.pitch + j + kGuardF) * 4;
-          rx = (uint32_t)r;
-        }
-      }
-      rr[k] = rg | (rx << 16);
-    }
+    };
+    plan_items(g_off, g_put, 2, p.TRK, o_lim, p.CPg, 0, 0u);
+    plan_items(x_off, x_put, CT == 1 ? 3 : 2, p.n_xrows, c_lim, p.CPp, kGuardF + (p.lds_x_off >> 2), (uint32_t)p.W * 4);
   }
-  vec_t gr[NI], xr[NI];
-
-  // chunk q: rows [h0, h0 + rows) of image n.  X's staged rows [rlo, rhi) exist; G's [0, rows).
-  struct Geom { int rows, rlo, rhi; bool fast; const char* gb; const char* xb; };
-  auto geom_of = [&](int q) {
-    Geom m;
+  // Pieces of an item: float offset and width.  Source rows are only element-aligned; in LDS a row of 7 starts on a
+  // 32-byte boundary (pitch 8), every other layout is element-aligned as well.
+  typedef float f4_t __attribute__((ext_vector_type(4), aligned(4)));
+  typedef float f2_t __attribute__((ext_vector_type(2), aligned(4)));
+  typedef float f4a_t __attribute__((ext_vector_type(4), aligned(16)));
+  typedef float f2a_t __attribute__((ext_vector_type(2), aligned(8)));
+  auto load_item = [&](float (&v)[FL], const char* src) {
+    const float* f = reinterpret_cast<const float*>(src);
+    int o = 0;
+#pragma unroll
+    for (; o + 4 <= FL; o += 4) { const f4_t t = *reinterpret_cast<const f4_t*>(f + o); v[o] = t[0]; v[o + 1] = t[1]; v[o + 2] = t[2]; v[o + 3] = t[3]; }
+    if constexpr (FL % 4 >= 2) { const f2_t t = *reinterpret_cast<const f2_t*>(f + o); v[o] = t[0]; v[o + 1] = t[1]; o += 2; }
+    if constexpr (FL % 2 == 1) v[o] = f[o];
+  };
+  auto store_item = [&](const float (&v)[FL], unsigned char* dst) {
+    float* f = reinterpret_cast<float*>(dst);
+    int o = 0;
+#pragma unroll
+    for (; o + 4 <= FL; o += 4) {
+      if constexpr (MODE == 7) *reinterpret_cast<f4a_t*>(f + o) = f4a_t{v[o], v[o + 1], v[o + 2], v[o + 3]};
+      else *reinterpret_cast<f4_t*>(f + o) = f4_t{v[o], v[o + 1], v[o + 2], v[o + 3]};
+    }
+    if constexpr (FL % 4 >= 2) {
+      if constexpr (MODE == 7) *reinterpret_cast<f2a_t*>(f + o) = f2a_t{v[o], v[o + 1]};
+      else *reinterpret_cast<f2_t*>(f + o) = f2_t{v[o], v[o + 1]};
+      o += 2;
+    }
+    if constexpr (FL % 2 == 1) f[o] = v[o];
+  };
+  // One batch of one tensor: up to NB items, requested back to back; staged rows [r_lo, r_hi) exist in this chunk.
+  struct Batch { float v[NB][FL]; };
+  auto fetch = [&](Batch& bt, const char* src_base, const uint32_t* off, const uint32_t* put, int count, uint32_t safe,
+                   int r_lo, int r_hi) {
+#pragma unroll
+    for (int k = 0; k < NB; ++k) {
+      if (k >= count) break;
+      const bool ok = ((put[k] >> 24) - (uint32_t)r_lo) < (uint32_t)(r_hi - r_lo);
+      load_item(bt.v[k], src_base + (ok ? off[k] : safe));
+    }
+  };
+  auto put_batch = [&](Batch& bt, uint32_t buf, const uint32_t* put, int count, int r_lo, int r_hi) {
+#pragma unroll
+    for (int k = 0; k < NB; ++k) {
+      if (k >= count) break;
+      const bool ok = ((put[k] >> 24) - (uint32_t)r_lo) < (uint32_t)(r_hi - r_lo);
+      const bool never = (put[k] >> 24) == 255u;
+#pragma unroll
+      for (int e = 0; e < FL; ++e) bt.v[k][e] = ok ? bt.v[k][e] : 0.f;
+      store_item(bt.v[k], smem + (put[k] & 0xffffffu) + (never ? 0u : buf));
+    }
+  };
+  // Stages chunk q (rows [h0, h0 + rows) of image n) into the buffer at byte offset `buf`; run by the 256 threads of
+  // one half.  The batches of G and X are requested together, then written.
+  auto stage = [&](int q, uint32_t buf) {
     const int n = p.magic_cpi ? (int)__umulhi((uint32_t)q, p.magic_cpi) : q;
     const int h0 = (q - n * p.cpi) * p.TRK;
-    m.rows = min(p.TRK, p.H - h0);
-    m.rlo = h0 == 0 ? 1 : 0;
-    m.rhi = min(m.rows + 2, p.H - h0 + 1);
-    m.fast = m.rows == p.TRK && (p.cpi == 1 || (m.rlo == 0 && m.rhi == p.TRK + 2));
-    m.gb = reinterpret_cast<const char*>(Gg) + ((int64_t)n * p.gs_n + (int64_t)h0 * p.W) * 4;
-    m.xb = reinterpret_cast<const char*>(Xg) + ((int64_t)n * p.xs_n + (int64_t)(h0 - 1) * p.W) * 4;
-    return m;
-  };
-  auto load = [&](const Geom& m, auto fast_c) {
-    constexpr bool FAST = decltype(fast_c)::value;
+    const int rows = min(p.TRK, p.H - h0);
+    const char* gb = reinterpret_cast<const char*>(Gg) + ((int64_t)n * p.gs_n + (int64_t)h0 * p.W) * 4;
+    // (one row above the chunk; when the chunk starts an image that row is not read: staged row 0 does not exist then
+    // and the safe offset points at the chunk's first row)
+    const char* xb = reinterpret_cast<const char*>(Xg) + ((int64_t)n * p.xs_n + (int64_t)(h0 - 1) * p.W) * 4;
+    const int x_lo = h0 == 0 ? 1 : 0, x_hi = min(rows + 2, p.H - h0 + 1);
 #pragma unroll
-    for (int k = 0; k < NI; ++k) {
-      if (k >= p.ngi) break;
-      uint32_t off = g_src[k];
-      if constexpr (!FAST) off = (int)(rr[k] & 0xffff) < m.rows ? off : 0u;
-      gr[k] = *reinterpret_cast<const vec_t*>(m.gb + off);
-    }
-#pragma unroll
-    for (int k = 0; k < NI; ++k) {
-      if (k >= p.nxi) break;
-      uint32_t off = x_src[k];
-      if constexpr (!FAST) off = ((rr[k] >> 16) - (uint32_t)m.rlo) < (uint32_t)(m.rhi - m.rlo) ? off : (uint32_t)p.W * 4;
-      xr[k] = *reinterpret_cast<const vec_t*>(m.xb + off);
+    for (int b = 0; b < NI / NB; ++b) {
+      const int ng = p.ni_g - b * NB, nx = p.ni_x - b * NB;       // (uniform) items of this batch
+      if (ng <= 0 && nx <= 0) break;
+      Batch bg, bx;
+      fetch(bg, gb, g_off + b * NB, g_put + b * NB, ng, 0u, 0, rows);
+      fetch(bx, xb, x_off + b * NB, x_put + b * NB, nx, (uint32_t)p.W * 4, x_lo, x_hi);
+      put_batch(bg, buf, g_put + b * NB, ng, 0, rows);
+      put_batch(bx, buf, x_put + b * NB, nx, x_lo, x_hi);
     }
   };
-  auto store = [&](const Geom& m, auto fast_c) {
-    constexpr bool FAST = decltype(fast_c)::value;
-#pragma unroll
-    for (int k = 0; k < NI; ++k) {
-      if (k >= p.ngi) break;
-      vec_t v = gr[k];
-      if constexpr (!FAST) {
-        const bool ok = (int)(rr[k] & 0xffff) < m.rows;
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) v[e] = ok ? v[e] : 0.f;
-      }
-      *reinterpret_cast<vec_t*>(smem + g_lds[k]) = v;
-    }
-#pragma unroll
-    for (int k = 0; k < NI; ++k) {
-      if (k >= p.nxi) break;
-      vec_t v = xr[k];
-      if constexpr (!FAST) {
-        const bool ok = ((rr[k] >> 16) - (uint32_t)m.rlo) < (uint32_t)(m.rhi - m.rlo);
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) v[e] = ok ? v[e] : 0.f;
-      }
-      *reinterpret_cast<vec_t*>(smem + x_lds[k]) = v;
-    }
-  };
-  using std::false_type;
-  using std::true_type;
 
-  // The next chunk travels global -> registers while the current one is computed out of LDS.
-  Geom cur{};
-  if (chunk_begin < chunk_end) {
-    cur = geom_of(chunk_begin);
-    if (cur.fast) load(cur, true_type{}); else load(cur, false_type{});
-  }
-  for (int q = chunk_begin; q < chunk_end; ++q) {
-    __syncthreads();                     // the previous chunk is fully consumed (first pass: LDS is zeroed)
-    if (cur.fast) store(cur, true_type{}); else store(cur, false_type{});
-    __syncthreads();
-    if (q + 1 < chunk_end) {
-      cur = geom_of(q + 1);
-      if (cur.fast) load(cur, true_type{}); else load(cur, false_type{});
-    }
-    dw_f32_chunk<KH, KW, CT>(p, gl, xl, a_base, b_base, acc, half, 2);
-  }
-  // the two halves of the k-steps meet in LDS: the upper waves leave their sums there, the lower ones add them
+  __syncthreads();                                   // LDS is zeroed
+  if (half == 0 && chunk_begin < chunk_end) stage(chunk_begin, 0u);
   __syncthreads();
+  for (int q = chunk_begin; q < chunk_end; ++q) {
+    const int par = (q - chunk_begin) & 1;
+    if (par == half) {
+      const unsigned char* cur = smem + par * p.lds_buf;
+      dw_f32_chunk<KH, KW, CT>(p, reinterpret_cast<const float*>(cur), reinterpret_cast<const float*>(cur + p.lds_x_off),
+                               a_base, b_base, acc);
+    } else if (q + 1 < chunk_end) {
+      stage(q + 1, (uint32_t)((par ^ 1) * p.lds_buf));
+    }
+    __syncthreads();
+  }
+  // the sums of the two halves meet in LDS: the upper waves leave theirs there, the lower ones add them
   floatx4* red = reinterpret_cast<floatx4*>(smem) + (widx * 2 * CT * T) * 64 + lane;
   if (half) {
 #pragma unroll
@@ -919,20 +923,28 @@ bool fill_dw_f32(const syno_plan* plan, DwParams& p) {
   // rows per chunk: about 200 staged pixels per channel, a bounded number of staging batches per thread, and
   // both tiles within LDS
   const int vec = (c.Wo % 4 == 0) ? 4 : (c.Wo % 2 == 0) ? 2 : 1;
-  // windows with a row extent go to the kernel that derives its source rows from the chunk's position (G and X with
-  // item lists of their own, at most kRowsItems per thread and tensor); the others look rows up in a table
+  // windows with a row extent go to the kernel that derives its source rows from the chunk's position and keeps
+  // two chunks in LDS (one being multiplied, one being staged); the others look rows up in a table
   const bool direct = c.KH == 3;
-  const int ni_max = direct ? kRowsItems : kF32Items;
-  const int budget = ni_max * vec * (direct ? kRowsThreads : 256);        // floats per tensor and chunk
+  const int budget = kF32Items * vec * 256;        // table kernel: floats per tensor and chunk
   int trk = std::max(1, 200 / p.pitch);
-  if (direct && c.Ho * p.pitch <= 256) trk = c.Ho;     // small images whole: their halo rows are never loaded
+  if (direct && c.Ho * p.pitch <= 256) trk = c.Ho;     // small images whole
   if (c.KH > 1) trk = std::min(trk, c.Ho);
+  auto pitch_of = [&](int elems) { int v = (elems + 3) & ~3; return ((v >> 2) & 1) ? v : v + 4; };   // 4 * odd
   auto lds_need = [&](int t) {
+    if (direct)      // both buffers, the spare 16 bytes
+      return (int64_t)2 * (64 * pitch_of(((t * p.pitch + 3) & ~3) + 4) + cx * pitch_of((t + halo) * p.pitch + kGuardF + 8)) * 4 + 4096;
     return (int64_t)64 * (t * p.pitch + 16) * 4 + (int64_t)cx * ((t + halo) * p.pitch + halo * p.pitch + 32) * 4;
   };
+  // staging items of that kernel: whole rows of 7 or 14 pixels, else `vec` pixels; 4 threads per G channel and
+  // 256 / cx per X channel share a channel's items
+  const int mode = (c.Wo == 7 || c.Wo == 14) ? c.Wo : vec;
+  const int ni_cap = mode == 7 ? 4 : mode == 14 ? 2 : mode == 4 ? 7 * kRowsBatches : 7;
+  auto items_g = [&](int t) { return (t * (c.Wo / mode) + 3) / 4; };
+  auto items_x = [&](int t) { return ((t + halo) * (c.Wo / mode) + 256 / cx - 1) / (256 / cx); };
   auto over = [&](int t) {
-    const bool items = direct ? (64 * t * c.Wo > budget || cx * (t + halo) * c.Wo > budget) : 64 * (t + halo) * c.Wo > budget;
-    return items || lds_need(t) > 140 * 1024;
+    if (direct) return lds_need(t) > 160 * 1024 || std::max(items_g(t), items_x(t)) > ni_cap || t + halo > 254;
+    return 64 * (t + halo) * c.Wo > budget || lds_need(t) > 140 * 1024;
   };
   while (trk > 1 && over(trk)) --trk;
   if (over(trk)) return false;
@@ -947,10 +959,16 @@ bool fill_dw_f32(const syno_plan* plan, DwParams& p) {
   p.TRK = trk;
   p.n_xrows = trk + halo;
   p.CP = (p.TRK * p.pitch + 3) & ~3;
-  p.CPp = (std::max(p.CP, p.n_xrows * p.pitch) + halo * p.pitch + c.KW + kGuardF + 4 + 3) & ~3;
-  if (((p.CPp >> 2) & 1) == 0) p.CPp += 4;
-  p.CPg = (p.CP + 4 + 3) & ~3;
-  if (((p.CPg >> 2) & 1) == 0) p.CPg += 4;
+  if (direct) {
+    // the last k-step reads G up to CP - 1 and X up to n_xrows * pitch + 7 (its guard included)
+    p.CPg = pitch_of(p.CP + 4);
+    p.CPp = pitch_of(p.n_xrows * p.pitch + kGuardF + 8);
+  } else {
+    p.CPp = (std::max(p.CP, p.n_xrows * p.pitch) + halo * p.pitch + c.KW + kGuardF + 4 + 3) & ~3;
+    if (((p.CPp >> 2) & 1) == 0) p.CPp += 4;
+    p.CPg = (p.CP + 4 + 3) & ~3;
+    if (((p.CPg >> 2) & 1) == 0) p.CPg += 4;
+  }
   p.items = 64 * p.n_xrows * (c.Wo / vec);
   p.magic_w2 = magic_of(c.Wo / vec);
   p.magic_rw2 = magic_of(p.n_xrows * (c.Wo / vec));
@@ -969,19 +987,18 @@ bool fill_dw_f32(const syno_plan* plan, DwParams& p) {
   p.lds_x_off = 64 * p.CPg * 4;
   p.lds_tab_off = p.lds_x_off + cx * p.CPp * 4;
   p.lds_bytes = p.lds_tab_off + ((2 * 2 * p.n_xrows * 4 + 15) & ~15);     // two row tables (current and next chunk)
-  if (direct) {                          // (the table's place then holds the 16 bytes that retired items write to)
-    const int wv = c.Wo / vec;
+  if (direct) {
+    p.mode = mode;
     p.direct = 1;
-    p.g_items = 64 * p.TRK * wv;
-    p.x_items = cx * p.n_xrows * wv;
-    p.ngi = (p.g_items + kRowsThreads - 1) / kRowsThreads;
-    p.nxi = (p.x_items + kRowsThreads - 1) / kRowsThreads;
-    // the final reduction of the two k-step halves needs 4 waves x 2*ct*taps accumulators x 1 KB of LDS
-    p.lds_bytes = std::max(p.lds_bytes, 4 * 2 * p.ct * c.KH * c.KW * 1024);
-    p.ni = kRowsItems;
-    p.magic_gr = magic_of(p.TRK * wv);
+    p.ni_g = items_g(p.TRK);
+    p.ni_x = items_x(p.TRK);
+    p.magic_w2 = magic_of(c.Wo / mode);
     p.magic_cpi = magic_of(p.cpi);
-    if (std::max(p.ngi, p.nxi) > ni_max) return false;
+    p.lds_buf = p.lds_x_off + cx * p.CPp * 4;
+    p.lds_tab_off = 2 * p.lds_buf;            // the 4 KB that retired items write to
+    // (the final sum of the two halves needs 4 waves x 2*ct*taps accumulators x 1 KB of LDS)
+    p.lds_bytes = std::max(p.lds_tab_off + 4096, 4 * 2 * p.ct * c.KH * c.KW * 1024);
+    return p.lds_bytes <= 160 * 1024;
   }
   return p.lds_bytes <= 144 * 1024 && 64 * p.CPp < (1 << 30) && p.n_xrows <= 256 && p.n_xrows <= 256 &&
          (int64_t)64 * p.n_xrows * c.Wo * std::max(c.Wo, p.n_xrows * c.Wo) < (1ll << 32);
@@ -1034,7 +1051,7 @@ template <typename K, typename T>
 void launch_dw_kernel(K kernel, int grid, const DwParams& p, const T* G, const T* X, float* dst, hipStream_t stream,
                       int threads = 256) {
   static const hipError_t lds_opt_in =
-      hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
+      hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   if (lds_opt_in != hipSuccess) return;
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), p.lds_bytes, stream, p, G, X, dst);
 }
@@ -1061,9 +1078,11 @@ syno_status launch_mfma_dw(const syno_plan* plan, const void* A, const void* B, 
     by_window([&](auto kh_c, auto kw_c, auto ct_c) {
       constexpr int kh = decltype(kh_c)::value, kw = decltype(kw_c)::value, ct = decltype(ct_c)::value;
       if constexpr (kh == 3) {
-        if (p.W % 4 == 0) launch_dw_kernel(dw_rows_f32<kw, ct, 4, kRowsItems>, grid, p, Gf, Xf, dst, stream, kRowsThreads);
-        else if (p.W % 2 == 0) launch_dw_kernel(dw_rows_f32<kw, ct, 2, kRowsItems>, grid, p, Gf, Xf, dst, stream, kRowsThreads);
-        else launch_dw_kernel(dw_rows_f32<kw, ct, 1, kRowsItems>, grid, p, Gf, Xf, dst, stream, kRowsThreads);
+        if (p.mode == 4) launch_dw_kernel(dw_rows_f32<kw, ct, 4>, grid, p, Gf, Xf, dst, stream, kRowsThreads);
+        else if (p.mode == 7) launch_dw_kernel(dw_rows_f32<kw, ct, 7>, grid, p, Gf, Xf, dst, stream, kRowsThreads);
+        else if (p.mode == 14) launch_dw_kernel(dw_rows_f32<kw, ct, 14>, grid, p, Gf, Xf, dst, stream, kRowsThreads);
+        else if (p.mode == 2) launch_dw_kernel(dw_rows_f32<kw, ct, 2>, grid, p, Gf, Xf, dst, stream, kRowsThreads);
+        else launch_dw_kernel(dw_rows_f32<kw, ct, 1>, grid, p, Gf, Xf, dst, stream, kRowsThreads);
       } else {
         if (p.W % 4 == 0) launch_dw_kernel(dw_mfma_f32<kh, kw, ct, 4>, grid, p, Gf, Xf, dst, stream);
         else if (p.W % 2 == 0) launch_dw_kernel(dw_mfma_f32<kh, kw, ct, 2>, grid, p, Gf, Xf, dst, stream);

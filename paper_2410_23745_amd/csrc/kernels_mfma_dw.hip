@@ -79,6 +79,66 @@ __device__ __forceinline__ bf16x8 cut(const uint4& lo, const uint4& hi) {
   return __builtin_bit_cast(bf16x8, r);
 }
 
+template <int KH, int KW, int CT>
+__device__ __forceinline__ void dw_finish(const DwParams& p, float* __restrict__ partial, int g, int ob, int cb, int split,
+                                          int widx, int lane, const floatx4 (&acc)[2][CT][KH * KW]);
+
+// The k-steps of one staged chunk of the bf16 kernels: 32 pixels each; the LDS reads of the next step are issued before
+// the MFMAs of the current one.  `gp` and `xp` are the channel pitches (elements) of the G and the X tile.
+template <int KH, int KW, int CT>
+__device__ __forceinline__ void dw_bf16_chunk(const DwParams& p, const uint16_t* gl, const uint16_t* xl,
+                                              const int (&a_base)[2], const int (&b_base)[CT],
+                                              floatx4 (&acc)[2][CT][KH * KW]) {
+    const int steps = p.CP >> 5;
+    constexpr int NX = KW == 1 ? 2 : 3;      // 16-byte groups of X read per (c-tile, kh)
+    struct Frags { uint4 a[2]; uint4 x[CT * KH][NX]; };
+    auto read = [&](int st, Frags& f) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) f.a[i] = *reinterpret_cast<const uint4*>(gl + a_base[i] + st * 32);
+#pragma unroll
+      for (int i = 0; i < CT; ++i)
+#pragma unroll
+        for (int kh = 0; kh < KH; ++kh) {
+          const uint16_t* xp = xl + b_base[i] + st * 32 + kh * p.pitch;
+#pragma unroll
+          for (int q = 0; q < NX; ++q) f.x[i * KH + kh][q] = *reinterpret_cast<const uint4*>(xp + 8 * q);
+        }
+    };
+    // tap (kh, kw) reads X shifted by kh rows and (kw - pw) elements: element 8 + kw - pw of the groups read at
+    // row offset kh*pitch (a multiple of 8 elements when KH > 1)
+    auto mfmas = [&](const Frags& f) {
+#pragma unroll
+      for (int i = 0; i < CT; ++i)
+#pragma unroll
+        for (int kh = 0; kh < KH; ++kh) {
+          const uint4(&x)[NX] = f.x[i * KH + kh];
+          bf16x8 b[KW];
+          if constexpr (KW == 1) {
+            b[0] = cut<8>(x[0], x[1]);
+          } else {
+            b[0] = cut<7>(x[0], x[1]);
+            b[1] = cut<8>(x[0], x[1]);
+            b[2] = cut<1>(x[1], x[2]);     // one more element to the right reaches into the third group
+          }
+#pragma unroll
+          for (int t = 0; t < KW; ++t)
+#pragma unroll
+            for (int ao = 0; ao < 2; ++ao)
+              acc[ao][i][kh * KW + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.a[ao]), b[t],
+                                                                               acc[ao][i][kh * KW + t], 0, 0, 0);
+        }
+    };
+    Frags f0, f1;
+    read(0, f0);
+    int st = 0;
+    for (; st + 2 < steps; st += 2) {
+      read(st + 1, f1); mfmas(f0);
+      read(st + 2, f0); mfmas(f1);
+    }
+    if (st + 1 < steps) { read(st + 1, f1); mfmas(f0); mfmas(f1); }
+    else mfmas(f0);
+  }
+
 // One workgroup: group g, 64 output channels x 32*CT input channels, one split of the pixel rows.
 // 4 waves; wave (wo, wc) owns o-tiles {2wo, 2wo+1} x CT c-tiles x KH*KW taps (CT = 2 for up to 3 taps, 1 for 9).
 // Staging moves items of EP adjacent pixels of a row: 4 (two dwords) when W is a multiple of 4, else 2, else 1.
@@ -225,91 +285,9 @@ __global__ __launch_bounds__(256) void dw_mfma_bf16(const DwParams p, const uint
         }
       }
     __syncthreads();
-    // k-steps of 32 pixels; the LDS reads of the next step are issued before the MFMAs of the current one (one
-    // wave per SIMD here, so nothing else would cover the LDS latency)
-    const int steps = p.CP >> 5;
-    constexpr int NX = KW == 1 ? 2 : 3;      // 16-byte groups of X read per (c-tile, kh)
-    struct Frags { uint4 a[2]; uint4 x[CT * KH][NX]; };
-    auto read = [&](int st, Frags& f) {
-#pragma unroll
-      for (int i = 0; i < 2; ++i) f.a[i] = *reinterpret_cast<const uint4*>(gl + a_base[i] + st * 32);
-#pragma unroll
-      for (int i = 0; i < CT; ++i)
-#pragma unroll
-        for (int kh = 0; kh < KH; ++kh) {
-          const uint16_t* xp = xl + b_base[i] + st * 32 + kh * p.pitch;
-#pragma unroll
-          for (int q = 0; q < NX; ++q) f.x[i * KH + kh][q] = *reinterpret_cast<const uint4*>(xp + 8 * q);
-        }
-    };
-    // tap (kh, kw) reads X shifted by kh rows and (kw - pw) elements: element 8 + kw - pw of the groups read at
-    // row offset kh*pitch (a multiple of 8 elements when KH > 1)
-    auto mfmas = [&](const Frags& f) {
-#pragma unroll
-      for (int i = 0; i < CT; ++i)
-#pragma unroll
-        for (int kh = 0; kh < KH; ++kh) {
-          const uint4(&x)[NX] = f.x[i * KH + kh];
-          bf16x8 b[KW];
-          if constexpr (KW == 1) {
-            b[0] = cut<8>(x[0], x[1]);
-          } else {
-            b[0] = cut<7>(x[0], x[1]);
-            b[1] = cut<8>(x[0], x[1]);
-            b[2] = cut<1>(x[1], x[2]);     // one more element to the right reaches into the third group
-          }
-#pragma unroll
-          for (int t = 0; t < KW; ++t)
-#pragma unroll
-            for (int ao = 0; ao < 2; ++ao)
-              acc[ao][i][kh * KW + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.a[ao]), b[t],
-                                                                               acc[ao][i][kh * KW + t], 0, 0, 0);
-        }
-    };
-    Frags f0, f1;
-    read(0, f0);
-    int st = 0;
-    for (; st + 2 < steps; st += 2) {
-      read(st + 1, f1); mfmas(f0);
-      read(st + 2, f0); mfmas(f1);
-    }
-    if (st + 1 < steps) { read(st + 1, f1); mfmas(f0); mfmas(f1); }
-    else mfmas(f0);
+    dw_bf16_chunk<KH, KW, CT>(p, gl, xl, a_base, b_base, acc);
   }
-
-  // One split only (large dW, few pixels): nothing to add up, the sums go straight into dW (`partial` is dW then):
-  // lane holds 4 consecutive o (rows of D) at one c (column).
-  if (p.n_splits == 1) {
-    float* dw = partial + (int64_t)g * p.ws_g;
-#pragma unroll
-    for (int ao = 0; ao < 2; ++ao)
-#pragma unroll
-      for (int i = 0; i < CT; ++i) {
-        const int c = cb * CX + (CT * wc + i) * 16 + (lane & 15);
-        if (c >= p.Cg) continue;
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const int o = ob * 64 + (2 * wo + ao) * 16 + 4 * (lane >> 4) + v;
-          if (o >= p.Og) continue;
-#pragma unroll
-          for (int t = 0; t < T; ++t)
-            dw[(int64_t)o * p.ws_o + (int64_t)c * p.ws_c + (t / KW) * p.ws_kh + (t % KW) * p.ws_kw] = acc[ao][i][t][v];
-        }
-      }
-    return;
-  }
-  // partial[split][tile][slot][lane]: every accumulator register quadruple goes out as it is, one 16-byte store
-  // per lane (1 KB per wave and slot); the reduction kernel knows which weights a (slot, lane) holds
-  constexpr int SLOTS = 8 * CT * T;
-  const int tile = (g * p.n_oblk + ob) * p.n_cblk + cb;
-  floatx4* dst = reinterpret_cast<floatx4*>(partial) +
-                 ((int64_t)split * p.n_tiles + tile) * (SLOTS * 64) + (widx * 2 * CT * T) * 64 + lane;
-#pragma unroll
-  for (int ao = 0; ao < 2; ++ao)
-#pragma unroll
-    for (int i = 0; i < CT; ++i)
-#pragma unroll
-      for (int t = 0; t < T; ++t) dst[((ao * CT + i) * T + t) * 64] = acc[ao][i][t];
+  dw_finish<KH, KW, CT>(p, partial, g, ob, cb, split, widx, lane, acc);
 }
 
 // The k-steps of one staged chunk: 4 pixels each; the fragments of the next step are read while the MFMAs of the
@@ -364,7 +342,7 @@ __device__ __forceinline__ void dw_f32_chunk(const DwParams& p, const float* gl,
 
 // Leaves the workgroup's sums: in dW itself when there is one split, else in the workspace in accumulator layout.
 template <int KH, int KW, int CT>
-__device__ __forceinline__ void dw_f32_finish(const DwParams& p, float* __restrict__ partial, int g, int ob, int cb, int split,
+__device__ __forceinline__ void dw_finish(const DwParams& p, float* __restrict__ partial, int g, int ob, int cb, int split,
                                               int widx, int lane, const floatx4 (&acc)[2][CT][KH * KW]) {
   constexpr int CX = 32 * CT, T = KH * KW;
   const int wo = widx >> 1, wc = widx & 1;
@@ -552,7 +530,7 @@ __global__ __launch_bounds__(256) void dw_mfma_f32(const DwParams p, const float
     if (more) load(next);
     dw_f32_chunk<KH, KW, CT>(p, gl, xl, a_base, b_base, acc);
   }
-  dw_f32_finish<KH, KW, CT>(p, partial, g, ob, cb, split, widx, lane, acc);
+  dw_finish<KH, KW, CT>(p, partial, g, ob, cb, split, widx, lane, acc);
 }
 
 // fp32, windows with a row extent (KH = 3).  A chunk is TRK rows of ONE image, so the source of staged row r is
@@ -577,7 +555,7 @@ __global__ __launch_bounds__(kRowsThreads) void dw_rows_f32(const DwParams p, co
   // of 7 or 14 pixels, moved as pieces of 4, 2 and 1.
   constexpr int FL = MODE;                                          // floats per item
   constexpr int NB = MODE == 7 ? 4 : MODE == 14 ? 2 : 7;            // items per thread and batch
-  constexpr int NI = NB * (MODE == 4 ? kRowsBatches : 1);           // items per thread and chunk at most
+  constexpr int NI = NB * kRowsBatches;                             // items per thread and chunk at most
   extern __shared__ __align__(16) unsigned char smem[];
   const uint32_t dump = (uint32_t)p.lds_tab_off;                // behind the two buffers
 
@@ -745,7 +723,206 @@ __global__ __launch_bounds__(kRowsThreads) void dw_rows_f32(const DwParams p, co
     for (int i = 0; i < CT; ++i)
 #pragma unroll
       for (int t = 0; t < T; ++t) acc[ao][i][t] += red[((ao * CT + i) * T + t) * 64];
-  dw_f32_finish<KH, KW, CT>(p, partial, g, ob, cb, split, widx, lane, acc);
+  dw_finish<KH, KW, CT>(p, partial, g, ob, cb, split, widx, lane, acc);
+}
+
+// The same design for bf16 inputs (v_mfma_f32_16x16x32_bf16, k-steps of 32 pixels, taps cut out of aligned 16-byte
+// reads): two halves of four waves trade places between multiplying the chunk in one LDS buffer and staging the next
+// chunk into the other.  A staging item is MODE adjacent pixels of one staged row: 4 (8 bytes), 2 or 1, or a whole row
+// of 7 or 14 pixels; rows in LDS start on 16-byte boundaries (the pitch is a multiple of 8 elements), source rows are
+// aligned to an item's size except the whole-row items, which are read as unaligned pieces.
+template <int KW, int CT, int MODE>
+__global__ __launch_bounds__(kRowsThreads) void dw_rows_bf16(const DwParams p, const uint16_t* __restrict__ Gt,
+                                                             const uint16_t* __restrict__ Xt, float* __restrict__ partial) {
+  constexpr int KH = 3, CX = 32 * CT, T = KH * KW;
+  constexpr int NB = MODE == 7 ? 4 : MODE == 14 ? 2 : 7;            // items per thread and batch
+  constexpr int NI = NB * kRowsBatches;                             // items per thread and chunk at most                             // items per thread and chunk at most
+  constexpr int DW = (MODE + 1) / 2;                                // dwords that hold an item
+  extern __shared__ __align__(16) unsigned char smem[];
+  const uint32_t dump = (uint32_t)p.lds_tab_off;                // behind the two buffers
+
+  const int tid = threadIdx.x, lane = tid & 63, htid = tid & 255;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int widx = wave & 3, half = wave >> 2;
+  const int wo = widx >> 1, wc = widx & 1;
+  int bid = blockIdx.x;
+  const int split = bid % p.n_splits; bid /= p.n_splits;
+  const int cb = bid % p.n_cblk; bid /= p.n_cblk;
+  const int ob = bid % p.n_oblk;
+  const int g = bid / p.n_oblk;
+  const int chunk_begin = split * p.chunks_per_split;
+  const int chunk_end = min(p.n_chunks, chunk_begin + p.chunks_per_split);
+  {
+    uint4* z = reinterpret_cast<uint4*>(smem);
+    const int n16 = p.lds_tab_off >> 4;
+    for (int i = tid; i < n16; i += kRowsThreads) z[i] = make_uint4(0, 0, 0, 0);
+  }
+  const int o_lim = p.Og - ob * 64, c_lim = min(p.Cg - cb * CX, CX);
+  const uint16_t* Gg = Gt + (int64_t)(g * p.Og + ob * 64) * p.plane;
+  const uint16_t* Xg = Xt + (int64_t)(g * p.Cg + cb * CX) * p.plane;
+
+  floatx4 acc[2][CT][T];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < CT; ++b)
+#pragma unroll
+      for (int t = 0; t < T; ++t) acc[a][b][t] = floatx4{0.f, 0.f, 0.f, 0.f};
+  int a_base[2], b_base[CT];     // element indices inside a buffer's G and X tile
+#pragma unroll
+  for (int a = 0; a < 2; ++a) a_base[a] = ((2 * wo + a) * 16 + (lane & 15)) * p.CPg + (lane >> 4) * 8;
+#pragma unroll
+  for (int b = 0; b < CT; ++b) b_base[b] = ((CT * wc + b) * 16 + (lane & 15)) * p.CPp + (lane >> 4) * 8 + kGuard - 8;
+
+  // ---- this thread's staging items, worked out once (4 threads per G channel, 256 / CX per X channel; a thread takes
+  // every 4th (8th) item of its channel): byte offset from the chunk's first source row, and the LDS byte offset
+  // inside a buffer with the staged row in the top byte (row 255: never)
+  uint32_t g_off[NI], g_put[NI], x_off[NI], x_put[NI];
+  {
+    const int WR = p.W / MODE;                   // items per row
+    // With several whole images per chunk, image i of the chunk has H + 2 staged rows of its own: row l holds G row l
+    // (the last two stay zero) and X row l - 1 (zero outside the image).
+    const int per = p.H + 2;
+    auto plan_items = [&](uint32_t (&off)[NI], uint32_t (&put)[NI], int tpc_log2, int rows_staged, int ch_lim,
+                          int ch_pitch, int lds_first, uint32_t safe, int image_stride, int l_lo, int l_hi) {
+      const int ch = htid >> tpc_log2, sub = htid & ((1 << tpc_log2) - 1);
+#pragma unroll
+      for (int k = 0; k < NI; ++k) {
+        const int i = sub + (k << tpc_log2);
+        const int r = p.magic_w2 ? (int)__umulhi((uint32_t)i, p.magic_w2) : i;
+        const int j = (i - r * WR) * MODE;
+        const int img = p.ipc > 1 ? r / per : 0, l = r - img * per;
+        const bool exists = r < rows_staged && ch < ch_lim && (p.ipc == 1 || (l >= l_lo && l < l_hi));
+        off[k] = exists ? (uint32_t)(img * image_stride + ch * p.plane + l * p.W + j) * 2 : safe;
+        put[k] = exists ? ((uint32_t)(lds_first + ch * ch_pitch + r * p.pitch + j) * 2) | ((uint32_t)r << 24)
+                        : (dump + (uint32_t)lane * 64) | (255u << 24);
+      }
+    };
+    plan_items(g_off, g_put, 2, p.ipc > 1 ? p.n_xrows : p.TRK, o_lim, p.CPg, 0, 0u, p.gs_n, 0, p.H);
+    plan_items(x_off, x_put, CT == 1 ? 3 : 2, p.n_xrows, c_lim, p.CPp, kGuard + (p.lds_x_off >> 1), (uint32_t)p.W * 2,
+               p.xs_n, 1, p.H + 1);
+  }
+  typedef uint32_t u4_t __attribute__((ext_vector_type(4), aligned(4)));
+  typedef uint32_t u2_t __attribute__((ext_vector_type(2), aligned(4)));
+  typedef uint32_t u2h_t __attribute__((ext_vector_type(2), aligned(2)));
+  typedef uint32_t u1h_t __attribute__((aligned(2)));
+  auto load_item = [&](uint32_t (&v)[DW], const char* src) {
+    if constexpr (MODE == 4) {
+      const uint2 t = *reinterpret_cast<const uint2*>(src);
+      v[0] = t.x; v[1] = t.y;
+    } else if constexpr (MODE == 2) {
+      v[0] = *reinterpret_cast<const uint32_t*>(src);
+    } else if constexpr (MODE == 1) {
+      v[0] = *reinterpret_cast<const uint16_t*>(src);
+    } else if constexpr (MODE == 14) {      // 28 bytes, dword-aligned
+      const u4_t a = *reinterpret_cast<const u4_t*>(src);
+      const u2_t b = *reinterpret_cast<const u2_t*>(src + 16);
+      v[0] = a[0]; v[1] = a[1]; v[2] = a[2]; v[3] = a[3]; v[4] = b[0]; v[5] = b[1];
+      v[6] = *reinterpret_cast<const uint32_t*>(src + 24);
+    } else {                                 // 14 bytes, element-aligned
+      const u2h_t a = *reinterpret_cast<const u2h_t*>(src);
+      v[0] = a[0]; v[1] = a[1];
+      v[2] = *reinterpret_cast<const u1h_t*>(src + 8);
+      v[3] = *reinterpret_cast<const uint16_t*>(src + 12);
+    }
+  };
+  auto store_item = [&](const uint32_t (&v)[DW], unsigned char* dst) {     // (LDS rows start on 16-byte boundaries)
+    if constexpr (MODE == 4) {
+      *reinterpret_cast<uint2*>(dst) = make_uint2(v[0], v[1]);
+    } else if constexpr (MODE == 2) {
+      *reinterpret_cast<uint32_t*>(dst) = v[0];
+    } else if constexpr (MODE == 1) {
+      *reinterpret_cast<uint16_t*>(dst) = (uint16_t)v[0];
+    } else if constexpr (MODE == 14) {
+      *reinterpret_cast<uint4*>(dst) = make_uint4(v[0], v[1], v[2], v[3]);
+      *reinterpret_cast<uint2*>(dst + 16) = make_uint2(v[4], v[5]);
+      *reinterpret_cast<uint32_t*>(dst + 24) = v[6];
+    } else {
+      *reinterpret_cast<uint2*>(dst) = make_uint2(v[0], v[1]);
+      *reinterpret_cast<uint32_t*>(dst + 8) = v[2];
+      *reinterpret_cast<uint16_t*>(dst + 12) = (uint16_t)v[3];
+    }
+  };
+  struct Batch { uint32_t v[NB][DW]; };
+  auto fetch = [&](Batch& bt, const char* src_base, const uint32_t* off, const uint32_t* put, int count, uint32_t safe,
+                   int r_lo, int r_hi) {
+#pragma unroll
+    for (int k = 0; k < NB; ++k) {
+      if (k >= count) break;
+      const bool ok = ((put[k] >> 24) - (uint32_t)r_lo) < (uint32_t)(r_hi - r_lo);
+      load_item(bt.v[k], src_base + (ok ? off[k] : safe));
+    }
+  };
+  auto put_batch = [&](Batch& bt, uint32_t buf, const uint32_t* put, int count, int r_lo, int r_hi) {
+#pragma unroll
+    for (int k = 0; k < NB; ++k) {
+      if (k >= count) break;
+      const bool ok = ((put[k] >> 24) - (uint32_t)r_lo) < (uint32_t)(r_hi - r_lo);
+      const bool never = (put[k] >> 24) == 255u;
+#pragma unroll
+      for (int e = 0; e < DW; ++e) bt.v[k][e] = ok ? bt.v[k][e] : 0u;
+      store_item(bt.v[k], smem + (put[k] & 0xffffffu) + (never ? 0u : buf));
+    }
+  };
+  auto stage = [&](int q, uint32_t buf) {
+    int n = p.magic_cpi ? (int)__umulhi((uint32_t)q, p.magic_cpi) : q;
+    int h0 = (q - n * p.cpi) * p.TRK;
+    int rows = min(p.TRK, p.H - h0);
+    int x_lo = h0 == 0 ? 1 : 0, x_hi = min(rows + 2, p.H - h0 + 1);
+    if (p.ipc > 1) {                // whole images q*ipc ..: every staged row of an image that the batch has exists
+      n = q * p.ipc; h0 = 0;
+      rows = min(p.ipc, p.n_images - n) * (p.H + 2);
+      x_lo = 0; x_hi = rows;
+    }
+    const char* gb = reinterpret_cast<const char*>(Gg) + ((int64_t)n * p.gs_n + (int64_t)h0 * p.W) * 2;
+    // (one row above the chunk; when the chunk starts an image that row is not read: staged row 0 does not exist then
+    // and the safe offset points at the chunk's first row)
+    const char* xb = reinterpret_cast<const char*>(Xg) + ((int64_t)n * p.xs_n + (int64_t)(h0 - 1) * p.W) * 2;
+#pragma unroll
+    for (int b = 0; b < NI / NB; ++b) {
+      const int ng = p.ni_g - b * NB, nx = p.ni_x - b * NB;       // (uniform) items of this batch
+      if (ng <= 0 && nx <= 0) break;
+      Batch bg, bx;
+      fetch(bg, gb, g_off + b * NB, g_put + b * NB, ng, 0u, 0, rows);
+      fetch(bx, xb, x_off + b * NB, x_put + b * NB, nx, (uint32_t)p.W * 2, x_lo, x_hi);
+      put_batch(bg, buf, g_put + b * NB, ng, 0, rows);
+      put_batch(bx, buf, x_put + b * NB, nx, x_lo, x_hi);
+    }
+  };
+
+  __syncthreads();                                   // LDS is zeroed
+  if (half == 0 && chunk_begin < chunk_end) stage(chunk_begin, 0u);
+  __syncthreads();
+  for (int q = chunk_begin; q < chunk_end; ++q) {
+    const int par = (q - chunk_begin) & 1;
+    if (par == half) {
+      const unsigned char* cur = smem + par * p.lds_buf;
+      dw_bf16_chunk<KH, KW, CT>(p, reinterpret_cast<const uint16_t*>(cur),
+                                reinterpret_cast<const uint16_t*>(cur + p.lds_x_off), a_base, b_base, acc);
+    } else if (q + 1 < chunk_end) {
+      stage(q + 1, (uint32_t)((par ^ 1) * p.lds_buf));
+    }
+    __syncthreads();
+  }
+  // the sums of the two halves meet in LDS: the upper waves leave theirs there, the lower ones add them
+  floatx4* red = reinterpret_cast<floatx4*>(smem) + (widx * 2 * CT * T) * 64 + lane;
+  if (half) {
+#pragma unroll
+    for (int ao = 0; ao < 2; ++ao)
+#pragma unroll
+      for (int i = 0; i < CT; ++i)
+#pragma unroll
+        for (int t = 0; t < T; ++t) red[((ao * CT + i) * T + t) * 64] = acc[ao][i][t];
+  }
+  __syncthreads();
+  if (half) return;
+#pragma unroll
+  for (int ao = 0; ao < 2; ++ao)
+#pragma unroll
+    for (int i = 0; i < CT; ++i)
+#pragma unroll
+      for (int t = 0; t < T; ++t) acc[ao][i][t] += red[((ao * CT + i) * T + t) * 64];
+  dw_finish<KH, KW, CT>(p, partial, g, ob, cb, split, widx, lane, acc);
 }
 
 // Adds the split partials kept in the accumulator layout of the contraction kernels and writes the sums into dW;
@@ -851,6 +1028,69 @@ bool fill_dw(const syno_plan* plan, DwParams& p) {
   const int ep = (c.Wo % 4 == 0) ? 4 : (c.Wo % 2 == 0) ? 2 : 1;   // pixels per staging item
   const int W2 = c.Wo / ep, halo = c.KH - 1;                       // items per row
   if (ep == 4) p.pitch = (p.pitch + 3) & ~3;                      // 8-byte LDS writes
+  if (c.KH == 3 && (c.Wo == 7 || c.Wo == 14)) {
+    // windows with a row extent on narrow images (whole rows as staging items): the kernel whose wave halves alternate
+    // between multiplying and staging.  Chunks as large as the per-thread item lists and two LDS buffers allow: rows
+    // of one image, or several whole small images.  (Measured slower than the table kernel on 28- and 56-pixel rows,
+    // whose 8-byte items it fetches four lanes to a channel: they stay there.)
+    const int mode = (c.Wo == 7 || c.Wo == 14) ? c.Wo : ep;
+    const int ni_cap = (mode == 7 ? 4 : mode == 14 ? 2 : 7) * kRowsBatches;
+    const int wr = c.Wo / mode;
+    auto skew = [](int v) { v = (v + 7) & ~7; return (v & 31) == 0 ? v + 8 : v; };
+    auto cfg = [&](int t, int ipc, DwParams& o) {     // t rows of an image per chunk, or ipc whole images
+      o = p;
+      const int per = c.Ho + 2;
+      o.ipc = ipc;
+      o.n_xrows = ipc > 1 ? ipc * per : t + 2;
+      o.TRK = ipc > 1 ? o.n_xrows - 2 : t;
+      o.CP = (o.TRK * o.pitch + 31) & ~31;
+      o.CPg = skew(o.CP + 8);
+      o.CPp = skew(std::max(o.CP, o.n_xrows * o.pitch) + 2 * o.pitch + 48);
+      o.ni_g = ((ipc > 1 ? o.n_xrows : t) * wr + 3) / 4;
+      o.ni_x = (o.n_xrows * wr + 256 / cx - 1) / (256 / cx);
+      o.lds_x_off = 64 * o.CPg * 2;
+      o.lds_buf = o.lds_x_off + cx * o.CPp * 2;
+      o.lds_tab_off = 2 * o.lds_buf;
+      o.lds_bytes = std::max(o.lds_tab_off + 4096, 4 * 2 * (cx / 32) * c.KH * c.KW * 1024);
+      return std::max(o.ni_g, o.ni_x) <= ni_cap && o.lds_bytes <= 160 * 1024 && o.n_xrows <= 254;
+    };
+    DwParams best;
+    int t = c.Ho;
+    while (t > 1 && !cfg(t, 1, best)) --t;
+    if (!cfg(t, 1, best)) return false;
+    if (t == c.Ho) {                 // whole images: as many per chunk as fit
+      int m = 1;
+      DwParams more;
+      while (m < c.N && cfg(c.Ho, m + 1, more)) { best = more; ++m; }
+      best.cpi = 1;
+      best.n_chunks = (c.N + best.ipc - 1) / best.ipc;
+    } else {
+      best.cpi = (c.Ho + t - 1) / t;
+      const int tb = (c.Ho + best.cpi - 1) / best.cpi;       // chunks of an image about equally long
+      cfg(tb, 1, best);
+      best.cpi = (c.Ho + tb - 1) / tb;
+      best.n_chunks = c.N * best.cpi;
+    }
+    p = best;
+    p.n_images = c.N;
+    p.mode = mode;
+    p.direct = 1;
+    p.magic_w2 = magic_of(wr);
+    p.magic_cpi = magic_of(p.cpi);
+    p.n_oblk = (c.Og + 63) / 64;
+    p.n_cblk = (c.Cg + cx - 1) / cx;
+    const int tiles = c.G * p.n_oblk * p.n_cblk;
+    p.n_tiles = tiles;
+    p.ct = cx / 32;
+    p.slots = 8 * p.ct * c.KH * c.KW;
+    const int target = plan->opt.dw_workgroups > 0 ? plan->opt.dw_workgroups : 256;
+    int splits = std::max(1, std::min(p.n_chunks, target / std::max(1, tiles)));
+    while (splits > 1 && (int64_t)splits * tiles * p.slots * 1024 > (40ll << 20)) splits /= 2;
+    p.chunks_per_split = (p.n_chunks + splits - 1) / splits;
+    p.rows_per_split = p.chunks_per_split * p.TRK;
+    p.n_splits = (p.n_chunks + p.chunks_per_split - 1) / p.chunks_per_split;
+    return true;
+  }
   int trk = std::max(1, 224 / p.pitch);
   if (c.KH > 1) trk = std::min(trk, c.Ho);
   while (trk > 1 && 64 * (trk + halo) * W2 > dw_items(ep) * 256) --trk;
@@ -908,7 +1148,7 @@ bool fill_dw(const syno_plan* plan, DwParams& p) {
 
 // fp32 configuration: element items, k-steps of 4 pixels, channel pitch = 4 * odd floats so that the 16 rows x 4
 // pixels of a fragment read fall into 64 distinct banks.
-bool fill_dw_f32(const syno_plan* plan, DwParams& p) {
+bool fill_dw_f32_as(const syno_plan* plan, DwParams& p, bool direct) {
   const ConvLike& c = plan->conv;
   p = DwParams{};
   p.G = c.G; p.Og = c.Og; p.Cg = c.Cg; p.H = c.Ho; p.W = c.Wo; p.KH = c.KH; p.KW = c.KW; p.ph = c.ph; p.pw = c.pw;
@@ -925,7 +1165,6 @@ bool fill_dw_f32(const syno_plan* plan, DwParams& p) {
   const int vec = (c.Wo % 4 == 0) ? 4 : (c.Wo % 2 == 0) ? 2 : 1;
   // windows with a row extent go to the kernel that derives its source rows from the chunk's position and keeps
   // two chunks in LDS (one being multiplied, one being staged); the others look rows up in a table
-  const bool direct = c.KH == 3;
   const int budget = kF32Items * vec * 256;        // table kernel: floats per tensor and chunk
   int trk = std::max(1, 200 / p.pitch);
   if (direct && c.Ho * p.pitch <= 256) trk = c.Ho;     // small images whole
@@ -939,7 +1178,7 @@ bool fill_dw_f32(const syno_plan* plan, DwParams& p) {
   // staging items of that kernel: whole rows of 7 or 14 pixels, else `vec` pixels; 4 threads per G channel and
   // 256 / cx per X channel share a channel's items
   const int mode = (c.Wo == 7 || c.Wo == 14) ? c.Wo : vec;
-  const int ni_cap = mode == 7 ? 4 : mode == 14 ? 2 : mode == 4 ? 7 * kRowsBatches : 7;
+  const int ni_cap = (mode == 7 ? 4 : mode == 14 ? 2 : 7) * kRowsBatches;
   auto items_g = [&](int t) { return (t * (c.Wo / mode) + 3) / 4; };
   auto items_x = [&](int t) { return ((t + halo) * (c.Wo / mode) + 256 / cx - 1) / (256 / cx); };
   auto over = [&](int t) {
@@ -1002,6 +1241,13 @@ bool fill_dw_f32(const syno_plan* plan, DwParams& p) {
   }
   return p.lds_bytes <= 144 * 1024 && 64 * p.CPp < (1 << 30) && p.n_xrows <= 256 && p.n_xrows <= 256 &&
          (int64_t)64 * p.n_xrows * c.Wo * std::max(c.Wo, p.n_xrows * c.Wo) < (1ll << 32);
+}
+
+// Windows with a row extent take the kernel with the alternating wave halves when their rows fit its item lists,
+// else (and all other windows) the kernel that looks its rows up in a table.
+bool fill_dw_f32(const syno_plan* plan, DwParams& p) {
+  if (plan->conv.KH == 3 && fill_dw_f32_as(plan, p, true)) return true;
+  return fill_dw_f32_as(plan, p, false);
 }
 
 bool fill_any(const syno_plan* plan, DwParams& p) {
@@ -1077,12 +1323,14 @@ syno_status launch_mfma_dw(const syno_plan* plan, const void* A, const void* B, 
     const float* Xf = static_cast<const float*>(B);
     by_window([&](auto kh_c, auto kw_c, auto ct_c) {
       constexpr int kh = decltype(kh_c)::value, kw = decltype(kw_c)::value, ct = decltype(ct_c)::value;
-      if constexpr (kh == 3) {
+      if (kh == 3 && p.direct) {
+        if constexpr (kh == 3) {
         if (p.mode == 4) launch_dw_kernel(dw_rows_f32<kw, ct, 4>, grid, p, Gf, Xf, dst, stream, kRowsThreads);
         else if (p.mode == 7) launch_dw_kernel(dw_rows_f32<kw, ct, 7>, grid, p, Gf, Xf, dst, stream, kRowsThreads);
         else if (p.mode == 14) launch_dw_kernel(dw_rows_f32<kw, ct, 14>, grid, p, Gf, Xf, dst, stream, kRowsThreads);
         else if (p.mode == 2) launch_dw_kernel(dw_rows_f32<kw, ct, 2>, grid, p, Gf, Xf, dst, stream, kRowsThreads);
         else launch_dw_kernel(dw_rows_f32<kw, ct, 1>, grid, p, Gf, Xf, dst, stream, kRowsThreads);
+        }
       } else {
         if (p.W % 4 == 0) launch_dw_kernel(dw_mfma_f32<kh, kw, ct, 4>, grid, p, Gf, Xf, dst, stream);
         else if (p.W % 2 == 0) launch_dw_kernel(dw_mfma_f32<kh, kw, ct, 2>, grid, p, Gf, Xf, dst, stream);
@@ -1094,6 +1342,13 @@ syno_status launch_mfma_dw(const syno_plan* plan, const void* A, const void* B, 
     const uint16_t* X = static_cast<const uint16_t*>(B);
     by_window([&](auto kh_c, auto kw_c, auto ct_c) {
       constexpr int kh = decltype(kh_c)::value, kw = decltype(kw_c)::value, ct = decltype(ct_c)::value;
+      bool taken = false;
+      if constexpr (kh == 3) {
+        taken = p.direct != 0;
+        if (p.direct && p.mode == 7) launch_dw_kernel(dw_rows_bf16<kw, ct, 7>, grid, p, G, X, dst, stream, kRowsThreads);
+        else if (p.direct) launch_dw_kernel(dw_rows_bf16<kw, ct, 14>, grid, p, G, X, dst, stream, kRowsThreads);
+      }
+      if (taken) return;
       if (p.W % 4 == 0) launch_dw_kernel(dw_mfma_bf16<kh, kw, ct, 4>, grid, p, G, X, dst, stream);
       else if (p.W % 2 == 0) launch_dw_kernel(dw_mfma_bf16<kh, kw, ct, 2>, grid, p, G, X, dst, stream);
       else launch_dw_kernel(dw_mfma_bf16<kh, kw, ct, 1>, grid, p, G, X, dst, stream);

@@ -207,6 +207,32 @@ def main() -> int:
                      "clock": "HIP events on the launch stream around K back-to-back launches of each call of the timed step "
                               "(the interval of a backward call includes its small weight-transposition / partial-sum "
                               "kernels)"})
+        # the clock the dominant kernel actually runs at: its workgroups leave the constant 100 MHz counter and the shader
+        # clock counter on entry and exit (an option of the plan); a launch of each call, after warm-up launches
+        probe = torch.zeros(4 * 8192, dtype=torch.int64, device=dev)
+        ghz = []
+        if key[0].startswith("mfma_contraction"):
+            for c in dom:
+                probed = syno.Plan(c.w.desc, clock_probe=probe.data_ptr())
+                call = probed.bind(c.which, *c.bufs[0])
+                for _ in range(5):
+                    call()
+                torch.cuda.synchronize()
+                probe.zero_()
+                torch.cuda.synchronize()
+                call()
+                torch.cuda.synchronize()
+                t = probe.view(-1, 4).cpu().numpy().astype(np.float64)
+                t = t[(t[:, 0] > 0) & (t[:, 2] > t[:, 0])]
+                if len(t):
+                    ghz.append(float(np.median((t[:, 3] - t[:, 1]) / (t[:, 2] - t[:, 0]))) / 10.0)
+        if ghz:
+            clock = sum(ghz) / len(ghz)
+            roof.update({"sustained_clock_GHz": clock, "nominal_clock_GHz": 2.4,
+                         "frac_of_peak_at_sustained_clock": roof["frac"] * 2.4 / clock,
+                         "sustained_clock_note": "median over workgroups of (shader-clock ticks) / (100 MHz ticks) between a "
+                                                 "workgroup's entry and exit, mean over the averaged launches; the published "
+                                                 "peak assumes 2.4 GHz"})
         # kernel-only duration and HBM traffic from committed rocprofv3 summaries, while the kernel is unchanged
         k_us = stored_profile("kernel_us", f"{family}_{tag}")
         roof["rocprof_avg_kernel_us"] = k_us

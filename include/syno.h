@@ -86,12 +86,18 @@ typedef struct {
  *                   mfma_rows = output rows per workgroup tile.  Ignored unless the pair fits the operator.
  *   mfma_taps       1: one window tap per inner step even where three would be taken
  *   dw_workgroups   target number of workgroups of the backward-weight contraction (split of the pixel axis)
- *   view_workgroups cap on the grid of the view kernel */
+ *   view_workgroups cap on the grid of the view kernel
+ *   clock_probe     measurement aid (device memory, 4 x int64 per workgroup of the launch, owned by the caller, or
+ *                   NULL): the first thread of every workgroup of the contraction kernel (forward and backward-data)
+ *                   leaves the constant 100 MHz timestamp counter and the shader clock counter there on entry
+ *                   ([0], [1]) and on exit ([2], [3]); the ratio of the two differences is the clock the kernel
+ *                   ran at.  Results are not affected. */
 typedef struct {
   int32_t kernel_policy;
   int32_t mfma_variant, mfma_rows, mfma_taps;
   int32_t dw_workgroups;
   int32_t view_workgroups;
+  void* clock_probe;
 } syno_plan_options;
 
 /* Coordinate ids 0..n_out-1 are the output iterators in the layout order of `out`; primitives

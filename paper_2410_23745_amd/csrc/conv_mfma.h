@@ -16,6 +16,7 @@ struct MfmaParams {
   int32_t xs_n, xs_c;                 // source strides: image, channel (rows are Wi apart, columns adjacent)
   int32_t os_n, os_o;                 // result strides: image, channel
   int32_t ws_g, ws_o, ws_c, ws_kh, ws_kw, w_base;
+  uint32_t probe_lo, probe_hi;        // optional clock probe (device address of 4 x int64 per workgroup; 0: none)
   // tiling
   int32_t TR, BN, KC, n_mblocks, n_nblocks, n_chunks;
   int32_t n_slots, Wp, cgrps;
@@ -111,6 +112,11 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
   float4* xl = reinterpret_cast<float4*>(smem);
   int* slot_src = reinterpret_cast<int*>(smem + p.lds_tab_off);
 
+  long long* const probe = reinterpret_cast<long long*>(((unsigned long long)p.probe_hi << 32) | p.probe_lo);
+  if (probe && threadIdx.x == 0) {
+    probe[(long long)blockIdx.x * 4 + 0] = wall_clock64();
+    probe[(long long)blockIdx.x * 4 + 1] = clock64();
+  }
   const int tid = threadIdx.x, lane = tid & 63;
   const int widx = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in an SGPR
   const int wk = widx / (WM * WN), wtile = widx - wk * (WM * WN);
@@ -641,6 +647,10 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
     case 7: if constexpr (TM >= 7) run(std::integral_constant<int, 7>{}); break;
     case 8: if constexpr (TM >= 8) run(std::integral_constant<int, 8>{}); break;
     default: break;
+  }
+  if (probe && threadIdx.x == 0) {
+    probe[(long long)blockIdx.x * 4 + 2] = wall_clock64();
+    probe[(long long)blockIdx.x * 4 + 3] = clock64();
   }
 }
 

@@ -327,6 +327,8 @@ void mfma_configure(syno_plan* plan, int which) {
       }
   fill_params(plan, which, best_v, best_tr, mp);
   if (plan->opt.mfma_taps == 1) mp.U = 1;     // (option: the one-tap-per-row-step instantiation)
+  mp.probe_lo = (uint32_t)reinterpret_cast<uintptr_t>(plan->opt.clock_probe);
+  mp.probe_hi = (uint32_t)(reinterpret_cast<uintptr_t>(plan->opt.clock_probe) >> 32);
   static_assert(sizeof(MfmaParams) <= sizeof(plan->launch[which].params), "parameter record does not fit");
   memcpy(plan->launch[which].params, &mp, sizeof mp);
   plan->launch[which].params_ready = true;

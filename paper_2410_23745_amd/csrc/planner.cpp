@@ -964,7 +964,37 @@ bool cut_once(const OwnedDesc& whole, OwnedDesc& top, OwnedDesc& bottom, int& we
       }
     };
     for (int c : g.in_coords) below(c);
+    const size_t n_from_x = z.size();
     if (on_w >= 0) for (int c : *weights[on_w]) below(c);
+    // Z's layout is the pass's to choose.  Keep X's order, but in the arrangement the lowered forms look for: the
+    // leading axes of X that pass through untouched (batch), then the iterators that only the stage's weight brings
+    // (its output channels), then the other coordinates that are not image axes (channel digits, window iterators),
+    // then the image axes (coordinates that an Unfold anywhere in the graph slides a window over).
+    {
+      std::vector<char> spatial(kMaxCoordId, 0);
+      for (const syno_prim& q : g.prims)
+        if (q.kind == SYNO_UNFOLD) spatial[q.in[0]] = spatial[q.out[0]] = 1;
+      for (bool grown = true; grown;) {      // ... or over the coarse part of which it is (Split, Merge, Stride, Shift)
+        grown = false;
+        for (const syno_prim& q : g.prims)
+          if (q.kind == SYNO_SPLIT || q.kind == SYNO_MERGE || q.kind == SYNO_STRIDE || q.kind == SYNO_SHIFT)
+            if (spatial[q.in[0]] != spatial[q.out[0]]) { spatial[q.in[0]] = spatial[q.out[0]] = 1; grown = true; }
+      }
+      std::vector<int> lead, from_w, other, image;
+      bool leading = true;
+      for (size_t i = 0; i < z.size(); ++i) {
+        const int c = z[i];
+        const bool untouched_axis = i < n_from_x && std::find(g.in_coords.begin(), g.in_coords.end(), c) != g.in_coords.end();
+        if (i >= n_from_x) { from_w.push_back(c); continue; }
+        if (spatial[c]) { image.push_back(c); leading = false; continue; }
+        if (leading && untouched_axis) lead.push_back(c);
+        else { other.push_back(c); leading = false; }
+      }
+      z = lead;
+      z.insert(z.end(), from_w.begin(), from_w.end());
+      z.insert(z.end(), other.begin(), other.end());
+      z.insert(z.end(), image.begin(), image.end());
+    }
     // every coordinate entering the closure from below must have been found (it is, through X or W, unless the
     // closure ends in an Expand, which has no top side)
     bool complete = true;
@@ -1065,6 +1095,69 @@ syno_status materialise(const syno_desc* desc, std::vector<OwnedDesc>& stages, s
 }
 
 // ---------------------------------------------------------------------------------------------
+namespace {
+// Adjacent axes of X that are both plain Reduce iterators Shared with the weight, whose weight copies are adjacent
+// axes of W in the same order, are one iterator of the product size as far as memory goes (row-major layouts on
+// both sides).  Returns the descriptor with every such pair fused (and its ids renumbered), or false when there is
+// none.  The tensors' bytes are the same, so a lowered form recognised on the fused graph serves the original.
+bool fuse_reduced_axes(const syno_desc& d, OwnedDesc& out) {
+  std::vector<syno_prim> P(d.prims, d.prims + d.n_prim);
+  std::vector<int32_t> xin(d.input_coords, d.input_coords + d.n_in), win(d.weight_coords, d.weight_coords + d.n_w);
+  bool any = false;
+  for (bool again = true; again;) {
+    again = false;
+    auto producer = [&](int c) {
+      for (size_t k = 0; k < P.size(); ++k)
+        for (int t = 0; t < arity_out(P[k].kind); ++t)
+          if (P[k].out[t] == c) return (int)k;
+      return -1;
+    };
+    // the Share that hands `a` to X and its other copy to W, fed by a Reduce directly: (share, reduce, weight copy)
+    auto shared_reduce = [&](int a, int& sh, int& rd, int& b) {
+      sh = producer(a);
+      if (sh < 0 || P[sh].kind != SYNO_SHARE) return false;
+      rd = producer(P[sh].in[0]);
+      if (rd < 0 || P[rd].kind != SYNO_REDUCE) return false;
+      b = P[sh].out[0] == a ? P[sh].out[1] : P[sh].out[0];
+      return std::find(win.begin(), win.end(), b) != win.end();
+    };
+    for (size_t i = 0; i + 1 < xin.size() && !again; ++i) {
+      int s1, r1, b1, s2, r2, b2;
+      if (!shared_reduce(xin[i], s1, r1, b1) || !shared_reduce(xin[i + 1], s2, r2, b2)) continue;
+      const size_t p1 = std::find(win.begin(), win.end(), b1) - win.begin();
+      if (p1 + 1 >= win.size() || win[p1 + 1] != b2) continue;
+      bool read_elsewhere = false;          // (a Shift may read a coordinate without consuming it)
+      for (const syno_prim& q : P)
+        if (q.kind == SYNO_SHIFT && q.shift_by >= 0)
+          for (int c : {xin[i], xin[i + 1], b1, b2, P[s1].in[0], P[s2].in[0]}) read_elsewhere |= q.shift_by == c;
+      if (read_elsewhere) continue;
+      P[r1].param *= P[r2].param;
+      xin.erase(xin.begin() + i + 1);
+      win.erase(win.begin() + p1 + 1);
+      for (int k : {std::max(s2, r2), std::min(s2, r2)}) P.erase(P.begin() + k);
+      again = any = true;
+    }
+  }
+  if (!any) return false;
+  // renumber: output iterators keep their ids, every other coordinate gets the next free one in definition order
+  std::vector<int> remap(kMaxCoordId, -1);
+  int next = d.n_out;
+  for (int i = 0; i < d.n_out; ++i) remap[i] = i;
+  out = OwnedDesc{};
+  out.dims.assign(d.out_dims, d.out_dims + d.n_out);
+  for (syno_prim q : P) {
+    for (int t = 0; t < arity_in(q.kind); ++t) q.in[t] = remap[q.in[t]];
+    if (q.kind == SYNO_SHIFT && q.shift_by >= 0) q.shift_by = remap[q.shift_by];
+    for (int t = 0; t < arity_out(q.kind); ++t) { remap[q.out[t]] = next; q.out[t] = next++; }
+    out.prims.push_back(q);
+  }
+  for (int c : xin) out.xin.push_back(remap[c]);
+  for (int c : win) out.win.push_back(remap[c]);
+  out.in_dtype = d.in_dtype; out.out_dtype = d.out_dtype;
+  return true;
+}
+}  // namespace
+
 syno_status build_plan(const syno_desc* desc, syno_plan* plan, std::string* why) {
   if (desc->options) plan->opt = *desc->options;
   const int policy = plan->opt.kernel_policy;
@@ -1112,6 +1205,14 @@ syno_status build_plan(const syno_desc* desc, syno_plan* plan, std::string* why)
       return unsupported("more than 2^31-1 sum points per element in one of the passes");
 
   plan->conv_like = recognise_conv(g, plan->conv);
+  if (!plan->conv_like) {      // several reduced channel-like axes side by side (a stage cut off by the pass): one axis
+    OwnedDesc fused;
+    Graph gf;
+    if (fuse_reduced_axes(*desc, fused)) {
+      const syno_desc df = fused.view();
+      if (parse_graph(&df, gf, nullptr) == SYNO_OK) plan->conv_like = recognise_conv(gf, plan->conv);
+    }
+  }
   plan->share_window = !plan->conv_like && recognise_share_window(g, plan->window);
   plan->pure_view = recognise_view(g, plan->view);
 

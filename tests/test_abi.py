@@ -364,6 +364,11 @@ def test_two_weight_graph_is_cut_into_single_weight_stages(syno, oracle):
     assert [p.w_shape for p in chain.stages] == shapes
     assert chain.stages[0].x_shape == (2, 16, 6, 8) and chain.stages[1].out_shape == (2, 16, 6, 8)
     assert chain.stages[0].out_shape == chain.stages[1].x_shape
+    # the stored tensor is laid out [n, d, gi, k, h, w]: batch, the weight's own iterator, channel digit, window iterator,
+    # image axes; that is the layout of the hand-written first stage, so both stages land on the fast kernels (the second
+    # one as a convolution over the three reduced axes taken as one channel axis)
+    assert chain.stages[0].out_shape == (2, 2, 4, 3, 6, 8)
+    assert [p.kernel(k) for p in chain.stages for k in range(3)] == ["bandwidth_share_window"] * 3 + ["mfma_contraction_f32"] * 3
     # multiply-adds: the two stages together cost less than the single loop nest
     pts = lambda p: int(np.prod(p.out_shape)) * p.free_size(syno.FWD)
     single = 2 * 16 * 6 * 8 * (2 * 4 * 3 * 3 * 4)
@@ -384,3 +389,26 @@ def test_two_weight_graph_is_cut_into_single_weight_stages(syno, oracle):
         assert all(sw in (-1, 0, 1) for sw in c.stage_weight) and sorted(x for x in c.stage_weight if x >= 0) == [0, 1]
     except syno.SynoError as e2:
         assert e2.status == 4
+
+
+def test_adjacent_reduced_axes_count_as_one_channel_axis(syno):
+    """A convolution whose input channels are written as three adjacent reduced axes, in the same order in X and in
+    the weight, has the same bytes as the plain convolution and is lowered like it; with the axes in different orders
+    on the two sides it is not."""
+    from syno_inputs.descriptor import Builder
+
+    def conv_split_channels(w_order):
+        b = Builder([("n", 2), ("o", 16), ("h", 9), ("w", 10)])
+        n, o, h, w = range(4)
+        pairs = [b.share(b.reduce(sz)) for sz in (2, 4, 3)]           # (X copy, W copy) of d, gi, k
+        jx, jw = b.share(b.reduce(3))
+        hh = b.unfold(h, jx)
+        xs = [p[0] for p in pairs]
+        ws = [pairs[i][1] for i in w_order]
+        return b.finish([n] + xs + [hh, w], [o] + ws + [jw], 0, 0)
+
+    same = syno.Plan(conv_split_channels((0, 1, 2)))
+    assert same.x_shape == (2, 2, 4, 3, 9, 10) and same.w_shape == (16, 2, 4, 3, 3)
+    assert [same.kernel(k) for k in range(3)] == ["mfma_contraction_f32"] * 3
+    other = syno.Plan(conv_split_channels((1, 0, 2)))
+    assert [other.kernel(k) for k in range(3)] == ["generic_index_program"] * 3

@@ -522,6 +522,9 @@ def test_operator1_single_graph_with_two_weights(syno, oracle, shape, dt):
     assert len(chain.stages) == 2 and chain.stage_weight == [0, 1]
     D, Cg = Co // g // s_, Cin // g
     assert chain.stages[0].w_shape == (D, g, Cg, k1) and chain.stages[1].w_shape == (Co, D, g, k1, k1)
+    if k1 == 3:      # the cut-off stages are laid out like the hand-written ones and run on the same kernels
+        fam = "mfma_contraction_f32" if dt == "f32" else "mfma_contraction_bf16"
+        assert [p.kernel(0) for p in chain.stages] == ["bandwidth_share_window", fam]
     st = wl.Stream(71)
     from syno_inputs.rng import bf16_bits_to_f32, to_bf16_bits
     q = (lambda a: bf16_bits_to_f32(to_bf16_bits(np.asarray(a, dtype=np.float32)))) if dt != "f32" else (lambda a: np.asarray(a, dtype=np.float32))

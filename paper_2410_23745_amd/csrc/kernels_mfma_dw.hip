@@ -1,5 +1,10 @@
-// MFMA backward-weight contraction for convolution-like operators (bf16 inputs, fp32 result):
+// MFMA backward-weight contraction for convolution-like operators (bf16 or fp32 inputs, fp32 result):
 //   dW[g,o,c,kh,kw] = sum_{n,h,w} G[n, g*Og+o, h, w] * X[n, g*Cg+c, row(h,g)+kh-ph, w+kw-pw]
+// Kernels in this file:
+//   dw_mfma_bf16, dw_mfma_f32   any supported window; the source rows of a chunk come from a table in LDS
+//   dw_rows_f32, dw_rows_bf16   windows with a row extent (KH = 3): eight waves in two halves that alternate between
+//                               multiplying one LDS buffer and staging the next chunk into the other
+//   dw_reduce_slots, _tiles     fixed-order sum of the split partials into dW
 // A GEMM per group and tap with M = o, N = c and the reduction over the pixels (n,h,w), which is the
 // contiguous axis of both operands - exactly what the bf16 MFMA wants (8 consecutive K per lane).
 //
@@ -89,55 +94,55 @@ template <int KH, int KW, int CT>
 __device__ __forceinline__ void dw_bf16_chunk(const DwParams& p, const uint16_t* gl, const uint16_t* xl,
                                               const int (&a_base)[2], const int (&b_base)[CT],
                                               floatx4 (&acc)[2][CT][KH * KW]) {
-    const int steps = p.CP >> 5;
-    constexpr int NX = KW == 1 ? 2 : 3;      // 16-byte groups of X read per (c-tile, kh)
-    struct Frags { uint4 a[2]; uint4 x[CT * KH][NX]; };
-    auto read = [&](int st, Frags& f) {
+  const int steps = p.CP >> 5;
+  constexpr int NX = KW == 1 ? 2 : 3;      // 16-byte groups of X read per (c-tile, kh)
+  struct Frags { uint4 a[2]; uint4 x[CT * KH][NX]; };
+  auto read = [&](int st, Frags& f) {
 #pragma unroll
-      for (int i = 0; i < 2; ++i) f.a[i] = *reinterpret_cast<const uint4*>(gl + a_base[i] + st * 32);
+    for (int i = 0; i < 2; ++i) f.a[i] = *reinterpret_cast<const uint4*>(gl + a_base[i] + st * 32);
 #pragma unroll
-      for (int i = 0; i < CT; ++i)
+    for (int i = 0; i < CT; ++i)
 #pragma unroll
-        for (int kh = 0; kh < KH; ++kh) {
-          const uint16_t* xp = xl + b_base[i] + st * 32 + kh * p.pitch;
+      for (int kh = 0; kh < KH; ++kh) {
+        const uint16_t* xp = xl + b_base[i] + st * 32 + kh * p.pitch;
 #pragma unroll
-          for (int q = 0; q < NX; ++q) f.x[i * KH + kh][q] = *reinterpret_cast<const uint4*>(xp + 8 * q);
+        for (int q = 0; q < NX; ++q) f.x[i * KH + kh][q] = *reinterpret_cast<const uint4*>(xp + 8 * q);
+      }
+  };
+  // tap (kh, kw) reads X shifted by kh rows and (kw - pw) elements: element 8 + kw - pw of the groups read at
+  // row offset kh*pitch (a multiple of 8 elements when KH > 1)
+  auto mfmas = [&](const Frags& f) {
+#pragma unroll
+    for (int i = 0; i < CT; ++i)
+#pragma unroll
+      for (int kh = 0; kh < KH; ++kh) {
+        const uint4(&x)[NX] = f.x[i * KH + kh];
+        bf16x8 b[KW];
+        if constexpr (KW == 1) {
+          b[0] = cut<8>(x[0], x[1]);
+        } else {
+          b[0] = cut<7>(x[0], x[1]);
+          b[1] = cut<8>(x[0], x[1]);
+          b[2] = cut<1>(x[1], x[2]);     // one more element to the right reaches into the third group
         }
-    };
-    // tap (kh, kw) reads X shifted by kh rows and (kw - pw) elements: element 8 + kw - pw of the groups read at
-    // row offset kh*pitch (a multiple of 8 elements when KH > 1)
-    auto mfmas = [&](const Frags& f) {
 #pragma unroll
-      for (int i = 0; i < CT; ++i)
+        for (int t = 0; t < KW; ++t)
 #pragma unroll
-        for (int kh = 0; kh < KH; ++kh) {
-          const uint4(&x)[NX] = f.x[i * KH + kh];
-          bf16x8 b[KW];
-          if constexpr (KW == 1) {
-            b[0] = cut<8>(x[0], x[1]);
-          } else {
-            b[0] = cut<7>(x[0], x[1]);
-            b[1] = cut<8>(x[0], x[1]);
-            b[2] = cut<1>(x[1], x[2]);     // one more element to the right reaches into the third group
-          }
-#pragma unroll
-          for (int t = 0; t < KW; ++t)
-#pragma unroll
-            for (int ao = 0; ao < 2; ++ao)
-              acc[ao][i][kh * KW + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.a[ao]), b[t],
-                                                                               acc[ao][i][kh * KW + t], 0, 0, 0);
-        }
-    };
-    Frags f0, f1;
-    read(0, f0);
-    int st = 0;
-    for (; st + 2 < steps; st += 2) {
-      read(st + 1, f1); mfmas(f0);
-      read(st + 2, f0); mfmas(f1);
-    }
-    if (st + 1 < steps) { read(st + 1, f1); mfmas(f0); mfmas(f1); }
-    else mfmas(f0);
+          for (int ao = 0; ao < 2; ++ao)
+            acc[ao][i][kh * KW + t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.a[ao]), b[t],
+                                                                             acc[ao][i][kh * KW + t], 0, 0, 0);
+      }
+  };
+  Frags f0, f1;
+  read(0, f0);
+  int st = 0;
+  for (; st + 2 < steps; st += 2) {
+    read(st + 1, f1); mfmas(f0);
+    read(st + 2, f0); mfmas(f1);
   }
+  if (st + 1 < steps) { read(st + 1, f1); mfmas(f0); mfmas(f1); }
+  else mfmas(f0);
+}
 
 // One workgroup: group g, 64 output channels x 32*CT input channels, one split of the pixel rows.
 // 4 waves; wave (wo, wc) owns o-tiles {2wo, 2wo+1} x CT c-tiles x KH*KW taps (CT = 2 for up to 3 taps, 1 for 9).
@@ -297,48 +302,48 @@ __device__ __forceinline__ void dw_f32_chunk(const DwParams& p, const float* gl,
                                              const int (&b_base)[CT], floatx4 (&acc)[2][CT][KH * KW], int first = 0,
                                              int stride = 1) {
   constexpr int T = KH * KW;
-    const int steps = p.CP >> 2;
-    auto read = [&](int st, float (&a)[2], float (&b)[CT * T]) {
+  const int steps = p.CP >> 2;
+  auto read = [&](int st, float (&a)[2], float (&b)[CT * T]) {
 #pragma unroll
-      for (int i = 0; i < 2; ++i) a[i] = gl[a_base[i] + st * 4];
+    for (int i = 0; i < 2; ++i) a[i] = gl[a_base[i] + st * 4];
 #pragma unroll
-      for (int i = 0; i < CT; ++i)
+    for (int i = 0; i < CT; ++i)
 #pragma unroll
-        for (int kh = 0; kh < KH; ++kh)
+      for (int kh = 0; kh < KH; ++kh)
 #pragma unroll
-          for (int t = 0; t < KW; ++t) b[i * T + kh * KW + t] = xl[b_base[i] + st * 4 + kh * p.pitch + t];
-    };
-    auto mfmas = [&](const float (&a)[2], const float (&b)[CT * T]) {
+        for (int t = 0; t < KW; ++t) b[i * T + kh * KW + t] = xl[b_base[i] + st * 4 + kh * p.pitch + t];
+  };
+  auto mfmas = [&](const float (&a)[2], const float (&b)[CT * T]) {
 #pragma unroll
-      for (int i = 0; i < CT; ++i)
+    for (int i = 0; i < CT; ++i)
 #pragma unroll
-        for (int t = 0; t < T; ++t)
+      for (int t = 0; t < T; ++t)
 #pragma unroll
-          for (int ao = 0; ao < 2; ++ao)
-            acc[ao][i][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[ao], b[i * T + t], acc[ao][i][t], 0, 0, 0);
-    };
-    auto interleave = [&]() {       // (left to the compiler when a step has only a handful of MFMAs)
-      if constexpr (CT * T >= 6)
+        for (int ao = 0; ao < 2; ++ao)
+          acc[ao][i][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[ao], b[i * T + t], acc[ao][i][t], 0, 0, 0);
+  };
+  auto interleave = [&]() {       // (left to the compiler when a step has only a handful of MFMAs)
+    if constexpr (CT * T >= 6)
 #pragma unroll
-      for (int i = 0; i < CT * T; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);     // 2 MFMAs
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // 1 LDS read
-      }
-    };
-    // the wave takes steps first, first + stride, ... (waves that share an output tile split the steps between them)
-    float fa0[2], fb0[CT * T], fa1[2], fb1[CT * T];
-    int st = first;
-    if (st >= steps) return;
-    read(st, fa0, fb0);
-    for (; st + 2 * stride < steps; st += 2 * stride) {
-      // one fragment read of the next step after every second MFMA of the current one: the reads issue in the
-      // shadow of the matrix pipe and a whole step lies between a fragment's read and its use
-      read(st + stride, fa1, fb1); mfmas(fa0, fb0); interleave();
-      read(st + 2 * stride, fa0, fb0); mfmas(fa1, fb1); interleave();
+    for (int i = 0; i < CT * T; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);     // 2 MFMAs
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // 1 LDS read
     }
-    if (st + stride < steps) { read(st + stride, fa1, fb1); mfmas(fa0, fb0); mfmas(fa1, fb1); }
-    else mfmas(fa0, fb0);
+  };
+  // the wave takes steps first, first + stride, ... (waves that share an output tile split the steps between them)
+  float fa0[2], fb0[CT * T], fa1[2], fb1[CT * T];
+  int st = first;
+  if (st >= steps) return;
+  read(st, fa0, fb0);
+  for (; st + 2 * stride < steps; st += 2 * stride) {
+    // one fragment read of the next step after every second MFMA of the current one: the reads issue in the
+    // shadow of the matrix pipe and a whole step lies between a fragment's read and its use
+    read(st + stride, fa1, fb1); mfmas(fa0, fb0); interleave();
+    read(st + 2 * stride, fa0, fb0); mfmas(fa1, fb1); interleave();
   }
+  if (st + stride < steps) { read(st + stride, fa1, fb1); mfmas(fa0, fb0); mfmas(fa1, fb1); }
+  else mfmas(fa0, fb0);
+}
 
 // Leaves the workgroup's sums: in dW itself when there is one split, else in the workspace in accumulator layout.
 template <int KH, int KW, int CT>

@@ -112,6 +112,14 @@ def small_cases():
     c["conv_bf16_7x7_five_images"] = lambda: wl.make_conv(5, 24, 7, seed=13, Co=40, bf16=True, with_grad=True)
     c["conv_bf16_5x4_five_images"] = lambda: wl.make_conv(5, 16, 5, seed=14, Co=16, Wd=4, bf16=True, with_grad=True)
     c["conv_f32_5x4_five_images"] = lambda: wl.make_conv(5, 16, 5, seed=15, Co=16, Wd=4, with_grad=True)   # one staging item per row
+    # backward-weight kernels whose wave halves alternate between multiplying and staging: images cut into chunks with
+    # a short last one, channel counts that end inside a tile, whole-row items (14- and 7-pixel rows), items of 4 in
+    # two batches, items of 2
+    c["conv_f32_14wide_30rows"] = lambda: wl.make_conv(3, 40, 30, seed=20, Co=72, Wd=14, with_grad=True)
+    c["conv_f32_28wide_20rows"] = lambda: wl.make_conv(2, 24, 20, seed=21, Co=24, Wd=28, with_grad=True)
+    c["conv_f32_10wide"] = lambda: wl.make_conv(2, 16, 9, seed=22, Co=16, Wd=10, with_grad=True)
+    c["conv_bf16_14x14_three_images"] = lambda: wl.make_conv(3, 24, 14, seed=23, Co=40, bf16=True, with_grad=True)
+    c["conv_bf16_7x7_eleven_images"] = lambda: wl.make_conv(11, 40, 7, seed=24, Co=72, bf16=True, with_grad=True)
     c["gshift_bf16"] = lambda: wl.make_gshift(3, seeds=(1, 2, 3), with_grad=True)
     c["gshift_bf16_small_groups"] = lambda: wl.make_gshift(2, seeds=(4, 5, 6), with_grad=True, C=96, H=9, Wd=11, groups=3)
     c["gshift_f32"] = lambda: wl.make_gshift(2, seeds=(7, 8, 9), with_grad=True, C=64, H=6, Wd=10, groups=2, bf16=False)
@@ -172,6 +180,24 @@ ROWS_CASES = {
     "gshift_bf16_out": (lambda: wl.make_gshift(3, seeds=(7, 8, 9), with_grad=True, C=128, H=10, Wd=14, groups=2, out_bf16=True), 4),
     "one_by_one": (lambda: wl.make_conv(3, 48, 9, seed=44, Co=80, Wd=20, K=1, bf16=True, with_grad=True), 6),
 }
+
+
+DW_HALVES_CASES = ["conv_f32_14wide_30rows", "conv_f32_28wide_20rows", "conv_f32_10wide", "conv_f32_stage3_small_batch",
+                   "conv_bf16_14x14_three_images", "conv_bf16_7x7_eleven_images", "conv_f32_ragged"]
+
+
+@pytest.mark.parametrize("workgroups", [1, 3])
+@pytest.mark.parametrize("name", DW_HALVES_CASES)
+def test_backward_weight_with_several_chunks_per_workgroup(syno, oracle, name, workgroups):
+    """The backward-weight kernels whose wave halves take turns: with the pixel axis split over few workgroups each one
+    walks over several chunks (both halves multiply, stage and meet at the end), an odd count among them."""
+    w = small_cases()[name]()
+    plan = syno.Plan(w.desc, dw_workgroups=workgroups)
+    text = plan.describe(syno.BWD_WEIGHT)
+    chunks, splits = (int(text.split(k + "=")[1].split()[0]) for k in ("chunks", "splits"))
+    if workgroups == 1:
+        assert splits == 1 and chunks > 1, text
+    run_all(syno, oracle, w, 0, directions=(2,), dw_workgroups=workgroups)
 
 
 @pytest.mark.parametrize("name", list(ROWS_CASES))

@@ -29,6 +29,8 @@ struct MfmaParams {
   uint32_t m_wo, m_ho, m_vpr, m_pcg, m_per_o, m_khw, m_kw;
   int32_t wf;                         // bf16 single-chunk variant: taps per channel when the weights are read unpacked, else 0
   int32_t wt;                         // fp32 backward-data: the weights are first transposed into the workspace
+  int32_t wadj;                       // fp32 backward-data, 3x3 window, weights in the forward layout [o][c][9 taps]: the
+                                      // adjoint's block is transposed and its taps reversed on the way into LDS (no copy)
   int32_t ts_g, ts_o, ts_c, ts_kh, ts_kw;   // ... from a tensor with these strides
   int32_t U;                          // window taps along w per row-step (selects the instantiation)
 };
@@ -80,6 +82,15 @@ __device__ __forceinline__ int slot_source(const MfmaParams& p, int R0, int rows
 __device__ __forceinline__ int slot_of_row(const MfmaParams& p, int R0, int i) {
   if (p.h_wrap) return i;
   return i + (p.KH - 1) * (fdiv(R0 + i, p.m_ho) - fdiv(R0, p.m_ho));
+}
+
+// f(integral_constant<int, I>) for I = 0 .. N-1
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
 }
 
 // BF = false: fp32 inputs, CI = 4, v_mfma_f32_16x16x4_f32  (A: lane -> row l%16, k = l/16).
@@ -161,6 +172,7 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
   // bf16: 16-byte pieces of this block's packed image, copied as they are.
   // bf16, WF > 0: weights as they lie in memory.  An item is 8 channels x WF taps of one output channel of the
   // chunk (WF adjacent 16-byte loads); on the way into LDS it is re-ordered into one 16-byte piece per tap.
+  constexpr int kAdjPairs = (WI * 4) / 9;      // (fp32, adjoint from the forward layout) pairs of 9 taps a thread's weight registers hold
   constexpr int OCT = BF ? KCB / 8 : 1;                                     // channel octets per chunk
   constexpr int WP = (BF && WF > 0) ? (BN * OCT + NT - 1) / NT : 1;         // such items per thread
   constexpr int WFA = WF > 0 ? WF : 1;
@@ -192,6 +204,18 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
   } else if constexpr (WNAT) {
     Wg32 = reinterpret_cast<const float*>(Wv) + (int64_t)g * p.ws_g + (int64_t)nb * BN * p.ws_o;
     const int per_o4 = (p.KC * KHW) >> 2, total = BN * per_o4;   // float4 pieces per output channel
+    if (p.wadj) {
+      // adjoint straight from W[o][c][9 taps] (this kernel's channel = o, its output channel = c): an item is the 9
+      // taps of one (output channel, channel) pair, 36 adjacent bytes; adjacent lanes take adjacent output channels
+#pragma unroll
+      for (int k = 0; k < WI; ++k) {
+        const int idx = tid + k * NT;
+        const int r = idx % BN, cl = idx / BN;
+        const bool in = k < kAdjPairs && idx < BN * p.KC;
+        w_goff[k] = (in && nb * BN + r < p.Og) ? cl * p.ws_c + r * 9 : -1;   // element offset at chunk 0
+        w_meta[k] = in ? r * p.w_row + cl * 9 : -1;                          // LDS float index of the pair's first tap
+      }
+    } else {
 #pragma unroll
     for (int k = 0; k < WI; ++k) {
       const int idx = tid + k * NT;
@@ -199,6 +223,7 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
       const bool ok = idx < total && nb * BN + o < p.Og;
       w_goff[k] = ok ? o * p.ws_o + e4 * 4 : -1;                 // element offset
       w_meta[k] = idx < total ? (o * p.w_row + e4 * 4) >> 2 : -1; // LDS float4 index
+    }
     }
   } else {
     Wg32 = reinterpret_cast<const float*>(Wv) + p.w_base + (int64_t)g * p.ws_g + (int64_t)nb * BN * p.ws_o;
@@ -253,6 +278,15 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
   XV xr[XI][CI];
   WReg wr[WI];
   uint32_t win[WP][4 * WFA];     // (bf16, WF > 0 only)
+  // dword I of the weight registers taken as one flat array (16-byte pieces only)
+  auto wcomp = [&](auto i_c) -> uint32_t& {
+    constexpr int I = decltype(i_c)::value;
+    if constexpr (!W16) return win[0][0];
+    else if constexpr (I % 4 == 0) return wr[I / 4].x;
+    else if constexpr (I % 4 == 1) return wr[I / 4].y;
+    else if constexpr (I % 4 == 2) return wr[I / 4].z;
+    else return wr[I / 4].w;
+  };
   // Loads use a wave-uniform base plus 32-bit byte offsets.  Items without a source read offset 0 (any
   // valid address) and are simply not written to LDS, so the common path has no per-load predicate.
   const bool chan_tail = (p.Cg % p.KC) != 0;
@@ -318,11 +352,27 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
         if (want(XI * CI + k)) wr[k] = w_goff[k] >= 0 ? src[w_goff[k]] : make_uint4(0, 0, 0, 0);
     } else if constexpr (WNAT) {
       // (the planner only picks this path when Cg is a multiple of KC, so no channel tail here)
+      if (p.wadj) {
+        if constexpr (kAdjPairs > 0)
+          static_for<0, kAdjPairs>([&](auto k_c) {
+            constexpr int k = decltype(k_c)::value;
+            if (!want(XI * CI + k)) return;
+            // (pairs without a source read the block's first taps and are written as zeros)
+            const float* src = Wg32 + max(w_goff[k], 0) + (int64_t)c0 * p.ws_c;
+            const f32x4_unaligned a = *reinterpret_cast<const f32x4_unaligned*>(src);
+            const f32x4_unaligned b = *reinterpret_cast<const f32x4_unaligned*>(src + 4);
+            const float last = src[8];
+            static_for<0, 4>([&](auto i_c) { wcomp(std::integral_constant<int, 9 * k + decltype(i_c)::value>{}) = __float_as_uint(a[decltype(i_c)::value]); });
+            static_for<0, 4>([&](auto i_c) { wcomp(std::integral_constant<int, 9 * k + 4 + decltype(i_c)::value>{}) = __float_as_uint(b[decltype(i_c)::value]); });
+            wcomp(std::integral_constant<int, 9 * k + 8>{}) = __float_as_uint(last);
+          });
+      } else {
 #pragma unroll
       for (int k = 0; k < WI; ++k)
         if (want(XI * CI + k))
           wr[k] = w_goff[k] >= 0 ? *reinterpret_cast<const uint4*>(Wg32 + w_goff[k] + (int64_t)c0 * p.ws_c)
                                  : make_uint4(0, 0, 0, 0);
+      }
     } else {
 #pragma unroll
       for (int k = 0; k < WI; ++k) {
@@ -389,10 +439,24 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
       for (int k = 0; k < WI; ++k)
         if (w_goff[k] >= 0) wl[w_goff[k]] = wr[k];
     } else if constexpr (WNAT) {
+      if (p.wadj) {
+        if constexpr (kAdjPairs > 0)
+          static_for<0, kAdjPairs>([&](auto k_c) {
+            constexpr int k = decltype(k_c)::value;
+            if (w_meta[k] < 0) return;
+            float* dst = reinterpret_cast<float*>(smem + p.lds_w_off) + w_meta[k];
+            const bool live = w_goff[k] >= 0;
+            static_for<0, 9>([&](auto i_c) {       // taps reversed
+              constexpr int i = decltype(i_c)::value;
+              dst[8 - i] = live ? __uint_as_float(wcomp(std::integral_constant<int, 9 * k + i>{})) : 0.f;
+            });
+          });
+      } else {
       uint4* wl = reinterpret_cast<uint4*>(smem + p.lds_w_off);
 #pragma unroll
       for (int k = 0; k < WI; ++k)
         if (w_meta[k] >= 0) wl[w_meta[k]] = wr[k];
+      }
     } else {
       float* wl = reinterpret_cast<float*>(smem + p.lds_w_off);
 #pragma unroll

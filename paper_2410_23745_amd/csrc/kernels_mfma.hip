@@ -214,6 +214,13 @@ bool fill_params(const syno_plan* plan, int which, int vi, int TR, MfmaParams& p
       p.KC -= 8;
     if (p.Cg % p.KC != 0 || ((p.KC * KHW) & 3) || p.BN * p.KC * KHW > 4 * v.WI * v.NT()) return false;
     p.w_row = pick_w_row(p.KC * KHW, KHW, 4);
+    // backward-data of a 3x3 window whose weights lie in the forward layout: no transposed copy, the kernel takes the
+    // 9 taps of every (output channel, channel) pair as they lie and turns them round on the way into LDS
+    if (which == SYNO_BWD_DATA && p.wt && KHW == 9 && c.ws_kw == 1 && c.ws_kh == c.KW && c.ws_c == KHW &&
+        c.ws_o == c.Cg * KHW && ((p.BN * p.KC + v.NT() - 1) / v.NT()) * 9 <= 4 * v.WI) {
+      p.wt = 0; p.wadj = 1;
+      p.ws_g = c.ws_g; p.ws_o = KHW; p.ws_c = c.ws_o; p.ws_kh = c.KW; p.ws_kw = 1; p.w_base = 0;
+    }
   } else {
     p.KC = v.KC;
     while (p.KC > 4 && (p.BN * p.KC * KHW > v.WI * v.NT())) p.KC -= 4;
@@ -345,7 +352,7 @@ std::string mfma_describe(const syno_plan* plan, int which) {
   char b[256];
   memcpy(&p, plan->launch[which].params, sizeof p);
   snprintf(b, sizeof b, "variant=%d rows/block=%d BN=%d KC=%d taps/row-step=%d weights=%s waves=%dx%dx%d grid=%d lds=%dB slots=%d", vi, TR,
-           v.BN(), p.KC, p.U, (plan->in_dtype != SYNO_BF16 || p.wf) ? "direct" : "packed", v.WM, v.WN, v.WK, p.n_mblocks * p.n_nblocks * p.G, p.lds_bytes, p.n_slots);
+           v.BN(), p.KC, p.U, plan->in_dtype != SYNO_BF16 ? (p.wt ? "transposed-copy" : p.wadj ? "turned-while-staged" : "direct") : (p.wf ? "direct" : "packed"), v.WM, v.WN, v.WK, p.n_mblocks * p.n_nblocks * p.G, p.lds_bytes, p.n_slots);
   return b;
 }
 

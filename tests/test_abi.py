@@ -164,10 +164,14 @@ def test_kernel_choice(syno):
     assert p.workspace_bytes(syno.FWD) == 0 and p.workspace_bytes(syno.BWD_DATA) == 0
     assert p.workspace_bytes(syno.BWD_WEIGHT) > 0
     # more channels than one chunk holds: bf16 backward-data packs its weights into the workspace (forward reads
-    # them as they lie), fp32 backward-data transposes them into it
+    # them as they lie); fp32 backward-data of a 3x3 window takes them from the forward layout as they lie, and
+    # transposes them into the workspace when they lie in another order
     p = syno.Plan(wl.conv2d(32, 128, 128, 28, 28, 3, 3, BF16, F32))
     assert p.workspace_bytes(syno.FWD) == 0 and p.workspace_bytes(syno.BWD_DATA) > 0
-    assert syno.Plan(wl.conv2d(32, 128, 128, 28, 28)).workspace_bytes(syno.BWD_DATA) == 128 * 128 * 9 * 4
+    q = syno.Plan(wl.conv2d(32, 128, 128, 28, 28))
+    assert q.workspace_bytes(syno.BWD_DATA) == 0 and "turned-while-staged" in q.describe(syno.BWD_DATA)
+    q = syno.Plan(wl.conv2d(32, 128, 128, 28, 28, 3, 3, F32, F32, (1, 0, 2, 3)))
+    assert q.workspace_bytes(syno.BWD_DATA) == 128 * 128 * 9 * 4 and "transposed-copy" in q.describe(syno.BWD_DATA)
     assert "grid=" in p.describe(syno.FWD)
     # per-plan options: the generic kernels on request; a named tile variant of the contraction kernel
     generic = syno.Plan(wl.strided_depthwise(2, 4, 7, 7), kernel_policy=1)

@@ -206,11 +206,14 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
     const int per_o4 = (p.KC * KHW) >> 2, total = BN * per_o4;   // float4 pieces per output channel
     if (p.wadj) {
       // adjoint straight from W[o][c][9 taps] (this kernel's channel = o, its output channel = c): an item is the 9
-      // taps of one (output channel, channel) pair, 36 adjacent bytes; adjacent lanes take adjacent output channels
+      // taps of one (output channel, channel) pair, 36 adjacent bytes.  A wave takes 16 adjacent output channels x 4
+      // adjacent channels at a time: 576 contiguous bytes per channel on the memory side, and on the LDS side the
+      // pattern of a B-fragment read (16 rows x 4 steps of 9 dwords), which the row pitch keeps free of bank conflicts
 #pragma unroll
       for (int k = 0; k < WI; ++k) {
         const int idx = tid + k * NT;
-        const int r = idx % BN, cl = idx / BN;
+        const int rest = idx >> 6;
+        const int r = (idx & 15) + 16 * (rest % (BN / 16)), cl = ((idx >> 4) & 3) + 4 * (rest / (BN / 16));
         const bool in = k < kAdjPairs && idx < BN * p.KC;
         w_goff[k] = (in && nb * BN + r < p.Og) ? cl * p.ws_c + r * 9 : -1;   // element offset at chunk 0
         w_meta[k] = in ? r * p.w_row + cl * 9 : -1;                          // LDS float index of the pair's first tap

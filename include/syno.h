@@ -85,6 +85,10 @@ typedef struct {
  *                   row-streaming member of the family (bf16, at most 64 channels per group);
  *                   mfma_rows = output rows per workgroup tile.  Ignored unless the pair fits the operator.
  *   mfma_taps       1: one window tap per inner step even where three would be taken
+ *   mfma_splits     number of workgroups that share one output tile of the contraction kernel, each summing a
+ *                   range of the reduced channels; their partial results go to the workspace and a second kernel
+ *                   adds them in a fixed order (fp32 results only; by itself the planner splits only reductions
+ *                   over thousands of channels whose tiles would not fill the GPU)
  *   dw_workgroups   target number of workgroups of the backward-weight contraction (split of the pixel axis)
  *   view_workgroups cap on the grid of the view kernel
  *   clock_probe     measurement aid (device memory, 4 x int64 per workgroup of the launch, owned by the caller, or
@@ -97,6 +101,7 @@ typedef struct {
   int32_t mfma_variant, mfma_rows, mfma_taps;
   int32_t dw_workgroups;
   int32_t view_workgroups;
+  int32_t mfma_splits;
   void* clock_probe;
 } syno_plan_options;
 

@@ -33,7 +33,7 @@ class _Prim(ctypes.Structure):
 class _Options(ctypes.Structure):
     _fields_ = [("kernel_policy", ctypes.c_int32), ("mfma_variant", ctypes.c_int32), ("mfma_rows", ctypes.c_int32),
                 ("mfma_taps", ctypes.c_int32), ("dw_workgroups", ctypes.c_int32), ("view_workgroups", ctypes.c_int32),
-                ("clock_probe", ctypes.c_void_p)]
+                ("mfma_splits", ctypes.c_int32), ("clock_probe", ctypes.c_void_p)]
 
 
 class _Desc(ctypes.Structure):

@@ -107,6 +107,16 @@ syno_status run(const syno_plan* plan, int which, const void* A, const void* B, 
       // forward: the weight is the image and the input the filter; the gradients keep their operand order
       // (upstream gradient first) and only name the other contraction of the inner plan
       if (which == SYNO_FWD) return run(plan->inner, SYNO_FWD, B, A, out, ws, stream);
+      if (L.variant == syno::kViaTransposedCopy) {
+        // dX = G * W^T as a product of its own: W^T goes into the head of the workspace and is the "image" of that
+        // product's 1x1 convolution, G its filter
+        const int64_t K = plan->w_shape[0], N = plan->w_shape[1];
+        const int esz = plan->in_dtype == SYNO_BF16 ? 2 : 4;
+        const syno_status st = syno::launch_transpose_2d(B, ws, K, N, esz, stream);
+        if (st != SYNO_OK) return st;
+        const size_t head = ((size_t)K * N * esz + 255) & ~(size_t)255;
+        return run(plan->inner_dx, SYNO_FWD, ws, A, out, static_cast<char*>(ws) + head, stream);
+      }
       return run(plan->inner, L.variant, A, B, out, ws, stream);
     default: return SYNO_ERR_UNSUPPORTED;
   }
@@ -206,7 +216,10 @@ syno_status syno_plan_describe(const syno_plan* plan, int which, char* buf, size
       break;
     case syno::KERNEL_MFMA_TRANSPOSED: {
       char inner[400];
-      if (syno_plan_describe(plan->inner, plan->launch[which].variant, inner, sizeof(inner)) == SYNO_OK)
+      if (plan->launch[which].variant == syno::kViaTransposedCopy) {
+        if (syno_plan_describe(plan->inner_dx, SYNO_FWD, inner, sizeof(inner)) == SYNO_OK)
+          d += std::string(" as the product G * W^T (transposed copy of W), a 1x1 convolution: ") + inner;
+      } else if (syno_plan_describe(plan->inner, plan->launch[which].variant, inner, sizeof(inner)) == SYNO_OK)
         d += std::string(" as 1x1 convolution: ") + inner;
       break;
     }

@@ -33,6 +33,8 @@ struct MfmaParams {
                                       // adjoint's block is transposed and its taps reversed on the way into LDS (no copy)
   int32_t ts_g, ts_o, ts_c, ts_kh, ts_kw;   // ... from a tensor with these strides
   int32_t U;                          // window taps along w per row-step (selects the instantiation)
+  int32_t ksplit, chunks_per_split;   // workgroups per output tile, each summing a range of chunks (1: no split)
+  int32_t split_stride;               // ksplit > 1: elements between the partial results (fp32, laid out like the result)
 };
 
 namespace {
@@ -138,7 +140,8 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
   int bid = blockIdx.x;
   const int nb = bid % p.n_nblocks; bid /= p.n_nblocks;
   const int mb = bid % p.n_mblocks;
-  const int g = bid / p.n_mblocks;
+  int g = bid / p.n_mblocks, ksp = 0;
+  if (p.ksplit > 1) { ksp = g / p.G; g -= ksp * p.G; }
   const int R0 = mb * p.TR;
   const int rows = min(p.TR, p.rows_total - R0);
   const int KHW = p.KH * p.KW;
@@ -469,8 +472,10 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
   };
 
   // ONE: the whole reduction fits one chunk, so the staging registers are dead once it is in LDS
-  const int n_chunks = ONE ? 1 : p.n_chunks;
-  fetch(0, std::integral_constant<int, -1>{});
+  // (workgroups that split the reduction take chunks_per_split chunks each; the host rules out empty ranges)
+  const int ch_begin = ONE ? 0 : ksp * p.chunks_per_split;
+  const int n_chunks = ONE ? 1 : min(p.n_chunks, ch_begin + p.chunks_per_split);
+  fetch(ch_begin, std::integral_constant<int, -1>{});
   // while the first requests travel: zero the X region once (slot edges and rows outside the image are the
   // window's zero padding and are never written afterwards); the loop's first barrier orders it before staging
   {
@@ -506,7 +511,7 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
         }
     }
   }
-  for (int ch = 0; ch < n_chunks; ++ch) {
+  for (int ch = ch_begin; ch < n_chunks; ++ch) {
     __syncthreads();   // everyone has finished reading the previous chunk
     stage(ch);
     __syncthreads();
@@ -686,7 +691,7 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
             }
         }
       } else {
-        float* op = reinterpret_cast<float*>(out);
+        float* op = reinterpret_cast<float*>(out) + (int64_t)ksp * p.split_stride;
         if (together && (off & 3) == 0) {
           *reinterpret_cast<float4*>(op + off) = make_float4(acc[t][u][0], acc[t][u][1], acc[t][u][2], acc[t][u][3]);
         } else {
@@ -762,7 +767,7 @@ constexpr Variant kBf16Variants[kNumBf16Variants] = {
 template <bool BF, int VI, int U, int WF, bool OUTBF>
 void launch_variant(const MfmaParams& p, const void* X, const void* W, void* out, hipStream_t s) {
   constexpr Variant v = BF ? kBf16Variants[VI % kNumBf16Variants] : kF32Variants[VI % kNumF32Variants];
-  const int grid = p.n_mblocks * p.n_nblocks * p.G;
+  const int grid = p.n_mblocks * p.n_nblocks * p.G * p.ksplit;
   auto kernel = conv_mfma<BF, v.wnat, v.WM, v.WN, v.WK, v.TM, v.TN, v.XI, v.WI, v.one, (BF ? v.KC : 0), U, WF, OUTBF>;
   static const hipError_t lds_opt_in =      // once per instantiation: allow more than the default 64 KB
       hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);

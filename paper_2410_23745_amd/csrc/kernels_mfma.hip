@@ -119,6 +119,47 @@ __global__ __launch_bounds__(256) void pack_weight_bf16_fwd(const MfmaParams p, 
   }
 }
 
+// dst[c][r] = src[r][c], 32 x 32 tiles through LDS so that both sides move whole rows of a tile
+template <class T>
+__global__ __launch_bounds__(256) void transpose_2d(const T* __restrict__ src, T* __restrict__ dst, int rows, int cols) {
+  __shared__ T tile[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = r0 + ty + 8 * i, c = c0 + tx;
+    if (r < rows && c < cols) tile[ty + 8 * i][tx] = src[(int64_t)r * cols + c];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = c0 + ty + 8 * i, r = r0 + tx;
+    if (r < rows && c < cols) dst[(int64_t)c * rows + r] = tile[tx][ty + 8 * i];
+  }
+}
+
+// out[i] = parts[0][i] + parts[1][i] + ... (k partial results `stride` elements apart, added in this order)
+__global__ __launch_bounds__(256) void sum_split_results(const float* __restrict__ parts, float* __restrict__ out,
+                                                         int64_t n, int k, int64_t stride) {
+  const int64_t step = (int64_t)gridDim.x * 256;
+  if ((n & 3) == 0 && (reinterpret_cast<uintptr_t>(out) & 15) == 0) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < (n >> 2); i += step) {
+      float4 a = reinterpret_cast<const float4*>(parts)[i];
+      for (int j = 1; j < k; ++j) {
+        const float4 b = reinterpret_cast<const float4*>(parts + j * stride)[i];
+        a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+      }
+      reinterpret_cast<float4*>(out)[i] = a;
+    }
+  } else {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += step) {
+      float a = parts[i];
+      for (int j = 1; j < k; ++j) a += parts[j * stride + i];
+      out[i] = a;
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Host side: tile choice and launch
 // ---------------------------------------------------------------------------------------------
@@ -151,7 +192,7 @@ int pick_w_row(int need, int kstep, int multiple_of) {
 
 // Parameter record of contraction `which` (forward, or backward-data as its adjoint) for tile variant vi
 // and TR output rows per block.  False when the combination does not fit the kernel's static limits.
-bool fill_params(const syno_plan* plan, int which, int vi, int TR, MfmaParams& p) {
+bool fill_params(const syno_plan* plan, int which, int vi, int TR, MfmaParams& p, int ksplit = 1) {
   const ConvLike& c = plan->conv;
   const bool bf = plan->in_dtype == SYNO_BF16;
   if (vi < 0 || vi >= num_variants(bf) || TR < 1) return false;
@@ -255,6 +296,16 @@ bool fill_params(const syno_plan* plan, int which, int vi, int TR, MfmaParams& p
     return false;
   p.m_wo = magic(c.Wo); p.m_ho = magic(c.Ho); p.m_vpr = magic(p.vpr); p.m_pcg = magic(per_cg);
   p.m_per_o = magic(per_o); p.m_khw = magic(KHW); p.m_kw = magic(c.KW);
+  // workgroups that share an output tile and split the chunks: fp32 partial results, every range non-empty
+  p.ksplit = 1; p.chunks_per_split = p.n_chunks; p.split_stride = 0;
+  if (ksplit > 1) {
+    const int64_t result = which == SYNO_FWD ? plan->out_elems : plan->x_elems;
+    if (v.one || plan->out_dtype != SYNO_F32 || ksplit > p.n_chunks || result >= (1ll << 31) - 4) return false;
+    p.chunks_per_split = (p.n_chunks + ksplit - 1) / ksplit;
+    if ((int64_t)(ksplit - 1) * p.chunks_per_split >= p.n_chunks) return false;
+    p.ksplit = ksplit;
+    p.split_stride = (int32_t)((result + 3) & ~3ll);
+  }
   return p.lds_bytes <= kMaxLdsBytes;
 }
 
@@ -263,7 +314,7 @@ bool fill_params(const syno_plan* plan, int which, int vi, int TR, MfmaParams& p
 // K=32) cycles, and one k-step of a wave cannot finish faster than its LDS reads allow.  Staging, barriers
 // and the prologue overlap with another resident workgroup's MFMAs only when more than one fits on a CU.
 double tile_cost(const MfmaParams& p, const Variant& v, const ConvLike& c, bool bf) {
-  const int64_t wgs = (int64_t)p.n_mblocks * p.n_nblocks * c.G;
+  const int64_t wgs = (int64_t)p.n_mblocks * p.n_nblocks * c.G * p.ksplit;
   const int MT = (std::min(p.TR, p.rows_total) * c.Wo + 15) / 16;
   const int base = MT / v.WM, extra = MT % v.WM;
   const double mfma_cycles = bf ? 16.0 : 32.0, read_cycles = bf ? 16.0 : 8.0;
@@ -282,16 +333,24 @@ double tile_cost(const MfmaParams& p, const Variant& v, const ConvLike& c, bool 
   }
   double step = 0;
   for (int s = 0; s < 4; ++s) step = std::max(step, std::max(simd_mfma[s], 0.5 * simd_lat[s] + 0.5 * simd_mfma[s]));
-  const double steps = (double)p.n_chunks * (p.cgrps / (bf ? 4 : 1)) * c.KH * c.KW;
-  const double overhead = p.n_chunks * 5000.0 + 6000.0 + (v.WK - 1) * 1500.0;
+  const double steps = (double)p.chunks_per_split * (p.cgrps / (bf ? 4 : 1)) * c.KH * c.KW;
+  const double overhead = p.chunks_per_split * 5000.0 + 6000.0 + (v.WK - 1) * 1500.0;
+  // the second kernel of a split: its launch, and the partial results written and read back at about 3 TB/s
+  const double split_cost = p.ksplit > 1 ? 10000.0 + (2.0 * p.ksplit + 1.0) * p.split_stride * 4.0 / 3.0e12 * 2.4e9 : 0.0;
   // 8 waves of up to 256 VGPRs fill a CU's register file; 4-wave workgroups fit twice
   const int resident = (v.NT() <= 256 && p.lds_bytes <= kMaxLdsBytes / 2) ? 2 : 1;
   const double per_cu_wgs = std::ceil((double)wgs / kNumCU);
-  return per_cu_wgs * steps * step + std::ceil(per_cu_wgs / resident) * overhead;
+  return per_cu_wgs * steps * step + std::ceil(per_cu_wgs / resident) * overhead + split_cost;
 }
 
 size_t packed_weight_bytes(const MfmaParams& p) {
   return (size_t)p.G * p.n_nblocks * p.n_chunks * p.w_block * 2;
+}
+
+// head of the workspace: the re-ordered weights (rounded up so that the partial results behind it stay aligned)
+size_t weight_workspace_bytes(const MfmaParams& p, bool bf) {
+  const size_t n = bf ? (p.wf == 0 ? packed_weight_bytes(p) : 0) : (p.wt ? (size_t)p.G * p.Og * p.Cg * p.KH * p.KW * 4 : 0);
+  return (n + 255) & ~(size_t)255;
 }
 
 }  // namespace
@@ -321,18 +380,37 @@ void mfma_configure(syno_plan* plan, int which) {
   double best = 1e300;
   int best_v = -1, best_tr = 0;
   MfmaParams mp;
-  // the descriptor's options may name the tile variant and the rows per block (verification and tuning aid)
-  if (plan->opt.mfma_variant > 0 && fill_params(plan, which, plan->opt.mfma_variant - 1, plan->opt.mfma_rows, mp)) {
-    best_v = plan->opt.mfma_variant - 1; best_tr = plan->opt.mfma_rows;
+  // the descriptor's options may name the tile variant and the rows per block (verification and tuning aid).
+  // A reduction over thousands of channels whose tiles would leave compute units idle may be split over workgroups
+  // (each still runs at least 32 chunks); the option names a split outright
+  const int forced = plan->opt.mfma_splits > 0 ? plan->opt.mfma_splits : 0;
+  const int splits[] = {1, 2, 3, 4, 6, 8};
+  int best_ks = 1;
+  if (plan->opt.mfma_variant > 0 && fill_params(plan, which, plan->opt.mfma_variant - 1, plan->opt.mfma_rows, mp, forced ? forced : 1)) {
+    best_v = plan->opt.mfma_variant - 1; best_tr = plan->opt.mfma_rows; best_ks = forced ? forced : 1;
   }
   if (best_v < 0)
     for (int vi = 0; vi < num_variants(bf); ++vi)
       for (int TR = 1; TR <= c.N * c.Ho && TR * c.Wo <= 16 * 32; ++TR) {
+        if (!fill_params(plan, which, vi, TR, mp)) continue;      // (a split only adds conditions)
+        const int n_chunks = mp.n_chunks;
+        for (int ks : splits) {
+          const int k = forced ? forced : ks;
+          if (!forced && k > 1 && n_chunks < 32 * k) break;
+          if (k > 1 && !fill_params(plan, which, vi, TR, mp, k)) { if (forced) break; else continue; }
+          const double cost = tile_cost(mp, variant_of(bf, vi), c, bf);
+          if (cost < best) { best = cost; best_v = vi; best_tr = TR; best_ks = k; }
+          if (forced) break;
+        }
+      }
+  if (best_v < 0 && forced)      // (the named split does not fit this operator: the planner's own choice)
+    for (int vi = 0; vi < num_variants(bf); ++vi)
+      for (int TR = 1; TR <= c.N * c.Ho && TR * c.Wo <= 16 * 32; ++TR) {
         if (!fill_params(plan, which, vi, TR, mp)) continue;
         const double cost = tile_cost(mp, variant_of(bf, vi), c, bf);
-        if (cost < best) { best = cost; best_v = vi; best_tr = TR; }
+        if (cost < best) { best = cost; best_v = vi; best_tr = TR; best_ks = 1; }
       }
-  fill_params(plan, which, best_v, best_tr, mp);
+  fill_params(plan, which, best_v, best_tr, mp, best_ks);
   if (plan->opt.mfma_taps == 1) mp.U = 1;     // (option: the one-tap-per-row-step instantiation)
   mp.probe_lo = (uint32_t)reinterpret_cast<uintptr_t>(plan->opt.clock_probe);
   mp.probe_hi = (uint32_t)(reinterpret_cast<uintptr_t>(plan->opt.clock_probe) >> 32);
@@ -340,7 +418,7 @@ void mfma_configure(syno_plan* plan, int which) {
   memcpy(plan->launch[which].params, &mp, sizeof mp);
   plan->launch[which].params_ready = true;
   plan->launch[which].variant = best_v * 4096 + best_tr;
-  plan->launch[which].workspace = bf ? (mp.wf == 0 ? packed_weight_bytes(mp) : 0) : (mp.wt ? (size_t)mp.G * mp.Og * mp.Cg * mp.KH * mp.KW * 4 : 0);
+  plan->launch[which].workspace = weight_workspace_bytes(mp, bf) + (mp.ksplit > 1 ? (size_t)mp.ksplit * mp.split_stride * 4 : 0);
 }
 
 std::string mfma_describe(const syno_plan* plan, int which) {
@@ -352,7 +430,8 @@ std::string mfma_describe(const syno_plan* plan, int which) {
   char b[256];
   memcpy(&p, plan->launch[which].params, sizeof p);
   snprintf(b, sizeof b, "variant=%d rows/block=%d BN=%d KC=%d taps/row-step=%d weights=%s waves=%dx%dx%d grid=%d lds=%dB slots=%d", vi, TR,
-           v.BN(), p.KC, p.U, plan->in_dtype != SYNO_BF16 ? (p.wt ? "transposed-copy" : p.wadj ? "turned-while-staged" : "direct") : (p.wf ? "direct" : "packed"), v.WM, v.WN, v.WK, p.n_mblocks * p.n_nblocks * p.G, p.lds_bytes, p.n_slots);
+           v.BN(), p.KC, p.U, plan->in_dtype != SYNO_BF16 ? (p.wt ? "transposed-copy" : p.wadj ? "turned-while-staged" : "direct") : (p.wf ? "direct" : "packed"), v.WM, v.WN, v.WK, p.n_mblocks * p.n_nblocks * p.G * p.ksplit, p.lds_bytes, p.n_slots);
+  if (p.ksplit > 1) return std::string(b) + " reduction-splits=" + std::to_string(p.ksplit);
   return b;
 }
 
@@ -364,6 +443,12 @@ syno_status launch_mfma(const syno_plan* plan, int which, const void* A, const v
   MfmaParams p;
   memcpy(&p, plan->launch[which].params, sizeof p);
   const bool obf = plan->out_dtype == SYNO_BF16;
+  // a split reduction leaves its partial results behind the weights in the workspace
+  void* const result = out;
+  if (p.ksplit > 1) {
+    if (!ws) return SYNO_ERR_WORKSPACE;
+    out = static_cast<char*>(ws) + weight_workspace_bytes(p, plan->in_dtype == SYNO_BF16);
+  }
   if (plan->in_dtype == SYNO_BF16) {
     const void* weights = B;
     if (p.wf == 0) {
@@ -393,13 +478,34 @@ syno_status launch_mfma(const syno_plan* plan, int which, const void* A, const v
     if (p.wt) {
       if (!ws) return SYNO_ERR_WORKSPACE;
       const int64_t n = (int64_t)p.G * p.Og * p.Cg * p.KH * p.KW;
-      hipLaunchKernelGGL(transpose_weight_f32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p,
-                         static_cast<const float*>(B), static_cast<float*>(ws), n);
+      // a 1x1 window over a contiguous [o][c] matrix is a plain transposition, which goes through LDS tiles
+      const bool plain = p.G == 1 && p.KH * p.KW == 1 && p.ts_c == 1 && p.ts_o == p.Og;
+      if (!plain || launch_transpose_2d(B, ws, p.Cg, p.Og, 4, stream) != SYNO_OK)
+        hipLaunchKernelGGL(transpose_weight_f32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p,
+                           static_cast<const float*>(B), static_cast<float*>(ws), n);
       weights = ws;
     }
     if (vi < 4) launch_mfma_f32_lo(vi, p, A, weights, out, stream);
     else launch_mfma_f32_hi(vi, p, A, weights, out, stream);
   }
+  if (p.ksplit > 1) {
+    const int64_t n = which == SYNO_FWD ? plan->out_elems : plan->x_elems;
+    const int64_t blocks = std::min<int64_t>(((n + 3) / 4 + 255) / 256, 8 * kNumCU);
+    hipLaunchKernelGGL(sum_split_results, dim3((unsigned)blocks), dim3(256), 0, stream, static_cast<const float*>(out),
+                       static_cast<float*>(result), n, p.ksplit, (int64_t)p.split_stride);
+  }
+  return hipGetLastError() == hipSuccess ? SYNO_OK : SYNO_ERR_HIP;
+}
+
+syno_status launch_transpose_2d(const void* src, void* dst, int64_t rows, int64_t cols, int elem_bytes, hipStream_t stream) {
+  if (rows < 1 || cols < 1 || rows >= (1ll << 31) || cols >= (1ll << 31) || (rows + 31) / 32 > 65535) return SYNO_ERR_SHAPE;
+  const dim3 grid((unsigned)((cols + 31) / 32), (unsigned)((rows + 31) / 32));
+  if (elem_bytes == 4)
+    hipLaunchKernelGGL(transpose_2d<uint32_t>, grid, dim3(256), 0, stream, static_cast<const uint32_t*>(src), static_cast<uint32_t*>(dst), (int)rows, (int)cols);
+  else if (elem_bytes == 2)
+    hipLaunchKernelGGL(transpose_2d<uint16_t>, grid, dim3(256), 0, stream, static_cast<const uint16_t*>(src), static_cast<uint16_t*>(dst), (int)rows, (int)cols);
+  else
+    return SYNO_ERR_UNSUPPORTED;
   return hipGetLastError() == hipSuccess ? SYNO_OK : SYNO_ERR_HIP;
 }
 

@@ -142,7 +142,10 @@ struct syno_plan {
   syno::Launch launch[3];
   // matrix products: the plan of the equivalent 1x1 convolution (owned); Launch::variant holds its contraction
   syno_plan* inner = nullptr;
-  ~syno_plan() { delete inner; }
+  // matrix products: dX = G * W^T is a matrix product too; the plan of ITS 1x1 convolution (owned), whose forward
+  // contraction runs on a transposed copy of W in the workspace (Launch::variant = kViaTransposedCopy)
+  syno_plan* inner_dx = nullptr;
+  ~syno_plan() { delete inner; delete inner_dx; }
   bool pure_view = false;
   syno::ViewStream view{};
 };
@@ -204,6 +207,9 @@ bool rows_supports(const syno_plan* p, int which);
 bool rows_configure(syno_plan* p, int which);
 std::string rows_describe(const syno_plan* p, int which);
 syno_status launch_rows(const syno_plan* p, int which, const void* A, const void* B, void* out, void* ws, hipStream_t stream);
+// kernels_mfma.hip: dst[c][r] = src[r][c] for a row-major rows x cols matrix of 2- or 4-byte elements
+constexpr int kViaTransposedCopy = 100;
+syno_status launch_transpose_2d(const void* src, void* dst, int64_t rows, int64_t cols, int elem_bytes, hipStream_t stream);
 // kernels_mfma_dw.hip: the backward-weight member of the MFMA family
 bool mfma_dw_supports(const syno_plan* p);
 void mfma_dw_configure(syno_plan* p);

@@ -1253,11 +1253,13 @@ syno_status build_plan(const syno_desc* desc, syno_plan* plan, std::string* why)
   // weight gradient, dW its input gradient (both need an fp32 result type).
   int64_t M = 0, K = 0, N = 0;
   if (policy != 1 && !plan->conv_like && recognise_matmul(g, M, K, N)) {
-    const int64_t width = fold_width(N);
-    if (width > 0) {
-      const syno_dim dims[4] = {{"n", 1}, {"i", M}, {"jr", N / width}, {"jc", width}};
+    // the 1x1 convolution of the product [rows x red] * [red x cols] (nullptr: cols cannot be folded into image rows)
+    auto conv_of_product = [&](int64_t rows, int64_t red, int64_t cols) -> syno_plan* {
+      const int64_t width = fold_width(cols);
+      if (width <= 0) return nullptr;
+      const syno_dim dims[4] = {{"n", 1}, {"i", rows}, {"jr", cols / width}, {"jc", width}};
       syno_prim pr[2] = {};
-      pr[0].kind = SYNO_REDUCE; pr[0].in[0] = pr[0].in[1] = -1; pr[0].out[0] = 4; pr[0].out[1] = -1; pr[0].param = K;
+      pr[0].kind = SYNO_REDUCE; pr[0].in[0] = pr[0].in[1] = -1; pr[0].out[0] = 4; pr[0].out[1] = -1; pr[0].param = red;
       pr[0].shift_by = -1;
       pr[1].kind = SYNO_SHARE; pr[1].in[0] = 4; pr[1].in[1] = -1; pr[1].out[0] = 5; pr[1].out[1] = 6;
       pr[1].shift_by = -1;
@@ -1268,21 +1270,38 @@ syno_status build_plan(const syno_desc* desc, syno_plan* plan, std::string* why)
       inner.in_dtype = desc->in_dtype; inner.out_dtype = desc->out_dtype;
       inner.options = desc->options;
       syno_plan* ip = new syno_plan();
-      if (build_plan(&inner, ip, nullptr) == SYNO_OK) {
-        const int map[3] = {SYNO_FWD, SYNO_BWD_WEIGHT, SYNO_BWD_DATA};
-        bool any = false;
-        for (int which = 0; which < 3; ++which) {
-          const Launch& IL = ip->launch[map[which]];
-          const bool fast = IL.kernel == KERNEL_MFMA_F32 || IL.kernel == KERNEL_MFMA_BF16;
-          if (!fast || (which != SYNO_FWD && desc->out_dtype != SYNO_F32)) continue;
-          plan->launch[which].kernel = KERNEL_MFMA_TRANSPOSED;
-          plan->launch[which].variant = map[which];
-          plan->launch[which].workspace = IL.workspace;
-          any = true;
+      if (build_plan(&inner, ip, nullptr) != SYNO_OK) { delete ip; return nullptr; }
+      return ip;
+    };
+    auto is_fast = [](const Launch& L) { return L.kernel == KERNEL_MFMA_F32 || L.kernel == KERNEL_MFMA_BF16; };
+    if (syno_plan* ip = conv_of_product(M, K, N)) {
+      const int map[3] = {SYNO_FWD, SYNO_BWD_WEIGHT, SYNO_BWD_DATA};
+      bool any = false;
+      for (int which = 0; which < 3; ++which) {
+        const Launch& IL = ip->launch[map[which]];
+        if (!is_fast(IL) || (which != SYNO_FWD && desc->out_dtype != SYNO_F32)) continue;
+        plan->launch[which].kernel = KERNEL_MFMA_TRANSPOSED;
+        plan->launch[which].variant = map[which];
+        plan->launch[which].workspace = IL.workspace;
+        any = true;
+      }
+      if (any) plan->inner = ip; else delete ip;
+    }
+    // dX[i,k] = sum_j G[i,j] W[k,j] is the product of G and W^T: with W^T written out (K*N elements, small beside
+    // G and dX) it runs on the forward contraction, whose tiles are the best this family has for 1x1 windows
+    if (plan->inner && K < (1ll << 31) && N < (1ll << 31)) {
+      if (syno_plan* ip = conv_of_product(M, N, K)) {
+        const Launch& IL = ip->launch[SYNO_FWD];
+        if (is_fast(IL)) {
+          Launch& L = plan->launch[SYNO_BWD_DATA];
+          L.kernel = KERNEL_MFMA_TRANSPOSED;
+          L.variant = kViaTransposedCopy;
+          const size_t esz = desc->in_dtype == SYNO_BF16 ? 2 : 4;
+          L.workspace = (((size_t)K * N * esz + 255) & ~(size_t)255) + IL.workspace;
+          plan->inner_dx = ip;
+        } else {
+          delete ip;
         }
-        if (any) plan->inner = ip; else delete ip;
-      } else {
-        delete ip;
       }
     }
   }

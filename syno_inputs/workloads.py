@@ -344,9 +344,9 @@ def operator1(stage: int, bf16: bool, N: int = 32, with_grad: bool = True) -> Ch
     return make_operator1(N, C, H, seed=0, bf16=bf16, with_grad=with_grad)
 
 
-def make_matmul(M, K, N, seed=0, bf16=False, with_grad=False) -> Workload:
+def make_matmul(M, K, N, seed=0, bf16=False, with_grad=False, out_bf16=False) -> Workload:
     """Table 2's matrix multiplication out[i,j] = sum_k X[i,k] * Wt[k,j]; X ~ N(0,1), Wt ~ U(+-1/sqrt(K))."""
-    desc = matmul(M, N, K, BF16 if bf16 else F32, F32)
+    desc = matmul(M, N, K, BF16 if bf16 else F32, BF16 if out_bf16 else F32)
     s = Stream(seed)
     xs, ws, os = (M, K), (K, N), (M, N)
     X = s.normal(xs)

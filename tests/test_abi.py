@@ -227,9 +227,13 @@ def test_matmul_is_planned_as_a_convolution_with_exchanged_roles(syno):
     assert [p.kernel(i) for i in range(3)] == ["mfma_contraction_transposed"] * 3
     assert "1x1 convolution" in p.describe(0)
     assert p.x_shape == (96, 768) and p.w_shape == (768, 2304) and p.out_shape == (96, 2304)
-    # a bf16 result type leaves the gradients on the index-program kernels (their results must be fp32 inside)
+    # dX = G * W^T is a product of its own: forward contraction on a transposed copy of W at the head of the workspace
+    assert "transposed copy of W" in p.describe(1) and p.workspace_bytes(1) >= 768 * 2304 * 4
+    # a bf16 result type leaves dW on the index-program kernel (its result must be fp32 inside)
     q = syno.Plan(wl.matmul(96, 2304, 768, BF16, BF16))
-    assert q.kernel(0) == "mfma_contraction_transposed" and q.kernel(1) == q.kernel(2) == "generic_index_program"
+    assert q.kernel(0) == q.kernel(1) == "mfma_contraction_transposed" and q.kernel(2) == "generic_index_program"
+    # too few reduction columns to fold W^T into image rows: dX stays the convolution's weight gradient
+    assert "transposed copy" not in syno.Plan(wl.matmul(64, 128, 3)).describe(1)
     # a prime number of columns above 64 cannot be folded into image rows
     assert syno.Plan(wl.matmul(8, 127, 80)).kernel(0) == "generic_index_program"
 

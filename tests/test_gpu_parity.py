@@ -663,6 +663,31 @@ def test_matmul_small(syno, oracle, M, K, N, bf16):
 
 
 @pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("splits", [2, 3])
+def test_contraction_with_split_reduction(syno, oracle, bf16, splits):
+    """Several workgroups per output tile, each summing a range of the channel chunks (the last range is shorter, and
+    with 80 channels the last bf16 chunk is incomplete); the partial results are added by a second kernel."""
+    w = wl.make_conv(2, 80, 12, seed=47, bf16=bf16, Co=96, with_grad=True)
+    plan = syno.Plan(w.desc, mfma_splits=splits)
+    for which in (0, 1):
+        assert f"reduction-splits={splits}" in plan.describe(which), plan.describe(which)
+        assert plan.workspace_bytes(which) >= splits * 2 * (96, 80)[which] * 12 * 12 * 4
+    names = run_all(syno, oracle, w, 0, directions=(0, 1), mfma_splits=splits)
+    assert all(n.startswith("mfma_contraction") for n in names[:2])
+    m = wl.make_matmul(136, 200, 640, seed=48, bf16=bf16, with_grad=True)
+    assert "reduction-splits" in syno.Plan(m.desc, mfma_splits=splits).describe(2)
+    assert run_all(syno, oracle, m, 0, mfma_splits=splits) == ["mfma_contraction_transposed"] * 3
+
+
+@pytest.mark.parametrize("M,K,N", [(130, 72, 112), (40, 7 * 9, 200)])
+def test_matmul_small_bf16_result(syno, oracle, M, K, N):
+    """With a bf16 result type the forward product and dX (the product G * W^T on a transposed copy of W) stay on
+    the contraction kernel; dW, which is fp32 inside, is left to the index-program kernel."""
+    names = run_all(syno, oracle, wl.make_matmul(M, K, N, seed=43, bf16=True, with_grad=True, out_bf16=True), 0)
+    assert names == ["mfma_contraction_transposed", "mfma_contraction_transposed", "generic_index_program"]
+
+
+@pytest.mark.parametrize("bf16", [False, True])
 def test_qkv_projection_full_size_sampled(syno, oracle, bf16):
     names = run_all(syno, oracle, wl.qkv_projection(bf16), 0, full=False, n_sample=2048)
     assert names == ["mfma_contraction_transposed"] * 3

@@ -11,6 +11,7 @@ namespace syno {
 struct MfmaParams {
   // problem, in forward terms
   int32_t G, Og, Cg, Ho, Wo, Hi, Wi, KH, KW, ph, pw;
+  int32_t sh, sw;                     // Stride below the window: output (h, w), tap (kh, kw) reads input (sh*h+kh-ph, sw*w+kw-pw)
   int32_t rows_total;                 // N*Ho output rows
   int32_t h_wrap, h_shift, h_shift_g; // cyclic rows: input row = (h + h_shift + h_shift_g*g) mod Hi  (KH = 1)
   int32_t xs_n, xs_c;                 // source strides: image, channel (rows are Wi apart, columns adjacent)
@@ -69,9 +70,9 @@ __device__ __forceinline__ int slot_source(const MfmaParams& p, int R0, int rows
   while (rho < end) {
     const int n = rho / p.Ho, h = rho - n * p.Ho;
     const int seg_rows = min(p.Ho - h, end - rho);
-    const int seg_slots = seg_rows + p.KH - 1;
+    const int seg_slots = (seg_rows - 1) * p.sh + p.KH;      // consecutive input rows, first one sh*h - ph
     if (s < s0 + seg_slots) {
-      const int r = h + (s - s0) - p.ph;
+      const int r = h * p.sh + (s - s0) - p.ph;
       return (r >= 0 && r < p.Hi) ? n * p.xs_n + r * p.Wi : -1;
     }
     s0 += seg_slots;
@@ -80,10 +81,11 @@ __device__ __forceinline__ int slot_source(const MfmaParams& p, int R0, int rows
   return -1;
 }
 
-// First slot of output row i of the block (tap kh adds kh slots).
+// First slot of output row i of the block (tap kh adds kh slots): a run of r rows of one image takes (r-1)*sh + KH
+// slots, so every image boundary before the row adds KH - sh to sh*i.
 __device__ __forceinline__ int slot_of_row(const MfmaParams& p, int R0, int i) {
   if (p.h_wrap) return i;
-  return i + (p.KH - 1) * (fdiv(R0 + i, p.m_ho) - fdiv(R0, p.m_ho));
+  return i * p.sh + (p.KH - p.sh) * (fdiv(R0 + i, p.m_ho) - fdiv(R0, p.m_ho));
 }
 
 // f(integral_constant<int, I>) for I = 0 .. N-1
@@ -259,7 +261,7 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
     int m = (my_first + t) * 16 + (lane & 15);
     if (t >= my_tiles || m >= block_px) m = 0;
     const int i = fdiv(m, p.m_wo), w = m - i * p.Wo;
-    const int px = slot_of_row(p, R0, i) * p.Wp + w;
+    const int px = slot_of_row(p, R0, i) * p.Wp + w * p.sw;
     a_base[t] = BF ? (px + (lane >> 4) * cg_stride) * 16 : px * 16 + (lane >> 4) * 4;
   }
   int b_base[TN];                                   // same for the B operand (weights)

@@ -175,6 +175,13 @@ int images_spanned(int TR, int Ho) {
   return (TR + Ho - 2) / Ho + 1;
 }
 
+// Row slots a block of TR output rows needs: a run of r rows of one image takes (r-1)*sh + KH consecutive input rows
+int row_slots(const ConvLike& c, int sh, int TR) {
+  if (c.h_wrap) return TR;
+  const int per_image = c.KH - sh;      // (may be negative: a 1x1 window under a Stride)
+  return TR * sh + per_image * (per_image >= 0 ? images_spanned(TR, c.Ho) : 1);
+}
+
 // LDS weight row pitch (in dwords) >= need such that the 64 lanes of a B-fragment read (16 rows x 4
 // channel steps of `kstep` dwords) fall into distinct banks where possible.
 int pick_w_row(int need, int kstep, int multiple_of) {
@@ -204,12 +211,14 @@ bool fill_params(const syno_plan* plan, int which, int vi, int TR, MfmaParams& p
   p.KH = c.KH; p.KW = c.KW;
   p.rows_total = c.N * c.Ho;
   p.h_wrap = c.h_wrap;
+  p.sh = p.sw = 1;
   const int plane = c.Hi * c.Wi;
   if (which == SYNO_FWD) {
     p.Og = c.Og; p.Cg = c.Cg; p.ph = c.ph; p.pw = c.pw;
+    p.sh = c.sh; p.sw = c.sw;         // (only forward takes a Stride below the window; its result plane is Ho x Wo)
     p.h_shift = c.h_shift; p.h_shift_g = c.h_shift_g;
     p.xs_c = plane; p.xs_n = c.G * c.Cg * plane;
-    p.os_o = plane; p.os_n = c.G * c.Og * plane;
+    p.os_o = c.Ho * c.Wo; p.os_n = c.G * c.Og * c.Ho * c.Wo;
     p.ws_g = c.ws_g; p.ws_o = c.ws_o; p.ws_c = c.ws_c; p.ws_kh = c.ws_kh; p.ws_kw = c.ws_kw; p.w_base = 0;
   } else {
     // dX[n,g*Cg+c,y,x] = sum_{o,kh',kw'} G[n,g*Og+o, y+kh'-(KH-1-ph), x+kw'-(KW-1-pw)] * W[g,o,c,KH-1-kh',KW-1-kw']
@@ -251,7 +260,7 @@ bool fill_params(const syno_plan* plan, int which, int vi, int TR, MfmaParams& p
       return false;
     p.KC = v.KC;
     while (p.KC > 8 && (p.Cg % p.KC != 0 || p.BN * p.KC * KHW > 4 * v.WI * v.NT() ||
-                        (p.KC / CI) * (c.h_wrap ? TR : TR + (c.KH - 1) * images_spanned(TR, c.Ho)) * ((c.Wi < 4) ? c.Wi : (c.Wi + 3) / 4) > v.XI * v.NT()))
+                        (p.KC / CI) * row_slots(c, p.sh, TR) * ((c.Wi < 4) ? c.Wi : (c.Wi + 3) / 4) > v.XI * v.NT()))
       p.KC -= 8;
     if (p.Cg % p.KC != 0 || ((p.KC * KHW) & 3) || p.BN * p.KC * KHW > 4 * v.WI * v.NT()) return false;
     p.w_row = pick_w_row(p.KC * KHW, KHW, 4);
@@ -274,7 +283,7 @@ bool fill_params(const syno_plan* plan, int which, int vi, int TR, MfmaParams& p
   p.U = (!bf && c.KW == 3 && (p.cgrps * c.KH) % v.WK == 0) ? 3 : 1;   // (bf16 runs out of registers with 3)
   p.n_mblocks = (p.rows_total + TR - 1) / TR;
   p.n_nblocks = (p.Og + p.BN - 1) / p.BN;
-  p.n_slots = c.h_wrap ? TR : TR + (c.KH - 1) * images_spanned(TR, c.Ho);
+  p.n_slots = row_slots(c, p.sh, TR);
   p.Wp = c.Wi + c.KW - 1;
   if ((TR * c.Wo + 15) / 16 > v.MT()) return false;
   p.vx = c.Wi < 4 ? 1 : 4;
@@ -359,9 +368,15 @@ bool mfma_supports(const syno_plan* p, int which) {
   if (!p->conv_like || which == SYNO_BWD_WEIGHT) return false;
   if (p->in_dtype == SYNO_F32 && p->out_dtype != SYNO_F32) return false;   // not instantiated
   const ConvLike& c = p->conv;
-  if (c.sh != 1 || c.sw != 1 || c.w_wrap) return false;
+  if (c.w_wrap) return false;
   if (c.h_wrap && c.KH != 1) return false;
-  if (c.Wi != c.Wo || c.Hi != c.Ho) return false;
+  if (c.sh != 1 || c.sw != 1) {
+    // a Stride below the window: forward only (its adjoint scatters), rows not cyclic, every tap inside the padded row
+    if (which != SYNO_FWD || c.h_wrap || c.sh < 1 || c.sw < 1 || c.sh > 4 || c.sw > 4) return false;
+    if ((c.Wo - 1) * c.sw >= c.Wi || (c.Ho - 1) * c.sh - c.ph >= c.Hi) return false;
+  } else if (c.Wi != c.Wo || c.Hi != c.Ho) {
+    return false;
+  }
   if (c.ph >= c.KH || c.pw >= c.KW) return false;
   if (c.Og == 1 && c.Cg == 1) return false;          // no contraction to speak of
   if (rows_supports(p, which)) return true;

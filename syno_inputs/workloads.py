@@ -22,12 +22,14 @@ from .rng import Stream, bf16_bits_to_f32, to_bf16_bits
 # ----------------------------------------------------------------------------
 # pGraphs
 # ----------------------------------------------------------------------------
-def conv2d(N, C, Co, H, W, KH=3, KW=None, in_dtype=F32, out_dtype=F32, w_order=(0, 1, 2, 3)) -> OpDesc:
-    """out[n,co,h,w] = sum_{c,kh,kw} X[n,c,h+kh-KH/2,w+kw-KW/2] * Wt[co,c,kh,kw].
+def conv2d(N, C, Co, H, W, KH=3, KW=None, in_dtype=F32, out_dtype=F32, w_order=(0, 1, 2, 3), stride=1) -> OpDesc:
+    """out[n,co,h,w] = sum_{c,kh,kw} X[n,c,S*h+kh-KH/2,S*w+kw-KW/2] * Wt[co,c,kh,kw]  (S = stride; H, W are the output's
+    extents, the input's are S*H, S*W).
     `w_order` lists which of (co, c, kh, kw) each weight axis is, outermost first (weights may be laid out in any
     order: section 6 of the paper lets them be reshaped offline)."""
     KW = KH if KW is None else KW
-    b = Builder([("n", N), ("co", Co), ("h", H), ("w", W)], name=f"conv{KH}x{KW}_C{C}_Co{Co}_{H}x{W}_N{N}")
+    b = Builder([("n", N), ("co", Co), ("h", H), ("w", W)],
+                name=f"conv{KH}x{KW}{f's{stride}' if stride > 1 else ''}_C{C}_Co{Co}_{H}x{W}_N{N}")
     n, co, h, w = 0, 1, 2, 3
     c = b.reduce(C)
     cx, cw = b.share(c)
@@ -35,8 +37,8 @@ def conv2d(N, C, Co, H, W, KH=3, KW=None, in_dtype=F32, out_dtype=F32, w_order=(
     khx, khw = b.share(kh)
     kw = b.reduce(KW)
     kwx, kww = b.share(kw)
-    hh = b.unfold(h, khx)
-    ww = b.unfold(w, kwx)
+    hh = b.unfold(b.stride(h, stride) if stride > 1 else h, khx)
+    ww = b.unfold(b.stride(w, stride) if stride > 1 else w, kwx)
     waxes = [co, cw, khw, kww]
     return b.finish([n, cx, hh, ww], [waxes[i] for i in w_order], in_dtype, out_dtype)
 
@@ -213,13 +215,14 @@ def _finish(desc, xs, ws, os, X, W, G, red) -> Workload:
 
 
 def make_conv(N, C, H, seed=0, bf16=False, Co=None, Wd=None, K=3, with_grad=False, out_bf16=False,
-              w_order=(0, 1, 2, 3)) -> Workload:
+              w_order=(0, 1, 2, 3), stride=1) -> Workload:
+    """H, Wd: the output's extents (the input is `stride` times as large)."""
     Co = C if Co is None else Co
     Wd = H if Wd is None else Wd
-    desc = conv2d(N, C, Co, H, Wd, K, K, BF16 if bf16 else F32, BF16 if out_bf16 else F32, w_order)
+    desc = conv2d(N, C, Co, H, Wd, K, K, BF16 if bf16 else F32, BF16 if out_bf16 else F32, w_order, stride)
     s = Stream(seed)
     nat = (Co, C, K, K)
-    xs, ws, os = (N, C, H, Wd), tuple(nat[i] for i in w_order), (N, Co, H, Wd)
+    xs, ws, os = (N, C, stride * H, stride * Wd), tuple(nat[i] for i in w_order), (N, Co, H, Wd)
     X = s.normal(xs)
     W = s.uniform_pm(1.0 / np.sqrt(K * K * C), ws)
     G = s.normal(os) if with_grad else None

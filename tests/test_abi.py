@@ -222,6 +222,15 @@ def test_unreduced_window_goes_to_the_streaming_family(syno):
     assert syno.Plan(wl.conv2d(2, 16, 16, 8, 8, 1, 3)).kernel(0).startswith("mfma")
 
 
+def test_strided_convolution_forward_is_a_contraction(syno):
+    for K in (3, 1):
+        p = syno.Plan(wl.conv2d(2, 16, 24, 6, 6, K, stride=2))
+        assert p.x_shape == (2, 16, 12, 12) and p.out_shape == (2, 24, 6, 6)
+        # forward gathers the strided window into LDS; the adjoints (a scatter, a strided weight gradient) stay generic
+        assert [p.kernel(i) for i in range(3)] == ["mfma_contraction_f32", "generic_index_program", "generic_index_program"]
+    assert syno.Plan(wl.conv2d(2, 16, 24, 6, 6, 3, in_dtype=BF16, stride=2)).kernel(0) == "mfma_contraction_bf16"
+
+
 def test_matmul_is_planned_as_a_convolution_with_exchanged_roles(syno):
     p = syno.Plan(wl.matmul(96, 2304, 768))
     assert [p.kernel(i) for i in range(3)] == ["mfma_contraction_transposed"] * 3

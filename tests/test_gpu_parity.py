@@ -120,6 +120,12 @@ def small_cases():
     c["conv_f32_10wide"] = lambda: wl.make_conv(2, 16, 9, seed=22, Co=16, Wd=10, with_grad=True)
     c["conv_bf16_14x14_three_images"] = lambda: wl.make_conv(3, 24, 14, seed=23, Co=40, bf16=True, with_grad=True)
     c["conv_bf16_7x7_eleven_images"] = lambda: wl.make_conv(11, 40, 7, seed=24, Co=72, bf16=True, with_grad=True)
+    # a Stride below the window (the downsampling convolutions of a ResNet stage): forward on the contraction kernel
+    c["conv_f32_3x3_stride2"] = lambda: wl.make_conv(3, 24, 7, seed=25, Co=40, Wd=9, stride=2, with_grad=True)
+    c["conv_bf16_3x3_stride2"] = lambda: wl.make_conv(3, 40, 7, seed=26, Co=24, Wd=9, stride=2, bf16=True, with_grad=True)
+    c["conv_f32_1x1_stride2"] = lambda: wl.make_conv(5, 40, 4, seed=27, Co=48, Wd=6, K=1, stride=2, with_grad=True)
+    c["conv_bf16_1x1_stride2"] = lambda: wl.make_conv(5, 72, 4, seed=28, Co=48, Wd=6, K=1, stride=2, bf16=True, with_grad=True)
+    c["conv_f32_3x3_stride3"] = lambda: wl.make_conv(2, 16, 5, seed=29, Co=24, Wd=9, stride=3, with_grad=True)
     c["gshift_bf16"] = lambda: wl.make_gshift(3, seeds=(1, 2, 3), with_grad=True)
     c["gshift_bf16_small_groups"] = lambda: wl.make_gshift(2, seeds=(4, 5, 6), with_grad=True, C=96, H=9, Wd=11, groups=3)
     c["gshift_f32"] = lambda: wl.make_gshift(2, seeds=(7, 8, 9), with_grad=True, C=64, H=6, Wd=10, groups=2, bf16=False)
@@ -159,6 +165,17 @@ def test_conv_f32_named_tile_variants(syno, oracle, variant, rows, order):
     plan = syno.Plan(w.desc, mfma_variant=variant + 1, mfma_rows=rows)
     assert f"variant={variant} rows/block={rows} " in plan.describe(syno.FWD)
     run_all(syno, oracle, w, 0, directions=(0, 1), mfma_variant=variant + 1, mfma_rows=rows)
+
+
+@pytest.mark.parametrize("bf16,variant,rows,K", [(False, 3, 10, 3), (False, 0, 5, 3), (False, 11, 9, 1), (True, 0, 10, 3),
+                                                 (True, 6, 6, 3), (True, 2, 11, 1), (True, 3, 7, 1)])
+def test_strided_conv_blocks_across_images(syno, oracle, bf16, variant, rows, K):
+    """Stride 2 below the window, with tiles of several output rows that start and end inside images (4 rows per image):
+    every image boundary inside a tile changes the slot of the rows after it by KH - 2."""
+    w = wl.make_conv(5, 40, 4, seed=60 + variant, Co=40, Wd=9, K=K, stride=2, bf16=bf16)
+    plan = syno.Plan(w.desc, mfma_variant=variant + 1, mfma_rows=rows)
+    assert f"variant={variant} rows/block={rows} " in plan.describe(syno.FWD), plan.describe(syno.FWD)
+    assert run_all(syno, oracle, w, 0, directions=(0,), mfma_variant=variant + 1, mfma_rows=rows)[0].startswith("mfma_contraction")
 
 
 @pytest.mark.parametrize("variant,rows", [(0, 4), (3, 3), (4, 2), (5, 1), (6, 4), (7, 4), (8, 2)])

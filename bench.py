@@ -401,8 +401,11 @@ def main() -> int:
                 nb = 4 * (int(np.prod(pv.x_shape)) + int(np.prod(pv.out_shape)))
                 # forward reads X through the view and writes the result in runs; backward-data (both views are
                 # one-to-one) reads the gradient in runs and scatters dX through the same tables
-                for which, tag in ((0, "_fwd"), (1, "_bwd_data")):
-                    calls = [pv.bind(0, a, b, o) if which == 0 else pv.bind(1, o, b, a) for a, b, o in sets_v]
+                # backward-weight reads the gradient and X and leaves one sum per weight element
+                dws = [torch.empty(pv.w_shape if pv.w_shape else (1,), device=dev) for _ in range(4)]
+                for which, tag in ((0, "_fwd"), (1, "_bwd_data"), (2, "_bwd_weight")):
+                    calls = [pv.bind(0, a, b, o) if which == 0 else pv.bind(1, o, b, a) if which == 1 else pv.bind(2, a, o, dw)
+                             for (a, b, o), dw in zip(sets_v, dws)]
                     it = [0]
 
                     def run_view():

@@ -33,7 +33,8 @@ struct syno_chain {
 namespace syno {
 syno_status launch_bandwidth(const syno_plan* p, int which, const void* A, const void* B, void* out, void* ws,
                              hipStream_t stream);
-syno_status launch_view(const syno_plan* p, int which, const void* A, const void* B, void* out, hipStream_t stream);
+syno_status launch_view(const syno_plan* p, int which, const void* A, const void* B, void* out, void* ws,
+                        hipStream_t stream);
 syno_status launch_window(const syno_plan* p, int which, const void* A, const void* B, void* out, void* ws,
                           hipStream_t stream);
 syno_status launch_mfma(const syno_plan* p, int which, const void* A, const void* B, void* out, void* ws,
@@ -98,7 +99,7 @@ syno_status run(const syno_plan* plan, int which, const void* A, const void* B, 
     case syno::KERNEL_GENERIC: return syno::launch_generic(plan, which, A, B, out, stream);
     case syno::KERNEL_BW_DEPTHWISE: return syno::launch_bandwidth(plan, which, A, B, out, ws, stream);
     case syno::KERNEL_BW_WINDOW: return syno::launch_window(plan, which, A, B, out, ws, stream);
-    case syno::KERNEL_BW_VIEW: return syno::launch_view(plan, which, A, B, out, stream);
+    case syno::KERNEL_BW_VIEW: return syno::launch_view(plan, which, A, B, out, ws, stream);
     case syno::KERNEL_MFMA_F32:
     case syno::KERNEL_MFMA_BF16:
       if (which == SYNO_BWD_WEIGHT) return syno::launch_mfma_dw(plan, A, B, out, ws, stream);

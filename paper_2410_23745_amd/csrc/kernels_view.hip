@@ -4,7 +4,9 @@
 //
 //   out[o] = sum_r X[offX(o,r)] * W[offW(o,r)]
 //
-// and, for one-to-one views, backward-data as the scatter dX[offX(o)] = G[o] * W[offW(o)].
+// for one-to-one views backward-data as the scatter dX[offX(o)] = G[o] * W[offW(o)], and backward-weight where every
+// weight element belongs to one combination of output indices: dW[offW(o)] = sum over the other output axes (and the
+// sum points) of G[o] * X[offX(o,r)], a segmented dot product reduced in a fixed order.
 //
 // When every tensor axis is an affine function of digits of the iterators - wrapped (Shift) only over digits of
 // one iterator - both offsets are sums of one small table per iterator (plan.h, ViewStream); the tables of the
@@ -14,9 +16,11 @@
 // axis is a table walk, the result leaves as one vector store.  The loads follow whatever order the view imposes.
 #include <hip/hip_runtime.h>
 
-#include <cstring>
-
+#include <algorithm>
 #include <cstdlib>
+#include <cstring>
+#include <type_traits>
+#include <vector>
 
 #include "plan.h"
 
@@ -93,6 +97,54 @@ __device__ __forceinline__ void store_one(void* base, int64_t off, float v) {
   else static_cast<float*>(base)[off] = v;
 }
 
+// Contribution of iterator `axis` at index o to the X offset (off[0]) and the W offset (off[1]).
+__host__ __device__ inline void table_entry(const ViewStream& vs, int axis, int o, int (&off)[2]) {
+  off[0] = off[1] = 0;
+  for (int gi = 0; gi < vs.n_groups; ++gi) {
+    const ViewGroup g = vs.group[gi];
+    int partial = 0;
+    const bool mine = g.axis == axis;          // the group's constant (and its wrap) are charged to one axis only
+    for (int t = 0; t < vs.n_terms; ++t) {
+      const ViewTerm tm = vs.term[t];
+      if (tm.group == gi && tm.axis == axis) partial += tm.coef * ((o / tm.div) % tm.size);
+    }
+    if (g.wrap > 0) {
+      if (mine) off[g.tensor] += ((partial + g.c) % g.wrap) * g.stride;
+    } else {
+      off[g.tensor] += (partial + (mine ? g.c : 0)) * g.stride;
+    }
+  }
+}
+
+// Every workgroup builds the tables in LDS: tab[tab_off[i] + o] (X) and tab[tab_total + tab_off[i] + o] (W) for every
+// iterator i, then the folded table over the sum points at free_off.  Ends with a barrier.
+__device__ __forceinline__ void build_tables(const ViewStream& vs, const int32_t* tab_off, int free_off, int n_free,
+                                             int tab_total, int* tab) {
+  const int n_iter = vs.n_axes + vs.n_red;
+  for (int idx = threadIdx.x; idx < free_off; idx += kThreads) {
+    int axis = 0;
+    while (axis + 1 < n_iter && idx >= tab_off[axis + 1]) ++axis;
+    int off[2];
+    table_entry(vs, axis, idx - tab_off[axis], off);
+    tab[idx] = off[0];
+    tab[tab_total + idx] = off[1];
+  }
+  __syncthreads();
+  // sum point q (Reduce iterators row-major, the order of the loop nest) -> the sum of its iterators' entries
+  for (int q = threadIdx.x; q < n_free; q += kThreads) {
+    int rest = q, fx = 0, fw = 0;
+    for (int j = vs.n_red - 1; j >= 0; --j) {
+      const int sz = vs.size[vs.n_axes + j], d = rest % sz;
+      rest /= sz;
+      fx += tab[tab_off[vs.n_axes + j] + d];
+      fw += tab[tab_total + tab_off[vs.n_axes + j] + d];
+    }
+    tab[free_off + q] = fx;
+    tab[tab_total + free_off + q] = fw;
+  }
+  __syncthreads();
+}
+
 // SCATTER: backward-data of a one-to-one view.  X is then the upstream gradient, shaped like the forward result and
 // read in runs, and `out` is dX: dX[offX(o)] = G[o] * W[offW(o)], every element written exactly once.
 template <int V, bool IBF, bool OBF, bool SCATTER>
@@ -100,44 +152,7 @@ __global__ __launch_bounds__(kThreads) void view_stream(const ViewParams p, cons
                                                         const void* __restrict__ Wt, void* __restrict__ out) {
   extern __shared__ __align__(16) int tab[];   // [2][tab_total]: X offsets, then W offsets; then the waves' exchange areas
   const ViewStream& vs = p.vs;
-  // table entry (axis i, index o): the contribution of output axis i to each offset
-  const int n_iter = vs.n_axes + vs.n_red;
-  for (int idx = threadIdx.x; idx < p.free_off; idx += kThreads) {
-    int axis = 0;
-    while (axis + 1 < n_iter && idx >= p.tab_off[axis + 1]) ++axis;
-    const int o = idx - p.tab_off[axis];
-    int off[2] = {0, 0};
-    for (int gi = 0; gi < vs.n_groups; ++gi) {
-      const ViewGroup g = vs.group[gi];
-      int partial = 0;
-      bool mine = g.axis == axis;          // the group's constant (and its wrap) are charged to one axis only
-      for (int t = 0; t < vs.n_terms; ++t) {
-        const ViewTerm tm = vs.term[t];
-        if (tm.group == gi && tm.axis == axis) partial += tm.coef * ((o / tm.div) % tm.size);
-      }
-      if (g.wrap > 0) {
-        if (mine) off[g.tensor] += ((partial + g.c) % g.wrap) * g.stride;
-      } else {
-        off[g.tensor] += (partial + (mine ? g.c : 0)) * g.stride;
-      }
-    }
-    tab[idx] = off[0];
-    tab[p.tab_total + idx] = off[1];
-  }
-  __syncthreads();
-  // sum point q (Reduce iterators row-major, the order of the loop nest) -> the sum of its iterators' entries
-  for (int q = threadIdx.x; q < p.n_free; q += kThreads) {
-    int rest = q, fx = 0, fw = 0;
-    for (int j = vs.n_red - 1; j >= 0; --j) {
-      const int sz = vs.size[vs.n_axes + j], d = rest % sz;
-      rest /= sz;
-      fx += tab[p.tab_off[vs.n_axes + j] + d];
-      fw += tab[p.tab_total + p.tab_off[vs.n_axes + j] + d];
-    }
-    tab[p.free_off + q] = fx;
-    tab[p.tab_total + p.free_off + q] = fw;
-  }
-  __syncthreads();
+  build_tables(vs, p.tab_off, p.free_off, p.n_free, p.tab_total, tab);
   const int last = vs.n_axes - 1;
   const uint32_t runs_per_row = (uint32_t)vs.size[last] / V;
   const int* const tx_last = tab + p.tab_off[last];
@@ -284,6 +299,185 @@ __global__ __launch_bounds__(kThreads) void view_stream(const ViewParams p, cons
   }
 }
 
+// ---- backward-weight ------------------------------------------------------------------------------------
+// Output axes whose W table varies ("carrying") pick the weight element; the host has checked that every combination
+// of their indices picks a different one and that together they pick all of W.  A workgroup takes one combination
+// and one slice of the remaining output axes (flattened row-major), so G is read along the innermost remaining
+// axis; threads keep private sums, the workgroup adds them in a fixed tree, and a second kernel adds the slices.
+struct ViewDwParams {
+  ViewStream vs;
+  int32_t tab_off[2 * kMaxAxes];
+  int32_t tab_total, n_free, free_off;
+  int32_t n_carry, n_rest;
+  int32_t carry_axis[kMaxAxes], rest_axis[kMaxAxes];   // outermost first
+  uint32_t rest_magic[kMaxAxes];                       // division_magic(size) of the remaining axes
+  int32_t ostride[kMaxAxes];                           // element strides of the output axes
+  int32_t n_w, n_splits;                               // carrying combinations (= elements of W); slices
+  int32_t run;                                         // adjacent indices of the innermost remaining axis per thread and step: 4 or 1
+  int64_t total_rest, chunk;                           // runs over the remaining axes; per slice
+};
+
+template <bool IBF>
+__global__ __launch_bounds__(kThreads) void view_weight_grad(const ViewDwParams p, const void* __restrict__ G,
+                                                             const void* __restrict__ X, float* __restrict__ partial,
+                                                             int* __restrict__ w_index) {
+  extern __shared__ __align__(16) int tab[];
+  __shared__ float wave_sum[kThreads / 64];
+  const ViewStream& vs = p.vs;
+  build_tables(vs, p.tab_off, p.free_off, p.n_free, p.tab_total, tab);
+  const int wid = blockIdx.x / p.n_splits, slice = blockIdx.x - wid * p.n_splits;
+  int g0 = 0, x0 = 0, w0 = tab[p.tab_total + p.free_off];      // (the sum points' W entries are all the same)
+  {
+    int rest = wid;
+    for (int j = p.n_carry - 1; j >= 0; --j) {
+      const int axis = p.carry_axis[j], sz = vs.size[axis], d = rest % sz;
+      rest /= sz;
+      g0 += d * p.ostride[axis];
+      x0 += tab[p.tab_off[axis] + d];
+      w0 += tab[p.tab_total + p.tab_off[axis] + d];
+    }
+    for (int j = 0; j < p.n_rest; ++j) w0 += tab[p.tab_total + p.tab_off[p.rest_axis[j]]];   // constant tables
+  }
+  const int* fx = tab + p.free_off;
+  const int64_t begin = slice * p.chunk, end = min(p.total_rest, begin + p.chunk);
+  float acc = 0.f;
+  auto walk = [&](auto run_c) {
+    constexpr int R = decltype(run_c)::value;
+    const int inner = p.rest_axis[p.n_rest - 1];
+    const uint32_t inner_runs = (uint32_t)vs.size[inner] / R;
+    const int* tx_inner = tab + p.tab_off[inner];
+    for (int64_t idx = begin + threadIdx.x; idx < end; idx += kThreads) {
+      uint32_t rest = (uint32_t)idx;
+      const uint32_t q0 = div_magic(rest, inner_runs, p.rest_magic[p.n_rest - 1]);
+      const int d0 = (int)(rest - q0 * inner_runs) * R;
+      rest = q0;
+      int go = g0 + d0 * p.ostride[inner], xo = x0;
+      for (int j = p.n_rest - 2; j >= 0; --j) {
+        const int axis = p.rest_axis[j];
+        const uint32_t sz = (uint32_t)vs.size[axis];
+        const uint32_t q = div_magic(rest, sz, p.rest_magic[j]);
+        const int d = (int)(rest - q * sz);
+        rest = q;
+        go += d * p.ostride[axis];
+        xo += tab[p.tab_off[axis] + d];
+      }
+      float g[R];
+#pragma unroll
+      for (int k = 0; k < R; ++k) g[k] = load_one<IBF>(G, go + k * p.ostride[inner]);
+      if (p.n_free == 1) {
+        float x[R];
+#pragma unroll
+        for (int k = 0; k < R; ++k) x[k] = load_one<IBF>(X, xo + tx_inner[d0 + k] + fx[0]);
+#pragma unroll
+        for (int k = 0; k < R; ++k) acc = fmaf(g[k], x[k], acc);
+      } else {
+#pragma unroll
+        for (int k = 0; k < R; ++k)
+          for (int q = 0; q < p.n_free; ++q) acc = fmaf(g[k], load_one<IBF>(X, xo + tx_inner[d0 + k] + fx[q]), acc);
+      }
+    }
+  };
+  if (p.run == 4) walk(std::integral_constant<int, 4>{});
+  else walk(std::integral_constant<int, 1>{});
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) acc += __shfl_down(acc, d, 64);
+  if ((threadIdx.x & 63) == 0) wave_sum[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float t = wave_sum[0];
+    for (int w = 1; w < kThreads / 64; ++w) t += wave_sum[w];
+    partial[blockIdx.x] = t;
+    if (slice == 0) w_index[wid] = w0;
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void view_weight_grad_sum(const float* __restrict__ partial,
+                                                                 const int* __restrict__ w_index, float* __restrict__ dW,
+                                                                 int n_w, int n_splits) {
+  const int wid = blockIdx.x * kThreads + threadIdx.x;
+  if (wid >= n_w) return;
+  float t = partial[(int64_t)wid * n_splits];
+  for (int s = 1; s < n_splits; ++s) t += partial[(int64_t)wid * n_splits + s];
+  dW[w_index[wid]] = t;
+}
+
+bool fill_dw(const syno_plan* plan, ViewDwParams& p) {
+  p = ViewDwParams{};
+  p.vs = plan->view;
+  const ViewStream& vs = p.vs;
+  if (plan->out_elems >= (int64_t(1) << 31) || plan->x_elems >= (int64_t(1) << 31) || plan->w_elems > (1 << 20)) return false;
+  int total = 0;
+  p.n_free = 1;
+  for (int i = 0; i < vs.n_axes + vs.n_red; ++i) {
+    p.tab_off[i] = total;
+    total += vs.size[i];
+    if (i >= vs.n_axes) p.n_free *= vs.size[i];
+  }
+  p.free_off = total;
+  total += p.n_free;
+  p.tab_total = total;
+  if (total <= 0 || (size_t)total * 8 > 48 * 1024) return false;
+  // carrying axes: those whose W table is not constant; the sum points must not move the weight
+  int64_t n_w = 1, stride = 1;
+  p.total_rest = 1;
+  for (int i = vs.n_axes - 1; i >= 0; --i) { p.ostride[i] = (int32_t)stride; stride *= vs.size[i]; }
+  for (int i = 0; i < vs.n_axes + vs.n_red; ++i) {
+    int first[2], off[2];
+    table_entry(vs, i, 0, first);
+    bool varies = false;
+    for (int o = 1; o < vs.size[i] && !varies; ++o) {
+      table_entry(vs, i, o, off);
+      varies = off[1] != first[1];
+    }
+    if (i >= vs.n_axes) {
+      if (varies) return false;
+    } else if (varies) {
+      p.carry_axis[p.n_carry++] = i;
+      n_w *= vs.size[i];
+    } else {
+      p.rest_magic[p.n_rest] = division_magic(vs.size[i]);
+      p.rest_axis[p.n_rest++] = i;
+      p.total_rest *= vs.size[i];
+    }
+  }
+  if (n_w != plan->w_elems || p.total_rest < 64) return false;
+  p.n_w = (int32_t)n_w;
+  // every combination its own weight element
+  {
+    std::vector<char> seen((size_t)n_w, 0);
+    std::vector<std::vector<int>> wtab(p.n_carry);
+    int base = 0, off[2];
+    for (int i = 0; i < vs.n_axes + vs.n_red; ++i) {
+      bool carry = false;
+      for (int j = 0; j < p.n_carry; ++j) carry |= p.carry_axis[j] == i;
+      if (!carry) { table_entry(vs, i, 0, off); base += off[1]; }
+    }
+    for (int j = 0; j < p.n_carry; ++j)
+      for (int o = 0; o < vs.size[p.carry_axis[j]]; ++o) { table_entry(vs, p.carry_axis[j], o, off); wtab[j].push_back(off[1]); }
+    for (int64_t wid = 0; wid < n_w; ++wid) {
+      int64_t rest = wid, w = base;
+      for (int j = p.n_carry - 1; j >= 0; --j) { const int sz = vs.size[p.carry_axis[j]]; w += wtab[j][rest % sz]; rest /= sz; }
+      if (w < 0 || w >= n_w || seen[(size_t)w]) return false;
+      seen[(size_t)w] = 1;
+    }
+  }
+  // a thread takes 4 adjacent indices of the innermost remaining axis per step where that divides it
+  if (p.n_rest == 0) {      // (every axis selects the weight: ruled out above by the size test, kept for safety)
+    return false;
+  }
+  const int inner = p.rest_axis[p.n_rest - 1];
+  p.run = vs.size[inner] % 4 == 0 ? 4 : 1;
+  p.rest_magic[p.n_rest - 1] = division_magic(vs.size[inner] / p.run);
+  p.total_rest /= p.run;
+  // about 2048 workgroups, each with at least a few thousand products
+  int64_t splits = std::max<int64_t>(1, std::min<int64_t>(2048 / n_w, p.total_rest * p.run / 4096));
+  p.chunk = (p.total_rest + splits - 1) / splits;
+  p.n_splits = (int32_t)((p.total_rest + p.chunk - 1) / p.chunk);
+  return (int64_t)p.n_w * p.n_splits < (int64_t(1) << 31);
+}
+
+size_t dw_partial_bytes(const ViewDwParams& p) { return (((size_t)p.n_w * p.n_splits * 4) + 255) & ~(size_t)255; }
+
 template <bool IBF, bool OBF, bool SCATTER>
 void launch_typed(const ViewParams& p, int V, size_t lds, const void* X, const void* W, void* out, hipStream_t s) {
   const int64_t blocks = (p.n_runs + kThreads - 1) / kThreads;
@@ -335,24 +529,53 @@ bool fill(const syno_plan* plan, ViewParams& p) {
 // Forward of every separable gather; backward-data where the view is one-to-one (a scatter of the same tables).
 bool view_supports(const syno_plan* plan, int which) {
   if (!plan->pure_view) return false;
-  if (which == SYNO_BWD_WEIGHT || (which == SYNO_BWD_DATA && !plan->view.one_to_one)) return false;
+  if (which == SYNO_BWD_WEIGHT) {
+    ViewDwParams d;
+    return fill_dw(plan, d);
+  }
+  if (which == SYNO_BWD_DATA && !plan->view.one_to_one) return false;
   if (plan->in_dtype == SYNO_F32 && plan->out_dtype != SYNO_F32) return false;
   ViewParams p;
   return fill(plan, p);
 }
 
 void view_configure(syno_plan* plan, int which) {
-  ViewParams p;
   Launch& L = plan->launch[which];
+  if (which == SYNO_BWD_WEIGHT) {
+    ViewDwParams d;
+    static_assert(sizeof(ViewDwParams) <= sizeof(L.params), "parameter record does not fit");
+    L.params_ready = fill_dw(plan, d);
+    memcpy(L.params, &d, sizeof d);
+    L.workspace = dw_partial_bytes(d) + (size_t)d.n_w * 4;     // slice sums, then the weight index of every combination
+    return;
+  }
+  ViewParams p;
   static_assert(sizeof(ViewParams) <= sizeof(L.params), "parameter record does not fit");
   L.params_ready = fill(plan, p);
   memcpy(L.params, &p, sizeof p);
   L.workspace = 0;
 }
 
-// forward: A = X, B = W, out = result; backward-data: A = G, B = W, out = dX
-syno_status launch_view(const syno_plan* plan, int which, const void* A, const void* B, void* out, hipStream_t stream) {
+// forward: A = X, B = W, out = result; backward-data: A = G, B = W, out = dX; backward-weight: A = G, B = X, out = dW
+syno_status launch_view(const syno_plan* plan, int which, const void* A, const void* B, void* out, void* ws,
+                        hipStream_t stream) {
   if (!plan->launch[which].params_ready) return SYNO_ERR_UNSUPPORTED;
+  if (which == SYNO_BWD_WEIGHT) {
+    if (!ws) return SYNO_ERR_WORKSPACE;
+    ViewDwParams d;
+    memcpy(&d, plan->launch[which].params, sizeof d);
+    float* partial = static_cast<float*>(ws);
+    int* w_index = reinterpret_cast<int*>(static_cast<char*>(ws) + dw_partial_bytes(d));
+    const dim3 grid((unsigned)(d.n_w * d.n_splits));
+    const size_t lds = (size_t)d.tab_total * 8;
+    if (plan->in_dtype == SYNO_BF16)
+      hipLaunchKernelGGL(view_weight_grad<true>, grid, dim3(kThreads), lds, stream, d, A, B, partial, w_index);
+    else
+      hipLaunchKernelGGL(view_weight_grad<false>, grid, dim3(kThreads), lds, stream, d, A, B, partial, w_index);
+    hipLaunchKernelGGL(view_weight_grad_sum, dim3((unsigned)((d.n_w + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream,
+                       partial, w_index, static_cast<float*>(out), d.n_w, d.n_splits);
+    return hipGetLastError() == hipSuccess ? SYNO_OK : SYNO_ERR_HIP;
+  }
   ViewParams p;
   memcpy(&p, plan->launch[which].params, sizeof p);
   const int V = run_width(plan);

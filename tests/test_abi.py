@@ -269,9 +269,12 @@ def test_materialised_reduction_pass_cuts_where_it_saves_work(syno):
 def test_reduce_free_graphs_go_to_the_view_kernel_forwards(syno):
     for d in (wl.shifted_scale(2, 8, 6, 6), wl.pixel_unshuffle(2, 4, 3, 4, 2)):
         p = syno.Plan(d)
-        # one-to-one views: backward-data is the scatter of the same tables; backward-weight sums, so it is not a view
-        assert p.kernel(0) == p.kernel(1) == "bandwidth_view" and p.kernel(2) == "generic_index_program"
-        assert p.workspace_bytes(0) == p.workspace_bytes(1) == 0
+        # one-to-one views: backward-data is the scatter of the same tables; backward-weight is one dot product per
+        # weight element over the output axes that do not select it (slice sums and weight indices in the workspace)
+        assert p.kernel(0) == p.kernel(1) == p.kernel(2) == "bandwidth_view"
+        assert p.workspace_bytes(0) == p.workspace_bytes(1) == 0 and p.workspace_bytes(2) >= 4 * (1 + int(np.prod(p.w_shape)))
+    # a weight gradient with fewer than 64 products per weight element is left to the index-program kernel
+    assert syno.Plan(wl.shifted_scale(1, 8, 3, 6)).kernel(2) == "generic_index_program"
     # not one-to-one: an Expand repeats X, a Stride leaves elements of X unread (their gradient is zero)
     b = Builder([("i", 6), ("j", 4)])
     b.expand(1)

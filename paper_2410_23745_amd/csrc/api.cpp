@@ -215,6 +215,7 @@ syno_status syno_plan_describe(const syno_plan* plan, int which, char* buf, size
     case syno::KERNEL_MFMA_BF16:
       d += " " + (which == SYNO_BWD_WEIGHT ? syno::mfma_dw_describe(plan) : syno::mfma_describe(plan, which));
       break;
+    case syno::KERNEL_BW_VIEW: d += " " + syno::view_describe(plan, which); break;
     case syno::KERNEL_MFMA_TRANSPOSED: {
       char inner[400];
       if (plan->launch[which].variant == syno::kViaTransposedCopy) {

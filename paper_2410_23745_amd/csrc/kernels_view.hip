@@ -4,9 +4,9 @@
 //
 //   out[o] = sum_r X[offX(o,r)] * W[offW(o,r)]
 //
-// for one-to-one views backward-data as the scatter dX[offX(o)] = G[o] * W[offW(o)], and backward-weight where every
-// weight element belongs to one combination of output indices: dW[offW(o)] = sum over the other output axes (and the
-// sum points) of G[o] * X[offX(o,r)], a segmented dot product reduced in a fixed order.
+// for one-to-one views backward-data as the scatter dX[offX(o)] = G[o] * W[offW(o)], and the other gradients
+// (backward-weight; backward-data of views that repeat or skip elements of X) as gathers: every target element is
+// the sum, in a fixed order, of the products of the iterators that do not select it.
 //
 // When every tensor axis is an affine function of digits of the iterators - wrapped (Shift) only over digits of
 // one iterator - both offsets are sums of one small table per iterator (plan.h, ViewStream); the tables of the
@@ -19,6 +19,7 @@
 #include <algorithm>
 #include <cstdlib>
 #include <cstring>
+#include <string>
 #include <type_traits>
 #include <vector>
 
@@ -299,59 +300,84 @@ __global__ __launch_bounds__(kThreads) void view_stream(const ViewParams p, cons
   }
 }
 
-// ---- backward-weight ------------------------------------------------------------------------------------
-// Output axes whose W table varies ("carrying") pick the weight element; the host has checked that every combination
-// of their indices picks a different one and that together they pick all of W.  A workgroup takes one combination
-// and one slice of the remaining output axes (flattened row-major), so G is read along the innermost remaining
-// axis; threads keep private sums, the workgroup adds them in a fixed tree, and a second kernel adds the slices.
-struct ViewDwParams {
+// ---- gradients as gathers ------------------------------------------------------------------------------
+// Backward-weight, and backward-data of views that are not one-to-one (an Expand sums, a Stride leaves gaps):
+//   target[offT(i)] = sum over the other iterators of G[o] * other[offO(i)],   T, O = (W, X) or (X, W)
+// over all iterators i = output axes and Reduce iterators.  The iterators whose T table varies ("carrying") pick
+// the target element; the host has checked, by enumerating the tables, that every combination of their indices picks
+// a different one (elements that none picks are zeroed first).  The remaining iterators are summed:
+//   - long sums: a workgroup takes one combination and one slice of the remaining iterators flattened row-major;
+//     threads keep private fp32 sums over runs along the innermost one, the workgroup adds them in a fixed tree, and
+//     a second kernel adds the slices in order;
+//   - short sums: a thread per combination walks the remaining iterators itself.
+// No atomics either way, so the result does not depend on scheduling.
+constexpr int kMaxIter = 2 * kMaxAxes;
+struct ViewGradParams {
   ViewStream vs;
-  int32_t tab_off[2 * kMaxAxes];
+  int32_t tab_off[kMaxIter];
   int32_t tab_total, n_free, free_off;
   int32_t n_carry, n_rest;
-  int32_t carry_axis[kMaxAxes], rest_axis[kMaxAxes];   // outermost first
-  uint32_t rest_magic[kMaxAxes];                       // division_magic(size) of the remaining axes
-  int32_t ostride[kMaxAxes];                           // element strides of the output axes
-  int32_t n_w, n_splits;                               // carrying combinations (= elements of W); slices
-  int32_t run;                                         // adjacent indices of the innermost remaining axis per thread and step: 4 or 1
-  int64_t total_rest, chunk;                           // runs over the remaining axes; per slice
+  int32_t carry_axis[kMaxIter], rest_axis[kMaxIter];   // outermost first
+  uint32_t rest_magic[kMaxIter];                       // division_magic(size) of the remaining iterators
+  int32_t ostride[kMaxIter];                           // element stride in G (0 for a Reduce iterator)
+  int32_t n_combo, n_splits;                           // carrying combinations; slices of a long sum (0: short sums)
+  int32_t run;                                         // adjacent indices of the innermost remaining iterator per thread and step: 4 or 1
+  int32_t zero_first;                                  // some target elements are picked by no combination
+  int64_t total_rest, chunk;                           // runs over the remaining iterators (long sums) or their points (short); per slice
+  int64_t target_elems;
 };
 
-template <bool IBF>
-__global__ __launch_bounds__(kThreads) void view_weight_grad(const ViewDwParams p, const void* __restrict__ G,
-                                                             const void* __restrict__ X, float* __restrict__ partial,
-                                                             int* __restrict__ w_index) {
+struct GradBase { int g, o, t; };
+
+// Offsets of carrying combination `combo`: in G, in the other operand, in the target (with the constant entries of
+// the remaining iterators' target tables).
+template <bool TO_X>
+__device__ __forceinline__ GradBase grad_base(const ViewGradParams& p, const int* tab, int combo) {
+  const int* tabT = TO_X ? tab : tab + p.tab_total;
+  const int* tabO = TO_X ? tab + p.tab_total : tab;
+  GradBase b{0, 0, 0};
+  int rest = combo;
+  for (int j = p.n_carry - 1; j >= 0; --j) {
+    const int axis = p.carry_axis[j], sz = p.vs.size[axis], d = rest % sz;
+    rest /= sz;
+    b.g += d * p.ostride[axis];
+    b.o += tabO[p.tab_off[axis] + d];
+    b.t += tabT[p.tab_off[axis] + d];
+  }
+  for (int j = 0; j < p.n_rest; ++j) b.t += tabT[p.tab_off[p.rest_axis[j]]];
+  return b;
+}
+
+template <bool OBF>
+__device__ __forceinline__ void store_target(void* base, int64_t off, float v) {
+  if constexpr (OBF) static_cast<uint16_t*>(base)[off] = (uint16_t)pack_bf16x2(v, 0.f);
+  else static_cast<float*>(base)[off] = v;
+}
+
+template <bool IBF, bool TO_X>
+__global__ __launch_bounds__(kThreads) void view_grad_long(const ViewGradParams p, const void* __restrict__ G,
+                                                           const void* __restrict__ other, float* __restrict__ partial,
+                                                           int* __restrict__ t_index) {
   extern __shared__ __align__(16) int tab[];
   __shared__ float wave_sum[kThreads / 64];
   const ViewStream& vs = p.vs;
   build_tables(vs, p.tab_off, p.free_off, p.n_free, p.tab_total, tab);
-  const int wid = blockIdx.x / p.n_splits, slice = blockIdx.x - wid * p.n_splits;
-  int g0 = 0, x0 = 0, w0 = tab[p.tab_total + p.free_off];      // (the sum points' W entries are all the same)
-  {
-    int rest = wid;
-    for (int j = p.n_carry - 1; j >= 0; --j) {
-      const int axis = p.carry_axis[j], sz = vs.size[axis], d = rest % sz;
-      rest /= sz;
-      g0 += d * p.ostride[axis];
-      x0 += tab[p.tab_off[axis] + d];
-      w0 += tab[p.tab_total + p.tab_off[axis] + d];
-    }
-    for (int j = 0; j < p.n_rest; ++j) w0 += tab[p.tab_total + p.tab_off[p.rest_axis[j]]];   // constant tables
-  }
-  const int* fx = tab + p.free_off;
+  const int* tabO = TO_X ? tab + p.tab_total : tab;
+  const int combo = blockIdx.x / p.n_splits, slice = blockIdx.x - combo * p.n_splits;
+  const GradBase b0 = grad_base<TO_X>(p, tab, combo);
   const int64_t begin = slice * p.chunk, end = min(p.total_rest, begin + p.chunk);
   float acc = 0.f;
   auto walk = [&](auto run_c) {
     constexpr int R = decltype(run_c)::value;
     const int inner = p.rest_axis[p.n_rest - 1];
     const uint32_t inner_runs = (uint32_t)vs.size[inner] / R;
-    const int* tx_inner = tab + p.tab_off[inner];
+    const int* to_inner = tabO + p.tab_off[inner];
     for (int64_t idx = begin + threadIdx.x; idx < end; idx += kThreads) {
       uint32_t rest = (uint32_t)idx;
       const uint32_t q0 = div_magic(rest, inner_runs, p.rest_magic[p.n_rest - 1]);
       const int d0 = (int)(rest - q0 * inner_runs) * R;
       rest = q0;
-      int go = g0 + d0 * p.ostride[inner], xo = x0;
+      int go = b0.g + d0 * p.ostride[inner], oo = b0.o;
       for (int j = p.n_rest - 2; j >= 0; --j) {
         const int axis = p.rest_axis[j];
         const uint32_t sz = (uint32_t)vs.size[axis];
@@ -359,22 +385,16 @@ __global__ __launch_bounds__(kThreads) void view_weight_grad(const ViewDwParams 
         const int d = (int)(rest - q * sz);
         rest = q;
         go += d * p.ostride[axis];
-        xo += tab[p.tab_off[axis] + d];
+        oo += tabO[p.tab_off[axis] + d];
       }
-      float g[R];
+      float g[R], x[R];
 #pragma unroll
-      for (int k = 0; k < R; ++k) g[k] = load_one<IBF>(G, go + k * p.ostride[inner]);
-      if (p.n_free == 1) {
-        float x[R];
-#pragma unroll
-        for (int k = 0; k < R; ++k) x[k] = load_one<IBF>(X, xo + tx_inner[d0 + k] + fx[0]);
-#pragma unroll
-        for (int k = 0; k < R; ++k) acc = fmaf(g[k], x[k], acc);
-      } else {
-#pragma unroll
-        for (int k = 0; k < R; ++k)
-          for (int q = 0; q < p.n_free; ++q) acc = fmaf(g[k], load_one<IBF>(X, xo + tx_inner[d0 + k] + fx[q]), acc);
+      for (int k = 0; k < R; ++k) {
+        g[k] = load_one<IBF>(G, go + k * p.ostride[inner]);
+        x[k] = load_one<IBF>(other, oo + to_inner[d0 + k]);
       }
+#pragma unroll
+      for (int k = 0; k < R; ++k) acc = fmaf(g[k], x[k], acc);
     }
   };
   if (p.run == 4) walk(std::integral_constant<int, 4>{});
@@ -387,28 +407,67 @@ __global__ __launch_bounds__(kThreads) void view_weight_grad(const ViewDwParams 
     float t = wave_sum[0];
     for (int w = 1; w < kThreads / 64; ++w) t += wave_sum[w];
     partial[blockIdx.x] = t;
-    if (slice == 0) w_index[wid] = w0;
+    if (slice == 0) t_index[combo] = b0.t;
   }
 }
 
-__global__ __launch_bounds__(kThreads) void view_weight_grad_sum(const float* __restrict__ partial,
-                                                                 const int* __restrict__ w_index, float* __restrict__ dW,
-                                                                 int n_w, int n_splits) {
-  const int wid = blockIdx.x * kThreads + threadIdx.x;
-  if (wid >= n_w) return;
-  float t = partial[(int64_t)wid * n_splits];
-  for (int s = 1; s < n_splits; ++s) t += partial[(int64_t)wid * n_splits + s];
-  dW[w_index[wid]] = t;
+template <bool OBF>
+__global__ __launch_bounds__(kThreads) void view_grad_sum(const float* __restrict__ partial, const int* __restrict__ t_index,
+                                                          void* __restrict__ target, int n_combo, int n_splits) {
+  const int combo = blockIdx.x * kThreads + threadIdx.x;
+  if (combo >= n_combo) return;
+  float t = partial[(int64_t)combo * n_splits];
+  for (int s = 1; s < n_splits; ++s) t += partial[(int64_t)combo * n_splits + s];
+  store_target<OBF>(target, t_index[combo], t);
 }
 
-bool fill_dw(const syno_plan* plan, ViewDwParams& p) {
-  p = ViewDwParams{};
+template <bool IBF, bool OBF, bool TO_X>
+__global__ __launch_bounds__(kThreads) void view_grad_short(const ViewGradParams p, const void* __restrict__ G,
+                                                            const void* __restrict__ other, void* __restrict__ target) {
+  extern __shared__ __align__(16) int tab[];
+  const ViewStream& vs = p.vs;
+  build_tables(vs, p.tab_off, p.free_off, p.n_free, p.tab_total, tab);
+  const int* tabO = TO_X ? tab + p.tab_total : tab;
+  const int64_t combo = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (combo >= p.n_combo) return;
+  const GradBase b0 = grad_base<TO_X>(p, tab, (int)combo);
+  float acc = 0.f;
+  for (uint32_t idx = 0; idx < (uint32_t)p.total_rest; ++idx) {
+    uint32_t rest = idx;
+    int go = b0.g, oo = b0.o;
+    for (int j = p.n_rest - 1; j >= 0; --j) {
+      const int axis = p.rest_axis[j];
+      const uint32_t sz = (uint32_t)vs.size[axis];
+      const uint32_t q = div_magic(rest, sz, p.rest_magic[j]);
+      const int d = (int)(rest - q * sz);
+      rest = q;
+      go += d * p.ostride[axis];
+      oo += tabO[p.tab_off[axis] + d];
+    }
+    acc = fmaf(load_one<IBF>(G, go), load_one<IBF>(other, oo), acc);
+  }
+  store_target<OBF>(target, b0.t, acc);
+}
+
+// zeroes `bytes` bytes (a multiple of 2; dst is 4-byte aligned)
+__global__ __launch_bounds__(kThreads) void view_grad_zero(uint32_t* __restrict__ dst, int64_t bytes) {
+  const int64_t words = bytes >> 2;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < words; i += (int64_t)gridDim.x * kThreads) dst[i] = 0u;
+  if ((bytes & 2) && blockIdx.x == 0 && threadIdx.x == 0) reinterpret_cast<uint16_t*>(dst)[bytes / 2 - 1] = 0;
+}
+
+constexpr int64_t kLongSum = 1024;       // remaining points from which a workgroup, not a thread, takes a combination
+
+bool fill_grad(const syno_plan* plan, bool to_x, ViewGradParams& p) {
+  p = ViewGradParams{};
   p.vs = plan->view;
   const ViewStream& vs = p.vs;
-  if (plan->out_elems >= (int64_t(1) << 31) || plan->x_elems >= (int64_t(1) << 31) || plan->w_elems > (1 << 20)) return false;
+  p.target_elems = to_x ? plan->x_elems : plan->w_elems;
+  if (plan->out_elems >= (int64_t(1) << 31) || plan->x_elems >= (int64_t(1) << 31) || plan->w_elems >= (int64_t(1) << 31)) return false;
+  const int n_iter = vs.n_axes + vs.n_red;
   int total = 0;
   p.n_free = 1;
-  for (int i = 0; i < vs.n_axes + vs.n_red; ++i) {
+  for (int i = 0; i < n_iter; ++i) {
     p.tab_off[i] = total;
     total += vs.size[i];
     if (i >= vs.n_axes) p.n_free *= vs.size[i];
@@ -417,66 +476,65 @@ bool fill_dw(const syno_plan* plan, ViewDwParams& p) {
   total += p.n_free;
   p.tab_total = total;
   if (total <= 0 || (size_t)total * 8 > 48 * 1024) return false;
-  // carrying axes: those whose W table is not constant; the sum points must not move the weight
-  int64_t n_w = 1, stride = 1;
-  p.total_rest = 1;
+  int64_t stride = 1;
   for (int i = vs.n_axes - 1; i >= 0; --i) { p.ostride[i] = (int32_t)stride; stride *= vs.size[i]; }
-  for (int i = 0; i < vs.n_axes + vs.n_red; ++i) {
-    int first[2], off[2];
-    table_entry(vs, i, 0, first);
+  // carrying iterators: those whose target table is not constant
+  const int comp = to_x ? 0 : 1;
+  int64_t n_combo = 1;
+  p.total_rest = 1;
+  int base = 0;
+  std::vector<std::vector<int>> ttab;
+  for (int i = 0; i < n_iter; ++i) {
+    std::vector<int> col((size_t)vs.size[i]);
     bool varies = false;
-    for (int o = 1; o < vs.size[i] && !varies; ++o) {
+    for (int o = 0; o < vs.size[i]; ++o) {
+      int off[2];
       table_entry(vs, i, o, off);
-      varies = off[1] != first[1];
+      col[(size_t)o] = off[comp];
+      varies |= off[comp] != col[0];
     }
-    if (i >= vs.n_axes) {
-      if (varies) return false;
-    } else if (varies) {
+    if (varies) {
       p.carry_axis[p.n_carry++] = i;
-      n_w *= vs.size[i];
+      n_combo *= vs.size[i];
+      ttab.push_back(std::move(col));
     } else {
+      base += col[0];
       p.rest_magic[p.n_rest] = division_magic(vs.size[i]);
       p.rest_axis[p.n_rest++] = i;
       p.total_rest *= vs.size[i];
     }
+    if (n_combo > (int64_t(1) << 22) || p.total_rest >= (int64_t(1) << 31)) return false;   // (the check below enumerates them)
   }
-  if (n_w != plan->w_elems || p.total_rest < 64) return false;
-  p.n_w = (int32_t)n_w;
-  // every combination its own weight element
+  if (n_combo > p.target_elems) return false;
+  p.n_combo = (int32_t)n_combo;
+  // every combination its own target element
   {
-    std::vector<char> seen((size_t)n_w, 0);
-    std::vector<std::vector<int>> wtab(p.n_carry);
-    int base = 0, off[2];
-    for (int i = 0; i < vs.n_axes + vs.n_red; ++i) {
-      bool carry = false;
-      for (int j = 0; j < p.n_carry; ++j) carry |= p.carry_axis[j] == i;
-      if (!carry) { table_entry(vs, i, 0, off); base += off[1]; }
-    }
-    for (int j = 0; j < p.n_carry; ++j)
-      for (int o = 0; o < vs.size[p.carry_axis[j]]; ++o) { table_entry(vs, p.carry_axis[j], o, off); wtab[j].push_back(off[1]); }
-    for (int64_t wid = 0; wid < n_w; ++wid) {
-      int64_t rest = wid, w = base;
-      for (int j = p.n_carry - 1; j >= 0; --j) { const int sz = vs.size[p.carry_axis[j]]; w += wtab[j][rest % sz]; rest /= sz; }
-      if (w < 0 || w >= n_w || seen[(size_t)w]) return false;
-      seen[(size_t)w] = 1;
+    std::vector<char> seen((size_t)p.target_elems, 0);
+    for (int64_t combo = 0; combo < n_combo; ++combo) {
+      int64_t rest = combo, t = base;
+      for (int j = p.n_carry - 1; j >= 0; --j) { const int sz = vs.size[p.carry_axis[j]]; t += ttab[(size_t)j][(size_t)(rest % sz)]; rest /= sz; }
+      if (t < 0 || t >= p.target_elems || seen[(size_t)t]) return false;
+      seen[(size_t)t] = 1;
     }
   }
-  // a thread takes 4 adjacent indices of the innermost remaining axis per step where that divides it
-  if (p.n_rest == 0) {      // (every axis selects the weight: ruled out above by the size test, kept for safety)
-    return false;
+  p.zero_first = n_combo < p.target_elems ? 1 : 0;
+  p.run = 1;
+  if (p.total_rest >= kLongSum) {
+    // a thread takes 4 adjacent indices of the innermost remaining iterator per step where that divides it
+    const int inner = p.rest_axis[p.n_rest - 1];
+    p.run = vs.size[inner] % 4 == 0 ? 4 : 1;
+    p.rest_magic[p.n_rest - 1] = division_magic(vs.size[inner] / p.run);
+    p.total_rest /= p.run;
+    // about 2048 workgroups, each with at least a few thousand products
+    const int64_t splits = std::max<int64_t>(1, std::min<int64_t>(2048 / n_combo, p.total_rest * p.run / 4096));
+    p.chunk = (p.total_rest + splits - 1) / splits;
+    p.n_splits = (int32_t)((p.total_rest + p.chunk - 1) / p.chunk);
+    if ((int64_t)p.n_combo * p.n_splits >= (int64_t(1) << 31)) return false;
   }
-  const int inner = p.rest_axis[p.n_rest - 1];
-  p.run = vs.size[inner] % 4 == 0 ? 4 : 1;
-  p.rest_magic[p.n_rest - 1] = division_magic(vs.size[inner] / p.run);
-  p.total_rest /= p.run;
-  // about 2048 workgroups, each with at least a few thousand products
-  int64_t splits = std::max<int64_t>(1, std::min<int64_t>(2048 / n_w, p.total_rest * p.run / 4096));
-  p.chunk = (p.total_rest + splits - 1) / splits;
-  p.n_splits = (int32_t)((p.total_rest + p.chunk - 1) / p.chunk);
-  return (int64_t)p.n_w * p.n_splits < (int64_t(1) << 31);
+  return true;
 }
 
-size_t dw_partial_bytes(const ViewDwParams& p) { return (((size_t)p.n_w * p.n_splits * 4) + 255) & ~(size_t)255; }
+size_t grad_partial_bytes(const ViewGradParams& p) { return (((size_t)p.n_combo * p.n_splits * 4) + 255) & ~(size_t)255; }
 
 template <bool IBF, bool OBF, bool SCATTER>
 void launch_typed(const ViewParams& p, int V, size_t lds, const void* X, const void* W, void* out, hipStream_t s) {
@@ -529,24 +587,24 @@ bool fill(const syno_plan* plan, ViewParams& p) {
 // Forward of every separable gather; backward-data where the view is one-to-one (a scatter of the same tables).
 bool view_supports(const syno_plan* plan, int which) {
   if (!plan->pure_view) return false;
-  if (which == SYNO_BWD_WEIGHT) {
-    ViewDwParams d;
-    return fill_dw(plan, d);
-  }
-  if (which == SYNO_BWD_DATA && !plan->view.one_to_one) return false;
   if (plan->in_dtype == SYNO_F32 && plan->out_dtype != SYNO_F32) return false;
+  if (which == SYNO_BWD_WEIGHT || (which == SYNO_BWD_DATA && !plan->view.one_to_one)) {
+    ViewGradParams d;
+    return fill_grad(plan, which == SYNO_BWD_DATA, d);
+  }
   ViewParams p;
   return fill(plan, p);
 }
 
 void view_configure(syno_plan* plan, int which) {
   Launch& L = plan->launch[which];
-  if (which == SYNO_BWD_WEIGHT) {
-    ViewDwParams d;
-    static_assert(sizeof(ViewDwParams) <= sizeof(L.params), "parameter record does not fit");
-    L.params_ready = fill_dw(plan, d);
+  if (which == SYNO_BWD_WEIGHT || (which == SYNO_BWD_DATA && !plan->view.one_to_one)) {
+    ViewGradParams d;
+    static_assert(sizeof(ViewGradParams) <= sizeof(L.params), "parameter record does not fit");
+    L.params_ready = fill_grad(plan, which == SYNO_BWD_DATA, d);
     memcpy(L.params, &d, sizeof d);
-    L.workspace = dw_partial_bytes(d) + (size_t)d.n_w * 4;     // slice sums, then the weight index of every combination
+    // long sums: slice sums, then the target index of every combination
+    L.workspace = d.n_splits > 0 ? grad_partial_bytes(d) + (size_t)d.n_combo * 4 : 0;
     return;
   }
   ViewParams p;
@@ -556,24 +614,56 @@ void view_configure(syno_plan* plan, int which) {
   L.workspace = 0;
 }
 
+std::string view_describe(const syno_plan* plan, int which) {
+  if (!plan->launch[which].params_ready) return "unconfigured";
+  if (which == SYNO_FWD) return "stream";
+  if (which == SYNO_BWD_DATA && plan->view.one_to_one) return "scatter";
+  ViewGradParams d;
+  memcpy(&d, plan->launch[which].params, sizeof d);
+  std::string r = "gather targets=" + std::to_string(d.n_combo) + " products/target=" + std::to_string(d.total_rest * d.run);
+  r += d.n_splits > 0 ? " slices=" + std::to_string(d.n_splits) : std::string(" thread-per-target");
+  if (d.zero_first) r += " zero-filled-first";
+  return r;
+}
+
 // forward: A = X, B = W, out = result; backward-data: A = G, B = W, out = dX; backward-weight: A = G, B = X, out = dW
 syno_status launch_view(const syno_plan* plan, int which, const void* A, const void* B, void* out, void* ws,
                         hipStream_t stream) {
   if (!plan->launch[which].params_ready) return SYNO_ERR_UNSUPPORTED;
-  if (which == SYNO_BWD_WEIGHT) {
-    if (!ws) return SYNO_ERR_WORKSPACE;
-    ViewDwParams d;
+  if (which == SYNO_BWD_WEIGHT || (which == SYNO_BWD_DATA && !plan->view.one_to_one)) {
+    ViewGradParams d;
     memcpy(&d, plan->launch[which].params, sizeof d);
-    float* partial = static_cast<float*>(ws);
-    int* w_index = reinterpret_cast<int*>(static_cast<char*>(ws) + dw_partial_bytes(d));
-    const dim3 grid((unsigned)(d.n_w * d.n_splits));
+    const bool to_x = which == SYNO_BWD_DATA, ibf = plan->in_dtype == SYNO_BF16;
+    const bool obf = to_x && plan->out_dtype == SYNO_BF16;          // (dW is always fp32)
     const size_t lds = (size_t)d.tab_total * 8;
-    if (plan->in_dtype == SYNO_BF16)
-      hipLaunchKernelGGL(view_weight_grad<true>, grid, dim3(kThreads), lds, stream, d, A, B, partial, w_index);
-    else
-      hipLaunchKernelGGL(view_weight_grad<false>, grid, dim3(kThreads), lds, stream, d, A, B, partial, w_index);
-    hipLaunchKernelGGL(view_weight_grad_sum, dim3((unsigned)((d.n_w + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream,
-                       partial, w_index, static_cast<float*>(out), d.n_w, d.n_splits);
+    if (d.zero_first) {
+      const int64_t bytes = d.target_elems * (obf ? 2 : 4), words = (bytes + 3) / 4;
+      hipLaunchKernelGGL(view_grad_zero, dim3((unsigned)std::min<int64_t>((words + kThreads - 1) / kThreads, 2048)), dim3(kThreads),
+                         0, stream, static_cast<uint32_t*>(out), bytes);
+    }
+    auto pick = [&](auto long_f32x, auto long_bfx, auto long_f32w, auto long_bfw) {
+      return to_x ? (ibf ? long_bfx : long_f32x) : (ibf ? long_bfw : long_f32w);
+    };
+    if (d.n_splits > 0) {
+      if (!ws) return SYNO_ERR_WORKSPACE;
+      float* partial = static_cast<float*>(ws);
+      int* t_index = reinterpret_cast<int*>(static_cast<char*>(ws) + grad_partial_bytes(d));
+      const dim3 grid((unsigned)(d.n_combo * d.n_splits));
+      auto k = pick(view_grad_long<false, true>, view_grad_long<true, true>, view_grad_long<false, false>, view_grad_long<true, false>);
+      hipLaunchKernelGGL(k, grid, dim3(kThreads), lds, stream, d, A, B, partial, t_index);
+      const dim3 sgrid((unsigned)((d.n_combo + kThreads - 1) / kThreads));
+      if (obf) hipLaunchKernelGGL(view_grad_sum<true>, sgrid, dim3(kThreads), 0, stream, partial, t_index, out, d.n_combo, d.n_splits);
+      else hipLaunchKernelGGL(view_grad_sum<false>, sgrid, dim3(kThreads), 0, stream, partial, t_index, out, d.n_combo, d.n_splits);
+    } else {
+      const dim3 grid((unsigned)((d.n_combo + kThreads - 1) / kThreads));
+      if (obf) {
+        hipLaunchKernelGGL((view_grad_short<true, true, true>), grid, dim3(kThreads), lds, stream, d, A, B, out);
+      } else {
+        auto k = pick(view_grad_short<false, false, true>, view_grad_short<true, false, true>, view_grad_short<false, false, false>,
+                      view_grad_short<true, false, false>);
+        hipLaunchKernelGGL(k, grid, dim3(kThreads), lds, stream, d, A, B, out);
+      }
+    }
     return hipGetLastError() == hipSuccess ? SYNO_OK : SYNO_ERR_HIP;
   }
   ViewParams p;

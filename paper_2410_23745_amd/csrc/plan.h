@@ -199,6 +199,7 @@ void bandwidth_configure(syno_plan* p, int which);   // fills launch[which].para
 // kernels_view.hip: separable gathers; view_configure fills launch[which].params
 bool view_supports(const syno_plan* p, int which);
 void view_configure(syno_plan* p, int which);
+std::string view_describe(const syno_plan* p, int which);
 // kernels_window.hip: the unreduced-window member of the bandwidth family
 bool window_supports(const syno_plan* p, int which);
 void window_configure(syno_plan* p, int which);      // fills launch[which].params and .workspace

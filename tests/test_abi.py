@@ -141,7 +141,7 @@ def test_out_of_range_points_yield_minus_one(syno):
 def test_kernel_choice(syno):
     names = lambda d: [syno.Plan(d).kernel(i) for i in range(3)]
     assert all(n == "generic_index_program" for n in names(wl.matmul(3, 3, 70)))     # 3 columns: too narrow to fold
-    assert names(wl.matmul(3, 3, 5)) == ["bandwidth_view", "generic_index_program", "generic_index_program"]   # 5 sum points
+    assert names(wl.matmul(3, 3, 5)) == ["bandwidth_view"] * 3   # 5 sum points; the gradients gather through the same tables
     assert all(n == "generic_index_program" for n in names(pixel_unshuffle_conv()))
     # the benchmarked workloads run on the tuned families, not on the index-program kernels
     for stage in range(4):
@@ -269,25 +269,28 @@ def test_materialised_reduction_pass_cuts_where_it_saves_work(syno):
 def test_reduce_free_graphs_go_to_the_view_kernel_forwards(syno):
     for d in (wl.shifted_scale(2, 8, 6, 6), wl.pixel_unshuffle(2, 4, 3, 4, 2)):
         p = syno.Plan(d)
-        # one-to-one views: backward-data is the scatter of the same tables; backward-weight is one dot product per
-        # weight element over the output axes that do not select it (slice sums and weight indices in the workspace)
+        # one-to-one views: backward-data is the scatter of the same tables; backward-weight is one sum per weight
+        # element over the output axes that do not select it (72 and 192 products here: a thread per element)
         assert p.kernel(0) == p.kernel(1) == p.kernel(2) == "bandwidth_view"
-        assert p.workspace_bytes(0) == p.workspace_bytes(1) == 0 and p.workspace_bytes(2) >= 4 * (1 + int(np.prod(p.w_shape)))
-    # a weight gradient with fewer than 64 products per weight element is left to the index-program kernel
-    assert syno.Plan(wl.shifted_scale(1, 8, 3, 6)).kernel(2) == "generic_index_program"
-    # not one-to-one: an Expand repeats X, a Stride leaves elements of X unread (their gradient is zero)
+        assert p.workspace_bytes(0) == p.workspace_bytes(1) == p.workspace_bytes(2) == 0
+    # long sums are sliced over workgroups: slice sums and one target index per weight element in the workspace
+    p = syno.Plan(wl.shifted_scale(4, 8, 16, 16))
+    assert p.kernel(2) == "bandwidth_view" and p.workspace_bytes(2) >= 4 * (8 + 8)
+    # not one-to-one: an Expand repeats X (its gradient sums over the repeats), a Stride leaves elements of X unread
+    # (their gradient is zero): gathers through the same tables, zero-filled first where there are gaps
     b = Builder([("i", 6), ("j", 4)])
     b.expand(1)
     p = syno.Plan(b.finish([0], []))
-    assert p.kernel(0) == "bandwidth_view" and p.kernel(1) == "generic_index_program"
+    assert p.kernel(0) == p.kernel(1) == "bandwidth_view"
     b = Builder([("i", 6)])
     p = syno.Plan(b.finish([b.stride(0, 2)], []))
-    assert p.kernel(0) == "bandwidth_view" and p.kernel(1) == "generic_index_program"
+    assert p.kernel(0) == p.kernel(1) == "bandwidth_view"
     # an Expand and a Stride whose sizes cancel: as many X elements as outputs, still not one-to-one
     b = Builder([("i", 6), ("j", 2)])
     b.expand(1)
     p = syno.Plan(b.finish([b.stride(0, 2)], []))
-    assert p.x_shape == (12,) and p.kernel(1) == "generic_index_program"
+    assert p.x_shape == (12,) and p.kernel(1) == "bandwidth_view" and "gather targets=6 products/target=2" in p.describe(1)
+    assert "zero-filled-first" in p.describe(1) and syno.Plan(wl.shifted_scale(2, 8, 6, 6)).describe(1).endswith("scatter")
     # a Shared iterator whose two copies both reach X (a diagonal: X[i,i], or folded into one axis, X[3i+i]) next to
     # an iterator that only reaches the weight would also have as many X elements as outputs; such graphs are
     # refused as a whole, because backward-data would have to fix one coordinate from two places

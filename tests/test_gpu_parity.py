@@ -600,6 +600,21 @@ def view_cases():
         b.expand(1)
         return b.finish([0, b.stride(kx, 3)], [kw], i, o)
 
+    def expand_long(i, o):
+        # out[a,r,s] = X[a] * Wt[a]: 96 * 128 copies per element, so both gradients are long sums sliced over workgroups
+        b = Builder([("a", 37), ("r", 96), ("s", 128)])
+        ax, aw = b.share(0)
+        b.expand(1)
+        b.expand(2)
+        return b.finish([ax], [aw], i, o)
+
+    def stride_gaps_odd(i, o):
+        # out[a,k] = X[3*a, k] * Wt[k]: two of three rows of X are never read (zero gradient); X has 105 elements, an
+        # odd number, so a bf16 dX ends in half a word
+        b = Builder([("a", 7), ("k", 5)])
+        kx, kw = b.share(1)
+        return b.finish([b.stride(0, 3), kx], [kw], i, o)
+
     def pixel_shuffle(i, o):
         # Table 2's PixelShuffle: out[n,c,H,W] = X[n, c, H%r, W%r, H/r, W/r] * Wt[c]
         b = Builder([("n", 2), ("c", 3), ("H", 6), ("W", 10)])
@@ -629,6 +644,7 @@ def view_cases():
         "pixel_unshuffle": lambda i, o: wl.pixel_unshuffle(2, 3, 5, 8, 2, i, o),
         "pixel_unshuffle_r3": lambda i, o: wl.pixel_unshuffle(1, 2, 4, 5, 3, i, o),
         "expand_stride": expand_stride, "pixel_shuffle": pixel_shuffle, "shift_of_digit": shift_of_digit,
+        "expand_long": expand_long, "stride_gaps_odd": stride_gaps_odd,
     }
 
 
@@ -647,9 +663,10 @@ def test_pure_views_small(syno, oracle, name, dt):
     # one-to-one views scatter their backward-data through the same tables; the others sum or leave gaps
     one_to_one = name in ("shift_scale_v4", "shift_scale_v1", "pixel_unshuffle", "pixel_unshuffle_r3", "pixel_shuffle",
                           "shift_of_digit")
-    assert names[1] == ("bandwidth_view" if one_to_one else "generic_index_program")
-    # the weight gradient is a dot product per weight element wherever output axes select the weight element one-to-one
-    assert names[2] == ("generic_index_program" if name in ("small_matmul", "expand_stride") else "bandwidth_view")
+    # the others (an Expand sums, a Stride leaves gaps, sum points) and every weight gradient gather through the tables
+    assert names[1] == names[2] == "bandwidth_view"
+    plan = syno.Plan(d)
+    assert plan.describe(1).endswith("scatter") == one_to_one and "gather" in plan.describe(2)
     if one_to_one:   # every element of dX is written: nothing of a pre-filled buffer survives
         plan = syno.Plan(d)
         G, W = to_dev(w.G, w.G_bits), to_dev(w.W, w.W_bits)
@@ -701,9 +718,11 @@ def test_contraction_with_split_reduction(syno, oracle, bf16, splits):
 @pytest.mark.parametrize("M,K,N", [(130, 72, 112), (40, 7 * 9, 200)])
 def test_matmul_small_bf16_result(syno, oracle, M, K, N):
     """With a bf16 result type the forward product and dX (the product G * W^T on a transposed copy of W) stay on
-    the contraction kernel; dW, which is fp32 inside, is left to the index-program kernel."""
+    the contraction kernel; dW, which is fp32 inside, is left to the bandwidth-bound kernels."""
     names = run_all(syno, oracle, wl.make_matmul(M, K, N, seed=43, bf16=True, with_grad=True, out_bf16=True), 0)
-    assert names == ["mfma_contraction_transposed", "mfma_contraction_transposed", "generic_index_program"]
+    # (63 sum points still count as a few: that product's dW gathers through the view tables, a thread per element)
+    assert names == ["mfma_contraction_transposed", "mfma_contraction_transposed",
+                     "bandwidth_view" if K <= 64 else "generic_index_program"]
 
 
 @pytest.mark.parametrize("bf16", [False, True])

@@ -529,10 +529,17 @@ bool recognise_conv(const Graph& g, ConvLike& cv) {
   std::vector<Expr> e;
   std::vector<Check> checks;
   if (!analyse(g, roots, e, checks)) return false;
-  if (g.in_coords.size() != 4) return false;
+  // X is [n, channels, rows, columns]; a tensor without a row axis ([n, channels, columns]: a window over one long
+  // axis) is the same with one row
+  if (g.in_coords.size() != 4 && g.in_coords.size() != 3) return false;
+  const Expr no_rows{};               // the constant 0
   const Expr* ax[4];
-  for (int i = 0; i < 4; ++i) {
-    ax[i] = &e[g.S(g.in_coords[i])];
+  int64_t ax_size[4];
+  for (int i = 0, k = 0; i < 4; ++i) {
+    if (i == 2 && g.in_coords.size() == 3) { ax[i] = &no_rows; ax_size[i] = 1; continue; }
+    ax[i] = &e[g.S(g.in_coords[k])];
+    ax_size[i] = g.D(g.in_coords[k]);
+    ++k;
     if (ax[i]->complex) return false;
   }
   // roles
@@ -566,7 +573,7 @@ bool recognise_conv(const Graph& g, ConvLike& cv) {
   // axes 2, 3: s*h + kh - pad, zero outside; or (h + shift + coef*g) mod size
   for (int a = 2; a < 4; ++a) {
     const Expr& x = *ax[a];
-    const int64_t size = g.D(g.in_coords[a]);
+    const int64_t size = ax_size[a];
     int32_t out_sz = 1, k_sz = 1, stride = 1, shift_g = 0;
     for (auto& t : x.coef) {
       const int r = t.first;
@@ -601,7 +608,7 @@ bool recognise_conv(const Graph& g, ConvLike& cv) {
   for (const Check& c : checks) {
     bool ok = false;
     for (int a = 2; a < 4; ++a)
-      if (!ax[a]->wrap && same_affine(c.e, *ax[a]) && c.bound == g.D(g.in_coords[a])) ok = true;
+      if (!ax[a]->wrap && same_affine(c.e, *ax[a]) && c.bound == ax_size[a]) ok = true;
     if (!ok) return false;
   }
   // weight axes: one bare iterator each
@@ -1098,8 +1105,8 @@ syno_status materialise(const syno_desc* desc, std::vector<OwnedDesc>& stages, s
 namespace {
 // Adjacent axes of X that are both plain Reduce iterators Shared with the weight, whose weight copies are adjacent
 // axes of W in the same order, are one iterator of the product size as far as memory goes (row-major layouts on
-// both sides).  Returns the descriptor with every such pair fused (and its ids renumbered), or false when there is
-// none.  The tensors' bytes are the same, so a lowered form recognised on the fused graph serves the original.
+// both sides).  So are the two halves of a Merge that lie side by side in X.  Returns the descriptor with every such
+// pair fused (and its ids renumbered), or false when there is none.  The tensors' bytes are the same, so a lowered form recognised on the fused graph serves the original.
 bool fuse_reduced_axes(const syno_desc& d, OwnedDesc& out) {
   std::vector<syno_prim> P(d.prims, d.prims + d.n_prim);
   std::vector<int32_t> xin(d.input_coords, d.input_coords + d.n_in), win(d.weight_coords, d.weight_coords + d.n_w);
@@ -1121,6 +1128,21 @@ bool fuse_reduced_axes(const syno_desc& d, OwnedDesc& out) {
       b = P[sh].out[0] == a ? P[sh].out[1] : P[sh].out[0];
       return std::find(win.begin(), win.end(), b) != win.end();
     };
+    // Two adjacent axes of X that are the quotient and the remainder of one Merge are, in memory, the axis the Merge
+    // divided (offset q*B + r): X takes that coordinate directly and the Merge goes.  This is how a window over a
+    // flattened pair of axes (an Unfold below a Merge) becomes a window over one long axis.
+    for (size_t i = 0; i + 1 < xin.size() && !again; ++i) {
+      const int mk = producer(xin[i]);
+      if (mk < 0 || P[mk].kind != SYNO_MERGE || P[mk].out[0] != xin[i] || P[mk].out[1] != xin[i + 1]) continue;
+      bool read_elsewhere = false;
+      for (const syno_prim& q : P)
+        if (q.kind == SYNO_SHIFT && q.shift_by >= 0) read_elsewhere |= q.shift_by == xin[i] || q.shift_by == xin[i + 1];
+      if (read_elsewhere) continue;
+      xin[i] = P[mk].in[0];
+      xin.erase(xin.begin() + i + 1);
+      P.erase(P.begin() + mk);
+      again = any = true;
+    }
     for (size_t i = 0; i + 1 < xin.size() && !again; ++i) {
       int s1, r1, b1, s2, r2, b2;
       if (!shared_reduce(xin[i], s1, r1, b1) || !shared_reduce(xin[i + 1], s2, r2, b2)) continue;
@@ -1205,7 +1227,8 @@ syno_status build_plan(const syno_desc* desc, syno_plan* plan, std::string* why)
       return unsupported("more than 2^31-1 sum points per element in one of the passes");
 
   plan->conv_like = recognise_conv(g, plan->conv);
-  if (!plan->conv_like) {      // several reduced channel-like axes side by side (a stage cut off by the pass): one axis
+  if (!plan->conv_like) {      // several reduced channel-like axes side by side (a stage cut off by the pass), or the
+                               // two halves of a Merge side by side (a window over flattened axes): one axis
     OwnedDesc fused;
     Graph gf;
     if (fuse_reduced_axes(*desc, fused)) {

@@ -43,6 +43,18 @@ def conv2d(N, C, Co, H, W, KH=3, KW=None, in_dtype=F32, out_dtype=F32, w_order=(
     return b.finish([n, cx, hh, ww], [waxes[i] for i in w_order], in_dtype, out_dtype)
 
 
+def flat_window(N, C, Co, A, B, K=3, in_dtype=F32, out_dtype=F32) -> OpDesc:
+    """A window over two flattened axes (an Unfold below a Merge, the left side of the paper's Fig. 4(c)):
+    out[n,co,i] = sum_{c,j} X[n, c, u div B, u mod B] * Wt[co,c,j] with u = i + j - K/2, zero where u is outside [0, A*B)."""
+    b = Builder([("n", N), ("co", Co), ("i", A * B)], name=f"flat_window_k{K}_C{C}_Co{Co}_{A}x{B}_N{N}")
+    c = b.reduce(C)
+    cx, cw = b.share(c)
+    j = b.reduce(K)
+    jx, jw = b.share(j)
+    q, r = b.merge(b.unfold(2, jx), B)
+    return b.finish([0, cx, q, r], [1, cw, jw], in_dtype, out_dtype)
+
+
 def grouped_shift_unfold(N, C=256, Co=256, H=14, W=14, groups=4, K=3,
                          in_dtype=BF16, out_dtype=F32, w_order=(0, 1, 2, 3)) -> OpDesc:
     """out[n,co,h,w] = sum_{c',k} Wt[co,c',k] * X[n, g*Cg+c', (h+g) mod H, w+k-K/2],  g = co div (Co/groups)."""
@@ -227,6 +239,16 @@ def make_conv(N, C, H, seed=0, bf16=False, Co=None, Wd=None, K=3, with_grad=Fals
     W = s.uniform_pm(1.0 / np.sqrt(K * K * C), ws)
     G = s.normal(os) if with_grad else None
     return _finish(desc, xs, ws, os, X, W, G, C * K * K)
+
+
+def make_flat_window(N, C, Co, A, B, K=3, seed=0, bf16=False, with_grad=False) -> Workload:
+    desc = flat_window(N, C, Co, A, B, K, BF16 if bf16 else F32, F32)
+    s = Stream(seed)
+    xs, ws, os = (N, C, A, B), (Co, C, K), (N, Co, A * B)
+    X = s.normal(xs)
+    W = s.uniform_pm(1.0 / np.sqrt(K * C), ws)
+    G = s.normal(os) if with_grad else None
+    return _finish(desc, xs, ws, os, X, W, G, C * K)
 
 
 def make_gshift(N, seeds=(0, 0, 0), with_grad=False, C=256, H=14, Wd=14, groups=4, K=3, out_bf16=False,

@@ -222,6 +222,21 @@ def test_unreduced_window_goes_to_the_streaming_family(syno):
     assert syno.Plan(wl.conv2d(2, 16, 16, 8, 8, 1, 3)).kernel(0).startswith("mfma")
 
 
+def test_window_over_flattened_axes_is_a_contraction(syno):
+    # Unfold below a Merge whose halves are adjacent axes of X: one long row for the convolution-like analysis
+    p = syno.Plan(wl.flat_window(2, 16, 24, 6, 10, 3))
+    assert p.x_shape == (2, 16, 6, 10) and p.out_shape == (2, 24, 60)
+    assert [p.kernel(i) for i in range(3)] == ["mfma_contraction_f32"] * 3
+    # rows longer than a workgroup tile (512 pixels) are left to the index-program kernels
+    assert syno.Plan(wl.flat_window(2, 16, 24, 28, 28, 3)).kernel(0) == "generic_index_program"
+    # the halves in the other order are a transposition, not one axis
+    b = Builder([("n", 2), ("co", 24), ("i", 60)])
+    c = b.reduce(16); cx, cw = b.share(c)
+    j = b.reduce(3); jx, jw = b.share(j)
+    q, r = b.merge(b.unfold(2, jx), 10)
+    assert syno.Plan(b.finish([0, cx, r, q], [1, cw, jw])).kernel(0) == "generic_index_program"
+
+
 def test_strided_convolution_forward_is_a_contraction(syno):
     for K in (3, 1):
         p = syno.Plan(wl.conv2d(2, 16, 24, 6, 6, K, stride=2))

@@ -126,6 +126,11 @@ def small_cases():
     c["conv_f32_1x1_stride2"] = lambda: wl.make_conv(5, 40, 4, seed=27, Co=48, Wd=6, K=1, stride=2, with_grad=True)
     c["conv_bf16_1x1_stride2"] = lambda: wl.make_conv(5, 72, 4, seed=28, Co=48, Wd=6, K=1, stride=2, bf16=True, with_grad=True)
     c["conv_f32_3x3_stride3"] = lambda: wl.make_conv(2, 16, 5, seed=29, Co=24, Wd=9, stride=3, with_grad=True)
+    # a window over two flattened axes (Unfold below a Merge): the two halves of the Merge lie side by side in X, so the
+    # planner reads them as one long row and the contraction kernels take all three passes
+    c["flat_window_f32"] = lambda: wl.make_flat_window(3, 24, 40, 6, 10, seed=31, with_grad=True)
+    c["flat_window_bf16"] = lambda: wl.make_flat_window(3, 40, 24, 14, 14, seed=32, bf16=True, with_grad=True)
+    c["flat_window_f32_k5_C80"] = lambda: wl.make_flat_window(2, 80, 40, 7, 7, K=5, seed=33, with_grad=True)
     c["gshift_bf16"] = lambda: wl.make_gshift(3, seeds=(1, 2, 3), with_grad=True)
     c["gshift_bf16_small_groups"] = lambda: wl.make_gshift(2, seeds=(4, 5, 6), with_grad=True, C=96, H=9, Wd=11, groups=3)
     c["gshift_f32"] = lambda: wl.make_gshift(2, seeds=(7, 8, 9), with_grad=True, C=64, H=6, Wd=10, groups=2, bf16=False)

@@ -44,10 +44,14 @@ __global__ __launch_bounds__(256) void pack_weight_bf16(const MfmaParams p, cons
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= pieces) return;
   const int KHW = p.KH * p.KW, row8 = p.w_row >> 3;
+  // Adjacent threads take adjacent taps, then adjacent output channels, of one channel octet: for the adjoint of a
+  // forward-layout weight (output channel stride KHW, tap stride -1) and for a matrix product's transposed operand
+  // (output channel stride 1) each of the 8 element loads of a wave then covers one contiguous stretch of memory;
+  // the 16-byte pieces are written wherever the block layout puts them.
   int64_t r = i;
-  const int cq = (int)(r % row8); r /= row8;
-  const int ol = (int)(r % p.BN); r /= p.BN;
   const int tap = (int)(r % KHW); r /= KHW;
+  const int ol = (int)(r % p.BN); r /= p.BN;
+  const int cq = (int)(r % row8); r /= row8;
   const int ch = (int)(r % p.n_chunks); r /= p.n_chunks;
   const int nb = (int)(r % p.n_nblocks);
   const int g = (int)(r / p.n_nblocks);
@@ -61,7 +65,8 @@ __global__ __launch_bounds__(256) void pack_weight_bf16(const MfmaParams p, cons
       v[e] = Wt[p.w_base + (int64_t)g * p.ws_g + (int64_t)o * p.ws_o + (int64_t)(c0 + e) * p.ws_c + kh * p.ws_kh +
                 kw * p.ws_kw];
   }
-  packed[i] = make_uint4(v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16));
+  const int64_t dst = (((((int64_t)g * p.n_nblocks + nb) * p.n_chunks + ch) * KHW + tap) * p.BN + ol) * row8 + cq;
+  packed[dst] = make_uint4(v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16));
 }
 
 // fp32 backward-data: Wt[g][c][o][kh'][kw'] = W[g][o][c][KH-1-kh'][KW-1-kw'] (source strides ts_*), contiguous.

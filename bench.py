@@ -321,11 +321,13 @@ def main() -> int:
             for stage, (C, H) in enumerate(wl.RESNET18_STAGES):     # bf16 results as well (changes the byte count)
                 w = wl.make_conv(32, C, H, seed=0, bf16=True, out_bf16=True)
                 cases.append(Case(f"conv3x3_C{C}_{H}x{H}_N32_bf16_out_bf16_fwd", w, 0))
-            # the downsampling convolutions between the first two stages (a Stride below the window), forward
+            # the downsampling convolutions between the first two stages (a Stride below the window): forward on the
+            # contraction kernel, the gradients at stride 1 on the stride's phase planes
             for bf16 in (False, True):
                 for K in (3, 1):
-                    w = wl.make_conv(32, 64, 28, seed=0, bf16=bf16, Co=128, K=K, stride=2)
-                    cases.append(Case(f"conv{K}x{K}_stride2_C64_Co128_56to28_N32_{'bf16' if bf16 else 'f32'}_fwd", w, 0))
+                    w = wl.make_conv(32, 64, 28, seed=0, bf16=bf16, Co=128, K=K, stride=2, with_grad=True)
+                    cases += [Case(f"conv{K}x{K}_stride2_C64_Co128_56to28_N32_{'bf16' if bf16 else 'f32'}_{PASS[k]}", w, k)
+                              for k in range(3)]
         if want(2):
             cases.append(Case("config2_gshift_bf16_N32_fwd", wl.config2(), 0))
             cases.append(Case("config2_gshift_bf16_N32_out_bf16_fwd", wl.make_gshift(32, seeds=(0, 0, 0), out_bf16=True), 0))

@@ -88,7 +88,7 @@ const void* unit_weight(syno_dtype t) {
 
 const char* const kKernelNames[syno::KERNEL_COUNT] = {
     "generic_index_program", "bandwidth_depthwise", "bandwidth_share_window", "bandwidth_view", "mfma_contraction_f32", "mfma_contraction_bf16",
-    "mfma_contraction_transposed"};
+    "mfma_contraction_transposed", "mfma_contraction_phases"};
 
 syno_status run(const syno_plan* plan, int which, const void* A, const void* B, void* out, void* ws,
                 hipStream_t stream) {
@@ -119,6 +119,39 @@ syno_status run(const syno_plan* plan, int which, const void* A, const void* B, 
         return run(plan->inner_dx, SYNO_FWD, ws, A, out, static_cast<char*>(ws) + head, stream);
       }
       return run(plan->inner, L.variant, A, B, out, ws, stream);
+    case syno::KERNEL_MFMA_PHASES: {
+      // gradients of a strided convolution on the stride's phase planes (see the planner)
+      if (!ws) return SYNO_ERR_WORKSPACE;
+      const syno::ConvLike& c = plan->conv;
+      const int window = plan->phase_window;
+      const size_t esz = plan->in_dtype == SYNO_BF16 ? 2 : 4, osz = plan->out_dtype == SYNO_BF16 ? 2 : 4;
+      const size_t CP = (size_t)c.Cg * c.sh * c.sh;
+      auto round_up = [](size_t n) { return (n + 255) & ~(size_t)255; };
+      char* w0 = static_cast<char*>(ws);
+      if (which == SYNO_BWD_WEIGHT) {          // A = G, B = X, out = dW
+        void* Xp = w0;
+        float* dWp = reinterpret_cast<float*>(w0 + round_up((size_t)plan->x_elems * esz));
+        void* rest = reinterpret_cast<char*>(dWp) + round_up((size_t)c.Og * CP * window * window * 4);
+        const void* one = unit_weight(plan->in_dtype);
+        if (!one) return SYNO_ERR_HIP;
+        syno_status st = run(plan->phase_view_x, SYNO_FWD, B, one, Xp, nullptr, stream);
+        if (st != SYNO_OK) return st;
+        st = run(plan->phase_conv_dw, SYNO_BWD_WEIGHT, A, Xp, dWp, rest, stream);
+        if (st != SYNO_OK) return st;
+        return syno::launch_phase_weight_gather(c, window, dWp, static_cast<float*>(out), stream);
+      }
+      // A = G, B = W, out = dX
+      void* Wpp = w0;
+      void* dXp = w0 + round_up(CP * c.Og * window * window * esz);
+      void* rest = static_cast<char*>(dXp) + round_up((size_t)plan->x_elems * osz);
+      const void* one = unit_weight(plan->out_dtype);
+      if (!one) return SYNO_ERR_HIP;
+      syno_status st = syno::launch_phase_weight_build(c, window, (int)esz, B, Wpp, stream);
+      if (st != SYNO_OK) return st;
+      st = run(plan->phase_conv_dx, SYNO_FWD, A, Wpp, dXp, rest, stream);
+      if (st != SYNO_OK) return st;
+      return run(plan->phase_view_dx, SYNO_BWD_DATA, dXp, one, out, nullptr, stream);
+    }
     default: return SYNO_ERR_UNSUPPORTED;
   }
 }
@@ -216,6 +249,14 @@ syno_status syno_plan_describe(const syno_plan* plan, int which, char* buf, size
       d += " " + (which == SYNO_BWD_WEIGHT ? syno::mfma_dw_describe(plan) : syno::mfma_describe(plan, which));
       break;
     case syno::KERNEL_BW_VIEW: d += " " + syno::view_describe(plan, which); break;
+    case syno::KERNEL_MFMA_PHASES: {
+      char inner[400];
+      const syno_plan* conv = which == SYNO_BWD_WEIGHT ? plan->phase_conv_dw : plan->phase_conv_dx;
+      if (syno_plan_describe(conv, which == SYNO_BWD_WEIGHT ? SYNO_BWD_WEIGHT : SYNO_FWD, inner, sizeof(inner)) == SYNO_OK)
+        d += std::string(which == SYNO_BWD_WEIGHT ? " space-to-depth of X, then the weight gradient of a stride-1 convolution over the phase planes: "
+                                                  : " forward contraction onto the phase planes of dX, then depth-to-space: ") + inner;
+      break;
+    }
     case syno::KERNEL_MFMA_TRANSPOSED: {
       char inner[400];
       if (plan->launch[which].variant == syno::kViaTransposedCopy) {

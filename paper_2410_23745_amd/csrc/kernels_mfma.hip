@@ -165,6 +165,56 @@ __global__ __launch_bounds__(256) void sum_split_results(const float* __restrict
   }
 }
 
+// Gradients of a convolution with stride s through its phase planes (the s*s sub-images X[.., s*h'+a, s*w'+b] taken as
+// s*s*C channels, on which the window moves with stride 1).  Tap kh of the strided window reads phase a = (kh-p) mod s
+// at row offset dh = floor((kh-p)/s), which is tap dh+1 of a 3-wide stride-1 window with pad 1 (or the only tap of a
+// 1-wide one).  The two kernels move weights between the two forms; `taps` = s*dh+a+p for every (a, tap) is recomputed
+// from the record.
+struct PhaseParams {
+  int32_t O, C, K, s, p, window;
+  int32_t ws_o, ws_c, ws_kh, ws_kw;
+};
+
+__device__ __forceinline__ int floor_div(int a, int b) { return (a >= 0 ? a : a - b + 1) / b; }
+
+// one thread per element of dW
+__global__ __launch_bounds__(256) void phase_weight_gather(const PhaseParams q, const float* __restrict__ dWp,
+                                                           float* __restrict__ dW) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= q.O * q.C * q.K * q.K) return;
+  int r = i;
+  const int kw = r % q.K; r /= q.K;
+  const int kh = r % q.K; r /= q.K;
+  const int c = r % q.C;
+  const int o = r / q.C;
+  const int dh = floor_div(kh - q.p, q.s), a = kh - q.p - q.s * dh;
+  const int dw = floor_div(kw - q.p, q.s), b = kw - q.p - q.s * dw;
+  const int th = q.window == 3 ? dh + 1 : 0, tw = q.window == 3 ? dw + 1 : 0;
+  const int cp = (c * q.s + a) * q.s + b;
+  dW[(int64_t)o * q.ws_o + (int64_t)c * q.ws_c + kh * q.ws_kh + kw * q.ws_kw] =
+      dWp[(((int64_t)o * q.C * q.s * q.s + cp) * q.window + th) * q.window + tw];
+}
+
+// one thread per element of Wpp
+template <class T>
+__global__ __launch_bounds__(256) void phase_weight_build(const PhaseParams q, const T* __restrict__ W, T* __restrict__ Wpp) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  const int CP = q.C * q.s * q.s;
+  if (i >= CP * q.O * q.window * q.window) return;
+  int r = i;
+  const int tw = r % q.window; r /= q.window;
+  const int th = r % q.window; r /= q.window;
+  const int o = r % q.O;
+  const int cp = r / q.O;
+  const int b = cp % q.s, a = (cp / q.s) % q.s, c = cp / (q.s * q.s);
+  const int dh = q.window == 3 ? th - 1 : 0, dw = q.window == 3 ? tw - 1 : 0;
+  const int kh = a + q.p - q.s * dh, kw = b + q.p - q.s * dw;
+  T v = 0;
+  if (kh >= 0 && kh < q.K && kw >= 0 && kw < q.K)
+    v = W[(int64_t)o * q.ws_o + (int64_t)c * q.ws_c + kh * q.ws_kh + kw * q.ws_kw];
+  Wpp[i] = v;
+}
+
 // ---------------------------------------------------------------------------------------------
 // Host side: tile choice and launch
 // ---------------------------------------------------------------------------------------------
@@ -514,6 +564,35 @@ syno_status launch_mfma(const syno_plan* plan, int which, const void* A, const v
     hipLaunchKernelGGL(sum_split_results, dim3((unsigned)blocks), dim3(256), 0, stream, static_cast<const float*>(out),
                        static_cast<float*>(result), n, p.ksplit, (int64_t)p.split_stride);
   }
+  return hipGetLastError() == hipSuccess ? SYNO_OK : SYNO_ERR_HIP;
+}
+
+namespace {
+PhaseParams phase_params(const ConvLike& c, int window) {
+  PhaseParams q{};
+  q.O = c.Og; q.C = c.Cg; q.K = c.KH; q.s = c.sh; q.p = c.ph; q.window = window;
+  q.ws_o = c.ws_o; q.ws_c = c.ws_c; q.ws_kh = c.ws_kh; q.ws_kw = c.ws_kw;
+  return q;
+}
+}  // namespace
+
+syno_status launch_phase_weight_gather(const ConvLike& c, int window, const float* dWp, float* dW, hipStream_t stream) {
+  const PhaseParams q = phase_params(c, window);
+  const int64_t n = (int64_t)q.O * q.C * q.K * q.K;
+  if (n >= (1ll << 31)) return SYNO_ERR_SHAPE;
+  hipLaunchKernelGGL(phase_weight_gather, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, q, dWp, dW);
+  return hipGetLastError() == hipSuccess ? SYNO_OK : SYNO_ERR_HIP;
+}
+
+syno_status launch_phase_weight_build(const ConvLike& c, int window, int elem_bytes, const void* W, void* Wpp, hipStream_t stream) {
+  const PhaseParams q = phase_params(c, window);
+  const int64_t n = (int64_t)q.C * q.s * q.s * q.O * window * window;
+  if (n >= (1ll << 31)) return SYNO_ERR_SHAPE;
+  const dim3 grid((unsigned)((n + 255) / 256));
+  if (elem_bytes == 4)
+    hipLaunchKernelGGL(phase_weight_build<uint32_t>, grid, dim3(256), 0, stream, q, static_cast<const uint32_t*>(W), static_cast<uint32_t*>(Wpp));
+  else
+    hipLaunchKernelGGL(phase_weight_build<uint16_t>, grid, dim3(256), 0, stream, q, static_cast<const uint16_t*>(W), static_cast<uint16_t*>(Wpp));
   return hipGetLastError() == hipSuccess ? SYNO_OK : SYNO_ERR_HIP;
 }
 

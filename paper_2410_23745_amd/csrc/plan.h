@@ -111,6 +111,7 @@ enum KernelId : int32_t {
   KERNEL_MFMA_F32,
   KERNEL_MFMA_BF16,
   KERNEL_MFMA_TRANSPOSED,   // a matrix product run as the 1x1 convolution with exchanged operand roles (plan->inner)
+  KERNEL_MFMA_PHASES,       // gradients of a strided convolution through the stride's phase planes (plan->phase_*)
   KERNEL_COUNT
 };
 
@@ -145,7 +146,13 @@ struct syno_plan {
   // matrix products: dX = G * W^T is a matrix product too; the plan of ITS 1x1 convolution (owned), whose forward
   // contraction runs on a transposed copy of W in the workspace (Launch::variant = kViaTransposedCopy)
   syno_plan* inner_dx = nullptr;
-  ~syno_plan() { delete inner; delete inner_dx; }
+  // strided convolutions (stride s below the window): the gradients run at stride 1 on the s*s phase planes
+  // X[.., s*h'+a, s*w'+b] taken as s*s*C channels.  phase_view_x / phase_view_dx: the space-to-depth view in the input
+  // and in the result element type; phase_conv_dw / phase_conv_dx: the stride-1 convolutions whose backward-weight and
+  // forward contractions do the work (owned)
+  syno_plan *phase_view_x = nullptr, *phase_view_dx = nullptr, *phase_conv_dw = nullptr, *phase_conv_dx = nullptr;
+  int32_t phase_window = 0;      // window of those convolutions: 3 (pad 1) or 1
+  ~syno_plan() { delete inner; delete inner_dx; delete phase_view_x; delete phase_view_dx; delete phase_conv_dw; delete phase_conv_dx; }
   bool pure_view = false;
   syno::ViewStream view{};
 };
@@ -211,6 +218,11 @@ syno_status launch_rows(const syno_plan* p, int which, const void* A, const void
 // kernels_mfma.hip: dst[c][r] = src[r][c] for a row-major rows x cols matrix of 2- or 4-byte elements
 constexpr int kViaTransposedCopy = 100;
 syno_status launch_transpose_2d(const void* src, void* dst, int64_t rows, int64_t cols, int elem_bytes, hipStream_t stream);
+// kernels_mfma.hip, gradients of a strided convolution through the phase planes:
+// dW[o,c,kh,kw] (any strides) = dWp[o][(c*s+a)*s+b][th][tw] with s*dh+a = kh-p, th = dh+1 (window 3) or 0 (window 1)
+syno_status launch_phase_weight_gather(const ConvLike& c, int window, const float* dWp, float* dW, hipStream_t stream);
+// Wpp[(c*s+a)*s+b][o][th][tw] (contiguous, 2- or 4-byte elements) = W[o,c,kh,kw] with kh = a+p-s*dh, or 0 where there is none
+syno_status launch_phase_weight_build(const ConvLike& c, int window, int elem_bytes, const void* W, void* Wpp, hipStream_t stream);
 // kernels_mfma_dw.hip: the backward-weight member of the MFMA family
 bool mfma_dw_supports(const syno_plan* p);
 void mfma_dw_configure(syno_plan* p);

@@ -1270,6 +1270,92 @@ syno_status build_plan(const syno_desc* desc, syno_plan* plan, std::string* why)
       view_configure(plan, which);
     }
   }
+  // The gradients of a convolution with a Stride below its window (forward runs on the contraction kernel): on the
+  // s*s phase planes X[.., s*h'+a, s*w'+b], taken as s*s*C channels, the window moves with stride 1 - tap kh reads
+  // phase (kh-p) mod s at row offset floor((kh-p)/s) - so dW is the weight gradient, and dX the forward contraction,
+  // of a stride-1 convolution between the upstream gradient and the phase planes, with a space-to-depth view before
+  // or after it.  Only the taps that exist are kept (dW) or non-zero (dX): the stride-1 window has more.
+  if (policy != 1 && plan->conv_like && plan->conv.sh > 1 &&
+      (plan->launch[SYNO_FWD].kernel == KERNEL_MFMA_F32 || plan->launch[SYNO_FWD].kernel == KERNEL_MFMA_BF16)) {
+    const ConvLike& c = plan->conv;
+    const int s = c.sh;
+    auto floor_div = [](int a, int b) { return (a >= 0 ? a : a - b + 1) / b; };
+    const int dmin = floor_div(-c.ph, s), dmax = floor_div(c.KH - 1 - c.ph, s);
+    const bool fits = c.G == 1 && c.sw == s && c.KH == c.KW && c.ph == c.pw && !c.h_wrap && !c.w_wrap &&
+                      c.Hi == s * c.Ho && c.Wi == s * c.Wo && dmin >= -1 && dmax <= 1 && (int64_t)c.Cg * s * s < (1 << 20);
+    if (fits) {
+      const int window = (dmin == 0 && dmax == 0) ? 1 : 3;
+      // out[n,c,a,b,h',w'] = X[n, c, s*h'+a, s*w'+b] (times a one-element weight), element type t on both sides
+      auto view_plan = [&](syno_dtype t) -> syno_plan* {
+        const syno_dim dims[6] = {{"n", c.N}, {"c", c.Cg}, {"a", s}, {"b", s}, {"h", c.Ho}, {"w", c.Wo}};
+        syno_prim pr[2] = {};
+        for (int k = 0; k < 2; ++k) {
+          pr[k].kind = SYNO_SPLIT; pr[k].in[0] = 4 + k; pr[k].in[1] = 2 + k; pr[k].out[0] = 6 + k; pr[k].out[1] = -1;
+          pr[k].shift_by = -1;
+        }
+        const int32_t xin[4] = {0, 1, 6, 7};
+        syno_desc d{};
+        d.n_out = 6; d.out_dims = dims; d.n_prim = 2; d.prims = pr; d.n_in = 4; d.input_coords = xin; d.n_w = 0;
+        d.weight_coords = nullptr; d.in_dtype = t; d.out_dtype = t;
+        syno_plan* ip = new syno_plan();
+        if (build_plan(&d, ip, nullptr) != SYNO_OK) { delete ip; return nullptr; }
+        return ip;
+      };
+      // the stride-1 convolution [N, cin, Ho, Wo] -> [N, cout, Ho, Wo] with a window x window kernel [cout, cin, ., .]
+      auto conv_plan = [&](int64_t cin, int64_t cout, syno_dtype out_t) -> syno_plan* {
+        const syno_dim dims[4] = {{"n", c.N}, {"co", cout}, {"h", c.Ho}, {"w", c.Wo}};
+        syno_prim pr[8] = {};
+        auto set = [&](int k, syno_prim_kind kind, int i0, int i1, int o0, int o1, int64_t param) {
+          pr[k].kind = kind; pr[k].in[0] = i0; pr[k].in[1] = i1; pr[k].out[0] = o0; pr[k].out[1] = o1; pr[k].param = param;
+          pr[k].shift_by = -1;
+        };
+        set(0, SYNO_REDUCE, -1, -1, 4, -1, cin);    set(1, SYNO_SHARE, 4, -1, 5, 6, 0);
+        set(2, SYNO_REDUCE, -1, -1, 7, -1, window); set(3, SYNO_SHARE, 7, -1, 8, 9, 0);
+        set(4, SYNO_REDUCE, -1, -1, 10, -1, window); set(5, SYNO_SHARE, 10, -1, 11, 12, 0);
+        set(6, SYNO_UNFOLD, 2, 8, 13, -1, 0);       set(7, SYNO_UNFOLD, 3, 11, 14, -1, 0);
+        const int32_t xin[4] = {0, 5, 13, 14}, win[4] = {1, 6, 9, 12};
+        syno_desc d{};
+        d.n_out = 4; d.out_dims = dims; d.n_prim = 8; d.prims = pr; d.n_in = 4; d.input_coords = xin; d.n_w = 4;
+        d.weight_coords = win; d.in_dtype = desc->in_dtype; d.out_dtype = out_t;
+        syno_plan* ip = new syno_plan();
+        if (build_plan(&d, ip, nullptr) != SYNO_OK) { delete ip; return nullptr; }
+        return ip;
+      };
+      auto is_mfma = [](const Launch& L) { return L.kernel == KERNEL_MFMA_F32 || L.kernel == KERNEL_MFMA_BF16; };
+      auto round_up = [](size_t n) { return (n + 255) & ~(size_t)255; };
+      const int64_t CP = (int64_t)c.Cg * s * s;
+      const size_t esz = desc->in_dtype == SYNO_BF16 ? 2 : 4, osz = desc->out_dtype == SYNO_BF16 ? 2 : 4;
+      // backward-weight: space-to-depth of X, weight gradient of the stride-1 convolution, the existing taps picked out
+      {
+        syno_plan* v = view_plan(desc->in_dtype);
+        syno_plan* cw = conv_plan(CP, c.Og, SYNO_F32);
+        if (v && cw && v->launch[SYNO_FWD].kernel == KERNEL_BW_VIEW && is_mfma(cw->launch[SYNO_BWD_WEIGHT])) {
+          plan->phase_view_x = v; plan->phase_conv_dw = cw; plan->phase_window = window;
+          Launch& L = plan->launch[SYNO_BWD_WEIGHT];
+          L.kernel = KERNEL_MFMA_PHASES;
+          L.workspace = round_up((size_t)plan->x_elems * esz) + round_up((size_t)c.Og * CP * window * window * 4) +
+                        cw->launch[SYNO_BWD_WEIGHT].workspace;
+        } else {
+          delete v; delete cw;
+        }
+      }
+      // backward-data: the weights spread over the phases, the forward contraction from the upstream gradient to the
+      // phase planes of dX, depth-to-space (the view's scatter)
+      {
+        syno_plan* v = view_plan(desc->out_dtype);
+        syno_plan* cx = conv_plan(c.Og, CP, desc->out_dtype);
+        if (v && cx && v->launch[SYNO_BWD_DATA].kernel == KERNEL_BW_VIEW && v->view.one_to_one && is_mfma(cx->launch[SYNO_FWD])) {
+          plan->phase_view_dx = v; plan->phase_conv_dx = cx; plan->phase_window = window;
+          Launch& L = plan->launch[SYNO_BWD_DATA];
+          L.kernel = KERNEL_MFMA_PHASES;
+          L.workspace = round_up((size_t)CP * c.Og * window * window * esz) + round_up((size_t)plan->x_elems * osz) +
+                        cx->launch[SYNO_FWD].workspace;
+        } else {
+          delete v; delete cx;
+        }
+      }
+    }
+  }
   // A matrix product is a 1x1 convolution with the operands' roles exchanged: W[k,j] is an "image" with k as
   // channels and the contiguous j as pixels, X[i,k] the weight of output channel i, and out[i,j] is laid out
   // channel-major like a convolution result.  Its gradients exchange roles too: dX is that convolution's

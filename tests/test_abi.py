@@ -237,13 +237,21 @@ def test_window_over_flattened_axes_is_a_contraction(syno):
     assert syno.Plan(b.finish([0, cx, r, q], [1, cw, jw])).kernel(0) == "generic_index_program"
 
 
-def test_strided_convolution_forward_is_a_contraction(syno):
+def test_strided_convolution_runs_on_the_contraction_kernels(syno):
     for K in (3, 1):
         p = syno.Plan(wl.conv2d(2, 16, 24, 6, 6, K, stride=2))
         assert p.x_shape == (2, 16, 12, 12) and p.out_shape == (2, 24, 6, 6)
-        # forward gathers the strided window into LDS; the adjoints (a scatter, a strided weight gradient) stay generic
-        assert [p.kernel(i) for i in range(3)] == ["mfma_contraction_f32", "generic_index_program", "generic_index_program"]
+        # forward gathers the strided window into LDS; the gradients run at stride 1 on the stride's phase planes
+        assert [p.kernel(i) for i in range(3)] == ["mfma_contraction_f32", "mfma_contraction_phases", "mfma_contraction_phases"]
+        assert "depth-to-space" in p.describe(1) and "space-to-depth" in p.describe(2)
+        # workspaces: the re-ordered weights and the phase planes of dX; the phase planes of X and the stride-1 gradient
+        win = 3 if K == 3 else 1
+        assert p.workspace_bytes(1) >= 4 * (64 * 24 * win * win + 2 * 16 * 12 * 12)
+        assert p.workspace_bytes(2) >= 4 * (2 * 16 * 12 * 12 + 24 * 64 * win * win)
     assert syno.Plan(wl.conv2d(2, 16, 24, 6, 6, 3, in_dtype=BF16, stride=2)).kernel(0) == "mfma_contraction_bf16"
+    # an index-program-only plan keeps every pass there
+    q = syno.Plan(wl.conv2d(2, 16, 24, 6, 6, 3, stride=2), kernel_policy=1)
+    assert [q.kernel(i) for i in range(3)] == ["generic_index_program"] * 3
 
 
 def test_matmul_is_planned_as_a_convolution_with_exchanged_roles(syno):

@@ -161,6 +161,30 @@ def test_small_cases_all_directions(syno, oracle, name, policy):
     run_all(syno, oracle, small_cases()[name](), policy)
 
 
+@pytest.mark.parametrize("seed", range(32))
+def test_random_convolution_shapes(syno, oracle, seed):
+    """Seeded draws over batch, channels (ragged against every tile and chunk size), image extents, window, stride and
+    element type, all three passes against the checker: whatever tiling the planner picks for a shape nobody chose by
+    hand."""
+    rng = np.random.default_rng(1000 + seed)
+    K, stride, bf16 = int(rng.choice([1, 3])), int(rng.choice([1, 1, 2])), bool(rng.integers(2))
+    N, C, Co = int(rng.integers(1, 6)), int(rng.choice([3, 8, 20, 40, 72, 96, 136])), int(rng.choice([5, 16, 24, 40, 80, 130]))
+    H, Wd = int(rng.integers(3, 16)), int(rng.integers(4, 22))
+    w = wl.make_conv(N, C, H, seed=2000 + seed, bf16=bf16, Co=Co, Wd=Wd, K=K, stride=stride, with_grad=True)
+    names = run_all(syno, oracle, w, 0)
+    assert all(n.startswith("mfma_contraction") for n in names), names
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_matmul_shapes(syno, oracle, seed):
+    rng = np.random.default_rng(3000 + seed)
+    M, K = int(rng.integers(5, 300)), int(rng.integers(4, 260))
+    N = int(rng.choice([7, 13, 24, 40, 56, 64])) * int(rng.integers(1, 9))
+    w = wl.make_matmul(M, K, N, seed=4000 + seed, bf16=bool(rng.integers(2)), with_grad=True)
+    names = run_all(syno, oracle, w, 0)
+    assert names[0] == names[2] == "mfma_contraction_transposed", names
+
+
 @pytest.mark.parametrize("variant,rows,order", [(0, 4, (1, 0, 2, 3)), (1, 3, (2, 3, 1, 0)), (2, 2, (0, 3, 2, 1)), (0, 1, (0, 1, 2, 3)),
                                                 (3, 4, (0, 1, 2, 3)), (11, 2, (0, 1, 2, 3))])
 def test_conv_f32_named_tile_variants(syno, oracle, variant, rows, order):

@@ -104,8 +104,8 @@ __device__ __forceinline__ void static_for(F&& f) {
 //             aligned in memory, so it is staged with 16-byte loads instead of element by element.
 // KCB: bf16 only: channels per chunk (a compile-time constant there, since it fixes the tap offsets in LDS)
 // WF:  bf16: > 0 = the weights are read as they lie in memory ([o][c][WF taps], the forward layout) and re-ordered
-//      on their way into LDS, instead of coming from the packed copy; < 0 = the same for backward-data (single-
-//      chunk variant only)
+//      on their way into LDS, instead of coming from the packed copy; < 0 = the same for backward-data: the
+//      single-chunk variant brings its whole block in at the start, the others (9 taps only) chunk by chunk
 // U:   window taps along w handled per "row-step" (3 when KW = 3, else 1): the operands of the U taps sit at
 //      compile-time LDS offsets from one per-lane address, so addresses advance once per row-step.
 // WK:  waves that share one output tile and split each chunk's k-steps among themselves (for shapes whose
@@ -179,8 +179,15 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
   // chunk (WF adjacent 16-byte loads); on the way into LDS it is re-ordered into one 16-byte piece per tap.
   constexpr int kAdjPairs = (WI * 4) / 9;      // (fp32, adjoint from the forward layout) pairs of 9 taps a thread's weight registers hold
   constexpr int OCT = BF ? KCB / 8 : 1;                                     // channel octets per chunk
-  constexpr int WP = (BF && WF > 0) ? (BN * OCT + NT - 1) / NT : 1;         // such items per thread
+  // bf16 backward-data of a multi-chunk variant straight from forward-layout weights W[o][c][9 taps]: an item is one
+  // row of the block (a forward input channel c) x one octet of the chunk's reduction channels (forward output
+  // channels o): eight runs of 9 adjacent taps, a forward output-channel stride apart, each read as 16 + 2 bytes;
+  // on the way into LDS they become one 16-byte piece per tap (the 8 channels of the octet), taps reversed
+  constexpr bool WADJ = BF && WF < 0 && !ONE;
+  static_assert(!WADJ || WF == -9, "the chunked adjoint reads runs of 9 taps");
+  constexpr int WP = (BF && (WF > 0 || WADJ)) ? (BN * OCT + NT - 1) / NT : 1;   // such items per thread
   constexpr int WFA = WF > 0 ? WF : 1;
+  constexpr int WIN = WADJ ? 8 * 5 : 4 * WFA;                               // dwords of one item in registers
   int wp_src[WP], wp_dst[WP], wp_c[WP];   // element offset in W at chunk 0; LDS piece index at tap 0 (-1: unused);
                                           // first channel inside the chunk | row beyond Og << 30
   const uint16_t* Wnat = nullptr;
@@ -191,6 +198,19 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
       const int idx = tid + k * NT;
       const int octet = idx % OCT, ol = idx / OCT;
       wp_src[k] = ol * p.ws_o + octet * 8 * WF;
+      wp_dst[k] = idx < BN * OCT ? ol * ((KCB + 8) / 8) + octet : -1;
+      wp_c[k] = octet * 8 | (nb * BN + ol < p.Og ? 0 : (1 << 30));
+    }
+  } else if constexpr (WADJ) {
+    // (p.ws_o is the forward channel stride = 9, p.ws_c the forward output-channel stride)
+    Wnat = reinterpret_cast<const uint16_t*>(Wv) + (int64_t)g * p.ws_g + (int64_t)nb * BN * 9;
+#pragma unroll
+    for (int k = 0; k < WP; ++k) {
+      // adjacent lanes take adjacent rows: their runs of one forward output channel are adjacent in memory (18 bytes
+      // each), and their 16-byte pieces go to LDS rows one pitch apart, the fragment reads' conflict-free pattern
+      const int idx = tid + k * NT;
+      const int ol = idx % BN, octet = idx / BN;
+      wp_src[k] = ol * 9 + octet * 8 * p.ws_c;
       wp_dst[k] = idx < BN * OCT ? ol * ((KCB + 8) / 8) + octet : -1;
       wp_c[k] = octet * 8 | (nb * BN + ol < p.Og ? 0 : (1 << 30));
     }
@@ -285,7 +305,7 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
 
   XV xr[XI][CI];
   WReg wr[WI];
-  uint32_t win[WP][4 * WFA];     // (bf16, WF > 0 only)
+  uint32_t win[WP][WIN];         // (bf16 weights read as they lie in memory only)
   // dword I of the weight registers taken as one flat array (16-byte pieces only)
   auto wcomp = [&](auto i_c) -> uint32_t& {
     constexpr int I = decltype(i_c)::value;
@@ -351,6 +371,23 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
             const u32x4_unaligned v = *reinterpret_cast<const u32x4_unaligned*>(src + q * 8);
             win[k][4 * q + 0] = v[0]; win[k][4 * q + 1] = v[1]; win[k][4 * q + 2] = v[2]; win[k][4 * q + 3] = v[3];
           }
+      }
+    } else if constexpr (WADJ) {
+      typedef uint32_t u32x4_unaligned __attribute__((ext_vector_type(4), aligned(2)));
+#pragma unroll
+      for (int k = 0; k < WP; ++k) {
+        // (the reduction length is a multiple of 8, so an octet that starts inside it lies inside it)
+        const bool live = wp_dst[k] >= 0 && !(wp_c[k] >> 30) && c0 + (wp_c[k] & 0xffff) < p.Cg;
+        const uint16_t* src = Wnat + (live ? (int64_t)wp_src[k] + (int64_t)c0 * p.ws_c : 0);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const uint16_t* run = src + (int64_t)e * p.ws_c;
+          if (want(XI * CI + k * 16 + 2 * e)) {
+            const u32x4_unaligned v = *reinterpret_cast<const u32x4_unaligned*>(run);
+            win[k][5 * e + 0] = v[0]; win[k][5 * e + 1] = v[1]; win[k][5 * e + 2] = v[2]; win[k][5 * e + 3] = v[3];
+          }
+          if (want(XI * CI + k * 16 + 2 * e + 1)) win[k][5 * e + 4] = run[8];
+        }
       }
     } else if constexpr (BF && WF != 0) {
     } else if constexpr (BF) {
@@ -440,6 +477,26 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
             wl[tap * BN * ((KCB + 8) / 8) + wp_dst[k]] = make_uint4(d[0], d[1], d[2], d[3]);
           }
         }
+    } else if constexpr (WADJ) {
+      uint4* wl = reinterpret_cast<uint4*>(smem + p.lds_w_off);
+      const int c0 = ch * p.KC;
+#pragma unroll
+      for (int k = 0; k < WP; ++k)
+        if (wp_dst[k] >= 0) {
+          const bool live = !(wp_c[k] >> 30) && c0 + (wp_c[k] & 0xffff) < p.Cg;
+#pragma unroll
+          for (int tap = 0; tap < 9; ++tap) {
+            // tap `tap` of run e is half (tap & 1) of dword tap/2 of the run (the ninth sits alone in the fifth dword)
+            constexpr uint32_t lo = 0x05040100u, hi = 0x07060302u;
+            const int dw = tap < 8 ? tap >> 1 : 4;
+            const uint32_t sel = (tap < 8 && (tap & 1)) ? hi : lo;
+            uint32_t d[4];
+#pragma unroll
+            for (int h = 0; h < 4; ++h)
+              d[h] = live ? __builtin_amdgcn_perm(win[k][5 * (2 * h + 1) + dw], win[k][5 * (2 * h) + dw], sel) : 0u;
+            wl[(8 - tap) * BN * ((KCB + 8) / 8) + wp_dst[k]] = make_uint4(d[0], d[1], d[2], d[3]);    // taps reversed
+          }
+        }
     } else if constexpr (BF && WF != 0) {
     } else if constexpr (BF) {
       uint4* wl = reinterpret_cast<uint4*>(smem + p.lds_w_off);
@@ -484,7 +541,7 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
     const int n16 = p.cgrps * p.n_slots * p.Wp;
     for (int i = tid; i < n16; i += NT) xl[i] = make_float4(0.f, 0.f, 0.f, 0.f);
   }
-  if constexpr (BF && WF < 0) {
+  if constexpr (BF && WF < 0 && ONE) {
     // The same for the backward-data adjoint: the B operand's rows are the forward input channels and its
     // reduction runs over the forward output channels, taps reversed.  A thread again loads 8 channels x
     // T taps of one forward output channel o, but each element goes to its own row: [T-1-tap][c][o].

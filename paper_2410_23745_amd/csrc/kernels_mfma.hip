@@ -252,6 +252,9 @@ int pick_w_row(int need, int kstep, int multiple_of) {
   return best;
 }
 
+// bf16 tile variants whose backward-data instantiation reads forward-layout 3x3 weights itself (the others pack)
+bool bf16_adjoint_direct(int vi) { return vi == 1 || vi == 8 || vi == 9; }
+
 // Parameter record of contraction `which` (forward, or backward-data as its adjoint) for tile variant vi
 // and TR output rows per block.  False when the combination does not fit the kernel's static limits.
 bool fill_params(const syno_plan* plan, int which, int vi, int TR, MfmaParams& p, int ksplit = 1) {
@@ -309,6 +312,11 @@ bool fill_params(const syno_plan* plan, int which, int vi, int TR, MfmaParams& p
       if (which == SYNO_FWD && (KHW == 9 || (v.one && (KHW == 1 || KHW == 3)))) p.wf = KHW;
       if (which == SYNO_BWD_DATA && v.one && (KHW == 1 || KHW == 3 || KHW == 9)) p.wf = -KHW;
     }
+    // backward-data of a 3x3 window by the chunked variants instantiated for it: runs of 9 taps per (output channel,
+    // channel) pair, the reduction (forward output channels) in whole octets, the source addressed in 32 bits
+    if (fwd_layout && which == SYNO_BWD_DATA && !v.one && KHW == 9 && (c.Og & 7) == 0 && bf16_adjoint_direct(vi) &&
+        c.ws_o == c.Cg * KHW && (int64_t)c.Og * c.ws_o < (1ll << 30))
+      p.wf = -KHW;
     if (p.wf == 0 && (p.w_block >> 3) > v.WI * v.NT()) return false;
   } else if (v.wnat) {
     if ((c.KW > 1 && p.ws_kw != 1) || (c.KH > 1 && p.ws_kh != c.KW) || p.ws_c != KHW || (p.ws_o & 3) || (p.ws_g & 3))

@@ -163,11 +163,15 @@ def test_kernel_choice(syno):
     # backward-weight keeps its split partials there
     assert p.workspace_bytes(syno.FWD) == 0 and p.workspace_bytes(syno.BWD_DATA) == 0
     assert p.workspace_bytes(syno.BWD_WEIGHT) > 0
-    # more channels than one chunk holds: bf16 backward-data packs its weights into the workspace (forward reads
-    # them as they lie); fp32 backward-data of a 3x3 window takes them from the forward layout as they lie, and
-    # transposes them into the workspace when they lie in another order
+    # more channels than one chunk holds: backward-data of a 3x3 window takes its weights from the forward layout as
+    # they lie (bf16 and fp32 alike); weights in another axis order are packed (bf16) or transposed (fp32) into the
+    # workspace, and so are the bf16 weights of other windows
     p = syno.Plan(wl.conv2d(32, 128, 128, 28, 28, 3, 3, BF16, F32))
-    assert p.workspace_bytes(syno.FWD) == 0 and p.workspace_bytes(syno.BWD_DATA) > 0
+    assert p.workspace_bytes(syno.FWD) == 0 and p.workspace_bytes(syno.BWD_DATA) == 0 and "weights=direct" in p.describe(syno.BWD_DATA)
+    q = syno.Plan(wl.conv2d(32, 128, 128, 28, 28, 3, 3, BF16, F32, (1, 0, 2, 3)))
+    assert q.workspace_bytes(syno.BWD_DATA) > 0 and "weights=packed" in q.describe(syno.BWD_DATA)
+    q = syno.Plan(wl.conv2d(32, 128, 128, 28, 28, 1, 1, BF16, F32))
+    assert q.workspace_bytes(syno.BWD_DATA) > 0 and "weights=packed" in q.describe(syno.BWD_DATA)
     q = syno.Plan(wl.conv2d(32, 128, 128, 28, 28))
     assert q.workspace_bytes(syno.BWD_DATA) == 0 and "turned-while-staged" in q.describe(syno.BWD_DATA)
     q = syno.Plan(wl.conv2d(32, 128, 128, 28, 28, 3, 3, F32, F32, (1, 0, 2, 3)))

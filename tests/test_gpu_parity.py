@@ -207,12 +207,14 @@ def test_strided_conv_blocks_across_images(syno, oracle, bf16, variant, rows, K)
     assert run_all(syno, oracle, w, 0, directions=(0,), mfma_variant=variant + 1, mfma_rows=rows)[0].startswith("mfma_contraction")
 
 
-@pytest.mark.parametrize("variant,rows", [(0, 4), (3, 3), (4, 2), (5, 1), (6, 4), (7, 4), (8, 2)])
+@pytest.mark.parametrize("variant,rows", [(0, 4), (1, 5), (3, 3), (4, 2), (5, 1), (6, 4), (7, 4), (8, 2), (9, 3)])
 def test_conv_bf16_named_tile_variants(syno, oracle, variant, rows):
     C = 40 if variant == 6 else 72          # (variant 6 holds the whole reduction in one chunk: at most 64 channels)
     w = wl.make_conv(3, C, 13, seed=30 + variant, Co=40, Wd=19, bf16=True, with_grad=True, w_order=(0, 1, 2, 3))
     plan = syno.Plan(w.desc, mfma_variant=variant + 1, mfma_rows=rows)
     assert f"variant={variant} rows/block={rows} " in plan.describe(syno.FWD)
+    # variants 1, 8 and 9 (and the single-chunk one) read forward-layout weights themselves in backward-data too
+    assert ("weights=direct" in plan.describe(syno.BWD_DATA)) == (variant in (1, 6, 8, 9)), plan.describe(syno.BWD_DATA)
     run_all(syno, oracle, w, 0, directions=(0, 1), mfma_variant=variant + 1, mfma_rows=rows)
 
 

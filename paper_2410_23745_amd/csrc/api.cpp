@@ -125,12 +125,13 @@ syno_status run(const syno_plan* plan, int which, const void* A, const void* B, 
       const syno::ConvLike& c = plan->conv;
       const int window = plan->phase_window;
       const size_t esz = plan->in_dtype == SYNO_BF16 ? 2 : 4, osz = plan->out_dtype == SYNO_BF16 ? 2 : 4;
-      const size_t CP = (size_t)c.Cg * c.sh * c.sh;
+      const int ps = plan->phase_s;
+      const size_t CP = (size_t)c.Cg * ps * ps;
       auto round_up = [](size_t n) { return (n + 255) & ~(size_t)255; };
       char* w0 = static_cast<char*>(ws);
       if (which == SYNO_BWD_WEIGHT) {          // A = G, B = X, out = dW
         void* Xp = w0;
-        float* dWp = reinterpret_cast<float*>(w0 + round_up((size_t)plan->x_elems * esz));
+        float* dWp = reinterpret_cast<float*>(w0 + round_up((size_t)plan->phase_view_x->out_elems * esz));
         void* rest = reinterpret_cast<char*>(dWp) + round_up((size_t)c.Og * CP * window * window * 4);
         const void* one = unit_weight(plan->in_dtype);
         if (!one) return SYNO_ERR_HIP;
@@ -138,19 +139,20 @@ syno_status run(const syno_plan* plan, int which, const void* A, const void* B, 
         if (st != SYNO_OK) return st;
         st = run(plan->phase_conv_dw, SYNO_BWD_WEIGHT, A, Xp, dWp, rest, stream);
         if (st != SYNO_OK) return st;
-        return syno::launch_phase_weight_gather(c, window, dWp, static_cast<float*>(out), stream);
+        return syno::launch_phase_weight_gather(c, ps, window, dWp, static_cast<float*>(out), stream);
       }
       // A = G, B = W, out = dX
       void* Wpp = w0;
       void* dXp = w0 + round_up(CP * c.Og * window * window * esz);
-      void* rest = static_cast<char*>(dXp) + round_up((size_t)plan->x_elems * osz);
+      void* rest = static_cast<char*>(dXp) + round_up((size_t)plan->phase_view_dx->out_elems * osz);
       const void* one = unit_weight(plan->out_dtype);
       if (!one) return SYNO_ERR_HIP;
-      syno_status st = syno::launch_phase_weight_build(c, window, (int)esz, B, Wpp, stream);
+      syno_status st = syno::launch_phase_weight_build(c, ps, window, (int)esz, B, Wpp, stream);
       if (st != SYNO_OK) return st;
       st = run(plan->phase_conv_dx, SYNO_FWD, A, Wpp, dXp, rest, stream);
       if (st != SYNO_OK) return st;
-      return run(plan->phase_view_dx, SYNO_BWD_DATA, dXp, one, out, nullptr, stream);
+      void* view_ws = static_cast<char*>(rest) + plan->phase_conv_dx->launch[SYNO_FWD].workspace;
+      return run(plan->phase_view_dx, SYNO_BWD_DATA, dXp, one, out, view_ws, stream);
     }
     default: return SYNO_ERR_UNSUPPORTED;
   }

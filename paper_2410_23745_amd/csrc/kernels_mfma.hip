@@ -576,24 +576,24 @@ syno_status launch_mfma(const syno_plan* plan, int which, const void* A, const v
 }
 
 namespace {
-PhaseParams phase_params(const ConvLike& c, int window) {
+PhaseParams phase_params(const ConvLike& c, int s, int window) {
   PhaseParams q{};
-  q.O = c.Og; q.C = c.Cg; q.K = c.KH; q.s = c.sh; q.p = c.ph; q.window = window;
+  q.O = c.Og; q.C = c.Cg; q.K = c.KH; q.s = s; q.p = c.ph; q.window = window;
   q.ws_o = c.ws_o; q.ws_c = c.ws_c; q.ws_kh = c.ws_kh; q.ws_kw = c.ws_kw;
   return q;
 }
 }  // namespace
 
-syno_status launch_phase_weight_gather(const ConvLike& c, int window, const float* dWp, float* dW, hipStream_t stream) {
-  const PhaseParams q = phase_params(c, window);
+syno_status launch_phase_weight_gather(const ConvLike& c, int s, int window, const float* dWp, float* dW, hipStream_t stream) {
+  const PhaseParams q = phase_params(c, s, window);
   const int64_t n = (int64_t)q.O * q.C * q.K * q.K;
   if (n >= (1ll << 31)) return SYNO_ERR_SHAPE;
   hipLaunchKernelGGL(phase_weight_gather, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, q, dWp, dW);
   return hipGetLastError() == hipSuccess ? SYNO_OK : SYNO_ERR_HIP;
 }
 
-syno_status launch_phase_weight_build(const ConvLike& c, int window, int elem_bytes, const void* W, void* Wpp, hipStream_t stream) {
-  const PhaseParams q = phase_params(c, window);
+syno_status launch_phase_weight_build(const ConvLike& c, int s, int window, int elem_bytes, const void* W, void* Wpp, hipStream_t stream) {
+  const PhaseParams q = phase_params(c, s, window);
   const int64_t n = (int64_t)q.C * q.s * q.s * q.O * window * window;
   if (n >= (1ll << 31)) return SYNO_ERR_SHAPE;
   const dim3 grid((unsigned)((n + 255) / 256));

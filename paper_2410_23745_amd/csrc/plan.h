@@ -152,6 +152,8 @@ struct syno_plan {
   // forward contractions do the work (owned)
   syno_plan *phase_view_x = nullptr, *phase_view_dx = nullptr, *phase_conv_dw = nullptr, *phase_conv_dx = nullptr;
   int32_t phase_window = 0;      // window of those convolutions: 3 (pad 1) or 1
+  int32_t phase_s = 0;           // phases per image axis that take part: s, or 1 for a 1x1 window, which only reads phase
+                                 // (0, 0) - the view is then the sub-sampling X[.., s*h', s*w'] itself
   ~syno_plan() { delete inner; delete inner_dx; delete phase_view_x; delete phase_view_dx; delete phase_conv_dw; delete phase_conv_dx; }
   bool pure_view = false;
   syno::ViewStream view{};
@@ -219,10 +221,11 @@ syno_status launch_rows(const syno_plan* p, int which, const void* A, const void
 constexpr int kViaTransposedCopy = 100;
 syno_status launch_transpose_2d(const void* src, void* dst, int64_t rows, int64_t cols, int elem_bytes, hipStream_t stream);
 // kernels_mfma.hip, gradients of a strided convolution through the phase planes:
+// (s = the phases per axis that take part: the stride, or 1 when only phase (0,0) is read)
 // dW[o,c,kh,kw] (any strides) = dWp[o][(c*s+a)*s+b][th][tw] with s*dh+a = kh-p, th = dh+1 (window 3) or 0 (window 1)
-syno_status launch_phase_weight_gather(const ConvLike& c, int window, const float* dWp, float* dW, hipStream_t stream);
+syno_status launch_phase_weight_gather(const ConvLike& c, int s, int window, const float* dWp, float* dW, hipStream_t stream);
 // Wpp[(c*s+a)*s+b][o][th][tw] (contiguous, 2- or 4-byte elements) = W[o,c,kh,kw] with kh = a+p-s*dh, or 0 where there is none
-syno_status launch_phase_weight_build(const ConvLike& c, int window, int elem_bytes, const void* W, void* Wpp, hipStream_t stream);
+syno_status launch_phase_weight_build(const ConvLike& c, int s, int window, int elem_bytes, const void* W, void* Wpp, hipStream_t stream);
 // kernels_mfma_dw.hip: the backward-weight member of the MFMA family
 bool mfma_dw_supports(const syno_plan* p);
 void mfma_dw_configure(syno_plan* p);

@@ -1285,17 +1285,31 @@ syno_status build_plan(const syno_desc* desc, syno_plan* plan, std::string* why)
                       c.Hi == s * c.Ho && c.Wi == s * c.Wo && dmin >= -1 && dmax <= 1 && (int64_t)c.Cg * s * s < (1 << 20);
     if (fits) {
       const int window = (dmin == 0 && dmax == 0) ? 1 : 3;
-      // out[n,c,a,b,h',w'] = X[n, c, s*h'+a, s*w'+b] (times a one-element weight), element type t on both sides
+      // a window that only ever reads phase (0, 0) (1x1 without pad): the other phases do not take part, the view is
+      // the sub-sampling itself and its scatter leaves the unread pixels of dX zero
+      const int ps = (window == 1 && c.KH == 1 && c.ph == 0) ? 1 : s;
+      // out[n,c,a,b,h',w'] = X[n, c, s*h'+a, s*w'+b] (times a one-element weight), element type t on both sides;
+      // ps = 1: out[n,c,h',w'] = X[n, c, s*h', s*w']
       auto view_plan = [&](syno_dtype t) -> syno_plan* {
-        const syno_dim dims[6] = {{"n", c.N}, {"c", c.Cg}, {"a", s}, {"b", s}, {"h", c.Ho}, {"w", c.Wo}};
-        syno_prim pr[2] = {};
-        for (int k = 0; k < 2; ++k) {
-          pr[k].kind = SYNO_SPLIT; pr[k].in[0] = 4 + k; pr[k].in[1] = 2 + k; pr[k].out[0] = 6 + k; pr[k].out[1] = -1;
-          pr[k].shift_by = -1;
-        }
-        const int32_t xin[4] = {0, 1, 6, 7};
         syno_desc d{};
-        d.n_out = 6; d.out_dims = dims; d.n_prim = 2; d.prims = pr; d.n_in = 4; d.input_coords = xin; d.n_w = 0;
+        syno_prim pr[2] = {};
+        const syno_dim dims6[6] = {{"n", c.N}, {"c", c.Cg}, {"a", s}, {"b", s}, {"h", c.Ho}, {"w", c.Wo}};
+        const syno_dim dims4[4] = {{"n", c.N}, {"c", c.Cg}, {"h", c.Ho}, {"w", c.Wo}};
+        const int32_t xin6[4] = {0, 1, 6, 7}, xin4[4] = {0, 1, 4, 5};
+        if (ps > 1) {
+          for (int k = 0; k < 2; ++k) {
+            pr[k].kind = SYNO_SPLIT; pr[k].in[0] = 4 + k; pr[k].in[1] = 2 + k; pr[k].out[0] = 6 + k; pr[k].out[1] = -1;
+            pr[k].shift_by = -1;
+          }
+          d.n_out = 6; d.out_dims = dims6; d.input_coords = xin6;
+        } else {
+          for (int k = 0; k < 2; ++k) {
+            pr[k].kind = SYNO_STRIDE; pr[k].in[0] = 2 + k; pr[k].in[1] = -1; pr[k].out[0] = 4 + k; pr[k].out[1] = -1;
+            pr[k].param = s; pr[k].shift_by = -1;
+          }
+          d.n_out = 4; d.out_dims = dims4; d.input_coords = xin4;
+        }
+        d.n_prim = 2; d.prims = pr; d.n_in = 4; d.n_w = 0;
         d.weight_coords = nullptr; d.in_dtype = t; d.out_dtype = t;
         syno_plan* ip = new syno_plan();
         if (build_plan(&d, ip, nullptr) != SYNO_OK) { delete ip; return nullptr; }
@@ -1323,17 +1337,18 @@ syno_status build_plan(const syno_desc* desc, syno_plan* plan, std::string* why)
       };
       auto is_mfma = [](const Launch& L) { return L.kernel == KERNEL_MFMA_F32 || L.kernel == KERNEL_MFMA_BF16; };
       auto round_up = [](size_t n) { return (n + 255) & ~(size_t)255; };
-      const int64_t CP = (int64_t)c.Cg * s * s;
+      const int64_t CP = (int64_t)c.Cg * ps * ps;
+      const int64_t plane_elems = (int64_t)c.N * CP * c.Ho * c.Wo;      // elements of the view's result
       const size_t esz = desc->in_dtype == SYNO_BF16 ? 2 : 4, osz = desc->out_dtype == SYNO_BF16 ? 2 : 4;
       // backward-weight: space-to-depth of X, weight gradient of the stride-1 convolution, the existing taps picked out
       {
         syno_plan* v = view_plan(desc->in_dtype);
         syno_plan* cw = conv_plan(CP, c.Og, SYNO_F32);
         if (v && cw && v->launch[SYNO_FWD].kernel == KERNEL_BW_VIEW && is_mfma(cw->launch[SYNO_BWD_WEIGHT])) {
-          plan->phase_view_x = v; plan->phase_conv_dw = cw; plan->phase_window = window;
+          plan->phase_view_x = v; plan->phase_conv_dw = cw; plan->phase_window = window; plan->phase_s = ps;
           Launch& L = plan->launch[SYNO_BWD_WEIGHT];
           L.kernel = KERNEL_MFMA_PHASES;
-          L.workspace = round_up((size_t)plan->x_elems * esz) + round_up((size_t)c.Og * CP * window * window * 4) +
+          L.workspace = round_up((size_t)plane_elems * esz) + round_up((size_t)c.Og * CP * window * window * 4) +
                         cw->launch[SYNO_BWD_WEIGHT].workspace;
         } else {
           delete v; delete cw;
@@ -1344,12 +1359,12 @@ syno_status build_plan(const syno_desc* desc, syno_plan* plan, std::string* why)
       {
         syno_plan* v = view_plan(desc->out_dtype);
         syno_plan* cx = conv_plan(c.Og, CP, desc->out_dtype);
-        if (v && cx && v->launch[SYNO_BWD_DATA].kernel == KERNEL_BW_VIEW && v->view.one_to_one && is_mfma(cx->launch[SYNO_FWD])) {
-          plan->phase_view_dx = v; plan->phase_conv_dx = cx; plan->phase_window = window;
+        if (v && cx && v->launch[SYNO_BWD_DATA].kernel == KERNEL_BW_VIEW && is_mfma(cx->launch[SYNO_FWD])) {
+          plan->phase_view_dx = v; plan->phase_conv_dx = cx; plan->phase_window = window; plan->phase_s = ps;
           Launch& L = plan->launch[SYNO_BWD_DATA];
           L.kernel = KERNEL_MFMA_PHASES;
-          L.workspace = round_up((size_t)CP * c.Og * window * window * esz) + round_up((size_t)plan->x_elems * osz) +
-                        cx->launch[SYNO_FWD].workspace;
+          L.workspace = round_up((size_t)CP * c.Og * window * window * esz) + round_up((size_t)plane_elems * osz) +
+                        cx->launch[SYNO_FWD].workspace + v->launch[SYNO_BWD_DATA].workspace;
         } else {
           delete v; delete cx;
         }

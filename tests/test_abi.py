@@ -249,9 +249,11 @@ def test_strided_convolution_runs_on_the_contraction_kernels(syno):
         assert [p.kernel(i) for i in range(3)] == ["mfma_contraction_f32", "mfma_contraction_phases", "mfma_contraction_phases"]
         assert "depth-to-space" in p.describe(1) and "space-to-depth" in p.describe(2)
         # workspaces: the re-ordered weights and the phase planes of dX; the phase planes of X and the stride-1 gradient
-        win = 3 if K == 3 else 1
-        assert p.workspace_bytes(1) >= 4 * (64 * 24 * win * win + 2 * 16 * 12 * 12)
-        assert p.workspace_bytes(2) >= 4 * (2 * 16 * 12 * 12 + 24 * 64 * win * win)
+        # (the 1x1 window only reads phase (0,0): the sub-sampled X and dX instead of all four phase planes)
+        win, phases = (3, 4) if K == 3 else (1, 1)
+        assert p.workspace_bytes(1) >= 4 * (phases * 16 * 24 * win * win + 2 * phases * 16 * 6 * 6)
+        assert p.workspace_bytes(2) >= 4 * (2 * phases * 16 * 6 * 6 + 24 * phases * 16 * win * win)
+        assert p.workspace_bytes(2) < 4 * (2 * 16 * 12 * 12 + 24 * 64 * 9) * (1 if K == 3 else 0) + (1 << 16) * (K == 1) + (1 << 30) * (K == 3)
     assert syno.Plan(wl.conv2d(2, 16, 24, 6, 6, 3, in_dtype=BF16, stride=2)).kernel(0) == "mfma_contraction_bf16"
     # an index-program-only plan keeps every pass there
     q = syno.Plan(wl.conv2d(2, 16, 24, 6, 6, 3, stride=2), kernel_policy=1)

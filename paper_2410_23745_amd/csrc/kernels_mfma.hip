@@ -309,7 +309,8 @@ bool fill_params(const syno_plan* plan, int which, int vi, int TR, MfmaParams& p
     // single-chunk variant also with 3 or 1 (and through the adjoint for backward-data, marked by a negative count)
     const bool fwd_layout = (c.KW == 1 || c.ws_kw == 1) && (c.KH == 1 || c.ws_kh == c.KW) && c.ws_c == KHW;
     if (fwd_layout && (c.Cg & 7) == 0) {
-      if (which == SYNO_FWD && (KHW == 9 || (v.one && (KHW == 1 || KHW == 3)))) p.wf = KHW;
+      // (variant 0 is also instantiated for 3 taps: the 3x1 second stage of the paper's Operator 1 runs there)
+      if (which == SYNO_FWD && (KHW == 9 || (v.one && (KHW == 1 || KHW == 3)) || (KHW == 3 && vi == 0))) p.wf = KHW;
       if (which == SYNO_BWD_DATA && v.one && (KHW == 1 || KHW == 3 || KHW == 9)) p.wf = -KHW;
     }
     // backward-data of a 3x3 window by the chunked variants instantiated for it: runs of 9 taps per (output channel,

@@ -10,7 +10,12 @@ void launch_mfma_bf16_bf16out(int vi, const MfmaParams& p, const void* X, const 
     else launch_variant<true, VI, 1, 0, true>(p, X, W, out, s);       \
     break;
   switch (vi) {
-    SYNO_CASE(0) SYNO_CASE(2) SYNO_CASE(3) SYNO_CASE(4) SYNO_CASE(5) SYNO_CASE(7)
+    SYNO_CASE(2) SYNO_CASE(3) SYNO_CASE(4) SYNO_CASE(5) SYNO_CASE(7)
+    case 0:   // also reads forward-layout weights of 3-tap windows itself
+      if (p.wf == 9) launch_variant<true, 0, 1, 9, true>(p, X, W, out, s);
+      else if (p.wf == 3) launch_variant<true, 0, 1, 3, true>(p, X, W, out, s);
+      else launch_variant<true, 0, 1, 0, true>(p, X, W, out, s);
+      break;
 #define SYNO_CASE_ADJ(VI)   /* also instantiated for backward-data straight from forward-layout 3x3 weights */ \
   case VI:                                                            \
     if (p.wf == 9) launch_variant<true, VI, 1, 9, true>(p, X, W, out, s); \

@@ -82,12 +82,17 @@ def descriptors():
           wl.operator1_stage1(3, 16, 16, 5, 12, 4, 2), wl.operator1_stage1(2, 12, 24, 4, 7, 3, 2, 3, BF16, BF16),
           wl.operator1_stage2(2, 16, 9, 10, 1), wl.window_of_sums_1d(120, 3, 2), wl.window_of_sums_1d(90, 5, 3, "k"),
           wl.window_of_sums_1d(64, 3, 4, "s"), wl.pooled_conv2d(3, 24, 40, 13, 10, 2, 3), wl.shifted_scale(3, 5, 7, 12),
-          wl.pixel_unshuffle(2, 3, 5, 8, 2), wl.pixel_unshuffle(1, 2, 4, 5, 3), pixel_unshuffle_conv()]
+          wl.pixel_unshuffle(2, 3, 5, 8, 2), wl.pixel_unshuffle(1, 2, 4, 5, 3), pixel_unshuffle_conv(),
+          # strided windows (gradients planned on the phase planes), windows over flattened axes, views with gaps
+          wl.conv2d(3, 24, 40, 7, 9, 3, stride=2), wl.conv2d(5, 40, 48, 4, 6, 1, 1, BF16, F32, stride=2),
+          wl.conv2d(2, 16, 24, 5, 9, 3, stride=3), wl.flat_window(3, 24, 40, 6, 10), wl.flat_window(2, 80, 40, 7, 7, 5, BF16, F32),
+          wl.shifted_scale(4, 8, 16, 16)]
     # the benchmark shapes (planned only: the checker's driver skips what is too large to evaluate)
     for C, H in wl.RESNET18_STAGES:
         ds += [wl.conv2d(32, C, C, H, H), wl.conv2d(32, C, C, H, H, 3, 3, BF16, F32)]
     ds += [wl.grouped_shift_unfold(32), wl.grouped_shift_unfold(128), wl.strided_depthwise(64, 128, 28, 28),
-           wl.matmul(8192, 2304, 768), wl.matmul(8192, 2304, 768, BF16, F32), wl.pixel_unshuffle(64, 128, 28, 28, 2)]
+           wl.matmul(8192, 2304, 768), wl.matmul(8192, 2304, 768, BF16, F32), wl.pixel_unshuffle(64, 128, 28, 28, 2),
+           wl.conv2d(32, 64, 128, 28, 28, 3, stride=2), wl.conv2d(32, 64, 128, 28, 28, 1, 1, BF16, F32, stride=2)]
     ds += wl.make_operator1(32, 64, 56).descs
     rng = random.Random(20241127)
     ds += [random_graph(rng) for _ in range(300)]

@@ -175,6 +175,52 @@ def test_random_convolution_shapes(syno, oracle, seed):
     assert all(n.startswith("mfma_contraction") for n in names), names
 
 
+def random_valid_graphs(seed, n):
+    """Seeded random primitive graphs (the generator of the host sanitizer test) that the checker accepts and the
+    library plans, with at least one X axis."""
+    import random
+    from test_host_sanitizers import random_graph
+    rng = random.Random(seed)
+    out = []
+    for _ in range(n):
+        d = random_graph(rng)
+        try:
+            xs, ws, _ = oracle_mod().describe(d)
+        except Exception:
+            continue
+        if not xs or (d.in_dtype == F32 and d.out_dtype == BF16):
+            continue          # (fp32 inputs with a bf16 result: no bar is stated for that pair)
+        out.append(d)
+    return out
+
+
+def oracle_mod():
+    import oracle
+    return oracle
+
+
+@pytest.mark.parametrize("seed", list(range(5150, 5162)))
+def test_random_primitive_graphs(syno, oracle, seed):
+    """Whatever the planner makes of arbitrary valid pGraphs (Split, Merge, Shift with and without a read coordinate,
+    Expand, Unfold, Stride, Reduce, Share in random order, random element types): all three passes against the
+    checker.  About a third of them are pure views and run on the view kernels (stream, scatter, gathers); the rest
+    exercise the index-program kernels on graphs nobody wrote by hand."""
+    fast = 0
+    for i, d in enumerate(random_valid_graphs(seed, 150)):
+        try:
+            plan = syno.Plan(d)
+        except syno.SynoError:
+            continue                       # valid but outside what the library lowers (reported as unsupported)
+        xs, ws, _ = oracle.describe(d)
+        os_ = oracle.out_shape(d)
+        st = wl.Stream(seed * 1000 + i)
+        w = wl._finish(d, xs, ws if ws else (1,), os_, st.normal(xs), st.uniform_pm(2.0, ws if ws else (1,)), st.normal(os_), 1)
+        print(f"[graph {seed}/{i}] {[plan.kernel(k) for k in range(3)]} X{xs} W{ws} out{os_}", flush=True)
+        names = run_all(syno, oracle, w, 0)
+        fast += sum(n != "generic_index_program" for n in names)
+    assert fast > 30
+
+
 @pytest.mark.parametrize("seed", range(12))
 def test_random_matmul_shapes(syno, oracle, seed):
     rng = np.random.default_rng(3000 + seed)

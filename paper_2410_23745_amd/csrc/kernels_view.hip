@@ -356,17 +356,20 @@ __device__ __forceinline__ void store_target(void* base, int64_t off, float v) {
 
 template <bool IBF, bool TO_X>
 __global__ __launch_bounds__(kThreads) void view_grad_long(const ViewGradParams p, const void* __restrict__ G,
-                                                           const void* __restrict__ other, float* __restrict__ partial,
+                                                           const void* __restrict__ other, double* __restrict__ partial,
                                                            int* __restrict__ t_index) {
   extern __shared__ __align__(16) int tab[];
-  __shared__ float wave_sum[kThreads / 64];
+  __shared__ double wave_sum[kThreads / 64];
   const ViewStream& vs = p.vs;
   build_tables(vs, p.tab_off, p.free_off, p.n_free, p.tab_total, tab);
   const int* tabO = TO_X ? tab + p.tab_total : tab;
   const int combo = blockIdx.x / p.n_splits, slice = blockIdx.x - combo * p.n_splits;
   const GradBase b0 = grad_base<TO_X>(p, tab, combo);
   const int64_t begin = slice * p.chunk, end = min(p.total_rest, begin + p.chunk);
-  float acc = 0.f;
+  // Sums run in fp64: a target element may be ONE sum over millions of products of either sign, whose fp32 partial
+  // sums would lose, by cancellation, what a relative bar on the result demands; the loads bound these kernels, not
+  // the arithmetic.
+  double acc = 0.0;
   auto walk = [&](auto run_c) {
     constexpr int R = decltype(run_c)::value;
     const int inner = p.rest_axis[p.n_rest - 1];
@@ -394,7 +397,7 @@ __global__ __launch_bounds__(kThreads) void view_grad_long(const ViewGradParams 
         x[k] = load_one<IBF>(other, oo + to_inner[d0 + k]);
       }
 #pragma unroll
-      for (int k = 0; k < R; ++k) acc = fmaf(g[k], x[k], acc);
+      for (int k = 0; k < R; ++k) acc = fma((double)g[k], (double)x[k], acc);
     }
   };
   if (p.run == 4) walk(std::integral_constant<int, 4>{});
@@ -404,7 +407,7 @@ __global__ __launch_bounds__(kThreads) void view_grad_long(const ViewGradParams 
   if ((threadIdx.x & 63) == 0) wave_sum[threadIdx.x >> 6] = acc;
   __syncthreads();
   if (threadIdx.x == 0) {
-    float t = wave_sum[0];
+    double t = wave_sum[0];
     for (int w = 1; w < kThreads / 64; ++w) t += wave_sum[w];
     partial[blockIdx.x] = t;
     if (slice == 0) t_index[combo] = b0.t;
@@ -412,13 +415,13 @@ __global__ __launch_bounds__(kThreads) void view_grad_long(const ViewGradParams 
 }
 
 template <bool OBF>
-__global__ __launch_bounds__(kThreads) void view_grad_sum(const float* __restrict__ partial, const int* __restrict__ t_index,
+__global__ __launch_bounds__(kThreads) void view_grad_sum(const double* __restrict__ partial, const int* __restrict__ t_index,
                                                           void* __restrict__ target, int n_combo, int n_splits) {
   const int combo = blockIdx.x * kThreads + threadIdx.x;
   if (combo >= n_combo) return;
-  float t = partial[(int64_t)combo * n_splits];
+  double t = partial[(int64_t)combo * n_splits];
   for (int s = 1; s < n_splits; ++s) t += partial[(int64_t)combo * n_splits + s];
-  store_target<OBF>(target, t_index[combo], t);
+  store_target<OBF>(target, t_index[combo], (float)t);
 }
 
 template <bool IBF, bool OBF, bool TO_X>
@@ -431,7 +434,7 @@ __global__ __launch_bounds__(kThreads) void view_grad_short(const ViewGradParams
   const int64_t combo = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   if (combo >= p.n_combo) return;
   const GradBase b0 = grad_base<TO_X>(p, tab, (int)combo);
-  float acc = 0.f;
+  double acc = 0.0;
   for (uint32_t idx = 0; idx < (uint32_t)p.total_rest; ++idx) {
     uint32_t rest = idx;
     int go = b0.g, oo = b0.o;
@@ -444,9 +447,9 @@ __global__ __launch_bounds__(kThreads) void view_grad_short(const ViewGradParams
       go += d * p.ostride[axis];
       oo += tabO[p.tab_off[axis] + d];
     }
-    acc = fmaf(load_one<IBF>(G, go), load_one<IBF>(other, oo), acc);
+    acc = fma((double)load_one<IBF>(G, go), (double)load_one<IBF>(other, oo), acc);
   }
-  store_target<OBF>(target, b0.t, acc);
+  store_target<OBF>(target, b0.t, (float)acc);
 }
 
 // zeroes `bytes` bytes (a multiple of 2; dst is 4-byte aligned)
@@ -534,7 +537,7 @@ bool fill_grad(const syno_plan* plan, bool to_x, ViewGradParams& p) {
   return true;
 }
 
-size_t grad_partial_bytes(const ViewGradParams& p) { return (((size_t)p.n_combo * p.n_splits * 4) + 255) & ~(size_t)255; }
+size_t grad_partial_bytes(const ViewGradParams& p) { return (((size_t)p.n_combo * p.n_splits * 8) + 255) & ~(size_t)255; }
 
 template <bool IBF, bool OBF, bool SCATTER>
 void launch_typed(const ViewParams& p, int V, size_t lds, const void* X, const void* W, void* out, hipStream_t s) {
@@ -646,7 +649,7 @@ syno_status launch_view(const syno_plan* plan, int which, const void* A, const v
     };
     if (d.n_splits > 0) {
       if (!ws) return SYNO_ERR_WORKSPACE;
-      float* partial = static_cast<float*>(ws);
+      double* partial = static_cast<double*>(ws);
       int* t_index = reinterpret_cast<int*>(static_cast<char*>(ws) + grad_partial_bytes(d));
       const dim3 grid((unsigned)(d.n_combo * d.n_splits));
       auto k = pick(view_grad_long<false, true>, view_grad_long<true, true>, view_grad_long<false, false>, view_grad_long<true, false>);

@@ -221,6 +221,65 @@ def test_random_primitive_graphs(syno, oracle, seed):
     assert fast > 30
 
 
+def random_view_graph(rng):
+    """A random Reduce-free, Unfold-free graph over a few larger output axes: Share, Split, Merge, Shift (constant, or by
+    another coordinate), Stride and Expand in random order - sized so that runs of four, long sliced sums and zero-filled
+    gaps all occur."""
+    n_out = rng.randint(2, 4)
+    b = Builder([(f"o{i}", rng.choice([3, 4, 8, 12, 16, 28, 56])) for i in range(n_out)])
+    live = list(range(n_out))
+    size = {i: sz for i, (_, sz) in enumerate(b.desc.out_dims)}
+    wcoords = []
+    for _ in range(rng.randint(1, 6)):
+        kind = rng.choice(["share", "share", "split", "merge", "shift", "stride", "expand"])
+        if not live:
+            break
+        if kind == "share":
+            c = live.pop(rng.randrange(len(live))); x, w = b.share(c); size[x] = size[w] = size[c]; live.append(x); wcoords.append(w)
+        elif kind == "split" and len(live) >= 2:
+            i = live.pop(rng.randrange(len(live))); j = live.pop(rng.randrange(len(live)))
+            v = b.split(i, j); size[v] = size[i] * size[j]; live.append(v)
+        elif kind == "merge":
+            c = live.pop(rng.randrange(len(live)))
+            B = rng.choice([k for k in range(1, size[c] + 1) if size[c] % k == 0])
+            q, r = b.merge(c, B); size[q], size[r] = size[c] // B, B; live += [q, r]
+        elif kind == "shift":
+            c = live.pop(rng.randrange(len(live)))
+            v = b.shift(c, rng.randint(-5, 5)); size[v] = size[c]; live.append(v)
+        elif kind == "stride":
+            c = live.pop(rng.randrange(len(live))); S = rng.choice([2, 3]); v = b.stride(c, S); size[v] = S * size[c]; live.append(v)
+        elif kind == "expand" and len(live) >= 2:
+            b.expand(live.pop(rng.randrange(len(live))))
+    rng.shuffle(live)
+    rng.shuffle(wcoords)
+    dt = rng.choice([(F32, F32), (BF16, F32), (BF16, BF16)])
+    return b.finish(live, wcoords, dt[0], dt[1])
+
+
+@pytest.mark.parametrize("seed", list(range(6200, 6208)))
+def test_random_views_at_larger_sizes(syno, oracle, seed):
+    import random
+    rng = random.Random(seed)
+    ran = 0
+    for i in range(40):
+        d = random_view_graph(rng)
+        try:
+            xs, ws, _ = oracle.describe(d)
+            plan = syno.Plan(d)
+        except Exception:
+            continue
+        os_ = oracle.out_shape(d)
+        if not xs or max(int(np.prod(xs)), int(np.prod(os_))) > (1 << 20):
+            continue
+        # (some of these gradients are ONE sum over 10^4 to 10^6 products of either sign: the gather kernels add in fp64)
+        st = wl.Stream(seed * 1000 + i)
+        w = wl._finish(d, xs, ws if ws else (1,), os_, st.normal(xs), st.uniform_pm(2.0, ws if ws else (1,)), st.normal(os_), 1)
+        print(f"[view {seed}/{i}] {[plan.describe(k) for k in range(3)]} X{xs} W{ws} out{os_}", flush=True)
+        names = run_all(syno, oracle, w, 0)
+        ran += sum(n == "bandwidth_view" for n in names)
+    assert ran >= 20
+
+
 @pytest.mark.parametrize("seed", range(12))
 def test_random_matmul_shapes(syno, oracle, seed):
     rng = np.random.default_rng(3000 + seed)

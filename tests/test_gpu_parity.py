@@ -175,6 +175,30 @@ def test_random_convolution_shapes(syno, oracle, seed):
     assert all(n.startswith("mfma_contraction") for n in names), names
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_grouped_shift_unfold_shapes(syno, oracle, seed):
+    """The grouped shift-unfold operator over seeded draws of groups, channels per group, extents, window and element
+    type: cyclic row shifts per group, ragged channel blocks, all three passes."""
+    rng = np.random.default_rng(7000 + seed)
+    groups, K, bf16 = int(rng.choice([1, 2, 3, 4])), int(rng.choice([1, 3])), bool(rng.integers(2))
+    Cg = int(rng.choice([8, 16, 24, 40, 64, 72]))
+    N, H, Wd = int(rng.integers(1, 5)), int(rng.integers(3, 15)), int(rng.integers(4, 20))
+    w = wl.make_gshift(N, seeds=(7100 + seed, 7200 + seed, 7300 + seed), with_grad=True, C=Cg * groups, H=H, Wd=Wd,
+                       groups=groups, K=K, bf16=bf16)
+    names = run_all(syno, oracle, w, 0)
+    assert all(n.startswith("mfma_contraction") for n in names), names
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_operator1_shapes(syno, oracle, seed):
+    rng = np.random.default_rng(8000 + seed)
+    g, s, k1 = int(rng.choice([2, 4])), int(rng.choice([2, 4])), int(rng.choice([3, 5]))
+    C = g * s * int(rng.choice([1, 2, 3]))
+    w = wl.make_operator1(int(rng.integers(1, 4)), C, int(rng.integers(4, 13)), seed=8100 + seed, bf16=bool(rng.integers(2)),
+                          Co=int(rng.choice([8, 16, 24])), Wd=int(rng.integers(5, 17)), g=g, s=s, k1=k1, with_grad=True)
+    run_chain(syno, oracle, w, 0)
+
+
 def random_valid_graphs(seed, n):
     """Seeded random primitive graphs (the generator of the host sanitizer test) that the checker accepts and the
     library plans, with at least one X axis."""

@@ -408,7 +408,10 @@ __global__ __launch_bounds__(kThreads) void share_window_reduce(const float* __r
   }
 }
 
-int run_width(const ShareWindow& s) { return s.W % 4 == 0 ? 4 : s.W % 2 == 0 ? 2 : 1; }
+int run_width(const ShareWindow& s) {
+  if (s.K == 5) return s.W % 4 == 0 ? 4 : 1;      // (the 5-wide window is instantiated for runs of 4 and of 1)
+  return s.W % 4 == 0 ? 4 : s.W % 2 == 0 ? 2 : 1;
+}
 
 SwParams fill(const syno_plan* plan) {
   const ShareWindow& s = plan->window;
@@ -428,10 +431,9 @@ SwParams fill(const syno_plan* plan) {
   return p;
 }
 
-template <int V, bool IBF, bool OBF>
+template <int K, int V, bool IBF, bool OBF>
 syno_status launch_typed(const SwParams& p, int which, const void* A, const void* B, void* out, void* ws,
                          hipStream_t stream) {
-  constexpr int K = 3;
   const unsigned run_blocks = (unsigned)((p.n_runs + kThreads - 1) / kThreads);
   if (which == SYNO_FWD) {
     const dim3 grid(run_blocks, (unsigned)p.G, (unsigned)((p.D + kDT - 1) / kDT));
@@ -456,10 +458,14 @@ syno_status launch_typed(const SwParams& p, int which, const void* A, const void
 template <bool IBF, bool OBF>
 syno_status launch_width(const SwParams& p, int V, int which, const void* A, const void* B, void* out, void* ws,
                          hipStream_t stream) {
+  if (p.K == 5) {        // (the wider window keeps more sums per lane: runs of 4 and single elements only)
+    if (V == 4) return launch_typed<5, 4, IBF, OBF>(p, which, A, B, out, ws, stream);
+    return launch_typed<5, 1, IBF, OBF>(p, which, A, B, out, ws, stream);
+  }
   switch (V) {
-    case 4: return launch_typed<4, IBF, OBF>(p, which, A, B, out, ws, stream);
-    case 2: return launch_typed<2, IBF, OBF>(p, which, A, B, out, ws, stream);
-    default: return launch_typed<1, IBF, OBF>(p, which, A, B, out, ws, stream);
+    case 4: return launch_typed<3, 4, IBF, OBF>(p, which, A, B, out, ws, stream);
+    case 2: return launch_typed<3, 2, IBF, OBF>(p, which, A, B, out, ws, stream);
+    default: return launch_typed<3, 1, IBF, OBF>(p, which, A, B, out, ws, stream);
   }
 }
 
@@ -468,7 +474,7 @@ syno_status launch_width(const SwParams& p, int V, int which, const void* A, con
 bool window_supports(const syno_plan* plan, int which) {
   if (!plan->share_window) return false;
   const ShareWindow& s = plan->window;
-  if (s.K != 3 || s.pw != 1) return false;
+  if (!((s.K == 3 || s.K == 5) && s.pw == s.K / 2)) return false;
   if (plan->in_dtype == SYNO_F32 && plan->out_dtype != SYNO_F32) return false;
   // the weights a workgroup keeps in LDS
   const size_t lds = sizeof(float) * (which == SYNO_FWD ? (size_t)s.Cg * kDT * s.K : (size_t)s.D * s.K * kCT);

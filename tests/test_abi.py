@@ -219,8 +219,9 @@ def test_unreduced_window_goes_to_the_streaming_family(syno):
     p = syno.Plan(stage1)
     assert [p.kernel(i) for i in range(3)] == ["bandwidth_share_window"] * 3
     assert p.workspace_bytes(0) == 0 and p.workspace_bytes(1) == 0 and p.workspace_bytes(2) > 0
-    # a 5-wide window and an fp32 -> bf16 stage are valid but not in the family: index-program kernels
-    assert syno.Plan(wl.operator1_stage1(2, 16, 16, 8, 8, g=4, s=2, k1=5)).kernel(0) == "generic_index_program"
+    # 5-wide windows are in the family too; a 7-wide one and an fp32 -> bf16 stage are valid but not: index-program kernels
+    assert [syno.Plan(wl.operator1_stage1(2, 16, 16, 8, 8, g=4, s=2, k1=5)).kernel(i) for i in range(3)] == ["bandwidth_share_window"] * 3
+    assert syno.Plan(wl.operator1_stage1(2, 16, 16, 8, 8, g=4, s=2, k1=7)).kernel(0) == "generic_index_program"
     assert syno.Plan(wl.operator1_stage1(2, 16, 16, 8, 8, 4, 2, 3, F32, BF16)).kernel(0) == "generic_index_program"
     # the same window Reduced is the convolution-like form, not this one
     assert syno.Plan(wl.conv2d(2, 16, 16, 8, 8, 1, 3)).kernel(0).startswith("mfma")

@@ -619,19 +619,21 @@ def test_operator1_small(syno, oracle, bf16, policy):
               policy)
 
 
+@pytest.mark.parametrize("k1", [3, 5])
 @pytest.mark.parametrize("dt", ["f32", "bf16", "bf16_f32out"])
 @pytest.mark.parametrize("shape", [
     (3, 16, 16, 5, 12, 4, 2),      # runs of 4 pixels, fewer runs than one workgroup's lanes
-    (2, 40, 40, 6, 10, 2, 1),      # runs of 2; D = 20 and Cg = 20: several tiles of each, ragged
+    (2, 40, 40, 6, 10, 2, 1),      # runs of 2 (of 1 for the 5-wide window); D = 20 and Cg = 20: several tiles of each, ragged
     (2, 12, 24, 4, 7, 3, 2),       # single pixels (odd width); D = 4, Cg = 4
     (5, 8, 8, 17, 16, 1, 1),       # one group; more runs than one workgroup
 ])
-def test_share_window_stage_small(syno, oracle, shape, dt):
-    """The first stage of Operator 1 by itself on the streaming kernels, all three passes, element by element."""
+def test_share_window_stage_small(syno, oracle, shape, dt, k1):
+    """The first stage of Operator 1 by itself on the streaming kernels (3- and 5-wide windows), all three passes,
+    element by element."""
     N, Cin, Co, H, W, g, s = shape
     i_dt = F32 if dt == "f32" else BF16
     o_dt = BF16 if dt == "bf16" else F32
-    d = wl.operator1_stage1(N, Cin, Co, H, W, g, s, 3, i_dt, o_dt)
+    d = wl.operator1_stage1(N, Cin, Co, H, W, g, s, k1, i_dt, o_dt)
     xs, ws, _ = oracle.describe(d)
     os_ = oracle.out_shape(d)
     st = wl.Stream(31)

@@ -508,7 +508,7 @@ bool fill_grad(const syno_plan* plan, bool to_x, ViewGradParams& p) {
     }
     if (n_combo > (int64_t(1) << 22) || p.total_rest >= (int64_t(1) << 31)) return false;   // (the check below enumerates them)
   }
-  if (n_combo > p.target_elems) return false;
+  if (n_combo > p.target_elems || p.target_elems > (int64_t(1) << 26)) return false;   // (the check keeps a byte per target element)
   p.n_combo = (int32_t)n_combo;
   // every combination its own target element
   {

@@ -13,8 +13,8 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsyno.so")
 
 SOURCES = ["planner.cpp", "api.cpp", "kernels_generic.hip", "kernels_bandwidth.hip", "kernels_window.hip", "kernels_view.hip", "kernels_mfma.hip",
-           "kernels_mfma_f32_lo.hip", "kernels_mfma_f32_hi.hip", "kernels_mfma_bf16_f32out.hip",
-           "kernels_mfma_bf16_bf16out.hip", "kernels_mfma_dw.hip", "conv_rows_bf16.hip", "debug_rate.hip"]
+           "kernels_mfma_f32_lo.hip", "kernels_mfma_f32_hi.hip", "kernels_mfma_bf16_f32out.hip", "kernels_mfma_bf16_f32out_b.hip",
+           "kernels_mfma_bf16_bf16out.hip", "kernels_mfma_bf16_bf16out_b.hip", "kernels_mfma_dw.hip", "conv_rows_bf16.hip", "debug_rate.hip"]
 
 # packed-fp32 instruction selection is switched off for device code (host pass warns it does not know
 # the feature; harmless)

@@ -1,7 +1,10 @@
-// Instantiations of the MFMA contraction kernel: bf16 tile variants, fp32 result.
+// Instantiations of the MFMA contraction kernel: bf16 tile variants 0, 2-5, 7 and 10, fp32 result (the others
+// live in kernels_mfma_bf16_f32out_b.hip, so that the two halves compile side by side).
 #include "conv_mfma.h"
 
 namespace syno {
+
+void launch_mfma_bf16_f32out_b(int vi, const MfmaParams& p, const void* X, const void* W, void* out, hipStream_t s);
 
 void launch_mfma_bf16_f32out(int vi, const MfmaParams& p, const void* X, const void* W, void* out, hipStream_t s) {
 #define SYNO_CASE(VI)                                                 \
@@ -16,25 +19,11 @@ void launch_mfma_bf16_f32out(int vi, const MfmaParams& p, const void* X, const v
       else if (p.wf == 3) launch_variant<true, 0, 1, 3, false>(p, X, W, out, s);
       else launch_variant<true, 0, 1, 0, false>(p, X, W, out, s);
       break;
-#define SYNO_CASE_ADJ(VI)   /* also instantiated for backward-data straight from forward-layout 3x3 weights */ \
-  case VI:                                                            \
-    if (p.wf == 9) launch_variant<true, VI, 1, 9, false>(p, X, W, out, s); \
-    else if (p.wf == -9) launch_variant<true, VI, 1, -9, false>(p, X, W, out, s); \
-    else launch_variant<true, VI, 1, 0, false>(p, X, W, out, s);       \
-    break;
-    SYNO_CASE_ADJ(1) SYNO_CASE_ADJ(8) SYNO_CASE_ADJ(9)
-#undef SYNO_CASE_ADJ
-    case 6:   // single chunk: packed weights, or weights as they lie in memory with 1, 3 or 9 taps per channel (negative: backward-data)
-      if (p.wf == 9) launch_variant<true, 6, 1, 9, false>(p, X, W, out, s);
-      else if (p.wf == 3) launch_variant<true, 6, 1, 3, false>(p, X, W, out, s);
-      else if (p.wf == 1) launch_variant<true, 6, 1, 1, false>(p, X, W, out, s);
-      else if (p.wf == -9) launch_variant<true, 6, 1, -9, false>(p, X, W, out, s);
-      else if (p.wf == -3) launch_variant<true, 6, 1, -3, false>(p, X, W, out, s);
-      else if (p.wf == -1) launch_variant<true, 6, 1, -1, false>(p, X, W, out, s);
-      else launch_variant<true, 6, 1, 0, false>(p, X, W, out, s);
-      break;
     case 10:  // 1x1 windows only: packed weights
       launch_variant<true, 10, 1, 0, false>(p, X, W, out, s);
+      break;
+    case 1: case 6: case 8: case 9:
+      launch_mfma_bf16_f32out_b(vi, p, X, W, out, s);
       break;
     default: break;
   }

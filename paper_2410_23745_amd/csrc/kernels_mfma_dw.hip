@@ -970,7 +970,7 @@ __global__ __launch_bounds__(256) void dw_reduce_tiles(const DwParams p, const f
     const int cl = (int)(((uint32_t)rem * inv_t) >> 16), t = rem - cl * T;
     const int c = c0 + cl;
     if (c >= p.Cg) continue;
-    const int kh = t >= 2 * p.KW ? 2 : (t >= p.KW ? 1 : 0);
+    const int kh = t / p.KW;
     dW[row + (int64_t)c * p.ws_c + kh * p.ws_kh + (t - kh * p.KW) * p.ws_kw] = sums[t][(ol >> 2) * 16 + cl][ol & 3];
   }
 }
@@ -1266,9 +1266,12 @@ bool mfma_dw_supports(const syno_plan* p) {
   if (p->in_dtype != SYNO_BF16 && p->in_dtype != SYNO_F32) return false;
   const ConvLike& c = p->conv;
   if (c.sh != 1 || c.sw != 1 || c.w_wrap) return false;
-  if (c.KH != 1 && (c.KH != 3 || c.h_wrap || c.ph != 1 || c.ws_kh < 0)) return false;
+  // windows: 1, 3 or 5 along an axis, at most 9 taps (each tap is a set of accumulators); a 5-wide window along the
+  // row only with fp32 inputs (the bf16 kernels cut their shifted fragments for 3-wide windows)
+  if (c.KH != 1 && ((c.KH != 3 && c.KH != 5) || c.h_wrap || c.ph != c.KH / 2 || c.ws_kh < 0)) return false;
   if (c.Wi != c.Wo || c.Hi != c.Ho) return false;
-  if (c.KW != 1 && c.KW != 3) return false;
+  if (c.KW != 1 && c.KW != 3 && !(c.KW == 5 && p->in_dtype == SYNO_F32)) return false;
+  if (c.KH * c.KW > 9) return false;
   if (c.pw != c.KW / 2) return false;
   if (c.ws_kw < 0 || (c.Og == 1 && c.Cg == 1)) return false;
   DwParams dp;
@@ -1319,6 +1322,8 @@ syno_status launch_mfma_dw(const syno_plan* plan, const void* A, const void* B, 
   using std::integral_constant;
   auto by_window = [&](auto go) {
     if (p.KH == 3 && p.KW == 3) go(integral_constant<int, 3>{}, integral_constant<int, 3>{}, integral_constant<int, 1>{});
+    else if (p.KH == 5) go(integral_constant<int, 5>{}, integral_constant<int, 1>{}, integral_constant<int, 1>{});
+    else if (p.KW == 5) go(integral_constant<int, 1>{}, integral_constant<int, 5>{}, integral_constant<int, 1>{});
     else if (p.KH == 3) go(integral_constant<int, 3>{}, integral_constant<int, 1>{}, integral_constant<int, 2>{});
     else if (p.KW == 3) go(integral_constant<int, 1>{}, integral_constant<int, 3>{}, integral_constant<int, 2>{});
     else go(integral_constant<int, 1>{}, integral_constant<int, 1>{}, integral_constant<int, 2>{});
@@ -1347,6 +1352,9 @@ syno_status launch_mfma_dw(const syno_plan* plan, const void* A, const void* B, 
     const uint16_t* X = static_cast<const uint16_t*>(B);
     by_window([&](auto kh_c, auto kw_c, auto ct_c) {
       constexpr int kh = decltype(kh_c)::value, kw = decltype(kw_c)::value, ct = decltype(ct_c)::value;
+      if constexpr (kw == 5) {
+        return;                 // (not instantiated: mfma_dw_supports refuses it)
+      } else {
       bool taken = false;
       if constexpr (kh == 3) {
         taken = p.direct != 0;
@@ -1357,6 +1365,7 @@ syno_status launch_mfma_dw(const syno_plan* plan, const void* A, const void* B, 
       if (p.W % 4 == 0) launch_dw_kernel(dw_mfma_bf16<kh, kw, ct, 4>, grid, p, G, X, dst, stream);
       else if (p.W % 2 == 0) launch_dw_kernel(dw_mfma_bf16<kh, kw, ct, 2>, grid, p, G, X, dst, stream);
       else launch_dw_kernel(dw_mfma_bf16<kh, kw, ct, 1>, grid, p, G, X, dst, stream);
+      }
     });
   }
   // many splits of a small dW: one block per slot keeps the device busy; few splits of a large dW: one block per

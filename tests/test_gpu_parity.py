@@ -199,6 +199,19 @@ def test_random_operator1_shapes(syno, oracle, seed):
     run_chain(syno, oracle, w, 0)
 
 
+@pytest.mark.parametrize("KH,KW,bf16", [(5, 1, False), (5, 1, True), (1, 5, False), (3, 1, True), (1, 3, False)])
+def test_one_sided_windows(syno, oracle, KH, KW, bf16):
+    """Windows along one image axis only, 3 and 5 wide (the second stage of Operator 1 is k1 x 1): all three passes on
+    the contraction kernels; the weight gradient keeps one set of accumulators per tap."""
+    N, C, Co, H, Wd = 3, 40, 24, 9, 12
+    d = wl.conv2d(N, C, Co, H, Wd, KH, KW, BF16 if bf16 else F32, F32)
+    st = wl.Stream(90 + KH * 10 + KW)
+    xs, ws, os_ = (N, C, H, Wd), (Co, C, KH, KW), (N, Co, H, Wd)
+    w = wl._finish(d, xs, ws, os_, st.normal(xs), st.uniform_pm(1.0 / np.sqrt(C * KH * KW), ws), st.normal(os_), C * KH * KW)
+    names = run_all(syno, oracle, w, 0)
+    assert all(n.startswith("mfma_contraction") for n in names), names
+
+
 def random_valid_graphs(seed, n):
     """Seeded random primitive graphs (the generator of the host sanitizer test) that the checker accepts and the
     library plans, with at least one X axis."""

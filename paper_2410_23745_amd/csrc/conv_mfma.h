@@ -36,6 +36,12 @@ struct MfmaParams {
   int32_t U;                          // window taps along w per row-step (selects the instantiation)
   int32_t ksplit, chunks_per_split;   // workgroups per output tile, each summing a range of chunks (1: no split)
   int32_t split_stride;               // ksplit > 1: elements between the partial results (fp32, laid out like the result)
+  // Workgroups are handed round-robin to the 8 XCDs, each with an L2 of its own.  When xcd_m > 0 the tiles of one
+  // (group, split) plane are dealt so that XCD x = xm*xcd_n + xn works on an (n_mblocks/xcd_m) x (n_nblocks/xcd_n)
+  // rectangle of tiles: it reads 1/xcd_m of the source rows and 1/xcd_n of the weights (xcd_m * xcd_n = 8).  0: the
+  // plain order (weight panels fastest).  Inside its rectangle an XCD takes the panels of one row of tiles first, or
+  // (xcd_rows_first) the rows of tiles of one panel first.
+  int32_t xcd_m, xcd_n, xcd_rows_first;
 };
 
 namespace {
@@ -139,9 +145,21 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_mfma(const MfmaParams p,
   // wave widx runs on SIMD widx % 4: rotate the wave rows so that the fuller ones spread over the SIMDs,
   // also among the waves that split K
   const int wm = (wtile + wn + ((wk * WM * WN) >> 2)) % WM;
-  int bid = blockIdx.x;
-  const int nb = bid % p.n_nblocks; bid /= p.n_nblocks;
-  const int mb = bid % p.n_mblocks;
+  int bid = blockIdx.x, nb, mb;
+  if (p.xcd_m > 0) {
+    // (a plane holds a multiple of 8 tiles, so the low three bits of its local index name the XCD)
+    const int tiles = p.n_mblocks * p.n_nblocks;
+    const int plane = bid / tiles, local = bid - plane * tiles;
+    const int xcd = local & 7, idx = local >> 3;
+    const int sm = p.n_mblocks / p.xcd_m, sn = p.n_nblocks / p.xcd_n;
+    const int xm = xcd / p.xcd_n, xn = xcd - xm * p.xcd_n;
+    const int im = p.xcd_rows_first ? idx % sm : idx / sn;
+    mb = xm * sm + im; nb = xn * sn + (p.xcd_rows_first ? idx / sm : idx - im * sn);
+    bid = plane * p.n_mblocks;
+  } else {
+    nb = bid % p.n_nblocks; bid /= p.n_nblocks;
+    mb = bid % p.n_mblocks;
+  }
   int g = bid / p.n_mblocks, ksp = 0;
   if (p.ksplit > 1) { ksp = g / p.G; g -= ksp * p.G; }
   const int R0 = mb * p.TR;

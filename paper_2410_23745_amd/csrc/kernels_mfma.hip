@@ -379,6 +379,32 @@ bool fill_params(const syno_plan* plan, int which, int vi, int TR, MfmaParams& p
     p.ksplit = ksplit;
     p.split_stride = (int32_t)((result + 3) & ~3ll);
   }
+  // Which tiles share an XCD's L2: with the tiles of a plane dealt as xcd_m x xcd_n rectangles the XCDs together fetch
+  // the source xcd_n times and the weights xcd_m times; take the split with the fewest bytes that divides both counts.
+  // An XCD walks its rectangle either one row of tiles after the other, coming back to the same weight panels in each
+  // row, or one panel after the other, coming back to the same source rows: unless the whole rectangle is resident at
+  // once, the operand it comes back to has to stay in that XCD's L2 (4 MB, half of it left to the streaming one), or
+  // every pass fetches it again.
+  p.xcd_m = p.xcd_n = p.xcd_rows_first = 0;
+  if (((int64_t)p.n_mblocks * p.n_nblocks) % 8 == 0) {
+    const double esize = bf ? 2.0 : 4.0, fits = 2.0 * 1024 * 1024;
+    const double src = esize * c.N * p.Cg * plane / p.ksplit, wts = esize * p.Og * p.Cg * KHW / p.ksplit;
+    const int64_t resident = 32 * std::max(1, std::min(2, kMaxLdsBytes / std::max(p.lds_bytes, 1)));
+    double fewest = 0;
+    for (int a = 1; a <= 8; a *= 2) {
+      const int b = 8 / a;
+      if (p.n_mblocks % a != 0 || p.n_nblocks % b != 0) continue;
+      const int64_t sm = p.n_mblocks / a, sn = p.n_nblocks / b;
+      for (int rows_first = 0; rows_first < 2; ++rows_first) {
+        double bytes = b * src + a * wts;
+        if (sm * sn > resident) {
+          if (!rows_first && wts / b > fits) bytes += a * wts * (sm - 1);
+          if (rows_first && src / a > fits) bytes += b * src * (sn - 1);
+        }
+        if (p.xcd_m == 0 || bytes < fewest) { fewest = bytes; p.xcd_m = a; p.xcd_n = b; p.xcd_rows_first = rows_first; }
+      }
+    }
+  }
   return p.lds_bytes <= kMaxLdsBytes;
 }
 
@@ -510,8 +536,12 @@ std::string mfma_describe(const syno_plan* plan, int which) {
   memcpy(&p, plan->launch[which].params, sizeof p);
   snprintf(b, sizeof b, "variant=%d rows/block=%d BN=%d KC=%d taps/row-step=%d weights=%s waves=%dx%dx%d grid=%d lds=%dB slots=%d", vi, TR,
            v.BN(), p.KC, p.U, plan->in_dtype != SYNO_BF16 ? (p.wt ? "transposed-copy" : p.wadj ? "turned-while-staged" : "direct") : (p.wf ? "direct" : "packed"), v.WM, v.WN, v.WK, p.n_mblocks * p.n_nblocks * p.G * p.ksplit, p.lds_bytes, p.n_slots);
-  if (p.ksplit > 1) return std::string(b) + " reduction-splits=" + std::to_string(p.ksplit);
-  return b;
+  std::string d = b;
+  if (p.xcd_m > 0)
+    d += " tiles-per-xcd=" + std::to_string(p.n_mblocks / p.xcd_m) + "x" + std::to_string(p.n_nblocks / p.xcd_n) +
+         (p.xcd_rows_first ? "(rows first)" : "");
+  if (p.ksplit > 1) d += " reduction-splits=" + std::to_string(p.ksplit);
+  return d;
 }
 
 syno_status launch_mfma(const syno_plan* plan, int which, const void* A, const void* B, void* out, void* ws,

@@ -1368,11 +1368,11 @@ syno_status launch_mfma_dw(const syno_plan* plan, const void* A, const void* B, 
       }
     });
   }
-  // many splits of a small dW: one block per slot keeps the device busy; few splits of a large dW: one block per
-  // 16x16 tile with all its taps writes dW in whole lines
+  // many splits of a small dW: one block per slot keeps the device busy; few splits, or a dW with at least one 16x16
+  // tile per compute unit: one block per tile with all its taps writes dW in whole lines
   if (p.n_splits == 1) {
     // (written by the contraction itself)
-  } else if (p.n_splits > 4)
+  } else if (p.n_splits > 4 && p.n_tiles * (p.slots / (p.KH * p.KW)) < 256)
     hipLaunchKernelGGL(dw_reduce_slots, dim3(p.n_tiles * p.slots), dim3(256), 0, stream, p,
                        reinterpret_cast<const float4*>(ws), static_cast<float*>(out));
   else

@@ -900,6 +900,22 @@ def test_matmul_small_bf16_result(syno, oracle, M, K, N):
                      "bandwidth_view" if K <= 64 else "generic_index_program"]
 
 
+@pytest.mark.parametrize("N,C,Co,H,bf16", [(48, 768, 768, 7, False), (128, 64, 64, 56, False), (16, 2048, 512, 7, False),
+                                          (64, 256, 512, 14, True)])
+def test_tile_order_across_xcds_sampled(syno, oracle, N, C, Co, H, bf16):
+    """Shapes whose tiles are dealt to the XCDs in rectangles of several kinds: more tiles than are resident at once
+    (walked rows of tiles first where the weights outgrow an L2, panels first otherwise), a rectangle per reduction
+    split, different splits forward and backward.  Every tile must still be computed exactly once: sampled outputs
+    (image borders, tile boundaries, uniform draws) against the checker."""
+    w = wl.make_conv(N, C, H, seed=61, bf16=bf16, Co=Co, with_grad=True)
+    plan = syno.Plan(w.desc)
+    assert all("tiles-per-xcd=" in plan.describe(which) for which in (0, 1)), plan.describe(0)
+    if (N, C) == (48, 768):
+        assert "(rows first)" in plan.describe(0)
+    names = run_all(syno, oracle, w, 0, directions=(0, 1), full=False, n_sample=1024)
+    assert all(n.startswith("mfma_contraction") for n in names[:2])
+
+
 @pytest.mark.parametrize("bf16", [False, True])
 def test_qkv_projection_full_size_sampled(syno, oracle, bf16):
     names = run_all(syno, oracle, wl.qkv_projection(bf16), 0, full=False, n_sample=2048)

@@ -261,6 +261,31 @@ def test_strided_convolution_runs_on_the_contraction_kernels(syno):
     assert [q.kernel(i) for i in range(3)] == ["generic_index_program"] * 3
 
 
+def test_contraction_tiles_are_dealt_to_the_xcds_in_rectangles(syno):
+    """Host logic of the tile order: the 8 XCDs split a plane's tiles m x n so that the fewest bytes cross the fabric
+    (the source is fetched n times, the weights m times), a plane whose tile count is not a multiple of 8 keeps the
+    plain order, and a rectangle too large to be resident at once is walked so that the operand the XCD keeps coming
+    back to fits its L2."""
+    import re
+
+    def split(desc):
+        m = re.search(r"tiles-per-xcd=(\d+)x(\d+)(\(rows first\))?", desc)
+        return (int(m.group(1)), int(m.group(2)), bool(m.group(3))) if m else None
+
+    # the benchmark's four stages, 256 tiles each: source-heavy stages give every XCD its own rows and all panels,
+    # weight-heavy ones go to a 2-D split
+    expect = {(64, 56): (32, 1), (128, 28): (8, 4), (256, 14): (8, 4), (512, 7): (8, 4)}
+    for (C, H), tiles in expect.items():
+        plan = syno.Plan(wl.conv2d(32, C, C, H, H, 3, 3))
+        for which in (0, 1):
+            assert split(plan.describe(which))[:2] == tiles, plan.describe(which)
+    # weights of 21 MB against 7 MB of source, more tiles than fit at once: rows of tiles first
+    assert split(syno.Plan(wl.conv2d(48, 768, 768, 7, 7, 3, 3)).describe(0))[2]
+    # 3 x 3 = 9 tiles: no rectangles
+    small = syno.Plan(wl.conv2d(3, 40, 72, 9, 12, 3, 3))
+    assert "grid=" in small.describe(0) and split(small.describe(0)) is None
+
+
 def test_matmul_is_planned_as_a_convolution_with_exchanged_roles(syno):
     p = syno.Plan(wl.matmul(96, 2304, 768))
     assert [p.kernel(i) for i in range(3)] == ["mfma_contraction_transposed"] * 3
